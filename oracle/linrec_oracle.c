@@ -1,0 +1,108 @@
+/*
+ * linrec_oracle.c -- TEST INFRASTRUCTURE, not product code.
+ *
+ * Plain sequential fp64 evaluation of the diagonal linear recurrence of
+ * arXiv 1709.04057 and of its gradients.  It exists so that the GPU library
+ * can be checked against something obviously correct; only the tests, the
+ * smoke check and the cpu_baseline leg of the benchmark may call it.  It
+ * shares no source, header, table or helper with the GPU path.
+ *
+ * Storage convention used by every function here
+ *   - tensors are row-major [T, C]: element (t, c) at t*C + c, C = B*n
+ *     independent columns ("T vectors each of b*n elements", Section 3.1.1);
+ *   - 0-based row t holds the paper's lambda_{t+1}, x_{t+1}, h_{t+1};
+ *     h0 is the paper's h_0 and is an input, never an output row
+ *     (the SCAN definition in Section 1 returns n outputs for n inputs);
+ *   - inputs are fp32 and are widened exactly to fp64; all arithmetic and
+ *     all outputs are fp64 (round-to-nearest; build with -ffp-contract=off).
+ *
+ * Every function works on the column range [c0, c1) and the row slab
+ * [t0, t1) of the full tensors, carrying the recurrence state in a caller
+ * supplied fp64 vector, so that big problems can be streamed through in
+ * slabs and columns can be handed to several host threads.  Rows are never
+ * split across threads: time is always walked sequentially.
+ *
+ * Pins (tests/test_oracle_pins.py): exact rational closed form by brute
+ * force (T <= 64), lambda==0, lambda==1 vs numpy.cumsum, geometric series,
+ * scipy.signal.lfilter, backward closed form by brute force, reversed
+ * cumprod, finite differences, adjoint identity, row perturbation, slab and
+ * column split invariance.
+ */
+#include <stddef.h>
+#include <stdint.h>
+
+/*
+ * Forward recurrence (Section 2, "h_t = lambda_t (.) h_{t-1} + x_t";
+ * Algorithm 1 fixes the initial value: C_{-1} = h_0).
+ *
+ *   state[c]      on entry: h at row t0-1 (h0 when t0 == 0), fp64
+ *                 on exit : h at row t1-1
+ *   href          fp64 [T, C] (full-size array); rows [t0,t1), columns
+ *                 [c0,c1) are written
+ */
+void linrec_oracle_forward(const float *lambda, const float *x,
+                           double *state, double *href,
+                           int64_t T, int64_t C,
+                           int64_t t0, int64_t t1, int64_t c0, int64_t c1)
+{
+    (void)T;
+    for (int64_t t = t0; t < t1; ++t) {
+        const float *lt = lambda + (size_t)t * (size_t)C;
+        const float *xt = x + (size_t)t * (size_t)C;
+        double *ht = href + (size_t)t * (size_t)C;
+        for (int64_t c = c0; c < c1; ++c) {
+            double s = (double)lt[c] * state[c] + (double)xt[c];
+            state[c] = s;
+            ht[c] = s;
+        }
+    }
+}
+
+/*
+ * Backward pass (Section 2.2, "Backpropagation").  With e = dL/dh (the direct
+ * upstream gradient) and g_t the accumulated gradient nabla_{h_t} L:
+ *
+ *   g_{T-1} = e_{T-1}                                   (last row: no successor)
+ *   g_t     = lambda_{t+1} * g_{t+1} + e_t
+ *   grad_x_t      = g_t
+ *   grad_lambda_t = h_{t-1} * g_t          (h_{-1} = h0, zero if h0 == NULL)
+ *   grad_h0       = lambda_0 * g_0
+ *
+ * Rows are walked from t1-1 down to t0.
+ *
+ *   gstate[c]     on entry: g at row t1 (ignored when t1 == T: row T of
+ *                 lambda does not exist and is never read)
+ *                 on exit : g at row t0
+ *   h             fp32 [T, C]: the forward output handed to the backward pass
+ *   gx, glam      fp64 [T, C] full-size; rows [t0,t1), columns [c0,c1) written
+ *   gh0           fp64 [C]; written only when t0 == 0
+ */
+void linrec_oracle_backward(const float *lambda, const float *h,
+                            const float *h0, const float *e,
+                            double *gstate,
+                            double *gx, double *glam, double *gh0,
+                            int64_t T, int64_t C,
+                            int64_t t0, int64_t t1, int64_t c0, int64_t c1)
+{
+    for (int64_t t = t1 - 1; t >= t0; --t) {
+        const float *et = e + (size_t)t * (size_t)C;
+        const float *lnext = (t + 1 < T) ? lambda + (size_t)(t + 1) * (size_t)C : NULL;
+        const float *hprev = (t > 0) ? h + (size_t)(t - 1) * (size_t)C : h0;
+        double *gxt = gx + (size_t)t * (size_t)C;
+        double *glt = glam + (size_t)t * (size_t)C;
+        for (int64_t c = c0; c < c1; ++c) {
+            double g = (double)et[c];
+            if (lnext)
+                g += (double)lnext[c] * gstate[c];
+            gstate[c] = g;
+            gxt[c] = g;
+            glt[c] = g * (hprev ? (double)hprev[c] : 0.0);
+        }
+    }
+    if (t0 == 0 && t1 > 0) {
+        for (int64_t c = c0; c < c1; ++c)
+            gh0[c] = (double)lambda[c] * gstate[c];
+    }
+}
+
+int linrec_oracle_version(void) { return 1; }
