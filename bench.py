@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the linear-recurrence hot path on one MI355X.
+
+A step is one forward pass plus one backward pass of h_t = lambda_t*h_{t-1} + x_t over one batch of
+synthetic, HBM-resident inputs (default workload: [T=65536, B=4, n=256] fp32, the configuration the
+metric is quoted on).  Prints ONE JSON line:
+
+  value        elements/s of forward+backward together, E / (t_fwd + t_bwd), E = T*B*n
+  roofline     the dominant kernel (the backward pass, 20 B/element) against the 8 TB/s HBM peak,
+               its duration measured with HIP events on the launch stream inside the timed region
+  cpu_baseline the fp64 oracle timed on the host cores on the same workload (a baseline, not a target)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+FWD_BYTES_PER_EL = 12.0   # read lambda, x; write h
+BWD_BYTES_PER_EL = 20.0   # read lambda, h, grad_h; write grad_x, grad_lambda
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
+    ap.add_argument("--variant", default="auto", choices=["auto", "threephase", "lookback", "serial"])
+    ap.add_argument("--tile-fwd", type=int, default=0)
+    ap.add_argument("--tile-bwd", type=int, default=0)
+    ap.add_argument("--hprev-late", type=int, default=-1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=0)
+    return ap.parse_args()
+
+
+def cpu_baseline(inp, threads):
+    """Times the fp64 oracle (forward + backward, one pass) on the host; returns the JSON object."""
+    import numpy as np
+
+    import oracle
+    T, B, n = inp["T"], inp["B"], inp["n"]
+    C = B * n
+    f = lambda t: None if t is None else t.cpu().numpy().reshape(-1, C)
+    lam, x, e = f(inp["lam"]), f(inp["x"]), f(inp["grad_h"])
+    h0 = None if inp["h0"] is None else inp["h0"].cpu().numpy().reshape(-1)
+    oracle.build()
+    t0 = time.perf_counter()
+    h = oracle.forward(lam, x, h0, threads=threads)
+    t1 = time.perf_counter()
+    h32 = h.astype(np.float32)
+    del h
+    t2 = time.perf_counter()
+    if e is not None:
+        oracle.backward(lam, h32, h0, e, threads=threads)
+    t3 = time.perf_counter()
+    sec = (t1 - t0) + (t3 - t2)
+    return {"value": T * C / sec, "unit": "elements/s", "cores": threads, "kind": "oracle",
+            "sample": "the full workload, one forward + one backward pass of the fp64 oracle, columns split "
+                      f"over {threads} host threads; forward {t1 - t0:.3f} s, backward {t3 - t2:.3f} s"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import linrec_workloads as wl
+    import paper_1709_04057_amd as lr
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    lr.lib()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    variant = {"auto": lr.VARIANT_AUTO, "threephase": lr.VARIANT_THREEPHASE, "lookback": lr.VARIANT_LOOKBACK,
+               "serial": lr.VARIANT_SERIAL}[args.variant]
+    lr.linrec_set_option(lr.OPT_VARIANT, variant)
+    lr.linrec_set_option(lr.OPT_HPREV_LATE, args.hprev_late)
+
+    inp = wl.make_inputs(args.config, device=dev)
+    T, B, n = inp["T"], inp["B"], inp["n"]
+    E = T * B * n
+    lam, x, h0 = inp["lam"], inp["x"], inp["h0"]
+    do_bwd = inp["grad_h"] is not None
+    e = inp["grad_h"]
+    h = torch.empty_like(x)
+    gx = torch.empty_like(x) if do_bwd else None
+    gl = torch.empty_like(x) if do_bwd else None
+    gh0 = torch.empty((B, n), device=dev) if do_bwd else None
+    stream = torch.cuda.current_stream()
+
+    def fwd():
+        lr.linrec_set_option(lr.OPT_TILE, args.tile_fwd)
+        lr.linrec_forward(lam, x, h0, h_out=h, stream=stream)
+
+    def bwd():
+        lr.linrec_set_option(lr.OPT_TILE, args.tile_bwd)
+        lr.linrec_backward(lam, h, h0, e, grad_x=gx, grad_lambda=gl, grad_h0=gh0, stream=stream)
+
+    for _ in range(args.warmup):
+        fwd()
+        if do_bwd:
+            bwd()
+    torch.cuda.synchronize()
+
+    K = args.steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        ev[i][0].record(stream)
+        fwd()
+        ev[i][1].record(stream)
+        if do_bwd:
+            bwd()
+        ev[i][2].record(stream)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    lr.linrec_check(stream)
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    fwd_ms = sorted(ev[i][0].elapsed_time(ev[i][1]) for i in range(K))
+    bwd_ms = sorted(ev[i][1].elapsed_time(ev[i][2]) for i in range(K))
+    fwd_avg, bwd_avg = sum(fwd_ms) / K, sum(bwd_ms) / K
+    fwd_gbs = FWD_BYTES_PER_EL * E / (fwd_avg * 1e-3) / 1e9
+    bwd_gbs = BWD_BYTES_PER_EL * E / (bwd_avg * 1e-3) / 1e9 if do_bwd else None
+
+    vf, tf = lr.linrec_plan(T, B, n, backward=False) if not args.tile_fwd else (variant, args.tile_fwd)
+    vb, tb = lr.linrec_plan(T, B, n, backward=True) if not args.tile_bwd else (variant, args.tile_bwd)
+    if do_bwd:
+        roof = {"bound": "hbm", "kernel": "backward pass (look-back kernel)" if vb == lr.VARIANT_LOOKBACK else "backward pass",
+                "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
+                "traffic": None, "bytes_per_element": BWD_BYTES_PER_EL, "avg_ms": bwd_avg}
+    else:
+        roof = {"bound": "hbm", "kernel": "forward pass", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_element": FWD_BYTES_PER_EL,
+                "avg_ms": fwd_avg}
+
+    out = {
+        "metric": "linrec fwd+bwd elements/sec and achieved HBM GB/s (% of MI355X peak)",
+        "value": E / (ms_per_step * 1e-3), "unit": "elements/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"cfg{args.config}: forward{'+backward' if do_bwd else ''}, fp32, time-major "
+                               f"[T={T}, B={B}, n={n}]; {wl.CONFIGS[args.config]['note']}",
+                   "variant": args.variant, "tile_fwd": tf, "tile_bwd": tb},
+        "forward": {"avg_ms": fwd_avg, "min_ms": fwd_ms[0], "median_ms": fwd_ms[K // 2], "GB/s": fwd_gbs,
+                    "frac_of_peak": fwd_gbs / HBM_PEAK_GBS, "elements/s": E / (fwd_avg * 1e-3)},
+        "backward": None if not do_bwd else {
+            "avg_ms": bwd_avg, "min_ms": bwd_ms[0], "median_ms": bwd_ms[K // 2], "GB/s": bwd_gbs,
+            "frac_of_peak": bwd_gbs / HBM_PEAK_GBS, "elements/s": E / (bwd_avg * 1e-3)},
+        "combined_GB/s": (FWD_BYTES_PER_EL + (BWD_BYTES_PER_EL if do_bwd else 0)) * E / (ms_per_step * 1e-3) / 1e9,
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
+        out["cpu_baseline"] = cpu_baseline(inp, threads)
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

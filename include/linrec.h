@@ -1,0 +1,151 @@
+/*
+ * linrec.h -- C ABI of liblinrec: the diagonal linear recurrence
+ *
+ *     h_t = lambda_t (.) h_{t-1} + x_t                     (arXiv 1709.04057, Section 2)
+ *
+ * evaluated in parallel over the sequence length as a scan of the affine pairs
+ * (lambda_t, x_t) under  (a1,b1) (+) (a2,b2) = (a1*a2, a2*b1 + b2)  (Algorithm 1 of the
+ * paper: per-chunk reduce, scan of the chunk summaries, per-chunk rescan from the carry),
+ * and its backward pass, the same recurrence run in reverse over the upstream gradient
+ * (Section 2.2, "Backpropagation").  AMD MI355X (gfx950) only.
+ *
+ * Conventions shared by every entry point
+ *   - Tensors are fp32, contiguous, time-major [T, B, n]: element (t, b, i) lives at
+ *     (t*B + b)*n + i.  The C = B*n columns are independent recurrences ("T vectors each of
+ *     b*n elements", Section 3.1.1); time runs down the rows.
+ *   - Row t (0-based) holds the paper's lambda_{t+1}, x_{t+1}, h_{t+1}.  h0 [B, n] is the
+ *     paper's h_0: an input, never an output row (the SCAN of Section 1 returns T outputs
+ *     for T inputs).
+ *   - Every pointer is a DEVICE pointer owned by the caller, valid on the device the stream
+ *     belongs to.  The library neither frees nor retains them.  Any 4-byte aligned pointer
+ *     is accepted; the 16-byte vector path is taken only when every tensor pointer is
+ *     16-byte aligned and C is a multiple of 4.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
+ *     enqueue work and return: there is no host synchronisation, device-side faults surface
+ *     at the caller's next synchronisation.
+ *   - The library keeps one cached device workspace (chunk summaries, carries, look-back
+ *     flags) per (device, stream); it is allocated on first use and grown on demand (this is
+ *     the only place a call may block), and freed by linrec_release_workspace().  Calls that
+ *     use the same stream from several host threads at once are not supported; calls on
+ *     different streams are independent.
+ *   - Return value: LINREC_OK (0) or a negative LINREC_ERR_* code.  Arguments are validated
+ *     before any HIP call is made.  T == 0 or B*n == 0 is a successful no-op (for T == 0 a
+ *     non-NULL grad_h0 is zero-filled).
+ *   - Results are deterministic for a fixed variant and tile shape (no floating-point
+ *     atomics); different variants / tile shapes may differ in the last bits.
+ *   - Domain: finite inputs whose partial products of lambda stay finite (|lambda| <= 1 is
+ *     always safe).  NaN/Inf propagate along their own column only.
+ */
+#ifndef LINREC_H
+#define LINREC_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    LINREC_OK = 0,
+    LINREC_ERR_NULL = -1,   /* a required pointer is NULL                                   */
+    LINREC_ERR_SHAPE = -2,  /* negative dimension, or T*B*n overflows / exceeds 2^40        */
+    LINREC_ERR_ALIAS = -3,  /* forbidden overlap between an output and another tensor       */
+    LINREC_ERR_HIP = -4,    /* a HIP allocation or launch failed; see linrec_last_hip_error */
+    LINREC_ERR_OPTION = -5, /* unknown option or value out of range                         */
+    LINREC_ERR_DEVICE = -6  /* a kernel reported a look-back wait that exceeded its limit   */
+};
+
+/* Which kernel family evaluates the scan (linrec_set_option(LINREC_OPT_VARIANT, ...)). */
+enum {
+    LINREC_VARIANT_AUTO = 0,       /* library picks (single pass where it applies)           */
+    LINREC_VARIANT_THREEPHASE = 1, /* Algorithm 1 as three kernels: reduce, scan, rescan     */
+    LINREC_VARIANT_LOOKBACK = 2,   /* one kernel; chunk carries found by decoupled look-back */
+    LINREC_VARIANT_SERIAL = 3      /* one thread per column walks T (the paper's baseline of
+                                      Section 4.1.1, "in serial over sequence length")       */
+};
+
+enum {
+    LINREC_OPT_VARIANT = 1,    /* LINREC_VARIANT_*                                           */
+    LINREC_OPT_TILE = 2,       /* tile-shape id, 0 = automatic (see linrec_tile_info)        */
+    LINREC_OPT_CHUNK_TILES = 3,/* three-phase: tiles walked per chunk, 0 = automatic         */
+    LINREC_OPT_SPIN_LIMIT = 4, /* look-back: polls before a wait is declared failed          */
+    LINREC_OPT_HPREV_LATE = 5  /* look-back backward: load h after the rescan (1), together
+                                  with lambda and grad_h (0), or let the library decide (-1)  */
+};
+
+/*
+ * Forward pass.  (Section 2; Algorithm 1.)
+ *   lambda, x : [T, B, n] inputs.
+ *   h0        : [B, n] initial state, or NULL for a zero state.
+ *   h_out     : [T, B, n] output; h_out[t] is the state after consuming row t.
+ * h_out may alias x exactly (same pointer): every tile reads its rows before it writes
+ * them.  Any other overlap of h_out with an input returns LINREC_ERR_ALIAS.
+ */
+int linrec_forward(const float *lambda, const float *x, const float *h0, float *h_out,
+                   int64_t T, int64_t B, int64_t n, void *stream);
+
+/*
+ * Backward pass.  (Section 2.2.)  With e = grad_h, the direct upstream dL/dh_t, and
+ * g_t the accumulated gradient nabla_{h_t} L:
+ *     g_{T-1} = e_{T-1},   g_t = lambda_{t+1} * g_{t+1} + e_t      (row T of lambda is never read)
+ *     grad_x[t]      = g_t
+ *     grad_lambda[t] = g_t * h[t-1]          (h[-1] = h0, zero if h0 == NULL)
+ *     grad_h0        = lambda[0] * g_0
+ *   lambda, h, grad_h : [T, B, n] inputs; h is the forward pass' h_out (x is not needed).
+ *   h0                : [B, n] or NULL.
+ *   grad_x, grad_lambda : [T, B, n] outputs; either may be NULL to skip it.
+ *   grad_h0           : [B, n] output or NULL to skip it.
+ * grad_x may alias grad_h exactly; any other overlap of an output with another tensor
+ * returns LINREC_ERR_ALIAS.  grad_lambda is the partial derivative with x held fixed.
+ */
+int linrec_backward(const float *lambda, const float *h, const float *h0, const float *grad_h,
+                    float *grad_x, float *grad_lambda, float *grad_h0,
+                    int64_t T, int64_t B, int64_t n, void *stream);
+
+/* Process-wide tuning knobs (LINREC_OPT_*).  Environment variables LINREC_VARIANT
+ * ("auto", "threephase", "lookback", "serial") and LINREC_TILE (integer id) give the
+ * initial values.  Returns LINREC_OK or LINREC_ERR_OPTION.  Not thread-safe against
+ * concurrent linrec_forward/backward calls. */
+int linrec_set_option(int option, int64_t value);
+int64_t linrec_get_option(int option);
+
+/* Describes tile shape `tile_id` (1-based): threads along columns, threads along time, rows
+ * per thread, columns per thread.  Returns LINREC_ERR_OPTION past the last id.  Any output
+ * pointer may be NULL.  Host-only; makes no HIP call. */
+int linrec_tile_info(int tile_id, int *threads_cols, int *threads_time, int *rows_per_thread,
+                     int *cols_per_thread);
+
+/* Reports the variant and tile shape the library would use for a [T, B, n] problem under the
+ * current options (`aligned16_and_c_mult4`: whether the 16-byte vector path is available).
+ * Host-only; makes no HIP call. */
+int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int aligned16_and_c_mult4,
+                int *variant, int *tile_id);
+
+/* Host-side argument checks only (exactly the checks linrec_forward / linrec_backward run
+ * before touching the GPU); no HIP call is made, so these work on a machine without a GPU. */
+int linrec_validate_forward(const float *lambda, const float *x, const float *h0,
+                            const float *h_out, int64_t T, int64_t B, int64_t n);
+int linrec_validate_backward(const float *lambda, const float *h, const float *h0,
+                             const float *grad_h, const float *grad_x, const float *grad_lambda,
+                             const float *grad_h0, int64_t T, int64_t B, int64_t n);
+
+/* Synchronises `stream` and reports whether any look-back kernel enqueued on it since the
+ * last check gave up waiting (LINREC_ERR_DEVICE), LINREC_ERR_HIP if the synchronisation
+ * itself failed, else LINREC_OK.  Optional: a healthy run never needs it. */
+int linrec_check(void *stream);
+
+/* Frees every cached workspace of the calling process (all devices, all streams).  The
+ * caller must make sure no linrec call is still running on the GPU. */
+int linrec_release_workspace(void);
+
+/* Static strings; never NULL. */
+const char *linrec_status_string(int status);
+const char *linrec_last_hip_error(void);
+
+/* ABI version of this header (major*100 + minor). */
+int linrec_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LINREC_H */

@@ -1,0 +1,32 @@
+"""Thin Python binding of liblinrec (AMD MI355X / gfx950).
+
+The functions here only marshal arguments (device pointers, shapes, the current HIP stream) into the
+C ABI declared in ``include/linrec.h``; every step of the recurrence runs in the library's HIP
+kernels.  There is no CPU fallback: if ``liblinrec.so`` has not been built the first call raises.
+PyTorch is used for device memory and streams only.
+"""
+from .binding import (  # noqa: F401
+    LinrecError,
+    OPT_CHUNK_TILES,
+    OPT_HPREV_LATE,
+    OPT_SPIN_LIMIT,
+    OPT_TILE,
+    OPT_VARIANT,
+    VARIANT_AUTO,
+    VARIANT_LOOKBACK,
+    VARIANT_SERIAL,
+    VARIANT_THREEPHASE,
+    declared_symbols,
+    lib,
+    lib_path,
+    linrec_backward,
+    linrec_check,
+    linrec_forward,
+    linrec_get_option,
+    linrec_plan,
+    linrec_release_workspace,
+    linrec_set_option,
+    linrec_status_string,
+    linrec_tile_info,
+    linrec_version,
+)

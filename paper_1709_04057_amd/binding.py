@@ -1,0 +1,193 @@
+"""ctypes binding of the liblinrec C ABI (argument marshalling only)."""
+from __future__ import annotations
+
+import ctypes
+import os
+import re
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liblinrec.so")
+_HEADER = os.path.join(os.path.dirname(_HERE), "include", "linrec.h")
+_lib = None
+
+VARIANT_AUTO, VARIANT_THREEPHASE, VARIANT_LOOKBACK, VARIANT_SERIAL = 0, 1, 2, 3
+OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE = 1, 2, 3, 4, 5
+
+
+class LinrecError(RuntimeError):
+    def __init__(self, status, detail=""):
+        self.status = status
+        msg = "liblinrec error %d: %s" % (status, linrec_status_string(status))
+        if detail:
+            msg += " (" + detail + ")"
+        super().__init__(msg)
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def lib():
+    """Loads liblinrec.so (built in-tree by ``paper_1709_04057_amd/build.py``); raises if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(
+                "liblinrec.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(_LIB_PATH)
+        i64, p, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+        pi = ctypes.POINTER(ctypes.c_int)
+        L.linrec_forward.argtypes = [p, p, p, p, i64, i64, i64, p]
+        L.linrec_forward.restype = ci
+        L.linrec_backward.argtypes = [p, p, p, p, p, p, p, i64, i64, i64, p]
+        L.linrec_backward.restype = ci
+        L.linrec_validate_forward.argtypes = [p, p, p, p, i64, i64, i64]
+        L.linrec_validate_forward.restype = ci
+        L.linrec_validate_backward.argtypes = [p, p, p, p, p, p, p, i64, i64, i64]
+        L.linrec_validate_backward.restype = ci
+        L.linrec_set_option.argtypes = [ci, i64]
+        L.linrec_set_option.restype = ci
+        L.linrec_get_option.argtypes = [ci]
+        L.linrec_get_option.restype = i64
+        L.linrec_tile_info.argtypes = [ci, pi, pi, pi, pi]
+        L.linrec_tile_info.restype = ci
+        L.linrec_plan.argtypes = [i64, i64, i64, ci, ci, pi, pi]
+        L.linrec_plan.restype = ci
+        L.linrec_check.argtypes = [p]
+        L.linrec_check.restype = ci
+        L.linrec_release_workspace.argtypes = []
+        L.linrec_release_workspace.restype = ci
+        L.linrec_status_string.argtypes = [ci]
+        L.linrec_status_string.restype = ctypes.c_char_p
+        L.linrec_last_hip_error.argtypes = []
+        L.linrec_last_hip_error.restype = ctypes.c_char_p
+        L.linrec_version.argtypes = []
+        L.linrec_version.restype = ci
+        _lib = L
+    return _lib
+
+
+def declared_symbols():
+    """Names of the functions declared in include/linrec.h."""
+    with open(_HEADER) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(linrec_[a-z0-9_]+)\s*\(", text)))
+
+
+def linrec_status_string(status: int) -> str:
+    return lib().linrec_status_string(int(status)).decode()
+
+
+def linrec_version() -> int:
+    return lib().linrec_version()
+
+
+def _check(rc):
+    if rc != 0:
+        detail = lib().linrec_last_hip_error().decode() if rc == -4 else ""
+        raise LinrecError(rc, detail)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _tbn(t, name):
+    import torch
+    if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.dim() != 3:
+        raise ValueError(f"{name} must be a contiguous float32 CUDA tensor of shape [T, B, n]")
+    return t.shape
+
+
+def _bn(t, name, B, n):
+    import torch
+    if t is None:
+        return
+    if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, n):
+        raise ValueError(f"{name} must be a contiguous float32 CUDA tensor of shape [B, n] = [{B}, {n}]")
+
+
+def linrec_forward(lam, x, h0=None, h_out=None, stream=None):
+    """h_out[t] = lam[t] * h_out[t-1] + x[t], h_out[-1] = h0.  Enqueues on ``stream`` and returns h_out."""
+    import torch
+    T, B, n = _tbn(lam, "lambda")
+    if tuple(x.shape) != (T, B, n):
+        raise ValueError("x must have lambda's shape")
+    _tbn(x, "x")
+    _bn(h0, "h0", B, n)
+    if h_out is None:
+        h_out = torch.empty_like(x)
+    elif tuple(_tbn(h_out, "h_out")) != (T, B, n):
+        raise ValueError("h_out must have lambda's shape")
+    _check(lib().linrec_forward(_ptr(lam), _ptr(x), _ptr(h0), _ptr(h_out), T, B, n, _stream_ptr(stream)))
+    return h_out
+
+
+def linrec_backward(lam, h, h0, grad_h, grad_x=None, grad_lambda=None, grad_h0=None, stream=None,
+                    want_grad_x=True, want_grad_lambda=True, want_grad_h0=True):
+    """Gradients of the recurrence for upstream ``grad_h``; returns (grad_x, grad_lambda, grad_h0).
+
+    Output tensors are allocated unless given; pass ``want_*=False`` to skip an output (returned as None).
+    """
+    import torch
+    T, B, n = _tbn(lam, "lambda")
+    for name, t in (("h", h), ("grad_h", grad_h)):
+        if tuple(_tbn(t, name)) != (T, B, n):
+            raise ValueError(f"{name} must have lambda's shape")
+    _bn(h0, "h0", B, n)
+    if grad_x is None and want_grad_x:
+        grad_x = torch.empty_like(grad_h)
+    if grad_lambda is None and want_grad_lambda:
+        grad_lambda = torch.empty_like(grad_h)
+    if grad_h0 is None and want_grad_h0:
+        grad_h0 = torch.empty((B, n), dtype=torch.float32, device=lam.device)
+    for name, t in (("grad_x", grad_x), ("grad_lambda", grad_lambda)):
+        if t is not None and tuple(_tbn(t, name)) != (T, B, n):
+            raise ValueError(f"{name} must have lambda's shape")
+    _bn(grad_h0, "grad_h0", B, n)
+    _check(lib().linrec_backward(_ptr(lam), _ptr(h), _ptr(h0), _ptr(grad_h), _ptr(grad_x), _ptr(grad_lambda),
+                                 _ptr(grad_h0), T, B, n, _stream_ptr(stream)))
+    return grad_x, grad_lambda, grad_h0
+
+
+def linrec_set_option(option: int, value: int) -> None:
+    _check(lib().linrec_set_option(int(option), int(value)))
+
+
+def linrec_get_option(option: int) -> int:
+    return int(lib().linrec_get_option(int(option)))
+
+
+def linrec_tile_info(tile_id: int):
+    """Returns dict(threads_cols, threads_time, rows_per_thread, cols_per_thread, rows, cols) or None past the end."""
+    a, b, c, d = (ctypes.c_int() for _ in range(4))
+    rc = lib().linrec_tile_info(int(tile_id), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d))
+    if rc != 0:
+        return None
+    return dict(threads_cols=a.value, threads_time=b.value, rows_per_thread=c.value, cols_per_thread=d.value,
+                rows=b.value * c.value, cols=a.value * d.value)
+
+
+def linrec_plan(T, B, n, backward=False, vec4=True):
+    v, t = ctypes.c_int(), ctypes.c_int()
+    _check(lib().linrec_plan(int(T), int(B), int(n), int(bool(backward)), int(bool(vec4)), ctypes.byref(v), ctypes.byref(t)))
+    return v.value, t.value
+
+
+def linrec_check(stream=None) -> None:
+    """Synchronises the stream and raises if a look-back kernel gave up waiting."""
+    _check(lib().linrec_check(_stream_ptr(stream)))
+
+
+def linrec_release_workspace() -> None:
+    _check(lib().linrec_release_workspace())

@@ -1,0 +1,66 @@
+"""Builds liblinrec.so (HIP, gfx950 only) next to this file.
+
+One hipcc invocation per translation unit, run in parallel: the tile kernels are compiled once per
+tile shape (-DLINREC_TILE_ID=n), then everything is linked into one shared library.
+"""
+from __future__ import annotations
+
+import os
+import re
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "liblinrec.so")
+OBJ_DIR = os.path.join(HERE, "_build")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+
+
+def tile_ids():
+    with open(os.path.join(CSRC, "linrec_launch.h")) as f:
+        return [int(m) for m in re.findall(r"^\s*X\((\d+),", f.read(), flags=re.M)]
+
+
+def _run(cmd):
+    p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in p.stdout.splitlines() if "packed-fp32-ops" not in l)
+    if p.returncode != 0:
+        raise RuntimeError("command failed: %s\n%s" % (" ".join(cmd), out))
+    return out
+
+
+def build(verbose: bool = False, jobs: int | None = None) -> str:
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    units = [("linrec_api.hip", [], "api.o"), ("linrec_scan.hip", [], "scan.o"),
+             ("linrec_validate.cpp", ["-x", "c++"], "validate.o")]
+    for i in tile_ids():
+        units.append(("linrec_tiles.hip", ["-DLINREC_TILE_ID=%d" % i], "tile_%d.o" % i))
+    cmds = []
+    for src, extra, obj in units:
+        if src.endswith(".cpp"):
+            cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", "-I" + os.path.join(ROOT, "include"),
+                   "-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ_DIR, obj)]
+        else:
+            cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ_DIR, obj)]
+        cmds.append(cmd)
+    jobs = jobs or min(8, os.cpu_count() or 4)
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        for out in ex.map(_run, cmds):
+            if verbose and out.strip():
+                print(out)
+    objs = [os.path.join(OBJ_DIR, o) for _, _, o in units]
+    tmp = LIB + ".tmp.%d" % os.getpid()
+    _run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs)
+    os.replace(tmp, LIB)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose="-v" in sys.argv))

@@ -1,0 +1,383 @@
+// C ABI of liblinrec (see include/linrec.h): argument checks, choice of variant and tile shape,
+// the cached per-(device, stream) workspace, and the kernel launches.
+#include "linrec.h"
+#include "linrec_launch.h"
+
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <map>
+#include <mutex>
+#include <utility>
+
+namespace linrec {
+
+#define X(ID, VEC, R, WC, WT) hipError_t launch_tile_##ID(Kind, bool, bool, const Args &, hipStream_t);
+LINREC_TILES(X)
+#undef X
+
+static const TileDesc kTiles[NUM_TILES] = {
+#define X(ID, VEC, R, WC, WT) {VEC, R, WC, WT},
+    LINREC_TILES(X)
+#undef X
+};
+
+const TileDesc &tile_desc(int id) { return kTiles[id - 1]; }
+
+hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, const Args &A, hipStream_t s)
+{
+    switch (id) {
+#define X(ID, VEC, R, WC, WT) \
+    case ID: return launch_tile_##ID(kind, bwd, hp_late, A, s);
+        LINREC_TILES(X)
+#undef X
+    default: return hipErrorInvalidValue;
+    }
+}
+
+namespace {
+
+// ---- process-wide options ------------------------------------------------------------------
+struct Options {
+    int64_t variant = LINREC_VARIANT_AUTO;
+    int64_t tile = 0;
+    int64_t chunk_tiles = 0;
+    int64_t spin_limit = 1 << 22;
+    int64_t hp_late = -1;  // -1 automatic
+    Options()
+    {
+        if (const char *v = getenv("LINREC_VARIANT")) {
+            if (!strcmp(v, "threephase")) variant = LINREC_VARIANT_THREEPHASE;
+            else if (!strcmp(v, "lookback")) variant = LINREC_VARIANT_LOOKBACK;
+            else if (!strcmp(v, "serial")) variant = LINREC_VARIANT_SERIAL;
+        }
+        if (const char *v = getenv("LINREC_TILE")) {
+            const long t = strtol(v, nullptr, 10);
+            if (t >= 0 && t <= NUM_TILES) tile = t;
+        }
+    }
+};
+Options &opts()
+{
+    static Options o;
+    return o;
+}
+
+char g_hip_error[256] = "";
+int hip_fail(hipError_t e, const char *what)
+{
+    snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", what, hipGetErrorString(e));
+    return LINREC_ERR_HIP;
+}
+
+// ---- workspace -----------------------------------------------------------------------------
+// One per (device, stream).  The look-back words live in their own allocation that nothing else
+// ever writes, because a stale word is told from a fresh one only by its epoch.
+struct Workspace {
+    // look-back: [ticket u64][err u32][pad to 256 B][lbIncl K*C u64][lbAgg 2*K*C u64]
+    void *lb = nullptr;
+    size_t lb_bytes = 0;
+    uint32_t epoch = 0;
+    unsigned long long tickets_issued = 0;
+    // three-phase: aggP, aggS, carry, each K*C fp32
+    void *tp = nullptr;
+    size_t tp_bytes = 0;
+};
+std::mutex g_mu;
+std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
+
+constexpr size_t kLbHeader = 256;
+
+// Grows the buffer if needed.  Growing waits for the stream (older kernels may still use the old
+// buffer), which only happens while the problem sizes seen on a stream are still increasing.
+int ensure(void **buf, size_t *have, size_t need, bool zero, hipStream_t s)
+{
+    if (*have >= need) return LINREC_OK;
+    hipError_t e;
+    if (*buf) {
+        if ((e = hipStreamSynchronize(s)) != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+        if ((e = hipFree(*buf)) != hipSuccess) return hip_fail(e, "hipFree");
+        *buf = nullptr;
+        *have = 0;
+    }
+    need = (need + ((size_t)1 << 20) - 1) & ~(((size_t)1 << 20) - 1);
+    if ((e = hipMalloc(buf, need)) != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
+    if (zero && (e = hipMemset(*buf, 0, need)) != hipSuccess) return hip_fail(e, "hipMemset(workspace)");
+    *have = need;
+    return LINREC_OK;
+}
+
+bool aligned16(const void *p) { return p == nullptr || ((uintptr_t)p & 15u) == 0; }
+
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+int pow2_at_least(int64_t x)
+{
+    int p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// Tile shape for a [T, C] problem when the caller did not fix one.
+int auto_tile(int64_t T, int64_t C, bool vec4, bool bwd, int variant)
+{
+    (void)T;
+    if (!vec4) return C >= 48 ? 1 : 2;
+    const int64_t cv = C / 4;
+    // Tall, narrow tiles keep the look-back cheap (few summaries per element); the row segment of a
+    // tile is WC*16 bytes, kept at >= 128 B.
+    int wc = cv >= 16 ? 16 : 8;
+    if (variant == LINREC_VARIANT_THREEPHASE) wc = cv >= 64 ? 64 : pow2_at_least(cv) < 8 ? 8 : pow2_at_least(cv);
+    const bool r16 = !bwd;
+    switch (wc) {
+    case 8: return r16 ? 7 : 3;
+    case 16: return r16 ? 8 : 4;
+    case 32: return r16 ? 9 : 5;
+    default: return r16 ? 10 : 6;
+    }
+}
+
+struct Plan {
+    int variant, tile;
+    bool hp_late;
+};
+
+// Picks variant and tile, honouring the options where they apply to this problem.
+Plan make_plan(int64_t T, int64_t C, bool vec4, bool bwd)
+{
+    Plan p;
+    p.variant = (int)opts().variant;
+    if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
+    p.tile = (int)opts().tile;
+    if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec == 4 && !vec4) p.tile = 0;
+    if (p.tile < 1 || p.tile > NUM_TILES) p.tile = auto_tile(T, C, vec4, bwd, p.variant);
+    const TileDesc &d = kTiles[p.tile - 1];
+    // per-thread byte offsets inside a tile are 32-bit, tickets of a call are 31-bit
+    const int64_t G = ceil_div(C, d.cols()), K = ceil_div(T, d.rows());
+    if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32) || K * G >= ((int64_t)1 << 31))
+        p.variant = LINREC_VARIANT_SERIAL;
+    p.hp_late = opts().hp_late < 0 ? (d.r >= 16) : (opts().hp_late != 0);
+    return p;
+}
+
+int run(Args A, bool bwd, bool vec4, hipStream_t s)
+{
+    const Plan plan = make_plan(A.T, A.C, vec4, bwd);
+    hipError_t e;
+    if (plan.variant == LINREC_VARIANT_SERIAL) {
+        if ((e = launch_serial(A, bwd, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
+        return LINREC_OK;
+    }
+    const TileDesc &d = kTiles[plan.tile - 1];
+    A.G = (int32_t)ceil_div(A.C, d.cols());
+    const int64_t tiles_t = ceil_div(A.T, d.rows());
+
+    int dev = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e, "hipGetDevice");
+    std::lock_guard<std::mutex> lock(g_mu);
+    Workspace &ws = g_ws[std::make_pair(dev, s)];
+
+    if (plan.variant == LINREC_VARIANT_THREEPHASE) {
+        // enough chunks to fill the GPU several times over, few enough that phase 2 stays small
+        int64_t M = opts().chunk_tiles;
+        if (M <= 0) M = ceil_div(tiles_t * A.G, 4096);
+        if (M < 1) M = 1;
+        if (M > (1 << 20)) M = 1 << 20;
+        A.M = (int32_t)M;
+        A.K = ceil_div(tiles_t, M);
+        const size_t kc = (size_t)A.K * (size_t)A.C;
+        int rc = ensure(&ws.tp, &ws.tp_bytes, 3 * kc * sizeof(float), false, s);
+        if (rc != LINREC_OK) return rc;
+        A.aggP = (float *)ws.tp;
+        A.aggS = A.aggP + kc;
+        A.carry = A.aggS + kc;
+        if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, A, s)) != hipSuccess)
+            return hip_fail(e, "launch(reduce)");
+        if ((e = launch_scan_summaries(A.aggP, A.aggS, bwd ? nullptr : A.h0, A.carry, A.K, A.C, s)) != hipSuccess)
+            return hip_fail(e, "launch(scan_summaries)");
+        if ((e = launch_tile_kernel(plan.tile, KIND_FIXUP, bwd, false, A, s)) != hipSuccess)
+            return hip_fail(e, "launch(fixup)");
+        return LINREC_OK;
+    }
+
+    // single pass with look-back
+    A.K = tiles_t;
+    A.M = 1;
+    const size_t kc = (size_t)A.K * (size_t)A.C;
+    const size_t old_bytes = ws.lb_bytes;
+    int rc = ensure(&ws.lb, &ws.lb_bytes, kLbHeader + 3 * kc * sizeof(unsigned long long), true, s);
+    if (rc != LINREC_OK) return rc;
+    if (ws.lb_bytes != old_bytes) ws.tickets_issued = 0;  // fresh, zeroed buffer: its counter restarts
+    if (++ws.epoch == 0) {
+        // the 32-bit epoch wrapped: forget every stale word before reusing epoch values
+        if ((e = hipMemsetAsync((char *)ws.lb + kLbHeader, 0, ws.lb_bytes - kLbHeader, s)) != hipSuccess)
+            return hip_fail(e, "hipMemsetAsync(workspace)");
+        ws.epoch = 1;
+    }
+    A.ticket = (unsigned long long *)ws.lb;
+    A.err = (uint32_t *)((char *)ws.lb + 8);
+    A.lbIncl = (unsigned long long *)((char *)ws.lb + kLbHeader);
+    A.lbAgg = A.lbIncl + kc;
+    A.ticket_base = ws.tickets_issued;
+    A.epoch = ws.epoch;
+    A.spin_limit = (uint32_t)opts().spin_limit;
+    if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, A, s)) != hipSuccess)
+        return hip_fail(e, "launch(lookback)");
+    ws.tickets_issued += (unsigned long long)(A.K * A.G);
+    return LINREC_OK;
+}
+
+}  // namespace
+}  // namespace linrec
+
+using namespace linrec;
+
+extern "C" int linrec_forward(const float *lambda, const float *x, const float *h0, float *h_out, int64_t T, int64_t B,
+                              int64_t n, void *stream)
+{
+    const int rc = linrec_validate_forward(lambda, x, h0, h_out, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (T == 0 || C == 0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = lambda;
+    A.b = x;
+    A.h0 = h0;
+    A.out0 = h_out;
+    A.T = T;
+    A.C = C;
+    const bool vec4 = (C % 4 == 0) && aligned16(lambda) && aligned16(x) && aligned16(h0) && aligned16(h_out);
+    return run(A, false, vec4, (hipStream_t)stream);
+}
+
+extern "C" int linrec_backward(const float *lambda, const float *h, const float *h0, const float *grad_h, float *grad_x,
+                               float *grad_lambda, float *grad_h0, int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_backward(lambda, h, h0, grad_h, grad_x, grad_lambda, grad_h0, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (C == 0) return LINREC_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (T == 0) {
+        if (grad_h0) {
+            const hipError_t e = launch_fill_zero(grad_h0, C, s);
+            if (e != hipSuccess) return hip_fail(e, "launch(fill_zero)");
+        }
+        return LINREC_OK;
+    }
+    if (!grad_x && !grad_lambda && !grad_h0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = lambda;
+    A.b = grad_h;
+    A.hprev = h;
+    A.h0 = h0;
+    A.out0 = grad_x;
+    A.out1 = grad_lambda;
+    A.gh0 = grad_h0;
+    A.T = T;
+    A.C = C;
+    const bool vec4 = (C % 4 == 0) && aligned16(lambda) && aligned16(h) && aligned16(h0) && aligned16(grad_h) &&
+                      aligned16(grad_x) && aligned16(grad_lambda) && aligned16(grad_h0);
+    return run(A, true, vec4, s);
+}
+
+extern "C" int linrec_set_option(int option, int64_t value)
+{
+    switch (option) {
+    case LINREC_OPT_VARIANT:
+        if (value < LINREC_VARIANT_AUTO || value > LINREC_VARIANT_SERIAL) return LINREC_ERR_OPTION;
+        opts().variant = value;
+        return LINREC_OK;
+    case LINREC_OPT_TILE:
+        if (value < 0 || value > NUM_TILES) return LINREC_ERR_OPTION;
+        opts().tile = value;
+        return LINREC_OK;
+    case LINREC_OPT_CHUNK_TILES:
+        if (value < 0 || value > (1 << 20)) return LINREC_ERR_OPTION;
+        opts().chunk_tiles = value;
+        return LINREC_OK;
+    case LINREC_OPT_SPIN_LIMIT:
+        if (value < 1 || value > 0x7fffffff) return LINREC_ERR_OPTION;
+        opts().spin_limit = value;
+        return LINREC_OK;
+    case LINREC_OPT_HPREV_LATE:
+        if (value < -1 || value > 1) return LINREC_ERR_OPTION;
+        opts().hp_late = value;
+        return LINREC_OK;
+    default: return LINREC_ERR_OPTION;
+    }
+}
+
+extern "C" int64_t linrec_get_option(int option)
+{
+    switch (option) {
+    case LINREC_OPT_VARIANT: return opts().variant;
+    case LINREC_OPT_TILE: return opts().tile;
+    case LINREC_OPT_CHUNK_TILES: return opts().chunk_tiles;
+    case LINREC_OPT_SPIN_LIMIT: return opts().spin_limit;
+    case LINREC_OPT_HPREV_LATE: return opts().hp_late;
+    default: return LINREC_ERR_OPTION;
+    }
+}
+
+extern "C" int linrec_tile_info(int tile_id, int *threads_cols, int *threads_time, int *rows_per_thread,
+                                int *cols_per_thread)
+{
+    if (tile_id < 1 || tile_id > NUM_TILES) return LINREC_ERR_OPTION;
+    const TileDesc &d = tile_desc(tile_id);
+    if (threads_cols) *threads_cols = d.wc;
+    if (threads_time) *threads_time = d.wt;
+    if (rows_per_thread) *rows_per_thread = d.r;
+    if (cols_per_thread) *cols_per_thread = d.vec;
+    return LINREC_OK;
+}
+
+extern "C" int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int aligned16_and_c_mult4, int *variant,
+                           int *tile_id)
+{
+    int64_t C = B * n;
+    if (T <= 0 || B <= 0 || n <= 0) return LINREC_ERR_SHAPE;
+    const Plan p = make_plan(T, C, aligned16_and_c_mult4 != 0 && C % 4 == 0, backward != 0);
+    if (variant) *variant = p.variant;
+    if (tile_id) *tile_id = p.tile;
+    return LINREC_OK;
+}
+
+extern "C" int linrec_check(void *stream)
+{
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    int dev = 0;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e, "hipGetDevice");
+    std::lock_guard<std::mutex> lock(g_mu);
+    auto it = g_ws.find(std::make_pair(dev, s));
+    if (it == g_ws.end() || !it->second.lb) return LINREC_OK;
+    uint32_t flag = 0;
+    char *p = (char *)it->second.lb + 8;
+    if ((e = hipMemcpy(&flag, p, sizeof flag, hipMemcpyDeviceToHost)) != hipSuccess) return hip_fail(e, "hipMemcpy");
+    if (!flag) return LINREC_OK;
+    if ((e = hipMemset(p, 0, sizeof flag)) != hipSuccess) return hip_fail(e, "hipMemset");
+    return LINREC_ERR_DEVICE;
+}
+
+extern "C" int linrec_release_workspace(void)
+{
+    std::lock_guard<std::mutex> lock(g_mu);
+    int rc = LINREC_OK;
+    int cur = 0;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    for (auto &kv : g_ws) {
+        if (hipSetDevice(kv.first.first) != hipSuccess) { rc = LINREC_ERR_HIP; continue; }
+        if (kv.second.lb && hipFree(kv.second.lb) != hipSuccess) rc = LINREC_ERR_HIP;
+        if (kv.second.tp && hipFree(kv.second.tp) != hipSuccess) rc = LINREC_ERR_HIP;
+    }
+    g_ws.clear();
+    if (have_cur) (void)hipSetDevice(cur);
+    return rc;
+}
+
+extern "C" const char *linrec_last_hip_error(void) { return g_hip_error; }

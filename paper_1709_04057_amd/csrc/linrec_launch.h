@@ -1,0 +1,69 @@
+// Host-visible part of the kernel layer: the argument block every kernel takes, the table of tile
+// shapes, and the launch functions the C API calls.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace linrec {
+
+struct Args {
+    const float *a;      // lambda                                  [T, C]
+    const float *b;      // forward: x;  backward: grad_h            [T, C]
+    const float *hprev;  // backward: h (forward output);  forward: unused
+    const float *h0;     // [C] or nullptr
+    float *out0;         // forward: h_out;  backward: grad_x (may be nullptr)
+    float *out1;         // backward: grad_lambda (may be nullptr)
+    float *gh0;          // backward: grad_h0 [C] (may be nullptr)
+    int64_t T, C;
+    int64_t K;           // tiles (look-back) or chunks (three-phase) along time
+    int32_t G;           // column groups of COLS columns
+    int32_t M;           // three-phase: tiles walked per chunk
+    // three-phase workspace, each [K, C] fp32
+    float *aggP, *aggS, *carry;
+    // look-back workspace: 64-bit words {epoch : 32 | fp32 bits : 32}
+    unsigned long long *lbAgg;   // [K, C, 2]  (P, S) of a tile
+    unsigned long long *lbIncl;  // [K, C]     state after the tile's last step
+    unsigned long long *ticket;  // monotonically increasing tile counter
+    unsigned long long ticket_base;
+    uint32_t epoch;
+    uint32_t spin_limit;
+    uint32_t *err;
+};
+
+enum Kind { KIND_REDUCE = 0, KIND_FIXUP = 1, KIND_LOOKBACK = 2 };
+
+struct TileDesc {
+    int vec, r, wc, wt;
+    int rows() const { return r * wt; }
+    int cols() const { return vec * wc; }
+    int threads() const { return wc * wt; }
+};
+
+// Tile shapes, 1-based ids as used by LINREC_OPT_TILE.  Shapes 1-2 take one column per thread and
+// work for any C and any 4-byte alignment; the others take four columns per thread (16-byte
+// accesses) and need C % 4 == 0 and 16-byte aligned tensors.
+#define LINREC_TILES(X) \
+    X(1, 1, 8, 64, 4)   \
+    X(2, 1, 8, 16, 16)  \
+    X(3, 4, 8, 8, 32)   \
+    X(4, 4, 8, 16, 16)  \
+    X(5, 4, 8, 32, 8)   \
+    X(6, 4, 8, 64, 4)   \
+    X(7, 4, 16, 8, 32)  \
+    X(8, 4, 16, 16, 16) \
+    X(9, 4, 16, 32, 8)  \
+    X(10, 4, 16, 64, 4)
+constexpr int NUM_TILES = 10;
+
+const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
+
+// Launches kernel `kind` for tile shape `id` with grid A.K * A.G.  hp_late (look-back, backward):
+// load h after the rescan instead of together with lambda and grad_h.
+hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, const Args &A, hipStream_t s);
+
+hipError_t launch_scan_summaries(const float *aggP, const float *aggS, const float *h0, float *carry, int64_t K,
+                                 int64_t C, hipStream_t s);
+hipError_t launch_serial(const Args &A, bool bwd, hipStream_t s);
+hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
+
+}  // namespace linrec

@@ -1,0 +1,155 @@
+// Kernels that do not depend on the tile shape:
+//   k_scan_summaries -- phase 2 of Algorithm 1 (arXiv 1709.04057): C_i = P_i*C_{i-1} + R_i with
+//                       C_{-1} = h_0, over the K chunk summaries of every column;
+//   k_serial_fwd/bwd -- the paper's comparison kernel of Section 4.1.1: serial over the sequence
+//                       length, parallel over features and minibatch.
+#include "linrec_launch.h"
+
+namespace linrec {
+
+// DPP helpers: a lane takes `src` from another lane of the wavefront, or keeps `old` when the
+// source lane does not exist or the row is masked off.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp(float old, float src)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), CTRL, ROW_MASK, 0xF, false));
+}
+
+// One Kogge-Stone step of the inclusive scan of affine pairs: (Pe,Se) is the pair of the earlier
+// lane (identity (1,0) when there is none), combined on the left of the lane's own pair.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ void scan_step(float &P, float &S)
+{
+    const float pe = dpp<CTRL, ROW_MASK>(1.0f, P);
+    const float se = dpp<CTRL, ROW_MASK>(0.0f, S);
+    S = fmaf(P, se, S);
+    P = pe * P;
+}
+
+// Inclusive scan over the 64 lanes of a wavefront, lane index = time order.
+__device__ __forceinline__ void wave_scan_pairs(float &P, float &S)
+{
+    scan_step<0x111, 0xF>(P, S);  // row_shr:1
+    scan_step<0x112, 0xF>(P, S);  // row_shr:2
+    scan_step<0x114, 0xF>(P, S);  // row_shr:4
+    scan_step<0x118, 0xF>(P, S);  // row_shr:8   -> inclusive inside each row of 16 lanes
+    scan_step<0x142, 0xA>(P, S);  // row_bcast:15 into rows 1 and 3
+    scan_step<0x143, 0xC>(P, S);  // row_bcast:31 into rows 2 and 3
+}
+
+constexpr int SCAN_COLS = 16;     // columns per workgroup
+constexpr int SCAN_WAVES = 4;
+
+// grid = ceil(C / SCAN_COLS).  Blocks of 64 chunks x SCAN_COLS columns are staged through LDS
+// (coalesced along the columns in global memory, transposed so that lanes hold consecutive chunks),
+// scanned with DPP, and the state entering each chunk is written back the same way.  The state is
+// carried across the K/64 blocks in a register per (wavefront, column).
+__global__ __launch_bounds__(SCAN_WAVES * 64) void k_scan_summaries(const float *__restrict__ aggP,
+                                                                    const float *__restrict__ aggS,
+                                                                    const float *__restrict__ h0,
+                                                                    float *__restrict__ carry, int64_t K, int64_t C)
+{
+    __shared__ float tP[64][SCAN_COLS + 1];
+    __shared__ float tS[64][SCAN_COLS + 1];
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int64_t c0 = (int64_t)blockIdx.x * SCAN_COLS;
+    constexpr int PER_WAVE = SCAN_COLS / SCAN_WAVES;
+    float run[PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < PER_WAVE; ++i) {
+        const int64_t c = c0 + wave + SCAN_WAVES * i;
+        run[i] = (h0 && c < C) ? h0[c] : 0.0f;
+    }
+    for (int64_t k0 = 0; k0 < K; k0 += 64) {
+        for (int idx = tid; idx < 64 * SCAN_COLS; idx += SCAN_WAVES * 64) {
+            const int kk = idx / SCAN_COLS, cc = idx % SCAN_COLS;
+            float p = 1.0f, s = 0.0f;
+            if (k0 + kk < K && c0 + cc < C) {
+                p = aggP[(k0 + kk) * C + c0 + cc];
+                s = aggS[(k0 + kk) * C + c0 + cc];
+            }
+            tP[kk][cc] = p;
+            tS[kk][cc] = s;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < PER_WAVE; ++i) {
+            const int cc = wave + SCAN_WAVES * i;
+            float P = tP[lane][cc], S = tS[lane][cc];
+            wave_scan_pairs(P, S);
+            const float state = fmaf(P, run[i], S);              // state after chunk k0 + lane
+            tS[lane][cc] = dpp<0x138, 0xF>(run[i], state);       // wave_shr:1 -> state entering the chunk
+            run[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(state), 63));
+        }
+        __syncthreads();
+        for (int idx = tid; idx < 64 * SCAN_COLS; idx += SCAN_WAVES * 64) {
+            const int kk = idx / SCAN_COLS, cc = idx % SCAN_COLS;
+            if (k0 + kk < K && c0 + cc < C) carry[(k0 + kk) * C + c0 + cc] = tS[kk][cc];
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void k_serial_fwd(const float *__restrict__ a, const float *b,
+                                                    const float *__restrict__ h0, float *out, int64_t T, int64_t C)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s = h0 ? h0[c] : 0.0f;
+#pragma unroll 8
+    for (int64_t t = 0; t < T; ++t) {
+        s = fmaf(a[t * C + c], s, b[t * C + c]);
+        out[t * C + c] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_serial_bwd(const float *__restrict__ lam, const float *__restrict__ h,
+                                                    const float *__restrict__ h0, const float *e, float *gx, float *gl,
+                                                    float *gh0, int64_t T, int64_t C)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float g = 0.0f;
+#pragma unroll 4
+    for (int64_t t = T - 1; t >= 0; --t) {
+        const float l = (t + 1 < T) ? lam[(t + 1) * C + c] : 0.0f;
+        g = fmaf(l, g, e[t * C + c]);
+        const float hp = (t > 0) ? h[(t - 1) * C + c] : (h0 ? h0[c] : 0.0f);
+        if (gx) gx[t * C + c] = g;
+        if (gl) gl[t * C + c] = g * hp;
+    }
+    if (gh0) gh0[c] = lam[c] * g;
+}
+
+__global__ void k_fill_zero(float *p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0.0f;
+}
+
+hipError_t launch_scan_summaries(const float *aggP, const float *aggS, const float *h0, float *carry, int64_t K,
+                                 int64_t C, hipStream_t s)
+{
+    const unsigned grid = (unsigned)((C + SCAN_COLS - 1) / SCAN_COLS);
+    hipLaunchKernelGGL(k_scan_summaries, dim3(grid), dim3(SCAN_WAVES * 64), 0, s, aggP, aggS, h0, carry, K, C);
+    return hipGetLastError();
+}
+
+hipError_t launch_serial(const Args &A, bool bwd, hipStream_t s)
+{
+    const unsigned grid = (unsigned)((A.C + 255) / 256);
+    if (!bwd) hipLaunchKernelGGL(k_serial_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.h0, A.out0, A.T, A.C);
+    else
+        hipLaunchKernelGGL(k_serial_bwd, dim3(grid), dim3(256), 0, s, A.a, A.hprev, A.h0, A.b, A.out0, A.out1, A.gh0,
+                           A.T, A.C);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
+}  // namespace linrec

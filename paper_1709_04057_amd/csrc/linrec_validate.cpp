@@ -1,0 +1,88 @@
+// Host-only argument checks of liblinrec.  No HIP call is made here, so the checks can be
+// exercised (and run under host sanitizers) on a machine without a GPU.
+#include "linrec.h"
+
+#include <stddef.h>
+#include <stdint.h>
+
+namespace {
+
+constexpr int64_t kMaxElements = (int64_t)1 << 40;
+
+// Fills C = B*n and E = T*C; returns false when a dimension is negative or a product overflows the
+// supported range.
+bool shape_ok(int64_t T, int64_t B, int64_t n, int64_t *C, int64_t *E)
+{
+    if (T < 0 || B < 0 || n < 0) return false;
+    if (B > kMaxElements || n > kMaxElements || T > kMaxElements) return false;
+    if (B != 0 && n > kMaxElements / B) return false;
+    const int64_t c = B * n;
+    if (c != 0 && T > kMaxElements / c) return false;
+    *C = c;
+    *E = T * c;
+    return true;
+}
+
+// Do the element ranges [p, p+np) and [q, q+nq) of fp32 arrays share a byte?
+bool overlaps(const float *p, int64_t np, const float *q, int64_t nq)
+{
+    if (!p || !q || np == 0 || nq == 0) return false;
+    const uintptr_t a0 = (uintptr_t)p, a1 = a0 + (uintptr_t)np * sizeof(float);
+    const uintptr_t b0 = (uintptr_t)q, b1 = b0 + (uintptr_t)nq * sizeof(float);
+    return a0 < b1 && b0 < a1;
+}
+
+}  // namespace
+
+extern "C" int linrec_validate_forward(const float *lambda, const float *x, const float *h0, const float *h_out,
+                                       int64_t T, int64_t B, int64_t n)
+{
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (E == 0) return LINREC_OK;
+    if (!lambda || !x || !h_out) return LINREC_ERR_NULL;
+    if (overlaps(h_out, E, lambda, E)) return LINREC_ERR_ALIAS;
+    if (h_out != x && overlaps(h_out, E, x, E)) return LINREC_ERR_ALIAS;
+    if (overlaps(h_out, E, h0, C)) return LINREC_ERR_ALIAS;
+    return LINREC_OK;
+}
+
+extern "C" int linrec_validate_backward(const float *lambda, const float *h, const float *h0, const float *grad_h,
+                                        const float *grad_x, const float *grad_lambda, const float *grad_h0,
+                                        int64_t T, int64_t B, int64_t n)
+{
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (C == 0) return LINREC_OK;
+    if (T == 0) return LINREC_OK;  // only grad_h0 (if given) is touched: zero-filled
+    if (!lambda || !h || !grad_h) return LINREC_ERR_NULL;
+    const float *outs[3] = {grad_x, grad_lambda, grad_h0};
+    const int64_t out_len[3] = {E, E, C};
+    const float *ins[4] = {lambda, h, grad_h, h0};
+    const int64_t in_len[4] = {E, E, E, C};
+    for (int o = 0; o < 3; ++o) {
+        for (int i = 0; i < 4; ++i) {
+            if (o == 0 && i == 2 && grad_x == grad_h) continue;  // exact in-place update of the gradient
+            if (overlaps(outs[o], out_len[o], ins[i], in_len[i])) return LINREC_ERR_ALIAS;
+        }
+        for (int p = o + 1; p < 3; ++p)
+            if (overlaps(outs[o], out_len[o], outs[p], out_len[p])) return LINREC_ERR_ALIAS;
+    }
+    return LINREC_OK;
+}
+
+extern "C" const char *linrec_status_string(int status)
+{
+    switch (status) {
+    case LINREC_OK: return "ok";
+    case LINREC_ERR_NULL: return "a required pointer is NULL";
+    case LINREC_ERR_SHAPE: return "negative dimension or T*B*n out of range";
+    case LINREC_ERR_ALIAS: return "an output overlaps another tensor";
+    case LINREC_ERR_HIP: return "HIP allocation or launch failed";
+    case LINREC_ERR_OPTION: return "unknown option or value out of range";
+    case LINREC_ERR_DEVICE: return "a look-back wait exceeded its spin limit";
+    default: return "unknown status";
+    }
+}
+
+extern "C" int linrec_version(void) { return 100; }

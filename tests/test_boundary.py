@@ -1,0 +1,120 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, validates arguments before any HIP call, and reports its tile table."""
+import ctypes
+
+import pytest
+
+import paper_1709_04057_amd as lr
+
+
+@pytest.fixture(scope="module")
+def L():
+    return lr.lib()
+
+
+def test_exports_every_declared_symbol(L):
+    names = lr.declared_symbols()
+    assert {"linrec_forward", "linrec_backward", "linrec_status_string", "linrec_version"} <= set(names)
+    for name in names:
+        assert hasattr(L, name), f"liblinrec.so does not export {name}"
+
+
+def test_version_and_status_strings(L):
+    assert lr.linrec_version() >= 100
+    assert lr.linrec_status_string(0) == "ok"
+    for code in range(-6, 0):
+        assert lr.linrec_status_string(code) not in ("ok", "unknown status")
+    assert lr.linrec_status_string(-99) == "unknown status"
+
+
+def _p(addr):
+    return ctypes.c_void_p(addr)
+
+
+E = 1000 * 4 * 8  # elements of a [1000, 4, 8] tensor
+A0, A1, A2, A3, A4, A5, A6 = (0x10000000 + i * 0x1000000 for i in range(7))
+
+
+def test_validate_forward(L):
+    v = L.linrec_validate_forward
+    assert v(_p(A0), _p(A1), _p(A2), _p(A3), 1000, 4, 8) == 0
+    assert v(_p(A0), _p(A1), None, _p(A3), 1000, 4, 8) == 0               # h0 optional
+    assert v(_p(A0), _p(A1), None, _p(A1), 1000, 4, 8) == 0               # exact in-place on x
+    assert v(None, _p(A1), None, _p(A3), 1000, 4, 8) == -1
+    assert v(_p(A0), None, None, _p(A3), 1000, 4, 8) == -1
+    assert v(_p(A0), _p(A1), None, None, 1000, 4, 8) == -1
+    assert v(_p(A0), _p(A1), None, _p(A3), -1, 4, 8) == -2
+    assert v(_p(A0), _p(A1), None, _p(A3), 1 << 30, 1 << 20, 8) == -2     # T*B*n out of range
+    assert v(_p(A0), _p(A1), None, _p(A3), 1 << 62, 1 << 62, 1 << 62) == -2
+    assert v(_p(A0), _p(A1), None, _p(A0), 1000, 4, 8) == -3              # h_out on lambda
+    assert v(_p(A0), _p(A1), None, _p(A1 + 4), 1000, 4, 8) == -3          # partial overlap with x
+    assert v(_p(A0), _p(A1), _p(A3 + 4 * (E - 1)), _p(A3), 1000, 4, 8) == -3  # h0 inside h_out
+    assert v(None, None, None, None, 0, 4, 8) == 0                        # empty problems are no-ops
+    assert v(None, None, None, None, 1000, 0, 8) == 0
+
+
+def test_validate_backward(L):
+    v = L.linrec_validate_backward
+    ok = (_p(A0), _p(A1), _p(A2), _p(A3), _p(A4), _p(A5), _p(A6))
+    assert v(*ok, 1000, 4, 8) == 0
+    assert v(_p(A0), _p(A1), None, _p(A3), None, None, None, 1000, 4, 8) == 0   # every output optional
+    assert v(_p(A0), _p(A1), None, _p(A3), _p(A3), _p(A5), None, 1000, 4, 8) == 0  # grad_x in place on grad_h
+    assert v(None, _p(A1), None, _p(A3), _p(A4), None, None, 1000, 4, 8) == -1
+    assert v(_p(A0), None, None, _p(A3), _p(A4), None, None, 1000, 4, 8) == -1
+    assert v(_p(A0), _p(A1), None, None, _p(A4), None, None, 1000, 4, 8) == -1
+    assert v(_p(A0), _p(A1), None, _p(A3), _p(A0), None, None, 1000, 4, 8) == -3   # grad_x on lambda
+    assert v(_p(A0), _p(A1), None, _p(A3), _p(A4), _p(A1), None, 1000, 4, 8) == -3  # grad_lambda on h
+    assert v(_p(A0), _p(A1), None, _p(A3), _p(A4), _p(A4), None, 1000, 4, 8) == -3  # two outputs share memory
+    assert v(_p(A0), _p(A1), None, _p(A3), _p(A4), _p(A3), None, 1000, 4, 8) == -3  # grad_lambda on grad_h
+    assert v(_p(A0), _p(A1), None, _p(A3), _p(A3 + 8), None, None, 1000, 4, 8) == -3  # shifted in-place
+    assert v(*ok, 1000, 4, -8) == -2
+    assert v(None, None, None, None, None, None, _p(A6), 0, 4, 8) == 0
+
+
+def test_entry_points_validate_before_touching_the_gpu(L):
+    # invalid arguments must come back as error codes even on a machine without a GPU
+    assert L.linrec_forward(None, _p(A1), None, _p(A3), 10, 2, 2, None) == -1
+    assert L.linrec_forward(_p(A0), _p(A1), None, _p(A0), 10, 2, 2, None) == -3
+    assert L.linrec_forward(_p(A0), _p(A1), None, _p(A3), -5, 2, 2, None) == -2
+    assert L.linrec_forward(None, None, None, None, 0, 2, 2, None) == 0
+    assert L.linrec_backward(_p(A0), None, None, _p(A3), _p(A4), None, None, 10, 2, 2, None) == -1
+    assert L.linrec_backward(None, None, None, None, None, None, None, 10, 0, 2, None) == 0
+
+
+def test_options_and_tile_table(L):
+    assert lr.linrec_get_option(lr.OPT_VARIANT) in (0, 1, 2, 3)
+    old = lr.linrec_get_option(lr.OPT_VARIANT)
+    lr.linrec_set_option(lr.OPT_VARIANT, lr.VARIANT_THREEPHASE)
+    assert lr.linrec_get_option(lr.OPT_VARIANT) == lr.VARIANT_THREEPHASE
+    lr.linrec_set_option(lr.OPT_VARIANT, old)
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_set_option(lr.OPT_VARIANT, 17)
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_set_option(99, 0)
+    tiles = []
+    i = 1
+    while (info := lr.linrec_tile_info(i)) is not None:
+        tiles.append(info)
+        i += 1
+    assert len(tiles) >= 4
+    for t in tiles:
+        assert t["cols_per_thread"] in (1, 4)
+        assert t["threads_cols"] * t["threads_time"] in (256, 512, 1024)
+        assert t["rows"] == t["threads_time"] * t["rows_per_thread"]
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_set_option(lr.OPT_TILE, len(tiles) + 1)
+
+
+def test_plan_is_host_only_and_consistent(L):
+    for (T, B, n) in [(1024, 2, 32), (65536, 4, 256), (1048576, 1, 128), (4096, 16, 1024), (262144, 8, 512), (7, 1, 3)]:
+        for bwd in (False, True):
+            for vec4 in (False, True):
+                variant, tile = lr.linrec_plan(T, B, n, backward=bwd, vec4=vec4)
+                info = lr.linrec_tile_info(tile)
+                assert variant in (lr.VARIANT_THREEPHASE, lr.VARIANT_LOOKBACK, lr.VARIANT_SERIAL)
+                assert info is not None
+                if not vec4 or (B * n) % 4:
+                    assert info["cols_per_thread"] == 1
+    # a tile whose rows would not fit 32-bit offsets falls back to the serial kernel
+    variant, _ = lr.linrec_plan(64, 1, 1 << 24, vec4=True)
+    assert variant == lr.VARIANT_SERIAL
