@@ -75,12 +75,12 @@ int hip_fail(hipError_t e, const char *what)
 // One per (device, stream).  The look-back words live in their own allocation that nothing else
 // ever writes, because a stale word is told from a fresh one only by its epoch.
 struct Workspace {
-    // look-back: [ticket u64][err u32][pad to 256 B][lbIncl K*C u64][lbAgg 2*K*C u64]
+    // look-back: [ticket u64][err u32][pad to 256 B][lbIncl K*C u64][lbAgg 3*K*C u64]
     void *lb = nullptr;
     size_t lb_bytes = 0;
     uint32_t epoch = 0;
     unsigned long long tickets_issued = 0;
-    // three-phase: aggP, aggS, carry, each K*C fp32
+    // three-phase: aggP, aggS, carry, each K*C fp64
     void *tp = nullptr;
     size_t tp_bytes = 0;
 };
@@ -187,9 +187,9 @@ int run(Args A, bool bwd, bool vec4, hipStream_t s)
         A.M = (int32_t)M;
         A.K = ceil_div(tiles_t, M);
         const size_t kc = (size_t)A.K * (size_t)A.C;
-        int rc = ensure(&ws.tp, &ws.tp_bytes, 3 * kc * sizeof(float), false, s);
+        int rc = ensure(&ws.tp, &ws.tp_bytes, 3 * kc * sizeof(double), false, s);
         if (rc != LINREC_OK) return rc;
-        A.aggP = (float *)ws.tp;
+        A.aggP = (double *)ws.tp;
         A.aggS = A.aggP + kc;
         A.carry = A.aggS + kc;
         if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, A, s)) != hipSuccess)
@@ -206,7 +206,7 @@ int run(Args A, bool bwd, bool vec4, hipStream_t s)
     A.M = 1;
     const size_t kc = (size_t)A.K * (size_t)A.C;
     const size_t old_bytes = ws.lb_bytes;
-    int rc = ensure(&ws.lb, &ws.lb_bytes, kLbHeader + 3 * kc * sizeof(unsigned long long), true, s);
+    int rc = ensure(&ws.lb, &ws.lb_bytes, kLbHeader + 4 * kc * sizeof(unsigned long long), true, s);
     if (rc != LINREC_OK) return rc;
     if (ws.lb_bytes != old_bytes) ws.tickets_issued = 0;  // fresh, zeroed buffer: its counter restarts
     if (++ws.epoch == 0) {

@@ -34,6 +34,34 @@ struct Geo {
 template <int N>
 using vec = float __attribute__((ext_vector_type(N)));
 
+// Summaries are kept in fp64.  A product of many lambdas computed in fp32 drifts coherently when the
+// factors repeat (constant decay along T), which no fp32 evaluation order avoids; in fp64 the drift is
+// far below the fp32 resolution of the result.  Only the O(T*C/R) summary arithmetic pays for this,
+// the per-element rescan stays fp32.
+template <int N>
+using dvec = double __attribute__((ext_vector_type(N)));
+
+template <int N>
+__device__ __forceinline__ dvec<N> widen(vec<N> v)
+{
+    return __builtin_convertvector(v, dvec<N>);
+}
+template <int N>
+__device__ __forceinline__ vec<N> narrow(dvec<N> v)
+{
+    return __builtin_convertvector(v, vec<N>);
+}
+template <int N>
+__device__ __forceinline__ dvec<N> dsplat(double x)
+{
+    return dvec<N>(x);
+}
+template <int N>
+__device__ __forceinline__ dvec<N> dfma(dvec<N> a, dvec<N> b, dvec<N> c)
+{
+    return __builtin_elementwise_fma(a, b, c);
+}
+
 template <int N>
 __device__ __forceinline__ vec<N> ld(const float *p)
 {
@@ -142,14 +170,16 @@ __device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G,
     }
 }
 
-// Phase 1 of Algorithm 1 for one thread: P = prod a_j,  S = recurrence over the rows from state 0.
+// Phase 1 of Algorithm 1 for one thread: P = prod a_j (fp64),  S = recurrence over the rows from
+// state 0 (fp32: at most R roundings, each relative to the running value).
 template <class G>
-__device__ __forceinline__ void local_reduce(const Rows<G> &r, vec<G::VEC> &P, vec<G::VEC> &S)
+__device__ __forceinline__ void local_reduce(const Rows<G> &r, dvec<G::VEC> &P, vec<G::VEC> &S)
 {
-    vec<G::VEC> p = r.a[0], s = r.b[0];
+    dvec<G::VEC> p = widen<G::VEC>(r.a[0]);
+    vec<G::VEC> s = r.b[0];
 #pragma unroll
     for (int j = 1; j < G::R; ++j) {
-        p *= r.a[j];
+        p *= widen<G::VEC>(r.a[j]);
         s = vfma<G::VEC>(r.a[j], s, r.b[j]);
     }
     P = p;
@@ -201,17 +231,29 @@ __device__ __forceinline__ bool tile_interior(const Args &A, int64_t tu0, int g)
 // Phase 2 inside a tile: thread (tt, tc) gets the composition of the summaries of the threads with
 // smaller tt in its columns (identity for tt == 0).  sP/sS must have been filled and a barrier passed.
 template <class G>
-__device__ __forceinline__ void lds_exclusive(const vec<G::VEC> (*sP)[G::WC], const vec<G::VEC> (*sS)[G::WC], int tt,
-                                              int tc, vec<G::VEC> &Pe, vec<G::VEC> &Se)
+__device__ __forceinline__ void lds_exclusive(const dvec<G::VEC> (*sP)[G::WC], const vec<G::VEC> (*sS)[G::WC], int tt,
+                                              int tc, dvec<G::VEC> &Pe, dvec<G::VEC> &Se)
 {
-    vec<G::VEC> pe = splat<G::VEC>(1.0f), se = splat<G::VEC>(0.0f);
+    dvec<G::VEC> pe = dsplat<G::VEC>(1.0), se = dsplat<G::VEC>(0.0);
     for (int i = 0; i < tt; ++i) {
-        const vec<G::VEC> p = sP[i][tc], s = sS[i][tc];
-        se = vfma<G::VEC>(p, se, s);
+        const dvec<G::VEC> p = sP[i][tc];
+        const dvec<G::VEC> s = widen<G::VEC>(sS[i][tc]);
+        se = dfma<G::VEC>(p, se, s);
         pe *= p;
     }
     Pe = pe;
     Se = se;
+}
+
+template <int N>
+__device__ __forceinline__ dvec<N> ldd(const double *p)
+{
+    return *reinterpret_cast<const dvec<N> *>(p);
+}
+template <int N>
+__device__ __forceinline__ void std_(double *p, dvec<N> v)
+{
+    *reinterpret_cast<dvec<N> *>(p) = v;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -222,7 +264,7 @@ template <class G, bool BWD>
 __global__ __launch_bounds__(G::THREADS) void k_reduce(const Args A)
 {
     constexpr int VEC = G::VEC, R = G::R, WC = G::WC, WT = G::WT, ROWS = G::ROWS;
-    __shared__ vec<VEC> sP[WT][WC];
+    __shared__ dvec<VEC> sP[WT][WC];
     __shared__ vec<VEC> sS[WT][WC];
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
     const int g = (int)(blockIdx.x % (unsigned)A.G);
@@ -230,13 +272,14 @@ __global__ __launch_bounds__(G::THREADS) void k_reduce(const Args A)
     const int64_t col = ((int64_t)g * WC + tc) * VEC;
     const bool col_ok = col < A.C;
 
-    vec<VEC> Pc = splat<VEC>(1.0f), Sc = splat<VEC>(0.0f);  // chunk total so far (tt == WT-1 only)
+    dvec<VEC> Pc = dsplat<VEC>(1.0), Sc = dsplat<VEC>(0.0);  // chunk total so far (tt == WT-1 only)
     for (int m = 0; m < A.M; ++m) {
         const int64_t tu0 = (k * A.M + m) * ROWS;
         if (tu0 >= A.T) break;
         const bool interior = tile_interior<G, BWD>(A, tu0, g);
         Rows<G> r;
-        vec<VEC> P, S;
+        dvec<VEC> P;
+        vec<VEC> S;
         const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
         tile_load<G, BWD>(A, ad, tu0 + (int64_t)tt * R, col_ok, interior, r);
         local_reduce<G>(r, P, S);
@@ -245,17 +288,17 @@ __global__ __launch_bounds__(G::THREADS) void k_reduce(const Args A)
         sS[tt][tc] = S;
         __syncthreads();
         if (tt == WT - 1) {
-            vec<VEC> Pe, Se;
+            dvec<VEC> Pe, Se;
             lds_exclusive<G>(sP, sS, tt, tc, Pe, Se);
             // tile total = (earlier threads) (+) (own rows); chunk total = (earlier tiles) (+) (tile total)
-            const vec<VEC> St = vfma<VEC>(P, Se, S), Pt = Pe * P;
-            Sc = vfma<VEC>(Pt, Sc, St);
+            const dvec<VEC> St = dfma<VEC>(P, Se, widen<VEC>(S)), Pt = Pe * P;
+            Sc = dfma<VEC>(Pt, Sc, St);
             Pc *= Pt;
         }
     }
     if (tt == WT - 1 && col_ok) {
-        st<VEC>(A.aggP + k * A.C + col, Pc);
-        st<VEC>(A.aggS + k * A.C + col, Sc);
+        std_<VEC>(A.aggP + k * A.C + col, Pc);
+        std_<VEC>(A.aggS + k * A.C + col, Sc);
     }
 }
 
@@ -266,17 +309,17 @@ template <class G, bool BWD>
 __global__ __launch_bounds__(G::THREADS) void k_fixup(const Args A)
 {
     constexpr int VEC = G::VEC, R = G::R, WC = G::WC, WT = G::WT, ROWS = G::ROWS;
-    __shared__ vec<VEC> sP[WT][WC];
+    __shared__ dvec<VEC> sP[WT][WC];
     __shared__ vec<VEC> sS[WT][WC];
-    __shared__ vec<VEC> sTot[2][WC];
+    __shared__ dvec<VEC> sTot[2][WC];
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
     const int g = (int)(blockIdx.x % (unsigned)A.G);
     const int64_t k = blockIdx.x / (unsigned)A.G;
     const int64_t col = ((int64_t)g * WC + tc) * VEC;
     const bool col_ok = col < A.C;
 
-    vec<VEC> cc = splat<VEC>(0.0f);  // state entering the current tile
-    if (col_ok) cc = ld<VEC>(A.carry + k * A.C + col);
+    dvec<VEC> cc = dsplat<VEC>(0.0);  // state entering the current tile
+    if (col_ok) cc = ldd<VEC>(A.carry + k * A.C + col);
 
     for (int m = 0; m < A.M; ++m) {
         const int64_t tu0 = (k * A.M + m) * ROWS;
@@ -284,7 +327,8 @@ __global__ __launch_bounds__(G::THREADS) void k_fixup(const Args A)
         const bool interior = tile_interior<G, BWD>(A, tu0, g);
         const int64_t u0 = tu0 + (int64_t)tt * R;
         Rows<G> r;
-        vec<VEC> hp[BWD ? R : 1], P, S;
+        vec<VEC> hp[BWD ? R : 1], S;
+        dvec<VEC> P;
         const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
         tile_load<G, BWD>(A, ad, u0, col_ok, interior, r);
         if constexpr (BWD) {
@@ -294,16 +338,16 @@ __global__ __launch_bounds__(G::THREADS) void k_fixup(const Args A)
         sP[tt][tc] = P;
         sS[tt][tc] = S;
         __syncthreads();
-        vec<VEC> Pe, Se;
+        dvec<VEC> Pe, Se;
         lds_exclusive<G>(sP, sS, tt, tc, Pe, Se);
         if (tt == WT - 1) {
             sTot[0][tc] = Pe * P;
-            sTot[1][tc] = vfma<VEC>(P, Se, S);
+            sTot[1][tc] = dfma<VEC>(P, Se, widen<VEC>(S));
         }
-        rescan<G>(r, vfma<VEC>(Pe, cc, Se));
+        rescan<G>(r, narrow<VEC>(dfma<VEC>(Pe, cc, Se)));
         tile_store<G, BWD>(A, ad, u0, col, col_ok, interior, r, hp);
         __syncthreads();
-        cc = vfma<VEC>(sTot[0][tc], cc, sTot[1][tc]);
+        cc = dfma<VEC>(sTot[0][tc], cc, sTot[1][tc]);
     }
 }
 
@@ -316,15 +360,16 @@ __global__ __launch_bounds__(G::THREADS) void k_fixup(const Args A)
 //      k-1-w*WT-tt for its own columns) composing summaries until it meets a published inclusive
 //      state, which gives its carry-in,
 //   3. publishes its own inclusive state, re-runs the recurrence over its registers and stores.
-// A published word carries the fp32 payload and the call's epoch in one 64-bit relaxed agent-scope
+// A published word carries 32 payload bits and the call's epoch in one 64-bit relaxed agent-scope
 // atomic, so the flag can never be seen without its value and no fence or workspace clear is needed
-// between calls; the flag is never a data value.
+// between calls; the flag is never a data value.  Per tile and column there are four words: the two
+// halves of the fp64 product P, the fp32 sum S, and (later) the fp32 inclusive state.
 // ---------------------------------------------------------------------------------------------
 enum { ST_AGG = 1, ST_INCL = 2 };
 
-__device__ __forceinline__ unsigned long long lb_pack(float v, uint32_t epoch)
+__device__ __forceinline__ unsigned long long lb_pack(uint32_t bits, uint32_t epoch)
 {
-    return ((unsigned long long)epoch << 32) | (unsigned long long)__float_as_uint(v);
+    return ((unsigned long long)epoch << 32) | (unsigned long long)bits;
 }
 __device__ __forceinline__ void lb_store(unsigned long long *p, unsigned long long w)
 {
@@ -339,11 +384,11 @@ template <class G, bool BWD, bool HP_LATE>
 __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
 {
     constexpr int VEC = G::VEC, R = G::R, WC = G::WC, WT = G::WT, ROWS = G::ROWS;
-    __shared__ vec<VEC> sP[WT][WC];
+    __shared__ dvec<VEC> sP[WT][WC];
     __shared__ vec<VEC> sS[WT][WC];
     __shared__ int sSt[WT][WC];
-    __shared__ vec<VEC> sTot[2][WC];
-    __shared__ vec<VEC> sCarry[WC];
+    __shared__ dvec<VEC> sTot[2][WC];
+    __shared__ dvec<VEC> sCarry[WC];
     __shared__ uint32_t sTicket;
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
     // the host keeps K*G below 2^31, so a call's tickets fit 32 bits
@@ -361,7 +406,8 @@ __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
     const uint32_t epoch = A.epoch;
 
     Rows<G> r;
-    vec<VEC> hp[BWD ? R : 1], P, S;
+    vec<VEC> hp[BWD ? R : 1], S;
+    dvec<VEC> P;
     const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
     tile_load<G, BWD>(A, ad, u0, col_ok, interior, r);
     if constexpr (BWD && !HP_LATE) {
@@ -371,19 +417,24 @@ __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
     sP[tt][tc] = P;
     sS[tt][tc] = S;
     __syncthreads();
-    vec<VEC> Pe, Se;
+    dvec<VEC> Pe, Se;
     lds_exclusive<G>(sP, sS, tt, tc, Pe, Se);
     const bool publish = (k + 1 < A.K) && col_ok;
     if (tt == WT - 1) {
-        const vec<VEC> Pt = Pe * P, St = vfma<VEC>(P, Se, S);
+        const dvec<VEC> Pt = Pe * P;
+        // the published S is fp32; keep the same rounded value locally so that every tile composes
+        // exactly what its successors read
+        const vec<VEC> St = narrow<VEC>(dfma<VEC>(P, Se, widen<VEC>(S)));
         sTot[0][tc] = Pt;
-        sTot[1][tc] = St;
+        sTot[1][tc] = widen<VEC>(St);
         if (publish) {
-            unsigned long long *w = A.lbAgg + ((k * A.C + col) << 1);
+            unsigned long long *w = A.lbAgg + (k * A.C + col) * 3;
 #pragma unroll
             for (int v = 0; v < VEC; ++v) {
-                lb_store(w + 2 * v, lb_pack(Pt[v], epoch));
-                lb_store(w + 2 * v + 1, lb_pack(St[v], epoch));
+                const unsigned long long pb = (unsigned long long)__double_as_longlong(Pt[v]);
+                lb_store(w + 3 * v, lb_pack((uint32_t)pb, epoch));
+                lb_store(w + 3 * v + 1, lb_pack((uint32_t)(pb >> 32), epoch));
+                lb_store(w + 3 * v + 2, lb_pack(__float_as_uint(St[v]), epoch));
             }
         }
     }
@@ -391,18 +442,19 @@ __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
 
     // ---- look-back --------------------------------------------------------------------------
     // (Pr, Sr): composition of the predecessors visited so far, nearest first (tt == 0 threads only)
-    vec<VEC> Pr = splat<VEC>(1.0f), Sr = splat<VEC>(0.0f);
+    dvec<VEC> Pr = dsplat<VEC>(1.0), Sr = dsplat<VEC>(0.0);
     bool done = false;
     for (int64_t base = k - 1;; base -= WT) {
         const int64_t pred = base - tt;
         int status = ST_INCL;
-        vec<VEC> vP = splat<VEC>(0.0f), vS = splat<VEC>(0.0f);
+        dvec<VEC> vP = dsplat<VEC>(0.0);
+        vec<VEC> vS = splat<VEC>(0.0f);
         if (pred < 0 || !col_ok) {
             // before the first tile: the initial state (h0 forward, zero backward)
             if (!BWD && pred == -1 && col_ok && A.h0) vS = ld<VEC>(A.h0 + col);
         } else {
             const unsigned long long *wi = A.lbIncl + (pred * A.C + col);
-            const unsigned long long *wa = A.lbAgg + ((pred * A.C + col) << 1);
+            const unsigned long long *wa = A.lbAgg + (pred * A.C + col) * 3;
             uint32_t spins = 0;
             for (;;) {
                 bool ok = true;
@@ -416,9 +468,11 @@ __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
                 ok = true;
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
-                    const unsigned long long wp = lb_load(wa + 2 * v), ws = lb_load(wa + 2 * v + 1);
-                    ok = ok && ((uint32_t)(wp >> 32) == epoch) && ((uint32_t)(ws >> 32) == epoch);
-                    vP[v] = __uint_as_float((uint32_t)wp);
+                    const unsigned long long wl = lb_load(wa + 3 * v), wh = lb_load(wa + 3 * v + 1),
+                                             ws = lb_load(wa + 3 * v + 2);
+                    ok = ok && ((uint32_t)(wl >> 32) == epoch) && ((uint32_t)(wh >> 32) == epoch) &&
+                         ((uint32_t)(ws >> 32) == epoch);
+                    vP[v] = __longlong_as_double((long long)((wh << 32) | (wl & 0xffffffffull)));
                     vS[v] = __uint_as_float((uint32_t)ws);
                 }
                 if (ok) { status = ST_AGG; break; }
@@ -436,14 +490,15 @@ __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
         sSt[tt][tc] = status;
         __syncthreads();
         if (tt == 0 && !done) {
-            vec<VEC> carry = splat<VEC>(0.0f);
+            dvec<VEC> carry = dsplat<VEC>(0.0);
 #pragma unroll
             for (int j = 0; j < WT; ++j) {
                 const int stj = sSt[j][tc];
-                const vec<VEC> p = sP[j][tc], s = sS[j][tc];
+                const dvec<VEC> p = sP[j][tc];
+                const dvec<VEC> s = widen<VEC>(sS[j][tc]);
                 if (!done) {
                     // (p, s) is earlier in time than everything in (Pr, Sr): it goes on the left
-                    const vec<VEC> t = vfma<VEC>(Pr, s, Sr);
+                    const dvec<VEC> t = dfma<VEC>(Pr, s, Sr);
                     if (stj == ST_INCL) { carry = t; done = true; }
                     else { Sr = t; Pr = p * Pr; }
                 }
@@ -451,9 +506,10 @@ __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
             if (done) {
                 sCarry[tc] = carry;
                 if (publish) {
-                    const vec<VEC> incl = vfma<VEC>(sTot[0][tc], carry, sTot[1][tc]);
+                    const vec<VEC> incl = narrow<VEC>(dfma<VEC>(sTot[0][tc], carry, sTot[1][tc]));
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v) lb_store(A.lbIncl + (k * A.C + col + v), lb_pack(incl[v], epoch));
+                    for (int v = 0; v < VEC; ++v)
+                        lb_store(A.lbIncl + (k * A.C + col + v), lb_pack(__float_as_uint(incl[v]), epoch));
                 }
             }
         }
@@ -461,7 +517,7 @@ __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
     }
 
     // ---- rescan from the carry and store -------------------------------------------------------
-    rescan<G>(r, vfma<VEC>(Pe, sCarry[tc], Se));
+    rescan<G>(r, narrow<VEC>(dfma<VEC>(Pe, sCarry[tc], Se)));
     if constexpr (BWD && HP_LATE) {
         if (A.out1) tile_load_hprev<G>(A, ad, u0, col, col_ok, interior, hp);
     }

@@ -18,11 +18,11 @@ struct Args {
     int64_t K;           // tiles (look-back) or chunks (three-phase) along time
     int32_t G;           // column groups of COLS columns
     int32_t M;           // three-phase: tiles walked per chunk
-    // three-phase workspace, each [K, C] fp32
-    float *aggP, *aggS, *carry;
-    // look-back workspace: 64-bit words {epoch : 32 | fp32 bits : 32}
-    unsigned long long *lbAgg;   // [K, C, 2]  (P, S) of a tile
-    unsigned long long *lbIncl;  // [K, C]     state after the tile's last step
+    // three-phase workspace, each [K, C] fp64
+    double *aggP, *aggS, *carry;
+    // look-back workspace: 64-bit words {epoch : 32 | payload bits : 32}
+    unsigned long long *lbAgg;   // [K, C, 3]  low and high half of the fp64 P, fp32 S of a tile
+    unsigned long long *lbIncl;  // [K, C]     fp32 state after the tile's last step
     unsigned long long *ticket;  // monotonically increasing tile counter
     unsigned long long ticket_base;
     uint32_t epoch;
@@ -61,7 +61,7 @@ const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 // load h after the rescan instead of together with lambda and grad_h.
 hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, const Args &A, hipStream_t s);
 
-hipError_t launch_scan_summaries(const float *aggP, const float *aggS, const float *h0, float *carry, int64_t K,
+hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const float *h0, double *carry, int64_t K,
                                  int64_t C, hipStream_t s);
 hipError_t launch_serial(const Args &A, bool bwd, hipStream_t s);
 hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);

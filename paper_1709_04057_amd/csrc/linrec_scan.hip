@@ -8,26 +8,33 @@
 namespace linrec {
 
 // DPP helpers: a lane takes `src` from another lane of the wavefront, or keeps `old` when the
-// source lane does not exist or the row is masked off.
+// source lane does not exist or the row is masked off.  fp64 values move as two 32-bit halves.
 template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp(float old, float src)
+__device__ __forceinline__ int dpp32(int old, int src)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(old), __float_as_int(src), CTRL, ROW_MASK, 0xF, false));
+    return __builtin_amdgcn_update_dpp(old, src, CTRL, ROW_MASK, 0xF, false);
+}
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp(double old, double src)
+{
+    const int lo = dpp32<CTRL, ROW_MASK>(__double2loint(old), __double2loint(src));
+    const int hi = dpp32<CTRL, ROW_MASK>(__double2hiint(old), __double2hiint(src));
+    return __hiloint2double(hi, lo);
 }
 
-// One Kogge-Stone step of the inclusive scan of affine pairs: (Pe,Se) is the pair of the earlier
+// One Kogge-Stone step of the inclusive scan of affine pairs: (pe, se) is the pair of the earlier
 // lane (identity (1,0) when there is none), combined on the left of the lane's own pair.
 template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ void scan_step(float &P, float &S)
+__device__ __forceinline__ void scan_step(double &P, double &S)
 {
-    const float pe = dpp<CTRL, ROW_MASK>(1.0f, P);
-    const float se = dpp<CTRL, ROW_MASK>(0.0f, S);
-    S = fmaf(P, se, S);
+    const double pe = dpp<CTRL, ROW_MASK>(1.0, P);
+    const double se = dpp<CTRL, ROW_MASK>(0.0, S);
+    S = fma(P, se, S);
     P = pe * P;
 }
 
 // Inclusive scan over the 64 lanes of a wavefront, lane index = time order.
-__device__ __forceinline__ void wave_scan_pairs(float &P, float &S)
+__device__ __forceinline__ void wave_scan_pairs(double &P, double &S)
 {
     scan_step<0x111, 0xF>(P, S);  // row_shr:1
     scan_step<0x112, 0xF>(P, S);  // row_shr:2
@@ -43,27 +50,27 @@ constexpr int SCAN_WAVES = 4;
 // grid = ceil(C / SCAN_COLS).  Blocks of 64 chunks x SCAN_COLS columns are staged through LDS
 // (coalesced along the columns in global memory, transposed so that lanes hold consecutive chunks),
 // scanned with DPP, and the state entering each chunk is written back the same way.  The state is
-// carried across the K/64 blocks in a register per (wavefront, column).
-__global__ __launch_bounds__(SCAN_WAVES * 64) void k_scan_summaries(const float *__restrict__ aggP,
-                                                                    const float *__restrict__ aggS,
+// carried across the K/64 blocks in a register per (wavefront, column).  All in fp64.
+__global__ __launch_bounds__(SCAN_WAVES * 64) void k_scan_summaries(const double *__restrict__ aggP,
+                                                                    const double *__restrict__ aggS,
                                                                     const float *__restrict__ h0,
-                                                                    float *__restrict__ carry, int64_t K, int64_t C)
+                                                                    double *__restrict__ carry, int64_t K, int64_t C)
 {
-    __shared__ float tP[64][SCAN_COLS + 1];
-    __shared__ float tS[64][SCAN_COLS + 1];
+    __shared__ double tP[64][SCAN_COLS + 1];
+    __shared__ double tS[64][SCAN_COLS + 1];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int64_t c0 = (int64_t)blockIdx.x * SCAN_COLS;
     constexpr int PER_WAVE = SCAN_COLS / SCAN_WAVES;
-    float run[PER_WAVE];
+    double run[PER_WAVE];
 #pragma unroll
     for (int i = 0; i < PER_WAVE; ++i) {
         const int64_t c = c0 + wave + SCAN_WAVES * i;
-        run[i] = (h0 && c < C) ? h0[c] : 0.0f;
+        run[i] = (h0 && c < C) ? (double)h0[c] : 0.0;
     }
     for (int64_t k0 = 0; k0 < K; k0 += 64) {
         for (int idx = tid; idx < 64 * SCAN_COLS; idx += SCAN_WAVES * 64) {
             const int kk = idx / SCAN_COLS, cc = idx % SCAN_COLS;
-            float p = 1.0f, s = 0.0f;
+            double p = 1.0, s = 0.0;
             if (k0 + kk < K && c0 + cc < C) {
                 p = aggP[(k0 + kk) * C + c0 + cc];
                 s = aggS[(k0 + kk) * C + c0 + cc];
@@ -75,11 +82,12 @@ __global__ __launch_bounds__(SCAN_WAVES * 64) void k_scan_summaries(const float 
 #pragma unroll
         for (int i = 0; i < PER_WAVE; ++i) {
             const int cc = wave + SCAN_WAVES * i;
-            float P = tP[lane][cc], S = tS[lane][cc];
+            double P = tP[lane][cc], S = tS[lane][cc];
             wave_scan_pairs(P, S);
-            const float state = fmaf(P, run[i], S);              // state after chunk k0 + lane
+            const double state = fma(P, run[i], S);              // state after chunk k0 + lane
             tS[lane][cc] = dpp<0x138, 0xF>(run[i], state);       // wave_shr:1 -> state entering the chunk
-            run[i] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(state), 63));
+            run[i] = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(state), 63),
+                                      __builtin_amdgcn_readlane(__double2loint(state), 63));
         }
         __syncthreads();
         for (int idx = tid; idx < 64 * SCAN_COLS; idx += SCAN_WAVES * 64) {
@@ -127,7 +135,7 @@ __global__ void k_fill_zero(float *p, int64_t n)
     if (i < n) p[i] = 0.0f;
 }
 
-hipError_t launch_scan_summaries(const float *aggP, const float *aggS, const float *h0, float *carry, int64_t K,
+hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const float *h0, double *carry, int64_t K,
                                  int64_t C, hipStream_t s)
 {
     const unsigned grid = (unsigned)((C + SCAN_COLS - 1) / SCAN_COLS);
