@@ -129,6 +129,19 @@ int linrec_validate_backward(const float *lambda, const float *h, const float *h
                              const float *grad_h, const float *grad_x, const float *grad_lambda,
                              const float *grad_h0, int64_t T, int64_t B, int64_t n);
 
+/*
+ * Measurement aid, not part of the recurrence: a pure streaming kernel built from the same
+ * 16-byte non-temporal loads and stores as the scan kernels.  Reads the n-element device arrays
+ * in0, in1, in2 that are non-NULL and writes those of out0 (= in0*in1+in2, absent inputs taken
+ * as 1, 1, 0) and out1 (= out0 squared) that are non-NULL.  With (in0, NULL, NULL, out0, NULL)
+ * it is a plain copy of 4n bytes in and 4n bytes out, used to calibrate hardware byte
+ * counters; with two inputs and one output it moves the forward pass' 12 bytes per element,
+ * with three inputs and two outputs the backward pass' 20.  n must be a multiple of 4 and all
+ * pointers 16-byte aligned (LINREC_ERR_SHAPE otherwise); at least one output is required.
+ */
+int linrec_stream_probe(const float *in0, const float *in1, const float *in2, float *out0,
+                        float *out1, int64_t n, void *stream);
+
 /* Synchronises `stream` and reports whether any look-back kernel enqueued on it since the
  * last check gave up waiting (LINREC_ERR_DEVICE), LINREC_ERR_HIP if the synchronisation
  * itself failed, else LINREC_OK.  Optional: a healthy run never needs it. */

@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     linrec_release_workspace,
     linrec_set_option,
     linrec_status_string,
+    linrec_stream_probe,
     linrec_tile_info,
     linrec_version,
 )

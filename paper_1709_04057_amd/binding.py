@@ -6,7 +6,7 @@ import os
 import re
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liblinrec.so")
+_LIB_PATH = os.environ.get("LINREC_LIB_PATH", os.path.join(_HERE, "liblinrec.so"))
 _HEADER = os.path.join(os.path.dirname(_HERE), "include", "linrec.h")
 _lib = None
 
@@ -54,6 +54,8 @@ def lib():
         L.linrec_tile_info.restype = ci
         L.linrec_plan.argtypes = [i64, i64, i64, ci, ci, pi, pi]
         L.linrec_plan.restype = ci
+        L.linrec_stream_probe.argtypes = [p, p, p, p, p, i64, p]
+        L.linrec_stream_probe.restype = ci
         L.linrec_check.argtypes = [p]
         L.linrec_check.restype = ci
         L.linrec_release_workspace.argtypes = []
@@ -182,6 +184,12 @@ def linrec_plan(T, B, n, backward=False, vec4=True):
     v, t = ctypes.c_int(), ctypes.c_int()
     _check(lib().linrec_plan(int(T), int(B), int(n), int(bool(backward)), int(bool(vec4)), ctypes.byref(v), ctypes.byref(t)))
     return v.value, t.value
+
+
+def linrec_stream_probe(in0, in1, in2, out0, out1, stream=None) -> None:
+    """Pure streaming kernel over flat float32 CUDA tensors (None = absent); see include/linrec.h."""
+    n = (out0 if out0 is not None else out1).numel()
+    _check(lib().linrec_stream_probe(_ptr(in0), _ptr(in1), _ptr(in2), _ptr(out0), _ptr(out1), n, _stream_ptr(stream)))
 
 
 def linrec_check(stream=None) -> None:

@@ -14,13 +14,13 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "liblinrec.so")
-OBJ_DIR = os.path.join(HERE, "_build")
+LIB = os.environ.get("LINREC_BUILD_OUT", os.path.join(HERE, "liblinrec.so"))
+OBJ_DIR = os.environ.get("LINREC_BUILD_DIR", os.path.join(HERE, "_build"))
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+         "-I" + os.path.join(ROOT, "include"), "-I" + CSRC] + os.environ.get("LINREC_EXTRA_FLAGS", "").split()
 
 
 def tile_ids():

@@ -65,6 +65,7 @@ Options &opts()
 }
 
 char g_hip_error[256] = "";
+unsigned long long *g_trace = nullptr;  // set by linrec_debug_trace (trace builds)
 int hip_fail(hipError_t e, const char *what)
 {
     snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", what, hipGetErrorString(e));
@@ -75,7 +76,7 @@ int hip_fail(hipError_t e, const char *what)
 // One per (device, stream).  The look-back words live in their own allocation that nothing else
 // ever writes, because a stale word is told from a fresh one only by its epoch.
 struct Workspace {
-    // look-back: [ticket u64][err u32][pad to 256 B][lbIncl K*C u64][lbAgg 3*K*C u64]
+    // look-back: [ticket u64][err u32][pad to 256 B][3*K*C u64 words]
     void *lb = nullptr;
     size_t lb_bytes = 0;
     uint32_t epoch = 0;
@@ -206,22 +207,22 @@ int run(Args A, bool bwd, bool vec4, hipStream_t s)
     A.M = 1;
     const size_t kc = (size_t)A.K * (size_t)A.C;
     const size_t old_bytes = ws.lb_bytes;
-    int rc = ensure(&ws.lb, &ws.lb_bytes, kLbHeader + 4 * kc * sizeof(unsigned long long), true, s);
+    int rc = ensure(&ws.lb, &ws.lb_bytes, kLbHeader + 3 * kc * sizeof(unsigned long long), true, s);
     if (rc != LINREC_OK) return rc;
     if (ws.lb_bytes != old_bytes) ws.tickets_issued = 0;  // fresh, zeroed buffer: its counter restarts
-    if (++ws.epoch == 0) {
-        // the 32-bit epoch wrapped: forget every stale word before reusing epoch values
+    if (++ws.epoch >= 0x80000000u) {
+        // the 31-bit epoch wrapped: forget every stale word before reusing epoch values
         if ((e = hipMemsetAsync((char *)ws.lb + kLbHeader, 0, ws.lb_bytes - kLbHeader, s)) != hipSuccess)
             return hip_fail(e, "hipMemsetAsync(workspace)");
         ws.epoch = 1;
     }
     A.ticket = (unsigned long long *)ws.lb;
     A.err = (uint32_t *)((char *)ws.lb + 8);
-    A.lbIncl = (unsigned long long *)((char *)ws.lb + kLbHeader);
-    A.lbAgg = A.lbIncl + kc;
+    A.lbAgg = (unsigned long long *)((char *)ws.lb + kLbHeader);
     A.ticket_base = ws.tickets_issued;
     A.epoch = ws.epoch;
     A.spin_limit = (uint32_t)opts().spin_limit;
+    A.trace = g_trace;
     if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
     ws.tickets_issued += (unsigned long long)(A.K * A.G);
@@ -345,6 +346,24 @@ extern "C" int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int al
     if (tile_id) *tile_id = p.tile;
     return LINREC_OK;
 }
+
+extern "C" int linrec_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
+                                   int64_t n, void *stream)
+{
+    if (n < 0 || (n & 3)) return LINREC_ERR_SHAPE;
+    if (!out0 && !out1) return LINREC_ERR_NULL;
+    const void *ptrs[5] = {in0, in1, in2, out0, out1};
+    for (const void *p : ptrs)
+        if (!aligned16(p)) return LINREC_ERR_SHAPE;
+    if (n == 0) return LINREC_OK;
+    const hipError_t e = launch_stream_probe(in0, in1, in2, out0, out1, n, (hipStream_t)stream);
+    return e == hipSuccess ? LINREC_OK : hip_fail(e, "launch(stream_probe)");
+}
+
+#ifdef LINREC_TRACE
+// Trace builds only: device buffer of 8 u64 per tile that look-back kernels fill with their timeline.
+extern "C" void linrec_debug_trace(unsigned long long *device_buffer) { g_trace = device_buffer; }
+#endif
 
 extern "C" int linrec_check(void *stream)
 {

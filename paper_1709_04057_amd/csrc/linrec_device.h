@@ -27,6 +27,9 @@ template <int VEC_, int R_, int WC_, int WT_>
 struct Geo {
     static constexpr int VEC = VEC_, R = R_, WC = WC_, WT = WT_;
     static constexpr int THREADS = WC * WT, ROWS = WT * R, COLS = WC * VEC;
+    // wavefronts per SIMD the register allocation is held to: the tile data take 2*R*VEC registers
+    // per lane of the 512 a SIMD has, and the waits of the look-back are hidden by other tiles
+    static constexpr int OCC = 1;
 };
 
 // VEC adjacent columns of one row, kept as one SSA value (never addressed through a pointer, so the
@@ -62,15 +65,31 @@ __device__ __forceinline__ dvec<N> dfma(dvec<N> a, dvec<N> b, dvec<N> c)
     return __builtin_elementwise_fma(a, b, c);
 }
 
+// Streaming accesses: every element is touched once, so loads and stores carry the non-temporal
+// hint and do not displace the look-back words from the caches.
+#ifndef LINREC_NT_LOAD
+#define LINREC_NT_LOAD 1
+#endif
+#ifndef LINREC_NT_STORE
+#define LINREC_NT_STORE 1
+#endif
 template <int N>
 __device__ __forceinline__ vec<N> ld(const float *p)
 {
+#if LINREC_NT_LOAD
     return __builtin_nontemporal_load(reinterpret_cast<const vec<N> *>(p));
+#else
+    return *reinterpret_cast<const vec<N> *>(p);
+#endif
 }
 template <int N>
 __device__ __forceinline__ void st(float *p, vec<N> v)
 {
+#if LINREC_NT_STORE
     __builtin_nontemporal_store(v, reinterpret_cast<vec<N> *>(p));
+#else
+    *reinterpret_cast<vec<N> *>(p) = v;
+#endif
 }
 template <int N>
 __device__ __forceinline__ vec<N> vfma(vec<N> a, vec<N> b, vec<N> c)
@@ -84,42 +103,73 @@ __device__ __forceinline__ vec<N> splat(float x)
 }
 
 // ---------------------------------------------------------------------------------------------
-// Tile addressing.  Every access of a tile is written as (workgroup-uniform 64-bit base) +
-// (per-thread unsigned 32-bit byte offset), which maps onto the scalar-base + vector-offset form of
-// the global load/store instructions and keeps the per-row addresses out of the vector registers.
-// The host guarantees (ROWS*C + COLS)*4 < 2^32.
+// Tile addressing.  Every tensor access of a tile goes through a buffer resource whose base is a
+// workgroup-uniform corner of the tile, plus a per-thread 32-bit byte offset (one vector register
+// for the whole tile) plus a per-row scalar byte offset.  No 64-bit address ever lives in a vector
+// register, and rows past the end of the tensor fall outside the resource's range (loads return 0,
+// stores are dropped) on top of the explicit masks below.  The host guarantees
+// (ROWS*C + COLS)*4 < 2^32.
 //
-// Forward: the base is the tile's first row, thread (tt, tc) starts tt*R rows further down.
-// Backward: logical step u is row t = T-1-u, so rows go DOWN with u; the base is the tile's lowest
-// row t_low = T - tu0 - ROWS (negative for the last, partial tile: such rows are masked and never
-// dereferenced) and thread (tt, tc) starts (WT-1-tt)*R rows above it.
+// Forward: the corner is the tile's first row; thread (tt, tc) starts tt*R rows further down.
+// Backward: logical step u is row t = T-1-u, so rows go DOWN with u; the corner is the tile's lowest
+// row t_low = T - tu0 - ROWS (negative for the last, partial tile: those rows are masked and never
+// touched) and thread (tt, tc) starts (WT-1-tt)*R rows above it.
 // ---------------------------------------------------------------------------------------------
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kBufNT = 2;  // cache-policy bit "nt": streaming data, touched once
+
+template <int N>
+__device__ __forceinline__ vec<N> buf_ld(rsrc_t rs, uint32_t voff, uint32_t soff)
+{
+    if constexpr (N == 4) {
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
+        return __builtin_bit_cast(vec<4>, v);
+    } else {
+        static_assert(N == 1, "one or four columns per thread");
+        const unsigned int v = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
+        return vec<1>(__uint_as_float(v));
+    }
+}
+template <int N>
+__device__ __forceinline__ void buf_st(rsrc_t rs, uint32_t voff, uint32_t soff, vec<N> v)
+{
+    if constexpr (N == 4) {
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[0]), rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
+    }
+}
+
 template <class G, bool BWD>
 struct TileAddr {
     int64_t base;   // element index of the tile's reference corner (uniform)
-    uint32_t toff;  // this thread's byte offset from it
-    int64_t C;
-    __device__ __forceinline__ TileAddr(const Args &A, int64_t tu0, int g, int tt, int tc) : C(A.C)
+    int64_t total;  // T*C
+    uint32_t toff;  // this thread's byte offset from the corner
+    uint32_t rowb;  // bytes per row
+    __device__ __forceinline__ TileAddr(const Args &A, int64_t tu0, int g, int tt, int tc)
+        : total(A.T * A.C), rowb((uint32_t)A.C * 4u)
     {
         if constexpr (!BWD) {
             base = tu0 * A.C + (int64_t)g * G::COLS;
-            toff = ((uint32_t)(tt * G::R) * (uint32_t)A.C + (uint32_t)(tc * G::VEC)) * 4u;
+            toff = (uint32_t)(tt * G::R) * rowb + (uint32_t)(tc * G::VEC) * 4u;
         } else {
             base = (A.T - tu0 - G::ROWS) * A.C + (int64_t)g * G::COLS;
-            toff = ((uint32_t)((G::WT - 1 - tt) * G::R) * (uint32_t)A.C + (uint32_t)(tc * G::VEC)) * 4u;
+            toff = (uint32_t)((G::WT - 1 - tt) * G::R) * rowb + (uint32_t)(tc * G::VEC) * 4u;
         }
     }
-    // address of the thread's row j of tensor p, shifted by `shift` rows (+1: lambda one row ahead,
-    // -1: h one row behind; backward only)
-    __device__ __forceinline__ const float *at(const float *p, int j, int shift = 0) const
+    // Resource for tensor p seen `shift` rows away from the tile (+1: lambda one row ahead, -1: h one
+    // row behind; backward only).  Its range ends where the tensor ends.
+    __device__ __forceinline__ rsrc_t rsrc(const float *p, int shift = 0) const
     {
-        const float *row = BWD ? p + (base + (int64_t)(G::R - 1 - j + shift) * C) : p + (base + (int64_t)(j + shift) * C);
-        return reinterpret_cast<const float *>(reinterpret_cast<const char *>(row) + (size_t)toff);
+        const int64_t first = base + (int64_t)shift * (int64_t)(rowb / 4u);
+        int64_t bytes = (total - first) * 4;
+        if (first < 0 || bytes > 0xffffffffll) bytes = 0xffffffffll;
+        if (bytes < 0) bytes = 0;
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p + first), 0, (int)(uint32_t)bytes, 0x00020000);
     }
-    __device__ __forceinline__ float *at(float *p, int j) const
-    {
-        return const_cast<float *>(at(static_cast<const float *>(p), j, 0));
-    }
+    // scalar byte offset of the thread's row j (rows go up with j forward, down backward)
+    __device__ __forceinline__ uint32_t soff(int j) const { return (uint32_t)(BWD ? G::R - 1 - j : j) * rowb; }
 };
 
 // The thread's R rows of the two scan operands.
@@ -136,17 +186,18 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
                                           bool interior, Rows<G> &r)
 {
     constexpr int R = G::R, VEC = G::VEC;
+    const rsrc_t ra = ad.rsrc(A.a, BWD ? +1 : 0), rb = ad.rsrc(A.b);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const int64_t u = u0 + j;
         vec<VEC> va = splat<VEC>(1.0f), vb = splat<VEC>(0.0f);
         if (interior || (col_ok && u < A.T)) {
-            vb = ld<VEC>(ad.at(A.b, j));
+            vb = buf_ld<VEC>(rb, ad.toff, ad.soff(j));
             if constexpr (!BWD) {
-                va = ld<VEC>(ad.at(A.a, j));
+                va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
             } else {
                 va = splat<VEC>(0.0f);  // the last row has no successor
-                if (interior || u > 0) va = ld<VEC>(ad.at(A.a, j, +1));
+                if (interior || u > 0) va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
             }
         }
         r.a[j] = va;
@@ -160,11 +211,12 @@ __device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G,
                                                 bool col_ok, bool interior, vec<G::VEC> (&hp)[G::R])
 {
     constexpr int R = G::R, VEC = G::VEC;
+    const rsrc_t rh = ad.rsrc(A.hprev, -1);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const int64_t u = u0 + j;
         vec<VEC> v = splat<VEC>(0.0f);
-        if (interior || (col_ok && u < A.T - 1)) v = ld<VEC>(ad.at(A.hprev, j, -1));
+        if (interior || (col_ok && u < A.T - 1)) v = buf_ld<VEC>(rh, ad.toff, ad.soff(j));
         else if (col_ok && u == A.T - 1 && A.h0) v = ld<VEC>(A.h0 + col);
         hp[j] = v;
     }
@@ -203,15 +255,16 @@ __device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD>
                                            bool col_ok, bool interior, const Rows<G> &r, const vec<G::VEC> *hp)
 {
     constexpr int R = G::R, VEC = G::VEC;
+    const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(BWD ? A.out1 : A.out0);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         const int64_t u = u0 + j;
         if (interior || (col_ok && u < A.T)) {
             if constexpr (!BWD) {
-                st<VEC>(ad.at(A.out0, j), r.b[j]);
+                buf_st<VEC>(r0, ad.toff, ad.soff(j), r.b[j]);
             } else {
-                if (A.out0) st<VEC>(ad.at(A.out0, j), r.b[j]);
-                if (A.out1) st<VEC>(ad.at(A.out1, j), r.b[j] * hp[j]);
+                if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), r.b[j]);
+                if (A.out1) buf_st<VEC>(r1, ad.toff, ad.soff(j), r.b[j] * hp[j]);
                 if (!interior && u == A.T - 1 && A.gh0)  // row 0: grad_h0 = lambda[0] * g_0
                     st<VEC>(A.gh0 + col, ld<VEC>(A.a + col) * r.b[j]);
             }
@@ -228,23 +281,6 @@ __device__ __forceinline__ bool tile_interior(const Args &A, int64_t tu0, int g)
     else return cols_full && tu0 > 0 && (tu0 + G::ROWS < A.T);
 }
 
-// Phase 2 inside a tile: thread (tt, tc) gets the composition of the summaries of the threads with
-// smaller tt in its columns (identity for tt == 0).  sP/sS must have been filled and a barrier passed.
-template <class G>
-__device__ __forceinline__ void lds_exclusive(const dvec<G::VEC> (*sP)[G::WC], const vec<G::VEC> (*sS)[G::WC], int tt,
-                                              int tc, dvec<G::VEC> &Pe, dvec<G::VEC> &Se)
-{
-    dvec<G::VEC> pe = dsplat<G::VEC>(1.0), se = dsplat<G::VEC>(0.0);
-    for (int i = 0; i < tt; ++i) {
-        const dvec<G::VEC> p = sP[i][tc];
-        const dvec<G::VEC> s = widen<G::VEC>(sS[i][tc]);
-        se = dfma<G::VEC>(p, se, s);
-        pe *= p;
-    }
-    Pe = pe;
-    Se = se;
-}
-
 template <int N>
 __device__ __forceinline__ dvec<N> ldd(const double *p)
 {
@@ -257,46 +293,135 @@ __device__ __forceinline__ void std_(double *p, dvec<N> v)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Phase 2 inside a tile, in two levels.
+//   1. The TPW = 64/WC time-threads that share a wavefront (lanes tc + WC*ttl) run a Kogge-Stone
+//      scan over ttl with cross-lane moves (log2(TPW) steps, no LDS storage, no barrier).
+//   2. The NW wavefront totals go through LDS; every thread composes the totals of the wavefronts
+//      before its own (at most NW-1 of them) with its in-wavefront prefix.
+// Every thread returns its exclusive prefix (Pe, Se) -- the composition of all threads with smaller
+// tt in its columns -- and the tile total (Pt, St).  P travels in fp64; S is stored in fp32 between
+// steps but every combination is evaluated in fp64.  One __syncthreads inside.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float lane_move(float v, int src_lane)
+{
+    return __int_as_float(__builtin_amdgcn_ds_bpermute(src_lane << 2, __float_as_int(v)));
+}
+__device__ __forceinline__ double lane_move(double v, int src_lane)
+{
+    const int lo = __builtin_amdgcn_ds_bpermute(src_lane << 2, __double2loint(v));
+    const int hi = __builtin_amdgcn_ds_bpermute(src_lane << 2, __double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+template <int N>
+__device__ __forceinline__ vec<N> lane_move(vec<N> v, int src_lane)
+{
+    vec<N> r;
+#pragma unroll
+    for (int i = 0; i < N; ++i) r[i] = lane_move((float)v[i], src_lane);
+    return r;
+}
+template <int N>
+__device__ __forceinline__ dvec<N> lane_move(dvec<N> v, int src_lane)
+{
+    dvec<N> r;
+#pragma unroll
+    for (int i = 0; i < N; ++i) r[i] = lane_move((double)v[i], src_lane);
+    return r;
+}
+
+template <class G>
+struct ScanLds {
+    static constexpr int NW = G::THREADS / 64;
+    dvec<G::VEC> wP[NW][G::WC];
+    vec<G::VEC> wS[NW][G::WC];
+};
+
+template <class G>
+__device__ __forceinline__ void tile_scan(ScanLds<G> &lds, int tid, dvec<G::VEC> P, vec<G::VEC> S, dvec<G::VEC> &Pe,
+                                          vec<G::VEC> &Se, dvec<G::VEC> &Pt, vec<G::VEC> &St)
+{
+    constexpr int VEC = G::VEC, WC = G::WC;
+    constexpr int TPW = (64 / WC) < G::WT ? (64 / WC) : G::WT;  // time-threads per wavefront
+    constexpr int NW = ScanLds<G>::NW;
+    const int lane = tid & 63, wave = tid >> 6, tc = tid % WC, ttl = lane / WC;
+
+    // level 1: inclusive scan over ttl inside the wavefront
+#pragma unroll
+    for (int d = 1; d < TPW; d <<= 1) {
+        const int src = lane - d * WC;
+        const dvec<VEC> ps = lane_move<VEC>(P, src < 0 ? lane : src);
+        const vec<VEC> ss = lane_move<VEC>(S, src < 0 ? lane : src);
+        if (ttl >= d) {  // (ps, ss) is earlier in time: it goes on the left
+            S = narrow<VEC>(dfma<VEC>(P, widen<VEC>(ss), widen<VEC>(S)));
+            P = ps * P;
+        }
+    }
+    if (ttl == TPW - 1) {
+        lds.wP[wave][tc] = P;
+        lds.wS[wave][tc] = S;
+    }
+    // exclusive prefix inside the wavefront = inclusive value of the previous time-thread
+    dvec<VEC> Px = dsplat<VEC>(1.0);
+    vec<VEC> Sx = splat<VEC>(0.0f);
+    if constexpr (TPW > 1) {
+        const int src = lane - WC;
+        const dvec<VEC> ps = lane_move<VEC>(P, src < 0 ? lane : src);
+        const vec<VEC> ss = lane_move<VEC>(S, src < 0 ? lane : src);
+        if (ttl >= 1) { Px = ps; Sx = ss; }
+    }
+    __syncthreads();
+    // level 2: compose the wavefront totals; the running value when w reaches this thread's
+    // wavefront is what came before it
+    dvec<VEC> pt = dsplat<VEC>(1.0);
+    vec<VEC> st_ = splat<VEC>(0.0f);
+    Pe = Px;
+    Se = Sx;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        if (w == wave) {  // (waves before) (+) (in-wave prefix)
+            Se = narrow<VEC>(dfma<VEC>(Px, widen<VEC>(st_), widen<VEC>(Sx)));
+            Pe = pt * Px;
+        }
+        const dvec<VEC> p = lds.wP[w][tc];
+        st_ = narrow<VEC>(dfma<VEC>(p, widen<VEC>(st_), widen<VEC>(lds.wS[w][tc])));
+        pt *= p;
+    }
+    Pt = pt;
+    St = st_;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Three-phase variant, kernel 1: per-chunk reduce (Algorithm 1, first parallel-for).
 // grid = K*G workgroups, workgroup (k, g) walks the M tiles of chunk k in column group g.
 // ---------------------------------------------------------------------------------------------
 template <class G, bool BWD>
-__global__ __launch_bounds__(G::THREADS) void k_reduce(const Args A)
+__global__ __launch_bounds__(G::THREADS, G::OCC) void k_reduce(const Args A)
 {
-    constexpr int VEC = G::VEC, R = G::R, WC = G::WC, WT = G::WT, ROWS = G::ROWS;
-    __shared__ dvec<VEC> sP[WT][WC];
-    __shared__ vec<VEC> sS[WT][WC];
+    constexpr int VEC = G::VEC, R = G::R, WC = G::WC, ROWS = G::ROWS;
+    __shared__ ScanLds<G> lds;
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
     const int g = (int)(blockIdx.x % (unsigned)A.G);
     const int64_t k = blockIdx.x / (unsigned)A.G;
     const int64_t col = ((int64_t)g * WC + tc) * VEC;
     const bool col_ok = col < A.C;
 
-    dvec<VEC> Pc = dsplat<VEC>(1.0), Sc = dsplat<VEC>(0.0);  // chunk total so far (tt == WT-1 only)
+    dvec<VEC> Pc = dsplat<VEC>(1.0), Sc = dsplat<VEC>(0.0);  // chunk total so far
     for (int m = 0; m < A.M; ++m) {
         const int64_t tu0 = (k * A.M + m) * ROWS;
         if (tu0 >= A.T) break;
         const bool interior = tile_interior<G, BWD>(A, tu0, g);
         Rows<G> r;
-        dvec<VEC> P;
-        vec<VEC> S;
+        dvec<VEC> P, Pe, Pt;
+        vec<VEC> S, Se, St;
         const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
         tile_load<G, BWD>(A, ad, tu0 + (int64_t)tt * R, col_ok, interior, r);
         local_reduce<G>(r, P, S);
-        if (m > 0) __syncthreads();  // the previous tile's summaries have been consumed
-        sP[tt][tc] = P;
-        sS[tt][tc] = S;
-        __syncthreads();
-        if (tt == WT - 1) {
-            dvec<VEC> Pe, Se;
-            lds_exclusive<G>(sP, sS, tt, tc, Pe, Se);
-            // tile total = (earlier threads) (+) (own rows); chunk total = (earlier tiles) (+) (tile total)
-            const dvec<VEC> St = dfma<VEC>(P, Se, widen<VEC>(S)), Pt = Pe * P;
-            Sc = dfma<VEC>(Pt, Sc, St);
-            Pc *= Pt;
-        }
+        if (m > 0) __syncthreads();  // the previous tile's wavefront totals have been consumed
+        tile_scan<G>(lds, tid, P, S, Pe, Se, Pt, St);
+        Sc = dfma<VEC>(Pt, Sc, widen<VEC>(St));  // (earlier tiles) (+) (this tile)
+        Pc *= Pt;
     }
-    if (tt == WT - 1 && col_ok) {
+    if (tt == 0 && col_ok) {
         std_<VEC>(A.aggP + k * A.C + col, Pc);
         std_<VEC>(A.aggS + k * A.C + col, Sc);
     }
@@ -306,12 +431,10 @@ __global__ __launch_bounds__(G::THREADS) void k_reduce(const Args A)
 // Three-phase variant, kernel 3: per-chunk rescan from the carry (Algorithm 1, second parallel-for).
 // ---------------------------------------------------------------------------------------------
 template <class G, bool BWD>
-__global__ __launch_bounds__(G::THREADS) void k_fixup(const Args A)
+__global__ __launch_bounds__(G::THREADS, G::OCC) void k_fixup(const Args A)
 {
-    constexpr int VEC = G::VEC, R = G::R, WC = G::WC, WT = G::WT, ROWS = G::ROWS;
-    __shared__ dvec<VEC> sP[WT][WC];
-    __shared__ vec<VEC> sS[WT][WC];
-    __shared__ dvec<VEC> sTot[2][WC];
+    constexpr int VEC = G::VEC, R = G::R, WC = G::WC, ROWS = G::ROWS;
+    __shared__ ScanLds<G> lds;
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
     const int g = (int)(blockIdx.x % (unsigned)A.G);
     const int64_t k = blockIdx.x / (unsigned)A.G;
@@ -327,27 +450,19 @@ __global__ __launch_bounds__(G::THREADS) void k_fixup(const Args A)
         const bool interior = tile_interior<G, BWD>(A, tu0, g);
         const int64_t u0 = tu0 + (int64_t)tt * R;
         Rows<G> r;
-        vec<VEC> hp[BWD ? R : 1], S;
-        dvec<VEC> P;
+        vec<VEC> hp[BWD ? R : 1], S, Se, St;
+        dvec<VEC> P, Pe, Pt;
         const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
         tile_load<G, BWD>(A, ad, u0, col_ok, interior, r);
         if constexpr (BWD) {
             if (A.out1) tile_load_hprev<G>(A, ad, u0, col, col_ok, interior, hp);
         }
         local_reduce<G>(r, P, S);
-        sP[tt][tc] = P;
-        sS[tt][tc] = S;
-        __syncthreads();
-        dvec<VEC> Pe, Se;
-        lds_exclusive<G>(sP, sS, tt, tc, Pe, Se);
-        if (tt == WT - 1) {
-            sTot[0][tc] = Pe * P;
-            sTot[1][tc] = dfma<VEC>(P, Se, widen<VEC>(S));
-        }
-        rescan<G>(r, narrow<VEC>(dfma<VEC>(Pe, cc, Se)));
+        if (m > 0) __syncthreads();
+        tile_scan<G>(lds, tid, P, S, Pe, Se, Pt, St);
+        rescan<G>(r, narrow<VEC>(dfma<VEC>(Pe, cc, widen<VEC>(Se))));
         tile_store<G, BWD>(A, ad, u0, col, col_ok, interior, r, hp);
-        __syncthreads();
-        cc = dfma<VEC>(sTot[0][tc], cc, sTot[1][tc]);
+        cc = dfma<VEC>(Pt, cc, widen<VEC>(St));
     }
 }
 
@@ -360,16 +475,32 @@ __global__ __launch_bounds__(G::THREADS) void k_fixup(const Args A)
 //      k-1-w*WT-tt for its own columns) composing summaries until it meets a published inclusive
 //      state, which gives its carry-in,
 //   3. publishes its own inclusive state, re-runs the recurrence over its registers and stores.
-// A published word carries 32 payload bits and the call's epoch in one 64-bit relaxed agent-scope
-// atomic, so the flag can never be seen without its value and no fence or workspace clear is needed
-// between calls; the flag is never a data value.  Per tile and column there are four words: the two
-// halves of the fp64 product P, the fp32 sum S, and (later) the fp32 inclusive state.
+// Per tile and column there are three 64-bit words, each {tag : 32 | payload : 32}, written and read
+// with single relaxed agent-scope atomics, so a tag can never be seen without its payload and no
+// fence or workspace clear is needed between calls; the tag is never a data value:
+//   word 0, 1   low / high half of the fp64 product P            tag = epoch << 1
+//   word 2      fp32 S, tag = epoch << 1;  later overwritten by the fp32 inclusive state with
+//               tag = epoch << 1 | 1 (P is then irrelevant: the look-back ends at this tile)
 // ---------------------------------------------------------------------------------------------
-enum { ST_AGG = 1, ST_INCL = 2 };
+// Optional per-tile timeline (builds with -DLINREC_TRACE only): thread 0 of a tile stores the
+// constant-rate wall clock at the phase boundaries into Args::trace[ticket*8 + slot].
+#ifdef LINREC_TRACE
+#define LINREC_TRACE_MARK(slot)                                                         \
+    do {                                                                                \
+        if (A.trace && threadIdx.x == 0) A.trace[(size_t)ticket * 8 + (slot)] = wall_clock64(); \
+    } while (0)
+#define LINREC_TRACE_VAL(slot, val)                                                     \
+    do {                                                                                \
+        if (A.trace && threadIdx.x == 0) A.trace[(size_t)ticket * 8 + (slot)] = (unsigned long long)(val); \
+    } while (0)
+#else
+#define LINREC_TRACE_MARK(slot) do { } while (0)
+#define LINREC_TRACE_VAL(slot, val) do { } while (0)
+#endif
 
-__device__ __forceinline__ unsigned long long lb_pack(uint32_t bits, uint32_t epoch)
+__device__ __forceinline__ unsigned long long lb_pack(uint32_t bits, uint32_t tag)
 {
-    return ((unsigned long long)epoch << 32) | (unsigned long long)bits;
+    return ((unsigned long long)tag << 32) | (unsigned long long)bits;
 }
 __device__ __forceinline__ void lb_store(unsigned long long *p, unsigned long long w)
 {
@@ -381,14 +512,12 @@ __device__ __forceinline__ unsigned long long lb_load(const unsigned long long *
 }
 
 template <class G, bool BWD, bool HP_LATE>
-__global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
+__global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
 {
     constexpr int VEC = G::VEC, R = G::R, WC = G::WC, WT = G::WT, ROWS = G::ROWS;
-    __shared__ dvec<VEC> sP[WT][WC];
-    __shared__ vec<VEC> sS[WT][WC];
-    __shared__ int sSt[WT][WC];
-    __shared__ dvec<VEC> sTot[2][WC];
-    __shared__ dvec<VEC> sCarry[WC];
+    __shared__ ScanLds<G> lds;
+    __shared__ dvec<VEC> sPt[WC];   // tile total, kept for the inclusive-state publication
+    __shared__ vec<VEC> sSt[WC];
     __shared__ uint32_t sTicket;
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
     // the host keeps K*G below 2^31, so a call's tickets fit 32 bits
@@ -403,125 +532,124 @@ __global__ __launch_bounds__(G::THREADS) void k_lookback(const Args A)
     const int64_t tu0 = k * ROWS;
     const int64_t u0 = tu0 + (int64_t)tt * R;
     const bool interior = tile_interior<G, BWD>(A, tu0, g);
-    const uint32_t epoch = A.epoch;
+    const uint32_t tag_agg = A.epoch << 1, tag_incl = tag_agg | 1u;
+    LINREC_TRACE_MARK(0);
 
     Rows<G> r;
-    vec<VEC> hp[BWD ? R : 1], S;
-    dvec<VEC> P;
+    vec<VEC> hp[BWD ? R : 1];
     const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
     tile_load<G, BWD>(A, ad, u0, col_ok, interior, r);
     if constexpr (BWD && !HP_LATE) {
         if (A.out1) tile_load_hprev<G>(A, ad, u0, col, col_ok, interior, hp);
     }
-    local_reduce<G>(r, P, S);
-    sP[tt][tc] = P;
-    sS[tt][tc] = S;
-    __syncthreads();
-    dvec<VEC> Pe, Se;
-    lds_exclusive<G>(sP, sS, tt, tc, Pe, Se);
+    // thread-exclusive prefix inside the tile; rounded to fp32 once (it is used once, in the
+    // rescan's carry-in, and is not fed on along the chain of tiles)
+    vec<VEC> Pe32, Se32;
     const bool publish = (k + 1 < A.K) && col_ok;
-    if (tt == WT - 1) {
-        const dvec<VEC> Pt = Pe * P;
-        // the published S is fp32; keep the same rounded value locally so that every tile composes
-        // exactly what its successors read
-        const vec<VEC> St = narrow<VEC>(dfma<VEC>(P, Se, widen<VEC>(S)));
-        sTot[0][tc] = Pt;
-        sTot[1][tc] = widen<VEC>(St);
-        if (publish) {
-            unsigned long long *w = A.lbAgg + (k * A.C + col) * 3;
+    unsigned long long *const my_words = A.lbAgg + (k * A.C + col) * 3;
+    {
+        dvec<VEC> P, Pe, Pt;
+        vec<VEC> S, St32;
+        local_reduce<G>(r, P, S);
+        LINREC_TRACE_MARK(1);
+        tile_scan<G>(lds, tid, P, S, Pe, Se32, Pt, St32);
+        Pe32 = narrow<VEC>(Pe);
+        if (tt == 0) {
+            // the tile's own inclusive state below is built from the same fp32 S that is published,
+            // so that the tile and its successors agree on what it contributes
+            sPt[tc] = Pt;
+            sSt[tc] = St32;
+            if (publish) {
 #pragma unroll
-            for (int v = 0; v < VEC; ++v) {
-                const unsigned long long pb = (unsigned long long)__double_as_longlong(Pt[v]);
-                lb_store(w + 3 * v, lb_pack((uint32_t)pb, epoch));
-                lb_store(w + 3 * v + 1, lb_pack((uint32_t)(pb >> 32), epoch));
-                lb_store(w + 3 * v + 2, lb_pack(__float_as_uint(St[v]), epoch));
+                for (int v = 0; v < VEC; ++v) {
+                    const unsigned long long pb = (unsigned long long)__double_as_longlong(Pt[v]);
+                    lb_store(my_words + 3 * v, lb_pack((uint32_t)pb, tag_agg));
+                    lb_store(my_words + 3 * v + 1, lb_pack((uint32_t)(pb >> 32), tag_agg));
+                    lb_store(my_words + 3 * v + 2, lb_pack(__float_as_uint(St32[v]), tag_agg));
+                }
             }
         }
     }
-    __syncthreads();  // every thread is done reading sP/sS; they now hold the look-back window
+    LINREC_TRACE_MARK(2);
+    int n_windows = 0;
 
     // ---- look-back --------------------------------------------------------------------------
-    // (Pr, Sr): composition of the predecessors visited so far, nearest first (tt == 0 threads only)
-    dvec<VEC> Pr = dsplat<VEC>(1.0), Sr = dsplat<VEC>(0.0);
-    bool done = false;
+    // Window w covers predecessors k-1-w*WT down to k-(w+1)*WT; thread (tt, tc) reads the one that is
+    // WT-1-tt tiles before the window's nearest, so that tt increases with time like inside a tile.
+    // A predecessor that has published its inclusive state I enters as the pair (0, I): composed in
+    // time order, a zero product wipes out everything earlier, so the window total (Pw, Sw) is the
+    // affine map from the state before the window's earliest relevant tile to the state after its
+    // nearest.  (Pr, Sr) composes the windows visited so far.  The walk stops once Pr == 0 in every
+    // column of the tile: the remaining history cannot matter (an inclusive state was met, or the
+    // lambdas themselves multiplied to zero) and Sr is the carry-in.
+    dvec<VEC> Pr = dsplat<VEC>(1.0);
+    vec<VEC> Sr = splat<VEC>(0.0f);
     for (int64_t base = k - 1;; base -= WT) {
-        const int64_t pred = base - tt;
-        int status = ST_INCL;
+        const int64_t pred = base - (WT - 1 - tt);
         dvec<VEC> vP = dsplat<VEC>(0.0);
         vec<VEC> vS = splat<VEC>(0.0f);
         if (pred < 0 || !col_ok) {
-            // before the first tile: the initial state (h0 forward, zero backward)
+            // before the first tile: the initial state (h0 forward, zero backward), as (0, h0)
             if (!BWD && pred == -1 && col_ok && A.h0) vS = ld<VEC>(A.h0 + col);
         } else {
-            const unsigned long long *wi = A.lbIncl + (pred * A.C + col);
-            const unsigned long long *wa = A.lbAgg + (pred * A.C + col) * 3;
+            const unsigned long long *w = A.lbAgg + (pred * A.C + col) * 3;
             uint32_t spins = 0;
             for (;;) {
-                bool ok = true;
+                bool all_incl = true, all_agg = true;
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
-                    const unsigned long long w = lb_load(wi + v);
-                    ok = ok && ((uint32_t)(w >> 32) == epoch);
-                    vS[v] = __uint_as_float((uint32_t)w);
-                }
-                if (ok) { status = ST_INCL; break; }
-                ok = true;
-#pragma unroll
-                for (int v = 0; v < VEC; ++v) {
-                    const unsigned long long wl = lb_load(wa + 3 * v), wh = lb_load(wa + 3 * v + 1),
-                                             ws = lb_load(wa + 3 * v + 2);
-                    ok = ok && ((uint32_t)(wl >> 32) == epoch) && ((uint32_t)(wh >> 32) == epoch) &&
-                         ((uint32_t)(ws >> 32) == epoch);
+                    const unsigned long long wl = lb_load(w + 3 * v), wh = lb_load(w + 3 * v + 1),
+                                             ws = lb_load(w + 3 * v + 2);
+                    const uint32_t ts = (uint32_t)(ws >> 32);
+                    all_incl = all_incl && (ts == tag_incl);
+                    all_agg = all_agg && (ts == tag_agg) && ((uint32_t)(wl >> 32) == tag_agg) &&
+                              ((uint32_t)(wh >> 32) == tag_agg);
                     vP[v] = __longlong_as_double((long long)((wh << 32) | (wl & 0xffffffffull)));
                     vS[v] = __uint_as_float((uint32_t)ws);
                 }
-                if (ok) { status = ST_AGG; break; }
+                // (a predecessor caught between its two publications has some columns of this
+                // thread tagged inclusive and some not: neither test holds and it is read again)
+                if (all_incl) { vP = dsplat<VEC>(0.0); break; }
+                if (all_agg) break;
                 if (++spins > A.spin_limit) {  // give up: flag the error, finish with a zero state
                     atomicOr(A.err, 1u);
+                    vP = dsplat<VEC>(0.0);
                     vS = splat<VEC>(0.0f);
-                    status = ST_INCL;
                     break;
                 }
-                __builtin_amdgcn_s_sleep(2);
+                __builtin_amdgcn_s_sleep(1);
             }
         }
-        sP[tt][tc] = vP;
-        sS[tt][tc] = vS;
-        sSt[tt][tc] = status;
-        __syncthreads();
-        if (tt == 0 && !done) {
-            dvec<VEC> carry = dsplat<VEC>(0.0);
+        __syncthreads();  // the previous use of the scan's LDS staging is over
+        dvec<VEC> Pe, Pw;
+        vec<VEC> Se, Sw;
+        tile_scan<G>(lds, tid, vP, vS, Pe, Se, Pw, Sw);
+        // (window) is earlier in time than everything in (Pr, Sr): it goes on the left
+        Sr = narrow<VEC>(dfma<VEC>(Pr, widen<VEC>(Sw), widen<VEC>(Sr)));
+        Pr = Pw * Pr;
+        ++n_windows;
+        bool open = false;
 #pragma unroll
-            for (int j = 0; j < WT; ++j) {
-                const int stj = sSt[j][tc];
-                const dvec<VEC> p = sP[j][tc];
-                const dvec<VEC> s = widen<VEC>(sS[j][tc]);
-                if (!done) {
-                    // (p, s) is earlier in time than everything in (Pr, Sr): it goes on the left
-                    const dvec<VEC> t = dfma<VEC>(Pr, s, Sr);
-                    if (stj == ST_INCL) { carry = t; done = true; }
-                    else { Sr = t; Pr = p * Pr; }
-                }
-            }
-            if (done) {
-                sCarry[tc] = carry;
-                if (publish) {
-                    const vec<VEC> incl = narrow<VEC>(dfma<VEC>(sTot[0][tc], carry, sTot[1][tc]));
+        for (int v = 0; v < VEC; ++v) open = open || (Pr[v] != 0.0);
+        // every wavefront holds every tc, so this vote is the same in all of them
+        if (!__any(open)) break;
+    }
+    LINREC_TRACE_MARK(3);
+    LINREC_TRACE_VAL(5, n_windows);
+    LINREC_TRACE_VAL(6, ((unsigned long long)k << 32) | (unsigned)g);
+    if (tt == 0 && publish) {
+        const vec<VEC> incl = narrow<VEC>(dfma<VEC>(sPt[tc], widen<VEC>(Sr), widen<VEC>(sSt[tc])));
 #pragma unroll
-                    for (int v = 0; v < VEC; ++v)
-                        lb_store(A.lbIncl + (k * A.C + col + v), lb_pack(__float_as_uint(incl[v]), epoch));
-                }
-            }
-        }
-        if (!__syncthreads_or((tt == 0 && !done) ? 1 : 0)) break;
+        for (int v = 0; v < VEC; ++v) lb_store(my_words + 3 * v + 2, lb_pack(__float_as_uint(incl[v]), tag_incl));
     }
 
     // ---- rescan from the carry and store -------------------------------------------------------
-    rescan<G>(r, narrow<VEC>(dfma<VEC>(Pe, sCarry[tc], Se)));
+    rescan<G>(r, vfma<VEC>(Pe32, Sr, Se32));
     if constexpr (BWD && HP_LATE) {
         if (A.out1) tile_load_hprev<G>(A, ad, u0, col, col_ok, interior, hp);
     }
     tile_store<G, BWD>(A, ad, u0, col, col_ok, interior, r, hp);
+    LINREC_TRACE_MARK(4);
 }
 
 }  // namespace linrec

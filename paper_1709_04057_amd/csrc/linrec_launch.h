@@ -20,14 +20,14 @@ struct Args {
     int32_t M;           // three-phase: tiles walked per chunk
     // three-phase workspace, each [K, C] fp64
     double *aggP, *aggS, *carry;
-    // look-back workspace: 64-bit words {epoch : 32 | payload bits : 32}
-    unsigned long long *lbAgg;   // [K, C, 3]  low and high half of the fp64 P, fp32 S of a tile
-    unsigned long long *lbIncl;  // [K, C]     fp32 state after the tile's last step
+    // look-back workspace: 64-bit words {tag : 32 | payload bits : 32}
+    unsigned long long *lbAgg;   // [K, C, 3]  low and high half of the fp64 P; fp32 S, later the fp32 inclusive state
     unsigned long long *ticket;  // monotonically increasing tile counter
     unsigned long long ticket_base;
-    uint32_t epoch;
+    uint32_t epoch;              // 1 .. 2^31-1; tags are epoch<<1 (summary) and epoch<<1|1 (inclusive state)
     uint32_t spin_limit;
     uint32_t *err;
+    unsigned long long *trace;  // only read by builds with -DLINREC_TRACE: 8 words per tile
 };
 
 enum Kind { KIND_REDUCE = 0, KIND_FIXUP = 1, KIND_LOOKBACK = 2 };
@@ -52,8 +52,10 @@ struct TileDesc {
     X(7, 4, 16, 8, 32)  \
     X(8, 4, 16, 16, 16) \
     X(9, 4, 16, 32, 8)  \
-    X(10, 4, 16, 64, 4)
-constexpr int NUM_TILES = 10;
+    X(10, 4, 16, 64, 4) \
+    X(11, 4, 12, 8, 32) \
+    X(12, 4, 12, 16, 16)
+constexpr int NUM_TILES = 12;
 
 const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 
@@ -65,5 +67,7 @@ hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const f
                                  int64_t C, hipStream_t s);
 hipError_t launch_serial(const Args &A, bool bwd, hipStream_t s);
 hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
+hipError_t launch_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
+                               int64_t n, hipStream_t s);
 
 }  // namespace linrec

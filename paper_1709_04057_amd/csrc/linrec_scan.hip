@@ -3,7 +3,7 @@
 //                       C_{-1} = h_0, over the K chunk summaries of every column;
 //   k_serial_fwd/bwd -- the paper's comparison kernel of Section 4.1.1: serial over the sequence
 //                       length, parallel over features and minibatch.
-#include "linrec_launch.h"
+#include "linrec_device.h"
 
 namespace linrec {
 
@@ -133,6 +133,46 @@ __global__ void k_fill_zero(float *p, int64_t n)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0.0f;
+}
+
+// Streaming probe: the bandwidth a kernel with this library's access instructions reaches when it
+// does nothing but move data.  Reads the non-null inputs, writes the non-null outputs, 16 bytes per
+// lane per access, PROBE_R independent accesses per tensor in flight per thread.
+constexpr int PROBE_R = 8;
+__global__ __launch_bounds__(256) void k_stream_probe(const float *in0, const float *in1, const float *in2, float *out0,
+                                                      float *out1, int64_t n4)
+{
+    const int64_t chunk = (int64_t)blockIdx.x * (256 * PROBE_R);
+    vec<4> acc[PROBE_R];
+#pragma unroll
+    for (int j = 0; j < PROBE_R; ++j) {
+        const int64_t i = chunk + j * 256 + threadIdx.x;
+        vec<4> v = splat<4>(1.0f);
+        if (i < n4) {
+            if (in0) v = ld<4>(in0 + 4 * i);
+            if (in1) v *= ld<4>(in1 + 4 * i);
+            if (in2) v += ld<4>(in2 + 4 * i);
+        }
+        acc[j] = v;
+    }
+#pragma unroll
+    for (int j = 0; j < PROBE_R; ++j) {
+        const int64_t i = chunk + j * 256 + threadIdx.x;
+        if (i < n4) {
+            if (out0) st<4>(out0 + 4 * i, acc[j]);
+            if (out1) st<4>(out1 + 4 * i, acc[j] * acc[j]);
+        }
+    }
+}
+
+hipError_t launch_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
+                               int64_t n, hipStream_t s)
+{
+    const int64_t n4 = n / 4;
+    if (n4 <= 0) return hipSuccess;
+    const unsigned grid = (unsigned)((n4 + 256 * PROBE_R - 1) / (256 * PROBE_R));
+    hipLaunchKernelGGL(k_stream_probe, dim3(grid), dim3(256), 0, s, in0, in1, in2, out0, out1, n4);
+    return hipGetLastError();
 }
 
 hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const float *h0, double *carry, int64_t K,
