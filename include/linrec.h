@@ -18,8 +18,8 @@
  *     for T inputs).
  *   - Every pointer is a DEVICE pointer owned by the caller, valid on the device the stream
  *     belongs to.  The library neither frees nor retains them.  Any 4-byte aligned pointer
- *     is accepted; the 16-byte vector path is taken only when every tensor pointer is
- *     16-byte aligned and C is a multiple of 4.
+ *     is accepted; 16-byte (8-byte) accesses are used only when every tensor pointer is
+ *     16-byte (8-byte) aligned and C is a multiple of 4 (2).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only
  *     enqueue work and return: there is no host synchronisation, device-side faults surface
  *     at the caller's next synchronisation.
@@ -69,8 +69,10 @@ enum {
     LINREC_OPT_TILE = 2,       /* tile-shape id, 0 = automatic (see linrec_tile_info)        */
     LINREC_OPT_CHUNK_TILES = 3,/* three-phase: tiles walked per chunk, 0 = automatic         */
     LINREC_OPT_SPIN_LIMIT = 4, /* look-back: polls before a wait is declared failed          */
-    LINREC_OPT_HPREV_LATE = 5  /* look-back backward: load h after the rescan (1), together
+    LINREC_OPT_HPREV_LATE = 5, /* look-back backward: load h after the rescan (1), together
                                   with lambda and grad_h (0), or let the library decide (-1)  */
+    LINREC_OPT_TAPER = 6       /* look-back: end the tile sequence with half- and quarter-height
+                                  tiles (1, default) or use full-height tiles throughout (0)  */
 };
 
 /*
@@ -116,9 +118,9 @@ int linrec_tile_info(int tile_id, int *threads_cols, int *threads_time, int *row
                      int *cols_per_thread);
 
 /* Reports the variant and tile shape the library would use for a [T, B, n] problem under the
- * current options (`aligned16_and_c_mult4`: whether the 16-byte vector path is available).
+ * current options when every tensor pointer is aligned to `alignment_bytes` (4, 8 or 16).
  * Host-only; makes no HIP call. */
-int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int aligned16_and_c_mult4,
+int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int alignment_bytes,
                 int *variant, int *tile_id);
 
 /* Host-side argument checks only (exactly the checks linrec_forward / linrec_backward run

@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     OPT_CHUNK_TILES,
     OPT_HPREV_LATE,
     OPT_SPIN_LIMIT,
+    OPT_TAPER,
     OPT_TILE,
     OPT_VARIANT,
     VARIANT_AUTO,

@@ -11,7 +11,7 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "linrec.h")
 _lib = None
 
 VARIANT_AUTO, VARIANT_THREEPHASE, VARIANT_LOOKBACK, VARIANT_SERIAL = 0, 1, 2, 3
-OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE = 1, 2, 3, 4, 5
+OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE, OPT_TAPER = 1, 2, 3, 4, 5, 6
 
 
 class LinrecError(RuntimeError):
@@ -180,9 +180,10 @@ def linrec_tile_info(tile_id: int):
                 rows=b.value * c.value, cols=a.value * d.value)
 
 
-def linrec_plan(T, B, n, backward=False, vec4=True):
+def linrec_plan(T, B, n, backward=False, alignment=16):
+    """(variant, tile id) the library would pick for tensors aligned to ``alignment`` bytes."""
     v, t = ctypes.c_int(), ctypes.c_int()
-    _check(lib().linrec_plan(int(T), int(B), int(n), int(bool(backward)), int(bool(vec4)), ctypes.byref(v), ctypes.byref(t)))
+    _check(lib().linrec_plan(int(T), int(B), int(n), int(bool(backward)), int(alignment), ctypes.byref(v), ctypes.byref(t)))
     return v.value, t.value
 
 

@@ -7,6 +7,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
+#include <initializer_list>
 #include <map>
 #include <mutex>
 #include <utility>
@@ -45,6 +47,7 @@ struct Options {
     int64_t chunk_tiles = 0;
     int64_t spin_limit = 1 << 22;
     int64_t hp_late = -1;  // -1 automatic
+    int64_t taper = 1;
     Options()
     {
         if (const char *v = getenv("LINREC_VARIANT")) {
@@ -109,7 +112,26 @@ int ensure(void **buf, size_t *have, size_t need, bool zero, hipStream_t s)
     return LINREC_OK;
 }
 
+// Workgroups the device holds at once, for sizing the tail of short tiles: compute units x 3.
+int resident_workgroups(int dev)
+{
+    static std::map<int, int> cache;  // guarded by g_mu (callers hold it)
+    auto it = cache.find(dev);
+    if (it != cache.end()) return it->second;
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    return cache[dev] = 3 * cus;
+}
+
 bool aligned16(const void *p) { return p == nullptr || ((uintptr_t)p & 15u) == 0; }
+
+// Widest per-thread access (columns) that C and the pointers' alignment allow: 4, 2 or 1.
+int max_vec(int64_t C, std::initializer_list<const void *> ptrs)
+{
+    uintptr_t bits = (uintptr_t)(C * 4);
+    for (const void *p : ptrs) bits |= (uintptr_t)p;
+    return (bits & 15u) == 0 ? 4 : (bits & 7u) == 0 ? 2 : 1;
+}
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -120,23 +142,22 @@ int pow2_at_least(int64_t x)
     return p;
 }
 
-// Tile shape for a [T, C] problem when the caller did not fix one.
-int auto_tile(int64_t T, int64_t C, bool vec4, bool bwd, int variant)
+// Tile shape for a [T, C] problem when the caller did not fix one.  Measured on MI355X: one column
+// per thread with many rows per thread (few registers beyond the rows themselves, so three
+// workgroups fit a compute unit), 128-byte row segments, and tiles as tall as T allows (the taller
+// the tile, the fewer summaries the look-back moves per element); 256-byte segments once the rows
+// are long.
+int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
 {
-    (void)T;
-    if (!vec4) return C >= 48 ? 1 : 2;
-    const int64_t cv = C / 4;
-    // Tall, narrow tiles keep the look-back cheap (few summaries per element); the row segment of a
-    // tile is WC*16 bytes, kept at >= 128 B.
-    int wc = cv >= 16 ? 16 : 8;
-    if (variant == LINREC_VARIANT_THREEPHASE) wc = cv >= 64 ? 64 : pow2_at_least(cv) < 8 ? 8 : pow2_at_least(cv);
-    const bool r16 = !bwd;
-    switch (wc) {
-    case 8: return r16 ? 7 : 3;
-    case 16: return r16 ? 8 : 4;
-    case 32: return r16 ? 9 : 5;
-    default: return r16 ? 10 : 6;
-    }
+    (void)vec;
+    (void)bwd;
+    (void)variant;
+    if (C <= 16) return T >= 4096 ? 23 : 2;
+    if (T >= 32768) return C >= 2048 ? 20 : 22;
+    if (T >= 8192) return 17;
+    if (T >= 1536) return 19;
+    if (T >= 512) return 18;
+    return C >= 48 ? 1 : 2;
 }
 
 struct Plan {
@@ -145,26 +166,27 @@ struct Plan {
 };
 
 // Picks variant and tile, honouring the options where they apply to this problem.
-Plan make_plan(int64_t T, int64_t C, bool vec4, bool bwd)
+Plan make_plan(int64_t T, int64_t C, int vec, bool bwd)
 {
     Plan p;
     p.variant = (int)opts().variant;
     if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
     p.tile = (int)opts().tile;
-    if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec == 4 && !vec4) p.tile = 0;
-    if (p.tile < 1 || p.tile > NUM_TILES) p.tile = auto_tile(T, C, vec4, bwd, p.variant);
+    if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
+    if (p.tile < 1 || p.tile > NUM_TILES) p.tile = auto_tile(T, C, vec, bwd, p.variant);
     const TileDesc &d = kTiles[p.tile - 1];
     // per-thread byte offsets inside a tile are 32-bit, tickets of a call are 31-bit
     const int64_t G = ceil_div(C, d.cols()), K = ceil_div(T, d.rows());
-    if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32) || K * G >= ((int64_t)1 << 31))
+    // (the short tiles that end a look-back sequence can raise the tile count, by less than 4x)
+    if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32) || 4 * K * G >= ((int64_t)1 << 31))
         p.variant = LINREC_VARIANT_SERIAL;
-    p.hp_late = opts().hp_late < 0 ? (d.r >= 16) : (opts().hp_late != 0);
+    p.hp_late = opts().hp_late > 0;
     return p;
 }
 
-int run(Args A, bool bwd, bool vec4, hipStream_t s)
+int run(Args A, bool bwd, int vec, hipStream_t s)
 {
-    const Plan plan = make_plan(A.T, A.C, vec4, bwd);
+    const Plan plan = make_plan(A.T, A.C, vec, bwd);
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
         if ((e = launch_serial(A, bwd, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
@@ -202,9 +224,25 @@ int run(Args A, bool bwd, bool vec4, hipStream_t s)
         return LINREC_OK;
     }
 
-    // single pass with look-back
-    A.K = tiles_t;
+    // Single pass with look-back.  The rows that the last "round" of resident workgroups would take
+    // as full tiles are cut into half- and quarter-height tiles instead (see k_lookback).
     A.M = 1;
+    A.K1 = tiles_t;
+    A.K2 = 0;
+    A.K = tiles_t;
+    if (opts().taper && d.r % 4 == 0 && d.r >= 8) {
+        const int64_t rows = d.rows();
+        const int64_t full = A.T / rows;                                   // complete full-height tiles
+        const int64_t round = ceil_div((int64_t)resident_workgroups(dev), A.G);  // full tiles per chain in flight
+        const int64_t taper_tiles = std::min(full / 2, round);
+        if (taper_tiles > 0) {
+            A.K1 = full - taper_tiles;
+            const int64_t left = A.T - A.K1 * rows;                        // rows in the tapered region
+            A.K2 = (left / 2) / (rows / 2);
+            const int64_t rest = left - A.K2 * (rows / 2);
+            A.K = A.K1 + A.K2 + ceil_div(rest, rows / 4);
+        }
+    }
     const size_t kc = (size_t)A.K * (size_t)A.C;
     const size_t old_bytes = ws.lb_bytes;
     int rc = ensure(&ws.lb, &ws.lb_bytes, kLbHeader + 3 * kc * sizeof(unsigned long long), true, s);
@@ -249,8 +287,7 @@ extern "C" int linrec_forward(const float *lambda, const float *x, const float *
     A.out0 = h_out;
     A.T = T;
     A.C = C;
-    const bool vec4 = (C % 4 == 0) && aligned16(lambda) && aligned16(x) && aligned16(h0) && aligned16(h_out);
-    return run(A, false, vec4, (hipStream_t)stream);
+    return run(A, false, max_vec(C, {lambda, x, h0, h_out}), (hipStream_t)stream);
 }
 
 extern "C" int linrec_backward(const float *lambda, const float *h, const float *h0, const float *grad_h, float *grad_x,
@@ -280,9 +317,7 @@ extern "C" int linrec_backward(const float *lambda, const float *h, const float 
     A.gh0 = grad_h0;
     A.T = T;
     A.C = C;
-    const bool vec4 = (C % 4 == 0) && aligned16(lambda) && aligned16(h) && aligned16(h0) && aligned16(grad_h) &&
-                      aligned16(grad_x) && aligned16(grad_lambda) && aligned16(grad_h0);
-    return run(A, true, vec4, s);
+    return run(A, true, max_vec(C, {lambda, h, h0, grad_h, grad_x, grad_lambda, grad_h0}), s);
 }
 
 extern "C" int linrec_set_option(int option, int64_t value)
@@ -308,6 +343,10 @@ extern "C" int linrec_set_option(int option, int64_t value)
         if (value < -1 || value > 1) return LINREC_ERR_OPTION;
         opts().hp_late = value;
         return LINREC_OK;
+    case LINREC_OPT_TAPER:
+        if (value < 0 || value > 1) return LINREC_ERR_OPTION;
+        opts().taper = value;
+        return LINREC_OK;
     default: return LINREC_ERR_OPTION;
     }
 }
@@ -320,6 +359,7 @@ extern "C" int64_t linrec_get_option(int option)
     case LINREC_OPT_CHUNK_TILES: return opts().chunk_tiles;
     case LINREC_OPT_SPIN_LIMIT: return opts().spin_limit;
     case LINREC_OPT_HPREV_LATE: return opts().hp_late;
+    case LINREC_OPT_TAPER: return opts().taper;
     default: return LINREC_ERR_OPTION;
     }
 }
@@ -336,12 +376,13 @@ extern "C" int linrec_tile_info(int tile_id, int *threads_cols, int *threads_tim
     return LINREC_OK;
 }
 
-extern "C" int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int aligned16_and_c_mult4, int *variant,
+extern "C" int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int alignment_bytes, int *variant,
                            int *tile_id)
 {
     int64_t C = B * n;
     if (T <= 0 || B <= 0 || n <= 0) return LINREC_ERR_SHAPE;
-    const Plan p = make_plan(T, C, aligned16_and_c_mult4 != 0 && C % 4 == 0, backward != 0);
+    const int vec = max_vec(C, {(const void *)(uintptr_t)(alignment_bytes > 0 ? alignment_bytes : 4)});
+    const Plan p = make_plan(T, C, vec, backward != 0);
     if (variant) *variant = p.variant;
     if (tile_id) *tile_id = p.tile;
     return LINREC_OK;

@@ -27,9 +27,13 @@ template <int VEC_, int R_, int WC_, int WT_>
 struct Geo {
     static constexpr int VEC = VEC_, R = R_, WC = WC_, WT = WT_;
     static constexpr int THREADS = WC * WT, ROWS = WT * R, COLS = WC * VEC;
-    // wavefronts per SIMD the register allocation is held to: the tile data take 2*R*VEC registers
-    // per lane of the 512 a SIMD has, and the waits of the look-back are hidden by other tiles
+    // minimum wavefronts per SIMD handed to __launch_bounds__ (1 = leave the choice to the compiler,
+    // which lands on 2*R*VEC data registers plus 40-100 of overhead per lane)
+#ifdef LINREC_OCC_OVERRIDE
+    static constexpr int OCC = LINREC_OCC_OVERRIDE;
+#else
     static constexpr int OCC = 1;
+#endif
 };
 
 // VEC adjacent columns of one row, kept as one SSA value (never addressed through a pointer, so the
@@ -110,13 +114,15 @@ __device__ __forceinline__ vec<N> splat(float x)
 // stores are dropped) on top of the explicit masks below.  The host guarantees
 // (ROWS*C + COLS)*4 < 2^32.
 //
-// Forward: the corner is the tile's first row; thread (tt, tc) starts tt*R rows further down.
+// Forward: the corner is the tile's first row; thread (tt, tc) starts tt*rk rows further down
+// (rk = rows per thread of this tile, R except in the short tiles that end the sequence).
 // Backward: logical step u is row t = T-1-u, so rows go DOWN with u; the corner is the tile's lowest
-// row t_low = T - tu0 - ROWS (negative for the last, partial tile: those rows are masked and never
-// touched) and thread (tt, tc) starts (WT-1-tt)*R rows above it.
+// row t_low = T - tu0 - WT*rk (negative for the last, partial tile: those rows are masked and never
+// touched) and thread (tt, tc) starts (WT-1-tt)*rk rows above it.
 // ---------------------------------------------------------------------------------------------
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 constexpr int kBufNT = 2;  // cache-policy bit "nt": streaming data, touched once
 
 template <int N>
@@ -125,8 +131,11 @@ __device__ __forceinline__ vec<N> buf_ld(rsrc_t rs, uint32_t voff, uint32_t soff
     if constexpr (N == 4) {
         const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
         return __builtin_bit_cast(vec<4>, v);
+    } else if constexpr (N == 2) {
+        const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
+        return __builtin_bit_cast(vec<2>, v);
     } else {
-        static_assert(N == 1, "one or four columns per thread");
+        static_assert(N == 1, "one, two or four columns per thread");
         const unsigned int v = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
         return vec<1>(__uint_as_float(v));
     }
@@ -136,6 +145,8 @@ __device__ __forceinline__ void buf_st(rsrc_t rs, uint32_t voff, uint32_t soff, 
 {
     if constexpr (N == 4) {
         __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
+    } else if constexpr (N == 2) {
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, v), rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
     } else {
         __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(v[0]), rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
     }
@@ -147,15 +158,16 @@ struct TileAddr {
     int64_t total;  // T*C
     uint32_t toff;  // this thread's byte offset from the corner
     uint32_t rowb;  // bytes per row
-    __device__ __forceinline__ TileAddr(const Args &A, int64_t tu0, int g, int tt, int tc)
-        : total(A.T * A.C), rowb((uint32_t)A.C * 4u)
+    int rk;         // rows per thread of this tile: R, or R/2, R/4 for the short tiles at the end of T
+    __device__ __forceinline__ TileAddr(const Args &A, int64_t tu0, int g, int tt, int tc, int rk_ = G::R)
+        : total(A.T * A.C), rowb((uint32_t)A.C * 4u), rk(rk_)
     {
         if constexpr (!BWD) {
             base = tu0 * A.C + (int64_t)g * G::COLS;
-            toff = (uint32_t)(tt * G::R) * rowb + (uint32_t)(tc * G::VEC) * 4u;
+            toff = (uint32_t)(tt * rk) * rowb + (uint32_t)(tc * G::VEC) * 4u;
         } else {
-            base = (A.T - tu0 - G::ROWS) * A.C + (int64_t)g * G::COLS;
-            toff = (uint32_t)((G::WT - 1 - tt) * G::R) * rowb + (uint32_t)(tc * G::VEC) * 4u;
+            base = (A.T - tu0 - (int64_t)G::WT * rk) * A.C + (int64_t)g * G::COLS;
+            toff = (uint32_t)((G::WT - 1 - tt) * rk) * rowb + (uint32_t)(tc * G::VEC) * 4u;
         }
     }
     // Resource for tensor p seen `shift` rows away from the tile (+1: lambda one row ahead, -1: h one
@@ -168,8 +180,8 @@ struct TileAddr {
         if (bytes < 0) bytes = 0;
         return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p + first), 0, (int)(uint32_t)bytes, 0x00020000);
     }
-    // scalar byte offset of the thread's row j (rows go up with j forward, down backward)
-    __device__ __forceinline__ uint32_t soff(int j) const { return (uint32_t)(BWD ? G::R - 1 - j : j) * rowb; }
+    // scalar byte offset of the thread's row j < rk (rows go up with j forward, down backward)
+    __device__ __forceinline__ uint32_t soff(int j) const { return (uint32_t)(BWD ? rk - 1 - j : j) * rowb; }
 };
 
 // The thread's R rows of the two scan operands.
@@ -178,26 +190,46 @@ struct Rows {
     vec<G::VEC> a[G::R], b[G::R];
 };
 
+// Which of the thread's R rows exist, as small integers computed once per tile (row j is compared
+// against them with j a compile-time constant, so the masks cost no per-row registers).
+//   n   rows j < n are inside the tensor (0 when the thread's columns are outside)
+//   nh  backward: rows j < nh have a row t-1 inside the tensor; row j == nh < n is row t == 0
+//   first_has_next  backward: row j == 0 has a successor row t+1 (false only for the very last row T-1)
+template <class G, bool BWD>
+struct RowMask {
+    int n, nh;
+    bool first_has_next;
+    __device__ __forceinline__ RowMask(const Args &A, int64_t u0, bool col_ok, int rk = G::R)
+    {
+        int64_t left = A.T - u0;
+        left = left < 0 ? 0 : (left > rk ? rk : left);
+        n = col_ok ? (int)left : 0;
+        int64_t lefth = A.T - 1 - u0;
+        lefth = lefth < 0 ? 0 : (lefth > rk ? rk : lefth);
+        nh = col_ok ? (int)lefth : 0;
+        first_has_next = u0 > 0;
+    }
+};
+
 // Loads the thread's R rows.  `interior` is workgroup-uniform: no row or column of the tile needs
 // masking (and, backward, no row is one of the boundary cases u == 0, t == 0).  Masked steps are the
 // identity pair (1, 0).
 template <class G, bool BWD>
-__device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> &ad, int64_t u0, bool col_ok,
+__device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
                                           bool interior, Rows<G> &r)
 {
     constexpr int R = G::R, VEC = G::VEC;
     const rsrc_t ra = ad.rsrc(A.a, BWD ? +1 : 0), rb = ad.rsrc(A.b);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const int64_t u = u0 + j;
         vec<VEC> va = splat<VEC>(1.0f), vb = splat<VEC>(0.0f);
-        if (interior || (col_ok && u < A.T)) {
+        if (interior || j < mk.n) {
             vb = buf_ld<VEC>(rb, ad.toff, ad.soff(j));
             if constexpr (!BWD) {
                 va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
             } else {
                 va = splat<VEC>(0.0f);  // the last row has no successor
-                if (interior || u > 0) va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
+                if (interior || j > 0 || mk.first_has_next) va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
             }
         }
         r.a[j] = va;
@@ -207,17 +239,17 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
 
 // Backward only: h one row behind each step (h[-1] = h0, zero when h0 is null).
 template <class G>
-__device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G, true> &ad, int64_t u0, int64_t col,
-                                                bool col_ok, bool interior, vec<G::VEC> (&hp)[G::R])
+__device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G, true> &ad,
+                                                const RowMask<G, true> &mk, int64_t col, bool interior,
+                                                vec<G::VEC> (&hp)[G::R])
 {
     constexpr int R = G::R, VEC = G::VEC;
     const rsrc_t rh = ad.rsrc(A.hprev, -1);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const int64_t u = u0 + j;
         vec<VEC> v = splat<VEC>(0.0f);
-        if (interior || (col_ok && u < A.T - 1)) v = buf_ld<VEC>(rh, ad.toff, ad.soff(j));
-        else if (col_ok && u == A.T - 1 && A.h0) v = ld<VEC>(A.h0 + col);
+        if (interior || j < mk.nh) v = buf_ld<VEC>(rh, ad.toff, ad.soff(j));
+        else if (j == mk.nh && j < mk.n && A.h0) v = ld<VEC>(A.h0 + col);
         hp[j] = v;
     }
 }
@@ -251,21 +283,20 @@ __device__ __forceinline__ void rescan(Rows<G> &r, vec<G::VEC> c)
 }
 
 template <class G, bool BWD>
-__device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD> &ad, int64_t u0, int64_t col,
-                                           bool col_ok, bool interior, const Rows<G> &r, const vec<G::VEC> *hp)
+__device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
+                                           int64_t col, bool interior, const Rows<G> &r, const vec<G::VEC> *hp)
 {
     constexpr int R = G::R, VEC = G::VEC;
     const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(BWD ? A.out1 : A.out0);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        const int64_t u = u0 + j;
-        if (interior || (col_ok && u < A.T)) {
+        if (interior || j < mk.n) {
             if constexpr (!BWD) {
                 buf_st<VEC>(r0, ad.toff, ad.soff(j), r.b[j]);
             } else {
                 if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), r.b[j]);
                 if (A.out1) buf_st<VEC>(r1, ad.toff, ad.soff(j), r.b[j] * hp[j]);
-                if (!interior && u == A.T - 1 && A.gh0)  // row 0: grad_h0 = lambda[0] * g_0
+                if (!interior && j == mk.nh && A.gh0)  // row t == 0: grad_h0 = lambda[0] * g_0
                     st<VEC>(A.gh0 + col, ld<VEC>(A.a + col) * r.b[j]);
             }
         }
@@ -414,7 +445,8 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_reduce(const Args A)
         dvec<VEC> P, Pe, Pt;
         vec<VEC> S, Se, St;
         const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
-        tile_load<G, BWD>(A, ad, tu0 + (int64_t)tt * R, col_ok, interior, r);
+        const RowMask<G, BWD> mk(A, tu0 + (int64_t)tt * R, col_ok);
+        tile_load<G, BWD>(A, ad, mk, interior, r);
         local_reduce<G>(r, P, S);
         if (m > 0) __syncthreads();  // the previous tile's wavefront totals have been consumed
         tile_scan<G>(lds, tid, P, S, Pe, Se, Pt, St);
@@ -453,15 +485,16 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_fixup(const Args A)
         vec<VEC> hp[BWD ? R : 1], S, Se, St;
         dvec<VEC> P, Pe, Pt;
         const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
-        tile_load<G, BWD>(A, ad, u0, col_ok, interior, r);
+        const RowMask<G, BWD> mk(A, u0, col_ok);
+        tile_load<G, BWD>(A, ad, mk, interior, r);
         if constexpr (BWD) {
-            if (A.out1) tile_load_hprev<G>(A, ad, u0, col, col_ok, interior, hp);
+            if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
         }
         local_reduce<G>(r, P, S);
         if (m > 0) __syncthreads();
         tile_scan<G>(lds, tid, P, S, Pe, Se, Pt, St);
         rescan<G>(r, narrow<VEC>(dfma<VEC>(Pe, cc, widen<VEC>(Se))));
-        tile_store<G, BWD>(A, ad, u0, col, col_ok, interior, r, hp);
+        tile_store<G, BWD>(A, ad, mk, col, interior, r, hp);
         cc = dfma<VEC>(Pt, cc, widen<VEC>(St));
     }
 }
@@ -529,18 +562,32 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     if (k >= A.K) return;  // cannot happen with a matching launch; keeps a mismatched one in bounds
     const int64_t col = ((int64_t)g * WC + tc) * VEC;
     const bool col_ok = col < A.C;
-    const int64_t tu0 = k * ROWS;
-    const int64_t u0 = tu0 + (int64_t)tt * R;
-    const bool interior = tile_interior<G, BWD>(A, tu0, g);
+    // Tiles k < K1 are full height; then come K2 tiles of half height and, to the end, tiles of a
+    // quarter height (each thread then owns R/2 or R/4 rows, its other rows are masked).  They are the
+    // last tickets handed out, so that the kernel does not end on a few workgroups finishing big tiles.
+    int rk = R;
+    int64_t tu0 = k * ROWS;
+    if (k >= A.K1) {
+        if (k < A.K1 + A.K2) {
+            rk = R / 2;
+            tu0 = A.K1 * ROWS + (k - A.K1) * (ROWS / 2);
+        } else {
+            rk = R / 4;
+            tu0 = A.K1 * ROWS + A.K2 * (ROWS / 2) + (k - A.K1 - A.K2) * (ROWS / 4);
+        }
+    }
+    const int64_t u0 = tu0 + (int64_t)tt * rk;
+    const bool interior = rk == R && tile_interior<G, BWD>(A, tu0, g);
     const uint32_t tag_agg = A.epoch << 1, tag_incl = tag_agg | 1u;
     LINREC_TRACE_MARK(0);
 
     Rows<G> r;
     vec<VEC> hp[BWD ? R : 1];
-    const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
-    tile_load<G, BWD>(A, ad, u0, col_ok, interior, r);
+    const TileAddr<G, BWD> ad(A, tu0, g, tt, tc, rk);
+    const RowMask<G, BWD> mk(A, u0, col_ok, rk);
+    tile_load<G, BWD>(A, ad, mk, interior, r);
     if constexpr (BWD && !HP_LATE) {
-        if (A.out1) tile_load_hprev<G>(A, ad, u0, col, col_ok, interior, hp);
+        if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
     }
     // thread-exclusive prefix inside the tile; rounded to fp32 once (it is used once, in the
     // rescan's carry-in, and is not fed on along the chain of tiles)
@@ -551,6 +598,9 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         dvec<VEC> P, Pe, Pt;
         vec<VEC> S, St32;
         local_reduce<G>(r, P, S);
+#ifdef LINREC_TRACE
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the mark below means "rows have arrived"
+#endif
         LINREC_TRACE_MARK(1);
         tile_scan<G>(lds, tid, P, S, Pe, Se32, Pt, St32);
         Pe32 = narrow<VEC>(Pe);
@@ -593,8 +643,21 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
             if (!BWD && pred == -1 && col_ok && A.h0) vS = ld<VEC>(A.h0 + col);
         } else {
             const unsigned long long *w = A.lbAgg + (pred * A.C + col) * 3;
+            // Wait on ONE word of the predecessor (the S word of the column group's first column,
+            // the same address for all lanes that look at this predecessor) with a growing pause:
+            // hundreds of workgroups poll at once and must not crowd out the data streams.
+            const unsigned long long *flag = A.lbAgg + (pred * A.C + (int64_t)g * G::COLS) * 3 + 2;
             uint32_t spins = 0;
+            bool gave_up = false;
             for (;;) {
+                const uint32_t t = (uint32_t)(lb_load(flag) >> 32);
+                if (t == tag_agg || t == tag_incl) break;
+                if (++spins > A.spin_limit) { gave_up = true; break; }
+                if (spins < 4) __builtin_amdgcn_s_sleep(2);
+                else __builtin_amdgcn_s_sleep(16);
+            }
+            // then read this thread's own words until they are consistent
+            while (!gave_up) {
                 bool all_incl = true, all_agg = true;
 #pragma unroll
                 for (int v = 0; v < VEC; ++v) {
@@ -611,13 +674,13 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
                 // thread tagged inclusive and some not: neither test holds and it is read again)
                 if (all_incl) { vP = dsplat<VEC>(0.0); break; }
                 if (all_agg) break;
-                if (++spins > A.spin_limit) {  // give up: flag the error, finish with a zero state
-                    atomicOr(A.err, 1u);
-                    vP = dsplat<VEC>(0.0);
-                    vS = splat<VEC>(0.0f);
-                    break;
-                }
-                __builtin_amdgcn_s_sleep(1);
+                if (++spins > A.spin_limit) gave_up = true;
+                else __builtin_amdgcn_s_sleep(2);
+            }
+            if (gave_up) {  // flag the error and finish with a zero state
+                atomicOr(A.err, 1u);
+                vP = dsplat<VEC>(0.0);
+                vS = splat<VEC>(0.0f);
             }
         }
         __syncthreads();  // the previous use of the scan's LDS staging is over
@@ -646,9 +709,11 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     // ---- rescan from the carry and store -------------------------------------------------------
     rescan<G>(r, vfma<VEC>(Pe32, Sr, Se32));
     if constexpr (BWD && HP_LATE) {
-        if (A.out1) tile_load_hprev<G>(A, ad, u0, col, col_ok, interior, hp);
+        // keep these loads behind the rescan: they take over the registers lambda occupied until now
+        __builtin_amdgcn_sched_barrier(0);
+        if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
     }
-    tile_store<G, BWD>(A, ad, u0, col, col_ok, interior, r, hp);
+    tile_store<G, BWD>(A, ad, mk, col, interior, r, hp);
     LINREC_TRACE_MARK(4);
 }
 

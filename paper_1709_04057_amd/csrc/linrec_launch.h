@@ -16,6 +16,7 @@ struct Args {
     float *gh0;          // backward: grad_h0 [C] (may be nullptr)
     int64_t T, C;
     int64_t K;           // tiles (look-back) or chunks (three-phase) along time
+    int64_t K1, K2;      // look-back: K1 full-height tiles, then K2 of half height, the rest a quarter
     int32_t G;           // column groups of COLS columns
     int32_t M;           // three-phase: tiles walked per chunk
     // three-phase workspace, each [K, C] fp64
@@ -39,9 +40,9 @@ struct TileDesc {
     int threads() const { return wc * wt; }
 };
 
-// Tile shapes, 1-based ids as used by LINREC_OPT_TILE.  Shapes 1-2 take one column per thread and
-// work for any C and any 4-byte alignment; the others take four columns per thread (16-byte
-// accesses) and need C % 4 == 0 and 16-byte aligned tensors.
+// Tile shapes, 1-based ids as used by LINREC_OPT_TILE: (id, columns per thread, rows per thread,
+// threads along columns, threads along time).  A shape with v columns per thread makes 4v-byte
+// accesses and needs C % v == 0 and 4v-byte aligned tensors; v = 1 works for any C and alignment.
 #define LINREC_TILES(X) \
     X(1, 1, 8, 64, 4)   \
     X(2, 1, 8, 16, 16)  \
@@ -54,8 +55,19 @@ struct TileDesc {
     X(9, 4, 16, 32, 8)  \
     X(10, 4, 16, 64, 4) \
     X(11, 4, 12, 8, 32) \
-    X(12, 4, 12, 16, 16)
-constexpr int NUM_TILES = 12;
+    X(12, 4, 12, 16, 16) \
+    X(13, 2, 32, 16, 16) \
+    X(14, 2, 24, 16, 16) \
+    X(15, 2, 16, 16, 16) \
+    X(16, 2, 32, 32, 8)  \
+    X(17, 1, 64, 32, 8)  \
+    X(18, 1, 32, 32, 8)  \
+    X(19, 1, 48, 32, 8)  \
+    X(20, 1, 64, 64, 4)  \
+    X(21, 1, 32, 64, 4)  \
+    X(22, 1, 64, 32, 16) \
+    X(23, 1, 64, 16, 16)
+constexpr int NUM_TILES = 23;
 
 const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 

@@ -98,7 +98,7 @@ def test_options_and_tile_table(L):
         i += 1
     assert len(tiles) >= 4
     for t in tiles:
-        assert t["cols_per_thread"] in (1, 4)
+        assert t["cols_per_thread"] in (1, 2, 4)
         assert t["threads_cols"] * t["threads_time"] in (256, 512, 1024)
         assert t["rows"] == t["threads_time"] * t["rows_per_thread"]
     with pytest.raises(lr.LinrecError):
@@ -108,13 +108,13 @@ def test_options_and_tile_table(L):
 def test_plan_is_host_only_and_consistent(L):
     for (T, B, n) in [(1024, 2, 32), (65536, 4, 256), (1048576, 1, 128), (4096, 16, 1024), (262144, 8, 512), (7, 1, 3)]:
         for bwd in (False, True):
-            for vec4 in (False, True):
-                variant, tile = lr.linrec_plan(T, B, n, backward=bwd, vec4=vec4)
+            for align in (4, 8, 16):
+                variant, tile = lr.linrec_plan(T, B, n, backward=bwd, alignment=align)
                 info = lr.linrec_tile_info(tile)
                 assert variant in (lr.VARIANT_THREEPHASE, lr.VARIANT_LOOKBACK, lr.VARIANT_SERIAL)
                 assert info is not None
-                if not vec4 or (B * n) % 4:
-                    assert info["cols_per_thread"] == 1
+                assert (B * n) % info["cols_per_thread"] == 0
+                assert info["cols_per_thread"] * 4 <= align
     # a tile whose rows would not fit 32-bit offsets falls back to the serial kernel
-    variant, _ = lr.linrec_plan(64, 1, 1 << 24, vec4=True)
+    variant, _ = lr.linrec_plan(64, 1, 1 << 26, alignment=16)
     assert variant == lr.VARIANT_SERIAL

@@ -35,8 +35,8 @@ def test_edge_shapes_all_tiles(variant):
     seed = 0
     for tile_id, info in tiles:
         for (B, n) in EDGE_BN:
-            if info["cols_per_thread"] == 4 and (B * n) % 4:
-                continue  # the library would replace the tile; covered by the scalar tiles
+            if (B * n) % info["cols_per_thread"]:
+                continue  # the library would replace the tile; covered by the narrower tiles
             for T in EDGE_T:
                 seed += 1
                 if seed % 3 and T not in (1, 65, 1031):   # thin the grid, keep the corners
@@ -80,11 +80,11 @@ def test_config1_full(variant):
                                        (5, (16384, 8, 512))])
 @pytest.mark.parametrize("variant", ["threephase", "lookback"])
 def test_configs_reduced_T_every_vector_tile(cfg, shape, variant):
-    """Same widths and value distributions as the full workloads, shorter T; every 4-column tile shape."""
+    """Same widths and value distributions as the full workloads, shorter T; every multi-column tile shape."""
     T, B, n = shape
     inp = wl.make_inputs(cfg, T=T, B=B, n=n, device=DEV)
     for tile_id, info in all_tiles():
-        if info["cols_per_thread"] != 4:
+        if info["cols_per_thread"] == 1 and info["rows_per_thread"] < 32:
             continue
         with options(variant=VARIANTS[variant], tile=tile_id):
             fwd_bwd_check(inp, f"cfg{cfg} reduced {variant} tile={tile_id}")
