@@ -37,6 +37,9 @@ def parse():
     ap.add_argument("--hprev-late", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0)
+    ap.add_argument("--probe", action="store_true",
+                    help="also time the library's pure streaming kernels (copy, 2-in/1-out, 3-in/2-out) on arrays "
+                         "of the workload's size; the copy doubles as the calibration kernel for byte counters")
     return ap.parse_args()
 
 
@@ -64,6 +67,38 @@ def cpu_baseline(inp, threads):
     return {"value": T * C / sec, "unit": "elements/s", "cores": threads, "kind": "oracle",
             "sample": "the full workload, one forward + one backward pass of the fp64 oracle, columns split "
                       f"over {threads} host threads; forward {t1 - t0:.3f} s, backward {t3 - t2:.3f} s"}
+
+
+def measured_traffic(cfg, direction):
+    """HBM bytes per launch of the look-back kernel from the committed rocprofv3 counter summary
+    (profiles/hbm_traffic_cfg<N>.json, written by paper_1709_04057_amd/traffic.py), or None."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{cfg}.json")
+    try:
+        with open(path) as f:
+            d = json.load(f)
+        return d["kernels"]["k_lookback/" + direction]["hbm_bytes"]
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def stream_probe(lr, torch, E, stream, iters=10):
+    """GB/s of the library's streaming kernels on E-element arrays (no recurrence, same access instructions)."""
+    bufs = [torch.randn(E, device="cuda:0") for _ in range(3)] + [torch.empty(E, device="cuda:0") for _ in range(2)]
+    a, b, c, o0, o1 = bufs
+    res = {}
+    for name, argv, nbytes in (("copy_1in_1out", (a, None, None, o0, None), 8), ("fwd_like_2in_1out", (a, b, None, o0, None), 12),
+                               ("bwd_like_3in_2out", (a, b, c, o0, o1), 20)):
+        for _ in range(2):
+            lr.linrec_stream_probe(*argv, stream=stream)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        ev[0].record(stream)
+        for i in range(iters):
+            lr.linrec_stream_probe(*argv, stream=stream)
+            ev[i + 1].record(stream)
+        torch.cuda.synchronize()
+        ms = sum(ev[i].elapsed_time(ev[i + 1]) for i in range(iters)) / iters
+        res[name] = {"avg_ms": ms, "GB/s": nbytes * E / (ms * 1e-3) / 1e9, "bytes_per_element": nbytes}
+    return res
 
 
 def main():
@@ -137,14 +172,16 @@ def main():
 
     vf, tf = lr.linrec_plan(T, B, n, backward=False) if not args.tile_fwd else (variant, args.tile_fwd)
     vb, tb = lr.linrec_plan(T, B, n, backward=True) if not args.tile_bwd else (variant, args.tile_bwd)
+    traffic = measured_traffic(args.config, "backward" if do_bwd else "forward")
     if do_bwd:
         roof = {"bound": "hbm", "kernel": "backward pass (look-back kernel)" if vb == lr.VARIANT_LOOKBACK else "backward pass",
                 "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
-                "traffic": None, "bytes_per_element": BWD_BYTES_PER_EL, "avg_ms": bwd_avg}
+                "traffic": traffic, "bytes_per_element": BWD_BYTES_PER_EL, "algorithmic_bytes": BWD_BYTES_PER_EL * E,
+                "avg_ms": bwd_avg}
     else:
         roof = {"bound": "hbm", "kernel": "forward pass", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": None, "bytes_per_element": FWD_BYTES_PER_EL,
-                "avg_ms": fwd_avg}
+                "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": traffic, "bytes_per_element": FWD_BYTES_PER_EL,
+                "algorithmic_bytes": FWD_BYTES_PER_EL * E, "avg_ms": fwd_avg}
 
     out = {
         "metric": "linrec fwd+bwd elements/sec and achieved HBM GB/s (% of MI355X peak)",
@@ -162,6 +199,8 @@ def main():
         "combined_GB/s": (FWD_BYTES_PER_EL + (BWD_BYTES_PER_EL if do_bwd else 0)) * E / (ms_per_step * 1e-3) / 1e9,
         "roofline": roof,
     }
+    if args.probe:
+        out["stream_probe"] = stream_probe(lr, torch, E, stream)
     if not args.no_cpu_baseline:
         threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
         out["cpu_baseline"] = cpu_baseline(inp, threads)

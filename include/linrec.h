@@ -71,8 +71,8 @@ enum {
     LINREC_OPT_SPIN_LIMIT = 4, /* look-back: polls before a wait is declared failed          */
     LINREC_OPT_HPREV_LATE = 5, /* look-back backward: load h after the rescan (1), together
                                   with lambda and grad_h (0), or let the library decide (-1)  */
-    LINREC_OPT_TAPER = 6       /* look-back: end the tile sequence with half- and quarter-height
-                                  tiles (1, default) or use full-height tiles throughout (0)  */
+    LINREC_OPT_TAPER = 6       /* look-back: cut this many eighths (0..8) of the last round of
+                                  tiles into half- and quarter-height tiles; 0 = none       */
 };
 
 /*

@@ -3,6 +3,7 @@
 #include "linrec.h"
 #include "linrec_launch.h"
 
+#include <stddef.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -47,7 +48,7 @@ struct Options {
     int64_t chunk_tiles = 0;
     int64_t spin_limit = 1 << 22;
     int64_t hp_late = -1;  // -1 automatic
-    int64_t taper = 1;
+    int64_t taper = 2;
     Options()
     {
         if (const char *v = getenv("LINREC_VARIANT")) {
@@ -79,11 +80,10 @@ int hip_fail(hipError_t e, const char *what)
 // One per (device, stream).  The look-back words live in their own allocation that nothing else
 // ever writes, because a stale word is told from a fresh one only by its epoch.
 struct Workspace {
-    // look-back: [ticket u64][err u32][pad to 256 B][3*K*C u64 words]
+    // look-back: [LookbackHeader, padded to 256 B][3*K*C u64 words]
     void *lb = nullptr;
     size_t lb_bytes = 0;
-    uint32_t epoch = 0;
-    unsigned long long tickets_issued = 0;
+    unsigned long long calls_since_clear = 0;
     // three-phase: aggP, aggS, carry, each K*C fp64
     void *tp = nullptr;
     size_t tp_bytes = 0;
@@ -233,8 +233,10 @@ int run(Args A, bool bwd, int vec, hipStream_t s)
     if (opts().taper && d.r % 4 == 0 && d.r >= 8) {
         const int64_t rows = d.rows();
         const int64_t full = A.T / rows;                                   // complete full-height tiles
-        const int64_t round = ceil_div((int64_t)resident_workgroups(dev), A.G);  // full tiles per chain in flight
-        const int64_t taper_tiles = std::min(full / 2, round);
+        // full tiles per chain that are in flight at once; opts().taper eighths of them are cut up
+        const int64_t resident = (int64_t)resident_workgroups(dev) * (d.threads() >= 512 ? 1 : 3) / 3;
+        const int64_t round = ceil_div(resident, A.G);
+        const int64_t taper_tiles = std::min(full / 2, (round * opts().taper + 7) / 8);
         if (taper_tiles > 0) {
             A.K1 = full - taper_tiles;
             const int64_t left = A.T - A.K1 * rows;                        // rows in the tapered region
@@ -247,23 +249,28 @@ int run(Args A, bool bwd, int vec, hipStream_t s)
     const size_t old_bytes = ws.lb_bytes;
     int rc = ensure(&ws.lb, &ws.lb_bytes, kLbHeader + 3 * kc * sizeof(unsigned long long), true, s);
     if (rc != LINREC_OK) return rc;
-    if (ws.lb_bytes != old_bytes) ws.tickets_issued = 0;  // fresh, zeroed buffer: its counter restarts
-    if (++ws.epoch >= 0x80000000u) {
-        // the 31-bit epoch wrapped: forget every stale word before reusing epoch values
-        if ((e = hipMemsetAsync((char *)ws.lb + kLbHeader, 0, ws.lb_bytes - kLbHeader, s)) != hipSuccess)
-            return hip_fail(e, "hipMemsetAsync(workspace)");
-        ws.epoch = 1;
+    // The 31-bit epoch wraps after 2^31 calls; long before that, forget every stale word so that a
+    // slot untouched for that long cannot be mistaken for a fresh one.
+    const bool fresh = ws.lb_bytes != old_bytes;
+    if (fresh || ++ws.calls_since_clear >= (1ull << 30)) {
+        if (!fresh && (e = launch_fill_zero((float *)((char *)ws.lb + kLbHeader),
+                                            (int64_t)((ws.lb_bytes - kLbHeader) / sizeof(float)), s)) != hipSuccess)
+            return hip_fail(e, "launch(fill_zero)");
+        if (fresh) {  // a zeroed buffer: start at epoch 1 (tag 0 is what untouched words carry)
+            LookbackHeader h0;
+            memset(&h0, 0, sizeof h0);
+            h0.epoch = 1;
+            if ((e = hipMemcpy(ws.lb, &h0, sizeof h0, hipMemcpyHostToDevice)) != hipSuccess)
+                return hip_fail(e, "hipMemcpy(workspace header)");
+        }
+        ws.calls_since_clear = 0;
     }
-    A.ticket = (unsigned long long *)ws.lb;
-    A.err = (uint32_t *)((char *)ws.lb + 8);
+    A.hdr = (LookbackHeader *)ws.lb;
     A.lbAgg = (unsigned long long *)((char *)ws.lb + kLbHeader);
-    A.ticket_base = ws.tickets_issued;
-    A.epoch = ws.epoch;
     A.spin_limit = (uint32_t)opts().spin_limit;
     A.trace = g_trace;
     if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
-    ws.tickets_issued += (unsigned long long)(A.K * A.G);
     return LINREC_OK;
 }
 
@@ -344,7 +351,7 @@ extern "C" int linrec_set_option(int option, int64_t value)
         opts().hp_late = value;
         return LINREC_OK;
     case LINREC_OPT_TAPER:
-        if (value < 0 || value > 1) return LINREC_ERR_OPTION;
+        if (value < 0 || value > 8) return LINREC_ERR_OPTION;
         opts().taper = value;
         return LINREC_OK;
     default: return LINREC_ERR_OPTION;
@@ -417,7 +424,7 @@ extern "C" int linrec_check(void *stream)
     auto it = g_ws.find(std::make_pair(dev, s));
     if (it == g_ws.end() || !it->second.lb) return LINREC_OK;
     uint32_t flag = 0;
-    char *p = (char *)it->second.lb + 8;
+    char *p = (char *)it->second.lb + offsetof(LookbackHeader, err);
     if ((e = hipMemcpy(&flag, p, sizeof flag, hipMemcpyDeviceToHost)) != hipSuccess) return hip_fail(e, "hipMemcpy");
     if (!flag) return LINREC_OK;
     if ((e = hipMemset(p, 0, sizeof flag)) != hipSuccess) return hip_fail(e, "hipMemset");

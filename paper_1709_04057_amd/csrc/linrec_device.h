@@ -551,10 +551,13 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     __shared__ ScanLds<G> lds;
     __shared__ dvec<VEC> sPt[WC];   // tile total, kept for the inclusive-state publication
     __shared__ vec<VEC> sSt[WC];
-    __shared__ uint32_t sTicket;
+    __shared__ uint32_t sTicket, sEpoch;
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
     // the host keeps K*G below 2^31, so a call's tickets fit 32 bits
-    if (tid == 0) sTicket = (uint32_t)(atomicAdd(A.ticket, 1ull) - A.ticket_base);
+    if (tid == 0) {
+        sTicket = (uint32_t)atomicAdd(&A.hdr->ticket, 1ull);
+        sEpoch = __hip_atomic_load(&A.hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     __syncthreads();
     const uint32_t ticket = __builtin_amdgcn_readfirstlane(sTicket);
     const int g = (int)(ticket % (uint32_t)A.G);
@@ -578,7 +581,8 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     }
     const int64_t u0 = tu0 + (int64_t)tt * rk;
     const bool interior = rk == R && tile_interior<G, BWD>(A, tu0, g);
-    const uint32_t tag_agg = A.epoch << 1, tag_incl = tag_agg | 1u;
+    const uint32_t epoch = __builtin_amdgcn_readfirstlane(sEpoch);
+    const uint32_t tag_agg = epoch << 1, tag_incl = tag_agg | 1u;
     LINREC_TRACE_MARK(0);
 
     Rows<G> r;
@@ -678,7 +682,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
                 else __builtin_amdgcn_s_sleep(2);
             }
             if (gave_up) {  // flag the error and finish with a zero state
-                atomicOr(A.err, 1u);
+                atomicOr(&A.hdr->err, 1u);
                 vP = dsplat<VEC>(0.0);
                 vS = splat<VEC>(0.0f);
             }
@@ -704,6 +708,18 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         const vec<VEC> incl = narrow<VEC>(dfma<VEC>(sPt[tc], widen<VEC>(Sr), widen<VEC>(sSt[tc])));
 #pragma unroll
         for (int v = 0; v < VEC; ++v) lb_store(my_words + 3 * v + 2, lb_pack(__float_as_uint(incl[v]), tag_incl));
+    }
+    // Every wavefront of this workgroup is past its last look-back read.  The workgroup that finds
+    // all others past theirs too rewinds the ticket and moves to the next epoch for the next call
+    // (which starts only after this kernel has ended).
+    if (tid == 0) {
+        const unsigned long long total = (unsigned long long)A.K * (unsigned long long)A.G;
+        if (atomicAdd(&A.hdr->done, 1ull) + 1ull == total) {
+            __hip_atomic_store(&A.hdr->done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&A.hdr->ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&A.hdr->epoch, epoch >= 0x7fffffffu ? 1u : epoch + 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 
     // ---- rescan from the carry and store -------------------------------------------------------

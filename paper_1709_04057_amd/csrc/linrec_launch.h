@@ -6,6 +6,16 @@
 
 namespace linrec {
 
+// Device-resident state of a look-back workspace.  The kernel itself hands out tickets, counts
+// finished workgroups, and its last workgroup rewinds the ticket and advances the epoch, so nothing
+// about a call is baked into the kernel arguments: a launch recorded in a HIP graph can be replayed.
+struct LookbackHeader {
+    unsigned long long ticket;  // next tile of the running call
+    unsigned long long done;    // workgroups of the running call that have finished their look-back
+    uint32_t epoch;             // 1 .. 2^31-1; tags are epoch<<1 (summary) and epoch<<1|1 (inclusive state)
+    uint32_t err;               // set when a look-back wait gave up
+};
+
 struct Args {
     const float *a;      // lambda                                  [T, C]
     const float *b;      // forward: x;  backward: grad_h            [T, C]
@@ -23,11 +33,8 @@ struct Args {
     double *aggP, *aggS, *carry;
     // look-back workspace: 64-bit words {tag : 32 | payload bits : 32}
     unsigned long long *lbAgg;   // [K, C, 3]  low and high half of the fp64 P; fp32 S, later the fp32 inclusive state
-    unsigned long long *ticket;  // monotonically increasing tile counter
-    unsigned long long ticket_base;
-    uint32_t epoch;              // 1 .. 2^31-1; tags are epoch<<1 (summary) and epoch<<1|1 (inclusive state)
+    struct LookbackHeader *hdr;  // device-resident call state (ticket, epoch, ...)
     uint32_t spin_limit;
-    uint32_t *err;
     unsigned long long *trace;  // only read by builds with -DLINREC_TRACE: 8 words per tile
 };
 

@@ -1,0 +1,87 @@
+"""Turns two rocprofv3 counter runs into HBM bytes per launch of the liblinrec kernels.
+
+    cd /tmp && export TMPDIR=/tmp
+    rocprofv3 --pmc FETCH_SIZE -d <out>/fetch -o fetch -- python3 bench.py --steps 10 --warmup 2 --no-cpu-baseline --probe
+    rocprofv3 --pmc WRITE_SIZE -d <out>/write -o write -- python3 bench.py --steps 10 --warmup 2 --no-cpu-baseline --probe
+    python -m paper_1709_04057_amd.traffic <out>/fetch/fetch_results.db <out>/write/write_results.db \\
+           --elements 67108864 --out profiles/hbm_traffic_cfg2
+
+Each counter is scaled by what it reads for the library's plain copy kernel (`bench.py --probe` runs
+it first: 4 bytes read and 4 bytes written per element, nothing else), so the unit the counter
+happens to use drops out.  Writes <out>.json (read by bench.py for roofline.traffic) and <out>.txt.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sqlite3
+
+
+def _per_kernel(db_path, counter):
+    cur = sqlite3.connect(db_path).cursor()
+    rows = cur.execute("select kernel_name, value, start from counters_collection where counter_name = ? order by start",
+                       (counter,)).fetchall()
+    out = {}
+    for name, value, _ in rows:
+        out.setdefault(name, []).append(float(value))
+    return out
+
+
+def _kind(name):
+    if "k_stream_probe" in name:
+        return "stream_probe"
+    if "k_lookback" in name or "k_fixup" in name or "k_reduce" in name or "k_scan_summaries" in name or "k_serial" in name:
+        bwd = ", true" in name.split("k_", 1)[1] or "k_serial_bwd" in name
+        base = name.split("linrec::", 1)[1].split("<", 1)[0].split("(", 1)[0]
+        return base + ("/backward" if bwd else "/forward")
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("fetch_db")
+    ap.add_argument("write_db")
+    ap.add_argument("--elements", type=int, required=True, help="T*B*n of the workload (also the probe's array length)")
+    ap.add_argument("--probe-launches", type=int, default=12, help="launches of each probe variant (warm-up + timed)")
+    ap.add_argument("--out", required=True)
+    a = ap.parse_args()
+
+    E = a.elements
+    res = {"elements": E, "kernels": {}}
+    lines = []
+    factors = {}
+    for counter, db in (("FETCH_SIZE", a.fetch_db), ("WRITE_SIZE", a.write_db)):
+        per = _per_kernel(db, counter)
+        probe = [v for k, vs in per.items() if _kind(k) == "stream_probe" for v in vs]
+        if len(probe) < a.probe_launches:
+            raise SystemExit(f"{counter}: no copy-probe launches found in {db} (run bench.py with --probe)")
+        copy = probe[:a.probe_launches]          # the copy variant is launched first
+        copy_avg = sum(copy) / len(copy)
+        factors[counter] = 4.0 * E / copy_avg    # bytes per counter unit
+        lines.append(f"{counter}: copy kernel reads {copy_avg:.1f} per launch for {4 * E} bytes -> {factors[counter]:.2f} bytes per unit")
+        for name, vs in per.items():
+            kind = _kind(name)
+            if kind is None or kind == "stream_probe":
+                continue
+            d = res["kernels"].setdefault(kind, {"name": name})
+            d[counter] = sum(vs) / len(vs)
+            d[counter + "_launches"] = len(vs)
+            d[("read" if counter == "FETCH_SIZE" else "written") + "_bytes"] = d[counter] * factors[counter]
+    res["bytes_per_unit"] = factors
+    for kind, d in sorted(res["kernels"].items()):
+        alg = (20.0 if kind.endswith("backward") else 12.0) * E
+        if "read_bytes" in d and "written_bytes" in d:
+            d["hbm_bytes"] = d["read_bytes"] + d["written_bytes"]
+            d["algorithmic_bytes"] = alg
+            lines.append(f"{kind}: read {d['read_bytes'] / 2**20:.1f} MiB + written {d['written_bytes'] / 2**20:.1f} MiB = "
+                         f"{d['hbm_bytes'] / 2**20:.1f} MiB per launch; algorithmic {alg / 2**20:.1f} MiB "
+                         f"(x{d['hbm_bytes'] / alg:.3f})   [{d['name']}]")
+    with open(a.out + ".json", "w") as f:
+        json.dump(res, f, indent=1)
+    with open(a.out + ".txt", "w") as f:
+        f.write(__doc__.split("Each counter")[0].strip() + "\n\n" + "\n".join(lines) + "\n")
+    print("\n".join(lines))
+
+
+if __name__ == "__main__":
+    main()

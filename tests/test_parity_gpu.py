@@ -277,3 +277,39 @@ def test_lookback_wait_limit_is_reported_and_recovered():
     lr.linrec_check()                                             # the flag was cleared
     with options(variant=lr.VARIANT_LOOKBACK):
         fwd_bwd_check(inp, "after spin-limit")
+
+
+def test_hip_graph_replay_matches_eager():
+    """The look-back kernels keep their call state (ticket, epoch) on the device, so a captured launch
+    can be replayed.  Replays are interleaved with eager calls and synchronisations, and every replay
+    is compared with the eager result."""
+    inp = wl.make_inputs(2, T=16384, B=2, n=128, device=DEV)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with options(variant=lr.VARIANT_LOOKBACK):
+        with torch.cuda.stream(s):
+            h = torch.empty_like(inp["x"])
+            gx, gl = torch.empty_like(h), torch.empty_like(h)
+            gh0 = torch.empty_like(inp["h0"])
+            for _ in range(2):                                    # allocates the stream's workspace: not capturable
+                lr.linrec_forward(inp["lam"], inp["x"], inp["h0"], h_out=h)
+                lr.linrec_backward(inp["lam"], h, inp["h0"], inp["grad_h"], grad_x=gx, grad_lambda=gl, grad_h0=gh0)
+            s.synchronize()
+            ref = [t.clone() for t in (h, gx, gl, gh0)]
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                lr.linrec_forward(inp["lam"], inp["x"], inp["h0"], h_out=h)
+                lr.linrec_backward(inp["lam"], h, inp["h0"], inp["grad_h"], grad_x=gx, grad_lambda=gl, grad_h0=gh0)
+            for rep in range(4):
+                say(f"graph replay {rep}")
+                for t in (h, gx, gl, gh0):
+                    t.fill_(float("nan"))
+                g.replay()
+                s.synchronize()
+                for got, want in zip((h, gx, gl, gh0), ref):
+                    assert torch.equal(got, want), f"replay {rep} differs from the eager result"
+                # eager work of the library on the same stream between replays
+                other = wl.make_generic(3000 + 500 * rep, 1, 96, 900 + rep, device=DEV)
+                fwd_bwd_check(other, f"eager between replays {rep}")
+            lr.linrec_check(s)
+    check_forward(inp, ref[0], "graph reference")
