@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     LinrecError,
     OPT_CHUNK_TILES,
     OPT_HPREV_LATE,
+    OPT_PERSISTENT,
     OPT_SPIN_LIMIT,
     OPT_TAPER,
     OPT_TILE,

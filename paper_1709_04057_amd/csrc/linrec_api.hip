@@ -49,6 +49,7 @@ struct Options {
     int64_t spin_limit = 1 << 22;
     int64_t hp_late = -1;  // -1 automatic
     int64_t taper = 2;
+    int64_t persistent = -1;  // -1 automatic: forward persistent, backward one workgroup per tile (measured)
     Options()
     {
         if (const char *v = getenv("LINREC_VARIANT")) {
@@ -91,7 +92,8 @@ struct Workspace {
 std::mutex g_mu;
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
 
-constexpr size_t kLbHeader = 256;
+constexpr size_t kLbHeader = 512;
+static_assert(sizeof(LookbackHeader) <= kLbHeader, "header must fit its slot");
 
 // Grows the buffer if needed.  Growing waits for the stream (older kernels may still use the old
 // buffer), which only happens while the problem sizes seen on a stream are still increasing.
@@ -268,6 +270,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s)
     A.hdr = (LookbackHeader *)ws.lb;
     A.lbAgg = (unsigned long long *)((char *)ws.lb + kLbHeader);
     A.spin_limit = (uint32_t)opts().spin_limit;
+    A.persistent = opts().persistent < 0 ? (bwd ? 0 : 1) : (int32_t)opts().persistent;
     A.trace = g_trace;
     if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
@@ -354,6 +357,10 @@ extern "C" int linrec_set_option(int option, int64_t value)
         if (value < 0 || value > 8) return LINREC_ERR_OPTION;
         opts().taper = value;
         return LINREC_OK;
+    case LINREC_OPT_PERSISTENT:
+        if (value < -1 || value > 1) return LINREC_ERR_OPTION;
+        opts().persistent = value;
+        return LINREC_OK;
     default: return LINREC_ERR_OPTION;
     }
 }
@@ -367,6 +374,7 @@ extern "C" int64_t linrec_get_option(int option)
     case LINREC_OPT_SPIN_LIMIT: return opts().spin_limit;
     case LINREC_OPT_HPREV_LATE: return opts().hp_late;
     case LINREC_OPT_TAPER: return opts().taper;
+    case LINREC_OPT_PERSISTENT: return opts().persistent;
     default: return LINREC_ERR_OPTION;
     }
 }

@@ -551,18 +551,27 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     __shared__ ScanLds<G> lds;
     __shared__ dvec<VEC> sPt[WC];   // tile total, kept for the inclusive-state publication
     __shared__ vec<VEC> sSt[WC];
-    __shared__ uint32_t sTicket, sEpoch;
+    __shared__ uint32_t sTicket[2], sEpoch;  // the ticket slot alternates from tile to tile
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
-    // the host keeps K*G below 2^31, so a call's tickets fit 32 bits
+    // Workgroups are persistent: each takes tickets until none is left (a workgroup works through its
+    // tickets in increasing order, so the owner of the lowest unfinished ticket is always free to run
+    // it: no deadlock).
+    // The host keeps K*G below 2^31, so a call's tickets fit 32 bits.
+    const uint32_t total = (uint32_t)A.K * (uint32_t)A.G;
     if (tid == 0) {
-        sTicket = (uint32_t)atomicAdd(&A.hdr->ticket, 1ull);
+        sTicket[0] = (uint32_t)atomicAdd(&A.hdr->ticket, 1ull);
         sEpoch = __hip_atomic_load(&A.hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    const uint32_t ticket = __builtin_amdgcn_readfirstlane(sTicket);
+    const uint32_t epoch = __builtin_amdgcn_readfirstlane(sEpoch);
+    const uint32_t tag_agg = epoch << 1, tag_incl = tag_agg | 1u;
+    uint32_t ticket = __builtin_amdgcn_readfirstlane(sTicket[0]);
+    int slot = 0;
+    unsigned long long finished = 0;  // thread 0: workgroups known to be past their last look-back read
+  while (ticket < total) {
+    slot ^= 1;
     const int g = (int)(ticket % (uint32_t)A.G);
     const int64_t k = (int64_t)(ticket / (uint32_t)A.G);
-    if (k >= A.K) return;  // cannot happen with a matching launch; keeps a mismatched one in bounds
     const int64_t col = ((int64_t)g * WC + tc) * VEC;
     const bool col_ok = col < A.C;
     // Tiles k < K1 are full height; then come K2 tiles of half height and, to the end, tiles of a
@@ -581,8 +590,6 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     }
     const int64_t u0 = tu0 + (int64_t)tt * rk;
     const bool interior = rk == R && tile_interior<G, BWD>(A, tu0, g);
-    const uint32_t epoch = __builtin_amdgcn_readfirstlane(sEpoch);
-    const uint32_t tag_agg = epoch << 1, tag_incl = tag_agg | 1u;
     LINREC_TRACE_MARK(0);
 
     Rows<G> r;
@@ -626,6 +633,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     }
     LINREC_TRACE_MARK(2);
     int n_windows = 0;
+    unsigned long long next_ticket = 0xffffffffull;
 
     // ---- look-back --------------------------------------------------------------------------
     // Window w covers predecessors k-1-w*WT down to k-(w+1)*WT; thread (tt, tc) reads the one that is
@@ -709,20 +717,16 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
 #pragma unroll
         for (int v = 0; v < VEC; ++v) lb_store(my_words + 3 * v + 2, lb_pack(__float_as_uint(incl[v]), tag_incl));
     }
-    // Every wavefront of this workgroup is past its last look-back read.  The workgroup that finds
-    // all others past theirs too rewinds the ticket and moves to the next epoch for the next call
-    // (which starts only after this kernel has ended).
-    if (tid == 0) {
-        const unsigned long long total = (unsigned long long)A.K * (unsigned long long)A.G;
-        if (atomicAdd(&A.hdr->done, 1ull) + 1ull == total) {
-            __hip_atomic_store(&A.hdr->done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&A.hdr->ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&A.hdr->epoch, epoch >= 0x7fffffffu ? 1u : epoch + 1u, __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-
     // ---- rescan from the carry and store -------------------------------------------------------
+    // The next ticket is requested here, so that the counter's latency hides behind the stores; taking
+    // it any earlier would hold a tile that other workgroups already wait for.
+    // (A workgroup that takes a single tile reports itself finished at this point instead: every
+    // look-back read of the tile is over, and waiting for the counter after the stores would hold the
+    // workgroup until they have all been acknowledged.)
+    if (tid == 0) {
+        if (A.persistent) next_ticket = atomicAdd(&A.hdr->ticket, 1ull);
+        else finished = atomicAdd(&A.hdr->done, 1ull) + 1ull;
+    }
     rescan<G>(r, vfma<VEC>(Pe32, Sr, Se32));
     if constexpr (BWD && HP_LATE) {
         // keep these loads behind the rescan: they take over the registers lambda occupied until now
@@ -731,6 +735,21 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     }
     tile_store<G, BWD>(A, ad, mk, col, interior, r, hp);
     LINREC_TRACE_MARK(4);
+    if (tid == 0) sTicket[slot] = (uint32_t)(next_ticket > 0xffffffffull ? 0xffffffffull : next_ticket);
+    __syncthreads();  // this tile's LDS state has been consumed
+    ticket = __builtin_amdgcn_readfirstlane(sTicket[slot]);
+  }
+    // Out of tickets.  The workgroup that finds every other one out of tickets too rewinds the counter
+    // and moves to the next epoch, for the next call (which starts only after this kernel has ended).
+    if (tid == 0) {
+        if (A.persistent) finished = atomicAdd(&A.hdr->done, 1ull) + 1ull;
+        if (finished == (unsigned long long)gridDim.x) {
+            __hip_atomic_store(&A.hdr->done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&A.hdr->ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&A.hdr->epoch, epoch >= 0x7fffffffu ? 1u : epoch + 1u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
 }
 
 }  // namespace linrec

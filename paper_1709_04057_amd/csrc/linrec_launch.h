@@ -9,11 +9,16 @@ namespace linrec {
 // Device-resident state of a look-back workspace.  The kernel itself hands out tickets, counts
 // finished workgroups, and its last workgroup rewinds the ticket and advances the epoch, so nothing
 // about a call is baked into the kernel arguments: a launch recorded in a HIP graph can be replayed.
+// The three words every workgroup touches sit in different 128-byte lines: atomics on one address are
+// served one at a time, and a read of the epoch must not queue behind the ticket traffic.
 struct LookbackHeader {
     unsigned long long ticket;  // next tile of the running call
+    unsigned long long pad0[15];
     unsigned long long done;    // workgroups of the running call that have finished their look-back
+    unsigned long long pad1[15];
     uint32_t epoch;             // 1 .. 2^31-1; tags are epoch<<1 (summary) and epoch<<1|1 (inclusive state)
     uint32_t err;               // set when a look-back wait gave up
+    unsigned long long pad2[15];
 };
 
 struct Args {
@@ -35,6 +40,7 @@ struct Args {
     unsigned long long *lbAgg;   // [K, C, 3]  low and high half of the fp64 P; fp32 S, later the fp32 inclusive state
     struct LookbackHeader *hdr;  // device-resident call state (ticket, epoch, ...)
     uint32_t spin_limit;
+    int32_t persistent;          // look-back: workgroups loop over tickets (1) or take exactly one (0)
     unsigned long long *trace;  // only read by builds with -DLINREC_TRACE: 8 words per tile
 };
 

@@ -2,11 +2,32 @@
 // -DLINREC_TILE_ID=<id> so that the shapes build in parallel.
 #include "linrec_device.h"
 
+#include <algorithm>
+#include <map>
+#include <mutex>
+#include <utility>
+
 #ifndef LINREC_TILE_ID
 #error "compile with -DLINREC_TILE_ID=<id>"
 #endif
 
 namespace linrec {
+
+// Workgroups of `kernel` that fit the current device at once (compute units x blocks per unit).
+static int64_t resident_capacity(const void *kernel, int threads)
+{
+    static std::mutex mu;
+    static std::map<std::pair<int, const void *>, int64_t> cache;
+    int dev = 0;
+    (void)hipGetDevice(&dev);
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find({dev, kernel});
+    if (it != cache.end()) return it->second;
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) per_cu = 1;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+    return cache[{dev, kernel}] = (int64_t)per_cu * cus;
+}
 
 template <class G>
 static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, const Args &A, hipStream_t s)
@@ -21,11 +42,15 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, const Args &A, h
         if (bwd) hipLaunchKernelGGL((k_fixup<G, true>), grid, block, 0, s, A);
         else hipLaunchKernelGGL((k_fixup<G, false>), grid, block, 0, s, A);
         break;
-    case KIND_LOOKBACK:
-        if (!bwd) hipLaunchKernelGGL((k_lookback<G, false, false>), grid, block, 0, s, A);
-        else if (hp_late) hipLaunchKernelGGL((k_lookback<G, true, true>), grid, block, 0, s, A);
-        else hipLaunchKernelGGL((k_lookback<G, true, false>), grid, block, 0, s, A);
+    case KIND_LOOKBACK: {
+        // persistent workgroups: as many as the device holds at once, never more than there are tiles
+        void (*kern)(const Args) = !bwd ? k_lookback<G, false, false>
+                                        : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
+        const int64_t cap = resident_capacity(reinterpret_cast<const void *>(kern), G::THREADS);
+        const dim3 pgrid((unsigned)(A.persistent ? std::min<int64_t>(A.K * A.G, cap) : A.K * A.G));
+        hipLaunchKernelGGL(kern, pgrid, block, 0, s, A);
         break;
+    }
     }
     return hipGetLastError();
 }
