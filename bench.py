@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--tile-fwd", type=int, default=0)
     ap.add_argument("--tile-bwd", type=int, default=0)
     ap.add_argument("--hprev-late", type=int, default=-1)
+    ap.add_argument("--no-tune", action="store_true", help="skip linrec_tune(); use the library's static plan")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0)
     ap.add_argument("--probe", action="store_true",
@@ -143,6 +144,11 @@ def main():
         lr.linrec_set_option(lr.OPT_TILE, args.tile_bwd)
         lr.linrec_backward(lam, h, h0, e, grad_x=gx, grad_lambda=gl, grad_h0=gh0, stream=stream)
 
+    if not args.no_tune and args.variant in ("auto", "lookback"):
+        if not args.tile_fwd:
+            lr.linrec_tune(T, B, n, backward=False, stream=stream)
+        if do_bwd and not args.tile_bwd:
+            lr.linrec_tune(T, B, n, backward=True, stream=stream)
     for _ in range(args.warmup):
         fwd()
         if do_bwd:

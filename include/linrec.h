@@ -126,6 +126,16 @@ int linrec_tile_info(int tile_id, int *threads_cols, int *threads_time, int *row
 int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int alignment_bytes,
                 int *variant, int *tile_id);
 
+/*
+ * Optional: finds the fastest plan (tile shape, persistent workgroups or not) of the single-pass
+ * kernel for a [T, B, n] forward (backward = 0) or backward (1) pass by timing the candidates on
+ * `stream`, on scratch tensors it allocates and frees, and remembers it for later calls with this
+ * shape on the current device (when LINREC_OPT_TILE / LINREC_OPT_PERSISTENT are automatic).
+ * Blocking; allocates 3 (forward) or 5 (backward) tensors of T*B*n floats.  Returns LINREC_OK,
+ * LINREC_ERR_SHAPE or LINREC_ERR_HIP.  Must not run concurrently with other liblinrec calls.
+ */
+int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *stream);
+
 /* Host-side argument checks only (exactly the checks linrec_forward / linrec_backward run
  * before touching the GPU); no HIP call is made, so these work on a machine without a GPU. */
 int linrec_validate_forward(const float *lambda, const float *x, const float *h0,

@@ -31,5 +31,6 @@ from .binding import (  # noqa: F401
     linrec_status_string,
     linrec_stream_probe,
     linrec_tile_info,
+    linrec_tune,
     linrec_version,
 )

@@ -56,6 +56,8 @@ def lib():
         L.linrec_plan.restype = ci
         L.linrec_stream_probe.argtypes = [p, p, p, p, p, i64, p]
         L.linrec_stream_probe.restype = ci
+        L.linrec_tune.argtypes = [i64, i64, i64, ci, p]
+        L.linrec_tune.restype = ci
         L.linrec_check.argtypes = [p]
         L.linrec_check.restype = ci
         L.linrec_release_workspace.argtypes = []
@@ -191,6 +193,11 @@ def linrec_stream_probe(in0, in1, in2, out0, out1, stream=None) -> None:
     """Pure streaming kernel over flat float32 CUDA tensors (None = absent); see include/linrec.h."""
     n = (out0 if out0 is not None else out1).numel()
     _check(lib().linrec_stream_probe(_ptr(in0), _ptr(in1), _ptr(in2), _ptr(out0), _ptr(out1), n, _stream_ptr(stream)))
+
+
+def linrec_tune(T, B, n, backward=False, stream=None) -> None:
+    """Times the candidate plans for this shape on the GPU and remembers the fastest (see include/linrec.h)."""
+    _check(lib().linrec_tune(int(T), int(B), int(n), int(bool(backward)), _stream_ptr(stream)))
 
 
 def linrec_check(stream=None) -> None:

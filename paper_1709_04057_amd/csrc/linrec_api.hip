@@ -165,7 +165,27 @@ int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
 struct Plan {
     int variant, tile;
     bool hp_late;
+    int persistent;  // -1: not decided by the plan
 };
+
+// Plans found by linrec_tune, keyed by (device, T, C, pass).  Guarded by g_tuned_mu.
+struct TunedKey {
+    int dev;
+    int64_t T, C;
+    bool bwd;
+    bool operator<(const TunedKey &o) const
+    {
+        if (dev != o.dev) return dev < o.dev;
+        if (T != o.T) return T < o.T;
+        if (C != o.C) return C < o.C;
+        return bwd < o.bwd;
+    }
+};
+struct TunedPlan {
+    int tile, persistent;
+};
+std::mutex g_tuned_mu;
+std::map<TunedKey, TunedPlan> g_tuned;
 
 // Picks variant and tile, honouring the options where they apply to this problem.
 Plan make_plan(int64_t T, int64_t C, int vec, bool bwd)
@@ -174,6 +194,18 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd)
     p.variant = (int)opts().variant;
     if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
     p.tile = (int)opts().tile;
+    p.persistent = (int)opts().persistent;
+    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK) {  // a tuned plan, if there is one for this shape
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess) {
+            std::lock_guard<std::mutex> lock(g_tuned_mu);
+            auto it = g_tuned.find(TunedKey{dev, T, C, bwd});
+            if (it != g_tuned.end()) {
+                p.tile = it->second.tile;
+                if (p.persistent < 0) p.persistent = it->second.persistent;
+            }
+        }
+    }
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
     if (p.tile < 1 || p.tile > NUM_TILES) p.tile = auto_tile(T, C, vec, bwd, p.variant);
     const TileDesc &d = kTiles[p.tile - 1];
@@ -255,9 +287,9 @@ int run(Args A, bool bwd, int vec, hipStream_t s)
     // slot untouched for that long cannot be mistaken for a fresh one.
     const bool fresh = ws.lb_bytes != old_bytes;
     if (fresh || ++ws.calls_since_clear >= (1ull << 30)) {
-        if (!fresh && (e = launch_fill_zero((float *)((char *)ws.lb + kLbHeader),
-                                            (int64_t)((ws.lb_bytes - kLbHeader) / sizeof(float)), s)) != hipSuccess)
-            return hip_fail(e, "launch(fill_zero)");
+        if (!fresh && (e = launch_fill((float *)((char *)ws.lb + kLbHeader), 0.0f,
+                                       (int64_t)((ws.lb_bytes - kLbHeader) / sizeof(float)), s)) != hipSuccess)
+            return hip_fail(e, "launch(fill)");
         if (fresh) {  // a zeroed buffer: start at epoch 1 (tag 0 is what untouched words carry)
             LookbackHeader h0;
             memset(&h0, 0, sizeof h0);
@@ -270,7 +302,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s)
     A.hdr = (LookbackHeader *)ws.lb;
     A.lbAgg = (unsigned long long *)((char *)ws.lb + kLbHeader);
     A.spin_limit = (uint32_t)opts().spin_limit;
-    A.persistent = opts().persistent < 0 ? (bwd ? 0 : 1) : (int32_t)opts().persistent;
+    A.persistent = plan.persistent < 0 ? (bwd ? 0 : 1) : plan.persistent;
     A.trace = g_trace;
     if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
@@ -310,8 +342,8 @@ extern "C" int linrec_backward(const float *lambda, const float *h, const float 
     hipStream_t s = (hipStream_t)stream;
     if (T == 0) {
         if (grad_h0) {
-            const hipError_t e = launch_fill_zero(grad_h0, C, s);
-            if (e != hipSuccess) return hip_fail(e, "launch(fill_zero)");
+            const hipError_t e = launch_fill(grad_h0, 0.0f, C, s);
+            if (e != hipSuccess) return hip_fail(e, "launch(fill)");
         }
         return LINREC_OK;
     }
@@ -414,6 +446,90 @@ extern "C" int linrec_stream_probe(const float *in0, const float *in1, const flo
     if (n == 0) return LINREC_OK;
     const hipError_t e = launch_stream_probe(in0, in1, in2, out0, out1, n, (hipStream_t)stream);
     return e == hipSuccess ? LINREC_OK : hip_fail(e, "launch(stream_probe)");
+}
+
+// Times the look-back kernel under every candidate plan on scratch tensors of the given shape and
+// remembers the fastest for later calls with that shape on this device.
+extern "C" int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *stream)
+{
+    if (T <= 0 || B <= 0 || n <= 0 || B > ((int64_t)1 << 40) / n || T > ((int64_t)1 << 40) / (B * n))
+        return LINREC_ERR_SHAPE;
+    const int64_t C = B * n, E = T * C;
+    hipStream_t s = (hipStream_t)stream;
+    const bool bwd = backward != 0;
+    int dev = 0;
+    hipError_t e;
+    if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e, "hipGetDevice");
+
+    // scratch: lambda = 0.96875 (products neither overflow nor vanish within a tile), the rest 1 / 0
+    float *big[5] = {nullptr, nullptr, nullptr, nullptr, nullptr}, *small_[2] = {nullptr, nullptr};
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    int rc = LINREC_OK;
+    const int n_big = bwd ? 5 : 3;
+    for (int i = 0; i < n_big && rc == LINREC_OK; ++i)
+        if ((e = hipMalloc((void **)&big[i], (size_t)E * sizeof(float))) != hipSuccess) rc = hip_fail(e, "hipMalloc(tune)");
+    for (int i = 0; i < 2 && rc == LINREC_OK; ++i)
+        if ((e = hipMalloc((void **)&small_[i], (size_t)C * sizeof(float))) != hipSuccess) rc = hip_fail(e, "hipMalloc(tune)");
+    if (rc == LINREC_OK && ((e = hipEventCreate(&ev0)) != hipSuccess || (e = hipEventCreate(&ev1)) != hipSuccess))
+        rc = hip_fail(e, "hipEventCreate");
+    if (rc == LINREC_OK) {
+        e = launch_fill(big[0], 0.96875f, E, s);
+        for (int i = 1; i < n_big && e == hipSuccess; ++i) e = launch_fill(big[i], 1.0f, E, s);
+        for (int i = 0; i < 2 && e == hipSuccess; ++i) e = launch_fill(small_[i], 0.0f, C, s);
+        if (e != hipSuccess) rc = hip_fail(e, "launch(fill)");
+    }
+
+    TunedPlan best{0, -1};
+    float best_ms = 0.f;
+    if (rc == LINREC_OK) {
+        const int vec = max_vec(C, {});
+        const Options saved = opts();
+        opts().variant = LINREC_VARIANT_LOOKBACK;
+        static const int candidates[] = {17, 18, 19, 20, 21, 22, 11, 12, 14};
+        for (int tile : candidates) {
+            const TileDesc &d = kTiles[tile - 1];
+            if (d.vec > vec) continue;
+            if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
+            if (d.rows() > 2 * T && tile != 18) continue;  // far taller than the problem
+            for (int persistent = 0; persistent <= 1 && rc == LINREC_OK; ++persistent) {
+                opts().tile = tile;
+                opts().persistent = persistent;
+                float times[5];
+                for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {  // two warm-up launches, five timed
+                    if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
+                    rc = bwd ? linrec_backward(big[0], big[1], small_[0], big[2], big[3], big[4], small_[1], T, B, n, s)
+                             : linrec_forward(big[0], big[1], small_[0], big[2], T, B, n, s);
+                    if (rc != LINREC_OK) break;
+                    float ms = 0.f;
+                    if ((e = hipEventRecord(ev1, s)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
+                        (e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess) {
+                        rc = hip_fail(e, "tune: timing");
+                        break;
+                    }
+                    if (it >= 0) times[it] = ms;
+                }
+                if (rc != LINREC_OK) break;
+                std::sort(times, times + 5);
+                if (best.tile == 0 || times[2] < best_ms) {
+                    best_ms = times[2];
+                    best = TunedPlan{tile, persistent};
+                }
+            }
+        }
+        opts() = saved;
+    }
+    if (ev0) (void)hipEventDestroy(ev0);
+    if (ev1) (void)hipEventDestroy(ev1);
+    (void)hipStreamSynchronize(s);
+    for (float *p : big)
+        if (p) (void)hipFree(p);
+    for (float *p : small_)
+        if (p) (void)hipFree(p);
+    if (rc == LINREC_OK && best.tile != 0) {
+        std::lock_guard<std::mutex> lock(g_tuned_mu);
+        g_tuned[TunedKey{dev, T, C, bwd}] = best;
+    }
+    return rc;
 }
 
 #ifdef LINREC_TRACE

@@ -91,7 +91,7 @@ hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, const A
 hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const float *h0, double *carry, int64_t K,
                                  int64_t C, hipStream_t s);
 hipError_t launch_serial(const Args &A, bool bwd, hipStream_t s);
-hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s);
+hipError_t launch_fill(float *p, float value, int64_t n, hipStream_t s);
 hipError_t launch_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
                                int64_t n, hipStream_t s);
 

@@ -5,6 +5,8 @@
 //                       length, parallel over features and minibatch.
 #include "linrec_device.h"
 
+#include <algorithm>
+
 namespace linrec {
 
 // DPP helpers: a lane takes `src` from another lane of the wavefront, or keeps `old` when the
@@ -129,10 +131,10 @@ __global__ __launch_bounds__(256) void k_serial_bwd(const float *__restrict__ la
     if (gh0) gh0[c] = lam[c] * g;
 }
 
-__global__ void k_fill_zero(float *p, int64_t n)
+__global__ void k_fill(float *p, float value, int64_t n)
 {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0.0f;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = value;
 }
 
 // Streaming probe: the bandwidth a kernel with this library's access instructions reaches when it
@@ -193,10 +195,11 @@ hipError_t launch_serial(const Args &A, bool bwd, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_fill_zero(float *p, int64_t n, hipStream_t s)
+hipError_t launch_fill(float *p, float value, int64_t n, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
+    const int64_t blocks = std::min<int64_t>((n + 255) / 256, 65536);
+    hipLaunchKernelGGL(k_fill, dim3((unsigned)blocks), dim3(256), 0, s, p, value, n);
     return hipGetLastError();
 }
 

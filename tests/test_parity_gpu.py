@@ -313,3 +313,20 @@ def test_hip_graph_replay_matches_eager():
                 fwd_bwd_check(other, f"eager between replays {rep}")
             lr.linrec_check(s)
     check_forward(inp, ref[0], "graph reference")
+
+
+def test_tuned_plan_is_used_and_correct():
+    """linrec_tune() times the candidate plans on scratch tensors and later calls with that shape use
+    the winner; results must stay correct whatever it picked."""
+    T, B, n = 20000, 2, 96
+    inp = wl.make_inputs(2, T=T, B=B, n=n, device=DEV)
+    lr.linrec_tune(T, B, n, backward=False)
+    lr.linrec_tune(T, B, n, backward=True)
+    vf, tf = lr.linrec_plan(T, B, n, backward=False)
+    vb, tb = lr.linrec_plan(T, B, n, backward=True)
+    say(f"tuned plan: forward tile {tf}, backward tile {tb}")
+    assert vf == lr.VARIANT_LOOKBACK and vb == lr.VARIANT_LOOKBACK
+    assert lr.linrec_tile_info(tf) is not None and lr.linrec_tile_info(tb) is not None
+    fwd_bwd_check(inp, "tuned plan")
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_tune(0, 2, 3)
