@@ -39,6 +39,10 @@ def parse():
     ap.add_argument("--no-tune", action="store_true", help="skip linrec_tune(); use the library's static plan")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0)
+    ap.add_argument("--table1", action="store_true",
+                    help="instead of the workload benchmark, time the parallel (single-pass) kernel against the "
+                         "serial-over-T kernel on the grid of the paper's Table 1 (minibatch 1; 4, 32, 128 features; "
+                         "T = 16 ... 65536) and print the speed-up ratios as one JSON line")
     ap.add_argument("--probe", action="store_true",
                     help="also time the library's pure streaming kernels (copy, 2-in/1-out, 3-in/2-out) on arrays "
                          "of the workload's size; the copy doubles as the calibration kernel for byte counters")
@@ -103,6 +107,39 @@ def stream_probe(lr, torch, E, stream, iters=10):
     return res
 
 
+def table1(lr, torch):
+    """Parallel / serial kernel throughput ratio on the paper's Table-1 grid (forward pass, b = 1)."""
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    grid = {}
+    for T in (16, 256, 4096, 65536):
+        for m in (4, 32, 128):
+            g = torch.Generator(device=dev)
+            g.manual_seed(1709 + T + m)
+            lam = torch.sigmoid(torch.randn((T, 1, m), device=dev, generator=g))
+            x = torch.randn((T, 1, m), device=dev, generator=g)
+            h = torch.empty_like(x)
+            times = {}
+            for name, variant in (("parallel", lr.VARIANT_LOOKBACK), ("serial", lr.VARIANT_SERIAL)):
+                lr.linrec_set_option(lr.OPT_VARIANT, variant)
+                iters = 200 if T <= 4096 else 30
+                for _ in range(5):
+                    lr.linrec_forward(lam, x, None, h_out=h, stream=stream)
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(stream)
+                for _ in range(iters):
+                    lr.linrec_forward(lam, x, None, h_out=h, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                times[name] = e0.elapsed_time(e1) / iters * 1e3   # microseconds per launch, back to back
+            grid[f"T={T},m={m}"] = {"parallel_us": times["parallel"], "serial_us": times["serial"],
+                                    "speedup": times["serial"] / times["parallel"],
+                                    "parallel_events_per_s": T / (times["parallel"] * 1e-6)}
+    lr.linrec_set_option(lr.OPT_VARIANT, lr.VARIANT_AUTO)
+    return grid
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -123,6 +160,16 @@ def main():
                "serial": lr.VARIANT_SERIAL}[args.variant]
     lr.linrec_set_option(lr.OPT_VARIANT, variant)
     lr.linrec_set_option(lr.OPT_HPREV_LATE, args.hprev_late)
+
+    if args.table1:
+        print(json.dumps({"metric": "parallel / serial linear-recurrence kernel throughput ratio (paper's Table 1 grid, "
+                                    "minibatch 1, forward pass, launches back to back)",
+                          "paper_values_for_context": {"hardware": "NVIDIA GPU of 2017 (K80 named for 'all experiments')",
+                                                       "T=16": [0.06, 0.06, 0.05], "T=256": [0.22, 0.22, 0.86],
+                                                       "T=4096": [1.02, 2.94, 3.36], "T=65536": [38.5, 41.8, 17.5],
+                                                       "columns": "m = 4, 32, 128"},
+                          "table1": table1(lr, torch)}), flush=True)
+        return
 
     inp = wl.make_inputs(args.config, device=dev)
     T, B, n = inp["T"], inp["B"], inp["n"]

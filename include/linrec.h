@@ -73,9 +73,11 @@ enum {
                                   with lambda and grad_h (0), or let the library decide (-1)  */
     LINREC_OPT_TAPER = 6,      /* look-back: cut this many eighths (0..8) of the last round of
                                   tiles into half- and quarter-height tiles; 0 = none       */
-    LINREC_OPT_PERSISTENT = 7  /* look-back: launch as many workgroups as the GPU holds and let
+    LINREC_OPT_PERSISTENT = 7, /* look-back: launch as many workgroups as the GPU holds and let
                                   each loop over tiles (1), one workgroup per tile (0), or
                                   let the library decide per pass (-1, default)              */
+    LINREC_OPT_GRID_CAP = 8    /* look-back, persistent: at most this many workgroups per
+                                  compute unit; 0 (default) = as many as fit                 */
 };
 
 /*

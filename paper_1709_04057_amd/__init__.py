@@ -8,6 +8,7 @@ PyTorch is used for device memory and streams only.
 from .binding import (  # noqa: F401
     LinrecError,
     OPT_CHUNK_TILES,
+    OPT_GRID_CAP,
     OPT_HPREV_LATE,
     OPT_PERSISTENT,
     OPT_SPIN_LIMIT,

@@ -11,7 +11,7 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "linrec.h")
 _lib = None
 
 VARIANT_AUTO, VARIANT_THREEPHASE, VARIANT_LOOKBACK, VARIANT_SERIAL = 0, 1, 2, 3
-OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE, OPT_TAPER, OPT_PERSISTENT = 1, 2, 3, 4, 5, 6, 7
+OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE, OPT_TAPER, OPT_PERSISTENT, OPT_GRID_CAP = 1, 2, 3, 4, 5, 6, 7, 8
 
 
 class LinrecError(RuntimeError):

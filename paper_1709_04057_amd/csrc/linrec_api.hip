@@ -49,6 +49,7 @@ struct Options {
     int64_t spin_limit = 1 << 22;
     int64_t hp_late = -1;  // -1 automatic
     int64_t taper = 2;
+    int64_t grid_cap = 0;
     int64_t persistent = -1;  // -1 automatic: forward persistent, backward one workgroup per tile (measured)
     Options()
     {
@@ -303,6 +304,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s)
     A.lbAgg = (unsigned long long *)((char *)ws.lb + kLbHeader);
     A.spin_limit = (uint32_t)opts().spin_limit;
     A.persistent = plan.persistent < 0 ? (bwd ? 0 : 1) : plan.persistent;
+    A.grid_cap = (int32_t)opts().grid_cap;
     A.trace = g_trace;
     if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
@@ -393,6 +395,10 @@ extern "C" int linrec_set_option(int option, int64_t value)
         if (value < -1 || value > 1) return LINREC_ERR_OPTION;
         opts().persistent = value;
         return LINREC_OK;
+    case LINREC_OPT_GRID_CAP:
+        if (value < 0 || value > 64) return LINREC_ERR_OPTION;
+        opts().grid_cap = value;
+        return LINREC_OK;
     default: return LINREC_ERR_OPTION;
     }
 }
@@ -407,6 +413,7 @@ extern "C" int64_t linrec_get_option(int option)
     case LINREC_OPT_HPREV_LATE: return opts().hp_late;
     case LINREC_OPT_TAPER: return opts().taper;
     case LINREC_OPT_PERSISTENT: return opts().persistent;
+    case LINREC_OPT_GRID_CAP: return opts().grid_cap;
     default: return LINREC_ERR_OPTION;
     }
 }

@@ -41,6 +41,7 @@ struct Args {
     struct LookbackHeader *hdr;  // device-resident call state (ticket, epoch, ...)
     uint32_t spin_limit;
     int32_t persistent;          // look-back: workgroups loop over tickets (1) or take exactly one (0)
+    int32_t grid_cap;            // look-back, persistent: at most this many workgroups per compute unit (0: no cap)
     unsigned long long *trace;  // only read by builds with -DLINREC_TRACE: 8 words per tile
 };
 

@@ -14,19 +14,24 @@
 namespace linrec {
 
 // Workgroups of `kernel` that fit the current device at once (compute units x blocks per unit).
-static int64_t resident_capacity(const void *kernel, int threads)
+static int64_t resident_capacity(const void *kernel, int threads, int cap_per_cu)
 {
     static std::mutex mu;
     static std::map<std::pair<int, const void *>, int64_t> cache;
     int dev = 0;
     (void)hipGetDevice(&dev);
     std::lock_guard<std::mutex> lock(mu);
+    static std::map<int, int> cu_count;
     auto it = cache.find({dev, kernel});
-    if (it != cache.end()) return it->second;
-    int per_cu = 0, cus = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) per_cu = 1;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
-    return cache[{dev, kernel}] = (int64_t)per_cu * cus;
+    if (it == cache.end()) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, threads, 0) != hipSuccess || per_cu < 1) per_cu = 1;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        cu_count[dev] = cus;
+        it = cache.emplace(std::make_pair(dev, kernel), (int64_t)per_cu).first;
+    }
+    const int64_t per_cu = (cap_per_cu > 0 && cap_per_cu < it->second) ? cap_per_cu : it->second;
+    return per_cu * cu_count[dev];
 }
 
 template <class G>
@@ -46,7 +51,7 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, const Args &A, h
         // persistent workgroups: as many as the device holds at once, never more than there are tiles
         void (*kern)(const Args) = !bwd ? k_lookback<G, false, false>
                                         : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
-        const int64_t cap = resident_capacity(reinterpret_cast<const void *>(kern), G::THREADS);
+        const int64_t cap = resident_capacity(reinterpret_cast<const void *>(kern), G::THREADS, A.grid_cap);
         const dim3 pgrid((unsigned)(A.persistent ? std::min<int64_t>(A.K * A.G, cap) : A.K * A.G));
         hipLaunchKernelGGL(kern, pgrid, block, 0, s, A);
         break;
