@@ -123,8 +123,8 @@ int linrec_tile_info(int tile_id, int *threads_cols, int *threads_time, int *row
                      int *cols_per_thread);
 
 /* Reports the variant and tile shape the library would use for a [T, B, n] problem under the
- * current options when every tensor pointer is aligned to `alignment_bytes` (4, 8 or 16).
- * Host-only; makes no HIP call. */
+ * current options (and the plans linrec_tune found for the current device) when every tensor
+ * pointer is aligned to `alignment_bytes` (4, 8 or 16).  Launches nothing. */
 int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int alignment_bytes,
                 int *variant, int *tile_id);
 
