@@ -365,16 +365,25 @@ struct ScanLds {
     static constexpr int NW = G::THREADS / 64;
     dvec<G::VEC> wP[NW][G::WC];
     vec<G::VEC> wS[NW][G::WC];
+    int wClosed[NW][G::WC];
 };
 
-template <class G>
+// With CLOSED = true every element also carries a flag "closed": the element is a complete state, not
+// a map (a published inclusive state in the look-back).  Composition then keeps the LATEST closed
+// element and what follows it and drops everything earlier without touching it -- in particular a
+// NaN or Inf that sits before a closed element cannot leak into the result, and a zero product is
+// not mistaken for the end of the dependence (0 * NaN stays NaN, as in the sequential recurrence).
+// `closed` is in/out: in, the thread's own element; out, whether the tile total is closed.
+template <class G, bool CLOSED = false>
 __device__ __forceinline__ void tile_scan(ScanLds<G> &lds, int tid, dvec<G::VEC> P, vec<G::VEC> S, dvec<G::VEC> &Pe,
-                                          vec<G::VEC> &Se, dvec<G::VEC> &Pt, vec<G::VEC> &St)
+                                          vec<G::VEC> &Se, dvec<G::VEC> &Pt, vec<G::VEC> &St, bool *closed = nullptr)
 {
     constexpr int VEC = G::VEC, WC = G::WC;
     constexpr int TPW = (64 / WC) < G::WT ? (64 / WC) : G::WT;  // time-threads per wavefront
     constexpr int NW = ScanLds<G>::NW;
     const int lane = tid & 63, wave = tid >> 6, tc = tid % WC, ttl = lane / WC;
+    int cl = 0;
+    if constexpr (CLOSED) cl = *closed ? 1 : 0;
 
     // level 1: inclusive scan over ttl inside the wavefront
 #pragma unroll
@@ -382,19 +391,24 @@ __device__ __forceinline__ void tile_scan(ScanLds<G> &lds, int tid, dvec<G::VEC>
         const int src = lane - d * WC;
         const dvec<VEC> ps = lane_move<VEC>(P, src < 0 ? lane : src);
         const vec<VEC> ss = lane_move<VEC>(S, src < 0 ? lane : src);
-        if (ttl >= d) {  // (ps, ss) is earlier in time: it goes on the left
+        int cs = 0;
+        if constexpr (CLOSED) cs = __builtin_amdgcn_ds_bpermute((src < 0 ? lane : src) << 2, cl);
+        if (ttl >= d && !cl) {  // (ps, ss) is earlier in time: it goes on the left
             S = narrow<VEC>(dfma<VEC>(P, widen<VEC>(ss), widen<VEC>(S)));
             P = ps * P;
+            cl = cs;
         }
     }
     if (ttl == TPW - 1) {
         lds.wP[wave][tc] = P;
         lds.wS[wave][tc] = S;
+        if constexpr (CLOSED) lds.wClosed[wave][tc] = cl;
     }
     // exclusive prefix inside the wavefront = inclusive value of the previous time-thread
+    // (not needed, and not meaningful, for the flagged form: its callers use the total only)
     dvec<VEC> Px = dsplat<VEC>(1.0);
     vec<VEC> Sx = splat<VEC>(0.0f);
-    if constexpr (TPW > 1) {
+    if constexpr (TPW > 1 && !CLOSED) {
         const int src = lane - WC;
         const dvec<VEC> ps = lane_move<VEC>(P, src < 0 ? lane : src);
         const vec<VEC> ss = lane_move<VEC>(S, src < 0 ? lane : src);
@@ -405,20 +419,29 @@ __device__ __forceinline__ void tile_scan(ScanLds<G> &lds, int tid, dvec<G::VEC>
     // wavefront is what came before it
     dvec<VEC> pt = dsplat<VEC>(1.0);
     vec<VEC> st_ = splat<VEC>(0.0f);
+    int ct = 0;
     Pe = Px;
     Se = Sx;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-        if (w == wave) {  // (waves before) (+) (in-wave prefix)
+        if (!CLOSED && w == wave) {  // (waves before) (+) (in-wave prefix)
             Se = narrow<VEC>(dfma<VEC>(Px, widen<VEC>(st_), widen<VEC>(Sx)));
             Pe = pt * Px;
         }
         const dvec<VEC> p = lds.wP[w][tc];
-        st_ = narrow<VEC>(dfma<VEC>(p, widen<VEC>(st_), widen<VEC>(lds.wS[w][tc])));
-        pt *= p;
+        const vec<VEC> sw = lds.wS[w][tc];
+        if (CLOSED && lds.wClosed[w][tc]) {  // a closed element replaces all that came before it
+            pt = p;
+            st_ = sw;
+            ct = 1;
+        } else {
+            st_ = narrow<VEC>(dfma<VEC>(p, widen<VEC>(st_), widen<VEC>(sw)));
+            pt *= p;
+        }
     }
     Pt = pt;
     St = st_;
+    if constexpr (CLOSED) *closed = ct != 0;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -638,20 +661,22 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     // ---- look-back --------------------------------------------------------------------------
     // Window w covers predecessors k-1-w*WT down to k-(w+1)*WT; thread (tt, tc) reads the one that is
     // WT-1-tt tiles before the window's nearest, so that tt increases with time like inside a tile.
-    // A predecessor that has published its inclusive state I enters as the pair (0, I): composed in
-    // time order, a zero product wipes out everything earlier, so the window total (Pw, Sw) is the
-    // affine map from the state before the window's earliest relevant tile to the state after its
-    // nearest.  (Pr, Sr) composes the windows visited so far.  The walk stops once Pr == 0 in every
-    // column of the tile: the remaining history cannot matter (an inclusive state was met, or the
-    // lambdas themselves multiplied to zero) and Sr is the carry-in.
+    // A predecessor that has published its inclusive state I enters as a "closed" element: composed
+    // in time order, the latest closed element and what follows it are kept and everything earlier is
+    // dropped unread, so the window total is either a state (closed: the walk ends, Sr becomes the
+    // carry-in) or the affine map of the whole window (open: the next, earlier window is needed).
+    // (Pr, Sr) composes the windows visited so far.  The initial state is a closed element too, so
+    // the walk always ends at the window that contains it.
     dvec<VEC> Pr = dsplat<VEC>(1.0);
     vec<VEC> Sr = splat<VEC>(0.0f);
+    bool have_state = false;
     for (int64_t base = k - 1;; base -= WT) {
         const int64_t pred = base - (WT - 1 - tt);
         dvec<VEC> vP = dsplat<VEC>(0.0);
         vec<VEC> vS = splat<VEC>(0.0f);
+        bool closed = true;  // this thread's element is a complete state (inclusive state, initial state)
         if (pred < 0 || !col_ok) {
-            // before the first tile: the initial state (h0 forward, zero backward), as (0, h0)
+            // before the first tile: the initial state (h0 forward, zero backward)
             if (!BWD && pred == -1 && col_ok && A.h0) vS = ld<VEC>(A.h0 + col);
         } else {
             const unsigned long long *w = A.lbAgg + (pred * A.C + col) * 3;
@@ -684,30 +709,32 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
                 }
                 // (a predecessor caught between its two publications has some columns of this
                 // thread tagged inclusive and some not: neither test holds and it is read again)
-                if (all_incl) { vP = dsplat<VEC>(0.0); break; }
-                if (all_agg) break;
+                if (all_incl) break;
+                if (all_agg) { closed = false; break; }
                 if (++spins > A.spin_limit) gave_up = true;
                 else __builtin_amdgcn_s_sleep(2);
             }
             if (gave_up) {  // flag the error and finish with a zero state
                 atomicOr(&A.hdr->err, 1u);
-                vP = dsplat<VEC>(0.0);
                 vS = splat<VEC>(0.0f);
+                closed = true;
             }
         }
         __syncthreads();  // the previous use of the scan's LDS staging is over
         dvec<VEC> Pe, Pw;
         vec<VEC> Se, Sw;
-        tile_scan<G>(lds, tid, vP, vS, Pe, Se, Pw, Sw);
-        // (window) is earlier in time than everything in (Pr, Sr): it goes on the left
-        Sr = narrow<VEC>(dfma<VEC>(Pr, widen<VEC>(Sw), widen<VEC>(Sr)));
-        Pr = Pw * Pr;
+        tile_scan<G, true>(lds, tid, vP, vS, Pe, Se, Pw, Sw, &closed);
+        // (window) is earlier in time than everything in (Pr, Sr): it goes on the left.  Columns that
+        // met a state in an earlier window are complete and take nothing more.
+        if (!have_state) {
+            Sr = narrow<VEC>(dfma<VEC>(Pr, widen<VEC>(Sw), widen<VEC>(Sr)));
+            Pr = Pw * Pr;
+            have_state = closed;
+        }
         ++n_windows;
-        bool open = false;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) open = open || (Pr[v] != 0.0);
-        // every wavefront holds every tc, so this vote is the same in all of them
-        if (!__any(open)) break;
+        // every wavefront holds every tc, so this vote is the same in all of them; a window that
+        // reached back to the initial state always closes (nothing precedes it)
+        if (!__any(!have_state) || base - (WT - 1) <= -1) break;
     }
     LINREC_TRACE_MARK(3);
     LINREC_TRACE_VAL(5, n_windows);

@@ -330,3 +330,50 @@ def test_tuned_plan_is_used_and_correct():
     fwd_bwd_check(inp, "tuned plan")
     with pytest.raises(lr.LinrecError):
         lr.linrec_tune(0, 2, 3)
+
+
+@pytest.mark.parametrize("cfg", [2, 3])
+def test_configs_full_size_with_tuned_plan(cfg):
+    """What bench.py times: the plan linrec_tune() picks for the full-size workload."""
+    inp = wl.make_inputs(cfg, device=DEV)
+    lr.linrec_tune(inp["T"], inp["B"], inp["n"], backward=False)
+    lr.linrec_tune(inp["T"], inp["B"], inp["n"], backward=True)
+    say(f"cfg{cfg} tuned: fwd {lr.linrec_plan(inp['T'], inp['B'], inp['n'], backward=False)}, "
+        f"bwd {lr.linrec_plan(inp['T'], inp['B'], inp['n'], backward=True)}")
+    fwd_bwd_check(inp, f"cfg{cfg} full tuned")
+
+
+@pytest.mark.parametrize("variant", ["threephase", "lookback"])
+def test_non_finite_values_stay_in_their_column(variant):
+    """NaN / Inf in one column must not leak into other columns, and must not hang the look-back."""
+    inp = wl.make_inputs(2, T=9000, B=1, n=96, device=DEV)
+    clean = {k: (v.clone() if torch.is_tensor(v) else v) for k, v in inp.items()}
+    inp["x"][1234, 0, 5] = float("nan")
+    inp["x"][4321, 0, 17] = float("inf")
+    inp["lam"][100, 0, 40] = float("nan")
+    bad = [5, 17, 40]
+    good = [c for c in range(96) if c not in bad]
+    with options(variant=VARIANTS[variant]):
+        h = run_forward(inp)
+        h_clean = run_forward(clean)
+        gx, gl, gh0 = run_backward(inp, h_clean)       # backward on finite h: only lambda's NaN column is affected
+        gx_c, gl_c, gh0_c = run_backward(clean, h_clean)
+    torch.cuda.synchronize()
+    lr.linrec_check()
+    assert torch.equal(h[:, :, good], h_clean[:, :, good])
+    assert torch.isnan(h[1234:, 0, 5]).all() and torch.isfinite(h[:1234, 0, 5]).all()
+    assert not torch.isfinite(h[4321:, 0, 17]).any() and torch.isfinite(h[:4321, 0, 17]).all()
+    assert torch.isnan(h[100:, 0, 40]).all()
+    ok = [c for c in range(96) if c != 40]
+    assert torch.equal(gx[:, :, ok], gx_c[:, :, ok]) and torch.equal(gl[:, :, ok], gl_c[:, :, ok])
+    assert torch.isnan(gx[:99, 0, 40]).all() and torch.isfinite(gx[100:, 0, 40]).all()
+
+
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "serial"])
+def test_growing_recurrence_within_the_documented_domain(variant):
+    """|lambda| > 1 is supported while the partial products stay finite."""
+    T, B, n = 700, 1, 64
+    inp = wl.make_generic(T, B, n, 77, device=DEV, lam_kind="signed")
+    inp["lam"] = (1.0 + 0.02 * inp["lam"]).contiguous()          # in [0.98, 1.02]: products up to ~1e6
+    with options(variant=VARIANTS[variant]):
+        fwd_bwd_check(inp, f"growing {variant}")
