@@ -34,7 +34,7 @@ def build(force: bool = False) -> str:
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(
             ["gcc", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
-             "-o", tmp, _SRC])
+             "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -49,6 +49,11 @@ def _load():
         lib.linrec_oracle_forward.restype = None
         lib.linrec_oracle_backward.argtypes = [p, p, p, p, p, p, p, p, i64, i64, i64, i64, i64, i64]
         lib.linrec_oracle_backward.restype = None
+        lib.linrec_oracle_gilr_forward.argtypes = [p, p, ctypes.c_int, p, p, i64, i64, i64, i64, i64, i64]
+        lib.linrec_oracle_gilr_forward.restype = None
+        lib.linrec_oracle_gilr_backward.argtypes = [p, p, ctypes.c_int, p, p, p, p, p, p, p,
+                                                    i64, i64, i64, i64, i64, i64]
+        lib.linrec_oracle_gilr_backward.restype = None
         _lib = lib
     return _lib
 
@@ -256,3 +261,49 @@ def backward_compare(lam, h, h0, grad_h, gx_cand, glam_cand, gh0_cand, threads=1
     if gh0_cand is not None:
         fold("grad_h0", np.asarray(gh0_cand).reshape(C), gh0)
     return out
+
+
+# ---------------------------------------------------------------------------------------------
+# Gated (GILR) form: h_t = g_t*h_{t-1} + (1-g_t)*i_t with g = sigmoid(g_pre), i = tau(i_pre)
+# ---------------------------------------------------------------------------------------------
+TAU_IDENTITY, TAU_TANH = 0, 1
+
+
+def gilr_forward(g_pre, i_pre, h0=None, tau=TAU_TANH, threads=1):
+    """fp64 h of the gated form from the fp32 pre-activations; same shape as ``g_pre``."""
+    g2 = _f32_2d(g_pre, "g_pre")
+    i2 = _f32_2d(i_pre, "i_pre")
+    if g2.shape != i2.shape:
+        raise ValueError("g_pre and i_pre must have the same shape")
+    T, C = g2.shape
+    h0v = _f32_1d(h0, C, "h0")
+    state = np.zeros(C, np.float64) if h0v is None else h0v.astype(np.float64)
+    href = np.empty((T, C), np.float64)
+    lib = _load()
+    if T > 0 and C > 0:
+        _run_over_columns(lambda c0, c1: lib.linrec_oracle_gilr_forward(
+            _ptr(g2), _ptr(i2), int(tau), _ptr(state), _ptr(href), T, C, 0, T, c0, c1), C, threads)
+    return href.reshape(np.asarray(g_pre).shape)
+
+
+def gilr_backward(g_pre, i_pre, h, h0, grad_h, tau=TAU_TANH, threads=1):
+    """Returns (grad_g_pre, grad_i_pre, grad_h0) in fp64 for upstream ``grad_h`` = dL/dh."""
+    g2 = _f32_2d(g_pre, "g_pre")
+    i2 = _f32_2d(i_pre, "i_pre")
+    h2 = _f32_2d(h, "h")
+    e2 = _f32_2d(grad_h, "grad_h")
+    if not (g2.shape == i2.shape == h2.shape == e2.shape):
+        raise ValueError("g_pre, i_pre, h and grad_h must have the same shape")
+    T, C = g2.shape
+    h0v = _f32_1d(h0, C, "h0")
+    dstate = np.zeros(C, np.float64)
+    gg = np.empty((T, C), np.float64)
+    gi = np.empty((T, C), np.float64)
+    gh0 = np.zeros(C, np.float64)
+    lib = _load()
+    if T > 0 and C > 0:
+        _run_over_columns(lambda c0, c1: lib.linrec_oracle_gilr_backward(
+            _ptr(g2), _ptr(i2), int(tau), _ptr(h2), _ptr(h0v), _ptr(e2), _ptr(dstate),
+            _ptr(gg), _ptr(gi), _ptr(gh0), T, C, 0, T, c0, c1), C, threads)
+    shp = np.asarray(g_pre).shape
+    return gg.reshape(shp), gi.reshape(shp), gh0.reshape(shp[1:])

@@ -26,8 +26,13 @@
  * force (T <= 64), lambda==0, lambda==1 vs numpy.cumsum, geometric series,
  * scipy.signal.lfilter, backward closed form by brute force, reversed
  * cumprod, finite differences, adjoint identity, row perturbation, slab and
- * column split invariance.
+ * column split invariance.  The gated (GILR) form further down is pinned by
+ * the exact dyadic case g_pre == 0, the moving-average closed form, the
+ * convex-hull invariant, reduction to the plain recurrence above through
+ * scipy.special.expit / numpy.tanh, and central finite differences of its own
+ * forward pass for every gradient.
  */
+#include <math.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -105,4 +110,85 @@ void linrec_oracle_backward(const float *lambda, const float *h,
     }
 }
 
-int linrec_oracle_version(void) { return 1; }
+/*
+ * Gated impulse linear recurrent layer (Section 3.1, "Gated impulse linear
+ * recurrent layer"), the part after the two matrix products: from the
+ * pre-activations g_pre = U x_t + b_g and i_pre = V x_t + b_z,
+ *
+ *   g_t = sigmoid(g_pre_t)        i_t = tau(i_pre_t)
+ *   h_t = g_t * h_{t-1} + (1 - g_t) * i_t
+ *
+ * tau is tanh (tau != 0) or the identity (tau == 0); the paper leaves tau open.
+ * Same storage, slab and state conventions as linrec_oracle_forward.
+ */
+static double sigmoid_f64(double z) { return 1.0 / (1.0 + exp(-z)); }
+
+void linrec_oracle_gilr_forward(const float *g_pre, const float *i_pre, int tau,
+                                double *state, double *href,
+                                int64_t T, int64_t C,
+                                int64_t t0, int64_t t1, int64_t c0, int64_t c1)
+{
+    (void)T;
+    for (int64_t t = t0; t < t1; ++t) {
+        const float *gt = g_pre + (size_t)t * (size_t)C;
+        const float *it = i_pre + (size_t)t * (size_t)C;
+        double *ht = href + (size_t)t * (size_t)C;
+        for (int64_t c = c0; c < c1; ++c) {
+            double g = sigmoid_f64((double)gt[c]);
+            double i = tau ? tanh((double)it[c]) : (double)it[c];
+            double s = g * state[c] + (1.0 - g) * i;
+            state[c] = s;
+            ht[c] = s;
+        }
+    }
+}
+
+/*
+ * Gradients of the layer above with respect to its pre-activations (chain
+ * rule through Section 2.2's backward recurrence).  With e = dL/dh (direct)
+ * and d_t the accumulated gradient nabla_{h_t} L:
+ *
+ *   d_{T-1} = e_{T-1},   d_t = g_{t+1} * d_{t+1} + e_t
+ *   dL/dg_t = d_t * (h_{t-1} - i_t)          (g_t also scales the impulse)
+ *   dL/di_t = d_t * (1 - g_t)
+ *   grad_g_pre_t = dL/dg_t * g_t * (1 - g_t)                 (sigmoid')
+ *   grad_i_pre_t = dL/di_t * (1 - i_t^2)   (tanh')   or  dL/di_t  (identity)
+ *   grad_h0      = g_0 * d_0
+ *
+ * h is the fp32 forward output handed to the backward pass; rows are walked
+ * from t1-1 down to t0; dstate carries d in and out like gstate above.
+ */
+void linrec_oracle_gilr_backward(const float *g_pre, const float *i_pre, int tau,
+                                 const float *h, const float *h0, const float *e,
+                                 double *dstate,
+                                 double *gg, double *gi, double *gh0,
+                                 int64_t T, int64_t C,
+                                 int64_t t0, int64_t t1, int64_t c0, int64_t c1)
+{
+    for (int64_t t = t1 - 1; t >= t0; --t) {
+        const float *et = e + (size_t)t * (size_t)C;
+        const float *gt = g_pre + (size_t)t * (size_t)C;
+        const float *it = i_pre + (size_t)t * (size_t)C;
+        const float *gnext = (t + 1 < T) ? g_pre + (size_t)(t + 1) * (size_t)C : NULL;
+        const float *hprev = (t > 0) ? h + (size_t)(t - 1) * (size_t)C : h0;
+        double *ggt = gg + (size_t)t * (size_t)C;
+        double *git = gi + (size_t)t * (size_t)C;
+        for (int64_t c = c0; c < c1; ++c) {
+            double d = (double)et[c];
+            if (gnext)
+                d += sigmoid_f64((double)gnext[c]) * dstate[c];
+            dstate[c] = d;
+            double g = sigmoid_f64((double)gt[c]);
+            double i = tau ? tanh((double)it[c]) : (double)it[c];
+            double hp = hprev ? (double)hprev[c] : 0.0;
+            ggt[c] = d * (hp - i) * (g * (1.0 - g));
+            git[c] = d * (1.0 - g) * (tau ? (1.0 - i * i) : 1.0);
+        }
+    }
+    if (t0 == 0 && t1 > 0) {
+        for (int64_t c = c0; c < c1; ++c)
+            gh0[c] = sigmoid_f64((double)g_pre[c]) * dstate[c];
+    }
+}
+
+int linrec_oracle_version(void) { return 2; }
