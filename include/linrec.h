@@ -109,6 +109,42 @@ int linrec_backward(const float *lambda, const float *h, const float *h0, const 
                     float *grad_x, float *grad_lambda, float *grad_h0,
                     int64_t T, int64_t B, int64_t n, void *stream);
 
+/* Impulse activation tau of the gated layer (Section 3.1 leaves it open; its LSTM uses tanh). */
+enum { LINREC_TAU_IDENTITY = 0, LINREC_TAU_TANH = 1 };
+
+/*
+ * Gated impulse linear recurrent layer, the part after its two matrix products, with the
+ * activations applied inside the scan kernel (Section 3.1, "Gated impulse linear recurrent
+ * layer"):
+ *     g_t = sigmoid(g_pre[t]),   i_t = tau(i_pre[t]),   h_t = g_t * h_{t-1} + (1 - g_t) * i_t
+ *   g_pre, i_pre : [T, B, n] pre-activations (U x_t + b_g and V x_t + b_z in the paper).
+ *   h0           : [B, n] or NULL (zero state).      h_out : [T, B, n].
+ *   tau          : LINREC_TAU_TANH or LINREC_TAU_IDENTITY (LINREC_ERR_OPTION otherwise).
+ * Moves the same 12 bytes per element as linrec_forward; separate activation kernels in front
+ * of it would move 16 more.  The kernel works with 1 - g_t = sigmoid(-g_pre[t]), formed without
+ * cancellation, so gates arbitrarily close to one keep their decay rate (an fp32 g_t could not).
+ * h_out may alias i_pre exactly; any other overlap returns LINREC_ERR_ALIAS.  Always evaluated
+ * by the single-pass kernel (or the serial one when LINREC_OPT_VARIANT asks for it).
+ */
+int linrec_gilr_forward(const float *g_pre, const float *i_pre, const float *h0, float *h_out,
+                        int tau, int64_t T, int64_t B, int64_t n, void *stream);
+
+/*
+ * Gradients of the layer above with respect to its pre-activations (Section 2.2's reverse
+ * recurrence followed by the chain rule through the gate and tau).  With e = grad_h (direct
+ * dL/dh_t) and d_t = g_{t+1} * d_{t+1} + e_t, d_{T-1} = e_{T-1}:
+ *     grad_g_pre[t] = d_t * (h[t-1] - i_t) * g_t * (1 - g_t)          (h[-1] = h0)
+ *     grad_i_pre[t] = d_t * (1 - g_t) * tau'(i_pre[t])
+ *     grad_h0       = g_0 * d_0
+ *   g_pre, i_pre, h, grad_h : [T, B, n] inputs; h is linrec_gilr_forward's h_out.
+ *   grad_g_pre, grad_i_pre  : [T, B, n] outputs, either may be NULL; grad_h0 : [B, n] or NULL.
+ * 24 bytes per element (four tensors in, two out).  No output may overlap any other tensor
+ * (LINREC_ERR_ALIAS).
+ */
+int linrec_gilr_backward(const float *g_pre, const float *i_pre, const float *h, const float *h0,
+                         const float *grad_h, float *grad_g_pre, float *grad_i_pre, float *grad_h0,
+                         int tau, int64_t T, int64_t B, int64_t n, void *stream);
+
 /* Process-wide tuning knobs (LINREC_OPT_*).  Environment variables LINREC_VARIANT
  * ("auto", "threephase", "lookback", "serial") and LINREC_TILE (integer id) give the
  * initial values.  Returns LINREC_OK or LINREC_ERR_OPTION.  Not thread-safe against
@@ -145,6 +181,12 @@ int linrec_validate_forward(const float *lambda, const float *x, const float *h0
 int linrec_validate_backward(const float *lambda, const float *h, const float *h0,
                              const float *grad_h, const float *grad_x, const float *grad_lambda,
                              const float *grad_h0, int64_t T, int64_t B, int64_t n);
+int linrec_validate_gilr_forward(const float *g_pre, const float *i_pre, const float *h0,
+                                 const float *h_out, int tau, int64_t T, int64_t B, int64_t n);
+int linrec_validate_gilr_backward(const float *g_pre, const float *i_pre, const float *h,
+                                  const float *h0, const float *grad_h, const float *grad_g_pre,
+                                  const float *grad_i_pre, const float *grad_h0, int tau,
+                                  int64_t T, int64_t B, int64_t n);
 
 /*
  * Measurement aid, not part of the recurrence: a pure streaming kernel built from the same

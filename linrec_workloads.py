@@ -141,3 +141,36 @@ def make_generic(T, B, n, seed, device="cpu", lam_kind="sigmoid", with_h0=True):
     h0 = randn((B, n)) if with_h0 else None
     grad_h = randn(shape)
     return dict(T=T, B=B, n=n, lam=lam.contiguous(), x=x, h0=h0, grad_h=grad_h, backward=True)
+
+
+#: gated-layer workloads (Section 3.1): pre-activations in, as a matrix product would leave them
+GATED = {
+    "g4": dict(T=4096, B=16, n=1024, gate_mean=0.0, gate_std=1.0,
+               note="workload 4's shape and gate distribution, activations applied in the kernel"),
+    "g2": dict(T=65536, B=4, n=256, gate_mean=2.0, gate_std=1.0, note="workload 2's shape, gates sigmoid(N(2,1))"),
+    "g3": dict(T=1048576, B=1, n=128, gate_mean=7.0, gate_std=2.0,
+               note="one million steps, gates mostly within 1e-2..1e-5 of one (long memory)"),
+}
+
+
+def make_gated(T, B, n, seed, device="cpu", gate_mean=0.0, gate_std=1.0, with_h0=True, per_channel=False):
+    """Pre-activations ``g_pre ~ N(gate_mean, gate_std)``, ``i_pre ~ N(0,1)``, ``h0, grad_h ~ N(0,1)``.
+
+    ``per_channel=True`` holds g_pre constant along T in every column (a fixed decay rate: errors in
+    the gate cannot average out)."""
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(SEED_BASE + 7 * int(seed) + 3)
+    shape = (T, B, n)
+
+    def randn(s, mean=0.0, std=1.0):
+        t = torch.empty(s, dtype=torch.float32, device=dev)
+        return t.normal_(mean, std, generator=g)
+
+    g_pre = randn((1, B, n) if per_channel else shape, gate_mean, gate_std)
+    if per_channel:
+        g_pre = g_pre.expand(shape).contiguous()
+    i_pre = randn(shape)
+    h0 = randn((B, n)) if with_h0 else None
+    grad_h = randn(shape)
+    return dict(T=T, B=B, n=n, g_pre=g_pre, i_pre=i_pre, h0=h0, grad_h=grad_h)

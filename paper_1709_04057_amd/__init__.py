@@ -15,6 +15,8 @@ from .binding import (  # noqa: F401
     OPT_TAPER,
     OPT_TILE,
     OPT_VARIANT,
+    TAU_IDENTITY,
+    TAU_TANH,
     VARIANT_AUTO,
     VARIANT_LOOKBACK,
     VARIANT_SERIAL,
@@ -26,6 +28,8 @@ from .binding import (  # noqa: F401
     linrec_check,
     linrec_forward,
     linrec_get_option,
+    linrec_gilr_backward,
+    linrec_gilr_forward,
     linrec_plan,
     linrec_release_workspace,
     linrec_set_option,

@@ -11,6 +11,7 @@ _HEADER = os.path.join(os.path.dirname(_HERE), "include", "linrec.h")
 _lib = None
 
 VARIANT_AUTO, VARIANT_THREEPHASE, VARIANT_LOOKBACK, VARIANT_SERIAL = 0, 1, 2, 3
+TAU_IDENTITY, TAU_TANH = 0, 1
 OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE, OPT_TAPER, OPT_PERSISTENT, OPT_GRID_CAP = 1, 2, 3, 4, 5, 6, 7, 8
 
 
@@ -46,6 +47,14 @@ def lib():
         L.linrec_validate_forward.restype = ci
         L.linrec_validate_backward.argtypes = [p, p, p, p, p, p, p, i64, i64, i64]
         L.linrec_validate_backward.restype = ci
+        L.linrec_gilr_forward.argtypes = [p, p, p, p, ci, i64, i64, i64, p]
+        L.linrec_gilr_forward.restype = ci
+        L.linrec_gilr_backward.argtypes = [p, p, p, p, p, p, p, p, ci, i64, i64, i64, p]
+        L.linrec_gilr_backward.restype = ci
+        L.linrec_validate_gilr_forward.argtypes = [p, p, p, p, ci, i64, i64, i64]
+        L.linrec_validate_gilr_forward.restype = ci
+        L.linrec_validate_gilr_backward.argtypes = [p, p, p, p, p, p, p, p, ci, i64, i64, i64]
+        L.linrec_validate_gilr_backward.restype = ci
         L.linrec_set_option.argtypes = [ci, i64]
         L.linrec_set_option.restype = ci
         L.linrec_get_option.argtypes = [ci]
@@ -162,6 +171,46 @@ def linrec_backward(lam, h, h0, grad_h, grad_x=None, grad_lambda=None, grad_h0=N
     _check(lib().linrec_backward(_ptr(lam), _ptr(h), _ptr(h0), _ptr(grad_h), _ptr(grad_x), _ptr(grad_lambda),
                                  _ptr(grad_h0), T, B, n, _stream_ptr(stream)))
     return grad_x, grad_lambda, grad_h0
+
+
+def linrec_gilr_forward(g_pre, i_pre, h0=None, h_out=None, tau=TAU_TANH, stream=None):
+    """h[t] = g*h[t-1] + (1-g)*tau(i_pre[t]) with g = sigmoid(g_pre[t]); returns h_out."""
+    import torch
+    T, B, n = _tbn(g_pre, "g_pre")
+    if tuple(_tbn(i_pre, "i_pre")) != (T, B, n):
+        raise ValueError("i_pre must have g_pre's shape")
+    _bn(h0, "h0", B, n)
+    if h_out is None:
+        h_out = torch.empty_like(i_pre)
+    elif tuple(_tbn(h_out, "h_out")) != (T, B, n):
+        raise ValueError("h_out must have g_pre's shape")
+    _check(lib().linrec_gilr_forward(_ptr(g_pre), _ptr(i_pre), _ptr(h0), _ptr(h_out), int(tau), T, B, n,
+                                     _stream_ptr(stream)))
+    return h_out
+
+
+def linrec_gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre=None, grad_i_pre=None, grad_h0=None, tau=TAU_TANH,
+                         stream=None, want_grad_g_pre=True, want_grad_i_pre=True, want_grad_h0=True):
+    """Gradients of the gated layer w.r.t. its pre-activations; returns (grad_g_pre, grad_i_pre, grad_h0)."""
+    import torch
+    T, B, n = _tbn(g_pre, "g_pre")
+    for name, t in (("i_pre", i_pre), ("h", h), ("grad_h", grad_h)):
+        if tuple(_tbn(t, name)) != (T, B, n):
+            raise ValueError(f"{name} must have g_pre's shape")
+    _bn(h0, "h0", B, n)
+    if grad_g_pre is None and want_grad_g_pre:
+        grad_g_pre = torch.empty_like(grad_h)
+    if grad_i_pre is None and want_grad_i_pre:
+        grad_i_pre = torch.empty_like(grad_h)
+    if grad_h0 is None and want_grad_h0:
+        grad_h0 = torch.empty((B, n), dtype=torch.float32, device=g_pre.device)
+    for name, t in (("grad_g_pre", grad_g_pre), ("grad_i_pre", grad_i_pre)):
+        if t is not None and tuple(_tbn(t, name)) != (T, B, n):
+            raise ValueError(f"{name} must have g_pre's shape")
+    _bn(grad_h0, "grad_h0", B, n)
+    _check(lib().linrec_gilr_backward(_ptr(g_pre), _ptr(i_pre), _ptr(h), _ptr(h0), _ptr(grad_h), _ptr(grad_g_pre),
+                                      _ptr(grad_i_pre), _ptr(grad_h0), int(tau), T, B, n, _stream_ptr(stream)))
+    return grad_g_pre, grad_i_pre, grad_h0
 
 
 def linrec_set_option(option: int, value: int) -> None:

@@ -16,7 +16,7 @@
 
 namespace linrec {
 
-#define X(ID, VEC, R, WC, WT) hipError_t launch_tile_##ID(Kind, bool, bool, const Args &, hipStream_t);
+#define X(ID, VEC, R, WC, WT) hipError_t launch_tile_##ID(Kind, bool, bool, bool, const Args &, hipStream_t);
 LINREC_TILES(X)
 #undef X
 
@@ -28,11 +28,11 @@ static const TileDesc kTiles[NUM_TILES] = {
 
 const TileDesc &tile_desc(int id) { return kTiles[id - 1]; }
 
-hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, const Args &A, hipStream_t s)
+hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, bool gated, const Args &A, hipStream_t s)
 {
     switch (id) {
 #define X(ID, VEC, R, WC, WT) \
-    case ID: return launch_tile_##ID(kind, bwd, hp_late, A, s);
+    case ID: return launch_tile_##ID(kind, bwd, hp_late, gated, A, s);
         LINREC_TILES(X)
 #undef X
     default: return hipErrorInvalidValue;
@@ -219,12 +219,15 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd)
     return p;
 }
 
-int run(Args A, bool bwd, int vec, hipStream_t s)
+// gated: the form of Section 3.1 (activations applied in the kernel); it exists as the single-pass
+// kernel of the one-column-per-thread tile shapes and as the serial kernel.
+int run(Args A, bool bwd, int vec, hipStream_t s, bool gated = false)
 {
-    const Plan plan = make_plan(A.T, A.C, vec, bwd);
+    Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd);
+    if (gated && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
-        if ((e = launch_serial(A, bwd, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
+        if ((e = launch_serial(A, bwd, gated, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
         return LINREC_OK;
     }
     const TileDesc &d = kTiles[plan.tile - 1];
@@ -250,11 +253,11 @@ int run(Args A, bool bwd, int vec, hipStream_t s)
         A.aggP = (double *)ws.tp;
         A.aggS = A.aggP + kc;
         A.carry = A.aggS + kc;
-        if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, A, s)) != hipSuccess)
+        if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, false, A, s)) != hipSuccess)
             return hip_fail(e, "launch(reduce)");
         if ((e = launch_scan_summaries(A.aggP, A.aggS, bwd ? nullptr : A.h0, A.carry, A.K, A.C, s)) != hipSuccess)
             return hip_fail(e, "launch(scan_summaries)");
-        if ((e = launch_tile_kernel(plan.tile, KIND_FIXUP, bwd, false, A, s)) != hipSuccess)
+        if ((e = launch_tile_kernel(plan.tile, KIND_FIXUP, bwd, false, false, A, s)) != hipSuccess)
             return hip_fail(e, "launch(fixup)");
         return LINREC_OK;
     }
@@ -306,7 +309,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s)
     A.persistent = plan.persistent < 0 ? (bwd ? 0 : 1) : plan.persistent;
     A.grid_cap = (int32_t)opts().grid_cap;
     A.trace = g_trace;
-    if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, A, s)) != hipSuccess)
+    if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, gated, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
     return LINREC_OK;
 }
@@ -362,6 +365,58 @@ extern "C" int linrec_backward(const float *lambda, const float *h, const float 
     A.T = T;
     A.C = C;
     return run(A, true, max_vec(C, {lambda, h, h0, grad_h, grad_x, grad_lambda, grad_h0}), s);
+}
+
+extern "C" int linrec_gilr_forward(const float *g_pre, const float *i_pre, const float *h0, float *h_out, int tau,
+                                   int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_gilr_forward(g_pre, i_pre, h0, h_out, tau, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (T == 0 || C == 0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = g_pre;
+    A.b = i_pre;
+    A.h0 = h0;
+    A.out0 = h_out;
+    A.tau = tau;
+    A.T = T;
+    A.C = C;
+    return run(A, false, 1, (hipStream_t)stream, true);
+}
+
+extern "C" int linrec_gilr_backward(const float *g_pre, const float *i_pre, const float *h, const float *h0,
+                                    const float *grad_h, float *grad_g_pre, float *grad_i_pre, float *grad_h0, int tau,
+                                    int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0, tau, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (C == 0) return LINREC_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (T == 0) {
+        if (grad_h0) {
+            const hipError_t e = launch_fill(grad_h0, 0.0f, C, s);
+            if (e != hipSuccess) return hip_fail(e, "launch(fill)");
+        }
+        return LINREC_OK;
+    }
+    if (!grad_g_pre && !grad_i_pre && !grad_h0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = g_pre;
+    A.b = grad_h;
+    A.c = i_pre;
+    A.hprev = h;
+    A.h0 = h0;
+    A.out0 = grad_g_pre;
+    A.out1 = grad_i_pre;
+    A.gh0 = grad_h0;
+    A.tau = tau;
+    A.T = T;
+    A.C = C;
+    return run(A, true, 1, s, true);
 }
 
 extern "C" int linrec_set_option(int option, int64_t value)

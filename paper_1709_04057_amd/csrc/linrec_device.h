@@ -107,6 +107,79 @@ __device__ __forceinline__ vec<N> splat(float x)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Forms of the recurrence.  FORM_PLAIN is h = a*h + b on the caller's lambda.  FORM_GATED serves the
+// gated layers of Section 3.1 (g = sigmoid(g_pre), h_t = g_t*h_{t-1} + (1-g_t)*i_t): the register
+// tile holds the gate's COMPLEMENT c = 1 - g = sigmoid(-g_pre), computed without cancellation, and a
+// step is h = (h - c*h) + b.  A gate close to one is then as accurate as any other -- rounding g
+// itself to fp32 would be an error of 2^-25 against a complement that may be 1e-6, i.e. a wrong
+// decay rate, which adds up over the 1/c steps such a gate remembers.
+// ---------------------------------------------------------------------------------------------
+enum Form { FORM_PLAIN = 0, FORM_GATED = 1 };
+
+template <int FORM, int N>
+__device__ __forceinline__ vec<N> step(vec<N> a, vec<N> s, vec<N> b)
+{
+    if constexpr (FORM == FORM_PLAIN) return vfma<N>(a, s, b);
+    else return vfma<N>(-a, s, s) + b;
+}
+// the multiplier of a step as an fp64 factor of the chunk product
+template <int FORM, int N>
+__device__ __forceinline__ dvec<N> factor(vec<N> a)
+{
+    if constexpr (FORM == FORM_PLAIN) return widen<N>(a);
+    else return dsplat<N>(1.0) - widen<N>(a);
+}
+// the multiplier that makes a step the identity / that forgets the state (g = 0)
+template <int FORM, int N>
+__device__ __forceinline__ vec<N> mult_identity() { return splat<N>(FORM == FORM_PLAIN ? 1.0f : 0.0f); }
+template <int FORM, int N>
+__device__ __forceinline__ vec<N> mult_forget() { return splat<N>(FORM == FORM_PLAIN ? 0.0f : 1.0f); }
+
+// sigmoid(-z) and sigmoid(z) from one exponential of -|z|: both keep their relative accuracy in
+// either tail.  v_exp_f32 / v_rcp_f32 are good to about one ulp.
+__device__ __forceinline__ void gate_pair(float z, float &g, float &c)
+{
+    const float e = __builtin_amdgcn_exp2f(-fabsf(z) * 1.44269504088896340736f);
+    const float big = __builtin_amdgcn_rcpf(1.0f + e), small = e * big;
+    const bool pos = z >= 0.0f;
+    g = pos ? big : small;
+    c = pos ? small : big;  // (a NaN pre-activation gives NaN in both)
+}
+template <int N>
+__device__ __forceinline__ vec<N> gate_complement(vec<N> z)
+{
+    vec<N> r;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        float g, c;
+        gate_pair(z[i], g, c);
+        r[i] = c;
+    }
+    return r;
+}
+// tanh: (1-t)/(1+t) with t = exp(-2|y|); below 1/8 the subtraction would cancel, a short odd
+// series takes over there (its next term is below 2e-9 relative).
+__device__ __forceinline__ float tanh_f32(float y)
+{
+    const float ay = fabsf(y);
+    const float t = __builtin_amdgcn_exp2f(ay * -2.88539008177792681472f);
+    const float big = (1.0f - t) * __builtin_amdgcn_rcpf(1.0f + t);
+    const float y2 = ay * ay;
+    const float small = ay * fmaf(y2, fmaf(y2, fmaf(y2, -17.0f / 315.0f, 2.0f / 15.0f), -1.0f / 3.0f), 1.0f);
+    return copysignf(ay < 0.125f ? small : big, y);
+}
+// the impulse activation tau of Section 3.1: tanh, or the identity
+template <int N>
+__device__ __forceinline__ vec<N> impulse(vec<N> y, int tau)
+{
+    if (!tau) return y;
+    vec<N> r;
+#pragma unroll
+    for (int i = 0; i < N; ++i) r[i] = tanh_f32(y[i]);
+    return r;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Tile addressing.  Every tensor access of a tile goes through a buffer resource whose base is a
 // workgroup-uniform corner of the tile, plus a per-thread 32-bit byte offset (one vector register
 // for the whole tile) plus a per-row scalar byte offset.  No 64-bit address ever lives in a vector
@@ -182,6 +255,8 @@ struct TileAddr {
     }
     // scalar byte offset of the thread's row j < rk (rows go up with j forward, down backward)
     __device__ __forceinline__ uint32_t soff(int j) const { return (uint32_t)(BWD ? rk - 1 - j : j) * rowb; }
+    // the same for a row index that differs between lanes (goes into the vector offset)
+    __device__ __forceinline__ uint32_t soff_rt(int j) const { return (uint32_t)(BWD ? rk - 1 - j : j) * rowb; }
 };
 
 // The thread's R rows of the two scan operands.
@@ -213,8 +288,9 @@ struct RowMask {
 
 // Loads the thread's R rows.  `interior` is workgroup-uniform: no row or column of the tile needs
 // masking (and, backward, no row is one of the boundary cases u == 0, t == 0).  Masked steps are the
-// identity pair (1, 0).
-template <class G, bool BWD>
+// identity pair.  FORM_GATED: A.a holds the gate pre-activations and r.a becomes the gate complement;
+// forward, A.b holds the impulse pre-activations and r.b becomes (1-g)*tau(i_pre).
+template <class G, bool BWD, int FORM = FORM_PLAIN>
 __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
                                           bool interior, Rows<G> &r)
 {
@@ -222,14 +298,21 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
     const rsrc_t ra = ad.rsrc(A.a, BWD ? +1 : 0), rb = ad.rsrc(A.b);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        vec<VEC> va = splat<VEC>(1.0f), vb = splat<VEC>(0.0f);
+        vec<VEC> va = mult_identity<FORM, VEC>(), vb = splat<VEC>(0.0f);
         if (interior || j < mk.n) {
             vb = buf_ld<VEC>(rb, ad.toff, ad.soff(j));
             if constexpr (!BWD) {
                 va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
+                if constexpr (FORM == FORM_GATED) {
+                    va = gate_complement<VEC>(va);
+                    vb = va * impulse<VEC>(vb, A.tau);
+                }
             } else {
-                va = splat<VEC>(0.0f);  // the last row has no successor
-                if (interior || j > 0 || mk.first_has_next) va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
+                va = mult_forget<FORM, VEC>();  // the last row has no successor
+                if (interior || j > 0 || mk.first_has_next) {
+                    va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
+                    if constexpr (FORM == FORM_GATED) va = gate_complement<VEC>(va);
+                }
             }
         }
         r.a[j] = va;
@@ -254,30 +337,30 @@ __device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G,
     }
 }
 
-// Phase 1 of Algorithm 1 for one thread: P = prod a_j (fp64),  S = recurrence over the rows from
-// state 0 (fp32: at most R roundings, each relative to the running value).
-template <class G>
+// Phase 1 of Algorithm 1 for one thread: P = prod of the multipliers (fp64),  S = recurrence over
+// the rows from state 0 (fp32: at most R roundings, each relative to the running value).
+template <class G, int FORM = FORM_PLAIN>
 __device__ __forceinline__ void local_reduce(const Rows<G> &r, dvec<G::VEC> &P, vec<G::VEC> &S)
 {
-    dvec<G::VEC> p = widen<G::VEC>(r.a[0]);
+    dvec<G::VEC> p = factor<FORM, G::VEC>(r.a[0]);
     vec<G::VEC> s = r.b[0];
 #pragma unroll
     for (int j = 1; j < G::R; ++j) {
-        p *= widen<G::VEC>(r.a[j]);
-        s = vfma<G::VEC>(r.a[j], s, r.b[j]);
+        p *= factor<FORM, G::VEC>(r.a[j]);
+        s = step<FORM, G::VEC>(r.a[j], s, r.b[j]);
     }
     P = p;
     S = s;
 }
 
 // Phase 3 for one thread: re-run the recurrence over the registers from carry-in c; b becomes the output.
-template <class G>
+template <class G, int FORM = FORM_PLAIN>
 __device__ __forceinline__ void rescan(Rows<G> &r, vec<G::VEC> c)
 {
     vec<G::VEC> s = c;
 #pragma unroll
     for (int j = 0; j < G::R; ++j) {
-        s = vfma<G::VEC>(r.a[j], s, r.b[j]);
+        s = step<FORM, G::VEC>(r.a[j], s, r.b[j]);
         r.b[j] = s;
     }
 }
@@ -299,6 +382,46 @@ __device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD>
                 if (!interior && j == mk.nh && A.gh0)  // row t == 0: grad_h0 = lambda[0] * g_0
                     st<VEC>(A.gh0 + col, ld<VEC>(A.a + col) * r.b[j]);
             }
+        }
+    }
+}
+
+// Backward epilogue of the gated form.  After the rescan r.b[j] = d_t, the accumulated gradient of
+// row t, and r.a[j] is the gate complement of row t+1; so the complement of the row itself sits in
+// r.a[j+1] (the thread's next row is t-1) and only the thread's last row needs one of its own.
+//   grad_g_pre = d * (h_{t-1} - i) * g * (1-g)     grad_i_pre = d * (1-g) * tau'(i_pre)
+//   grad_h0    = g_0 * d_0
+// h one row behind and the impulse pre-activations are loaded here, after the rescan, when the
+// registers of the scan are free again.
+template <class G>
+__device__ __forceinline__ void tile_store_gated_bwd(const Args &A, const TileAddr<G, true> &ad,
+                                                     const RowMask<G, true> &mk, int64_t col, bool interior,
+                                                     const Rows<G> &r)
+{
+    constexpr int R = G::R, VEC = G::VEC;
+    const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(A.out1), rh = ad.rsrc(A.hprev, -1), ri = ad.rsrc(A.c),
+                 rg = ad.rsrc(A.a);
+    const int nv = interior ? R : mk.n;  // the thread's rows j < nv exist
+    vec<VEC> c_last = splat<VEC>(0.0f);
+    if (nv > 0) c_last = gate_complement<VEC>(buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0));
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        if (interior || j < mk.n) {
+            vec<VEC> c = c_last;
+            if (j + 1 < R) c = (j + 1 < nv) ? r.a[j + 1] : c_last;
+            const vec<VEC> g = splat<VEC>(1.0f) - c, d = r.b[j];
+            vec<VEC> hp = splat<VEC>(0.0f);
+            if (interior || j < mk.nh) hp = buf_ld<VEC>(rh, ad.toff, ad.soff(j));
+            else if (A.h0) hp = ld<VEC>(A.h0 + col);  // row t == 0
+            const vec<VEC> y = buf_ld<VEC>(ri, ad.toff, ad.soff(j));
+            const vec<VEC> i = impulse<VEC>(y, A.tau);
+            if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), d * (hp - i) * (g * c));
+            if (A.out1) {
+                vec<VEC> di = d * c;
+                if (A.tau) di = di * vfma<VEC>(-i, i, splat<VEC>(1.0f));
+                buf_st<VEC>(r1, ad.toff, ad.soff(j), di);
+            }
+            if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, g * d);
         }
     }
 }
@@ -567,7 +690,7 @@ __device__ __forceinline__ unsigned long long lb_load(const unsigned long long *
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <class G, bool BWD, bool HP_LATE>
+template <class G, bool BWD, bool HP_LATE, int FORM = FORM_PLAIN>
 __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
 {
     constexpr int VEC = G::VEC, R = G::R, WC = G::WC, WT = G::WT, ROWS = G::ROWS;
@@ -616,11 +739,11 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     LINREC_TRACE_MARK(0);
 
     Rows<G> r;
-    vec<VEC> hp[BWD ? R : 1];
+    vec<VEC> hp[(BWD && FORM == FORM_PLAIN) ? R : 1];
     const TileAddr<G, BWD> ad(A, tu0, g, tt, tc, rk);
     const RowMask<G, BWD> mk(A, u0, col_ok, rk);
-    tile_load<G, BWD>(A, ad, mk, interior, r);
-    if constexpr (BWD && !HP_LATE) {
+    tile_load<G, BWD, FORM>(A, ad, mk, interior, r);
+    if constexpr (BWD && !HP_LATE && FORM == FORM_PLAIN) {
         if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
     }
     // thread-exclusive prefix inside the tile; rounded to fp32 once (it is used once, in the
@@ -631,7 +754,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     {
         dvec<VEC> P, Pe, Pt;
         vec<VEC> S, St32;
-        local_reduce<G>(r, P, S);
+        local_reduce<G, FORM>(r, P, S);
 #ifdef LINREC_TRACE
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the mark below means "rows have arrived"
 #endif
@@ -754,13 +877,18 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         if (A.persistent) next_ticket = atomicAdd(&A.hdr->ticket, 1ull);
         else finished = atomicAdd(&A.hdr->done, 1ull) + 1ull;
     }
-    rescan<G>(r, vfma<VEC>(Pe32, Sr, Se32));
-    if constexpr (BWD && HP_LATE) {
-        // keep these loads behind the rescan: they take over the registers lambda occupied until now
-        __builtin_amdgcn_sched_barrier(0);
-        if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
+    rescan<G, FORM>(r, vfma<VEC>(Pe32, Sr, Se32));
+    if constexpr (BWD && FORM == FORM_GATED) {
+        __builtin_amdgcn_sched_barrier(0);  // the epilogue's loads stay behind the rescan
+        tile_store_gated_bwd<G>(A, ad, mk, col, interior, r);
+    } else {
+        if constexpr (BWD && HP_LATE) {
+            // keep these loads behind the rescan: they take over the registers lambda occupied until now
+            __builtin_amdgcn_sched_barrier(0);
+            if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
+        }
+        tile_store<G, BWD>(A, ad, mk, col, interior, r, hp);
     }
-    tile_store<G, BWD>(A, ad, mk, col, interior, r, hp);
     LINREC_TRACE_MARK(4);
     if (tid == 0) sTicket[slot] = (uint32_t)(next_ticket > 0xffffffffull ? 0xffffffffull : next_ticket);
     __syncthreads();  // this tile's LDS state has been consumed

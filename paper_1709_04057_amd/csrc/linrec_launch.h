@@ -22,18 +22,20 @@ struct LookbackHeader {
 };
 
 struct Args {
-    const float *a;      // lambda                                  [T, C]
-    const float *b;      // forward: x;  backward: grad_h            [T, C]
+    const float *a;      // lambda (gated form: the gate pre-activations g_pre)      [T, C]
+    const float *b;      // forward: x (gated: i_pre);  backward: grad_h            [T, C]
+    const float *c;      // gated form, backward: the impulse pre-activations i_pre  [T, C]
     const float *hprev;  // backward: h (forward output);  forward: unused
     const float *h0;     // [C] or nullptr
-    float *out0;         // forward: h_out;  backward: grad_x (may be nullptr)
-    float *out1;         // backward: grad_lambda (may be nullptr)
+    float *out0;         // forward: h_out;  backward: grad_x (gated: grad_g_pre) (may be nullptr)
+    float *out1;         // backward: grad_lambda (gated: grad_i_pre) (may be nullptr)
     float *gh0;          // backward: grad_h0 [C] (may be nullptr)
     int64_t T, C;
     int64_t K;           // tiles (look-back) or chunks (three-phase) along time
     int64_t K1, K2;      // look-back: K1 full-height tiles, then K2 of half height, the rest a quarter
     int32_t G;           // column groups of COLS columns
     int32_t M;           // three-phase: tiles walked per chunk
+    int32_t tau;         // gated form: impulse activation (0 identity, 1 tanh)
     // three-phase workspace, each [K, C] fp64
     double *aggP, *aggS, *carry;
     // look-back workspace: 64-bit words {tag : 32 | payload bits : 32}
@@ -86,12 +88,14 @@ constexpr int NUM_TILES = 23;
 const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 
 // Launches kernel `kind` for tile shape `id` with grid A.K * A.G.  hp_late (look-back, backward):
-// load h after the rescan instead of together with lambda and grad_h.
-hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, const Args &A, hipStream_t s);
+// load h after the rescan instead of together with lambda and grad_h.  gated: the form of Section
+// 3.1 with sigmoid / tau applied in the kernel (look-back kernels of one-column-per-thread shapes
+// only; hipErrorInvalidValue otherwise).
+hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, bool gated, const Args &A, hipStream_t s);
 
 hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const float *h0, double *carry, int64_t K,
                                  int64_t C, hipStream_t s);
-hipError_t launch_serial(const Args &A, bool bwd, hipStream_t s);
+hipError_t launch_serial(const Args &A, bool bwd, bool gated, hipStream_t s);
 hipError_t launch_fill(float *p, float value, int64_t n, hipStream_t s);
 hipError_t launch_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
                                int64_t n, hipStream_t s);

@@ -131,6 +131,48 @@ __global__ __launch_bounds__(256) void k_serial_bwd(const float *__restrict__ la
     if (gh0) gh0[c] = lam[c] * g;
 }
 
+// The gated form of Section 3.1 (sigmoid and tau applied here), serial over the sequence length.
+__global__ __launch_bounds__(256) void k_serial_gated_fwd(const float *__restrict__ g_pre, const float *i_pre,
+                                                          const float *__restrict__ h0, float *out, int tau, int64_t T,
+                                                          int64_t C)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s = h0 ? h0[c] : 0.0f;
+#pragma unroll 4
+    for (int64_t t = 0; t < T; ++t) {
+        const vec<1> cm = gate_complement<1>(vec<1>(g_pre[t * C + c]));
+        const vec<1> i = impulse<1>(vec<1>(i_pre[t * C + c]), tau);
+        s = step<FORM_GATED, 1>(cm, vec<1>(s), cm * i)[0];
+        out[t * C + c] = s;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_serial_gated_bwd(const float *__restrict__ g_pre,
+                                                          const float *__restrict__ i_pre, const float *__restrict__ h,
+                                                          const float *__restrict__ h0, const float *e, float *gg,
+                                                          float *gi, float *gh0, int tau, int64_t T, int64_t C)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float d = 0.0f;
+    float cnext = 1.0f;  // complement of the gate one row ahead; the last row has no successor (g = 0)
+    float g0 = 0.0f;
+#pragma unroll 2
+    for (int64_t t = T - 1; t >= 0; --t) {
+        d = step<FORM_GATED, 1>(vec<1>(cnext), vec<1>(d), vec<1>(e[t * C + c]))[0];
+        const float cm = gate_complement<1>(vec<1>(g_pre[t * C + c]))[0];
+        const float g = 1.0f - cm;
+        const float i = impulse<1>(vec<1>(i_pre[t * C + c]), tau)[0];
+        const float hp = (t > 0) ? h[(t - 1) * C + c] : (h0 ? h0[c] : 0.0f);
+        if (gg) gg[t * C + c] = d * (hp - i) * (g * cm);
+        if (gi) gi[t * C + c] = tau ? d * cm * fmaf(-i, i, 1.0f) : d * cm;
+        cnext = cm;
+        g0 = g;
+    }
+    if (gh0) gh0[c] = g0 * d;
+}
+
 __global__ void k_fill(float *p, float value, int64_t n)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
@@ -185,9 +227,17 @@ hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const f
     return hipGetLastError();
 }
 
-hipError_t launch_serial(const Args &A, bool bwd, hipStream_t s)
+hipError_t launch_serial(const Args &A, bool bwd, bool gated, hipStream_t s)
 {
     const unsigned grid = (unsigned)((A.C + 255) / 256);
+    if (gated) {
+        if (!bwd)
+            hipLaunchKernelGGL(k_serial_gated_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.h0, A.out0, A.tau, A.T, A.C);
+        else
+            hipLaunchKernelGGL(k_serial_gated_bwd, dim3(grid), dim3(256), 0, s, A.a, A.c, A.hprev, A.h0, A.b, A.out0,
+                               A.out1, A.gh0, A.tau, A.T, A.C);
+        return hipGetLastError();
+    }
     if (!bwd) hipLaunchKernelGGL(k_serial_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.h0, A.out0, A.T, A.C);
     else
         hipLaunchKernelGGL(k_serial_bwd, dim3(grid), dim3(256), 0, s, A.a, A.hprev, A.h0, A.b, A.out0, A.out1, A.gh0,

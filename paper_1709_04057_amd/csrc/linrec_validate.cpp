@@ -71,6 +71,38 @@ extern "C" int linrec_validate_backward(const float *lambda, const float *h, con
     return LINREC_OK;
 }
 
+extern "C" int linrec_validate_gilr_forward(const float *g_pre, const float *i_pre, const float *h0,
+                                            const float *h_out, int tau, int64_t T, int64_t B, int64_t n)
+{
+    if (tau != LINREC_TAU_IDENTITY && tau != LINREC_TAU_TANH) return LINREC_ERR_OPTION;
+    // same shapes, NULL rules and aliasing as the plain forward pass (h_out may be i_pre itself)
+    return linrec_validate_forward(g_pre, i_pre, h0, h_out, T, B, n);
+}
+
+extern "C" int linrec_validate_gilr_backward(const float *g_pre, const float *i_pre, const float *h, const float *h0,
+                                             const float *grad_h, const float *grad_g_pre, const float *grad_i_pre,
+                                             const float *grad_h0, int tau, int64_t T, int64_t B, int64_t n)
+{
+    if (tau != LINREC_TAU_IDENTITY && tau != LINREC_TAU_TANH) return LINREC_ERR_OPTION;
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (C == 0 || T == 0) return LINREC_OK;
+    if (!g_pre || !i_pre || !h || !grad_h) return LINREC_ERR_NULL;
+    // A tile reads rows of g_pre and h that belong to its neighbours, so no output may share memory
+    // with any input, nor with another output.
+    const float *outs[3] = {grad_g_pre, grad_i_pre, grad_h0};
+    const int64_t out_len[3] = {E, E, C};
+    const float *ins[5] = {g_pre, i_pre, h, grad_h, h0};
+    const int64_t in_len[5] = {E, E, E, E, C};
+    for (int o = 0; o < 3; ++o) {
+        for (int i = 0; i < 5; ++i)
+            if (overlaps(outs[o], out_len[o], ins[i], in_len[i])) return LINREC_ERR_ALIAS;
+        for (int p = o + 1; p < 3; ++p)
+            if (overlaps(outs[o], out_len[o], outs[p], out_len[p])) return LINREC_ERR_ALIAS;
+    }
+    return LINREC_OK;
+}
+
 extern "C" const char *linrec_status_string(int status)
 {
     switch (status) {
@@ -85,4 +117,4 @@ extern "C" const char *linrec_status_string(int status)
     }
 }
 
-extern "C" int linrec_version(void) { return 100; }
+extern "C" int linrec_version(void) { return 101; }

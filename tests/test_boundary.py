@@ -71,6 +71,28 @@ def test_validate_backward(L):
     assert v(None, None, None, None, None, None, _p(A6), 0, 4, 8) == 0
 
 
+def test_validate_gilr(L):
+    vf, vb = L.linrec_validate_gilr_forward, L.linrec_validate_gilr_backward
+    assert vf(_p(A0), _p(A1), _p(A2), _p(A3), 1, 1000, 4, 8) == 0
+    assert vf(_p(A0), _p(A1), None, _p(A1), 0, 1000, 4, 8) == 0            # h_out in place on i_pre
+    assert vf(_p(A0), _p(A1), None, _p(A0), 1, 1000, 4, 8) == -3           # h_out on g_pre
+    assert vf(_p(A0), _p(A1), None, _p(A3), 2, 1000, 4, 8) == -5           # unknown tau
+    assert vf(None, _p(A1), None, _p(A3), 1, 1000, 4, 8) == -1
+    assert vf(None, None, None, None, 1, 0, 4, 8) == 0
+    A7 = A6 + 0x1000000
+    ok = (_p(A0), _p(A1), _p(A2), _p(A3), _p(A4), _p(A5), _p(A6), _p(A7))
+    assert vb(*ok, 1, 1000, 4, 8) == 0
+    assert vb(_p(A0), _p(A1), _p(A2), None, _p(A4), None, None, None, 0, 1000, 4, 8) == 0   # outputs optional
+    assert vb(*ok, 7, 1000, 4, 8) == -5
+    assert vb(_p(A0), None, _p(A2), None, _p(A4), _p(A5), None, None, 1, 1000, 4, 8) == -1  # i_pre required
+    assert vb(_p(A0), _p(A1), _p(A2), None, _p(A4), _p(A4), None, None, 1, 1000, 4, 8) == -3  # output on grad_h
+    assert vb(_p(A0), _p(A1), _p(A2), None, _p(A4), _p(A5), _p(A5), None, 1, 1000, 4, 8) == -3  # outputs share memory
+    assert vb(_p(A0), _p(A1), _p(A2), None, _p(A4), _p(A5), _p(A1), None, 1, 1000, 4, 8) == -3  # output on i_pre
+    assert vb(*ok, 1, 1000, -4, 8) == -2
+    assert L.linrec_gilr_forward(_p(A0), _p(A1), None, _p(A0), 1, 10, 2, 2, None) == -3      # before any HIP call
+    assert L.linrec_gilr_backward(None, None, None, None, None, None, None, None, 1, 10, 0, 2, None) == 0
+
+
 def test_entry_points_validate_before_touching_the_gpu(L):
     # invalid arguments must come back as error codes even on a machine without a GPU
     assert L.linrec_forward(None, _p(A1), None, _p(A3), 10, 2, 2, None) == -1

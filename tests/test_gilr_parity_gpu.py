@@ -1,0 +1,171 @@
+"""GPU parity of the gated (GILR) entry points against the fp64 oracle, through the C ABI.
+
+arXiv 1709.04057, Section 3.1: g = sigmoid(g_pre), i = tau(i_pre), h_t = g_t*h_{t-1} + (1-g_t)*i_t,
+with sigmoid and tau applied inside the scan kernel.  Same tolerances as the plain recurrence:
+forward max|err| <= 1e-5*(1 + max|h_ref|), each gradient tensor ||err||_inf <= 1e-4*||ref||_inf.
+"""
+import numpy as np
+import pytest
+import torch
+
+import linrec_workloads as wl
+import oracle
+import paper_1709_04057_amd as lr
+from parity import FWD_TOL, GRAD_TOL, ORACLE_THREADS, all_tiles, options, say
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ONE_COLUMN_TILES = [i for i, info in all_tiles() if info["cols_per_thread"] == 1]
+
+
+def _np(t):
+    return None if t is None else t.detach().cpu().numpy()
+
+
+def gated_check(inp, tau, label, cols=None, backward=True):
+    """Forward and backward on the GPU; every element (or the sampled columns ``cols``) against the oracle."""
+    T, B, n = inp["T"], inp["B"], inp["n"]
+    C = B * n
+    say(f"{label}: gilr forward T={T} B={B} n={n} tau={tau}")
+    h = lr.linrec_gilr_forward(inp["g_pre"], inp["i_pre"], inp["h0"], tau=tau)
+    torch.cuda.synchronize()
+    sel = slice(None) if cols is None else torch.as_tensor(cols, device=h.device)
+
+    def pick(t, rows=True):  # [T, C] (or [C]) restricted to the sampled columns, on the host, contiguous
+        if t is None:
+            return None
+        t2 = t.reshape(T, C) if rows else t.reshape(C)
+        return np.ascontiguousarray(_np(t2[:, sel] if rows else t2[sel]))
+
+    gp, ip, h0 = pick(inp["g_pre"]), pick(inp["i_pre"]), pick(inp["h0"], rows=False)
+    href = oracle.gilr_forward(gp, ip, h0, tau, threads=ORACLE_THREADS)
+    hg = pick(h)
+    assert np.all(np.isfinite(hg))
+    err, ref = np.abs(hg - href).max() if href.size else 0.0, np.abs(href).max() if href.size else 0.0
+    assert err <= FWD_TOL * (1 + ref), f"{label}: forward max|err| {err:.3e} > {FWD_TOL * (1 + ref):.3e}"
+    out = {"fwd_err": err, "fwd_ref": ref}
+    if backward:
+        say(f"{label}: gilr backward")
+        gg, gi, gh0 = lr.linrec_gilr_backward(inp["g_pre"], inp["i_pre"], h, inp["h0"], inp["grad_h"], tau=tau)
+        torch.cuda.synchronize()
+        rg, ri, rh0 = oracle.gilr_backward(gp, ip, hg, h0, pick(inp["grad_h"]), tau, threads=ORACLE_THREADS)
+        for name, got, want in (("grad_g_pre", pick(gg), rg), ("grad_i_pre", pick(gi), ri),
+                                ("grad_h0", pick(gh0, rows=False), rh0)):
+            assert np.all(np.isfinite(got)), f"{label}: {name} has non-finite values"
+            e, r = (np.abs(got - want).max(), max(np.abs(want).max(), 1e-30)) if want.size else (0.0, 1.0)
+            assert e <= GRAD_TOL * r, f"{label}: {name} ||err||_inf {e:.3e} > {GRAD_TOL:.0e} * {r:.3e}"
+            out[name] = e / r
+    lr.linrec_check()
+    return out
+
+
+@pytest.mark.parametrize("tau", [lr.TAU_TANH, lr.TAU_IDENTITY])
+@pytest.mark.parametrize("tile", ONE_COLUMN_TILES)
+def test_every_one_column_tile_ragged_shapes(tile, tau):
+    # several tiles along T and along the columns, ragged in both, for every tile shape the form has
+    info = lr.linrec_tile_info(tile)
+    T = 2 * info["rows"] + info["rows"] // 2 + 3
+    C = 2 * info["cols"] + 5
+    inp = wl.make_gated(T, 1, C, seed=100 + tile, device=DEV, gate_mean=1.0, gate_std=2.0)
+    with options(variant=lr.VARIANT_LOOKBACK, tile=tile):
+        gated_check(inp, tau, f"tile {tile}")
+
+
+@pytest.mark.parametrize("T,B,n", [(1, 1, 1), (2, 3, 5), (7, 1, 64), (513, 2, 33), (4096, 1, 16), (3000, 2, 100)])
+@pytest.mark.parametrize("variant", ["lookback", "serial"])
+def test_small_and_degenerate_shapes(T, B, n, variant):
+    inp = wl.make_gated(T, B, n, seed=T + n, device=DEV, gate_mean=0.5, gate_std=1.5)
+    with options(variant=lr.VARIANT_LOOKBACK if variant == "lookback" else lr.VARIANT_SERIAL):
+        gated_check(inp, lr.TAU_TANH, f"{variant} {T}x{B}x{n}")
+
+
+def test_no_initial_state_and_skipped_outputs():
+    inp = wl.make_gated(2500, 2, 48, seed=5, device=DEV, with_h0=False)
+    gated_check(inp, lr.TAU_TANH, "no h0")
+    h = lr.linrec_gilr_forward(inp["g_pre"], inp["i_pre"], None)
+    full = lr.linrec_gilr_backward(inp["g_pre"], inp["i_pre"], h, None, inp["grad_h"])
+    only_g = lr.linrec_gilr_backward(inp["g_pre"], inp["i_pre"], h, None, inp["grad_h"], want_grad_i_pre=False,
+                                     want_grad_h0=False)
+    only_i = lr.linrec_gilr_backward(inp["g_pre"], inp["i_pre"], h, None, inp["grad_h"], want_grad_g_pre=False)
+    torch.cuda.synchronize()
+    assert only_g[1] is None and only_g[2] is None and only_i[0] is None
+    assert torch.equal(only_g[0], full[0]) and torch.equal(only_i[1], full[1]) and torch.equal(only_i[2], full[2])
+
+
+def test_in_place_on_the_impulse_and_empty_problems():
+    inp = wl.make_gated(1800, 2, 40, seed=6, device=DEV)
+    want = lr.linrec_gilr_forward(inp["g_pre"], inp["i_pre"], inp["h0"])
+    buf = inp["i_pre"].clone()
+    got = lr.linrec_gilr_forward(inp["g_pre"], buf, inp["h0"], h_out=buf)
+    torch.cuda.synchronize()
+    assert got.data_ptr() == buf.data_ptr() and torch.equal(got, want)
+    # T == 0: nothing to do, grad_h0 is zero-filled; B*n == 0: nothing at all
+    e = torch.empty((0, 2, 40), device=DEV)
+    assert lr.linrec_gilr_forward(e, e, inp["h0"]).shape == (0, 2, 40)
+    gh0 = torch.full((2, 40), 7.0, device=DEV)
+    lr.linrec_gilr_backward(e, e, e, inp["h0"], e, grad_h0=gh0)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(gh0) == 0
+    z = torch.empty((5, 0, 40), device=DEV)
+    lr.linrec_gilr_forward(z, z, None)
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_gilr_forward(inp["g_pre"], inp["i_pre"], inp["h0"], tau=5)
+
+
+@pytest.mark.parametrize("gate_mean", [7.0, 12.0])
+def test_gates_close_to_one_keep_their_decay_rate(gate_mean):
+    # g_pre constant along T in every column: 1-g between 1e-2 and 1e-7, memory of up to millions of
+    # steps; an fp32 g would carry a fixed relative error of up to 2^-25/(1-g) in the decay rate.
+    T = 300_000
+    inp = wl.make_gated(T, 1, 64, seed=int(gate_mean), device=DEV, gate_mean=gate_mean, gate_std=2.0, per_channel=True)
+    r = gated_check(inp, lr.TAU_TANH, f"saturated gates mean {gate_mean}")
+    say(f"saturated gates mean {gate_mean}: {r}")
+
+
+def test_saturated_and_extreme_pre_activations():
+    # |pre-activation| up to 1e4: sigmoid and tanh saturate without overflow, NaN or loss of the state
+    T, B, n = 2048, 1, 96
+    inp = wl.make_gated(T, B, n, seed=9, device=DEV)
+    scale = torch.logspace(-2, 4, n, device=DEV).reshape(1, 1, n)
+    inp["g_pre"] = (inp["g_pre"] * scale).contiguous()
+    inp["i_pre"] = (inp["i_pre"] * scale.flip(-1)).contiguous()
+    for tau in (lr.TAU_TANH, lr.TAU_IDENTITY):
+        gated_check(inp, tau, "extreme pre-activations")
+
+
+@pytest.mark.parametrize("variant", ["lookback", "serial"])
+def test_non_finite_pre_activations_stay_in_their_column(variant):
+    T, B, n = 3000, 1, 80
+    inp = wl.make_gated(T, B, n, seed=11, device=DEV)
+    clean = dict(inp)
+    g_pre, i_pre = inp["g_pre"].clone(), inp["i_pre"].clone()
+    g_pre[100, 0, 40] = float("nan")
+    i_pre[200, 0, 41] = float("inf")          # tanh(inf) = 1: stays finite
+    i_pre[300, 0, 42] = float("nan")
+    with options(variant=lr.VARIANT_LOOKBACK if variant == "lookback" else lr.VARIANT_SERIAL):
+        h = lr.linrec_gilr_forward(g_pre, i_pre, inp["h0"])
+        ref = lr.linrec_gilr_forward(clean["g_pre"], clean["i_pre"], inp["h0"])
+        torch.cuda.synchronize()
+        lr.linrec_check()
+    assert torch.isnan(h[100:, 0, 40]).all() and torch.isfinite(h[:100, 0, 40]).all()
+    assert torch.isnan(h[300:, 0, 42]).all() and torch.isfinite(h[:300, 0, 42]).all()
+    assert torch.isfinite(h[:, 0, 41]).all()
+    keep = [c for c in range(n) if c not in (40, 41, 42)]
+    assert torch.equal(h[:, 0, keep], ref[:, 0, keep])
+
+
+@pytest.mark.parametrize("name", sorted(wl.GATED))
+def test_full_size_workloads_on_sampled_columns(name):
+    # the shapes the benchmark times, in its launch configuration; the oracle evaluates a sample of
+    # whole columns (columns are independent recurrences), all rows of each
+    spec = wl.GATED[name]
+    T, B, n = spec["T"], spec["B"], spec["n"]
+    inp = wl.make_gated(T, B, n, seed=sum(map(ord, name)), device=DEV, gate_mean=spec["gate_mean"],
+                        gate_std=spec["gate_std"])
+    C = B * n
+    rng = np.random.default_rng(5)
+    k = max(8, min(C, (1 << 23) // T))
+    cols = np.sort(rng.choice(C, size=min(k, C), replace=False))
+    cols[0], cols[-1] = 0, C - 1
+    r = gated_check(inp, lr.TAU_TANH, f"workload {name} ({len(cols)} columns)", cols=cols)
+    say(f"workload {name}: {r}")
