@@ -43,6 +43,10 @@ def parse():
                     help="instead of the workload benchmark, time the parallel (single-pass) kernel against the "
                          "serial-over-T kernel on the grid of the paper's Table 1 (minibatch 1; 4, 32, 128 features; "
                          "T = 16 ... 65536) and print the speed-up ratios as one JSON line")
+    ap.add_argument("--gated", default="", choices=["", "g2", "g3", "g4"],
+                    help="time the gated (GILR) entry points on this workload instead (sigmoid / tanh applied in the "
+                         "scan kernel: 12 B/element forward, 24 backward), next to the unfused sequence "
+                         "elementwise kernels + linrec_forward")
     ap.add_argument("--probe", action="store_true",
                     help="also time the library's pure streaming kernels (copy, 2-in/1-out, 3-in/2-out) on arrays "
                          "of the workload's size; the copy doubles as the calibration kernel for byte counters")
@@ -140,6 +144,72 @@ def table1(lr, torch):
     return grid
 
 
+def gated_bench(args, lr, torch, wl):
+    """One JSON line for the gated entry points: per-pass times, GB/s against the 12 / 24 algorithmic
+    bytes per element, and the unfused forward (activation kernels, then the plain scan) beside it."""
+    dev = "cuda:0"
+    spec = wl.GATED[args.gated]
+    T, B, n = spec["T"], spec["B"], spec["n"]
+    E = T * B * n
+    inp = wl.make_gated(T, B, n, seed=sum(map(ord, args.gated)), device=dev, gate_mean=spec["gate_mean"],
+                        gate_std=spec["gate_std"])
+    g_pre, i_pre, h0, e = inp["g_pre"], inp["i_pre"], inp["h0"], inp["grad_h"]
+    h = torch.empty_like(g_pre)
+    gg, gi = torch.empty_like(g_pre), torch.empty_like(g_pre)
+    gh0 = torch.empty((B, n), device=dev)
+    lam, x = torch.empty_like(g_pre), torch.empty_like(g_pre)
+    stream = torch.cuda.current_stream()
+    K = args.steps
+
+    def fused_fwd():
+        lr.linrec_gilr_forward(g_pre, i_pre, h0, h_out=h, stream=stream)
+
+    def fused_bwd():
+        lr.linrec_gilr_backward(g_pre, i_pre, h, h0, e, grad_g_pre=gg, grad_i_pre=gi, grad_h0=gh0, stream=stream)
+
+    def unfused_fwd():  # what a framework does without the fused kernel: 3 elementwise kernels, then the scan
+        torch.sigmoid(g_pre, out=lam)
+        torch.tanh(i_pre, out=x)
+        torch.addcmul(x, lam, x, value=-1.0, out=x)      # x = (1 - lam) * tanh(i_pre)
+        lr.linrec_forward(lam, x, h0, h_out=h, stream=stream)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+        torch.cuda.synchronize()
+        ev[0].record(stream)
+        for i in range(K):
+            fn()
+            ev[i + 1].record(stream)
+        torch.cuda.synchronize()
+        ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(K))
+        return sum(ms) / K, ms[0]
+
+    f_avg, f_min = timed(fused_fwd)
+    b_avg, b_min = timed(fused_bwd)
+    u_avg, u_min = timed(unfused_fwd)
+    lr.linrec_check(stream)
+    gbs = lambda bpe, ms: bpe * E / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "gated linrec (GILR) fwd+bwd elements/sec and achieved HBM GB/s (% of MI355X peak)",
+        "value": E / ((f_avg + b_avg) * 1e-3), "unit": "elements/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": f_avg + b_avg, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.gated}: gated forward+backward, fp32, time-major [T={T}, B={B}, n={n}], tau=tanh; "
+                               + spec["note"]},
+        "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(12.0, f_avg), "frac_of_peak": gbs(12.0, f_avg) / HBM_PEAK_GBS},
+        "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(24.0, b_avg), "frac_of_peak": gbs(24.0, b_avg) / HBM_PEAK_GBS},
+        "unfused_forward": {"avg_ms": u_avg, "min_ms": u_min, "speedup_of_fused": u_avg / f_avg,
+                            "what": "torch.sigmoid, torch.tanh, torch.addcmul, then linrec_forward"},
+        "roofline": {"bound": "hbm", "kernel": "gated backward pass (look-back kernel)", "achieved": gbs(24.0, b_avg),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(24.0, b_avg) / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_element": 24.0, "algorithmic_bytes": 24.0 * E, "avg_ms": b_avg},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -169,6 +239,10 @@ def main():
                                                        "T=4096": [1.02, 2.94, 3.36], "T=65536": [38.5, 41.8, 17.5],
                                                        "columns": "m = 4, 32, 128"},
                           "table1": table1(lr, torch)}), flush=True)
+        return
+
+    if args.gated:
+        gated_bench(args, lr, torch, wl)
         return
 
     inp = wl.make_inputs(args.config, device=dev)

@@ -189,14 +189,14 @@ std::mutex g_tuned_mu;
 std::map<TunedKey, TunedPlan> g_tuned;
 
 // Picks variant and tile, honouring the options where they apply to this problem.
-Plan make_plan(int64_t T, int64_t C, int vec, bool bwd)
+Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, bool gated = false)
 {
     Plan p;
     p.variant = (int)opts().variant;
     if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
     p.tile = (int)opts().tile;
     p.persistent = (int)opts().persistent;
-    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK) {  // a tuned plan, if there is one for this shape
+    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK && !gated) {  // a tuned plan, if there is one for this shape
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess) {
             std::lock_guard<std::mutex> lock(g_tuned_mu);
@@ -208,7 +208,12 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd)
         }
     }
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
-    if (p.tile < 1 || p.tile > NUM_TILES) p.tile = auto_tile(T, C, vec, bwd, p.variant);
+    if (p.tile < 1 || p.tile > NUM_TILES) {
+        p.tile = auto_tile(T, C, vec, bwd, p.variant);
+        // The gated form computes a sigmoid and a tanh per element before it can publish a summary:
+        // 32-row threads (twice the resident workgroups of the 64-row shapes) hide that better.
+        if (gated && T >= 2048 && C > 16) p.tile = C >= 2048 ? 21 : 18;
+    }
     const TileDesc &d = kTiles[p.tile - 1];
     // per-thread byte offsets inside a tile are 32-bit, tickets of a call are 31-bit
     const int64_t G = ceil_div(C, d.cols()), K = ceil_div(T, d.rows());
@@ -223,7 +228,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd)
 // kernel of the one-column-per-thread tile shapes and as the serial kernel.
 int run(Args A, bool bwd, int vec, hipStream_t s, bool gated = false)
 {
-    Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd);
+    Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd, gated);
     if (gated && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
@@ -306,7 +311,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s, bool gated = false)
     A.hdr = (LookbackHeader *)ws.lb;
     A.lbAgg = (unsigned long long *)((char *)ws.lb + kLbHeader);
     A.spin_limit = (uint32_t)opts().spin_limit;
-    A.persistent = plan.persistent < 0 ? (bwd ? 0 : 1) : plan.persistent;
+    A.persistent = plan.persistent < 0 ? ((bwd && !gated) ? 0 : 1) : plan.persistent;
     A.grid_cap = (int32_t)opts().grid_cap;
     A.trace = g_trace;
     if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, gated, A, s)) != hipSuccess)

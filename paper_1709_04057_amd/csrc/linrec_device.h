@@ -296,27 +296,33 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
 {
     constexpr int R = G::R, VEC = G::VEC;
     const rsrc_t ra = ad.rsrc(A.a, BWD ? +1 : 0), rb = ad.rsrc(A.b);
+    // What a masked step holds BEFORE the activations are applied: the gated form runs them over every
+    // row after all loads have been issued (inside the per-row conditions they would make each load
+    // wait for the one before), and sigmoid(-(+inf)) = 0, sigmoid(-(-inf)) = 1 give the identity
+    // and the forgetting step.
+    const float raw_identity = FORM == FORM_PLAIN ? 1.0f : __builtin_inff();
+    const float raw_forget = FORM == FORM_PLAIN ? 0.0f : -__builtin_inff();
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        vec<VEC> va = mult_identity<FORM, VEC>(), vb = splat<VEC>(0.0f);
+        vec<VEC> va = splat<VEC>(raw_identity), vb = splat<VEC>(0.0f);
         if (interior || j < mk.n) {
             vb = buf_ld<VEC>(rb, ad.toff, ad.soff(j));
             if constexpr (!BWD) {
                 va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
-                if constexpr (FORM == FORM_GATED) {
-                    va = gate_complement<VEC>(va);
-                    vb = va * impulse<VEC>(vb, A.tau);
-                }
             } else {
-                va = mult_forget<FORM, VEC>();  // the last row has no successor
-                if (interior || j > 0 || mk.first_has_next) {
-                    va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
-                    if constexpr (FORM == FORM_GATED) va = gate_complement<VEC>(va);
-                }
+                va = splat<VEC>(raw_forget);  // the last row has no successor
+                if (interior || j > 0 || mk.first_has_next) va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
             }
         }
         r.a[j] = va;
         r.b[j] = vb;
+    }
+    if constexpr (FORM == FORM_GATED) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            r.a[j] = gate_complement<VEC>(r.a[j]);
+            if constexpr (!BWD) r.b[j] = r.a[j] * impulse<VEC>(r.b[j], A.tau);
+        }
     }
 }
 
@@ -399,29 +405,43 @@ __device__ __forceinline__ void tile_store_gated_bwd(const Args &A, const TileAd
                                                      const Rows<G> &r)
 {
     constexpr int R = G::R, VEC = G::VEC;
+    constexpr int CH = R < 8 ? R : 8;  // rows whose loads are in flight together
+    static_assert(R % CH == 0, "rows per thread: a multiple of 8, or fewer than 8");
     const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(A.out1), rh = ad.rsrc(A.hprev, -1), ri = ad.rsrc(A.c),
                  rg = ad.rsrc(A.a);
     const int nv = interior ? R : mk.n;  // the thread's rows j < nv exist
-    vec<VEC> c_last = splat<VEC>(0.0f);
-    if (nv > 0) c_last = gate_complement<VEC>(buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0));
+    vec<VEC> c_last = splat<VEC>(__builtin_inff());
+    if (nv > 0) c_last = buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
+    c_last = gate_complement<VEC>(c_last);
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        if (interior || j < mk.n) {
+    for (int j0 = 0; j0 < R; j0 += CH) {
+        vec<VEC> hp[CH], y[CH];
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {  // loads only: nothing in here waits for a load
+            const int j = j0 + q;
+            hp[q] = splat<VEC>(0.0f);
+            y[q] = splat<VEC>(0.0f);
+            if (interior || j < mk.n) {
+                y[q] = buf_ld<VEC>(ri, ad.toff, ad.soff(j));
+                if (interior || j < mk.nh) hp[q] = buf_ld<VEC>(rh, ad.toff, ad.soff(j));
+                else if (A.h0) hp[q] = ld<VEC>(A.h0 + col);  // row t == 0
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {
+            const int j = j0 + q;
             vec<VEC> c = c_last;
             if (j + 1 < R) c = (j + 1 < nv) ? r.a[j + 1] : c_last;
             const vec<VEC> g = splat<VEC>(1.0f) - c, d = r.b[j];
-            vec<VEC> hp = splat<VEC>(0.0f);
-            if (interior || j < mk.nh) hp = buf_ld<VEC>(rh, ad.toff, ad.soff(j));
-            else if (A.h0) hp = ld<VEC>(A.h0 + col);  // row t == 0
-            const vec<VEC> y = buf_ld<VEC>(ri, ad.toff, ad.soff(j));
-            const vec<VEC> i = impulse<VEC>(y, A.tau);
-            if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), d * (hp - i) * (g * c));
-            if (A.out1) {
-                vec<VEC> di = d * c;
-                if (A.tau) di = di * vfma<VEC>(-i, i, splat<VEC>(1.0f));
-                buf_st<VEC>(r1, ad.toff, ad.soff(j), di);
+            const vec<VEC> i = impulse<VEC>(y[q], A.tau);
+            const vec<VEC> dg = d * (hp[q] - i) * (g * c);
+            vec<VEC> di = d * c;
+            if (A.tau) di = di * vfma<VEC>(-i, i, splat<VEC>(1.0f));
+            if (interior || j < mk.n) {
+                if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), dg);
+                if (A.out1) buf_st<VEC>(r1, ad.toff, ad.soff(j), di);
+                if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, g * d);
             }
-            if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, g * d);
         }
     }
 }
