@@ -54,6 +54,10 @@ def _load():
         lib.linrec_oracle_gilr_backward.argtypes = [p, p, ctypes.c_int, p, p, p, p, p, p, p,
                                                     i64, i64, i64, i64, i64, i64]
         lib.linrec_oracle_gilr_backward.restype = None
+        lib.linrec_oracle_lstm_forward.argtypes = [p, p, p, p, p, p, p, i64, i64, i64, i64, i64, i64]
+        lib.linrec_oracle_lstm_forward.restype = None
+        lib.linrec_oracle_lstm_backward.argtypes = [p] * 13 + [i64] * 6
+        lib.linrec_oracle_lstm_backward.restype = None
         _lib = lib
     return _lib
 
@@ -307,3 +311,45 @@ def gilr_backward(g_pre, i_pre, h, h0, grad_h, tau=TAU_TANH, threads=1):
             _ptr(gg), _ptr(gi), _ptr(gh0), T, C, 0, T, c0, c1), C, threads)
     shp = np.asarray(g_pre).shape
     return gg.reshape(shp), gi.reshape(shp), gh0.reshape(shp[1:])
+
+
+# ---------------------------------------------------------------------------------------------
+# LSTM-cell form: c_t = f_t*c_{t-1} + i_t*z_t, h_t = o_t*c_t, gates from their pre-activations
+# ---------------------------------------------------------------------------------------------
+def lstm_forward(f_pre, i_pre, z_pre, o_pre, c0=None, threads=1):
+    """Returns (c, h) in fp64, both with ``f_pre``'s shape."""
+    a = [_f32_2d(v, n) for v, n in ((f_pre, "f_pre"), (i_pre, "i_pre"), (z_pre, "z_pre"), (o_pre, "o_pre"))]
+    if not all(v.shape == a[0].shape for v in a):
+        raise ValueError("the four pre-activation tensors must have the same shape")
+    T, C = a[0].shape
+    c0v = _f32_1d(c0, C, "c0")
+    state = np.zeros(C, np.float64) if c0v is None else c0v.astype(np.float64)
+    cref = np.empty((T, C), np.float64)
+    href = np.empty((T, C), np.float64)
+    lib = _load()
+    if T > 0 and C > 0:
+        _run_over_columns(lambda x0, x1: lib.linrec_oracle_lstm_forward(
+            _ptr(a[0]), _ptr(a[1]), _ptr(a[2]), _ptr(a[3]), _ptr(state), _ptr(cref), _ptr(href), T, C, 0, T, x0, x1),
+            C, threads)
+    shp = np.asarray(f_pre).shape
+    return cref.reshape(shp), href.reshape(shp)
+
+
+def lstm_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, threads=1):
+    """Returns (grad_f_pre, grad_i_pre, grad_z_pre, grad_o_pre, grad_c0) in fp64; ``c`` is the fp32 cell state."""
+    a = [_f32_2d(v, n) for v, n in ((f_pre, "f_pre"), (i_pre, "i_pre"), (z_pre, "z_pre"), (o_pre, "o_pre"),
+                                    (c, "c"), (grad_h, "grad_h"))]
+    if not all(v.shape == a[0].shape for v in a):
+        raise ValueError("all [T, C] tensors must have the same shape")
+    T, C = a[0].shape
+    c0v = _f32_1d(c0, C, "c0")
+    dstate = np.zeros(C, np.float64)
+    outs = [np.empty((T, C), np.float64) for _ in range(4)]
+    gc0 = np.zeros(C, np.float64)
+    lib = _load()
+    if T > 0 and C > 0:
+        _run_over_columns(lambda x0, x1: lib.linrec_oracle_lstm_backward(
+            _ptr(a[0]), _ptr(a[1]), _ptr(a[2]), _ptr(a[3]), _ptr(a[4]), _ptr(c0v), _ptr(a[5]), _ptr(dstate),
+            _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]), _ptr(outs[3]), _ptr(gc0), T, C, 0, T, x0, x1), C, threads)
+    shp = np.asarray(f_pre).shape
+    return tuple(o.reshape(shp) for o in outs) + (gc0.reshape(shp[1:]),)

@@ -30,7 +30,9 @@
  * the exact dyadic case g_pre == 0, the moving-average closed form, the
  * convex-hull invariant, reduction to the plain recurrence above through
  * scipy.special.expit / numpy.tanh, and central finite differences of its own
- * forward pass for every gradient.
+ * forward pass for every gradient.  The LSTM-cell form at the end is pinned
+ * the same way (exact dyadic case, closed forms, finite differences, reduction
+ * to the plain recurrence, planted mistakes; tests/test_lstm_oracle_pins.py).
  */
 #include <math.h>
 #include <stddef.h>
@@ -191,4 +193,81 @@ void linrec_oracle_gilr_backward(const float *g_pre, const float *i_pre, int tau
     }
 }
 
-int linrec_oracle_version(void) { return 2; }
+/*
+ * Cell of the GILR-LSTM (Section 3.2, "Linear surrogate RNNs": the LSTM equations with the
+ * gates computed from the surrogate state), the part after the matrix products.  From the
+ * pre-activations of the forget, input and output gates and of the candidate,
+ *
+ *   f_t = sigmoid(f_pre_t)   i_t = sigmoid(i_pre_t)   o_t = sigmoid(o_pre_t)   z_t = tanh(z_pre_t)
+ *   c_t = f_t * c_{t-1} + i_t * z_t                   h_t = o_t * c_t
+ *
+ * state[] carries c (c_0 on entry when t0 == 0).  cref, href: fp64 [T, C], rows [t0,t1) written.
+ */
+void linrec_oracle_lstm_forward(const float *f_pre, const float *i_pre, const float *z_pre,
+                                const float *o_pre, double *state, double *cref, double *href,
+                                int64_t T, int64_t C,
+                                int64_t t0, int64_t t1, int64_t c0, int64_t c1)
+{
+    (void)T;
+    for (int64_t t = t0; t < t1; ++t) {
+        const size_t row = (size_t)t * (size_t)C;
+        for (int64_t c = c0; c < c1; ++c) {
+            double f = sigmoid_f64((double)f_pre[row + c]);
+            double i = sigmoid_f64((double)i_pre[row + c]);
+            double o = sigmoid_f64((double)o_pre[row + c]);
+            double z = tanh((double)z_pre[row + c]);
+            double s = f * state[c] + i * z;
+            state[c] = s;
+            cref[row + c] = s;
+            href[row + c] = o * s;
+        }
+    }
+}
+
+/*
+ * Gradients of the cell with respect to its four pre-activations and c_0, for an upstream
+ * gradient e = dL/dh (c_t reaches the loss only through h_t and c_{t+1}).  With d_t the
+ * accumulated gradient nabla_{c_t} L (Section 2.2's reverse recurrence on the cell state):
+ *
+ *   d_t = e_t * o_t + f_{t+1} * d_{t+1}                    (no second term for t = T-1)
+ *   grad_o_pre_t = e_t * c_t * o_t (1 - o_t)
+ *   grad_f_pre_t = d_t * c_{t-1} * f_t (1 - f_t)           (c_{-1} = c0, zero if NULL)
+ *   grad_i_pre_t = d_t * z_t * i_t (1 - i_t)
+ *   grad_z_pre_t = d_t * i_t * (1 - z_t^2)
+ *   grad_c0      = f_0 * d_0
+ *
+ * cst is the fp32 cell state the forward pass stored; rows walked from t1-1 down to t0.
+ */
+void linrec_oracle_lstm_backward(const float *f_pre, const float *i_pre, const float *z_pre,
+                                 const float *o_pre, const float *cst, const float *c0v,
+                                 const float *e, double *dstate,
+                                 double *gf, double *gi, double *gz, double *go, double *gc0,
+                                 int64_t T, int64_t C,
+                                 int64_t t0, int64_t t1, int64_t c0, int64_t c1)
+{
+    for (int64_t t = t1 - 1; t >= t0; --t) {
+        const size_t row = (size_t)t * (size_t)C;
+        const float *fnext = (t + 1 < T) ? f_pre + (size_t)(t + 1) * (size_t)C : NULL;
+        const float *cprev = (t > 0) ? cst + (size_t)(t - 1) * (size_t)C : c0v;
+        for (int64_t c = c0; c < c1; ++c) {
+            double f = sigmoid_f64((double)f_pre[row + c]);
+            double i = sigmoid_f64((double)i_pre[row + c]);
+            double o = sigmoid_f64((double)o_pre[row + c]);
+            double z = tanh((double)z_pre[row + c]);
+            double d = (double)e[row + c] * o;
+            if (fnext)
+                d += sigmoid_f64((double)fnext[c]) * dstate[c];
+            dstate[c] = d;
+            go[row + c] = (double)e[row + c] * (double)cst[row + c] * (o * (1.0 - o));
+            gf[row + c] = d * (cprev ? (double)cprev[c] : 0.0) * (f * (1.0 - f));
+            gi[row + c] = d * z * (i * (1.0 - i));
+            gz[row + c] = d * i * (1.0 - z * z);
+        }
+    }
+    if (t0 == 0 && t1 > 0) {
+        for (int64_t c = c0; c < c1; ++c)
+            gc0[c] = sigmoid_f64((double)f_pre[c]) * dstate[c];
+    }
+}
+
+int linrec_oracle_version(void) { return 3; }
