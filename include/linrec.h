@@ -145,6 +145,39 @@ int linrec_gilr_backward(const float *g_pre, const float *i_pre, const float *h,
                          const float *grad_h, float *grad_g_pre, float *grad_i_pre, float *grad_h0,
                          int tau, int64_t T, int64_t B, int64_t n, void *stream);
 
+/*
+ * Cell of the GILR-LSTM, the part after its matrix products, with the activations applied inside
+ * the scan kernel (Section 3.2, "Linear surrogate RNNs": the LSTM whose gates are computed from
+ * the surrogate state, so that c_t depends only linearly on c_{t-1}):
+ *     f, i, o = sigmoid(f_pre, i_pre, o_pre)[t],   z = tanh(z_pre[t]),
+ *     c_t = f * c_{t-1} + i * z,                    h_t = o * c_t
+ *   f_pre, i_pre, z_pre, o_pre : [T, B, n] pre-activations.      c0 : [B, n] or NULL (zero).
+ *   c_out, h_out : [T, B, n] outputs; either may be NULL (o_pre may then be NULL too when h_out
+ *   is), not both.  c_out is what linrec_lstm_cell_backward needs.
+ * 24 bytes per element with both outputs.  No output may overlap any other tensor of the call
+ * (LINREC_ERR_ALIAS).  The forget gate is kept as 1 - f = sigmoid(-f_pre), as in the gated layer.
+ */
+int linrec_lstm_cell_forward(const float *f_pre, const float *i_pre, const float *z_pre,
+                             const float *o_pre, const float *c0, float *c_out, float *h_out,
+                             int64_t T, int64_t B, int64_t n, void *stream);
+
+/*
+ * Gradients of the cell with respect to its pre-activations and c0 for an upstream gradient
+ * e = grad_h = dL/dh_t (c_t reaches the loss through h_t and c_{t+1} only).  With
+ * d_t = e_t * o_t + f_{t+1} * d_{t+1}, d_{T-1} = e_{T-1} * o_{T-1} (Section 2.2 on the cell state):
+ *     grad_o_pre[t] = e_t * c[t] * o(1-o)           grad_f_pre[t] = d_t * c[t-1] * f(1-f)   (c[-1] = c0)
+ *     grad_i_pre[t] = d_t * z * i(1-i)              grad_z_pre[t] = d_t * i * (1 - z^2)
+ *     grad_c0       = f_0 * d_0
+ *   f_pre, i_pre, z_pre, o_pre, c, grad_h : [T, B, n] inputs; c is the forward pass' c_out.
+ *   grad_*_pre : [T, B, n] outputs, each may be NULL; grad_c0 : [B, n] or NULL.
+ * 40 bytes per element (six tensors in, four out).  No output may overlap any other tensor.
+ */
+int linrec_lstm_cell_backward(const float *f_pre, const float *i_pre, const float *z_pre,
+                              const float *o_pre, const float *c, const float *c0,
+                              const float *grad_h, float *grad_f_pre, float *grad_i_pre,
+                              float *grad_z_pre, float *grad_o_pre, float *grad_c0,
+                              int64_t T, int64_t B, int64_t n, void *stream);
+
 /* Process-wide tuning knobs (LINREC_OPT_*).  Environment variables LINREC_VARIANT
  * ("auto", "threephase", "lookback", "serial") and LINREC_TILE (integer id) give the
  * initial values.  Returns LINREC_OK or LINREC_ERR_OPTION.  Not thread-safe against
@@ -187,6 +220,15 @@ int linrec_validate_gilr_backward(const float *g_pre, const float *i_pre, const 
                                   const float *h0, const float *grad_h, const float *grad_g_pre,
                                   const float *grad_i_pre, const float *grad_h0, int tau,
                                   int64_t T, int64_t B, int64_t n);
+int linrec_validate_lstm_cell_forward(const float *f_pre, const float *i_pre, const float *z_pre,
+                                      const float *o_pre, const float *c0, const float *c_out,
+                                      const float *h_out, int64_t T, int64_t B, int64_t n);
+int linrec_validate_lstm_cell_backward(const float *f_pre, const float *i_pre, const float *z_pre,
+                                       const float *o_pre, const float *c, const float *c0,
+                                       const float *grad_h, const float *grad_f_pre,
+                                       const float *grad_i_pre, const float *grad_z_pre,
+                                       const float *grad_o_pre, const float *grad_c0,
+                                       int64_t T, int64_t B, int64_t n);
 
 /*
  * Measurement aid, not part of the recurrence: a pure streaming kernel built from the same

@@ -174,3 +174,25 @@ def make_gated(T, B, n, seed, device="cpu", gate_mean=0.0, gate_std=1.0, with_h0
     h0 = randn((B, n)) if with_h0 else None
     grad_h = randn(shape)
     return dict(T=T, B=B, n=n, g_pre=g_pre, i_pre=i_pre, h0=h0, grad_h=grad_h)
+
+
+#: LSTM-cell workloads (Section 3.2's GILR-LSTM cell): four pre-activation tensors in
+LSTM = {
+    "l4": dict(T=4096, B=16, n=1024, forget_mean=1.0, note="workload 4's shape; forget gates sigmoid(N(1,1))"),
+    "l2": dict(T=65536, B=4, n=256, forget_mean=2.0, note="workload 2's shape; forget gates sigmoid(N(2,1))"),
+}
+
+
+def make_lstm(T, B, n, seed, device="cpu", forget_mean=1.0, forget_std=1.0, with_c0=True):
+    """``f_pre ~ N(forget_mean, forget_std)``; ``i_pre, z_pre, o_pre, c0, grad_h ~ N(0,1)``."""
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(SEED_BASE + 7 * int(seed) + 5)
+    shape = (T, B, n)
+
+    def randn(s, mean=0.0, std=1.0):
+        t = torch.empty(s, dtype=torch.float32, device=dev)
+        return t.normal_(mean, std, generator=g)
+
+    return dict(T=T, B=B, n=n, f_pre=randn(shape, forget_mean, forget_std), i_pre=randn(shape), z_pre=randn(shape),
+                o_pre=randn(shape), c0=randn((B, n)) if with_c0 else None, grad_h=randn(shape))

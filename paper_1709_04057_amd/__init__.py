@@ -30,6 +30,8 @@ from .binding import (  # noqa: F401
     linrec_get_option,
     linrec_gilr_backward,
     linrec_gilr_forward,
+    linrec_lstm_cell_backward,
+    linrec_lstm_cell_forward,
     linrec_plan,
     linrec_release_workspace,
     linrec_set_option,

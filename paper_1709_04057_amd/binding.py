@@ -55,6 +55,14 @@ def lib():
         L.linrec_validate_gilr_forward.restype = ci
         L.linrec_validate_gilr_backward.argtypes = [p, p, p, p, p, p, p, p, ci, i64, i64, i64]
         L.linrec_validate_gilr_backward.restype = ci
+        L.linrec_lstm_cell_forward.argtypes = [p] * 7 + [i64, i64, i64, p]
+        L.linrec_lstm_cell_forward.restype = ci
+        L.linrec_lstm_cell_backward.argtypes = [p] * 12 + [i64, i64, i64, p]
+        L.linrec_lstm_cell_backward.restype = ci
+        L.linrec_validate_lstm_cell_forward.argtypes = [p] * 7 + [i64, i64, i64]
+        L.linrec_validate_lstm_cell_forward.restype = ci
+        L.linrec_validate_lstm_cell_backward.argtypes = [p] * 12 + [i64, i64, i64]
+        L.linrec_validate_lstm_cell_backward.restype = ci
         L.linrec_set_option.argtypes = [ci, i64]
         L.linrec_set_option.restype = ci
         L.linrec_get_option.argtypes = [ci]
@@ -211,6 +219,53 @@ def linrec_gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre=None, grad_i_pr
     _check(lib().linrec_gilr_backward(_ptr(g_pre), _ptr(i_pre), _ptr(h), _ptr(h0), _ptr(grad_h), _ptr(grad_g_pre),
                                       _ptr(grad_i_pre), _ptr(grad_h0), int(tau), T, B, n, _stream_ptr(stream)))
     return grad_g_pre, grad_i_pre, grad_h0
+
+
+def linrec_lstm_cell_forward(f_pre, i_pre, z_pre, o_pre, c0=None, c_out=None, h_out=None, stream=None,
+                             want_c=True, want_h=True):
+    """c[t] = f*c[t-1] + i*z, h[t] = o*c[t] with f, i, o = sigmoid(pre-activations), z = tanh(z_pre); returns (c, h)."""
+    import torch
+    T, B, n = _tbn(f_pre, "f_pre")
+    for name, t in (("i_pre", i_pre), ("z_pre", z_pre)) + ((("o_pre", o_pre),) if o_pre is not None else ()):
+        if tuple(_tbn(t, name)) != (T, B, n):
+            raise ValueError(f"{name} must have f_pre's shape")
+    _bn(c0, "c0", B, n)
+    if c_out is None and want_c:
+        c_out = torch.empty_like(f_pre)
+    if h_out is None and want_h:
+        h_out = torch.empty_like(f_pre)
+    for name, t in (("c_out", c_out), ("h_out", h_out)):
+        if t is not None and tuple(_tbn(t, name)) != (T, B, n):
+            raise ValueError(f"{name} must have f_pre's shape")
+    _check(lib().linrec_lstm_cell_forward(_ptr(f_pre), _ptr(i_pre), _ptr(z_pre), _ptr(o_pre), _ptr(c0), _ptr(c_out),
+                                          _ptr(h_out), T, B, n, _stream_ptr(stream)))
+    return c_out, h_out
+
+
+def linrec_lstm_cell_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grads=None, grad_c0=None, stream=None,
+                              want=(True, True, True, True), want_grad_c0=True):
+    """Gradients of the cell; returns (grad_f_pre, grad_i_pre, grad_z_pre, grad_o_pre, grad_c0).
+
+    ``grads`` may hold four preallocated tensors (or None entries); ``want[k] = False`` skips output k."""
+    import torch
+    T, B, n = _tbn(f_pre, "f_pre")
+    for name, t in (("i_pre", i_pre), ("z_pre", z_pre), ("o_pre", o_pre), ("c", c), ("grad_h", grad_h)):
+        if tuple(_tbn(t, name)) != (T, B, n):
+            raise ValueError(f"{name} must have f_pre's shape")
+    _bn(c0, "c0", B, n)
+    outs = list(grads) if grads is not None else [None] * 4
+    for k in range(4):
+        if outs[k] is None and want[k]:
+            outs[k] = torch.empty_like(grad_h)
+        if outs[k] is not None and tuple(_tbn(outs[k], "grads[%d]" % k)) != (T, B, n):
+            raise ValueError("gradient outputs must have f_pre's shape")
+    if grad_c0 is None and want_grad_c0:
+        grad_c0 = torch.empty((B, n), dtype=torch.float32, device=f_pre.device)
+    _bn(grad_c0, "grad_c0", B, n)
+    _check(lib().linrec_lstm_cell_backward(_ptr(f_pre), _ptr(i_pre), _ptr(z_pre), _ptr(o_pre), _ptr(c), _ptr(c0),
+                                           _ptr(grad_h), _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]), _ptr(outs[3]),
+                                           _ptr(grad_c0), T, B, n, _stream_ptr(stream)))
+    return outs[0], outs[1], outs[2], outs[3], grad_c0
 
 
 def linrec_set_option(option: int, value: int) -> None:

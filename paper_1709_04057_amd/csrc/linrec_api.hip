@@ -16,7 +16,7 @@
 
 namespace linrec {
 
-#define X(ID, VEC, R, WC, WT) hipError_t launch_tile_##ID(Kind, bool, bool, bool, const Args &, hipStream_t);
+#define X(ID, VEC, R, WC, WT) hipError_t launch_tile_##ID(Kind, bool, bool, int, const Args &, hipStream_t);
 LINREC_TILES(X)
 #undef X
 
@@ -28,11 +28,11 @@ static const TileDesc kTiles[NUM_TILES] = {
 
 const TileDesc &tile_desc(int id) { return kTiles[id - 1]; }
 
-hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, bool gated, const Args &A, hipStream_t s)
+hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, const Args &A, hipStream_t s)
 {
     switch (id) {
 #define X(ID, VEC, R, WC, WT) \
-    case ID: return launch_tile_##ID(kind, bwd, hp_late, gated, A, s);
+    case ID: return launch_tile_##ID(kind, bwd, hp_late, form, A, s);
         LINREC_TILES(X)
 #undef X
     default: return hipErrorInvalidValue;
@@ -189,8 +189,9 @@ std::mutex g_tuned_mu;
 std::map<TunedKey, TunedPlan> g_tuned;
 
 // Picks variant and tile, honouring the options where they apply to this problem.
-Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, bool gated = false)
+Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN)
 {
+    const bool gated = form != FORM_PLAIN;
     Plan p;
     p.variant = (int)opts().variant;
     if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
@@ -208,11 +209,13 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, bool gated = false)
         }
     }
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
+    if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 0;
     if (p.tile < 1 || p.tile > NUM_TILES) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
         // The gated form computes a sigmoid and a tanh per element before it can publish a summary:
         // 32-row threads (twice the resident workgroups of the 64-row shapes) hide that better.
         if (gated && T >= 2048 && C > 16) p.tile = C >= 2048 ? 21 : 18;
+        if (form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 18;  // (the cell has no 48- or 64-row kernels)
     }
     const TileDesc &d = kTiles[p.tile - 1];
     // per-thread byte offsets inside a tile are 32-bit, tickets of a call are 31-bit
@@ -226,13 +229,14 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, bool gated = false)
 
 // gated: the form of Section 3.1 (activations applied in the kernel); it exists as the single-pass
 // kernel of the one-column-per-thread tile shapes and as the serial kernel.
-int run(Args A, bool bwd, int vec, hipStream_t s, bool gated = false)
+int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN)
 {
-    Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd, gated);
+    const bool gated = form != FORM_PLAIN;
+    Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd, form);
     if (gated && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
-        if ((e = launch_serial(A, bwd, gated, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
+        if ((e = launch_serial(A, bwd, form, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
         return LINREC_OK;
     }
     const TileDesc &d = kTiles[plan.tile - 1];
@@ -258,11 +262,11 @@ int run(Args A, bool bwd, int vec, hipStream_t s, bool gated = false)
         A.aggP = (double *)ws.tp;
         A.aggS = A.aggP + kc;
         A.carry = A.aggS + kc;
-        if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, false, A, s)) != hipSuccess)
+        if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, FORM_PLAIN, A, s)) != hipSuccess)
             return hip_fail(e, "launch(reduce)");
         if ((e = launch_scan_summaries(A.aggP, A.aggS, bwd ? nullptr : A.h0, A.carry, A.K, A.C, s)) != hipSuccess)
             return hip_fail(e, "launch(scan_summaries)");
-        if ((e = launch_tile_kernel(plan.tile, KIND_FIXUP, bwd, false, false, A, s)) != hipSuccess)
+        if ((e = launch_tile_kernel(plan.tile, KIND_FIXUP, bwd, false, FORM_PLAIN, A, s)) != hipSuccess)
             return hip_fail(e, "launch(fixup)");
         return LINREC_OK;
     }
@@ -314,7 +318,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s, bool gated = false)
     A.persistent = plan.persistent < 0 ? ((bwd && !gated) ? 0 : 1) : plan.persistent;
     A.grid_cap = (int32_t)opts().grid_cap;
     A.trace = g_trace;
-    if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, gated, A, s)) != hipSuccess)
+    if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, form, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
     return LINREC_OK;
 }
@@ -388,7 +392,7 @@ extern "C" int linrec_gilr_forward(const float *g_pre, const float *i_pre, const
     A.tau = tau;
     A.T = T;
     A.C = C;
-    return run(A, false, 1, (hipStream_t)stream, true);
+    return run(A, false, 1, (hipStream_t)stream, FORM_GATED);
 }
 
 extern "C" int linrec_gilr_backward(const float *g_pre, const float *i_pre, const float *h, const float *h0,
@@ -421,7 +425,67 @@ extern "C" int linrec_gilr_backward(const float *g_pre, const float *i_pre, cons
     A.tau = tau;
     A.T = T;
     A.C = C;
-    return run(A, true, 1, s, true);
+    return run(A, true, 1, s, FORM_GATED);
+}
+
+extern "C" int linrec_lstm_cell_forward(const float *f_pre, const float *i_pre, const float *z_pre, const float *o_pre,
+                                        const float *c0, float *c_out, float *h_out, int64_t T, int64_t B, int64_t n,
+                                        void *stream)
+{
+    const int rc = linrec_validate_lstm_cell_forward(f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (T == 0 || C == 0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = f_pre;
+    A.b = i_pre;
+    A.c = z_pre;
+    A.d = o_pre;
+    A.h0 = c0;
+    A.out0 = c_out;
+    A.out1 = h_out;
+    A.T = T;
+    A.C = C;
+    return run(A, false, 1, (hipStream_t)stream, FORM_LSTM);
+}
+
+extern "C" int linrec_lstm_cell_backward(const float *f_pre, const float *i_pre, const float *z_pre, const float *o_pre,
+                                         const float *c, const float *c0, const float *grad_h, float *grad_f_pre,
+                                         float *grad_i_pre, float *grad_z_pre, float *grad_o_pre, float *grad_c0,
+                                         int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_lstm_cell_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre,
+                                                      grad_z_pre, grad_o_pre, grad_c0, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (C == 0) return LINREC_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (T == 0) {
+        if (grad_c0) {
+            const hipError_t e = launch_fill(grad_c0, 0.0f, C, s);
+            if (e != hipSuccess) return hip_fail(e, "launch(fill)");
+        }
+        return LINREC_OK;
+    }
+    if (!grad_f_pre && !grad_i_pre && !grad_z_pre && !grad_o_pre && !grad_c0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = f_pre;
+    A.b = grad_h;
+    A.c = i_pre;
+    A.d = z_pre;
+    A.e = o_pre;
+    A.hprev = c;
+    A.h0 = c0;
+    A.out0 = grad_f_pre;
+    A.out1 = grad_i_pre;
+    A.out2 = grad_z_pre;
+    A.out3 = grad_o_pre;
+    A.gh0 = grad_c0;
+    A.T = T;
+    A.C = C;
+    return run(A, true, 1, s, FORM_LSTM);
 }
 
 extern "C" int linrec_set_option(int option, int64_t value)

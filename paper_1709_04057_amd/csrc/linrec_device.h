@@ -114,7 +114,8 @@ __device__ __forceinline__ vec<N> splat(float x)
 // itself to fp32 would be an error of 2^-25 against a complement that may be 1e-6, i.e. a wrong
 // decay rate, which adds up over the 1/c steps such a gate remembers.
 // ---------------------------------------------------------------------------------------------
-enum Form { FORM_PLAIN = 0, FORM_GATED = 1 };
+// FORM_LSTM is the cell of Section 3.2's GILR-LSTM, c_t = f_t*c_{t-1} + i_t*z_t, h_t = o_t*c_t, with the forget
+// gate in the same complement form.  (enum Form: linrec_launch.h)
 
 template <int FORM, int N>
 __device__ __forceinline__ vec<N> step(vec<N> a, vec<N> s, vec<N> b)
@@ -144,6 +145,25 @@ __device__ __forceinline__ void gate_pair(float z, float &g, float &c)
     const bool pos = z >= 0.0f;
     g = pos ? big : small;
     c = pos ? small : big;  // (a NaN pre-activation gives NaN in both)
+}
+// sigmoid(z) and its complement, elementwise
+template <int N>
+__device__ __forceinline__ void gate_both(vec<N> z, vec<N> &g, vec<N> &c)
+{
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        float gg, cc;
+        gate_pair(z[i], gg, cc);
+        g[i] = gg;
+        c[i] = cc;
+    }
+}
+template <int N>
+__device__ __forceinline__ vec<N> gate_value(vec<N> z)
+{
+    vec<N> g, c;
+    gate_both<N>(z, g, c);
+    return g;
 }
 template <int N>
 __device__ __forceinline__ vec<N> gate_complement(vec<N> z)
@@ -296,17 +316,22 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
 {
     constexpr int R = G::R, VEC = G::VEC;
     const rsrc_t ra = ad.rsrc(A.a, BWD ? +1 : 0), rb = ad.rsrc(A.b);
-    // What a masked step holds BEFORE the activations are applied: the gated form runs them over every
+    // What a masked step holds BEFORE the activations are applied: the gated forms run them over every
     // row after all loads have been issued (inside the per-row conditions they would make each load
     // wait for the one before), and sigmoid(-(+inf)) = 0, sigmoid(-(-inf)) = 1 give the identity
     // and the forgetting step.
     const float raw_identity = FORM == FORM_PLAIN ? 1.0f : __builtin_inff();
     const float raw_forget = FORM == FORM_PLAIN ? 0.0f : -__builtin_inff();
+    // FORM_LSTM has a third operand per row: forward the candidate's pre-activation (A.c), backward
+    // the output gate's (A.e); the addend is sigmoid(i_pre)*tanh(z_pre), resp. grad_h*sigmoid(o_pre).
+    vec<VEC> third[FORM == FORM_LSTM ? R : 1];
+    const rsrc_t r3 = ad.rsrc(FORM == FORM_LSTM ? (BWD ? A.e : A.c) : A.b);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        vec<VEC> va = splat<VEC>(raw_identity), vb = splat<VEC>(0.0f);
+        vec<VEC> va = splat<VEC>(raw_identity), vb = splat<VEC>(0.0f), v3 = splat<VEC>(0.0f);
         if (interior || j < mk.n) {
             vb = buf_ld<VEC>(rb, ad.toff, ad.soff(j));
+            if constexpr (FORM == FORM_LSTM) v3 = buf_ld<VEC>(r3, ad.toff, ad.soff(j));
             if constexpr (!BWD) {
                 va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
             } else {
@@ -316,12 +341,22 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
         }
         r.a[j] = va;
         r.b[j] = vb;
+        if constexpr (FORM == FORM_LSTM) third[j] = v3;
     }
     if constexpr (FORM == FORM_GATED) {
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             r.a[j] = gate_complement<VEC>(r.a[j]);
             if constexpr (!BWD) r.b[j] = r.a[j] * impulse<VEC>(r.b[j], A.tau);
+        }
+    }
+    if constexpr (FORM == FORM_LSTM) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            r.a[j] = gate_complement<VEC>(r.a[j]);
+            // (masked rows hold b = 0, and sigmoid(0)*tanh(0) = 0, 0*sigmoid(0) = 0)
+            if constexpr (!BWD) r.b[j] = gate_value<VEC>(r.b[j]) * impulse<VEC>(third[j], 1);
+            else r.b[j] = r.b[j] * gate_value<VEC>(third[j]);
         }
     }
 }
@@ -441,6 +476,96 @@ __device__ __forceinline__ void tile_store_gated_bwd(const Args &A, const TileAd
                 if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), dg);
                 if (A.out1) buf_st<VEC>(r1, ad.toff, ad.soff(j), di);
                 if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, g * d);
+            }
+        }
+    }
+}
+
+// Forward epilogue of the LSTM cell: r.b[j] = c_t; the output gate's pre-activation is loaded here, in
+// chunks, and c_t and h_t = sigmoid(o_pre)*c_t are stored (either output may be absent).
+template <class G>
+__device__ __forceinline__ void tile_store_lstm_fwd(const Args &A, const TileAddr<G, false> &ad,
+                                                    const RowMask<G, false> &mk, bool interior, const Rows<G> &r)
+{
+    constexpr int R = G::R, VEC = G::VEC;
+    constexpr int CH = R < 8 ? R : 8;
+    static_assert(R % CH == 0, "rows per thread: a multiple of 8, or fewer than 8");
+    const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(A.out1), ro = ad.rsrc(A.d);
+#pragma unroll
+    for (int j0 = 0; j0 < R; j0 += CH) {
+        vec<VEC> op[CH];
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {
+            op[q] = splat<VEC>(0.0f);
+            if (A.out1 && (interior || j0 + q < mk.n)) op[q] = buf_ld<VEC>(ro, ad.toff, ad.soff(j0 + q));
+        }
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {
+            const int j = j0 + q;
+            const vec<VEC> h = gate_value<VEC>(op[q]) * r.b[j];
+            if (interior || j < mk.n) {
+                if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), r.b[j]);
+                if (A.out1) buf_st<VEC>(r1, ad.toff, ad.soff(j), h);
+            }
+        }
+    }
+}
+
+// Backward epilogue of the LSTM cell.  After the rescan r.b[j] = d_t (accumulated gradient of c_t) and
+// r.a[j] is the forget gate's complement of row t+1, so the row's own is r.a[j+1] (see the gated form).
+//   grad_o_pre = grad_h * c_t * o(1-o)         grad_f_pre = d * c_{t-1} * f(1-f)      (c_{-1} = c0)
+//   grad_i_pre = d * z * i(1-i)                grad_z_pre = d * i * (1 - z^2)          grad_c0 = f_0 * d_0
+// Everything but d and f is loaded here, in chunks of rows, after the rescan.
+template <class G>
+__device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAddr<G, true> &ad,
+                                                    const RowMask<G, true> &mk, int64_t col, bool interior,
+                                                    const Rows<G> &r)
+{
+    constexpr int R = G::R, VEC = G::VEC;
+    constexpr int CH = R < 8 ? R : 8;
+    static_assert(R % CH == 0, "rows per thread: a multiple of 8, or fewer than 8");
+    const rsrc_t rf = ad.rsrc(A.out0), ri = ad.rsrc(A.out1), rz = ad.rsrc(A.out2), ro = ad.rsrc(A.out3);
+    const rsrc_t rc = ad.rsrc(A.hprev), rcp = ad.rsrc(A.hprev, -1), rip = ad.rsrc(A.c), rzp = ad.rsrc(A.d),
+                 rop = ad.rsrc(A.e), rgh = ad.rsrc(A.b), rg = ad.rsrc(A.a);
+    const int nv = interior ? R : mk.n;
+    vec<VEC> c_last = splat<VEC>(__builtin_inff());
+    if (nv > 0) c_last = buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
+    c_last = gate_complement<VEC>(c_last);
+#pragma unroll
+    for (int j0 = 0; j0 < R; j0 += CH) {
+        vec<VEC> ct[CH], cp[CH], ip[CH], zp[CH], op[CH], gh[CH];
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {  // loads only
+            const int j = j0 + q;
+            ct[q] = cp[q] = ip[q] = zp[q] = op[q] = gh[q] = splat<VEC>(0.0f);
+            if (interior || j < mk.n) {
+                ip[q] = buf_ld<VEC>(rip, ad.toff, ad.soff(j));
+                zp[q] = buf_ld<VEC>(rzp, ad.toff, ad.soff(j));
+                if (A.out3) {
+                    ct[q] = buf_ld<VEC>(rc, ad.toff, ad.soff(j));
+                    op[q] = buf_ld<VEC>(rop, ad.toff, ad.soff(j));
+                    gh[q] = buf_ld<VEC>(rgh, ad.toff, ad.soff(j));
+                }
+                if (interior || j < mk.nh) cp[q] = buf_ld<VEC>(rcp, ad.toff, ad.soff(j));
+                else if (A.h0) cp[q] = ld<VEC>(A.h0 + col);  // row t == 0
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {
+            const int j = j0 + q;
+            vec<VEC> cf = c_last;
+            if (j + 1 < R) cf = (j + 1 < nv) ? r.a[j + 1] : c_last;
+            const vec<VEC> f = splat<VEC>(1.0f) - cf, d = r.b[j];
+            vec<VEC> ig, ic, og, oc;
+            gate_both<VEC>(ip[q], ig, ic);
+            gate_both<VEC>(op[q], og, oc);
+            const vec<VEC> z = impulse<VEC>(zp[q], 1);
+            if (interior || j < mk.n) {
+                if (A.out0) buf_st<VEC>(rf, ad.toff, ad.soff(j), d * cp[q] * (f * cf));
+                if (A.out1) buf_st<VEC>(ri, ad.toff, ad.soff(j), d * z * (ig * ic));
+                if (A.out2) buf_st<VEC>(rz, ad.toff, ad.soff(j), d * ig * vfma<VEC>(-z, z, splat<VEC>(1.0f)));
+                if (A.out3) buf_st<VEC>(ro, ad.toff, ad.soff(j), gh[q] * ct[q] * (og * oc));
+                if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, f * d);
             }
         }
     }
@@ -901,6 +1026,10 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     if constexpr (BWD && FORM == FORM_GATED) {
         __builtin_amdgcn_sched_barrier(0);  // the epilogue's loads stay behind the rescan
         tile_store_gated_bwd<G>(A, ad, mk, col, interior, r);
+    } else if constexpr (FORM == FORM_LSTM) {
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (BWD) tile_store_lstm_bwd<G>(A, ad, mk, col, interior, r);
+        else tile_store_lstm_fwd<G>(A, ad, mk, interior, r);
     } else {
         if constexpr (BWD && HP_LATE) {
             // keep these loads behind the rescan: they take over the registers lambda occupied until now

@@ -25,10 +25,15 @@ struct Args {
     const float *a;      // lambda (gated form: the gate pre-activations g_pre)      [T, C]
     const float *b;      // forward: x (gated: i_pre);  backward: grad_h            [T, C]
     const float *c;      // gated form, backward: the impulse pre-activations i_pre  [T, C]
+                         // LSTM cell: forward z_pre (a = f_pre, b = i_pre), backward i_pre (a = f_pre, b = grad_h)
+    const float *d;      // LSTM cell: forward o_pre, backward z_pre
+    const float *e;      // LSTM cell, backward: o_pre
     const float *hprev;  // backward: h (forward output);  forward: unused
     const float *h0;     // [C] or nullptr
     float *out0;         // forward: h_out;  backward: grad_x (gated: grad_g_pre) (may be nullptr)
     float *out1;         // backward: grad_lambda (gated: grad_i_pre) (may be nullptr)
+                         // LSTM cell: forward out0 = c, out1 = h; backward out0..3 = grad_f/i/z/o_pre
+    float *out2, *out3;
     float *gh0;          // backward: grad_h0 [C] (may be nullptr)
     int64_t T, C;
     int64_t K;           // tiles (look-back) or chunks (three-phase) along time
@@ -48,6 +53,7 @@ struct Args {
 };
 
 enum Kind { KIND_REDUCE = 0, KIND_FIXUP = 1, KIND_LOOKBACK = 2 };
+enum Form { FORM_PLAIN = 0, FORM_GATED = 1, FORM_LSTM = 2 };
 
 struct TileDesc {
     int vec, r, wc, wt;
@@ -90,12 +96,13 @@ const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 // Launches kernel `kind` for tile shape `id` with grid A.K * A.G.  hp_late (look-back, backward):
 // load h after the rescan instead of together with lambda and grad_h.  gated: the form of Section
 // 3.1 with sigmoid / tau applied in the kernel (look-back kernels of one-column-per-thread shapes
-// only; hipErrorInvalidValue otherwise).
-hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, bool gated, const Args &A, hipStream_t s);
+// only; hipErrorInvalidValue otherwise).  `form` is FORM_PLAIN, FORM_GATED or FORM_LSTM (the latter
+// for shapes of at most 32 rows per thread).
+hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, const Args &A, hipStream_t s);
 
 hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const float *h0, double *carry, int64_t K,
                                  int64_t C, hipStream_t s);
-hipError_t launch_serial(const Args &A, bool bwd, bool gated, hipStream_t s);
+hipError_t launch_serial(const Args &A, bool bwd, int form, hipStream_t s);
 hipError_t launch_fill(float *p, float value, int64_t n, hipStream_t s);
 hipError_t launch_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
                                int64_t n, hipStream_t s);

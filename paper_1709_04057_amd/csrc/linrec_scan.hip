@@ -173,6 +173,54 @@ __global__ __launch_bounds__(256) void k_serial_gated_bwd(const float *__restric
     if (gh0) gh0[c] = g0 * d;
 }
 
+// The LSTM cell of Section 3.2 (c_t = f_t*c_{t-1} + i_t*z_t, h_t = o_t*c_t), serial over the sequence length.
+__global__ __launch_bounds__(256) void k_serial_lstm_fwd(const float *__restrict__ f_pre, const float *__restrict__ i_pre,
+                                                         const float *__restrict__ z_pre, const float *__restrict__ o_pre,
+                                                         const float *__restrict__ c0, float *c_out, float *h_out,
+                                                         int64_t T, int64_t C)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s = c0 ? c0[c] : 0.0f;
+#pragma unroll 2
+    for (int64_t t = 0; t < T; ++t) {
+        const vec<1> cf = gate_complement<1>(vec<1>(f_pre[t * C + c]));
+        const vec<1> x = gate_value<1>(vec<1>(i_pre[t * C + c])) * impulse<1>(vec<1>(z_pre[t * C + c]), 1);
+        s = step<FORM_LSTM, 1>(cf, vec<1>(s), x)[0];
+        if (c_out) c_out[t * C + c] = s;
+        if (h_out) h_out[t * C + c] = gate_value<1>(vec<1>(o_pre[t * C + c]))[0] * s;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_serial_lstm_bwd(const float *__restrict__ f_pre, const float *__restrict__ i_pre,
+                                                         const float *__restrict__ z_pre, const float *__restrict__ o_pre,
+                                                         const float *__restrict__ cst, const float *__restrict__ c0,
+                                                         const float *__restrict__ e, float *gf, float *gi, float *gz,
+                                                         float *go, float *gc0, int64_t T, int64_t C)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float d = 0.0f, cnext = 1.0f, f0 = 0.0f;  // cnext: complement of the forget gate one row ahead
+    for (int64_t t = T - 1; t >= 0; --t) {
+        vec<1> og, oc, ig, ic;
+        gate_both<1>(vec<1>(o_pre[t * C + c]), og, oc);
+        gate_both<1>(vec<1>(i_pre[t * C + c]), ig, ic);
+        const float et = e[t * C + c];
+        d = step<FORM_LSTM, 1>(vec<1>(cnext), vec<1>(d), vec<1>(et * og[0]))[0];
+        const float cf = gate_complement<1>(vec<1>(f_pre[t * C + c]))[0];
+        const float f = 1.0f - cf;
+        const float z = tanh_f32(z_pre[t * C + c]);
+        const float cp = (t > 0) ? cst[(t - 1) * C + c] : (c0 ? c0[c] : 0.0f);
+        if (gf) gf[t * C + c] = d * cp * (f * cf);
+        if (gi) gi[t * C + c] = d * z * (ig[0] * ic[0]);
+        if (gz) gz[t * C + c] = d * ig[0] * fmaf(-z, z, 1.0f);
+        if (go) go[t * C + c] = et * cst[t * C + c] * (og[0] * oc[0]);
+        cnext = cf;
+        f0 = f;
+    }
+    if (gc0) gc0[c] = f0 * d;
+}
+
 __global__ void k_fill(float *p, float value, int64_t n)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
@@ -227,10 +275,19 @@ hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const f
     return hipGetLastError();
 }
 
-hipError_t launch_serial(const Args &A, bool bwd, bool gated, hipStream_t s)
+hipError_t launch_serial(const Args &A, bool bwd, int form, hipStream_t s)
 {
     const unsigned grid = (unsigned)((A.C + 255) / 256);
-    if (gated) {
+    if (form == FORM_LSTM) {
+        if (!bwd)
+            hipLaunchKernelGGL(k_serial_lstm_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.c, A.d, A.h0, A.out0, A.out1, A.T,
+                               A.C);
+        else
+            hipLaunchKernelGGL(k_serial_lstm_bwd, dim3(grid), dim3(256), 0, s, A.a, A.c, A.d, A.e, A.hprev, A.h0, A.b,
+                               A.out0, A.out1, A.out2, A.out3, A.gh0, A.T, A.C);
+        return hipGetLastError();
+    }
+    if (form == FORM_GATED) {
         if (!bwd)
             hipLaunchKernelGGL(k_serial_gated_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.h0, A.out0, A.tau, A.T, A.C);
         else

@@ -35,10 +35,15 @@ static int64_t resident_capacity(const void *kernel, int threads, int cap_per_cu
 }
 
 template <class G>
-static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, bool gated, const Args &A, hipStream_t s)
+static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, const Args &A, hipStream_t s)
 {
     const dim3 grid((unsigned)(A.K * A.G)), block(G::THREADS);
-    if (gated && (kind != KIND_LOOKBACK || G::VEC != 1)) return hipErrorInvalidValue;
+    // the forms with in-kernel activations exist as look-back kernels of one-column-per-thread shapes
+    // (the LSTM cell, which has three operands per row in flight, of at most 32 rows per thread)
+    constexpr bool kHasGated = G::VEC == 1, kHasLstm = G::VEC == 1 && G::R <= 32;
+    if (form != FORM_PLAIN && kind != KIND_LOOKBACK) return hipErrorInvalidValue;
+    if ((form == FORM_GATED && !kHasGated) || (form == FORM_LSTM && !kHasLstm) || form < FORM_PLAIN || form > FORM_LSTM)
+        return hipErrorInvalidValue;
     switch (kind) {
     case KIND_REDUCE:
         if (bwd) hipLaunchKernelGGL((k_reduce<G, true>), grid, block, 0, s, A);
@@ -52,8 +57,13 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, bool gated, cons
         // persistent workgroups: as many as the device holds at once, never more than there are tiles
         void (*kern)(const Args) = !bwd ? k_lookback<G, false, false>
                                         : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
-        if constexpr (G::VEC == 1) {
-            if (gated) kern = bwd ? k_lookback<G, true, true, FORM_GATED> : k_lookback<G, false, false, FORM_GATED>;
+        if constexpr (kHasGated) {
+            if (form == FORM_GATED)
+                kern = bwd ? k_lookback<G, true, true, FORM_GATED> : k_lookback<G, false, false, FORM_GATED>;
+        }
+        if constexpr (kHasLstm) {
+            if (form == FORM_LSTM)
+                kern = bwd ? k_lookback<G, true, true, FORM_LSTM> : k_lookback<G, false, false, FORM_LSTM>;
         }
         const int64_t cap = resident_capacity(reinterpret_cast<const void *>(kern), G::THREADS, A.grid_cap);
         const dim3 pgrid((unsigned)(A.persistent ? std::min<int64_t>(A.K * A.G, cap) : A.K * A.G));
@@ -72,10 +82,10 @@ LINREC_TILES(X)
 #undef X
 #define LINREC_TILE_TYPE LINREC_CAT(TileOf, LINREC_TILE_ID)<0>::type
 
-hipError_t LINREC_CAT(launch_tile_, LINREC_TILE_ID)(Kind kind, bool bwd, bool hp_late, bool gated, const Args &A,
+hipError_t LINREC_CAT(launch_tile_, LINREC_TILE_ID)(Kind kind, bool bwd, bool hp_late, int form, const Args &A,
                                                     hipStream_t s)
 {
-    return launch_for<LINREC_TILE_TYPE>(kind, bwd, hp_late, gated, A, s);
+    return launch_for<LINREC_TILE_TYPE>(kind, bwd, hp_late, form, A, s);
 }
 
 }  // namespace linrec

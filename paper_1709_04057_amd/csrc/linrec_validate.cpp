@@ -103,6 +103,52 @@ extern "C" int linrec_validate_gilr_backward(const float *g_pre, const float *i_
     return LINREC_OK;
 }
 
+// No output of the cell entry points may share memory with any other tensor of the call.
+static int check_disjoint(const float *const *outs, const int64_t *out_len, int n_out, const float *const *ins,
+                          const int64_t *in_len, int n_in)
+{
+    for (int o = 0; o < n_out; ++o) {
+        for (int i = 0; i < n_in; ++i)
+            if (overlaps(outs[o], out_len[o], ins[i], in_len[i])) return LINREC_ERR_ALIAS;
+        for (int p = o + 1; p < n_out; ++p)
+            if (overlaps(outs[o], out_len[o], outs[p], out_len[p])) return LINREC_ERR_ALIAS;
+    }
+    return LINREC_OK;
+}
+
+extern "C" int linrec_validate_lstm_cell_forward(const float *f_pre, const float *i_pre, const float *z_pre,
+                                                 const float *o_pre, const float *c0, const float *c_out,
+                                                 const float *h_out, int64_t T, int64_t B, int64_t n)
+{
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (E == 0) return LINREC_OK;
+    if (!f_pre || !i_pre || !z_pre || (h_out && !o_pre) || (!c_out && !h_out)) return LINREC_ERR_NULL;
+    const float *outs[2] = {c_out, h_out};
+    const int64_t out_len[2] = {E, E};
+    const float *ins[5] = {f_pre, i_pre, z_pre, o_pre, c0};
+    const int64_t in_len[5] = {E, E, E, E, C};
+    return check_disjoint(outs, out_len, 2, ins, in_len, 5);
+}
+
+extern "C" int linrec_validate_lstm_cell_backward(const float *f_pre, const float *i_pre, const float *z_pre,
+                                                  const float *o_pre, const float *c, const float *c0,
+                                                  const float *grad_h, const float *grad_f_pre,
+                                                  const float *grad_i_pre, const float *grad_z_pre,
+                                                  const float *grad_o_pre, const float *grad_c0, int64_t T, int64_t B,
+                                                  int64_t n)
+{
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (C == 0 || T == 0) return LINREC_OK;
+    if (!f_pre || !i_pre || !z_pre || !o_pre || !c || !grad_h) return LINREC_ERR_NULL;
+    const float *outs[5] = {grad_f_pre, grad_i_pre, grad_z_pre, grad_o_pre, grad_c0};
+    const int64_t out_len[5] = {E, E, E, E, C};
+    const float *ins[7] = {f_pre, i_pre, z_pre, o_pre, c, grad_h, c0};
+    const int64_t in_len[7] = {E, E, E, E, E, E, C};
+    return check_disjoint(outs, out_len, 5, ins, in_len, 7);
+}
+
 extern "C" const char *linrec_status_string(int status)
 {
     switch (status) {
@@ -117,4 +163,4 @@ extern "C" const char *linrec_status_string(int status)
     }
 }
 
-extern "C" int linrec_version(void) { return 101; }
+extern "C" int linrec_version(void) { return 102; }

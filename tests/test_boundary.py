@@ -93,6 +93,31 @@ def test_validate_gilr(L):
     assert L.linrec_gilr_backward(None, None, None, None, None, None, None, None, 1, 10, 0, 2, None) == 0
 
 
+def test_validate_lstm_cell(L):
+    vf, vb = L.linrec_validate_lstm_cell_forward, L.linrec_validate_lstm_cell_backward
+    B0 = [0x10000000 + i * 0x1000000 for i in range(13)]
+    P = [_p(a) for a in B0]
+    assert vf(P[0], P[1], P[2], P[3], P[4], P[5], P[6], 1000, 4, 8) == 0
+    assert vf(P[0], P[1], P[2], None, None, P[5], None, 1000, 4, 8) == 0       # cell state only: no o_pre needed
+    assert vf(P[0], P[1], P[2], P[3], None, None, P[6], 1000, 4, 8) == 0       # h only
+    assert vf(P[0], P[1], P[2], None, None, P[5], P[6], 1000, 4, 8) == -1      # h wanted but no o_pre
+    assert vf(P[0], P[1], P[2], P[3], None, None, None, 1000, 4, 8) == -1      # no output at all
+    assert vf(P[0], P[1], None, P[3], None, P[5], P[6], 1000, 4, 8) == -1
+    assert vf(P[0], P[1], P[2], P[3], None, P[1], P[6], 1000, 4, 8) == -3      # c_out on i_pre
+    assert vf(P[0], P[1], P[2], P[3], None, P[5], P[5], 1000, 4, 8) == -3      # outputs share memory
+    assert vf(P[0], P[1], P[2], P[3], None, P[5], P[6], 1000, -4, 8) == -2
+    assert vf(None, None, None, None, None, None, None, 0, 4, 8) == 0
+    ok = P[:12]
+    assert vb(*ok, 1000, 4, 8) == 0
+    assert vb(*P[:7], None, None, None, None, None, 1000, 4, 8) == 0           # every output optional
+    assert vb(P[0], P[1], P[2], P[3], None, P[5], P[6], P[7], None, None, None, None, 1000, 4, 8) == -1  # c required
+    assert vb(*P[:7], P[6], None, None, None, None, 1000, 4, 8) == -3          # output on grad_h
+    assert vb(*P[:7], P[7], P[7], None, None, None, 1000, 4, 8) == -3          # outputs share memory
+    assert vb(*P[:7], P[7], P[8], P[9], P[4], None, 1000, 4, 8) == -3          # output on the cell state
+    assert L.linrec_lstm_cell_forward(P[0], P[1], P[2], P[3], None, P[0], P[6], 10, 2, 2, None) == -3
+    assert L.linrec_lstm_cell_backward(*([None] * 12), 10, 0, 2, None) == 0
+
+
 def test_entry_points_validate_before_touching_the_gpu(L):
     # invalid arguments must come back as error codes even on a machine without a GPU
     assert L.linrec_forward(None, _p(A1), None, _p(A3), 10, 2, 2, None) == -1
