@@ -47,6 +47,9 @@ def parse():
                     help="time the gated (GILR) entry points on this workload instead (sigmoid / tanh applied in the "
                          "scan kernel: 12 B/element forward, 24 backward), next to the unfused sequence "
                          "elementwise kernels + linrec_forward")
+    ap.add_argument("--lstm", default="", choices=["", "l2", "l4"],
+                    help="time the LSTM-cell entry points on this workload instead (24 B/element forward, 40 backward), "
+                         "next to the unfused forward")
     ap.add_argument("--probe", action="store_true",
                     help="also time the library's pure streaming kernels (copy, 2-in/1-out, 3-in/2-out) on arrays "
                          "of the workload's size; the copy doubles as the calibration kernel for byte counters")
@@ -210,6 +213,74 @@ def gated_bench(args, lr, torch, wl):
     print(json.dumps(out), flush=True)
 
 
+def lstm_bench(args, lr, torch, wl):
+    """One JSON line for the LSTM-cell entry points (Section 3.2's GILR-LSTM cell)."""
+    dev = "cuda:0"
+    spec = wl.LSTM[args.lstm]
+    T, B, n = spec["T"], spec["B"], spec["n"]
+    E = T * B * n
+    inp = wl.make_lstm(T, B, n, seed=sum(map(ord, args.lstm)), device=dev, forget_mean=spec["forget_mean"])
+    pre = [inp[k] for k in ("f_pre", "i_pre", "z_pre", "o_pre")]
+    c0, e = inp["c0"], inp["grad_h"]
+    c, h = torch.empty_like(e), torch.empty_like(e)
+    grads = [torch.empty_like(e) for _ in range(4)]
+    gc0 = torch.empty((B, n), device=dev)
+    lam, x, og = torch.empty_like(e), torch.empty_like(e), torch.empty_like(e)
+    stream = torch.cuda.current_stream()
+    K = args.steps
+
+    def fused_fwd():
+        lr.linrec_lstm_cell_forward(*pre, c0, c_out=c, h_out=h, stream=stream)
+
+    def fused_bwd():
+        lr.linrec_lstm_cell_backward(*pre, c, c0, e, grads=grads, grad_c0=gc0, stream=stream)
+
+    def unfused_fwd():  # 6 elementwise kernels around the plain scan
+        torch.sigmoid(pre[0], out=lam)
+        torch.sigmoid(pre[1], out=x)
+        torch.tanh(pre[2], out=og)
+        torch.mul(x, og, out=x)
+        lr.linrec_forward(lam, x, c0, h_out=c, stream=stream)
+        torch.sigmoid(pre[3], out=og)
+        torch.mul(og, c, out=h)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(K + 1)]
+        torch.cuda.synchronize()
+        ev[0].record(stream)
+        for i in range(K):
+            fn()
+            ev[i + 1].record(stream)
+        torch.cuda.synchronize()
+        ms = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(K))
+        return sum(ms) / K, ms[0]
+
+    f_avg, f_min = timed(fused_fwd)
+    b_avg, b_min = timed(fused_bwd)
+    u_avg, u_min = timed(unfused_fwd)
+    lr.linrec_check(stream)
+    gbs = lambda bpe, ms: bpe * E / (ms * 1e-3) / 1e9
+    out = {
+        "metric": "LSTM-cell linrec fwd+bwd elements/sec and achieved HBM GB/s (% of MI355X peak)",
+        "value": E / ((f_avg + b_avg) * 1e-3), "unit": "elements/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
+        "ms_per_step": f_avg + b_avg, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.lstm}: LSTM cell forward+backward, fp32, time-major [T={T}, B={B}, n={n}]; "
+                               + spec["note"]},
+        "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(24.0, f_avg), "frac_of_peak": gbs(24.0, f_avg) / HBM_PEAK_GBS},
+        "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(40.0, b_avg), "frac_of_peak": gbs(40.0, b_avg) / HBM_PEAK_GBS},
+        "unfused_forward": {"avg_ms": u_avg, "min_ms": u_min, "speedup_of_fused": u_avg / f_avg,
+                            "what": "torch sigmoid x3, tanh, mul x2 around linrec_forward"},
+        "roofline": {"bound": "hbm", "kernel": "LSTM-cell backward pass (look-back kernel)", "achieved": gbs(40.0, b_avg),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(40.0, b_avg) / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_element": 40.0, "algorithmic_bytes": 40.0 * E, "avg_ms": b_avg},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(out), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -243,6 +314,9 @@ def main():
 
     if args.gated:
         gated_bench(args, lr, torch, wl)
+        return
+    if args.lstm:
+        lstm_bench(args, lr, torch, wl)
         return
 
     inp = wl.make_inputs(args.config, device=dev)

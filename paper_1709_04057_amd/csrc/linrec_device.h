@@ -324,14 +324,21 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
     const float raw_forget = FORM == FORM_PLAIN ? 0.0f : -__builtin_inff();
     // FORM_LSTM has a third operand per row: forward the candidate's pre-activation (A.c), backward
     // the output gate's (A.e); the addend is sigmoid(i_pre)*tanh(z_pre), resp. grad_h*sigmoid(o_pre).
-    vec<VEC> third[FORM == FORM_LSTM ? R : 1];
-    const rsrc_t r3 = ad.rsrc(FORM == FORM_LSTM ? (BWD ? A.e : A.c) : A.b);
+    // Backward, the cell state c_t comes along as a fourth: grad_o_pre = grad_h*c_t*o(1-o) does not
+    // depend on the scan and is written right here, while grad_h and o are at hand.
+    constexpr bool LSTM = FORM == FORM_LSTM;
+    vec<VEC> third[LSTM ? R : 1], fourth[(LSTM && BWD) ? R : 1];
+    const rsrc_t r3 = ad.rsrc(LSTM ? (BWD ? A.e : A.c) : A.b), r4 = ad.rsrc(LSTM && BWD ? A.hprev : A.b);
+    const bool want_go = LSTM && BWD && A.out3 != nullptr;
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        vec<VEC> va = splat<VEC>(raw_identity), vb = splat<VEC>(0.0f), v3 = splat<VEC>(0.0f);
+        vec<VEC> va = splat<VEC>(raw_identity), vb = splat<VEC>(0.0f), v3 = splat<VEC>(0.0f), v4 = splat<VEC>(0.0f);
         if (interior || j < mk.n) {
             vb = buf_ld<VEC>(rb, ad.toff, ad.soff(j));
-            if constexpr (FORM == FORM_LSTM) v3 = buf_ld<VEC>(r3, ad.toff, ad.soff(j));
+            if constexpr (LSTM) v3 = buf_ld<VEC>(r3, ad.toff, ad.soff(j));
+            if constexpr (LSTM && BWD) {
+                if (want_go) v4 = buf_ld<VEC>(r4, ad.toff, ad.soff(j));
+            }
             if constexpr (!BWD) {
                 va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
             } else {
@@ -341,7 +348,8 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
         }
         r.a[j] = va;
         r.b[j] = vb;
-        if constexpr (FORM == FORM_LSTM) third[j] = v3;
+        if constexpr (LSTM) third[j] = v3;
+        if constexpr (LSTM && BWD) fourth[j] = v4;
     }
     if constexpr (FORM == FORM_GATED) {
 #pragma unroll
@@ -350,13 +358,21 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
             if constexpr (!BWD) r.b[j] = r.a[j] * impulse<VEC>(r.b[j], A.tau);
         }
     }
-    if constexpr (FORM == FORM_LSTM) {
+    if constexpr (LSTM) {
+        const rsrc_t rgo = ad.rsrc(BWD ? A.out3 : A.out0);
 #pragma unroll
         for (int j = 0; j < R; ++j) {
             r.a[j] = gate_complement<VEC>(r.a[j]);
             // (masked rows hold b = 0, and sigmoid(0)*tanh(0) = 0, 0*sigmoid(0) = 0)
-            if constexpr (!BWD) r.b[j] = gate_value<VEC>(r.b[j]) * impulse<VEC>(third[j], 1);
-            else r.b[j] = r.b[j] * gate_value<VEC>(third[j]);
+            if constexpr (!BWD) {
+                r.b[j] = gate_value<VEC>(r.b[j]) * impulse<VEC>(third[j], 1);
+            } else {
+                vec<VEC> og, oc;
+                gate_both<VEC>(third[j], og, oc);
+                if (want_go && (interior || j < mk.n))
+                    buf_st<VEC>(rgo, ad.toff, ad.soff(j), r.b[j] * fourth[j] * (og * oc));
+                r.b[j] = r.b[j] * og;
+            }
         }
     }
 }
@@ -513,9 +529,10 @@ __device__ __forceinline__ void tile_store_lstm_fwd(const Args &A, const TileAdd
 
 // Backward epilogue of the LSTM cell.  After the rescan r.b[j] = d_t (accumulated gradient of c_t) and
 // r.a[j] is the forget gate's complement of row t+1, so the row's own is r.a[j+1] (see the gated form).
-//   grad_o_pre = grad_h * c_t * o(1-o)         grad_f_pre = d * c_{t-1} * f(1-f)      (c_{-1} = c0)
-//   grad_i_pre = d * z * i(1-i)                grad_z_pre = d * i * (1 - z^2)          grad_c0 = f_0 * d_0
-// Everything but d and f is loaded here, in chunks of rows, after the rescan.
+//   grad_f_pre = d * c_{t-1} * f(1-f)   (c_{-1} = c0)      grad_i_pre = d * z * i(1-i)
+//   grad_z_pre = d * i * (1 - z^2)                          grad_c0    = f_0 * d_0
+// (grad_o_pre was written by the prologue.)  c_{t-1}, i_pre and z_pre are loaded here, in chunks of
+// rows, after the rescan.
 template <class G>
 __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAddr<G, true> &ad,
                                                     const RowMask<G, true> &mk, int64_t col, bool interior,
@@ -524,28 +541,22 @@ __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAdd
     constexpr int R = G::R, VEC = G::VEC;
     constexpr int CH = R < 8 ? R : 8;
     static_assert(R % CH == 0, "rows per thread: a multiple of 8, or fewer than 8");
-    const rsrc_t rf = ad.rsrc(A.out0), ri = ad.rsrc(A.out1), rz = ad.rsrc(A.out2), ro = ad.rsrc(A.out3);
-    const rsrc_t rc = ad.rsrc(A.hprev), rcp = ad.rsrc(A.hprev, -1), rip = ad.rsrc(A.c), rzp = ad.rsrc(A.d),
-                 rop = ad.rsrc(A.e), rgh = ad.rsrc(A.b), rg = ad.rsrc(A.a);
+    const rsrc_t rf = ad.rsrc(A.out0), ri = ad.rsrc(A.out1), rz = ad.rsrc(A.out2);
+    const rsrc_t rcp = ad.rsrc(A.hprev, -1), rip = ad.rsrc(A.c), rzp = ad.rsrc(A.d), rg = ad.rsrc(A.a);
     const int nv = interior ? R : mk.n;
     vec<VEC> c_last = splat<VEC>(__builtin_inff());
     if (nv > 0) c_last = buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
     c_last = gate_complement<VEC>(c_last);
 #pragma unroll
     for (int j0 = 0; j0 < R; j0 += CH) {
-        vec<VEC> ct[CH], cp[CH], ip[CH], zp[CH], op[CH], gh[CH];
+        vec<VEC> cp[CH], ip[CH], zp[CH];
 #pragma unroll
         for (int q = 0; q < CH; ++q) {  // loads only
             const int j = j0 + q;
-            ct[q] = cp[q] = ip[q] = zp[q] = op[q] = gh[q] = splat<VEC>(0.0f);
+            cp[q] = ip[q] = zp[q] = splat<VEC>(0.0f);
             if (interior || j < mk.n) {
                 ip[q] = buf_ld<VEC>(rip, ad.toff, ad.soff(j));
                 zp[q] = buf_ld<VEC>(rzp, ad.toff, ad.soff(j));
-                if (A.out3) {
-                    ct[q] = buf_ld<VEC>(rc, ad.toff, ad.soff(j));
-                    op[q] = buf_ld<VEC>(rop, ad.toff, ad.soff(j));
-                    gh[q] = buf_ld<VEC>(rgh, ad.toff, ad.soff(j));
-                }
                 if (interior || j < mk.nh) cp[q] = buf_ld<VEC>(rcp, ad.toff, ad.soff(j));
                 else if (A.h0) cp[q] = ld<VEC>(A.h0 + col);  // row t == 0
             }
@@ -556,15 +567,13 @@ __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAdd
             vec<VEC> cf = c_last;
             if (j + 1 < R) cf = (j + 1 < nv) ? r.a[j + 1] : c_last;
             const vec<VEC> f = splat<VEC>(1.0f) - cf, d = r.b[j];
-            vec<VEC> ig, ic, og, oc;
+            vec<VEC> ig, ic;
             gate_both<VEC>(ip[q], ig, ic);
-            gate_both<VEC>(op[q], og, oc);
             const vec<VEC> z = impulse<VEC>(zp[q], 1);
             if (interior || j < mk.n) {
                 if (A.out0) buf_st<VEC>(rf, ad.toff, ad.soff(j), d * cp[q] * (f * cf));
                 if (A.out1) buf_st<VEC>(ri, ad.toff, ad.soff(j), d * z * (ig * ic));
                 if (A.out2) buf_st<VEC>(rz, ad.toff, ad.soff(j), d * ig * vfma<VEC>(-z, z, splat<VEC>(1.0f)));
-                if (A.out3) buf_st<VEC>(ro, ad.toff, ad.soff(j), gh[q] * ct[q] * (og * oc));
                 if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, f * d);
             }
         }
