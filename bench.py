@@ -82,14 +82,15 @@ def cpu_baseline(inp, threads):
                       f"over {threads} host threads; forward {t1 - t0:.3f} s, backward {t3 - t2:.3f} s"}
 
 
-def measured_traffic(cfg, direction):
+def measured_traffic(cfg, direction, form=""):
     """HBM bytes per launch of the look-back kernel from the committed rocprofv3 counter summary
-    (profiles/hbm_traffic_cfg<N>.json, written by paper_1709_04057_amd/traffic.py), or None."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{cfg}.json")
+    (profiles/hbm_traffic_cfg<N>.json or hbm_traffic_<gated/lstm workload>.json, written by
+    paper_1709_04057_amd/traffic.py), or None."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg}.json" if form else f"hbm_traffic_cfg{cfg}.json")
     try:
         with open(path) as f:
             d = json.load(f)
-        return d["kernels"]["k_lookback/" + direction]["hbm_bytes"]
+        return d["kernels"][form + "k_lookback/" + direction]["hbm_bytes"]
     except (OSError, KeyError, ValueError):
         return None
 
@@ -210,6 +211,9 @@ def gated_bench(args, lr, torch, wl):
                      "bytes_per_element": 24.0, "algorithmic_bytes": 24.0 * E, "avg_ms": b_avg},
         "cpu_baseline": None,
     }
+    out["roofline"]["traffic"] = measured_traffic(args.gated, "backward", "gated:")
+    if args.probe:
+        out["stream_probe"] = stream_probe(lr, torch, E, stream)
     print(json.dumps(out), flush=True)
 
 
@@ -278,6 +282,9 @@ def lstm_bench(args, lr, torch, wl):
                      "bytes_per_element": 40.0, "algorithmic_bytes": 40.0 * E, "avg_ms": b_avg},
         "cpu_baseline": None,
     }
+    out["roofline"]["traffic"] = measured_traffic(args.lstm, "backward", "lstm:")
+    if args.probe:
+        out["stream_probe"] = stream_probe(lr, torch, E, stream)
     print(json.dumps(out), flush=True)
 
 

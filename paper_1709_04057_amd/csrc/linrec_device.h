@@ -310,11 +310,14 @@ struct RowMask {
 // masking (and, backward, no row is one of the boundary cases u == 0, t == 0).  Masked steps are the
 // identity pair.  FORM_GATED: A.a holds the gate pre-activations and r.a becomes the gate complement;
 // forward, A.b holds the impulse pre-activations and r.b becomes (1-g)*tau(i_pre).
-template <class G, bool BWD, int FORM = FORM_PLAIN>
+// FORM_LSTM backward also returns the cell state c_t of the thread's rows in `cst` (the epilogue needs
+// c_{t-1}, which is the next row's entry).
+template <class G, bool BWD, int FORM = FORM_PLAIN, int NC = 1>
 __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
-                                          bool interior, Rows<G> &r)
+                                          bool interior, Rows<G> &r, vec<G::VEC> (&cst)[NC])
 {
     constexpr int R = G::R, VEC = G::VEC;
+    static_assert(NC == ((FORM == FORM_LSTM && BWD) ? R : 1), "cst: R entries for the LSTM cell's backward pass");
     const rsrc_t ra = ad.rsrc(A.a, BWD ? +1 : 0), rb = ad.rsrc(A.b);
     // What a masked step holds BEFORE the activations are applied: the gated forms run them over every
     // row after all loads have been issued (inside the per-row conditions they would make each load
@@ -327,7 +330,7 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
     // Backward, the cell state c_t comes along as a fourth: grad_o_pre = grad_h*c_t*o(1-o) does not
     // depend on the scan and is written right here, while grad_h and o are at hand.
     constexpr bool LSTM = FORM == FORM_LSTM;
-    vec<VEC> third[LSTM ? R : 1], fourth[(LSTM && BWD) ? R : 1];
+    vec<VEC> third[LSTM ? R : 1];
     const rsrc_t r3 = ad.rsrc(LSTM ? (BWD ? A.e : A.c) : A.b), r4 = ad.rsrc(LSTM && BWD ? A.hprev : A.b);
     const bool want_go = LSTM && BWD && A.out3 != nullptr;
 #pragma unroll
@@ -336,9 +339,7 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
         if (interior || j < mk.n) {
             vb = buf_ld<VEC>(rb, ad.toff, ad.soff(j));
             if constexpr (LSTM) v3 = buf_ld<VEC>(r3, ad.toff, ad.soff(j));
-            if constexpr (LSTM && BWD) {
-                if (want_go) v4 = buf_ld<VEC>(r4, ad.toff, ad.soff(j));
-            }
+            if constexpr (LSTM && BWD) v4 = buf_ld<VEC>(r4, ad.toff, ad.soff(j));
             if constexpr (!BWD) {
                 va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
             } else {
@@ -349,7 +350,7 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
         r.a[j] = va;
         r.b[j] = vb;
         if constexpr (LSTM) third[j] = v3;
-        if constexpr (LSTM && BWD) fourth[j] = v4;
+        if constexpr (LSTM && BWD) cst[j] = v4;
     }
     if constexpr (FORM == FORM_GATED) {
 #pragma unroll
@@ -370,11 +371,19 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
                 vec<VEC> og, oc;
                 gate_both<VEC>(third[j], og, oc);
                 if (want_go && (interior || j < mk.n))
-                    buf_st<VEC>(rgo, ad.toff, ad.soff(j), r.b[j] * fourth[j] * (og * oc));
+                    buf_st<VEC>(rgo, ad.toff, ad.soff(j), r.b[j] * cst[j] * (og * oc));
                 r.b[j] = r.b[j] * og;
             }
         }
     }
+}
+
+template <class G, bool BWD, int FORM = FORM_PLAIN>
+__device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
+                                          bool interior, Rows<G> &r)
+{
+    vec<G::VEC> none[1];
+    tile_load<G, BWD, FORM, 1>(A, ad, mk, interior, r, none);
 }
 
 // Backward only: h one row behind each step (h[-1] = h0, zero when h0 is null).
@@ -531,12 +540,12 @@ __device__ __forceinline__ void tile_store_lstm_fwd(const Args &A, const TileAdd
 // r.a[j] is the forget gate's complement of row t+1, so the row's own is r.a[j+1] (see the gated form).
 //   grad_f_pre = d * c_{t-1} * f(1-f)   (c_{-1} = c0)      grad_i_pre = d * z * i(1-i)
 //   grad_z_pre = d * i * (1 - z^2)                          grad_c0    = f_0 * d_0
-// (grad_o_pre was written by the prologue.)  c_{t-1}, i_pre and z_pre are loaded here, in chunks of
-// rows, after the rescan.
+// (grad_o_pre was written by the prologue.)  c_{t-1} is the cell state of the thread's next row, which
+// the prologue kept in `cst`; i_pre and z_pre are loaded here, in chunks of rows, after the rescan.
 template <class G>
 __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAddr<G, true> &ad,
                                                     const RowMask<G, true> &mk, int64_t col, bool interior,
-                                                    const Rows<G> &r)
+                                                    const Rows<G> &r, const vec<G::VEC> (&cst)[G::R])
 {
     constexpr int R = G::R, VEC = G::VEC;
     constexpr int CH = R < 8 ? R : 8;
@@ -544,34 +553,41 @@ __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAdd
     const rsrc_t rf = ad.rsrc(A.out0), ri = ad.rsrc(A.out1), rz = ad.rsrc(A.out2);
     const rsrc_t rcp = ad.rsrc(A.hprev, -1), rip = ad.rsrc(A.c), rzp = ad.rsrc(A.d), rg = ad.rsrc(A.a);
     const int nv = interior ? R : mk.n;
-    vec<VEC> c_last = splat<VEC>(__builtin_inff());
-    if (nv > 0) c_last = buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
+    // The thread's last existing row: its own forget-gate complement and the cell state before it
+    // are not among the thread's registers (c0 when that row is t == 0).
+    vec<VEC> c_last = splat<VEC>(__builtin_inff()), cp_last = splat<VEC>(0.0f);
+    if (nv > 0) {
+        c_last = buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
+        if (interior || nv - 1 < mk.nh) cp_last = buf_ld<VEC>(rcp, ad.toff + ad.soff_rt(nv - 1), 0);
+        else if (A.h0) cp_last = ld<VEC>(A.h0 + col);
+    }
     c_last = gate_complement<VEC>(c_last);
 #pragma unroll
     for (int j0 = 0; j0 < R; j0 += CH) {
-        vec<VEC> cp[CH], ip[CH], zp[CH];
+        vec<VEC> ip[CH], zp[CH];
 #pragma unroll
         for (int q = 0; q < CH; ++q) {  // loads only
             const int j = j0 + q;
-            cp[q] = ip[q] = zp[q] = splat<VEC>(0.0f);
+            ip[q] = zp[q] = splat<VEC>(0.0f);
             if (interior || j < mk.n) {
                 ip[q] = buf_ld<VEC>(rip, ad.toff, ad.soff(j));
                 zp[q] = buf_ld<VEC>(rzp, ad.toff, ad.soff(j));
-                if (interior || j < mk.nh) cp[q] = buf_ld<VEC>(rcp, ad.toff, ad.soff(j));
-                else if (A.h0) cp[q] = ld<VEC>(A.h0 + col);  // row t == 0
             }
         }
 #pragma unroll
         for (int q = 0; q < CH; ++q) {
             const int j = j0 + q;
-            vec<VEC> cf = c_last;
-            if (j + 1 < R) cf = (j + 1 < nv) ? r.a[j + 1] : c_last;
+            vec<VEC> cf = c_last, cp = cp_last;
+            if (j + 1 < R) {
+                cf = (j + 1 < nv) ? r.a[j + 1] : c_last;
+                cp = (j + 1 < nv) ? cst[j + 1] : cp_last;
+            }
             const vec<VEC> f = splat<VEC>(1.0f) - cf, d = r.b[j];
             vec<VEC> ig, ic;
             gate_both<VEC>(ip[q], ig, ic);
             const vec<VEC> z = impulse<VEC>(zp[q], 1);
             if (interior || j < mk.n) {
-                if (A.out0) buf_st<VEC>(rf, ad.toff, ad.soff(j), d * cp[q] * (f * cf));
+                if (A.out0) buf_st<VEC>(rf, ad.toff, ad.soff(j), d * cp * (f * cf));
                 if (A.out1) buf_st<VEC>(ri, ad.toff, ad.soff(j), d * z * (ig * ic));
                 if (A.out2) buf_st<VEC>(rz, ad.toff, ad.soff(j), d * ig * vfma<VEC>(-z, z, splat<VEC>(1.0f)));
                 if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, f * d);
@@ -896,7 +912,9 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     vec<VEC> hp[(BWD && FORM == FORM_PLAIN) ? R : 1];
     const TileAddr<G, BWD> ad(A, tu0, g, tt, tc, rk);
     const RowMask<G, BWD> mk(A, u0, col_ok, rk);
-    tile_load<G, BWD, FORM>(A, ad, mk, interior, r);
+    constexpr int NC = (BWD && FORM == FORM_LSTM) ? R : 1;
+    vec<VEC> cst[NC];
+    tile_load<G, BWD, FORM, NC>(A, ad, mk, interior, r, cst);
     if constexpr (BWD && !HP_LATE && FORM == FORM_PLAIN) {
         if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
     }
@@ -1037,7 +1055,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         tile_store_gated_bwd<G>(A, ad, mk, col, interior, r);
     } else if constexpr (FORM == FORM_LSTM) {
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (BWD) tile_store_lstm_bwd<G>(A, ad, mk, col, interior, r);
+        if constexpr (BWD) tile_store_lstm_bwd<G>(A, ad, mk, col, interior, r, cst);
         else tile_store_lstm_fwd<G>(A, ad, mk, interior, r);
     } else {
         if constexpr (BWD && HP_LATE) {

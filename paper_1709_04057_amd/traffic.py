@@ -5,6 +5,7 @@
     rocprofv3 --pmc WRITE_SIZE -d <out>/write -o write -- python3 bench.py --steps 10 --warmup 2 --no-cpu-baseline --probe
     python -m paper_1709_04057_amd.traffic <out>/fetch/fetch_results.db <out>/write/write_results.db \\
            --elements 67108864 --out profiles/hbm_traffic_cfg2
+(for the gated layer: bench.py --gated g2 --probe ... and --bytes-per-element 12,24; LSTM cell: --lstm l2, 24,40)
 
 Each counter is scaled by what it reads for the library's plain copy kernel (`bench.py --probe` runs
 it first: 4 bytes read and 4 bytes written per element, nothing else), so the unit the counter
@@ -31,9 +32,12 @@ def _kind(name):
     if "k_stream_probe" in name:
         return "stream_probe"
     if "k_lookback" in name or "k_fixup" in name or "k_reduce" in name or "k_scan_summaries" in name or "k_serial" in name:
-        bwd = ", true" in name.split("k_", 1)[1] or "k_serial_bwd" in name
+        bwd = ", true" in name.split("k_", 1)[1] or "_bwd" in name
         base = name.split("linrec::", 1)[1].split("<", 1)[0].split("(", 1)[0]
-        return base + ("/backward" if bwd else "/forward")
+        # the look-back kernel's last template argument is the form: 1 gated layer, 2 LSTM cell
+        form = {"1": "gated:", "2": "lstm:"}.get(name.rsplit(">(", 1)[0].rsplit(",", 1)[-1].strip(), "") \
+            if "k_lookback" in name else ""
+        return form + base + ("/backward" if bwd else "/forward")
     return None
 
 
@@ -43,6 +47,9 @@ def main():
     ap.add_argument("write_db")
     ap.add_argument("--elements", type=int, required=True, help="T*B*n of the workload (also the probe's array length)")
     ap.add_argument("--probe-launches", type=int, default=12, help="launches of each probe variant (warm-up + timed)")
+    ap.add_argument("--bytes-per-element", default="12,20",
+                    help="algorithmic bytes per element forward,backward of the entry points under test "
+                         "(12,20 plain; 12,24 gated layer; 24,40 LSTM cell); applied to the kernels of that form")
     ap.add_argument("--out", required=True)
     a = ap.parse_args()
 
@@ -69,7 +76,10 @@ def main():
             d[("read" if counter == "FETCH_SIZE" else "written") + "_bytes"] = d[counter] * factors[counter]
     res["bytes_per_unit"] = factors
     for kind, d in sorted(res["kernels"].items()):
-        alg = (20.0 if kind.endswith("backward") else 12.0) * E
+        fwd_b, bwd_b = (float(v) for v in a.bytes_per_element.split(","))
+        if ":" not in kind:
+            fwd_b, bwd_b = 12.0, 20.0
+        alg = (bwd_b if kind.endswith("backward") else fwd_b) * E
         if "read_bytes" in d and "written_bytes" in d:
             d["hbm_bytes"] = d["read_bytes"] + d["written_bytes"]
             d["algorithmic_bytes"] = alg
