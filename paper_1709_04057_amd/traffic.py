@@ -50,6 +50,8 @@ def main():
     ap.add_argument("--bytes-per-element", default="12,20",
                     help="algorithmic bytes per element forward,backward of the entry points under test "
                          "(12,20 plain; 12,24 gated layer; 24,40 LSTM cell); applied to the kernels of that form")
+    ap.add_argument("--bench-args", default="",
+                    help="the bench.py arguments of the two counter runs, recorded in the summary (e.g. '--gated g2')")
     ap.add_argument("--out", required=True)
     a = ap.parse_args()
 
@@ -88,8 +90,18 @@ def main():
                          f"(x{d['hbm_bytes'] / alg:.3f})   [{d['name']}]")
     with open(a.out + ".json", "w") as f:
         json.dump(res, f, indent=1)
+    bench = ("bench.py " + a.bench_args.strip() + " --steps 10 --warmup 2 --probe") if a.bench_args.strip() else \
+        "bench.py --steps 10 --warmup 2 --no-cpu-baseline --probe"
+    head = ("HBM bytes per launch from two rocprofv3 counter runs (one MI355X), each counter scaled by what it reads for the\n"
+            "library's copy kernel of known size.  Commands, from the repository root on the GPU box:\n"
+            "  cd /tmp && export TMPDIR=/tmp && cd $REPO\n"
+            f"  rocprofv3 --pmc FETCH_SIZE -d out/fetch -o fetch -- python3 {bench}\n"
+            f"  rocprofv3 --pmc WRITE_SIZE -d out/write -o write -- python3 {bench}\n"
+            f"  python3 -m paper_1709_04057_amd.traffic out/fetch/fetch_results.db out/write/write_results.db "
+            f"--elements {E} --bytes-per-element {a.bytes_per_element}"
+            + (f" --bench-args '{a.bench_args.strip()}'" if a.bench_args.strip() else "") + " --out <this file>\n")
     with open(a.out + ".txt", "w") as f:
-        f.write(__doc__.split("Each counter")[0].strip() + "\n\n" + "\n".join(lines) + "\n")
+        f.write(head + "\n" + "\n".join(lines) + "\n")
     print("\n".join(lines))
 
 
