@@ -5,6 +5,7 @@ C ABI declared in ``include/linrec.h``; every step of the recurrence runs in the
 kernels.  There is no CPU fallback: if ``liblinrec.so`` has not been built the first call raises.
 PyTorch is used for device memory and streams only.
 """
+from .autograd import gilr, linear_recurrence, lstm_cell  # noqa: F401
 from .binding import (  # noqa: F401
     LinrecError,
     OPT_CHUNK_TILES,
