@@ -109,6 +109,24 @@ int linrec_backward(const float *lambda, const float *h, const float *h0, const 
                     float *grad_x, float *grad_lambda, float *grad_h0,
                     int64_t T, int64_t B, int64_t n, void *stream);
 
+/*
+ * The same two passes on bf16 STORAGE: every tensor (and h0, grad_h0) holds bfloat16, i.e. the upper
+ * 16 bits of an fp32, passed as uint16_t.  Values are widened exactly on load, all arithmetic is that
+ * of linrec_forward / linrec_backward (fp32 steps, fp64 chunk products), results are rounded to
+ * nearest even on store.  6 bytes per element forward, 10 backward.  The paper's kernel is fp32 only
+ * (Section 2.3): this is a bandwidth option, not one of its experiments.  Same layout, NULL and
+ * aliasing rules as above.  Accuracy: each stored value is within half a bf16 unit in the last place
+ * (2^-9 relative) of what the fp32 entry points would store for the same (bf16-valued) inputs, up
+ * to their own tolerance; the backward pass consumes the ROUNDED h it is given.
+ * 4-byte aligned tensors with an even B*n use 4-byte accesses (8-byte ones when 8-byte aligned and
+ * B*n is a multiple of 4); anything else falls back to the serial kernel.
+ */
+int linrec_forward_bf16(const uint16_t *lambda, const uint16_t *x, const uint16_t *h0,
+                        uint16_t *h_out, int64_t T, int64_t B, int64_t n, void *stream);
+int linrec_backward_bf16(const uint16_t *lambda, const uint16_t *h, const uint16_t *h0,
+                         const uint16_t *grad_h, uint16_t *grad_x, uint16_t *grad_lambda,
+                         uint16_t *grad_h0, int64_t T, int64_t B, int64_t n, void *stream);
+
 /* Impulse activation tau of the gated layer (Section 3.1 leaves it open; its LSTM uses tanh). */
 enum { LINREC_TAU_IDENTITY = 0, LINREC_TAU_TANH = 1 };
 
@@ -214,6 +232,12 @@ int linrec_validate_forward(const float *lambda, const float *x, const float *h0
 int linrec_validate_backward(const float *lambda, const float *h, const float *h0,
                              const float *grad_h, const float *grad_x, const float *grad_lambda,
                              const float *grad_h0, int64_t T, int64_t B, int64_t n);
+int linrec_validate_forward_bf16(const uint16_t *lambda, const uint16_t *x, const uint16_t *h0,
+                                 const uint16_t *h_out, int64_t T, int64_t B, int64_t n);
+int linrec_validate_backward_bf16(const uint16_t *lambda, const uint16_t *h, const uint16_t *h0,
+                                  const uint16_t *grad_h, const uint16_t *grad_x,
+                                  const uint16_t *grad_lambda, const uint16_t *grad_h0,
+                                  int64_t T, int64_t B, int64_t n);
 int linrec_validate_gilr_forward(const float *g_pre, const float *i_pre, const float *h0,
                                  const float *h_out, int tau, int64_t T, int64_t B, int64_t n);
 int linrec_validate_gilr_backward(const float *g_pre, const float *i_pre, const float *h,

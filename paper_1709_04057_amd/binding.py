@@ -43,6 +43,15 @@ def lib():
         L.linrec_forward.restype = ci
         L.linrec_backward.argtypes = [p, p, p, p, p, p, p, i64, i64, i64, p]
         L.linrec_backward.restype = ci
+        for fn in (L.linrec_forward_bf16,):
+            fn.argtypes = [p, p, p, p, i64, i64, i64, p]
+            fn.restype = ci
+        L.linrec_backward_bf16.argtypes = [p, p, p, p, p, p, p, i64, i64, i64, p]
+        L.linrec_backward_bf16.restype = ci
+        L.linrec_validate_forward_bf16.argtypes = [p, p, p, p, i64, i64, i64]
+        L.linrec_validate_forward_bf16.restype = ci
+        L.linrec_validate_backward_bf16.argtypes = [p, p, p, p, p, p, p, i64, i64, i64]
+        L.linrec_validate_backward_bf16.restype = ci
         L.linrec_validate_forward.argtypes = [p, p, p, p, i64, i64, i64]
         L.linrec_validate_forward.restype = ci
         L.linrec_validate_backward.argtypes = [p, p, p, p, p, p, p, i64, i64, i64]
@@ -123,34 +132,40 @@ def _stream_ptr(stream):
     return ctypes.c_void_p(stream.cuda_stream)
 
 
-def _tbn(t, name):
+def _tbn(t, name, dtype=None):
     import torch
-    if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.dim() != 3:
-        raise ValueError(f"{name} must be a contiguous float32 CUDA tensor of shape [T, B, n]")
+    dtype = dtype or torch.float32
+    if t.dtype != dtype or not t.is_cuda or not t.is_contiguous() or t.dim() != 3:
+        raise ValueError(f"{name} must be a contiguous {dtype} CUDA tensor of shape [T, B, n]")
     return t.shape
 
 
-def _bn(t, name, B, n):
+def _bn(t, name, B, n, dtype=None):
     import torch
+    dtype = dtype or torch.float32
     if t is None:
         return
-    if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, n):
-        raise ValueError(f"{name} must be a contiguous float32 CUDA tensor of shape [B, n] = [{B}, {n}]")
+    if t.dtype != dtype or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, n):
+        raise ValueError(f"{name} must be a contiguous {dtype} CUDA tensor of shape [B, n] = [{B}, {n}]")
 
 
 def linrec_forward(lam, x, h0=None, h_out=None, stream=None):
-    """h_out[t] = lam[t] * h_out[t-1] + x[t], h_out[-1] = h0.  Enqueues on ``stream`` and returns h_out."""
+    """h_out[t] = lam[t] * h_out[t-1] + x[t], h_out[-1] = h0.  Enqueues on ``stream`` and returns h_out.
+
+    float32 tensors go to linrec_forward, bfloat16 tensors (all of them) to linrec_forward_bf16."""
     import torch
-    T, B, n = _tbn(lam, "lambda")
+    dt = lam.dtype if lam.dtype == torch.bfloat16 else torch.float32
+    T, B, n = _tbn(lam, "lambda", dt)
     if tuple(x.shape) != (T, B, n):
         raise ValueError("x must have lambda's shape")
-    _tbn(x, "x")
-    _bn(h0, "h0", B, n)
+    _tbn(x, "x", dt)
+    _bn(h0, "h0", B, n, dt)
     if h_out is None:
         h_out = torch.empty_like(x)
-    elif tuple(_tbn(h_out, "h_out")) != (T, B, n):
+    elif tuple(_tbn(h_out, "h_out", dt)) != (T, B, n):
         raise ValueError("h_out must have lambda's shape")
-    _check(lib().linrec_forward(_ptr(lam), _ptr(x), _ptr(h0), _ptr(h_out), T, B, n, _stream_ptr(stream)))
+    fn = lib().linrec_forward_bf16 if dt == torch.bfloat16 else lib().linrec_forward
+    _check(fn(_ptr(lam), _ptr(x), _ptr(h0), _ptr(h_out), T, B, n, _stream_ptr(stream)))
     return h_out
 
 
@@ -159,25 +174,28 @@ def linrec_backward(lam, h, h0, grad_h, grad_x=None, grad_lambda=None, grad_h0=N
     """Gradients of the recurrence for upstream ``grad_h``; returns (grad_x, grad_lambda, grad_h0).
 
     Output tensors are allocated unless given; pass ``want_*=False`` to skip an output (returned as None).
+    float32 tensors go to linrec_backward, bfloat16 tensors (all of them) to linrec_backward_bf16.
     """
     import torch
-    T, B, n = _tbn(lam, "lambda")
+    dt = lam.dtype if lam.dtype == torch.bfloat16 else torch.float32
+    T, B, n = _tbn(lam, "lambda", dt)
     for name, t in (("h", h), ("grad_h", grad_h)):
-        if tuple(_tbn(t, name)) != (T, B, n):
+        if tuple(_tbn(t, name, dt)) != (T, B, n):
             raise ValueError(f"{name} must have lambda's shape")
-    _bn(h0, "h0", B, n)
+    _bn(h0, "h0", B, n, dt)
     if grad_x is None and want_grad_x:
         grad_x = torch.empty_like(grad_h)
     if grad_lambda is None and want_grad_lambda:
         grad_lambda = torch.empty_like(grad_h)
     if grad_h0 is None and want_grad_h0:
-        grad_h0 = torch.empty((B, n), dtype=torch.float32, device=lam.device)
+        grad_h0 = torch.empty((B, n), dtype=dt, device=lam.device)
     for name, t in (("grad_x", grad_x), ("grad_lambda", grad_lambda)):
-        if t is not None and tuple(_tbn(t, name)) != (T, B, n):
+        if t is not None and tuple(_tbn(t, name, dt)) != (T, B, n):
             raise ValueError(f"{name} must have lambda's shape")
-    _bn(grad_h0, "grad_h0", B, n)
-    _check(lib().linrec_backward(_ptr(lam), _ptr(h), _ptr(h0), _ptr(grad_h), _ptr(grad_x), _ptr(grad_lambda),
-                                 _ptr(grad_h0), T, B, n, _stream_ptr(stream)))
+    _bn(grad_h0, "grad_h0", B, n, dt)
+    fn = lib().linrec_backward_bf16 if dt == torch.bfloat16 else lib().linrec_backward
+    _check(fn(_ptr(lam), _ptr(h), _ptr(h0), _ptr(grad_h), _ptr(grad_x), _ptr(grad_lambda), _ptr(grad_h0), T, B, n,
+              _stream_ptr(stream)))
     return grad_x, grad_lambda, grad_h0
 
 

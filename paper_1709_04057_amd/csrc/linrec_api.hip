@@ -16,7 +16,7 @@
 
 namespace linrec {
 
-#define X(ID, VEC, R, WC, WT) hipError_t launch_tile_##ID(Kind, bool, bool, int, const Args &, hipStream_t);
+#define X(ID, VEC, R, WC, WT) hipError_t launch_tile_##ID(Kind, bool, bool, int, bool, const Args &, hipStream_t);
 LINREC_TILES(X)
 #undef X
 
@@ -28,11 +28,11 @@ static const TileDesc kTiles[NUM_TILES] = {
 
 const TileDesc &tile_desc(int id) { return kTiles[id - 1]; }
 
-hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, const Args &A, hipStream_t s)
+hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A, hipStream_t s)
 {
     switch (id) {
 #define X(ID, VEC, R, WC, WT) \
-    case ID: return launch_tile_##ID(kind, bwd, hp_late, form, A, s);
+    case ID: return launch_tile_##ID(kind, bwd, hp_late, form, bf16, A, s);
         LINREC_TILES(X)
 #undef X
     default: return hipErrorInvalidValue;
@@ -136,6 +136,14 @@ int max_vec(int64_t C, std::initializer_list<const void *> ptrs)
     return (bits & 15u) == 0 ? 4 : (bits & 7u) == 0 ? 2 : 1;
 }
 
+// The same for bf16 storage: four columns are 8 bytes, two are 4.
+int max_vec_bf16(int64_t C, std::initializer_list<const void *> ptrs)
+{
+    uintptr_t bits = (uintptr_t)(C * 2);
+    for (const void *p : ptrs) bits |= (uintptr_t)p;
+    return (bits & 7u) == 0 ? 4 : (bits & 3u) == 0 ? 2 : 1;
+}
+
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 int pow2_at_least(int64_t x)
@@ -189,7 +197,7 @@ std::mutex g_tuned_mu;
 std::map<TunedKey, TunedPlan> g_tuned;
 
 // Picks variant and tile, honouring the options where they apply to this problem.
-Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN)
+Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, bool bf16 = false)
 {
     const bool gated = form != FORM_PLAIN;
     Plan p;
@@ -197,7 +205,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN)
     if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
     p.tile = (int)opts().tile;
     p.persistent = (int)opts().persistent;
-    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK && !gated) {  // a tuned plan, if there is one for this shape
+    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK && !gated && !bf16) {  // a tuned plan, if there is one for this shape
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess) {
             std::lock_guard<std::mutex> lock(g_tuned_mu);
@@ -210,13 +218,18 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN)
     }
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 0;
+    if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && kTiles[p.tile - 1].vec < 2) p.tile = 0;
     if (p.tile < 1 || p.tile > NUM_TILES) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
         // The gated form computes a sigmoid and a tanh per element before it can publish a summary:
         // 32-row threads (twice the resident workgroups of the 64-row shapes) hide that better.
         if (gated && T >= 2048 && C > 16) p.tile = C >= 2048 ? 21 : 18;
         if (form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 18;  // (the cell has no 48- or 64-row kernels)
+        // bf16 storage: the shapes with two columns (4 bytes) per thread mirror the fp32 choice
+        if (bf16) p.tile = T >= 2048 ? 16 : 15;
     }
+    // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
+    if (bf16 && vec < 2) p.variant = LINREC_VARIANT_SERIAL;
     const TileDesc &d = kTiles[p.tile - 1];
     // per-thread byte offsets inside a tile are 32-bit, tickets of a call are 31-bit
     const int64_t G = ceil_div(C, d.cols()), K = ceil_div(T, d.rows());
@@ -229,14 +242,14 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN)
 
 // gated: the form of Section 3.1 (activations applied in the kernel); it exists as the single-pass
 // kernel of the one-column-per-thread tile shapes and as the serial kernel.
-int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN)
+int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf16 = false)
 {
     const bool gated = form != FORM_PLAIN;
-    Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd, form);
-    if (gated && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
+    Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd, form, bf16);
+    if ((gated || bf16) && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
-        if ((e = launch_serial(A, bwd, form, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
+        if ((e = launch_serial(A, bwd, form, bf16, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
         return LINREC_OK;
     }
     const TileDesc &d = kTiles[plan.tile - 1];
@@ -262,11 +275,11 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN)
         A.aggP = (double *)ws.tp;
         A.aggS = A.aggP + kc;
         A.carry = A.aggS + kc;
-        if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, FORM_PLAIN, A, s)) != hipSuccess)
+        if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, FORM_PLAIN, false, A, s)) != hipSuccess)
             return hip_fail(e, "launch(reduce)");
         if ((e = launch_scan_summaries(A.aggP, A.aggS, bwd ? nullptr : A.h0, A.carry, A.K, A.C, s)) != hipSuccess)
             return hip_fail(e, "launch(scan_summaries)");
-        if ((e = launch_tile_kernel(plan.tile, KIND_FIXUP, bwd, false, FORM_PLAIN, A, s)) != hipSuccess)
+        if ((e = launch_tile_kernel(plan.tile, KIND_FIXUP, bwd, false, FORM_PLAIN, false, A, s)) != hipSuccess)
             return hip_fail(e, "launch(fixup)");
         return LINREC_OK;
     }
@@ -318,7 +331,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN)
     A.persistent = plan.persistent < 0 ? ((bwd && !gated) ? 0 : 1) : plan.persistent;
     A.grid_cap = (int32_t)opts().grid_cap;
     A.trace = g_trace;
-    if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, form, A, s)) != hipSuccess)
+    if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, form, bf16, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
     return LINREC_OK;
 }
@@ -374,6 +387,56 @@ extern "C" int linrec_backward(const float *lambda, const float *h, const float 
     A.T = T;
     A.C = C;
     return run(A, true, max_vec(C, {lambda, h, h0, grad_h, grad_x, grad_lambda, grad_h0}), s);
+}
+
+extern "C" int linrec_forward_bf16(const uint16_t *lambda, const uint16_t *x, const uint16_t *h0, uint16_t *h_out,
+                                   int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_forward_bf16(lambda, x, h0, h_out, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (T == 0 || C == 0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    // (the kernels' argument block types every tensor float*; with bf16 storage they address 2-byte elements)
+    A.a = (const float *)lambda;
+    A.b = (const float *)x;
+    A.h0 = (const float *)h0;
+    A.out0 = (float *)h_out;
+    A.T = T;
+    A.C = C;
+    return run(A, false, max_vec_bf16(C, {lambda, x, h_out}), (hipStream_t)stream, FORM_PLAIN, true);
+}
+
+extern "C" int linrec_backward_bf16(const uint16_t *lambda, const uint16_t *h, const uint16_t *h0, const uint16_t *grad_h,
+                                    uint16_t *grad_x, uint16_t *grad_lambda, uint16_t *grad_h0, int64_t T, int64_t B,
+                                    int64_t n, void *stream)
+{
+    const int rc = linrec_validate_backward_bf16(lambda, h, h0, grad_h, grad_x, grad_lambda, grad_h0, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (C == 0) return LINREC_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (T == 0) {
+        if (grad_h0) {
+            const hipError_t e = launch_fill16(grad_h0, C, s);
+            if (e != hipSuccess) return hip_fail(e, "launch(fill)");
+        }
+        return LINREC_OK;
+    }
+    if (!grad_x && !grad_lambda && !grad_h0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = (const float *)lambda;
+    A.b = (const float *)grad_h;
+    A.hprev = (const float *)h;
+    A.h0 = (const float *)h0;
+    A.out0 = (float *)grad_x;
+    A.out1 = (float *)grad_lambda;
+    A.gh0 = (float *)grad_h0;
+    A.T = T;
+    A.C = C;
+    return run(A, true, max_vec_bf16(C, {lambda, h, grad_h, grad_x, grad_lambda}), s, FORM_PLAIN, true);
 }
 
 extern "C" int linrec_gilr_forward(const float *g_pre, const float *i_pre, const float *h0, float *h_out, int tau,

@@ -23,9 +23,14 @@
 
 namespace linrec {
 
-template <int VEC_, int R_, int WC_, int WT_>
+// Storage type of the [T, C] tensors and of the [C] state vectors: fp32, or bf16 (the upper half of an
+// fp32; widened exactly on load, rounded to nearest even on store).  Arithmetic is the same either way.
+enum IoType { IO_F32 = 0, IO_BF16 = 1 };
+
+template <int VEC_, int R_, int WC_, int WT_, int IO_ = IO_F32>
 struct Geo {
-    static constexpr int VEC = VEC_, R = R_, WC = WC_, WT = WT_;
+    static constexpr int VEC = VEC_, R = R_, WC = WC_, WT = WT_, IO = IO_;
+    static constexpr int ES = IO_ == IO_F32 ? 4 : 2;  // bytes per stored element
     static constexpr int THREADS = WC * WT, ROWS = WT * R, COLS = WC * VEC;
     // minimum wavefronts per SIMD handed to __launch_bounds__ (1 = leave the choice to the compiler,
     // which lands on 2*R*VEC data registers plus 40-100 of overhead per lane)
@@ -245,6 +250,78 @@ __device__ __forceinline__ void buf_st(rsrc_t rs, uint32_t voff, uint32_t soff, 
     }
 }
 
+// bf16 <-> fp32.  Two bf16 values travel in one 32-bit word, the lower-addressed one in the low half.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned int pack_bf16(float lo, float hi)
+{
+    const vec<2> v = {lo, hi};
+    return __builtin_bit_cast(unsigned int, __builtin_convertvector(v, bf16x2));  // v_cvt_pk_bf16_f32: RNE
+}
+__device__ __forceinline__ float bf16_lo(unsigned int w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(unsigned int w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Tile element access in the geometry's storage type: VEC adjacent columns of one row as fp32.
+template <class G>
+__device__ __forceinline__ vec<G::VEC> gld(rsrc_t rs, uint32_t voff, uint32_t soff)
+{
+    constexpr int N = G::VEC;
+    if constexpr (G::IO == IO_F32) {
+        return buf_ld<N>(rs, voff, soff);
+    } else if constexpr (N == 4) {
+        const u32x2 w = __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
+        return vec<4>{bf16_lo(w[0]), bf16_hi(w[0]), bf16_lo(w[1]), bf16_hi(w[1])};
+    } else if constexpr (N == 2) {
+        const unsigned int w = __builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
+        return vec<2>{bf16_lo(w), bf16_hi(w)};
+    } else {
+        const unsigned short w = __builtin_amdgcn_raw_buffer_load_b16(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
+        return vec<1>(__uint_as_float((unsigned int)w << 16));
+    }
+}
+template <class G>
+__device__ __forceinline__ void gst(rsrc_t rs, uint32_t voff, uint32_t soff, vec<G::VEC> v)
+{
+    constexpr int N = G::VEC;
+    if constexpr (G::IO == IO_F32) {
+        buf_st<N>(rs, voff, soff, v);
+    } else if constexpr (N == 4) {
+        const u32x2 w = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+        __builtin_amdgcn_raw_buffer_store_b64(w, rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
+    } else if constexpr (N == 2) {
+        __builtin_amdgcn_raw_buffer_store_b32(pack_bf16(v[0], v[1]), rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b16((unsigned short)(pack_bf16(v[0], 0.0f) & 0xffffu), rs, voff, soff,
+                                              LINREC_NT_STORE ? kBufNT : 0);
+    }
+}
+// The same for the [C] vectors (initial state and its gradient), addressed by column through a pointer.
+template <class G>
+__device__ __forceinline__ vec<G::VEC> pld(const float *base, int64_t col)
+{
+    constexpr int N = G::VEC;
+    if constexpr (G::IO == IO_F32) {
+        return ld<N>(base + col);
+    } else {
+        const unsigned short *p = reinterpret_cast<const unsigned short *>(base) + col;
+        vec<N> r;
+#pragma unroll
+        for (int i = 0; i < N; ++i) r[i] = __uint_as_float((unsigned int)p[i] << 16);
+        return r;
+    }
+}
+template <class G>
+__device__ __forceinline__ void pst(float *base, int64_t col, vec<G::VEC> v)
+{
+    constexpr int N = G::VEC;
+    if constexpr (G::IO == IO_F32) {
+        st<N>(base + col, v);
+    } else {
+        unsigned short *p = reinterpret_cast<unsigned short *>(base) + col;
+#pragma unroll
+        for (int i = 0; i < N; ++i) p[i] = (unsigned short)(pack_bf16(v[i], 0.0f) & 0xffffu);
+    }
+}
+
 template <class G, bool BWD>
 struct TileAddr {
     int64_t base;   // element index of the tile's reference corner (uniform)
@@ -253,25 +330,27 @@ struct TileAddr {
     uint32_t rowb;  // bytes per row
     int rk;         // rows per thread of this tile: R, or R/2, R/4 for the short tiles at the end of T
     __device__ __forceinline__ TileAddr(const Args &A, int64_t tu0, int g, int tt, int tc, int rk_ = G::R)
-        : total(A.T * A.C), rowb((uint32_t)A.C * 4u), rk(rk_)
+        : total(A.T * A.C), rowb((uint32_t)A.C * (uint32_t)G::ES), rk(rk_)
     {
         if constexpr (!BWD) {
             base = tu0 * A.C + (int64_t)g * G::COLS;
-            toff = (uint32_t)(tt * rk) * rowb + (uint32_t)(tc * G::VEC) * 4u;
+            toff = (uint32_t)(tt * rk) * rowb + (uint32_t)(tc * G::VEC) * (uint32_t)G::ES;
         } else {
             base = (A.T - tu0 - (int64_t)G::WT * rk) * A.C + (int64_t)g * G::COLS;
-            toff = (uint32_t)((G::WT - 1 - tt) * rk) * rowb + (uint32_t)(tc * G::VEC) * 4u;
+            toff = (uint32_t)((G::WT - 1 - tt) * rk) * rowb + (uint32_t)(tc * G::VEC) * (uint32_t)G::ES;
         }
     }
     // Resource for tensor p seen `shift` rows away from the tile (+1: lambda one row ahead, -1: h one
     // row behind; backward only).  Its range ends where the tensor ends.
     __device__ __forceinline__ rsrc_t rsrc(const float *p, int shift = 0) const
     {
-        const int64_t first = base + (int64_t)shift * (int64_t)(rowb / 4u);
-        int64_t bytes = (total - first) * 4;
+        const int64_t first = base + (int64_t)shift * (int64_t)(rowb / (uint32_t)G::ES);
+        int64_t bytes = (total - first) * G::ES;
         if (first < 0 || bytes > 0xffffffffll) bytes = 0xffffffffll;
         if (bytes < 0) bytes = 0;
-        return __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(p + first), 0, (int)(uint32_t)bytes, 0x00020000);
+        // (tensor pointers are typed float* throughout; with bf16 storage they address 2-byte elements)
+        char *origin = reinterpret_cast<char *>(const_cast<float *>(p)) + first * G::ES;
+        return __builtin_amdgcn_make_buffer_rsrc(origin, 0, (int)(uint32_t)bytes, 0x00020000);
     }
     // scalar byte offset of the thread's row j < rk (rows go up with j forward, down backward)
     __device__ __forceinline__ uint32_t soff(int j) const { return (uint32_t)(BWD ? rk - 1 - j : j) * rowb; }
@@ -337,14 +416,14 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
     for (int j = 0; j < R; ++j) {
         vec<VEC> va = splat<VEC>(raw_identity), vb = splat<VEC>(0.0f), v3 = splat<VEC>(0.0f), v4 = splat<VEC>(0.0f);
         if (interior || j < mk.n) {
-            vb = buf_ld<VEC>(rb, ad.toff, ad.soff(j));
-            if constexpr (LSTM) v3 = buf_ld<VEC>(r3, ad.toff, ad.soff(j));
-            if constexpr (LSTM && BWD) v4 = buf_ld<VEC>(r4, ad.toff, ad.soff(j));
+            vb = gld<G>(rb, ad.toff, ad.soff(j));
+            if constexpr (LSTM) v3 = gld<G>(r3, ad.toff, ad.soff(j));
+            if constexpr (LSTM && BWD) v4 = gld<G>(r4, ad.toff, ad.soff(j));
             if constexpr (!BWD) {
-                va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
+                va = gld<G>(ra, ad.toff, ad.soff(j));
             } else {
                 va = splat<VEC>(raw_forget);  // the last row has no successor
-                if (interior || j > 0 || mk.first_has_next) va = buf_ld<VEC>(ra, ad.toff, ad.soff(j));
+                if (interior || j > 0 || mk.first_has_next) va = gld<G>(ra, ad.toff, ad.soff(j));
             }
         }
         r.a[j] = va;
@@ -371,7 +450,7 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
                 vec<VEC> og, oc;
                 gate_both<VEC>(third[j], og, oc);
                 if (want_go && (interior || j < mk.n))
-                    buf_st<VEC>(rgo, ad.toff, ad.soff(j), r.b[j] * cst[j] * (og * oc));
+                    gst<G>(rgo, ad.toff, ad.soff(j), r.b[j] * cst[j] * (og * oc));
                 r.b[j] = r.b[j] * og;
             }
         }
@@ -397,8 +476,8 @@ __device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G,
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         vec<VEC> v = splat<VEC>(0.0f);
-        if (interior || j < mk.nh) v = buf_ld<VEC>(rh, ad.toff, ad.soff(j));
-        else if (j == mk.nh && j < mk.n && A.h0) v = ld<VEC>(A.h0 + col);
+        if (interior || j < mk.nh) v = gld<G>(rh, ad.toff, ad.soff(j));
+        else if (j == mk.nh && j < mk.n && A.h0) v = pld<G>(A.h0, col);
         hp[j] = v;
     }
 }
@@ -441,12 +520,12 @@ __device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD>
     for (int j = 0; j < R; ++j) {
         if (interior || j < mk.n) {
             if constexpr (!BWD) {
-                buf_st<VEC>(r0, ad.toff, ad.soff(j), r.b[j]);
+                gst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
             } else {
-                if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), r.b[j]);
-                if (A.out1) buf_st<VEC>(r1, ad.toff, ad.soff(j), r.b[j] * hp[j]);
+                if (A.out0) gst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
+                if (A.out1) gst<G>(r1, ad.toff, ad.soff(j), r.b[j] * hp[j]);
                 if (!interior && j == mk.nh && A.gh0)  // row t == 0: grad_h0 = lambda[0] * g_0
-                    st<VEC>(A.gh0 + col, ld<VEC>(A.a + col) * r.b[j]);
+                    pst<G>(A.gh0, col, pld<G>(A.a, col) * r.b[j]);
             }
         }
     }
@@ -471,7 +550,7 @@ __device__ __forceinline__ void tile_store_gated_bwd(const Args &A, const TileAd
                  rg = ad.rsrc(A.a);
     const int nv = interior ? R : mk.n;  // the thread's rows j < nv exist
     vec<VEC> c_last = splat<VEC>(__builtin_inff());
-    if (nv > 0) c_last = buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
+    if (nv > 0) c_last = gld<G>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
     c_last = gate_complement<VEC>(c_last);
 #pragma unroll
     for (int j0 = 0; j0 < R; j0 += CH) {
@@ -482,9 +561,9 @@ __device__ __forceinline__ void tile_store_gated_bwd(const Args &A, const TileAd
             hp[q] = splat<VEC>(0.0f);
             y[q] = splat<VEC>(0.0f);
             if (interior || j < mk.n) {
-                y[q] = buf_ld<VEC>(ri, ad.toff, ad.soff(j));
-                if (interior || j < mk.nh) hp[q] = buf_ld<VEC>(rh, ad.toff, ad.soff(j));
-                else if (A.h0) hp[q] = ld<VEC>(A.h0 + col);  // row t == 0
+                y[q] = gld<G>(ri, ad.toff, ad.soff(j));
+                if (interior || j < mk.nh) hp[q] = gld<G>(rh, ad.toff, ad.soff(j));
+                else if (A.h0) hp[q] = pld<G>(A.h0, col);  // row t == 0
             }
         }
 #pragma unroll
@@ -498,9 +577,9 @@ __device__ __forceinline__ void tile_store_gated_bwd(const Args &A, const TileAd
             vec<VEC> di = d * c;
             if (A.tau) di = di * vfma<VEC>(-i, i, splat<VEC>(1.0f));
             if (interior || j < mk.n) {
-                if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), dg);
-                if (A.out1) buf_st<VEC>(r1, ad.toff, ad.soff(j), di);
-                if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, g * d);
+                if (A.out0) gst<G>(r0, ad.toff, ad.soff(j), dg);
+                if (A.out1) gst<G>(r1, ad.toff, ad.soff(j), di);
+                if (!interior && j == mk.nh && A.gh0) pst<G>(A.gh0, col, g * d);
             }
         }
     }
@@ -522,15 +601,15 @@ __device__ __forceinline__ void tile_store_lstm_fwd(const Args &A, const TileAdd
 #pragma unroll
         for (int q = 0; q < CH; ++q) {
             op[q] = splat<VEC>(0.0f);
-            if (A.out1 && (interior || j0 + q < mk.n)) op[q] = buf_ld<VEC>(ro, ad.toff, ad.soff(j0 + q));
+            if (A.out1 && (interior || j0 + q < mk.n)) op[q] = gld<G>(ro, ad.toff, ad.soff(j0 + q));
         }
 #pragma unroll
         for (int q = 0; q < CH; ++q) {
             const int j = j0 + q;
             const vec<VEC> h = gate_value<VEC>(op[q]) * r.b[j];
             if (interior || j < mk.n) {
-                if (A.out0) buf_st<VEC>(r0, ad.toff, ad.soff(j), r.b[j]);
-                if (A.out1) buf_st<VEC>(r1, ad.toff, ad.soff(j), h);
+                if (A.out0) gst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
+                if (A.out1) gst<G>(r1, ad.toff, ad.soff(j), h);
             }
         }
     }
@@ -557,9 +636,9 @@ __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAdd
     // are not among the thread's registers (c0 when that row is t == 0).
     vec<VEC> c_last = splat<VEC>(__builtin_inff()), cp_last = splat<VEC>(0.0f);
     if (nv > 0) {
-        c_last = buf_ld<VEC>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
-        if (interior || nv - 1 < mk.nh) cp_last = buf_ld<VEC>(rcp, ad.toff + ad.soff_rt(nv - 1), 0);
-        else if (A.h0) cp_last = ld<VEC>(A.h0 + col);
+        c_last = gld<G>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
+        if (interior || nv - 1 < mk.nh) cp_last = gld<G>(rcp, ad.toff + ad.soff_rt(nv - 1), 0);
+        else if (A.h0) cp_last = pld<G>(A.h0, col);
     }
     c_last = gate_complement<VEC>(c_last);
 #pragma unroll
@@ -570,8 +649,8 @@ __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAdd
             const int j = j0 + q;
             ip[q] = zp[q] = splat<VEC>(0.0f);
             if (interior || j < mk.n) {
-                ip[q] = buf_ld<VEC>(rip, ad.toff, ad.soff(j));
-                zp[q] = buf_ld<VEC>(rzp, ad.toff, ad.soff(j));
+                ip[q] = gld<G>(rip, ad.toff, ad.soff(j));
+                zp[q] = gld<G>(rzp, ad.toff, ad.soff(j));
             }
         }
 #pragma unroll
@@ -587,10 +666,10 @@ __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAdd
             gate_both<VEC>(ip[q], ig, ic);
             const vec<VEC> z = impulse<VEC>(zp[q], 1);
             if (interior || j < mk.n) {
-                if (A.out0) buf_st<VEC>(rf, ad.toff, ad.soff(j), d * cp * (f * cf));
-                if (A.out1) buf_st<VEC>(ri, ad.toff, ad.soff(j), d * z * (ig * ic));
-                if (A.out2) buf_st<VEC>(rz, ad.toff, ad.soff(j), d * ig * vfma<VEC>(-z, z, splat<VEC>(1.0f)));
-                if (!interior && j == mk.nh && A.gh0) st<VEC>(A.gh0 + col, f * d);
+                if (A.out0) gst<G>(rf, ad.toff, ad.soff(j), d * cp * (f * cf));
+                if (A.out1) gst<G>(ri, ad.toff, ad.soff(j), d * z * (ig * ic));
+                if (A.out2) gst<G>(rz, ad.toff, ad.soff(j), d * ig * vfma<VEC>(-z, z, splat<VEC>(1.0f)));
+                if (!interior && j == mk.nh && A.gh0) pst<G>(A.gh0, col, f * d);
             }
         }
     }
@@ -972,7 +1051,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         bool closed = true;  // this thread's element is a complete state (inclusive state, initial state)
         if (pred < 0 || !col_ok) {
             // before the first tile: the initial state (h0 forward, zero backward)
-            if (!BWD && pred == -1 && col_ok && A.h0) vS = ld<VEC>(A.h0 + col);
+            if (!BWD && pred == -1 && col_ok && A.h0) vS = pld<G>(A.h0, col);
         } else {
             const unsigned long long *w = A.lbAgg + (pred * A.C + col) * 3;
             // Wait on ONE word of the predecessor (the S word of the column group's first column,

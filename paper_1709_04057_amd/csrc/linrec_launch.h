@@ -97,13 +97,16 @@ const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 // load h after the rescan instead of together with lambda and grad_h.  gated: the form of Section
 // 3.1 with sigmoid / tau applied in the kernel (look-back kernels of one-column-per-thread shapes
 // only; hipErrorInvalidValue otherwise).  `form` is FORM_PLAIN, FORM_GATED or FORM_LSTM (the latter
-// for shapes of at most 32 rows per thread).
-hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, const Args &A, hipStream_t s);
+// for shapes of at most 32 rows per thread).  bf16: the tensors hold bf16 (plain form, look-back kernels
+// of shapes with 2 or 4 columns per thread).
+hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A,
+                              hipStream_t s);
 
 hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const float *h0, double *carry, int64_t K,
                                  int64_t C, hipStream_t s);
-hipError_t launch_serial(const Args &A, bool bwd, int form, hipStream_t s);
+hipError_t launch_serial(const Args &A, bool bwd, int form, bool bf16, hipStream_t s);
 hipError_t launch_fill(float *p, float value, int64_t n, hipStream_t s);
+hipError_t launch_fill16(void *p, int64_t n, hipStream_t s);  // n 16-bit zeros
 hipError_t launch_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
                                int64_t n, hipStream_t s);
 

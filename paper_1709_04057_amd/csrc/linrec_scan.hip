@@ -131,6 +131,49 @@ __global__ __launch_bounds__(256) void k_serial_bwd(const float *__restrict__ la
     if (gh0) gh0[c] = lam[c] * g;
 }
 
+// The same two kernels on bf16 storage (fp32 arithmetic, results rounded to nearest even on store).
+__device__ __forceinline__ float bf16_in(const unsigned short *p, int64_t i) { return __uint_as_float((unsigned int)p[i] << 16); }
+__device__ __forceinline__ void bf16_out(unsigned short *p, int64_t i, float v) { p[i] = (unsigned short)(pack_bf16(v, 0.0f) & 0xffffu); }
+
+__global__ __launch_bounds__(256) void k_serial_fwd_bf16(const unsigned short *__restrict__ a, const unsigned short *b,
+                                                         const unsigned short *__restrict__ h0, unsigned short *out,
+                                                         int64_t T, int64_t C)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float s = h0 ? bf16_in(h0, c) : 0.0f;
+#pragma unroll 8
+    for (int64_t t = 0; t < T; ++t) {
+        s = fmaf(bf16_in(a, t * C + c), s, bf16_in(b, t * C + c));
+        bf16_out(out, t * C + c, s);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_serial_bwd_bf16(const unsigned short *__restrict__ lam,
+                                                         const unsigned short *__restrict__ h,
+                                                         const unsigned short *__restrict__ h0, const unsigned short *e,
+                                                         unsigned short *gx, unsigned short *gl, unsigned short *gh0,
+                                                         int64_t T, int64_t C)
+{
+    const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    float g = 0.0f;
+#pragma unroll 4
+    for (int64_t t = T - 1; t >= 0; --t) {
+        const float l = (t + 1 < T) ? bf16_in(lam, (t + 1) * C + c) : 0.0f;
+        g = fmaf(l, g, bf16_in(e, t * C + c));
+        const float hp = (t > 0) ? bf16_in(h, (t - 1) * C + c) : (h0 ? bf16_in(h0, c) : 0.0f);
+        if (gx) bf16_out(gx, t * C + c, g);
+        if (gl) bf16_out(gl, t * C + c, g * hp);
+    }
+    if (gh0) bf16_out(gh0, c, bf16_in(lam, c) * g);
+}
+
+__global__ void k_fill16(unsigned short *p, int64_t n)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
 // The gated form of Section 3.1 (sigmoid and tau applied here), serial over the sequence length.
 __global__ __launch_bounds__(256) void k_serial_gated_fwd(const float *__restrict__ g_pre, const float *i_pre,
                                                           const float *__restrict__ h0, float *out, int tau, int64_t T,
@@ -275,9 +318,21 @@ hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const f
     return hipGetLastError();
 }
 
-hipError_t launch_serial(const Args &A, bool bwd, int form, hipStream_t s)
+hipError_t launch_serial(const Args &A, bool bwd, int form, bool bf16, hipStream_t s)
 {
     const unsigned grid = (unsigned)((A.C + 255) / 256);
+    if (bf16) {
+        if (form != FORM_PLAIN) return hipErrorInvalidValue;
+        typedef const unsigned short *cp;
+        typedef unsigned short *mp;
+        if (!bwd)
+            hipLaunchKernelGGL(k_serial_fwd_bf16, dim3(grid), dim3(256), 0, s, (cp)A.a, (cp)A.b, (cp)A.h0, (mp)A.out0, A.T,
+                               A.C);
+        else
+            hipLaunchKernelGGL(k_serial_bwd_bf16, dim3(grid), dim3(256), 0, s, (cp)A.a, (cp)A.hprev, (cp)A.h0, (cp)A.b,
+                               (mp)A.out0, (mp)A.out1, (mp)A.gh0, A.T, A.C);
+        return hipGetLastError();
+    }
     if (form == FORM_LSTM) {
         if (!bwd)
             hipLaunchKernelGGL(k_serial_lstm_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.c, A.d, A.h0, A.out0, A.out1, A.T,
@@ -299,6 +354,14 @@ hipError_t launch_serial(const Args &A, bool bwd, int form, hipStream_t s)
     else
         hipLaunchKernelGGL(k_serial_bwd, dim3(grid), dim3(256), 0, s, A.a, A.hprev, A.h0, A.b, A.out0, A.out1, A.gh0,
                            A.T, A.C);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill16(void *p, int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    const int64_t blocks = std::min<int64_t>((n + 255) / 256, 65536);
+    hipLaunchKernelGGL(k_fill16, dim3((unsigned)blocks), dim3(256), 0, s, (unsigned short *)p, n);
     return hipGetLastError();
 }
 

@@ -35,9 +35,13 @@ static int64_t resident_capacity(const void *kernel, int threads, int cap_per_cu
 }
 
 template <class G>
-static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, const Args &A, hipStream_t s)
+static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A, hipStream_t s)
 {
     const dim3 grid((unsigned)(A.K * A.G)), block(G::THREADS);
+    // bf16 storage: the plain recurrence's look-back kernels of the shapes with 2 or 4 columns per thread
+    // (4- and 8-byte accesses)
+    constexpr bool kHasBf16 = G::VEC >= 2;
+    if (bf16 && (!kHasBf16 || kind != KIND_LOOKBACK || form != FORM_PLAIN)) return hipErrorInvalidValue;
     // the forms with in-kernel activations exist as look-back kernels of one-column-per-thread shapes
     // (the LSTM cell, which has three operands per row in flight, of at most 32 rows per thread)
     constexpr bool kHasGated = G::VEC == 1, kHasLstm = G::VEC == 1 && G::R <= 32;
@@ -57,6 +61,10 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, const 
         // persistent workgroups: as many as the device holds at once, never more than there are tiles
         void (*kern)(const Args) = !bwd ? k_lookback<G, false, false>
                                         : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
+        if constexpr (kHasBf16) {
+            using GB = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16>;
+            if (bf16) kern = !bwd ? k_lookback<GB, false, false> : hp_late ? k_lookback<GB, true, true> : k_lookback<GB, true, false>;
+        }
         if constexpr (kHasGated) {
             if (form == FORM_GATED)
                 kern = bwd ? k_lookback<G, true, true, FORM_GATED> : k_lookback<G, false, false, FORM_GATED>;
@@ -82,10 +90,10 @@ LINREC_TILES(X)
 #undef X
 #define LINREC_TILE_TYPE LINREC_CAT(TileOf, LINREC_TILE_ID)<0>::type
 
-hipError_t LINREC_CAT(launch_tile_, LINREC_TILE_ID)(Kind kind, bool bwd, bool hp_late, int form, const Args &A,
-                                                    hipStream_t s)
+hipError_t LINREC_CAT(launch_tile_, LINREC_TILE_ID)(Kind kind, bool bwd, bool hp_late, int form, bool bf16,
+                                                    const Args &A, hipStream_t s)
 {
-    return launch_for<LINREC_TILE_TYPE>(kind, bwd, hp_late, form, A, s);
+    return launch_for<LINREC_TILE_TYPE>(kind, bwd, hp_late, form, bf16, A, s);
 }
 
 }  // namespace linrec

@@ -23,13 +23,49 @@ bool shape_ok(int64_t T, int64_t B, int64_t n, int64_t *C, int64_t *E)
     return true;
 }
 
-// Do the element ranges [p, p+np) and [q, q+nq) of fp32 arrays share a byte?
-bool overlaps(const float *p, int64_t np, const float *q, int64_t nq)
+// Do the element ranges [p, p+np) and [q, q+nq) of arrays of es-byte elements share a byte?
+bool overlaps(const void *p, int64_t np, const void *q, int64_t nq, size_t es = sizeof(float))
 {
     if (!p || !q || np == 0 || nq == 0) return false;
-    const uintptr_t a0 = (uintptr_t)p, a1 = a0 + (uintptr_t)np * sizeof(float);
-    const uintptr_t b0 = (uintptr_t)q, b1 = b0 + (uintptr_t)nq * sizeof(float);
+    const uintptr_t a0 = (uintptr_t)p, a1 = a0 + (uintptr_t)np * es;
+    const uintptr_t b0 = (uintptr_t)q, b1 = b0 + (uintptr_t)nq * es;
     return a0 < b1 && b0 < a1;
+}
+
+int validate_forward(const void *lambda, const void *x, const void *h0, const void *h_out, int64_t T, int64_t B,
+                     int64_t n, size_t es)
+{
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (E == 0) return LINREC_OK;
+    if (!lambda || !x || !h_out) return LINREC_ERR_NULL;
+    if (overlaps(h_out, E, lambda, E, es)) return LINREC_ERR_ALIAS;
+    if (h_out != x && overlaps(h_out, E, x, E, es)) return LINREC_ERR_ALIAS;
+    if (overlaps(h_out, E, h0, C, es)) return LINREC_ERR_ALIAS;
+    return LINREC_OK;
+}
+
+int validate_backward(const void *lambda, const void *h, const void *h0, const void *grad_h, const void *grad_x,
+                      const void *grad_lambda, const void *grad_h0, int64_t T, int64_t B, int64_t n, size_t es)
+{
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (C == 0) return LINREC_OK;
+    if (T == 0) return LINREC_OK;  // only grad_h0 (if given) is touched: zero-filled
+    if (!lambda || !h || !grad_h) return LINREC_ERR_NULL;
+    const void *outs[3] = {grad_x, grad_lambda, grad_h0};
+    const int64_t out_len[3] = {E, E, C};
+    const void *ins[4] = {lambda, h, grad_h, h0};
+    const int64_t in_len[4] = {E, E, E, C};
+    for (int o = 0; o < 3; ++o) {
+        for (int i = 0; i < 4; ++i) {
+            if (o == 0 && i == 2 && grad_x == grad_h) continue;  // exact in-place update of the gradient
+            if (overlaps(outs[o], out_len[o], ins[i], in_len[i], es)) return LINREC_ERR_ALIAS;
+        }
+        for (int p = o + 1; p < 3; ++p)
+            if (overlaps(outs[o], out_len[o], outs[p], out_len[p], es)) return LINREC_ERR_ALIAS;
+    }
+    return LINREC_OK;
 }
 
 }  // namespace
@@ -37,38 +73,28 @@ bool overlaps(const float *p, int64_t np, const float *q, int64_t nq)
 extern "C" int linrec_validate_forward(const float *lambda, const float *x, const float *h0, const float *h_out,
                                        int64_t T, int64_t B, int64_t n)
 {
-    int64_t C, E;
-    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
-    if (E == 0) return LINREC_OK;
-    if (!lambda || !x || !h_out) return LINREC_ERR_NULL;
-    if (overlaps(h_out, E, lambda, E)) return LINREC_ERR_ALIAS;
-    if (h_out != x && overlaps(h_out, E, x, E)) return LINREC_ERR_ALIAS;
-    if (overlaps(h_out, E, h0, C)) return LINREC_ERR_ALIAS;
-    return LINREC_OK;
+    return validate_forward(lambda, x, h0, h_out, T, B, n, sizeof(float));
 }
 
 extern "C" int linrec_validate_backward(const float *lambda, const float *h, const float *h0, const float *grad_h,
                                         const float *grad_x, const float *grad_lambda, const float *grad_h0,
                                         int64_t T, int64_t B, int64_t n)
 {
-    int64_t C, E;
-    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
-    if (C == 0) return LINREC_OK;
-    if (T == 0) return LINREC_OK;  // only grad_h0 (if given) is touched: zero-filled
-    if (!lambda || !h || !grad_h) return LINREC_ERR_NULL;
-    const float *outs[3] = {grad_x, grad_lambda, grad_h0};
-    const int64_t out_len[3] = {E, E, C};
-    const float *ins[4] = {lambda, h, grad_h, h0};
-    const int64_t in_len[4] = {E, E, E, C};
-    for (int o = 0; o < 3; ++o) {
-        for (int i = 0; i < 4; ++i) {
-            if (o == 0 && i == 2 && grad_x == grad_h) continue;  // exact in-place update of the gradient
-            if (overlaps(outs[o], out_len[o], ins[i], in_len[i])) return LINREC_ERR_ALIAS;
-        }
-        for (int p = o + 1; p < 3; ++p)
-            if (overlaps(outs[o], out_len[o], outs[p], out_len[p])) return LINREC_ERR_ALIAS;
-    }
-    return LINREC_OK;
+    return validate_backward(lambda, h, h0, grad_h, grad_x, grad_lambda, grad_h0, T, B, n, sizeof(float));
+}
+
+extern "C" int linrec_validate_forward_bf16(const uint16_t *lambda, const uint16_t *x, const uint16_t *h0,
+                                            const uint16_t *h_out, int64_t T, int64_t B, int64_t n)
+{
+    return validate_forward(lambda, x, h0, h_out, T, B, n, sizeof(uint16_t));
+}
+
+extern "C" int linrec_validate_backward_bf16(const uint16_t *lambda, const uint16_t *h, const uint16_t *h0,
+                                             const uint16_t *grad_h, const uint16_t *grad_x,
+                                             const uint16_t *grad_lambda, const uint16_t *grad_h0, int64_t T,
+                                             int64_t B, int64_t n)
+{
+    return validate_backward(lambda, h, h0, grad_h, grad_x, grad_lambda, grad_h0, T, B, n, sizeof(uint16_t));
 }
 
 extern "C" int linrec_validate_gilr_forward(const float *g_pre, const float *i_pre, const float *h0,
@@ -163,4 +189,4 @@ extern "C" const char *linrec_status_string(int status)
     }
 }
 
-extern "C" int linrec_version(void) { return 102; }
+extern "C" int linrec_version(void) { return 103; }

@@ -71,6 +71,21 @@ def test_validate_backward(L):
     assert v(None, None, None, None, None, None, _p(A6), 0, 4, 8) == 0
 
 
+def test_validate_bf16(L):
+    # 2-byte elements: ranges are half as long as the fp32 ones
+    vf, vb = L.linrec_validate_forward_bf16, L.linrec_validate_backward_bf16
+    assert vf(_p(A0), _p(A1), None, _p(A3), 1000, 4, 8) == 0
+    assert vf(_p(A0), _p(A1), None, _p(A1), 1000, 4, 8) == 0                  # exact in-place on x
+    assert vf(_p(A0), _p(A1), None, _p(A1 + 2), 1000, 4, 8) == -3             # shifted by one element
+    assert vf(_p(A0), _p(A1), None, _p(A1 + 2 * E), 1000, 4, 8) == 0          # right behind x: no overlap in bf16
+    assert L.linrec_validate_forward(_p(A0), _p(A1), None, _p(A1 + 2 * E), 1000, 4, 8) == -3   # but in fp32
+    assert vf(None, _p(A1), None, _p(A3), 1000, 4, 8) == -1
+    assert vb(_p(A0), _p(A1), None, _p(A3), _p(A3), _p(A5), None, 1000, 4, 8) == 0
+    assert vb(_p(A0), _p(A1), None, _p(A3), _p(A4), _p(A1), None, 1000, 4, 8) == -3
+    assert L.linrec_forward_bf16(_p(A0), _p(A1), None, _p(A0), 10, 2, 2, None) == -3
+    assert L.linrec_backward_bf16(None, None, None, None, None, None, None, 10, 0, 2, None) == 0
+
+
 def test_validate_gilr(L):
     vf, vb = L.linrec_validate_gilr_forward, L.linrec_validate_gilr_backward
     assert vf(_p(A0), _p(A1), _p(A2), _p(A3), 1, 1000, 4, 8) == 0
