@@ -43,6 +43,9 @@ def parse():
                     help="instead of the workload benchmark, time the parallel (single-pass) kernel against the "
                          "serial-over-T kernel on the grid of the paper's Table 1 (minibatch 1; 4, 32, 128 features; "
                          "T = 16 ... 65536) and print the speed-up ratios as one JSON line")
+    ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage type of the tensors (bf16: linrec_forward_bf16 / linrec_backward_bf16, 6 and 10 "
+                         "bytes per element; the arithmetic is fp32 either way)")
     ap.add_argument("--gated", default="", choices=["", "g2", "g3", "g4"],
                     help="time the gated (GILR) entry points on this workload instead (sigmoid / tanh applied in the "
                          "scan kernel: 12 B/element forward, 24 backward), next to the unfused sequence "
@@ -63,9 +66,9 @@ def cpu_baseline(inp, threads):
     import oracle
     T, B, n = inp["T"], inp["B"], inp["n"]
     C = B * n
-    f = lambda t: None if t is None else t.cpu().numpy().reshape(-1, C)
+    f = lambda t: None if t is None else t.float().cpu().numpy().reshape(-1, C)   # (bf16 values widen exactly)
     lam, x, e = f(inp["lam"]), f(inp["x"]), f(inp["grad_h"])
-    h0 = None if inp["h0"] is None else inp["h0"].cpu().numpy().reshape(-1)
+    h0 = None if inp["h0"] is None else inp["h0"].float().cpu().numpy().reshape(-1)
     oracle.build()
     t0 = time.perf_counter()
     h = oracle.forward(lam, x, h0, threads=threads)
@@ -327,6 +330,12 @@ def main():
         return
 
     inp = wl.make_inputs(args.config, device=dev)
+    bf16 = args.dtype == "bf16"
+    fwd_bpe, bwd_bpe = (FWD_BYTES_PER_EL / 2, BWD_BYTES_PER_EL / 2) if bf16 else (FWD_BYTES_PER_EL, BWD_BYTES_PER_EL)
+    if bf16:
+        for k in ("lam", "x", "h0", "grad_h"):
+            if inp[k] is not None:
+                inp[k] = inp[k].to(torch.bfloat16).contiguous()
     T, B, n = inp["T"], inp["B"], inp["n"]
     E = T * B * n
     lam, x, h0 = inp["lam"], inp["x"], inp["h0"]
@@ -335,7 +344,7 @@ def main():
     h = torch.empty_like(x)
     gx = torch.empty_like(x) if do_bwd else None
     gl = torch.empty_like(x) if do_bwd else None
-    gh0 = torch.empty((B, n), device=dev) if do_bwd else None
+    gh0 = torch.empty((B, n), device=dev, dtype=x.dtype) if do_bwd else None
     stream = torch.cuda.current_stream()
 
     def fwd():
@@ -346,7 +355,7 @@ def main():
         lr.linrec_set_option(lr.OPT_TILE, args.tile_bwd)
         lr.linrec_backward(lam, h, h0, e, grad_x=gx, grad_lambda=gl, grad_h0=gh0, stream=stream)
 
-    if not args.no_tune and args.variant in ("auto", "lookback"):
+    if not args.no_tune and args.variant in ("auto", "lookback") and not bf16:
         if not args.tile_fwd:
             lr.linrec_tune(T, B, n, backward=False, stream=stream)
         if do_bwd and not args.tile_bwd:
@@ -388,28 +397,32 @@ def main():
     fwd_ms = sorted(ev[i][0].elapsed_time(ev[i][1]) for i in range(K))
     bwd_ms = sorted(ev[i][1].elapsed_time(ev[i][2]) for i in range(K))
     fwd_avg, bwd_avg = sum(fwd_ms) / K, sum(bwd_ms) / K
-    fwd_gbs = FWD_BYTES_PER_EL * E / (fwd_avg * 1e-3) / 1e9
-    bwd_gbs = BWD_BYTES_PER_EL * E / (bwd_avg * 1e-3) / 1e9 if do_bwd else None
+    fwd_gbs = fwd_bpe * E / (fwd_avg * 1e-3) / 1e9
+    bwd_gbs = bwd_bpe * E / (bwd_avg * 1e-3) / 1e9 if do_bwd else None
 
     vf, tf = lr.linrec_plan(T, B, n, backward=False) if not args.tile_fwd else (variant, args.tile_fwd)
     vb, tb = lr.linrec_plan(T, B, n, backward=True) if not args.tile_bwd else (variant, args.tile_bwd)
-    traffic = measured_traffic(args.config, "backward" if do_bwd else "forward")
+    if bf16 and not args.tile_fwd:
+        tf = tb = None      # (linrec_plan reports the fp32 plan; the bf16 entry points pick their own shapes)
+        vb = lr.VARIANT_LOOKBACK
+    traffic = None if bf16 else measured_traffic(args.config, "backward" if do_bwd else "forward")
     if do_bwd:
         roof = {"bound": "hbm", "kernel": "backward pass (look-back kernel)" if vb == lr.VARIANT_LOOKBACK else "backward pass",
                 "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
-                "traffic": traffic, "bytes_per_element": BWD_BYTES_PER_EL, "algorithmic_bytes": BWD_BYTES_PER_EL * E,
+                "traffic": traffic, "bytes_per_element": bwd_bpe, "algorithmic_bytes": bwd_bpe * E,
                 "avg_ms": bwd_avg}
     else:
         roof = {"bound": "hbm", "kernel": "forward pass", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": traffic, "bytes_per_element": FWD_BYTES_PER_EL,
-                "algorithmic_bytes": FWD_BYTES_PER_EL * E, "avg_ms": fwd_avg}
+                "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": traffic, "bytes_per_element": fwd_bpe,
+                "algorithmic_bytes": fwd_bpe * E, "avg_ms": fwd_avg}
 
     out = {
         "metric": "linrec fwd+bwd elements/sec and achieved HBM GB/s (% of MI355X peak)",
         "value": E / (ms_per_step * 1e-3), "unit": "elements/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"cfg{args.config}: forward{'+backward' if do_bwd else ''}, fp32, time-major "
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 arithmetic on bf16 storage" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"cfg{args.config}: forward{'+backward' if do_bwd else ''}, {'bf16 storage' if bf16 else 'fp32'}, time-major "
                                f"[T={T}, B={B}, n={n}]; {wl.CONFIGS[args.config]['note']}",
                    "variant": args.variant, "tile_fwd": tf, "tile_bwd": tb},
         "forward": {"avg_ms": fwd_avg, "min_ms": fwd_ms[0], "median_ms": fwd_ms[K // 2], "GB/s": fwd_gbs,
@@ -417,7 +430,7 @@ def main():
         "backward": None if not do_bwd else {
             "avg_ms": bwd_avg, "min_ms": bwd_ms[0], "median_ms": bwd_ms[K // 2], "GB/s": bwd_gbs,
             "frac_of_peak": bwd_gbs / HBM_PEAK_GBS, "elements/s": E / (bwd_avg * 1e-3)},
-        "combined_GB/s": (FWD_BYTES_PER_EL + (BWD_BYTES_PER_EL if do_bwd else 0)) * E / (ms_per_step * 1e-3) / 1e9,
+        "combined_GB/s": (fwd_bpe + (bwd_bpe if do_bwd else 0)) * E / (ms_per_step * 1e-3) / 1e9,
         "roofline": roof,
     }
     if args.probe:

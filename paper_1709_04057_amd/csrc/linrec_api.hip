@@ -219,6 +219,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && kTiles[p.tile - 1].vec < 2) p.tile = 0;
+    if (p.tile >= 1 && p.tile <= NUM_TILES && !bf16 && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 64) p.tile = 0;
     if (p.tile < 1 || p.tile > NUM_TILES) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
         // The gated form computes a sigmoid and a tanh per element before it can publish a summary:
@@ -226,7 +227,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
         if (gated && T >= 2048 && C > 16) p.tile = C >= 2048 ? 21 : 18;
         if (form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 18;  // (the cell has no 48- or 64-row kernels)
         // bf16 storage: the shapes with two columns (4 bytes) per thread mirror the fp32 choice
-        if (bf16) p.tile = T >= 2048 ? 16 : 15;
+        if (bf16) p.tile = T >= 4096 ? (bwd ? 29 : (C >= 2048 ? 28 : 24)) : T >= 1024 ? 16 : 15;
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
     if (bf16 && vec < 2) p.variant = LINREC_VARIANT_SERIAL;

@@ -322,6 +322,101 @@ __device__ __forceinline__ void pst(float *base, int64_t col, vec<G::VEC> v)
     }
 }
 
+// How a thread keeps one row of its VEC columns between the load and the store.  fp32 storage: the
+// fp32 values themselves.  bf16 storage: the packed words as loaded, two elements per register, widened
+// where they are used -- a register then carries the same number of BYTES in flight as with fp32
+// storage, which is what the achieved bandwidth depends on (holding widened values halved it).
+template <int N>
+using uvec = unsigned int __attribute__((ext_vector_type(N)));
+template <int VEC, int IO>
+struct RowSel {
+    using type = vec<VEC>;
+};
+template <int VEC>
+struct RowSel<VEC, IO_BF16> {
+    static_assert(VEC == 2 || VEC == 4, "bf16 storage: two or four columns per thread");
+    using type = uvec<VEC / 2>;
+};
+template <class G>
+using row_t = typename RowSel<G::VEC, G::IO>::type;
+
+template <class G>
+__device__ __forceinline__ vec<G::VEC> unpack(row_t<G> w)
+{
+    if constexpr (G::IO == IO_F32) {
+        return w;
+    } else {
+        vec<G::VEC> v;
+#pragma unroll
+        for (int i = 0; i < G::VEC / 2; ++i) {
+            v[2 * i] = bf16_lo(w[i]);
+            v[2 * i + 1] = bf16_hi(w[i]);
+        }
+        return v;
+    }
+}
+template <class G>
+__device__ __forceinline__ row_t<G> pack(vec<G::VEC> v)
+{
+    if constexpr (G::IO == IO_F32) {
+        return v;
+    } else {
+        row_t<G> w;
+#pragma unroll
+        for (int i = 0; i < G::VEC / 2; ++i) w[i] = pack_bf16(v[2 * i], v[2 * i + 1]);
+        return w;
+    }
+}
+// Hides where a packed row came from.  The rescan widens the same words the reduce phase widened; left
+// alone, the compiler keeps the widened copies alive from one phase to the other and the tile occupies
+// twice the registers again.
+template <class G>
+__device__ __forceinline__ row_t<G> reread(row_t<G> w)
+{
+    if constexpr (G::IO == IO_BF16) {
+#pragma unroll
+        for (int i = 0; i < G::VEC / 2; ++i) {
+            unsigned int x = w[i];
+            asm volatile("" : "+v"(x));
+            w[i] = x;
+        }
+    }
+    return w;
+}
+// a row of copies of x (x must be a bf16 value when the storage is bf16: 0, 1, +-inf are)
+template <class G>
+__device__ __forceinline__ row_t<G> row_const(float x)
+{
+    if constexpr (G::IO == IO_F32) {
+        return splat<G::VEC>(x);
+    } else {
+        const unsigned int b = __float_as_uint(x);
+        return row_t<G>((b >> 16) | (b & 0xffff0000u));
+    }
+}
+template <class G>
+__device__ __forceinline__ row_t<G> rld(rsrc_t rs, uint32_t voff, uint32_t soff)
+{
+    if constexpr (G::IO == IO_F32) {
+        return buf_ld<G::VEC>(rs, voff, soff);
+    } else if constexpr (G::VEC == 4) {
+        return __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
+    } else {
+        return row_t<G>(__builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0));
+    }
+}
+template <class G>
+__device__ __forceinline__ void rst(rsrc_t rs, uint32_t voff, uint32_t soff, row_t<G> w)
+{
+    if constexpr (G::IO == IO_F32) {
+        buf_st<G::VEC>(rs, voff, soff, w);
+    } else if constexpr (G::VEC == 4) {
+        __builtin_amdgcn_raw_buffer_store_b64(w, rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
+    } else {
+        __builtin_amdgcn_raw_buffer_store_b32(w[0], rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
+    }
+}
+
 template <class G, bool BWD>
 struct TileAddr {
     int64_t base;   // element index of the tile's reference corner (uniform)
@@ -361,7 +456,7 @@ struct TileAddr {
 // The thread's R rows of the two scan operands.
 template <class G>
 struct Rows {
-    vec<G::VEC> a[G::R], b[G::R];
+    row_t<G> a[G::R], b[G::R];
 };
 
 // Which of the thread's R rows exist, as small integers computed once per tile (row j is compared
@@ -414,16 +509,17 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
     const bool want_go = LSTM && BWD && A.out3 != nullptr;
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        vec<VEC> va = splat<VEC>(raw_identity), vb = splat<VEC>(0.0f), v3 = splat<VEC>(0.0f), v4 = splat<VEC>(0.0f);
+        row_t<G> va = row_const<G>(raw_identity), vb = row_const<G>(0.0f);
+        vec<VEC> v3 = splat<VEC>(0.0f), v4 = splat<VEC>(0.0f);
         if (interior || j < mk.n) {
-            vb = gld<G>(rb, ad.toff, ad.soff(j));
+            vb = rld<G>(rb, ad.toff, ad.soff(j));
             if constexpr (LSTM) v3 = gld<G>(r3, ad.toff, ad.soff(j));
             if constexpr (LSTM && BWD) v4 = gld<G>(r4, ad.toff, ad.soff(j));
             if constexpr (!BWD) {
-                va = gld<G>(ra, ad.toff, ad.soff(j));
+                va = rld<G>(ra, ad.toff, ad.soff(j));
             } else {
-                va = splat<VEC>(raw_forget);  // the last row has no successor
-                if (interior || j > 0 || mk.first_has_next) va = gld<G>(ra, ad.toff, ad.soff(j));
+                va = row_const<G>(raw_forget);  // the last row has no successor
+                if (interior || j > 0 || mk.first_has_next) va = rld<G>(ra, ad.toff, ad.soff(j));
             }
         }
         r.a[j] = va;
@@ -469,15 +565,15 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
 template <class G>
 __device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G, true> &ad,
                                                 const RowMask<G, true> &mk, int64_t col, bool interior,
-                                                vec<G::VEC> (&hp)[G::R])
+                                                row_t<G> (&hp)[G::R])
 {
-    constexpr int R = G::R, VEC = G::VEC;
+    constexpr int R = G::R;
     const rsrc_t rh = ad.rsrc(A.hprev, -1);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
-        vec<VEC> v = splat<VEC>(0.0f);
-        if (interior || j < mk.nh) v = gld<G>(rh, ad.toff, ad.soff(j));
-        else if (j == mk.nh && j < mk.n && A.h0) v = pld<G>(A.h0, col);
+        row_t<G> v = row_const<G>(0.0f);
+        if (interior || j < mk.nh) v = rld<G>(rh, ad.toff, ad.soff(j));
+        else if (j == mk.nh && j < mk.n && A.h0) v = pack<G>(pld<G>(A.h0, col));
         hp[j] = v;
     }
 }
@@ -487,12 +583,13 @@ __device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G,
 template <class G, int FORM = FORM_PLAIN>
 __device__ __forceinline__ void local_reduce(const Rows<G> &r, dvec<G::VEC> &P, vec<G::VEC> &S)
 {
-    dvec<G::VEC> p = factor<FORM, G::VEC>(r.a[0]);
-    vec<G::VEC> s = r.b[0];
+    dvec<G::VEC> p = factor<FORM, G::VEC>(unpack<G>(r.a[0]));
+    vec<G::VEC> s = unpack<G>(r.b[0]);
 #pragma unroll
     for (int j = 1; j < G::R; ++j) {
-        p *= factor<FORM, G::VEC>(r.a[j]);
-        s = step<FORM, G::VEC>(r.a[j], s, r.b[j]);
+        const vec<G::VEC> a = unpack<G>(r.a[j]);
+        p *= factor<FORM, G::VEC>(a);
+        s = step<FORM, G::VEC>(a, s, unpack<G>(r.b[j]));
     }
     P = p;
     S = s;
@@ -505,25 +602,44 @@ __device__ __forceinline__ void rescan(Rows<G> &r, vec<G::VEC> c)
     vec<G::VEC> s = c;
 #pragma unroll
     for (int j = 0; j < G::R; ++j) {
-        s = step<FORM, G::VEC>(r.a[j], s, r.b[j]);
-        r.b[j] = s;
+        s = step<FORM, G::VEC>(unpack<G>(reread<G>(r.a[j])), s, unpack<G>(reread<G>(r.b[j])));
+        r.b[j] = pack<G>(s);  // (bf16 storage: the stored value is rounded, the running state is not)
+    }
+}
+
+// bf16 storage, backward: the products that depend on the unrounded g_t are formed while it is at hand.
+// hp[j] (h one row behind) becomes grad_lambda, and grad_h0 = lambda[0]*g_0 is written from the row t == 0.
+template <class G>
+__device__ __forceinline__ void rescan_bwd_packed(const Args &A, const RowMask<G, true> &mk, int64_t col, bool interior,
+                                                  Rows<G> &r, row_t<G> (&hp)[G::R], vec<G::VEC> c)
+{
+    vec<G::VEC> s = c;
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) {
+        s = step<FORM_PLAIN, G::VEC>(unpack<G>(reread<G>(r.a[j])), s, unpack<G>(reread<G>(r.b[j])));
+        r.b[j] = pack<G>(s);
+        hp[j] = pack<G>(s * unpack<G>(hp[j]));
+        if (!interior && j == mk.nh && j < mk.n && A.gh0) pst<G>(A.gh0, col, pld<G>(A.a, col) * s);
     }
 }
 
 template <class G, bool BWD>
 __device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
-                                           int64_t col, bool interior, const Rows<G> &r, const vec<G::VEC> *hp)
+                                           int64_t col, bool interior, const Rows<G> &r, const row_t<G> *hp)
 {
-    constexpr int R = G::R, VEC = G::VEC;
+    constexpr int R = G::R;
     const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(BWD ? A.out1 : A.out0);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         if (interior || j < mk.n) {
             if constexpr (!BWD) {
-                gst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
+                rst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
+            } else if constexpr (G::IO == IO_BF16) {  // (rescan_bwd_packed has formed grad_lambda and grad_h0)
+                if (A.out0) rst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
+                if (A.out1) rst<G>(r1, ad.toff, ad.soff(j), hp[j]);
             } else {
-                if (A.out0) gst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
-                if (A.out1) gst<G>(r1, ad.toff, ad.soff(j), r.b[j] * hp[j]);
+                if (A.out0) rst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
+                if (A.out1) rst<G>(r1, ad.toff, ad.soff(j), r.b[j] * hp[j]);
                 if (!interior && j == mk.nh && A.gh0)  // row t == 0: grad_h0 = lambda[0] * g_0
                     pst<G>(A.gh0, col, pld<G>(A.a, col) * r.b[j]);
             }
@@ -877,7 +993,8 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_fixup(const Args A)
         const bool interior = tile_interior<G, BWD>(A, tu0, g);
         const int64_t u0 = tu0 + (int64_t)tt * R;
         Rows<G> r;
-        vec<VEC> hp[BWD ? R : 1], S, Se, St;
+        row_t<G> hp[BWD ? R : 1];
+        vec<VEC> S, Se, St;
         dvec<VEC> P, Pe, Pt;
         const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
         const RowMask<G, BWD> mk(A, u0, col_ok);
@@ -988,7 +1105,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     LINREC_TRACE_MARK(0);
 
     Rows<G> r;
-    vec<VEC> hp[(BWD && FORM == FORM_PLAIN) ? R : 1];
+    row_t<G> hp[(BWD && FORM == FORM_PLAIN) ? R : 1];
     const TileAddr<G, BWD> ad(A, tu0, g, tt, tc, rk);
     const RowMask<G, BWD> mk(A, u0, col_ok, rk);
     constexpr int NC = (BWD && FORM == FORM_LSTM) ? R : 1;
@@ -1128,7 +1245,12 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         if (A.persistent) next_ticket = atomicAdd(&A.hdr->ticket, 1ull);
         else finished = atomicAdd(&A.hdr->done, 1ull) + 1ull;
     }
-    rescan<G, FORM>(r, vfma<VEC>(Pe32, Sr, Se32));
+    if constexpr (BWD && G::IO == IO_BF16) {
+        static_assert(FORM == FORM_PLAIN && !HP_LATE, "bf16 storage: the plain recurrence, h loaded with the tile");
+        rescan_bwd_packed<G>(A, mk, col, interior, r, hp, vfma<VEC>(Pe32, Sr, Se32));
+    } else {
+        rescan<G, FORM>(r, vfma<VEC>(Pe32, Sr, Se32));
+    }
     if constexpr (BWD && FORM == FORM_GATED) {
         __builtin_amdgcn_sched_barrier(0);  // the epilogue's loads stay behind the rescan
         tile_store_gated_bwd<G>(A, ad, mk, col, interior, r);

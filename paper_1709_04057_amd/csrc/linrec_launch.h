@@ -65,6 +65,8 @@ struct TileDesc {
 // Tile shapes, 1-based ids as used by LINREC_OPT_TILE: (id, columns per thread, rows per thread,
 // threads along columns, threads along time).  A shape with v columns per thread makes 4v-byte
 // accesses and needs C % v == 0 and 4v-byte aligned tensors; v = 1 works for any C and alignment.
+// (With bf16 storage the accesses are 2v bytes and v is 2 or 4.)  Shapes with more than 64 elements per
+// thread (ids 24 and up) exist for bf16 storage only, where two elements share a register.
 #define LINREC_TILES(X) \
     X(1, 1, 8, 64, 4)   \
     X(2, 1, 8, 16, 16)  \
@@ -88,8 +90,14 @@ struct TileDesc {
     X(20, 1, 64, 64, 4)  \
     X(21, 1, 32, 64, 4)  \
     X(22, 1, 64, 32, 16) \
-    X(23, 1, 64, 16, 16)
-constexpr int NUM_TILES = 23;
+    X(23, 1, 64, 16, 16) \
+    X(24, 2, 64, 32, 8)  \
+    X(25, 2, 64, 16, 16) \
+    X(26, 4, 32, 16, 16) \
+    X(27, 4, 32, 32, 8)  \
+    X(28, 2, 64, 64, 4)  \
+    X(29, 2, 48, 32, 8)
+constexpr int NUM_TILES = 29;
 
 const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 

@@ -38,47 +38,50 @@ template <class G>
 static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A, hipStream_t s)
 {
     const dim3 grid((unsigned)(A.K * A.G)), block(G::THREADS);
-    // bf16 storage: the plain recurrence's look-back kernels of the shapes with 2 or 4 columns per thread
-    // (4- and 8-byte accesses)
-    constexpr bool kHasBf16 = G::VEC >= 2;
-    if (bf16 && (!kHasBf16 || kind != KIND_LOOKBACK || form != FORM_PLAIN)) return hipErrorInvalidValue;
-    // the forms with in-kernel activations exist as look-back kernels of one-column-per-thread shapes
-    // (the LSTM cell, which has three operands per row in flight, of at most 32 rows per thread)
-    constexpr bool kHasGated = G::VEC == 1, kHasLstm = G::VEC == 1 && G::R <= 32;
-    if (form != FORM_PLAIN && kind != KIND_LOOKBACK) return hipErrorInvalidValue;
-    if ((form == FORM_GATED && !kHasGated) || (form == FORM_LSTM && !kHasLstm) || form < FORM_PLAIN || form > FORM_LSTM)
-        return hipErrorInvalidValue;
-    switch (kind) {
-    case KIND_REDUCE:
-        if (bwd) hipLaunchKernelGGL((k_reduce<G, true>), grid, block, 0, s, A);
-        else hipLaunchKernelGGL((k_reduce<G, false>), grid, block, 0, s, A);
-        break;
-    case KIND_FIXUP:
-        if (bwd) hipLaunchKernelGGL((k_fixup<G, true>), grid, block, 0, s, A);
-        else hipLaunchKernelGGL((k_fixup<G, false>), grid, block, 0, s, A);
-        break;
-    case KIND_LOOKBACK: {
-        // persistent workgroups: as many as the device holds at once, never more than there are tiles
-        void (*kern)(const Args) = !bwd ? k_lookback<G, false, false>
-                                        : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
-        if constexpr (kHasBf16) {
-            using GB = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16>;
-            if (bf16) kern = !bwd ? k_lookback<GB, false, false> : hp_late ? k_lookback<GB, true, true> : k_lookback<GB, true, false>;
+    // Which kernels exist for this shape:
+    //   fp32 storage       shapes of at most 64 elements per thread and operand (one register each)
+    //   bf16 storage       the plain recurrence's look-back kernels of the shapes with 2 or 4 columns per
+    //                      thread (4- and 8-byte accesses); two elements share a register, so these go up
+    //                      to 128 elements per thread
+    //   gated layer        look-back kernels of one-column-per-thread shapes
+    //   LSTM cell          the same, of at most 32 rows per thread (three operands per row in flight)
+    constexpr bool kHasF32 = G::R * G::VEC <= 64, kHasBf16 = G::VEC >= 2;
+    constexpr bool kHasGated = kHasF32 && G::VEC == 1, kHasLstm = kHasGated && G::R <= 32;
+    if (form < FORM_PLAIN || form > FORM_LSTM) return hipErrorInvalidValue;
+    if ((form != FORM_PLAIN || bf16) && kind != KIND_LOOKBACK) return hipErrorInvalidValue;
+    if (bf16 ? (!kHasBf16 || form != FORM_PLAIN) : !kHasF32) return hipErrorInvalidValue;
+    if ((form == FORM_GATED && !kHasGated) || (form == FORM_LSTM && !kHasLstm)) return hipErrorInvalidValue;
+    void (*kern)(const Args) = nullptr;
+    if constexpr (kHasF32) {
+        switch (kind) {
+        case KIND_REDUCE:
+            if (bwd) hipLaunchKernelGGL((k_reduce<G, true>), grid, block, 0, s, A);
+            else hipLaunchKernelGGL((k_reduce<G, false>), grid, block, 0, s, A);
+            return hipGetLastError();
+        case KIND_FIXUP:
+            if (bwd) hipLaunchKernelGGL((k_fixup<G, true>), grid, block, 0, s, A);
+            else hipLaunchKernelGGL((k_fixup<G, false>), grid, block, 0, s, A);
+            return hipGetLastError();
+        case KIND_LOOKBACK:
+            kern = !bwd ? k_lookback<G, false, false> : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
+            break;
         }
-        if constexpr (kHasGated) {
-            if (form == FORM_GATED)
-                kern = bwd ? k_lookback<G, true, true, FORM_GATED> : k_lookback<G, false, false, FORM_GATED>;
-        }
-        if constexpr (kHasLstm) {
-            if (form == FORM_LSTM)
-                kern = bwd ? k_lookback<G, true, true, FORM_LSTM> : k_lookback<G, false, false, FORM_LSTM>;
-        }
-        const int64_t cap = resident_capacity(reinterpret_cast<const void *>(kern), G::THREADS, A.grid_cap);
-        const dim3 pgrid((unsigned)(A.persistent ? std::min<int64_t>(A.K * A.G, cap) : A.K * A.G));
-        hipLaunchKernelGGL(kern, pgrid, block, 0, s, A);
-        break;
     }
+    if constexpr (kHasBf16) {
+        using GB = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16>;
+        if (bf16) kern = !bwd ? k_lookback<GB, false, false> : k_lookback<GB, true, false>;
     }
+    if constexpr (kHasGated) {
+        if (form == FORM_GATED) kern = bwd ? k_lookback<G, true, true, FORM_GATED> : k_lookback<G, false, false, FORM_GATED>;
+    }
+    if constexpr (kHasLstm) {
+        if (form == FORM_LSTM) kern = bwd ? k_lookback<G, true, true, FORM_LSTM> : k_lookback<G, false, false, FORM_LSTM>;
+    }
+    if (!kern) return hipErrorInvalidValue;
+    // persistent workgroups: as many as the device holds at once, never more than there are tiles
+    const int64_t cap = resident_capacity(reinterpret_cast<const void *>(kern), G::THREADS, A.grid_cap);
+    const dim3 pgrid((unsigned)(A.persistent ? std::min<int64_t>(A.K * A.G, cap) : A.K * A.G));
+    hipLaunchKernelGGL(kern, pgrid, block, 0, s, A);
     return hipGetLastError();
 }
 
