@@ -68,10 +68,17 @@ def main():
         copy_avg = sum(copy) / len(copy)
         factors[counter] = 4.0 * E / copy_avg    # bytes per counter unit
         lines.append(f"{counter}: copy kernel reads {copy_avg:.1f} per launch for {4 * E} bytes -> {factors[counter]:.2f} bytes per unit")
+        # several kernels of one kind may have run (linrec_tune times its candidates during warm-up):
+        # the one with the most launches is the plan's
+        best = {}
         for name, vs in per.items():
             kind = _kind(name)
             if kind is None or kind == "stream_probe":
                 continue
+            if kind not in best or len(vs) > len(per[best[kind]]):
+                best[kind] = name
+        for kind, name in best.items():
+            vs = per[name]
             d = res["kernels"].setdefault(kind, {"name": name})
             d[counter] = sum(vs) / len(vs)
             d[counter + "_launches"] = len(vs)
