@@ -1,0 +1,105 @@
+"""The gated layer, the LSTM cell and the bf16-storage entry points share the single-pass kernel's
+device-resident call state: they must be deterministic, safe on side streams that interleave with
+other calls of the library, and replayable from a HIP graph."""
+import pytest
+import torch
+
+import linrec_workloads as wl
+import paper_1709_04057_amd as lr
+from parity import options, say
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+PRE = ("f_pre", "i_pre", "z_pre", "o_pre")
+
+
+def _calls():
+    """name -> (function enqueuing forward+backward on the current stream, list of its output tensors)."""
+    g = wl.make_gated(12000, 2, 96, seed=1, device=DEV, gate_mean=1.5)
+    c = wl.make_lstm(12000, 2, 96, seed=2, device=DEV)
+    b = {k: (v.to(torch.bfloat16).contiguous() if torch.is_tensor(v) else v)
+         for k, v in wl.make_inputs(2, T=12000, B=2, n=96, device=DEV).items()}
+    out = {}
+
+    hg = torch.empty_like(g["g_pre"]); gg = torch.empty_like(hg); gi = torch.empty_like(hg)
+    gh0 = torch.empty_like(g["h0"])
+
+    def gated():
+        lr.linrec_gilr_forward(g["g_pre"], g["i_pre"], g["h0"], h_out=hg)
+        lr.linrec_gilr_backward(g["g_pre"], g["i_pre"], hg, g["h0"], g["grad_h"], grad_g_pre=gg, grad_i_pre=gi,
+                                grad_h0=gh0)
+    out["gated"] = (gated, [hg, gg, gi, gh0])
+
+    pre = [c[k] for k in PRE]
+    cs = torch.empty_like(pre[0]); hs = torch.empty_like(cs)
+    grads = [torch.empty_like(cs) for _ in range(4)]
+    gc0 = torch.empty_like(c["c0"])
+
+    def cell():
+        lr.linrec_lstm_cell_forward(*pre, c["c0"], c_out=cs, h_out=hs)
+        lr.linrec_lstm_cell_backward(*pre, cs, c["c0"], c["grad_h"], grads=grads, grad_c0=gc0)
+    out["lstm"] = (cell, [cs, hs] + grads + [gc0])
+
+    hb = torch.empty_like(b["x"]); gx = torch.empty_like(hb); gl = torch.empty_like(hb)
+    gb0 = torch.empty_like(b["h0"])
+
+    def bf16():
+        lr.linrec_forward(b["lam"], b["x"], b["h0"], h_out=hb)
+        lr.linrec_backward(b["lam"], hb, b["h0"], b["grad_h"], grad_x=gx, grad_lambda=gl, grad_h0=gb0)
+    out["bf16"] = (bf16, [hb, gx, gl, gb0])
+    return out
+
+
+def _same(a, b):
+    # bit-identical, NaN-safe
+    return torch.equal(a.view(torch.int16 if a.dtype == torch.bfloat16 else torch.int32),
+                       b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
+
+
+@pytest.mark.parametrize("name", ["gated", "lstm", "bf16"])
+def test_deterministic_on_interleaved_streams(name):
+    calls = _calls()
+    fn, outs = calls[name]
+    fn()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in outs]
+    others = [calls[k][0] for k in calls if k != name]
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for rep in range(3):
+        for t in outs:
+            t.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s1):
+            fn()
+        with torch.cuda.stream(s2):          # other entry points of the library at the same time, own workspace
+            for o in others:
+                o()
+        s1.synchronize(); s2.synchronize()
+        assert all(_same(a, b) for a, b in zip(outs, ref)), f"{name}: run {rep} differs"
+    for s in (s1, s2, torch.cuda.current_stream()):
+        lr.linrec_check(s)
+
+
+@pytest.mark.parametrize("name", ["gated", "lstm", "bf16"])
+def test_hip_graph_replay(name):
+    fn, outs = _calls()[name]
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with options(variant=lr.VARIANT_LOOKBACK), torch.cuda.stream(s):
+        for _ in range(2):                   # allocates the stream's workspace: not capturable
+            fn()
+        s.synchronize()
+        ref = [t.clone() for t in outs]
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            fn()
+        for rep in range(3):
+            say(f"{name}: graph replay {rep}")
+            for t in outs:
+                t.zero_()
+            g.replay()
+            s.synchronize()
+            assert all(_same(a, b) for a, b in zip(outs, ref)), f"{name}: replay {rep} differs from eager"
+            fn()                             # eager work on the same stream between replays
+            s.synchronize()
+        lr.linrec_check(s)
