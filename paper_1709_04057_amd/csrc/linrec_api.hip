@@ -48,7 +48,7 @@ struct Options {
     int64_t chunk_tiles = 0;
     int64_t spin_limit = 1 << 22;
     int64_t hp_late = -1;  // -1 automatic
-    int64_t taper = 2;
+    int64_t taper = 0;
     int64_t grid_cap = 0;
     int64_t persistent = -1;  // -1 automatic: forward persistent, backward one workgroup per tile (measured)
     Options()

@@ -103,3 +103,23 @@ def test_hip_graph_replay(name):
             fn()                             # eager work on the same stream between replays
             s.synchronize()
         lr.linrec_check(s)
+
+
+@pytest.mark.parametrize("taper", [2, 8])
+def test_tapered_tail_tiles_every_entry_point(taper):
+    """LINREC_OPT_TAPER (off by default) ends the sequence on half- and quarter-height tiles: same results
+    to tolerance for every entry point that runs the single-pass kernel."""
+    import numpy as np
+
+    import oracle
+    from parity import fwd_bwd_check
+    from test_bf16_parity_gpu import bf16_check, to_bf16
+    from test_gilr_parity_gpu import gated_check
+    from test_lstm_parity_gpu import cell_check
+
+    T = 40_000          # enough tiles per column for the tapered region to hold several short tiles
+    with options(variant=lr.VARIANT_LOOKBACK, taper=taper):
+        fwd_bwd_check(wl.make_generic(T, 1, 70, seed=31, device=DEV), f"taper {taper} plain")
+        gated_check(wl.make_gated(T, 1, 70, seed=32, device=DEV, gate_mean=1.0), lr.TAU_TANH, f"taper {taper} gated")
+        cell_check(wl.make_lstm(T, 1, 70, seed=33, device=DEV), f"taper {taper} lstm")
+        bf16_check(to_bf16(wl.make_generic(T, 1, 72, seed=34, device=DEV)), f"taper {taper} bf16")
