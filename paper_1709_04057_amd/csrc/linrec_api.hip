@@ -146,13 +146,6 @@ int max_vec_bf16(int64_t C, std::initializer_list<const void *> ptrs)
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-int pow2_at_least(int64_t x)
-{
-    int p = 1;
-    while (p < x) p <<= 1;
-    return p;
-}
-
 // Tile shape for a [T, C] problem when the caller did not fix one.  Measured on MI355X: one column
 // per thread with many rows per thread (few registers beyond the rows themselves, so three
 // workgroups fit a compute unit), 128-byte row segments, and tiles as tall as T allows (the taller

@@ -18,6 +18,12 @@
 // t = T-1-u, the multiplier of step u is lambda[t+1] (0 for u == 0: the last row has no successor
 // and row T of lambda is never read), the addend is grad_h[t], and the outputs are
 // grad_x[t] = g_t, grad_lambda[t] = g_t*h[t-1] (h[-1] = h0), grad_h0 = lambda[0]*g_0.
+//
+// Two things vary around that core.  The FORM (template parameter of the tile functions): the plain
+// recurrence, the gated layer of Section 3.1 or the LSTM cell of Section 3.2, the latter two with
+// their activations applied in a prologue after the loads and their chain rule in an epilogue before
+// the stores.  And the STORAGE type of the tensors (part of the tile geometry): fp32, or bf16 with
+// the packed words kept in registers; the arithmetic is fp32 steps and fp64 chunk products always.
 #pragma once
 #include "linrec_launch.h"
 
@@ -135,12 +141,6 @@ __device__ __forceinline__ dvec<N> factor(vec<N> a)
     if constexpr (FORM == FORM_PLAIN) return widen<N>(a);
     else return dsplat<N>(1.0) - widen<N>(a);
 }
-// the multiplier that makes a step the identity / that forgets the state (g = 0)
-template <int FORM, int N>
-__device__ __forceinline__ vec<N> mult_identity() { return splat<N>(FORM == FORM_PLAIN ? 1.0f : 0.0f); }
-template <int FORM, int N>
-__device__ __forceinline__ vec<N> mult_forget() { return splat<N>(FORM == FORM_PLAIN ? 0.0f : 1.0f); }
-
 // sigmoid(-z) and sigmoid(z) from one exponential of -|z|: both keep their relative accuracy in
 // either tail.  v_exp_f32 / v_rcp_f32 are good to about one ulp.
 __device__ __forceinline__ void gate_pair(float z, float &g, float &c)
