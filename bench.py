@@ -217,6 +217,22 @@ def gated_bench(args, lr, torch, wl):
     out["roofline"]["traffic"] = measured_traffic(args.gated, "backward", "gated:")
     if args.probe:
         out["stream_probe"] = stream_probe(lr, torch, E, stream)
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
+        C = B * n
+        f = lambda t: t.cpu().numpy().reshape(-1, C)
+        gp, ip, ee, hh = f(g_pre), f(i_pre), f(e), f(h)
+        h0v = h0.cpu().numpy().reshape(-1)
+        oracle.build()
+        t0 = time.perf_counter()
+        oracle.gilr_forward(gp, ip, h0v, threads=threads)
+        t1 = time.perf_counter()
+        oracle.gilr_backward(gp, ip, hh, h0v, ee, threads=threads)
+        t2 = time.perf_counter()
+        out["cpu_baseline"] = {"value": E / (t2 - t0), "unit": "elements/s", "cores": threads, "kind": "oracle",
+                               "sample": f"the full workload, one forward + one backward pass of the fp64 oracle of the gated "
+                                         f"layer over {threads} host threads; forward {t1 - t0:.3f} s, backward {t2 - t1:.3f} s"}
     print(json.dumps(out), flush=True)
 
 
@@ -288,6 +304,23 @@ def lstm_bench(args, lr, torch, wl):
     out["roofline"]["traffic"] = measured_traffic(args.lstm, "backward", "lstm:")
     if args.probe:
         out["stream_probe"] = stream_probe(lr, torch, E, stream)
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
+        C = B * n
+        f = lambda t: t.cpu().numpy().reshape(-1, C)
+        pp = [f(p) for p in pre]
+        c0v = c0.cpu().numpy().reshape(-1)
+        ee, cc = f(e), f(c)
+        oracle.build()
+        t0 = time.perf_counter()
+        oracle.lstm_forward(*pp, c0v, threads=threads)
+        t1 = time.perf_counter()
+        oracle.lstm_backward(*pp, cc, c0v, ee, threads=threads)
+        t2 = time.perf_counter()
+        out["cpu_baseline"] = {"value": E / (t2 - t0), "unit": "elements/s", "cores": threads, "kind": "oracle",
+                               "sample": f"the full workload, one forward + one backward pass of the fp64 oracle of the LSTM "
+                                         f"cell over {threads} host threads; forward {t1 - t0:.3f} s, backward {t2 - t1:.3f} s"}
     print(json.dumps(out), flush=True)
 
 

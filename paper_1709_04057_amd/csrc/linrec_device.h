@@ -1146,7 +1146,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         }
     }
     LINREC_TRACE_MARK(2);
-    int n_windows = 0;
+    [[maybe_unused]] int n_windows = 0;  // (read by trace builds)
     unsigned long long next_ticket = 0xffffffffull;
 
     // ---- look-back --------------------------------------------------------------------------
