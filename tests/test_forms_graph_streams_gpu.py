@@ -123,3 +123,21 @@ def test_tapered_tail_tiles_every_entry_point(taper):
         gated_check(wl.make_gated(T, 1, 70, seed=32, device=DEV, gate_mean=1.0), lr.TAU_TANH, f"taper {taper} gated")
         cell_check(wl.make_lstm(T, 1, 70, seed=33, device=DEV), f"taper {taper} lstm")
         bf16_check(to_bf16(wl.make_generic(T, 1, 72, seed=34, device=DEV)), f"taper {taper} bf16")
+
+
+def test_rows_too_long_for_32_bit_tile_offsets_fall_back_to_the_serial_kernel():
+    """A tile addresses its rows with 32-bit byte offsets; when rows*C*4 does not fit, every entry point
+    must take the serial kernel by itself (and still be right)."""
+    from parity import fwd_bwd_check
+    from test_bf16_parity_gpu import bf16_check, to_bf16
+    from test_gilr_parity_gpu import gated_check
+    from test_lstm_parity_gpu import cell_check
+
+    big = 1 << 25                           # 128 MiB rows: no tile shape can address even 32 of them
+    assert lr.linrec_plan(4, 1, big)[0] == lr.VARIANT_SERIAL
+    fwd_bwd_check(wl.make_generic(4, 1, big, seed=41, device=DEV), "long rows plain")
+    gated_check(wl.make_gated(4, 1, big, seed=42, device=DEV), lr.TAU_TANH, "long rows gated",
+                cols=list(range(0, big, big // 64)))
+    cell_check(wl.make_lstm(4, 1, big, seed=43, device=DEV), "long rows lstm", cols=list(range(0, big, big // 64)))
+    bf16_check(to_bf16(wl.make_generic(4, 1, big, seed=44, device=DEV)), "long rows bf16",
+               cols=list(range(0, big, big // 64)))
