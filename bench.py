@@ -465,6 +465,11 @@ def main():
             "frac_of_peak": bwd_gbs / HBM_PEAK_GBS, "elements/s": E / (bwd_avg * 1e-3)},
         "combined_GB/s": (fwd_bpe + (bwd_bpe if do_bwd else 0)) * E / (ms_per_step * 1e-3) / 1e9,
         "roofline": roof,
+        # context only (another machine, a ratio not a rate): the paper's Table 1, parallel kernel over serial kernel
+        "paper_context": {"source": "arXiv 1709.04057, Table 1 (Section 4.1.1): parallel / serial kernel throughput, minibatch 1, "
+                                    "NVIDIA GPU of 2017 (a K80 is named for 'all experiments' in Section 4.2)",
+                          "speedup_at_T=65536_for_m=4,32,128": [38.5, 41.8, 17.5],
+                          "ours": "bench.py --table1 measures the same grid on the MI355X (profiles/table1_parallel_vs_serial_mi355x.txt)"},
     }
     if args.probe:
         out["stream_probe"] = stream_probe(lr, torch, E, stream)
