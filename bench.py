@@ -204,7 +204,9 @@ def gated_bench(args, lr, torch, wl):
         "ms_per_step": f_avg + b_avg, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.gated}: gated forward+backward, fp32, time-major [T={T}, B={B}, n={n}], tau=tanh; "
-                               + spec["note"]},
+                               + spec["note"],
+                   "tile_fwd": lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n, backward=False)[1],
+                   "tile_bwd": lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n, backward=True)[1]},
         "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(12.0, f_avg), "frac_of_peak": gbs(12.0, f_avg) / HBM_PEAK_GBS},
         "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(24.0, b_avg), "frac_of_peak": gbs(24.0, b_avg) / HBM_PEAK_GBS},
         "unfused_forward": {"avg_ms": u_avg, "min_ms": u_min, "speedup_of_fused": u_avg / f_avg,
@@ -291,7 +293,9 @@ def lstm_bench(args, lr, torch, wl):
         "ms_per_step": f_avg + b_avg, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": f"{args.lstm}: LSTM cell forward+backward, fp32, time-major [T={T}, B={B}, n={n}]; "
-                               + spec["note"]},
+                               + spec["note"],
+                   "tile_fwd": lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=False)[1],
+                   "tile_bwd": lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=True)[1]},
         "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(24.0, f_avg), "frac_of_peak": gbs(24.0, f_avg) / HBM_PEAK_GBS},
         "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(40.0, b_avg), "frac_of_peak": gbs(40.0, b_avg) / HBM_PEAK_GBS},
         "unfused_forward": {"avg_ms": u_avg, "min_ms": u_min, "speedup_of_fused": u_avg / f_avg,
@@ -436,8 +440,8 @@ def main():
     vf, tf = lr.linrec_plan(T, B, n, backward=False) if not args.tile_fwd else (variant, args.tile_fwd)
     vb, tb = lr.linrec_plan(T, B, n, backward=True) if not args.tile_bwd else (variant, args.tile_bwd)
     if bf16 and not args.tile_fwd:
-        tf = tb = None      # (linrec_plan reports the fp32 plan; the bf16 entry points pick their own shapes)
-        vb = lr.VARIANT_LOOKBACK
+        vf, tf = lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, backward=False)
+        vb, tb = lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, backward=True)
     traffic = None if bf16 else measured_traffic(args.config, "backward" if do_bwd else "forward")
     if do_bwd:
         roof = {"bound": "hbm", "kernel": "backward pass (look-back kernel)" if vb == lr.VARIANT_LOOKBACK else "backward pass",

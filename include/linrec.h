@@ -216,6 +216,16 @@ int linrec_tile_info(int tile_id, int *threads_cols, int *threads_time, int *row
 int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int alignment_bytes,
                 int *variant, int *tile_id);
 
+/* The same for the other entry-point families (whose kernels exist for fewer tile shapes). */
+enum {
+    LINREC_ENTRY_PLAIN = 0,     /* linrec_forward / linrec_backward (what linrec_plan reports) */
+    LINREC_ENTRY_GILR = 1,      /* linrec_gilr_forward / linrec_gilr_backward                  */
+    LINREC_ENTRY_LSTM_CELL = 2, /* linrec_lstm_cell_forward / linrec_lstm_cell_backward        */
+    LINREC_ENTRY_BF16 = 3       /* linrec_forward_bf16 / linrec_backward_bf16                  */
+};
+int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward,
+                    int alignment_bytes, int *variant, int *tile_id);
+
 /*
  * Optional: finds the fastest plan (tile shape, persistent workgroups or not) of the single-pass
  * kernel for a [T, B, n] forward (backward = 0) or backward (1) pass by timing the candidates on

@@ -7,6 +7,10 @@ PyTorch is used for device memory and streams only.
 """
 from .autograd import gilr, linear_recurrence, lstm_cell  # noqa: F401
 from .binding import (  # noqa: F401
+    ENTRY_BF16,
+    ENTRY_GILR,
+    ENTRY_LSTM_CELL,
+    ENTRY_PLAIN,
     LinrecError,
     OPT_CHUNK_TILES,
     OPT_GRID_CAP,
@@ -34,6 +38,7 @@ from .binding import (  # noqa: F401
     linrec_lstm_cell_backward,
     linrec_lstm_cell_forward,
     linrec_plan,
+    linrec_plan_for,
     linrec_release_workspace,
     linrec_set_option,
     linrec_status_string,

@@ -80,6 +80,8 @@ def lib():
         L.linrec_tile_info.restype = ci
         L.linrec_plan.argtypes = [i64, i64, i64, ci, ci, pi, pi]
         L.linrec_plan.restype = ci
+        L.linrec_plan_for.argtypes = [ci, i64, i64, i64, ci, ci, pi, pi]
+        L.linrec_plan_for.restype = ci
         L.linrec_stream_probe.argtypes = [p, p, p, p, p, i64, p]
         L.linrec_stream_probe.restype = ci
         L.linrec_tune.argtypes = [i64, i64, i64, ci, p]
@@ -308,6 +310,17 @@ def linrec_plan(T, B, n, backward=False, alignment=16):
     """(variant, tile id) the library would pick for tensors aligned to ``alignment`` bytes."""
     v, t = ctypes.c_int(), ctypes.c_int()
     _check(lib().linrec_plan(int(T), int(B), int(n), int(bool(backward)), int(alignment), ctypes.byref(v), ctypes.byref(t)))
+    return v.value, t.value
+
+
+ENTRY_PLAIN, ENTRY_GILR, ENTRY_LSTM_CELL, ENTRY_BF16 = 0, 1, 2, 3
+
+
+def linrec_plan_for(entry_point, T, B, n, backward=False, alignment=16):
+    """(variant, tile id) for one of the entry-point families ENTRY_*."""
+    v, t = ctypes.c_int(), ctypes.c_int()
+    _check(lib().linrec_plan_for(int(entry_point), int(T), int(B), int(n), int(bool(backward)), int(alignment),
+                                 ctypes.byref(v), ctypes.byref(t)))
     return v.value, t.value
 
 

@@ -623,6 +623,23 @@ extern "C" int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int al
     return LINREC_OK;
 }
 
+extern "C" int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward, int alignment_bytes,
+                               int *variant, int *tile_id)
+{
+    int64_t C = B * n;
+    if (T <= 0 || B <= 0 || n <= 0) return LINREC_ERR_SHAPE;
+    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_BF16) return LINREC_ERR_OPTION;
+    const void *al = (const void *)(uintptr_t)(alignment_bytes > 0 ? alignment_bytes : 2);
+    const bool bf16 = entry_point == LINREC_ENTRY_BF16;
+    const int form = entry_point == LINREC_ENTRY_GILR ? FORM_GATED : entry_point == LINREC_ENTRY_LSTM_CELL ? FORM_LSTM : FORM_PLAIN;
+    const int vec = bf16 ? max_vec_bf16(C, {al}) : form != FORM_PLAIN ? 1 : max_vec(C, {al});
+    Plan p = make_plan(T, C, vec, backward != 0, form, bf16);
+    if ((form != FORM_PLAIN || bf16) && p.variant == LINREC_VARIANT_THREEPHASE) p.variant = LINREC_VARIANT_LOOKBACK;
+    if (variant) *variant = p.variant;
+    if (tile_id) *tile_id = p.tile;
+    return LINREC_OK;
+}
+
 extern "C" int linrec_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
                                    int64_t n, void *stream)
 {

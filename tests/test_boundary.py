@@ -177,6 +177,22 @@ def test_plan_is_host_only_and_consistent(L):
                 assert info is not None
                 assert (B * n) % info["cols_per_thread"] == 0
                 assert info["cols_per_thread"] * 4 <= align
+    # the other entry-point families report shapes their kernels exist for
+    for (T, B, n) in [(65536, 4, 256), (4096, 16, 1024), (300, 1, 7), (5000, 2, 33)]:
+        for bwd in (False, True):
+            v, t = lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n, backward=bwd)
+            assert v in (lr.VARIANT_LOOKBACK, lr.VARIANT_SERIAL) and lr.linrec_tile_info(t)["cols_per_thread"] == 1
+            v, t = lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=bwd)
+            info = lr.linrec_tile_info(t)
+            assert info["cols_per_thread"] == 1 and info["rows_per_thread"] <= 32
+            v, t = lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, backward=bwd, alignment=4)
+            if (B * n) % 2:
+                assert v == lr.VARIANT_SERIAL            # odd number of columns: no 4-byte rows
+            else:
+                assert v == lr.VARIANT_LOOKBACK and lr.linrec_tile_info(t)["cols_per_thread"] in (2, 4)
+            assert lr.linrec_plan_for(lr.ENTRY_PLAIN, T, B, n, backward=bwd) == lr.linrec_plan(T, B, n, backward=bwd)
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_plan_for(9, 10, 1, 1)
     # a tile whose rows would not fit 32-bit offsets falls back to the serial kernel
     variant, _ = lr.linrec_plan(64, 1, 1 << 26, alignment=16)
     assert variant == lr.VARIANT_SERIAL
