@@ -141,57 +141,47 @@ __device__ __forceinline__ dvec<N> factor(vec<N> a)
     if constexpr (FORM == FORM_PLAIN) return widen<N>(a);
     else return dsplat<N>(1.0) - widen<N>(a);
 }
-// sigmoid(-z) and sigmoid(z) from one exponential of -|z|: both keep their relative accuracy in
-// either tail.  v_exp_f32 / v_rcp_f32 are good to about one ulp.
-__device__ __forceinline__ void gate_pair(float z, float &g, float &c)
+// sigmoid(z) = 1 / (1 + exp(-z)) from one v_exp_f32 and one v_rcp_f32 (each good to about one ulp).
+// The relative accuracy holds in BOTH tails: for z -> -inf the result is 1/exp(-z) with nothing added
+// that matters, for z -> +inf it is 1/(1 + tiny); exp overflowing to +inf gives exactly 0.  So the
+// gate's complement is sigmoid(-g_pre), not 1 - sigmoid(g_pre).  A NaN pre-activation gives NaN.
+__device__ __forceinline__ float sigmoid_f32(float z)
 {
-    const float e = __builtin_amdgcn_exp2f(-fabsf(z) * 1.44269504088896340736f);
-    const float big = __builtin_amdgcn_rcpf(1.0f + e), small = e * big;
-    const bool pos = z >= 0.0f;
-    g = pos ? big : small;
-    c = pos ? small : big;  // (a NaN pre-activation gives NaN in both)
-}
-// sigmoid(z) and its complement, elementwise
-template <int N>
-__device__ __forceinline__ void gate_both(vec<N> z, vec<N> &g, vec<N> &c)
-{
-#pragma unroll
-    for (int i = 0; i < N; ++i) {
-        float gg, cc;
-        gate_pair(z[i], gg, cc);
-        g[i] = gg;
-        c[i] = cc;
-    }
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(z * -1.44269504088896340736f));
 }
 template <int N>
 __device__ __forceinline__ vec<N> gate_value(vec<N> z)
 {
-    vec<N> g, c;
-    gate_both<N>(z, g, c);
-    return g;
+    vec<N> r;
+#pragma unroll
+    for (int i = 0; i < N; ++i) r[i] = sigmoid_f32(z[i]);
+    return r;
 }
 template <int N>
 __device__ __forceinline__ vec<N> gate_complement(vec<N> z)
 {
     vec<N> r;
 #pragma unroll
-    for (int i = 0; i < N; ++i) {
-        float g, c;
-        gate_pair(z[i], g, c);
-        r[i] = c;
-    }
+    for (int i = 0; i < N; ++i) r[i] = sigmoid_f32(-z[i]);
     return r;
 }
-// tanh: (1-t)/(1+t) with t = exp(-2|y|); below 1/8 the subtraction would cancel, a short odd
-// series takes over there (its next term is below 2e-9 relative).
+// sigmoid(z) and 1 - sigmoid(z) for the derivative g*(1-g), where the complement only needs its
+// absolute accuracy
+template <int N>
+__device__ __forceinline__ void gate_both(vec<N> z, vec<N> &g, vec<N> &c)
+{
+    g = gate_value<N>(z);
+    c = splat<N>(1.0f) - g;
+}
+// tanh(y) = 1 - 2 / (1 + exp(2y)) (any sign; saturates to +-1 without overflow trouble).  Below
+// |y| < 1/8 the subtraction would cancel and a short odd series takes over (its next term is below
+// 2e-9 relative).
 __device__ __forceinline__ float tanh_f32(float y)
 {
-    const float ay = fabsf(y);
-    const float t = __builtin_amdgcn_exp2f(ay * -2.88539008177792681472f);
-    const float big = (1.0f - t) * __builtin_amdgcn_rcpf(1.0f + t);
-    const float y2 = ay * ay;
-    const float small = ay * fmaf(y2, fmaf(y2, fmaf(y2, -17.0f / 315.0f, 2.0f / 15.0f), -1.0f / 3.0f), 1.0f);
-    return copysignf(ay < 0.125f ? small : big, y);
+    const float big = fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(y * 2.88539008177792681472f)), 1.0f);
+    const float y2 = y * y;
+    const float small = y * fmaf(y2, fmaf(y2, fmaf(y2, -17.0f / 315.0f, 2.0f / 15.0f), -1.0f / 3.0f), 1.0f);
+    return fabsf(y) < 0.125f ? small : big;
 }
 // the impulse activation tau of Section 3.1: tanh, or the identity
 template <int N>
