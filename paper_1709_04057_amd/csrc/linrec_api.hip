@@ -217,7 +217,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
         // The gated form computes a sigmoid and a tanh per element before it can publish a summary:
         // 32-row threads (twice the resident workgroups of the 64-row shapes) hide that better.
-        if (gated && T >= 2048 && C > 16) p.tile = (C >= 2048 || (form == FORM_LSTM && C >= 128)) ? 21 : 18;
+        if (gated && T >= 2048 && C > 16) p.tile = C >= 2048 ? 21 : (form == FORM_GATED && !bwd) ? 19 : 18;
         if (form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 18;  // (the cell has no 48- or 64-row kernels)
         // bf16 storage: the shapes with two columns (4 bytes) per thread mirror the fp32 choice
         if (bf16) p.tile = T >= 4096 ? (bwd ? 29 : (C >= 2048 ? 28 : 24)) : T >= 1024 ? 16 : 15;
