@@ -580,21 +580,30 @@ __device__ __forceinline__ void tile_load(const Args &A, const TileAddr<G, BWD> 
     tile_load<G, BWD, FORM, 1>(A, ad, mk, interior, r, none);
 }
 
-// Backward only: h one row behind each step (h[-1] = h0, zero when h0 is null).
-template <class G>
-__device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G, true> &ad,
-                                                const RowMask<G, true> &mk, int64_t col, bool interior,
-                                                row_t<G> (&hp)[G::R])
+// Backward only: h one row behind each step (h[-1] = h0, zero when h0 is null).  Two instances like
+// tile_load: with unconditional loads here the reduce phase waits for lambda and grad_h only, not
+// for these loads that were issued after them.
+template <class G, bool INTERIOR>
+__device__ __forceinline__ void tile_load_hprev_impl(const Args &A, const TileAddr<G, true> &ad,
+                                                     const RowMask<G, true> &mk, int64_t col, row_t<G> (&hp)[G::R])
 {
     constexpr int R = G::R;
     const rsrc_t rh = ad.rsrc(A.hprev, -1);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         row_t<G> v = row_const<G>(0.0f);
-        if (interior || j < mk.nh) v = rld<G>(rh, ad.toff, ad.soff(j));
+        if (INTERIOR || j < mk.nh) v = rld<G>(rh, ad.toff, ad.soff(j));
         else if (j == mk.nh && j < mk.n && A.h0) v = pack<G>(pld<G>(A.h0, col));
         hp[j] = v;
     }
+}
+template <class G>
+__device__ __forceinline__ void tile_load_hprev(const Args &A, const TileAddr<G, true> &ad,
+                                                const RowMask<G, true> &mk, int64_t col, bool interior,
+                                                row_t<G> (&hp)[G::R])
+{
+    if (interior) tile_load_hprev_impl<G, true>(A, ad, mk, col, hp);
+    else tile_load_hprev_impl<G, false>(A, ad, mk, col, hp);
 }
 
 // Phase 1 of Algorithm 1 for one thread: P = prod of the multipliers (fp64),  S = recurrence over
