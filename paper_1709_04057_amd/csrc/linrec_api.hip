@@ -153,10 +153,11 @@ int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // are long.
 int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
 {
-    (void)vec;
     (void)bwd;
     (void)variant;
     if (C <= 16) return T >= 4096 ? 23 : 2;
+    // many columns, few tiles per column: the shapes with 16-byte (8-byte) accesses measure best
+    if (C >= 8192 && T >= 1536 && T < 8192) return vec >= 4 ? 11 : vec >= 2 ? 14 : 20;
     if (T >= 32768) return C >= 2048 ? 20 : 22;
     if (T >= 8192) return 17;
     if (T >= 1536) return 19;
