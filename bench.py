@@ -168,6 +168,10 @@ def gated_bench(args, lr, torch, wl):
     stream = torch.cuda.current_stream()
     K = args.steps
 
+    if not args.no_tune:
+        lr.linrec_tune_for(lr.ENTRY_GILR, T, B, n, backward=False, stream=stream)
+        lr.linrec_tune_for(lr.ENTRY_GILR, T, B, n, backward=True, stream=stream)
+
     def fused_fwd():
         lr.linrec_gilr_forward(g_pre, i_pre, h0, h_out=h, stream=stream)
 
@@ -253,6 +257,10 @@ def lstm_bench(args, lr, torch, wl):
     lam, x, og = torch.empty_like(e), torch.empty_like(e), torch.empty_like(e)
     stream = torch.cuda.current_stream()
     K = args.steps
+
+    if not args.no_tune:
+        lr.linrec_tune_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=False, stream=stream)
+        lr.linrec_tune_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=True, stream=stream)
 
     def fused_fwd():
         lr.linrec_lstm_cell_forward(*pre, c0, c_out=c, h_out=h, stream=stream)
@@ -392,11 +400,12 @@ def main():
         lr.linrec_set_option(lr.OPT_TILE, args.tile_bwd)
         lr.linrec_backward(lam, h, h0, e, grad_x=gx, grad_lambda=gl, grad_h0=gh0, stream=stream)
 
-    if not args.no_tune and args.variant in ("auto", "lookback") and not bf16:
+    if not args.no_tune and args.variant in ("auto", "lookback"):
+        family = lr.ENTRY_BF16 if bf16 else lr.ENTRY_PLAIN
         if not args.tile_fwd:
-            lr.linrec_tune(T, B, n, backward=False, stream=stream)
+            lr.linrec_tune_for(family, T, B, n, backward=False, stream=stream)
         if do_bwd and not args.tile_bwd:
-            lr.linrec_tune(T, B, n, backward=True, stream=stream)
+            lr.linrec_tune_for(family, T, B, n, backward=True, stream=stream)
     for _ in range(args.warmup):
         fwd()
         if do_bwd:

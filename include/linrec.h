@@ -235,6 +235,9 @@ int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backwa
  * LINREC_ERR_SHAPE or LINREC_ERR_HIP.  Must not run concurrently with other liblinrec calls.
  */
 int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *stream);
+/* The same for one of the entry-point families LINREC_ENTRY_* (linrec_tune is LINREC_ENTRY_PLAIN);
+ * allocates as many scratch tensors as the entry point has [T, B, n] arguments. */
+int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward, void *stream);
 
 /* Host-side argument checks only (exactly the checks linrec_forward / linrec_backward run
  * before touching the GPU); no HIP call is made, so these work on a machine without a GPU. */

@@ -45,5 +45,6 @@ from .binding import (  # noqa: F401
     linrec_stream_probe,
     linrec_tile_info,
     linrec_tune,
+    linrec_tune_for,
     linrec_version,
 )

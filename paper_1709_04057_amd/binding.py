@@ -86,6 +86,8 @@ def lib():
         L.linrec_stream_probe.restype = ci
         L.linrec_tune.argtypes = [i64, i64, i64, ci, p]
         L.linrec_tune.restype = ci
+        L.linrec_tune_for.argtypes = [ci, i64, i64, i64, ci, p]
+        L.linrec_tune_for.restype = ci
         L.linrec_check.argtypes = [p]
         L.linrec_check.restype = ci
         L.linrec_release_workspace.argtypes = []
@@ -328,6 +330,11 @@ def linrec_stream_probe(in0, in1, in2, out0, out1, stream=None) -> None:
     """Pure streaming kernel over flat float32 CUDA tensors (None = absent); see include/linrec.h."""
     n = (out0 if out0 is not None else out1).numel()
     _check(lib().linrec_stream_probe(_ptr(in0), _ptr(in1), _ptr(in2), _ptr(out0), _ptr(out1), n, _stream_ptr(stream)))
+
+
+def linrec_tune_for(entry_point, T, B, n, backward=False, stream=None) -> None:
+    """linrec_tune for one of the entry-point families ENTRY_*."""
+    _check(lib().linrec_tune_for(int(entry_point), int(T), int(B), int(n), int(bool(backward)), _stream_ptr(stream)))
 
 
 def linrec_tune(T, B, n, backward=False, stream=None) -> None:

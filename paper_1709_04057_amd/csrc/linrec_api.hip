@@ -176,12 +176,14 @@ struct TunedKey {
     int dev;
     int64_t T, C;
     bool bwd;
+    int family;  // LINREC_ENTRY_*
     bool operator<(const TunedKey &o) const
     {
         if (dev != o.dev) return dev < o.dev;
         if (T != o.T) return T < o.T;
         if (C != o.C) return C < o.C;
-        return bwd < o.bwd;
+        if (bwd != o.bwd) return bwd < o.bwd;
+        return family < o.family;
     }
 };
 struct TunedPlan {
@@ -199,11 +201,13 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
     p.tile = (int)opts().tile;
     p.persistent = (int)opts().persistent;
-    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK && !gated && !bf16) {  // a tuned plan, if there is one for this shape
+    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK) {  // a tuned plan, if there is one for this shape
+        const int family = bf16 ? LINREC_ENTRY_BF16 : form == FORM_GATED ? LINREC_ENTRY_GILR
+                                                    : form == FORM_LSTM ? LINREC_ENTRY_LSTM_CELL : LINREC_ENTRY_PLAIN;
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess) {
             std::lock_guard<std::mutex> lock(g_tuned_mu);
-            auto it = g_tuned.find(TunedKey{dev, T, C, bwd});
+            auto it = g_tuned.find(TunedKey{dev, T, C, bwd, family});
             if (it != g_tuned.end()) {
                 p.tile = it->second.tile;
                 if (p.persistent < 0) p.persistent = it->second.persistent;
@@ -656,10 +660,11 @@ extern "C" int linrec_stream_probe(const float *in0, const float *in1, const flo
 
 // Times the look-back kernel under every candidate plan on scratch tensors of the given shape and
 // remembers the fastest for later calls with that shape on this device.
-extern "C" int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *stream)
+extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward, void *stream)
 {
     if (T <= 0 || B <= 0 || n <= 0 || B > ((int64_t)1 << 40) / n || T > ((int64_t)1 << 40) / (B * n))
         return LINREC_ERR_SHAPE;
+    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_BF16) return LINREC_ERR_OPTION;
     const int64_t C = B * n, E = T * C;
     hipStream_t s = (hipStream_t)stream;
     const bool bwd = backward != 0;
@@ -667,11 +672,18 @@ extern "C" int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *
     hipError_t e;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e, "hipGetDevice");
 
-    // scratch: lambda = 0.96875 (products neither overflow nor vanish within a tile), the rest 1 / 0
-    float *big[5] = {nullptr, nullptr, nullptr, nullptr, nullptr}, *small_[2] = {nullptr, nullptr};
+    // Scratch tensors.  Tensor 0 is the multiplier (lambda, or the forget / gate pre-activation): 0.96875
+    // as lambda, 3.4 as a pre-activation (sigmoid = 0.968), so that products neither overflow nor vanish
+    // within a tile; the other inputs are 1, the state vectors 0.  With bf16 storage the same fills are
+    // written as 16-bit patterns (both constants are exact in bf16).
+    const bool bf16 = entry_point == LINREC_ENTRY_BF16;
+    const int n_in = entry_point == LINREC_ENTRY_LSTM_CELL ? (bwd ? 6 : 4) : entry_point == LINREC_ENTRY_GILR ? (bwd ? 4 : 2)
+                                                                                                              : (bwd ? 3 : 2);
+    const int n_out = entry_point == LINREC_ENTRY_LSTM_CELL ? (bwd ? 4 : 2) : (bwd ? 2 : 1);
+    const int n_big = n_in + n_out;
+    float *big[10] = {}, *small_[2] = {nullptr, nullptr};
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
     int rc = LINREC_OK;
-    const int n_big = bwd ? 5 : 3;
     for (int i = 0; i < n_big && rc == LINREC_OK; ++i)
         if ((e = hipMalloc((void **)&big[i], (size_t)E * sizeof(float))) != hipSuccess) rc = hip_fail(e, "hipMalloc(tune)");
     for (int i = 0; i < 2 && rc == LINREC_OK; ++i)
@@ -679,20 +691,55 @@ extern "C" int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *
     if (rc == LINREC_OK && ((e = hipEventCreate(&ev0)) != hipSuccess || (e = hipEventCreate(&ev1)) != hipSuccess))
         rc = hip_fail(e, "hipEventCreate");
     if (rc == LINREC_OK) {
-        e = launch_fill(big[0], 0.96875f, E, s);
-        for (int i = 1; i < n_big && e == hipSuccess; ++i) e = launch_fill(big[i], 1.0f, E, s);
+        const float first = (entry_point == LINREC_ENTRY_GILR || entry_point == LINREC_ENTRY_LSTM_CELL) ? 3.40625f : 0.96875f;
+        // a float whose two halves are the same bf16 pattern fills a bf16 tensor with that value
+        auto both_halves = [](float v) {
+            uint32_t b;
+            memcpy(&b, &v, 4);
+            b = (b & 0xffff0000u) | (b >> 16);
+            float r;
+            memcpy(&r, &b, 4);
+            return r;
+        };
+        e = launch_fill(big[0], bf16 ? both_halves(first) : first, E, s);
+        for (int i = 1; i < n_big && e == hipSuccess; ++i) e = launch_fill(big[i], bf16 ? both_halves(1.0f) : 1.0f, E, s);
         for (int i = 0; i < 2 && e == hipSuccess; ++i) e = launch_fill(small_[i], 0.0f, C, s);
         if (e != hipSuccess) rc = hip_fail(e, "launch(fill)");
     }
+    auto call = [&]() -> int {
+        typedef const uint16_t *cb;
+        typedef uint16_t *mb;
+        switch (entry_point) {
+        case LINREC_ENTRY_GILR:
+            return bwd ? linrec_gilr_backward(big[0], big[1], big[2], small_[0], big[3], big[4], big[5], small_[1],
+                                              LINREC_TAU_TANH, T, B, n, s)
+                       : linrec_gilr_forward(big[0], big[1], small_[0], big[2], LINREC_TAU_TANH, T, B, n, s);
+        case LINREC_ENTRY_LSTM_CELL:
+            return bwd ? linrec_lstm_cell_backward(big[0], big[1], big[2], big[3], big[4], small_[0], big[5], big[6], big[7],
+                                                   big[8], big[9], small_[1], T, B, n, s)
+                       : linrec_lstm_cell_forward(big[0], big[1], big[2], big[3], small_[0], big[4], big[5], T, B, n, s);
+        case LINREC_ENTRY_BF16:
+            return bwd ? linrec_backward_bf16((cb)big[0], (cb)big[1], (cb)small_[0], (cb)big[2], (mb)big[3], (mb)big[4],
+                                              (mb)small_[1], T, B, n, s)
+                       : linrec_forward_bf16((cb)big[0], (cb)big[1], (cb)small_[0], (mb)big[2], T, B, n, s);
+        default:
+            return bwd ? linrec_backward(big[0], big[1], small_[0], big[2], big[3], big[4], small_[1], T, B, n, s)
+                       : linrec_forward(big[0], big[1], small_[0], big[2], T, B, n, s);
+        }
+    };
 
     TunedPlan best{0, -1};
     float best_ms = 0.f;
     if (rc == LINREC_OK) {
-        const int vec = max_vec(C, {});
+        const int vec = bf16 ? max_vec_bf16(C, {}) : entry_point == LINREC_ENTRY_PLAIN ? max_vec(C, {}) : 1;
         const Options saved = opts();
         opts().variant = LINREC_VARIANT_LOOKBACK;
-        static const int candidates[] = {17, 18, 19, 20, 21, 22, 11, 12, 14};
-        for (int tile : candidates) {
+        static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0}, gated_c[] = {18, 19, 21, 17, 20, 22, 0},
+                         lstm_c[] = {18, 21, 0}, bf16_c[] = {24, 28, 29, 16, 26, 27, 0};
+        const int *candidates = entry_point == LINREC_ENTRY_GILR ? gated_c : entry_point == LINREC_ENTRY_LSTM_CELL ? lstm_c
+                                                                 : bf16 ? bf16_c : plain_c;
+        for (; *candidates; ++candidates) {
+            const int tile = *candidates;
             const TileDesc &d = kTiles[tile - 1];
             if (d.vec > vec) continue;
             if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
@@ -703,8 +750,7 @@ extern "C" int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *
                 float times[5];
                 for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {  // two warm-up launches, five timed
                     if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
-                    rc = bwd ? linrec_backward(big[0], big[1], small_[0], big[2], big[3], big[4], small_[1], T, B, n, s)
-                             : linrec_forward(big[0], big[1], small_[0], big[2], T, B, n, s);
+                    rc = call();
                     if (rc != LINREC_OK) break;
                     float ms = 0.f;
                     if ((e = hipEventRecord(ev1, s)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
@@ -733,9 +779,14 @@ extern "C" int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *
         if (p) (void)hipFree(p);
     if (rc == LINREC_OK && best.tile != 0) {
         std::lock_guard<std::mutex> lock(g_tuned_mu);
-        g_tuned[TunedKey{dev, T, C, bwd}] = best;
+        g_tuned[TunedKey{dev, T, C, bwd, entry_point}] = best;
     }
     return rc;
+}
+
+extern "C" int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *stream)
+{
+    return linrec_tune_for(LINREC_ENTRY_PLAIN, T, B, n, backward, stream);
 }
 
 #ifdef LINREC_TRACE

@@ -141,3 +141,26 @@ def test_rows_too_long_for_32_bit_tile_offsets_fall_back_to_the_serial_kernel():
     cell_check(wl.make_lstm(4, 1, big, seed=43, device=DEV), "long rows lstm", cols=list(range(0, big, big // 64)))
     bf16_check(to_bf16(wl.make_generic(4, 1, big, seed=44, device=DEV)), "long rows bf16",
                cols=list(range(0, big, big // 64)))
+
+
+def test_tuned_plans_of_every_family_are_used_and_correct():
+    """linrec_tune_for() times the candidate shapes of a family on scratch tensors; later calls with that
+    shape use the winner (linrec_plan_for reports it) and stay correct whatever it picked."""
+    from parity import fwd_bwd_check
+    from test_bf16_parity_gpu import bf16_check, to_bf16
+    from test_gilr_parity_gpu import gated_check
+    from test_lstm_parity_gpu import cell_check
+
+    T, B, n = 20000, 2, 96
+    for family in (lr.ENTRY_PLAIN, lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16):
+        for bwd in (False, True):
+            lr.linrec_tune_for(family, T, B, n, backward=bwd)
+            v, t = lr.linrec_plan_for(family, T, B, n, backward=bwd, alignment=16)
+            say(f"family {family} backward={bwd}: tuned tile {t}")
+            assert v == lr.VARIANT_LOOKBACK and lr.linrec_tile_info(t) is not None
+    fwd_bwd_check(wl.make_inputs(2, T=T, B=B, n=n, device=DEV), "tuned plain")
+    gated_check(wl.make_gated(T, B, n, seed=51, device=DEV, gate_mean=1.0), lr.TAU_TANH, "tuned gated")
+    cell_check(wl.make_lstm(T, B, n, seed=52, device=DEV), "tuned lstm")
+    bf16_check(to_bf16(wl.make_inputs(2, T=T, B=B, n=n, device=DEV)), "tuned bf16")
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_tune_for(7, T, B, n)
