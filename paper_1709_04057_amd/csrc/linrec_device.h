@@ -651,11 +651,14 @@ __device__ __forceinline__ void rescan_bwd_packed(const Args &A, const RowMask<G
     }
 }
 
-template <class G, bool BWD>
-__device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
-                                           int64_t col, bool interior, const Rows<G> &r, const row_t<G> *hp)
+// (Two instances, as for tile_load: in the interior one the stores are straight-line code instead of
+// one exec-mask branch per row.)
+template <class G, bool BWD, bool INTERIOR>
+__device__ __forceinline__ void tile_store_impl(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
+                                                int64_t col, const Rows<G> &r, const row_t<G> *hp)
 {
     constexpr int R = G::R;
+    constexpr bool interior = INTERIOR;
     const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(BWD ? A.out1 : A.out0);
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -673,6 +676,13 @@ __device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD>
             }
         }
     }
+}
+template <class G, bool BWD>
+__device__ __forceinline__ void tile_store(const Args &A, const TileAddr<G, BWD> &ad, const RowMask<G, BWD> &mk,
+                                           int64_t col, bool interior, const Rows<G> &r, const row_t<G> *hp)
+{
+    if (interior) tile_store_impl<G, BWD, true>(A, ad, mk, col, r, hp);
+    else tile_store_impl<G, BWD, false>(A, ad, mk, col, r, hp);
 }
 
 // Backward epilogue of the gated form.  After the rescan r.b[j] = d_t, the accumulated gradient of
