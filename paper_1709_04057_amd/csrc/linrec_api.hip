@@ -147,10 +147,9 @@ int max_vec_bf16(int64_t C, std::initializer_list<const void *> ptrs)
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // Tile shape for a [T, C] problem when the caller did not fix one.  Measured on MI355X: one column
-// per thread with many rows per thread (few registers beyond the rows themselves, so three
-// workgroups fit a compute unit), 128-byte row segments, and tiles as tall as T allows (the taller
-// the tile, the fewer summaries the look-back moves per element); 256-byte segments once the rows
-// are long.
+// per thread with many rows per thread (few registers beyond the rows themselves), 128-byte row
+// segments, and tiles as tall as T allows (the taller the tile, the fewer summaries the look-back
+// moves per element).
 int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
 {
     (void)bwd;
@@ -158,7 +157,7 @@ int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
     if (C <= 16) return T >= 4096 ? 23 : 2;
     // many columns, few tiles per column: the shapes with 16-byte (8-byte) accesses measure best
     if (C >= 8192 && T >= 1536 && T < 8192) return vec >= 4 ? 11 : vec >= 2 ? 14 : 20;
-    if (T >= 32768) return C >= 2048 ? 20 : 22;
+    if (T >= 32768) return 22;
     if (T >= 8192) return 17;
     if (T >= 1536) return 19;
     if (T >= 512) return 18;
