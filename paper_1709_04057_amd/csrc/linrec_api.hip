@@ -224,7 +224,14 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
         if (gated && T >= 2048 && C > 16) p.tile = C >= 2048 ? 21 : (form == FORM_GATED && !bwd) ? 19 : 18;
         if (form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 18;  // (the cell has no 48- or 64-row kernels)
         // bf16 storage: the shapes with two columns (4 bytes) per thread mirror the fp32 choice
-        if (bf16) p.tile = T >= 4096 ? (bwd ? 29 : (C >= 2048 ? 28 : 24)) : T >= 1024 ? 16 : 15;
+        // (forward: the 16-wavefront shape when few column groups make the chains of tiles long, the
+        // 256-byte-segment shape for wide, short problems)
+        if (bf16) {
+            if (T < 4096) p.tile = T >= 1024 ? 16 : 15;
+            else if (bwd) p.tile = 29;
+            else if (T >= 32768) p.tile = C <= 512 ? 30 : 24;
+            else p.tile = C >= 2048 ? 28 : 24;
+        }
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
     if (bf16 && vec < 2) p.variant = LINREC_VARIANT_SERIAL;
@@ -734,7 +741,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         const Options saved = opts();
         opts().variant = LINREC_VARIANT_LOOKBACK;
         static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0}, gated_c[] = {18, 19, 21, 17, 20, 22, 0},
-                         lstm_c[] = {18, 21, 0}, bf16_c[] = {24, 28, 29, 16, 26, 27, 0};
+                         lstm_c[] = {18, 21, 0}, bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 0};
         const int *candidates = entry_point == LINREC_ENTRY_GILR ? gated_c : entry_point == LINREC_ENTRY_LSTM_CELL ? lstm_c
                                                                  : bf16 ? bf16_c : plain_c;
         for (; *candidates; ++candidates) {

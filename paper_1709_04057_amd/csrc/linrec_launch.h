@@ -96,8 +96,9 @@ struct TileDesc {
     X(26, 4, 32, 16, 16) \
     X(27, 4, 32, 32, 8)  \
     X(28, 2, 64, 64, 4)  \
-    X(29, 2, 48, 32, 8)
-constexpr int NUM_TILES = 29;
+    X(29, 2, 48, 32, 8)  \
+    X(30, 2, 64, 32, 16)
+constexpr int NUM_TILES = 30;
 
 const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 
