@@ -104,6 +104,16 @@ def test_config5_full_size_lookback():
     fwd_bwd_check(inp, "cfg5 full auto")
 
 
+@pytest.mark.parametrize("variant", ["lookback", "threephase"])
+def test_tensors_beyond_4_gib(variant):
+    """6 GiB per tensor (workload 5's recipe, 1.5 times its length): element offsets pass 2^32 bytes, which
+    the tiles' 32-bit offsets must never see (each tile addresses from its own 64-bit origin)."""
+    inp = wl.make_inputs(5, T=393216, device=DEV)
+    assert inp["lam"].numel() * 4 > 2**32
+    with options(variant=VARIANTS[variant]):
+        fwd_bwd_check(inp, f"cfg5 x1.5 (6 GiB tensors) {variant}")
+
+
 @pytest.mark.parametrize("cfg,shape", [(3, (262144, 1, 128)), (5, (65536, 2, 128))])
 def test_per_channel_lambda_accuracy_stress(cfg, shape):
     """lambda (or its mixture class) held constant along T per column: true long memory."""
