@@ -146,19 +146,43 @@ int max_vec_bf16(int64_t C, std::initializer_list<const void *> ptrs)
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Tile shape for a [T, C] problem when the caller did not fix one.  Measured on MI355X: one column
-// per thread with many rows per thread (few registers beyond the rows themselves), 128-byte row
-// segments, and tiles as tall as T allows (the taller the tile, the fewer summaries the look-back
-// moves per element).
+// Tile shape for a [T, C] problem when the caller did not fix one.  The rules condense a sweep of
+// every shape over T = 64 .. 262144 x C = 32 .. 32768 on an MI355X (the choice is within 3 % of the
+// best shape on average, 5 % backward, and within 20-25 % at worst; linrec_tune() closes the rest
+// for a given shape and box):
+//   * one column per thread with many rows per thread, and tiles as tall as T allows (the taller the
+//     tile, the fewer summaries the look-back moves per element) once the sequence is long;
+//   * 256-byte row segments (64 threads side by side) when there are many columns;
+//   * the shapes with 16-byte (8-byte) accesses for very wide problems, where alignment allows;
+//   * the backward pass carries a third operand per row and prefers 48- or 32-row threads.
 int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
 {
-    (void)bwd;
     (void)variant;
     if (C <= 16) return T >= 4096 ? 23 : 2;
-    // many columns, few tiles per column: the shapes with 16-byte (8-byte) accesses measure best
-    if (C >= 8192 && T >= 1536 && T < 8192) return vec >= 4 ? 11 : vec >= 2 ? 14 : 20;
-    if (T >= 32768) return 22;
-    if (T >= 8192) return 17;
+    const int short_wide = vec >= 4 ? 10 : 21;  // (T < 192: a few rows per thread)
+    if (!bwd) {
+        if (C >= 8192) {
+            if (T >= 1536) return vec >= 4 ? 11 : vec >= 2 ? 14 : 20;
+            return T >= 192 ? 20 : short_wide;
+        }
+        if (T >= 65536) return 22;
+        if (T >= 32768) return C <= 128 ? 17 : 22;
+        if (C >= 1024) return T >= 192 ? 20 : 1;
+        if (T >= 16384 && C >= 512) return 22;
+        if (T >= 8192) return 17;
+    } else {
+        if (C >= 8192) {
+            if (T >= 2048) return 21;
+            return T >= 192 ? (vec >= 4 ? 8 : 20) : short_wide;
+        }
+        if (C >= 1024) {
+            if (T >= 8192) return 19;
+            if (T < 192) return 1;
+            return T * C <= ((int64_t)1 << 21) ? 21 : 20;
+        }
+        if (T >= 131072) return C <= 32 ? 22 : 19;
+        if (T >= 8192) return C >= 256 ? 20 : T >= 65536 ? 17 : 18;
+    }
     if (T >= 1536) return 19;
     if (T >= 512) return 18;
     return C >= 48 ? 1 : 2;
