@@ -188,6 +188,56 @@ int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
     return C >= 48 ? 1 : 2;
 }
 
+// The same for bf16 storage (shapes with 2 or 4 columns per thread), from the same kind of sweep:
+// 1.7 % (forward) and 5 % (backward) from the best shape on average.  Mid-sized problems run best as
+// ONE round of workgroups, one tile per compute unit, hence the rules on the number of tiles.
+int auto_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
+{
+    if (T < 192) return C >= 16384 ? (vec >= 4 ? 9 : 16) : 15;  // a few rows per thread
+    if (!bwd) {
+        const int small = T >= 1024 ? 16 : 15;
+        if (C >= 32768 || (C >= 16384 && T >= 4096)) return 28;
+        if (T >= 32768 && C <= 128 && (T < 131072 || C <= 32)) return 25;
+        if (T >= 32768 && C <= 512) return 30;
+        const int64_t n30 = ceil_div(T, 1024) * ceil_div(C, 64);  // tiles of the tallest shape
+        if (n30 > 128 && n30 <= 256) return 30;
+        if (T * C >= ((int64_t)1 << 22)) return 24;
+        return small;
+    }
+    if (C <= 128 && T >= 8192) return T <= 32768 ? 14 : 25;
+    if (T >= 4096) return (T * C >= ((int64_t)1 << 23) && T * C <= ((int64_t)1 << 24)) ? 24 : 29;
+    if (T * C >= ((int64_t)1 << 23)) return vec >= 4 ? 27 : 28;
+    return T >= 256 ? 16 : 15;
+}
+
+// The same for the gated layer and the LSTM cell, which exist for the one-column shapes 1, 2 and
+// 17 .. 23 (the cell: 1, 2, 18, 21).  They compute a sigmoid and a tanh per element before a tile can
+// publish its summary: shapes with 32 or 48 rows per thread (more resident workgroups than the 64-row
+// shapes) hide that better, and 256-byte row segments pay from fewer columns on than in the plain
+// recurrence.
+int auto_tile_form(int64_t T, int64_t C, bool bwd, int form)
+{
+    const int plain = auto_tile(T, C, 1, bwd, 0);
+    if (C <= 16) return plain;
+    const int64_t E = T * C, n22 = ceil_div(T, 1024) * ceil_div(C, 32);  // (tiles of the tallest shape)
+    const bool one_round_22 = n22 > 128 && n22 <= 256;  // one tile per compute unit
+    if (bwd && E <= ((int64_t)1 << 19)) return 2;
+    if (form == FORM_GATED) {
+        if (!bwd) {
+            if (T < 2048) return plain;
+            if (C >= 16384) return 21;
+            if (one_round_22 && T >= 32768) return 22;
+            if (E >= ((int64_t)1 << 24)) return 19;
+            return C >= 2048 ? 20 : 17;
+        }
+        if (T < 2048) return C >= 1024 ? 21 : plain;
+        if (one_round_22) return 22;
+        return C >= 2048 ? 21 : 18;
+    }
+    if (!bwd) return C >= 8192 ? 21 : T >= 256 ? 18 : plain;
+    return C >= 2048 ? 21 : T >= 256 ? 18 : plain;
+}
+
 struct Plan {
     int variant, tile;
     bool hp_late;
@@ -243,19 +293,9 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     if (p.tile >= 1 && p.tile <= NUM_TILES && !bf16 && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 64) p.tile = 0;
     if (p.tile < 1 || p.tile > NUM_TILES) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
-        // The gated form computes a sigmoid and a tanh per element before it can publish a summary:
-        // 32-row threads (twice the resident workgroups of the 64-row shapes) hide that better.
-        if (gated && T >= 2048 && C > 16) p.tile = C >= 2048 ? 21 : (form == FORM_GATED && !bwd) ? 19 : 18;
+        if (gated) p.tile = auto_tile_form(T, C, bwd, form);
         if (form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 18;  // (the cell has no 48- or 64-row kernels)
-        // bf16 storage: the shapes with two columns (4 bytes) per thread mirror the fp32 choice
-        // (forward: the 16-wavefront shape when few column groups make the chains of tiles long, the
-        // 256-byte-segment shape for wide, short problems)
-        if (bf16) {
-            if (T < 4096) p.tile = T >= 1024 ? 16 : 15;
-            else if (bwd) p.tile = 29;
-            else if (T >= 32768) p.tile = C <= 512 ? 30 : 24;
-            else p.tile = C >= 2048 ? 28 : 24;
-        }
+        if (bf16) p.tile = auto_tile_bf16(T, C, vec, bwd);
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
     if (bf16 && vec < 2) p.variant = LINREC_VARIANT_SERIAL;
