@@ -81,7 +81,11 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
     // persistent workgroups: as many as the device holds at once, never more than there are tiles
     const int64_t cap = resident_capacity(reinterpret_cast<const void *>(kern), G::THREADS, A.grid_cap);
     const dim3 pgrid((unsigned)(A.persistent ? std::min<int64_t>(A.K * A.G, cap) : A.K * A.G));
-    hipLaunchKernelGGL(kern, pgrid, block, 0, s, A);
+    // With a workgroup for every tile nobody needs to ask for a second one (and wait for the answer
+    // before it can end): a few microseconds off a small problem.
+    Args L = A;
+    if ((int64_t)pgrid.x == A.K * A.G) L.persistent = 0;
+    hipLaunchKernelGGL(kern, pgrid, block, 0, s, L);
     return hipGetLastError();
 }
 
