@@ -77,8 +77,12 @@ enum {
     LINREC_OPT_PERSISTENT = 7, /* look-back: launch as many workgroups as the GPU holds and let
                                   each loop over tiles (1), one workgroup per tile (0), or
                                   let the library decide per pass (-1, default)              */
-    LINREC_OPT_GRID_CAP = 8    /* look-back, persistent: at most this many workgroups per
+    LINREC_OPT_GRID_CAP = 8,   /* look-back, persistent: at most this many workgroups per
                                   compute unit; 0 (default) = as many as fit                 */
+    LINREC_OPT_STAGGER = 9     /* look-back: every other workgroup of the first round starts
+                                  this many microseconds (roughly; 0..16) late, so that the
+                                  workgroups do not load, scan and store in lock-step;
+                                  only launches of two rounds or more; default 3, 0 = off    */
 };
 
 /*

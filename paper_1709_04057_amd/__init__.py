@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     OPT_HPREV_LATE,
     OPT_PERSISTENT,
     OPT_SPIN_LIMIT,
+    OPT_STAGGER,
     OPT_TAPER,
     OPT_TILE,
     OPT_VARIANT,

@@ -13,6 +13,7 @@ _lib = None
 VARIANT_AUTO, VARIANT_THREEPHASE, VARIANT_LOOKBACK, VARIANT_SERIAL = 0, 1, 2, 3
 TAU_IDENTITY, TAU_TANH = 0, 1
 OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE, OPT_TAPER, OPT_PERSISTENT, OPT_GRID_CAP = 1, 2, 3, 4, 5, 6, 7, 8
+OPT_STAGGER = 9
 
 
 class LinrecError(RuntimeError):

@@ -50,6 +50,7 @@ struct Options {
     int64_t hp_late = -1;  // -1 automatic
     int64_t taper = 0;
     int64_t grid_cap = 0;
+    int64_t stagger = 3;
     int64_t persistent = -1;  // -1 automatic: forward persistent, backward one workgroup per tile (measured)
     Options()
     {
@@ -176,7 +177,7 @@ int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
             return T >= 192 ? (vec >= 4 ? 8 : 20) : short_wide;
         }
         if (C >= 1024) {
-            if (T >= 8192) return 19;
+            if (T >= 8192) return C >= 4096 ? 18 : 19;
             if (T < 192) return 1;
             return T * C <= ((int64_t)1 << 21) ? 21 : 20;
         }
@@ -399,6 +400,8 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
     A.spin_limit = (uint32_t)opts().spin_limit;
     A.persistent = plan.persistent < 0 ? ((bwd && !gated) ? 0 : 1) : plan.persistent;
     A.grid_cap = (int32_t)opts().grid_cap;
+    A.stagger = (int32_t)opts().stagger;
+    A.stagger_n = 0;
     A.trace = g_trace;
     if ((e = launch_tile_kernel(plan.tile, KIND_LOOKBACK, bwd, plan.hp_late, form, bf16, A, s)) != hipSuccess)
         return hip_fail(e, "launch(lookback)");
@@ -655,6 +658,10 @@ extern "C" int linrec_set_option(int option, int64_t value)
         if (value < 0 || value > 64) return LINREC_ERR_OPTION;
         opts().grid_cap = value;
         return LINREC_OK;
+    case LINREC_OPT_STAGGER:
+        if (value < 0 || value > 16) return LINREC_ERR_OPTION;
+        opts().stagger = value;
+        return LINREC_OK;
     default: return LINREC_ERR_OPTION;
     }
 }
@@ -670,6 +677,7 @@ extern "C" int64_t linrec_get_option(int option)
     case LINREC_OPT_TAPER: return opts().taper;
     case LINREC_OPT_PERSISTENT: return opts().persistent;
     case LINREC_OPT_GRID_CAP: return opts().grid_cap;
+    case LINREC_OPT_STAGGER: return opts().stagger;
     default: return LINREC_ERR_OPTION;
     }
 }

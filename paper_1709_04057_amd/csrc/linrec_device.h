@@ -1108,6 +1108,13 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     // it: no deadlock).
     // The host keeps K*G below 2^31, so a call's tickets fit 32 bits.
     const uint32_t total = (uint32_t)A.K * (uint32_t)A.G;
+    // The odd workgroups of the first round start a few microseconds late: the others, which are
+    // enough to saturate the memory system, are then scanning and storing while these load, instead of
+    // all of them doing each thing at the same time (consecutive workgroups go to different XCDs, so
+    // this is every other XCD).  Measured on an MI355X: up to 4 % on the forward pass of long sequences.
+    if ((int)blockIdx.x < A.stagger_n && (blockIdx.x & 1u)) {
+        for (int i = 0; i < A.stagger; ++i) __builtin_amdgcn_s_sleep(32);
+    }
     if (tid == 0) {
         sTicket[0] = (uint32_t)atomicAdd(&A.hdr->ticket, 1ull);
         sEpoch = __hip_atomic_load(&A.hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

@@ -49,6 +49,9 @@ struct Args {
     uint32_t spin_limit;
     int32_t persistent;          // look-back: workgroups loop over tickets (1) or take exactly one (0)
     int32_t grid_cap;            // look-back, persistent: at most this many workgroups per compute unit (0: no cap)
+    int32_t stagger;             // look-back: pause of the odd workgroups among the first stagger_n, in units of
+                                 // 2048 clocks (about a microsecond); stagger_n is set at launch
+    int32_t stagger_n;
     unsigned long long *trace;  // only read by builds with -DLINREC_TRACE: 8 words per tile
 };
 

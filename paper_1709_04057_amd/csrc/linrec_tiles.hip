@@ -85,6 +85,11 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
     // before it can end): a few microseconds off a small problem.
     Args L = A;
     if ((int64_t)pgrid.x == A.K * A.G) L.persistent = 0;
+    // Workgroups that start together load, scan and store together, and the memory system idles while
+    // they all scan.  When the launch is at least two rounds long, every other workgroup of the first
+    // round starts a little late (the kernel sleeps, see there).
+    const int64_t first_round = std::min<int64_t>(A.K * A.G, cap);
+    L.stagger_n = A.K * A.G >= 2 * first_round ? (int32_t)first_round : 0;
     hipLaunchKernelGGL(kern, pgrid, block, 0, s, L);
     return hipGetLastError();
 }

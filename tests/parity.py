@@ -88,7 +88,8 @@ class options:
     def __init__(self, **kw):
         self.kw = kw
         self.ids = dict(variant=lr.OPT_VARIANT, tile=lr.OPT_TILE, chunk_tiles=lr.OPT_CHUNK_TILES,
-                        spin_limit=lr.OPT_SPIN_LIMIT, hprev_late=lr.OPT_HPREV_LATE, taper=lr.OPT_TAPER, persistent=lr.OPT_PERSISTENT, grid_cap=lr.OPT_GRID_CAP)
+                        spin_limit=lr.OPT_SPIN_LIMIT, hprev_late=lr.OPT_HPREV_LATE, taper=lr.OPT_TAPER, persistent=lr.OPT_PERSISTENT, grid_cap=lr.OPT_GRID_CAP,
+                        stagger=lr.OPT_STAGGER)
 
     def __enter__(self):
         self.old = {k: lr.linrec_get_option(self.ids[k]) for k in self.kw}

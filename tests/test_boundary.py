@@ -153,6 +153,13 @@ def test_options_and_tile_table(L):
         lr.linrec_set_option(lr.OPT_VARIANT, 17)
     with pytest.raises(lr.LinrecError):
         lr.linrec_set_option(99, 0)
+    assert lr.linrec_get_option(lr.OPT_STAGGER) == 3           # documented default
+    lr.linrec_set_option(lr.OPT_STAGGER, 0)
+    assert lr.linrec_get_option(lr.OPT_STAGGER) == 0
+    lr.linrec_set_option(lr.OPT_STAGGER, 3)
+    for bad in (-1, 17):
+        with pytest.raises(lr.LinrecError):
+            lr.linrec_set_option(lr.OPT_STAGGER, bad)
     tiles = []
     i = 1
     while (info := lr.linrec_tile_info(i)) is not None:

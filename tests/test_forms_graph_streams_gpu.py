@@ -125,6 +125,37 @@ def test_tapered_tail_tiles_every_entry_point(taper):
         bf16_check(to_bf16(wl.make_generic(T, 1, 72, seed=34, device=DEV)), f"taper {taper} bf16")
 
 
+def test_staggered_start_changes_timing_only():
+    """LINREC_OPT_STAGGER delays every other workgroup of the first round: bit-identical results for every
+    entry point, whatever the delay, on a problem several rounds of workgroups long."""
+    T, B, n = 49_152, 4, 256
+    plain = wl.make_inputs(2, T=T, B=B, n=n, device=DEV)
+    gated = wl.make_gated(T, B, n, seed=41, device=DEV, gate_mean=1.0)
+    cell = wl.make_lstm(T, B, n, seed=42, device=DEV)
+    pre = [cell[k] for k in ("f_pre", "i_pre", "z_pre", "o_pre")]
+    half = {k: (v.to(torch.bfloat16) if torch.is_tensor(v) else v) for k, v in plain.items()}
+
+    def run_all():
+        h = lr.linrec_forward(plain["lam"], plain["x"], plain["h0"])
+        out = [h, *lr.linrec_backward(plain["lam"], h, plain["h0"], plain["grad_h"])]
+        hg = lr.linrec_gilr_forward(gated["g_pre"], gated["i_pre"], gated["h0"])
+        out += [hg, *lr.linrec_gilr_backward(gated["g_pre"], gated["i_pre"], hg, gated["h0"], gated["grad_h"])]
+        c, hc = lr.linrec_lstm_cell_forward(*pre, cell["c0"])
+        out += [c, hc, *lr.linrec_lstm_cell_backward(*pre, c, cell["c0"], cell["grad_h"])]
+        hb = lr.linrec_forward(half["lam"], half["x"], half["h0"])
+        out += [hb, *lr.linrec_backward(half["lam"], hb, half["h0"], half["grad_h"])]
+        torch.cuda.synchronize()
+        lr.linrec_check()
+        return out
+
+    with options(variant=lr.VARIANT_LOOKBACK, stagger=0):
+        ref = run_all()
+    for stagger in (3, 16):
+        with options(variant=lr.VARIANT_LOOKBACK, stagger=stagger):
+            got = run_all()
+        assert all(_same(a, b) for a, b in zip(got, ref)), f"stagger {stagger} changed a result"
+
+
 def test_rows_too_long_for_32_bit_tile_offsets_fall_back_to_the_serial_kernel():
     """A tile addresses its rows with 32-bit byte offsets; when rows*C*4 does not fit, every entry point
     must take the serial kernel by itself (and still be right)."""
