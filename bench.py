@@ -32,7 +32,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
-    ap.add_argument("--variant", default="auto", choices=["auto", "threephase", "lookback", "serial"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "threephase", "lookback", "serial", "walk"])
     ap.add_argument("--tile-fwd", type=int, default=0)
     ap.add_argument("--tile-bwd", type=int, default=0)
     ap.add_argument("--hprev-late", type=int, default=-1)
@@ -353,7 +353,7 @@ def main():
     dev = "cuda:0"
     torch.cuda.set_device(0)
     variant = {"auto": lr.VARIANT_AUTO, "threephase": lr.VARIANT_THREEPHASE, "lookback": lr.VARIANT_LOOKBACK,
-               "serial": lr.VARIANT_SERIAL}[args.variant]
+               "serial": lr.VARIANT_SERIAL, "walk": lr.VARIANT_WALK}[args.variant]
     lr.linrec_set_option(lr.OPT_VARIANT, variant)
     lr.linrec_set_option(lr.OPT_HPREV_LATE, args.hprev_late)
 

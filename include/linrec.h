@@ -60,8 +60,13 @@ enum {
     LINREC_VARIANT_AUTO = 0,       /* library picks (single pass where it applies)           */
     LINREC_VARIANT_THREEPHASE = 1, /* Algorithm 1 as three kernels: reduce, scan, rescan     */
     LINREC_VARIANT_LOOKBACK = 2,   /* one kernel; chunk carries found by decoupled look-back */
-    LINREC_VARIANT_SERIAL = 3      /* one thread per column walks T (the paper's baseline of
+    LINREC_VARIANT_SERIAL = 3,     /* one thread per column walks T (the paper's baseline of
                                       Section 4.1.1, "in serial over sequence length")       */
+    LINREC_VARIANT_WALK = 4        /* one workgroup per group of columns walks T tile by tile:
+                                      parallel over the sequence inside a tile only, nothing is
+                                      exchanged between workgroups; for short, wide problems
+                                      (plain fp32 recurrence; the other entry points take the
+                                      single pass instead)                                      */
 };
 
 enum {

@@ -27,6 +27,7 @@ from .binding import (  # noqa: F401
     VARIANT_LOOKBACK,
     VARIANT_SERIAL,
     VARIANT_THREEPHASE,
+    VARIANT_WALK,
     declared_symbols,
     lib,
     lib_path,

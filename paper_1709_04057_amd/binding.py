@@ -10,7 +10,7 @@ _LIB_PATH = os.environ.get("LINREC_LIB_PATH", os.path.join(_HERE, "liblinrec.so"
 _HEADER = os.path.join(os.path.dirname(_HERE), "include", "linrec.h")
 _lib = None
 
-VARIANT_AUTO, VARIANT_THREEPHASE, VARIANT_LOOKBACK, VARIANT_SERIAL = 0, 1, 2, 3
+VARIANT_AUTO, VARIANT_THREEPHASE, VARIANT_LOOKBACK, VARIANT_SERIAL, VARIANT_WALK = 0, 1, 2, 3, 4
 TAU_IDENTITY, TAU_TANH = 0, 1
 OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE, OPT_TAPER, OPT_PERSISTENT, OPT_GRID_CAP = 1, 2, 3, 4, 5, 6, 7, 8
 OPT_STAGGER = 9

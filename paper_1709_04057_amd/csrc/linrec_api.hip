@@ -58,6 +58,7 @@ struct Options {
             if (!strcmp(v, "threephase")) variant = LINREC_VARIANT_THREEPHASE;
             else if (!strcmp(v, "lookback")) variant = LINREC_VARIANT_LOOKBACK;
             else if (!strcmp(v, "serial")) variant = LINREC_VARIANT_SERIAL;
+            else if (!strcmp(v, "walk")) variant = LINREC_VARIANT_WALK;
         }
         if (const char *v = getenv("LINREC_TILE")) {
             const long t = strtol(v, nullptr, 10);
@@ -239,6 +240,24 @@ int auto_tile_form(int64_t T, int64_t C, bool bwd, int form)
     return C >= 2048 ? 21 : T >= 256 ? 18 : plain;
 }
 
+// Tile shape for the walk variant (one workgroup per column group, nothing between workgroups), or 0
+// where the single pass is the better choice.  Measured on an MI355X over T = 64 .. 16384 x
+// C = 1024 .. 65536: the walk wins by 1.2-1.7x for T <= 1024 and C >= 8192 and by 1.05-1.15x for the
+// widest problems up to T = 4096; it loses as soon as the columns alone do not fill the GPU.  It
+// wants about one workgroup per compute unit (256) to a few, all resident at once, so the width of
+// the tile follows C.
+int auto_walk_tile(int64_t T, int64_t C, int vec, bool bwd)
+{
+    const bool walk = (T <= 512 && C >= 4096) || (T <= 1024 && C >= 8192) || (T <= 2048 && C >= 24576) ||
+                      (T <= 4096 && C >= 32768 && !bwd);
+    if (!walk) return 0;
+    if (C <= 8192) return 22;                      // 32 columns x 1024 rows, 512 threads
+    if (C <= 16384) return vec >= 2 ? 16 : 20;     // 64 columns
+    if (C <= 24576) return 18;                     // 32 columns, three or four workgroups per compute unit
+    if (C <= 32768 || vec < 4) return 21;          // 64 columns
+    return bwd ? 6 : 10;                           // 256 columns (16-byte accesses)
+}
+
 struct Plan {
     int variant, tile;
     bool hp_late;
@@ -288,6 +307,17 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
             }
         }
     }
+    // No option and no tuned plan: short, wide problems of the plain fp32 recurrence take the walk.
+    if (opts().variant == LINREC_VARIANT_AUTO && p.tile == 0 && !gated && !bf16) {
+        if (const int wt = auto_walk_tile(T, C, vec, bwd)) {
+            p.variant = LINREC_VARIANT_WALK;
+            p.tile = wt;
+        }
+    }
+    if (p.variant == LINREC_VARIANT_WALK && p.tile == 0 && !gated && !bf16) {  // walk asked for by option
+        p.tile = auto_walk_tile(T, C, vec, bwd);
+        if (p.tile == 0) p.tile = auto_walk_tile(1, std::max<int64_t>(C, 4096), vec, bwd);
+    }
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && kTiles[p.tile - 1].vec < 2) p.tile = 0;
@@ -316,7 +346,8 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
 {
     const bool gated = form != FORM_PLAIN;
     Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd, form, bf16);
-    if ((gated || bf16) && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
+    if ((gated || bf16) && (plan.variant == LINREC_VARIANT_THREEPHASE || plan.variant == LINREC_VARIANT_WALK))
+        plan.variant = LINREC_VARIANT_LOOKBACK;
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
         if ((e = launch_serial(A, bwd, form, bf16, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
@@ -325,6 +356,14 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
     const TileDesc &d = kTiles[plan.tile - 1];
     A.G = (int32_t)ceil_div(A.C, d.cols());
     const int64_t tiles_t = ceil_div(A.T, d.rows());
+
+    if (plan.variant == LINREC_VARIANT_WALK) {  // one kernel, no workspace
+        A.M = 1;
+        A.K = tiles_t;
+        if ((e = launch_tile_kernel(plan.tile, KIND_WALK, bwd, false, FORM_PLAIN, false, A, s)) != hipSuccess)
+            return hip_fail(e, "launch(walk)");
+        return LINREC_OK;
+    }
 
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e, "hipGetDevice");
@@ -627,7 +666,7 @@ extern "C" int linrec_set_option(int option, int64_t value)
 {
     switch (option) {
     case LINREC_OPT_VARIANT:
-        if (value < LINREC_VARIANT_AUTO || value > LINREC_VARIANT_SERIAL) return LINREC_ERR_OPTION;
+        if (value < LINREC_VARIANT_AUTO || value > LINREC_VARIANT_WALK) return LINREC_ERR_OPTION;
         opts().variant = value;
         return LINREC_OK;
     case LINREC_OPT_TILE:
@@ -717,7 +756,8 @@ extern "C" int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n,
     const int form = entry_point == LINREC_ENTRY_GILR ? FORM_GATED : entry_point == LINREC_ENTRY_LSTM_CELL ? FORM_LSTM : FORM_PLAIN;
     const int vec = bf16 ? max_vec_bf16(C, {al}) : form != FORM_PLAIN ? 1 : max_vec(C, {al});
     Plan p = make_plan(T, C, vec, backward != 0, form, bf16);
-    if ((form != FORM_PLAIN || bf16) && p.variant == LINREC_VARIANT_THREEPHASE) p.variant = LINREC_VARIANT_LOOKBACK;
+    if ((form != FORM_PLAIN || bf16) && (p.variant == LINREC_VARIANT_THREEPHASE || p.variant == LINREC_VARIANT_WALK))
+        p.variant = LINREC_VARIANT_LOOKBACK;
     if (variant) *variant = p.variant;
     if (tile_id) *tile_id = p.tile;
     return LINREC_OK;

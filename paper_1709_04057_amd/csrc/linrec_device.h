@@ -1010,23 +1010,34 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_reduce(const Args A)
 
 // ---------------------------------------------------------------------------------------------
 // Three-phase variant, kernel 3: per-chunk rescan from the carry (Algorithm 1, second parallel-for).
+//
+// With WALK the same loop is the whole computation: grid = G workgroups, each walks ALL the tiles of
+// its column group in time order from the initial state (zero for the backward pass), so there are
+// no chunk summaries, no other kernel and no communication between workgroups.  Parallel over the
+// sequence inside a tile only -- the choice for short, wide problems, where the columns alone fill
+// the GPU and the summaries between workgroups are pure overhead (the overhead Section 4.1.1 names
+// for short sequences: several passes over the data, communication between processors).
 // ---------------------------------------------------------------------------------------------
-template <class G, bool BWD>
+template <class G, bool BWD, bool WALK = false>
 __global__ __launch_bounds__(G::THREADS, G::OCC) void k_fixup(const Args A)
 {
     constexpr int VEC = G::VEC, R = G::R, WC = G::WC, ROWS = G::ROWS;
     __shared__ ScanLds<G> lds;
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
-    const int g = (int)(blockIdx.x % (unsigned)A.G);
-    const int64_t k = blockIdx.x / (unsigned)A.G;
+    const int g = WALK ? (int)blockIdx.x : (int)(blockIdx.x % (unsigned)A.G);
+    const int64_t k = WALK ? 0 : (int64_t)(blockIdx.x / (unsigned)A.G);
     const int64_t col = ((int64_t)g * WC + tc) * VEC;
     const bool col_ok = col < A.C;
 
     dvec<VEC> cc = dsplat<VEC>(0.0);  // state entering the current tile
-    if (col_ok) cc = ldd<VEC>(A.carry + k * A.C + col);
+    if constexpr (WALK) {
+        if (!BWD && col_ok && A.h0) cc = widen<VEC>(pld<G>(A.h0, col));
+    } else {
+        if (col_ok) cc = ldd<VEC>(A.carry + k * A.C + col);
+    }
 
-    for (int m = 0; m < A.M; ++m) {
-        const int64_t tu0 = (k * A.M + m) * ROWS;
+    for (int64_t m = 0; WALK || m < A.M; ++m) {
+        const int64_t tu0 = (WALK ? m : k * A.M + m) * ROWS;
         if (tu0 >= A.T) break;
         const bool interior = tile_interior<G, BWD>(A, tu0, g);
         const int64_t u0 = tu0 + (int64_t)tt * R;

@@ -55,7 +55,7 @@ struct Args {
     unsigned long long *trace;  // only read by builds with -DLINREC_TRACE: 8 words per tile
 };
 
-enum Kind { KIND_REDUCE = 0, KIND_FIXUP = 1, KIND_LOOKBACK = 2 };
+enum Kind { KIND_REDUCE = 0, KIND_FIXUP = 1, KIND_LOOKBACK = 2, KIND_WALK = 3 };
 enum Form { FORM_PLAIN = 0, FORM_GATED = 1, FORM_LSTM = 2 };
 
 struct TileDesc {

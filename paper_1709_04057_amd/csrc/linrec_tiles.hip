@@ -62,6 +62,12 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
             if (bwd) hipLaunchKernelGGL((k_fixup<G, true>), grid, block, 0, s, A);
             else hipLaunchKernelGGL((k_fixup<G, false>), grid, block, 0, s, A);
             return hipGetLastError();
+        case KIND_WALK: {  // one workgroup per column group
+            const dim3 wgrid((unsigned)A.G);
+            if (bwd) hipLaunchKernelGGL((k_fixup<G, true, true>), wgrid, block, 0, s, A);
+            else hipLaunchKernelGGL((k_fixup<G, false, true>), wgrid, block, 0, s, A);
+            return hipGetLastError();
+        }
         case KIND_LOOKBACK:
             kern = !bwd ? k_lookback<G, false, false> : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
             break;

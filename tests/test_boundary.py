@@ -144,7 +144,7 @@ def test_entry_points_validate_before_touching_the_gpu(L):
 
 
 def test_options_and_tile_table(L):
-    assert lr.linrec_get_option(lr.OPT_VARIANT) in (0, 1, 2, 3)
+    assert lr.linrec_get_option(lr.OPT_VARIANT) in (0, 1, 2, 3, 4)
     old = lr.linrec_get_option(lr.OPT_VARIANT)
     lr.linrec_set_option(lr.OPT_VARIANT, lr.VARIANT_THREEPHASE)
     assert lr.linrec_get_option(lr.OPT_VARIANT) == lr.VARIANT_THREEPHASE
@@ -180,7 +180,7 @@ def test_plan_is_host_only_and_consistent(L):
             for align in (4, 8, 16):
                 variant, tile = lr.linrec_plan(T, B, n, backward=bwd, alignment=align)
                 info = lr.linrec_tile_info(tile)
-                assert variant in (lr.VARIANT_THREEPHASE, lr.VARIANT_LOOKBACK, lr.VARIANT_SERIAL)
+                assert variant in (lr.VARIANT_THREEPHASE, lr.VARIANT_LOOKBACK, lr.VARIANT_SERIAL, lr.VARIANT_WALK)
                 assert info is not None
                 assert (B * n) % info["cols_per_thread"] == 0
                 assert info["cols_per_thread"] * 4 <= align
@@ -198,6 +198,15 @@ def test_plan_is_host_only_and_consistent(L):
             else:
                 assert v == lr.VARIANT_LOOKBACK and lr.linrec_tile_info(t)["cols_per_thread"] in (2, 4)
             assert lr.linrec_plan_for(lr.ENTRY_PLAIN, T, B, n, backward=bwd) == lr.linrec_plan(T, B, n, backward=bwd)
+    # short and wide: the plain fp32 recurrence walks (one workgroup per column group), the other
+    # families and long sequences keep the single pass
+    for bwd in (False, True):
+        assert lr.linrec_plan(1024, 16, 1024, backward=bwd)[0] == lr.VARIANT_WALK
+        assert lr.linrec_plan(256, 8, 1024, backward=bwd)[0] == lr.VARIANT_WALK
+        assert lr.linrec_plan(65536, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
+        assert lr.linrec_plan(1024, 4, 256, backward=bwd)[0] == lr.VARIANT_LOOKBACK
+        for fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16):
+            assert lr.linrec_plan_for(fam, 1024, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
     with pytest.raises(lr.LinrecError):
         lr.linrec_plan_for(9, 10, 1, 1)
     # a tile whose rows would not fit 32-bit offsets falls back to the serial kernel

@@ -10,7 +10,8 @@ from parity import (all_tiles, check_backward, check_forward, fwd_bwd_check, opt
 pytestmark = pytest.mark.gpu
 
 DEV = "cuda:0"
-VARIANTS = {"threephase": lr.VARIANT_THREEPHASE, "lookback": lr.VARIANT_LOOKBACK, "serial": lr.VARIANT_SERIAL}
+VARIANTS = {"threephase": lr.VARIANT_THREEPHASE, "lookback": lr.VARIANT_LOOKBACK, "serial": lr.VARIANT_SERIAL,
+            "walk": lr.VARIANT_WALK}
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -29,7 +30,7 @@ EDGE_T = [1, 2, 63, 64, 65, 127, 129, 257, 600, 1031]
 EDGE_BN = [(1, 1), (1, 3), (1, 63), (1, 64), (1, 65), (1, 100), (3, 100), (2, 32), (1, 128), (4, 68)]
 
 
-@pytest.mark.parametrize("variant", ["threephase", "lookback"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "walk"])
 def test_edge_shapes_all_tiles(variant):
     tiles = all_tiles()
     seed = 0
@@ -69,7 +70,7 @@ def test_auto_plan_edge_shapes():
 # ------------------------------------------------------------------------------------------------
 # the five workloads
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", ["threephase", "lookback"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "walk"])
 def test_config1_full(variant):
     inp = wl.make_inputs(1, device=DEV)
     with options(variant=VARIANTS[variant]):
@@ -78,7 +79,7 @@ def test_config1_full(variant):
 
 @pytest.mark.parametrize("cfg,shape", [(2, (8192, 4, 256)), (3, (65536, 1, 128)), (4, (1024, 16, 1024)),
                                        (5, (16384, 8, 512))])
-@pytest.mark.parametrize("variant", ["threephase", "lookback"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "walk"])
 def test_configs_reduced_T_every_vector_tile(cfg, shape, variant):
     """Same widths and value distributions as the full workloads, shorter T; every multi-column tile shape."""
     T, B, n = shape
@@ -97,6 +98,16 @@ def test_configs_full_size(cfg, variant):
     inp = wl.make_inputs(cfg, device=DEV)
     with options(variant=VARIANTS[variant]):
         fwd_bwd_check(inp, f"cfg{cfg} full {variant}")
+
+
+@pytest.mark.parametrize("shape", [(1024, 16, 1024), (512, 8, 1024), (200, 3, 5000), (2048, 6, 4096), (64, 16, 4096)])
+def test_short_wide_shapes_take_the_walk(shape):
+    """Automatic plan on short, wide problems: one workgroup per column group walks the sequence (no
+    look-back); ragged numbers of columns and rows included."""
+    T, B, n = shape
+    for bwd in (False, True):
+        assert lr.linrec_plan(T, B, n, backward=bwd)[0] == lr.VARIANT_WALK
+    fwd_bwd_check(wl.make_inputs(2, T=T, B=B, n=n, device=DEV), f"short wide {shape} auto")
 
 
 def test_config5_full_size_lookback():
@@ -127,7 +138,7 @@ def test_per_channel_lambda_accuracy_stress(cfg, shape):
 # ------------------------------------------------------------------------------------------------
 # invariants the mathematics fixes, checked on the GPU result itself
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", ["threephase", "lookback", "serial"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "serial", "walk"])
 def test_lambda_zero_is_bit_exact(variant):
     inp = wl.make_generic(3000, 2, 96, 31, device=DEV)
     inp["lam"].zero_()
@@ -142,7 +153,7 @@ def test_lambda_zero_is_bit_exact(variant):
     assert torch.equal(gh0, torch.zeros_like(gh0))
 
 
-@pytest.mark.parametrize("variant", ["threephase", "lookback"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "walk"])
 def test_lambda_one_is_prefix_sum(variant):
     inp = wl.make_generic(20000, 1, 64, 32, device=DEV)
     inp["lam"].fill_(1.0)
@@ -154,7 +165,7 @@ def test_lambda_one_is_prefix_sum(variant):
     assert err <= 1e-5 * (1 + ref.abs().max().item())
 
 
-@pytest.mark.parametrize("variant", ["threephase", "lookback"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "walk"])
 def test_split_resume_matches_one_shot(variant):
     """Forward on [0,T1) then [T1,T) seeded with h[T1-1] equals the one-shot run (C_{-1} = h_0)."""
     inp = wl.make_inputs(2, T=6000, B=2, n=128, device=DEV)
@@ -173,7 +184,7 @@ def test_split_resume_matches_one_shot(variant):
 # ------------------------------------------------------------------------------------------------
 # boundary behaviour on the device
 # ------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("variant", ["threephase", "lookback", "serial"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "serial", "walk"])
 def test_in_place_and_optional_outputs(variant):
     inp = wl.make_inputs(2, T=3000, B=2, n=64, device=DEV)
     with options(variant=VARIANTS[variant]):
@@ -236,7 +247,7 @@ def test_invalid_arguments_raise_on_device_pointers():
     assert ei.value.status == -3
 
 
-@pytest.mark.parametrize("variant", ["threephase", "lookback"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "walk"])
 def test_deterministic_and_stream_safe(variant):
     inp = wl.make_inputs(5, T=20000, B=2, n=256, device=DEV)
     with options(variant=VARIANTS[variant]):
@@ -353,7 +364,7 @@ def test_configs_full_size_with_tuned_plan(cfg):
     fwd_bwd_check(inp, f"cfg{cfg} full tuned")
 
 
-@pytest.mark.parametrize("variant", ["threephase", "lookback"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "walk"])
 def test_non_finite_values_stay_in_their_column(variant):
     """NaN / Inf in one column must not leak into other columns, and must not hang the look-back."""
     inp = wl.make_inputs(2, T=9000, B=1, n=96, device=DEV)
@@ -379,7 +390,7 @@ def test_non_finite_values_stay_in_their_column(variant):
     assert torch.isnan(gx[:99, 0, 40]).all() and torch.isfinite(gx[100:, 0, 40]).all()
 
 
-@pytest.mark.parametrize("variant", ["threephase", "lookback", "serial"])
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "serial", "walk"])
 def test_growing_recurrence_within_the_documented_domain(variant):
     """|lambda| > 1 is supported while the partial products stay finite."""
     T, B, n = 700, 1, 64

@@ -25,7 +25,7 @@ def _cases(seed, n):
         B = int(rng.choice([1, 1, 2, 3]))
         n_ = max(1, C // B)
         opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_LOOKBACK, lr.VARIANT_THREEPHASE,
-                                            lr.VARIANT_SERIAL])),
+                                            lr.VARIANT_SERIAL, lr.VARIANT_WALK])),
                     tile=int(rng.integers(0, N_TILES + 1)), persistent=int(rng.integers(-1, 2)),
                     taper=int(rng.choice([0, 0, 2, 8])), hprev_late=int(rng.integers(-1, 2)))
         yield i, T, B, n_, opts, int(rng.integers(1 << 30))
