@@ -64,9 +64,8 @@ enum {
                                       Section 4.1.1, "in serial over sequence length")       */
     LINREC_VARIANT_WALK = 4        /* one workgroup per group of columns walks T tile by tile:
                                       parallel over the sequence inside a tile only, nothing is
-                                      exchanged between workgroups; for short, wide problems
-                                      (plain fp32 recurrence; the other entry points take the
-                                      single pass instead)                                      */
+                                      exchanged between workgroups; what the library picks for
+                                      short, wide problems                                      */
 };
 
 enum {

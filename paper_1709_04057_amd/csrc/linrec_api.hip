@@ -258,6 +258,32 @@ int auto_walk_tile(int64_t T, int64_t C, int vec, bool bwd)
     return bwd ? 6 : 10;                           // 256 columns (16-byte accesses)
 }
 
+// The same for the gated layer, the LSTM cell (both: one-column shapes) and bf16 storage (two or four
+// columns per thread).  Their tiles take longer (activations; half the bytes per element), so the
+// region where the walk wins is smaller: up to T = 256 for the cell, 512 .. 1024 for the gated layer,
+// 1024 .. 2048 with bf16 storage, by 1.1-2x.
+int auto_walk_tile_form(int64_t T, int64_t C, bool bwd, int form)
+{
+    if (form == FORM_GATED) {
+        const bool walk = (T <= 256 && C >= 8192) || (T <= 512 && C >= 16384) ||
+                          (!bwd && ((T <= 512 && C >= 8192) || (T <= 1024 && C >= 16384)));
+        if (!walk) return 0;
+        if (C <= 8192) return 17;
+        if (C <= 16384) return bwd ? 18 : 20;
+        if (C <= 24576) return 18;
+        return T <= 256 ? 1 : 21;
+    }
+    if (T > 256 || C < 4096) return 0;  // the cell
+    return T <= 64 ? 1 : C >= 32768 ? 21 : 18;
+}
+int auto_walk_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
+{
+    const bool walk = (T <= 1024 && C >= 12288) || (T <= 2048 && C >= 32768);
+    if (!walk || vec < 2) return 0;
+    if (C <= 16384) return T >= 768 ? 30 : (bwd && vec >= 4) ? 26 : 24;
+    return vec >= 4 ? 8 : 28;
+}
+
 struct Plan {
     int variant, tile;
     bool hp_late;
@@ -307,17 +333,19 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
             }
         }
     }
-    // No option and no tuned plan: short, wide problems of the plain fp32 recurrence take the walk.
-    if (opts().variant == LINREC_VARIANT_AUTO && p.tile == 0 && !gated && !bf16) {
-        if (const int wt = auto_walk_tile(T, C, vec, bwd)) {
+    // No option and no tuned plan: short, wide problems take the walk.
+    if (opts().variant == LINREC_VARIANT_AUTO && p.tile == 0) {
+        const int wt = bf16 ? auto_walk_tile_bf16(T, C, vec, bwd) : gated ? auto_walk_tile_form(T, C, bwd, form)
+                                                                  : auto_walk_tile(T, C, vec, bwd);
+        if (wt) {
             p.variant = LINREC_VARIANT_WALK;
             p.tile = wt;
         }
     }
-    if (p.variant == LINREC_VARIANT_WALK && p.tile == 0 && !gated && !bf16) {  // walk asked for by option
-        p.tile = auto_walk_tile(T, C, vec, bwd);
-        if (p.tile == 0) p.tile = auto_walk_tile(1, std::max<int64_t>(C, 4096), vec, bwd);
-    }
+    // (the walk asked for by option without a shape: the plain recurrence gets the shape the walk would
+    // take at this width; the other families their single-pass shape, below)
+    if (p.variant == LINREC_VARIANT_WALK && p.tile == 0 && !gated && !bf16)
+        p.tile = auto_walk_tile(1, std::max<int64_t>(C, 4096), vec, bwd);
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && kTiles[p.tile - 1].vec < 2) p.tile = 0;
@@ -346,8 +374,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
 {
     const bool gated = form != FORM_PLAIN;
     Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd, form, bf16);
-    if ((gated || bf16) && (plan.variant == LINREC_VARIANT_THREEPHASE || plan.variant == LINREC_VARIANT_WALK))
-        plan.variant = LINREC_VARIANT_LOOKBACK;
+    if ((gated || bf16) && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
         if ((e = launch_serial(A, bwd, form, bf16, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
@@ -360,7 +387,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
     if (plan.variant == LINREC_VARIANT_WALK) {  // one kernel, no workspace
         A.M = 1;
         A.K = tiles_t;
-        if ((e = launch_tile_kernel(plan.tile, KIND_WALK, bwd, false, FORM_PLAIN, false, A, s)) != hipSuccess)
+        if ((e = launch_tile_kernel(plan.tile, KIND_WALK, bwd, false, form, bf16, A, s)) != hipSuccess)
             return hip_fail(e, "launch(walk)");
         return LINREC_OK;
     }
@@ -756,8 +783,7 @@ extern "C" int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n,
     const int form = entry_point == LINREC_ENTRY_GILR ? FORM_GATED : entry_point == LINREC_ENTRY_LSTM_CELL ? FORM_LSTM : FORM_PLAIN;
     const int vec = bf16 ? max_vec_bf16(C, {al}) : form != FORM_PLAIN ? 1 : max_vec(C, {al});
     Plan p = make_plan(T, C, vec, backward != 0, form, bf16);
-    if ((form != FORM_PLAIN || bf16) && (p.variant == LINREC_VARIANT_THREEPHASE || p.variant == LINREC_VARIANT_WALK))
-        p.variant = LINREC_VARIANT_LOOKBACK;
+    if ((form != FORM_PLAIN || bf16) && p.variant == LINREC_VARIANT_THREEPHASE) p.variant = LINREC_VARIANT_LOOKBACK;
     if (variant) *variant = p.variant;
     if (tile_id) *tile_id = p.tile;
     return LINREC_OK;

@@ -1010,34 +1010,23 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_reduce(const Args A)
 
 // ---------------------------------------------------------------------------------------------
 // Three-phase variant, kernel 3: per-chunk rescan from the carry (Algorithm 1, second parallel-for).
-//
-// With WALK the same loop is the whole computation: grid = G workgroups, each walks ALL the tiles of
-// its column group in time order from the initial state (zero for the backward pass), so there are
-// no chunk summaries, no other kernel and no communication between workgroups.  Parallel over the
-// sequence inside a tile only -- the choice for short, wide problems, where the columns alone fill
-// the GPU and the summaries between workgroups are pure overhead (the overhead Section 4.1.1 names
-// for short sequences: several passes over the data, communication between processors).
 // ---------------------------------------------------------------------------------------------
-template <class G, bool BWD, bool WALK = false>
+template <class G, bool BWD>
 __global__ __launch_bounds__(G::THREADS, G::OCC) void k_fixup(const Args A)
 {
     constexpr int VEC = G::VEC, R = G::R, WC = G::WC, ROWS = G::ROWS;
     __shared__ ScanLds<G> lds;
     const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
-    const int g = WALK ? (int)blockIdx.x : (int)(blockIdx.x % (unsigned)A.G);
-    const int64_t k = WALK ? 0 : (int64_t)(blockIdx.x / (unsigned)A.G);
+    const int g = (int)(blockIdx.x % (unsigned)A.G);
+    const int64_t k = blockIdx.x / (unsigned)A.G;
     const int64_t col = ((int64_t)g * WC + tc) * VEC;
     const bool col_ok = col < A.C;
 
     dvec<VEC> cc = dsplat<VEC>(0.0);  // state entering the current tile
-    if constexpr (WALK) {
-        if (!BWD && col_ok && A.h0) cc = widen<VEC>(pld<G>(A.h0, col));
-    } else {
-        if (col_ok) cc = ldd<VEC>(A.carry + k * A.C + col);
-    }
+    if (col_ok) cc = ldd<VEC>(A.carry + k * A.C + col);
 
-    for (int64_t m = 0; WALK || m < A.M; ++m) {
-        const int64_t tu0 = (WALK ? m : k * A.M + m) * ROWS;
+    for (int m = 0; m < A.M; ++m) {
+        const int64_t tu0 = (k * A.M + m) * ROWS;
         if (tu0 >= A.T) break;
         const bool interior = tile_interior<G, BWD>(A, tu0, g);
         const int64_t u0 = tu0 + (int64_t)tt * R;
@@ -1056,6 +1045,69 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_fixup(const Args A)
         tile_scan<G>(lds, tid, P, S, Pe, Se, Pt, St);
         rescan<G>(r, narrow<VEC>(dfma<VEC>(Pe, cc, widen<VEC>(Se))));
         tile_store<G, BWD>(A, ad, mk, col, interior, r, hp);
+        cc = dfma<VEC>(Pt, cc, widen<VEC>(St));
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Walk: grid = G workgroups, each goes through ALL the tiles of its column group in time order from
+// the initial state (zero for the backward pass), carrying the state in fp64.  There are no chunk
+// summaries, no other kernel and nothing between workgroups; the sequence is parallel inside a tile
+// only.  The choice for short, wide problems, where the columns alone fill the GPU and summaries
+// between workgroups are pure overhead (the overhead Section 4.1.1 names for short sequences: several
+// passes over the data, communication between processors).  Exists for every form and storage type
+// the single-pass kernel exists for, with the same prologues and epilogues.
+// ---------------------------------------------------------------------------------------------
+template <class G, bool BWD, int FORM = FORM_PLAIN>
+__global__ __launch_bounds__(G::THREADS, G::OCC) void k_walk(const Args A)
+{
+    constexpr int VEC = G::VEC, R = G::R, WC = G::WC, ROWS = G::ROWS;
+    __shared__ ScanLds<G> lds;
+    const int tid = threadIdx.x, tc = tid % WC, tt = tid / WC;
+    const int g = (int)blockIdx.x;
+    const int64_t col = ((int64_t)g * WC + tc) * VEC;
+    const bool col_ok = col < A.C;
+
+    dvec<VEC> cc = dsplat<VEC>(0.0);  // state entering the current tile
+    if (!BWD && col_ok && A.h0) cc = widen<VEC>(pld<G>(A.h0, col));
+
+    for (int64_t m = 0;; ++m) {
+        const int64_t tu0 = m * ROWS;
+        if (tu0 >= A.T) break;
+        const bool interior = tile_interior<G, BWD>(A, tu0, g);
+        const int64_t u0 = tu0 + (int64_t)tt * R;
+        Rows<G> r;
+        row_t<G> hp[(BWD && FORM == FORM_PLAIN) ? R : 1];
+        const TileAddr<G, BWD> ad(A, tu0, g, tt, tc);
+        const RowMask<G, BWD> mk(A, u0, col_ok);
+        constexpr int NC = (BWD && FORM == FORM_LSTM) ? R : 1;
+        vec<VEC> cst[NC];
+        tile_load<G, BWD, FORM, NC>(A, ad, mk, interior, r, cst);
+        if constexpr (BWD && FORM == FORM_PLAIN) {
+            if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
+        }
+        vec<VEC> S, Se, St;
+        dvec<VEC> P, Pe, Pt;
+        local_reduce<G, FORM>(r, P, S);
+        if (m > 0) __syncthreads();  // the previous tile's wavefront totals have been consumed
+        tile_scan<G>(lds, tid, P, S, Pe, Se, Pt, St);
+        const vec<VEC> carry_in = narrow<VEC>(dfma<VEC>(Pe, cc, widen<VEC>(Se)));
+        if constexpr (BWD && G::IO == IO_BF16) {
+            static_assert(FORM == FORM_PLAIN, "bf16 storage: the plain recurrence");
+            rescan_bwd_packed<G>(A, mk, col, interior, r, hp, carry_in);
+        } else {
+            rescan<G, FORM>(r, carry_in);
+        }
+        if constexpr (BWD && FORM == FORM_GATED) {
+            __builtin_amdgcn_sched_barrier(0);  // the epilogue's loads stay behind the rescan
+            tile_store_gated_bwd<G>(A, ad, mk, col, interior, r);
+        } else if constexpr (FORM == FORM_LSTM) {
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (BWD) tile_store_lstm_bwd<G>(A, ad, mk, col, interior, r, cst);
+            else tile_store_lstm_fwd<G>(A, ad, mk, interior, r);
+        } else {
+            tile_store<G, BWD>(A, ad, mk, col, interior, r, hp);
+        }
         cc = dfma<VEC>(Pt, cc, widen<VEC>(St));
     }
 }

@@ -48,7 +48,7 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
     constexpr bool kHasF32 = G::R * G::VEC <= 64, kHasBf16 = G::VEC >= 2;
     constexpr bool kHasGated = kHasF32 && G::VEC == 1, kHasLstm = kHasGated && G::R <= 32;
     if (form < FORM_PLAIN || form > FORM_LSTM) return hipErrorInvalidValue;
-    if ((form != FORM_PLAIN || bf16) && kind != KIND_LOOKBACK) return hipErrorInvalidValue;
+    if ((form != FORM_PLAIN || bf16) && kind != KIND_LOOKBACK && kind != KIND_WALK) return hipErrorInvalidValue;
     if (bf16 ? (!kHasBf16 || form != FORM_PLAIN) : !kHasF32) return hipErrorInvalidValue;
     if ((form == FORM_GATED && !kHasGated) || (form == FORM_LSTM && !kHasLstm)) return hipErrorInvalidValue;
     void (*kern)(const Args) = nullptr;
@@ -62,28 +62,33 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
             if (bwd) hipLaunchKernelGGL((k_fixup<G, true>), grid, block, 0, s, A);
             else hipLaunchKernelGGL((k_fixup<G, false>), grid, block, 0, s, A);
             return hipGetLastError();
-        case KIND_WALK: {  // one workgroup per column group
-            const dim3 wgrid((unsigned)A.G);
-            if (bwd) hipLaunchKernelGGL((k_fixup<G, true, true>), wgrid, block, 0, s, A);
-            else hipLaunchKernelGGL((k_fixup<G, false, true>), wgrid, block, 0, s, A);
-            return hipGetLastError();
-        }
+        case KIND_WALK: kern = bwd ? k_walk<G, true> : k_walk<G, false>; break;
         case KIND_LOOKBACK:
             kern = !bwd ? k_lookback<G, false, false> : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
             break;
         }
     }
+    const bool walk = kind == KIND_WALK;
     if constexpr (kHasBf16) {
         using GB = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16>;
-        if (bf16) kern = !bwd ? k_lookback<GB, false, false> : k_lookback<GB, true, false>;
+        if (bf16) kern = walk ? (bwd ? k_walk<GB, true> : k_walk<GB, false>)
+                              : (bwd ? k_lookback<GB, true, false> : k_lookback<GB, false, false>);
     }
     if constexpr (kHasGated) {
-        if (form == FORM_GATED) kern = bwd ? k_lookback<G, true, true, FORM_GATED> : k_lookback<G, false, false, FORM_GATED>;
+        if (form == FORM_GATED)
+            kern = walk ? (bwd ? k_walk<G, true, FORM_GATED> : k_walk<G, false, FORM_GATED>)
+                        : (bwd ? k_lookback<G, true, true, FORM_GATED> : k_lookback<G, false, false, FORM_GATED>);
     }
     if constexpr (kHasLstm) {
-        if (form == FORM_LSTM) kern = bwd ? k_lookback<G, true, true, FORM_LSTM> : k_lookback<G, false, false, FORM_LSTM>;
+        if (form == FORM_LSTM)
+            kern = walk ? (bwd ? k_walk<G, true, FORM_LSTM> : k_walk<G, false, FORM_LSTM>)
+                        : (bwd ? k_lookback<G, true, true, FORM_LSTM> : k_lookback<G, false, false, FORM_LSTM>);
     }
     if (!kern) return hipErrorInvalidValue;
+    if (walk) {  // one workgroup per column group
+        hipLaunchKernelGGL(kern, dim3((unsigned)A.G), block, 0, s, A);
+        return hipGetLastError();
+    }
     // persistent workgroups: as many as the device holds at once, never more than there are tiles
     const int64_t cap = resident_capacity(reinterpret_cast<const void *>(kern), G::THREADS, A.grid_cap);
     const dim3 pgrid((unsigned)(A.persistent ? std::min<int64_t>(A.K * A.G, cap) : A.K * A.G));

@@ -206,7 +206,12 @@ def test_plan_is_host_only_and_consistent(L):
         assert lr.linrec_plan(65536, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
         assert lr.linrec_plan(1024, 4, 256, backward=bwd)[0] == lr.VARIANT_LOOKBACK
         for fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16):
-            assert lr.linrec_plan_for(fam, 1024, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
+            v, t = lr.linrec_plan_for(fam, 128, 16, 1024, backward=bwd)            # every family walks here
+            info = lr.linrec_tile_info(t)
+            assert v == lr.VARIANT_WALK
+            assert info["cols_per_thread"] >= 2 if fam == lr.ENTRY_BF16 else info["cols_per_thread"] == 1
+            assert fam != lr.ENTRY_LSTM_CELL or info["rows_per_thread"] <= 32
+            assert lr.linrec_plan_for(fam, 16384, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
     with pytest.raises(lr.LinrecError):
         lr.linrec_plan_for(9, 10, 1, 1)
     # a tile whose rows would not fit 32-bit offsets falls back to the serial kernel

@@ -125,6 +125,53 @@ def test_tapered_tail_tiles_every_entry_point(taper):
         bf16_check(to_bf16(wl.make_generic(T, 1, 72, seed=34, device=DEV)), f"taper {taper} bf16")
 
 
+@pytest.mark.parametrize("family", ["gated", "lstm", "bf16"])
+def test_walk_variant_every_tile_shape(family):
+    """LINREC_VARIANT_WALK (one workgroup per column group goes through the sequence, no look-back) for the
+    gated layer, the cell and bf16 storage: every tile shape the family has, ragged rows and columns, several
+    tiles per column group, and the initial state."""
+    from test_bf16_parity_gpu import BF16_TILES, bf16_check, to_bf16
+    from test_gilr_parity_gpu import ONE_COLUMN_TILES, gated_check
+    from test_lstm_parity_gpu import CELL_TILES, cell_check
+
+    tiles = {"gated": ONE_COLUMN_TILES, "lstm": CELL_TILES, "bf16": BF16_TILES}[family]
+    for tile in tiles:
+        info = lr.linrec_tile_info(tile)
+        T = 2 * info["rows"] + 37                      # three tiles per column group, the last one ragged
+        C = 2 * info["cols"] + 4 * info["cols_per_thread"]
+        with options(variant=lr.VARIANT_WALK, tile=tile):
+            label = f"walk {family} tile {tile} T={T} C={C}"
+            say(label)
+            if family == "gated":
+                assert lr.linrec_plan_for(lr.ENTRY_GILR, T, 1, C) == (lr.VARIANT_WALK, tile)
+                gated_check(wl.make_gated(T, 1, C, seed=tile, device=DEV, gate_mean=1.0), lr.TAU_TANH, label)
+            elif family == "lstm":
+                assert lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, 1, C) == (lr.VARIANT_WALK, tile)
+                cell_check(wl.make_lstm(T, 1, C, seed=tile, device=DEV), label)
+            else:
+                assert lr.linrec_plan_for(lr.ENTRY_BF16, T, 1, C, alignment=8) == (lr.VARIANT_WALK, tile)
+                bf16_check(to_bf16(wl.make_generic(T, 1, C, seed=tile, device=DEV)), label)
+
+
+def test_short_wide_problems_walk_in_every_family():
+    """The automatic plan of the gated layer, the cell and bf16 storage on short, wide problems is the walk."""
+    from test_bf16_parity_gpu import bf16_check, to_bf16
+    from test_gilr_parity_gpu import gated_check
+    from test_lstm_parity_gpu import cell_check
+
+    for (T, B, n) in [(128, 16, 1024), (500, 4, 4100), (1000, 8, 4096)]:
+        if lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n)[0] == lr.VARIANT_WALK:
+            gated_check(wl.make_gated(T, B, n, seed=51, device=DEV, gate_mean=1.0), lr.TAU_TANH, f"auto walk gated {T}x{B}x{n}")
+    assert lr.linrec_plan_for(lr.ENTRY_GILR, 128, 16, 1024)[0] == lr.VARIANT_WALK
+    assert lr.linrec_plan_for(lr.ENTRY_GILR, 1000, 8, 4096, backward=False)[0] == lr.VARIANT_WALK
+    for (T, B, n) in [(64, 16, 1024), (250, 4, 1100)]:
+        assert lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n)[0] == lr.VARIANT_WALK
+        cell_check(wl.make_lstm(T, B, n, seed=52, device=DEV), f"auto walk lstm {T}x{B}x{n}")
+    for (T, B, n) in [(1000, 4, 3072), (2048, 8, 4096), (77, 2, 9000)]:
+        assert lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, alignment=8)[0] == lr.VARIANT_WALK
+        bf16_check(to_bf16(wl.make_generic(T, B, n, seed=53, device=DEV)), f"auto walk bf16 {T}x{B}x{n}")
+
+
 def test_staggered_start_changes_timing_only():
     """LINREC_OPT_STAGGER delays every other workgroup of the first round: bit-identical results for every
     entry point, whatever the delay, on a problem several rounds of workgroups long."""
