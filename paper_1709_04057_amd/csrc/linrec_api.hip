@@ -306,7 +306,7 @@ struct TunedKey {
     }
 };
 struct TunedPlan {
-    int tile, persistent;
+    int tile, persistent, variant;
 };
 std::mutex g_tuned_mu;
 std::map<TunedKey, TunedPlan> g_tuned;
@@ -327,8 +327,9 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
         if (hipGetDevice(&dev) == hipSuccess) {
             std::lock_guard<std::mutex> lock(g_tuned_mu);
             auto it = g_tuned.find(TunedKey{dev, T, C, bwd, family});
-            if (it != g_tuned.end()) {
+            if (it != g_tuned.end() && (it->second.variant == LINREC_VARIANT_LOOKBACK || opts().variant == LINREC_VARIANT_AUTO)) {
                 p.tile = it->second.tile;
+                p.variant = it->second.variant;
                 if (p.persistent < 0) p.persistent = it->second.persistent;
             }
         }
@@ -872,7 +873,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         }
     };
 
-    TunedPlan best{0, -1};
+    TunedPlan best{0, -1, LINREC_VARIANT_LOOKBACK};
     float best_ms = 0.f;
     if (rc == LINREC_OK) {
         const int vec = bf16 ? max_vec_bf16(C, {}) : entry_point == LINREC_ENTRY_PLAIN ? max_vec(C, {}) : 1;
@@ -908,8 +909,49 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
                 std::sort(times, times + 5);
                 if (best.tile == 0 || times[2] < best_ms) {
                     best_ms = times[2];
-                    best = TunedPlan{tile, persistent};
+                    best = TunedPlan{tile, persistent, LINREC_VARIANT_LOOKBACK};
                 }
+            }
+        }
+        // The walk, where there are enough columns for it to stand a chance: the shapes its automatic
+        // rule would take at this width.
+        int walk_c[3] = {0, 0, 0};
+        if (C >= 4096) {
+            if (entry_point == LINREC_ENTRY_PLAIN) {
+                walk_c[0] = auto_walk_tile(1, C, vec, bwd);
+            } else if (bf16) {
+                walk_c[0] = T >= 768 ? 30 : 24;
+                walk_c[1] = vec >= 4 ? 8 : 28;
+            } else {
+                walk_c[0] = 18;
+                walk_c[1] = 21;
+            }
+        }
+        opts().variant = LINREC_VARIANT_WALK;
+        opts().persistent = -1;
+        for (int i = 0; walk_c[i] && rc == LINREC_OK; ++i) {
+            const int tile = walk_c[i];
+            const TileDesc &d = kTiles[tile - 1];
+            if (d.vec > vec || ((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
+            opts().tile = tile;
+            float times[5];
+            for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {
+                if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
+                rc = call();
+                if (rc != LINREC_OK) break;
+                float ms = 0.f;
+                if ((e = hipEventRecord(ev1, s)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
+                    (e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess) {
+                    rc = hip_fail(e, "tune: timing");
+                    break;
+                }
+                if (it >= 0) times[it] = ms;
+            }
+            if (rc != LINREC_OK) break;
+            std::sort(times, times + 5);
+            if (best.tile == 0 || times[2] < best_ms) {
+                best_ms = times[2];
+                best = TunedPlan{tile, -1, LINREC_VARIANT_WALK};
             }
         }
         opts() = saved;

@@ -351,6 +351,16 @@ def test_tuned_plan_is_used_and_correct():
     fwd_bwd_check(inp, "tuned plan")
     with pytest.raises(lr.LinrecError):
         lr.linrec_tune(0, 2, 3)
+    # a short, wide shape: the walk is among the candidates, and whatever wins is used and is right
+    T, B, n = 700, 8, 1536
+    for bwd in (False, True):
+        lr.linrec_tune(T, B, n, backward=bwd)
+        v, t = lr.linrec_plan(T, B, n, backward=bwd)
+        say(f"tuned plan, short and wide, {'backward' if bwd else 'forward'}: variant {v} tile {t}")
+        assert v in (lr.VARIANT_WALK, lr.VARIANT_LOOKBACK) and lr.linrec_tile_info(t) is not None
+        with options(variant=lr.VARIANT_LOOKBACK):                      # an explicit variant is not overridden
+            assert lr.linrec_plan(T, B, n, backward=bwd)[0] == lr.VARIANT_LOOKBACK
+    fwd_bwd_check(wl.make_inputs(2, T=T, B=B, n=n, device=DEV), "tuned plan, short and wide")
 
 
 @pytest.mark.parametrize("cfg", [2, 3])
