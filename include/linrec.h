@@ -235,10 +235,11 @@ int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backwa
                     int alignment_bytes, int *variant, int *tile_id);
 
 /*
- * Optional: finds the fastest plan (tile shape, persistent workgroups or not) of the single-pass
- * kernel for a [T, B, n] forward (backward = 0) or backward (1) pass by timing the candidates on
- * `stream`, on scratch tensors it allocates and frees, and remembers it for later calls with this
- * shape on the current device (when LINREC_OPT_TILE / LINREC_OPT_PERSISTENT are automatic).
+ * Optional: finds the fastest plan (single-pass kernel: tile shape, persistent workgroups or not;
+ * for wide problems also the walk) for a [T, B, n] forward (backward = 0) or backward (1) pass by
+ * timing the candidates on `stream`, on scratch tensors it allocates and frees, and remembers it for
+ * later calls with this shape on the current device (when LINREC_OPT_TILE / LINREC_OPT_PERSISTENT
+ * are automatic; a remembered walk only while LINREC_OPT_VARIANT is automatic too).
  * Blocking; allocates 3 (forward) or 5 (backward) tensors of T*B*n floats.  Returns LINREC_OK,
  * LINREC_ERR_SHAPE or LINREC_ERR_HIP.  Must not run concurrently with other liblinrec calls.
  */
