@@ -57,7 +57,8 @@ enum {
 
 /* Which kernel family evaluates the scan (linrec_set_option(LINREC_OPT_VARIANT, ...)). */
 enum {
-    LINREC_VARIANT_AUTO = 0,       /* library picks (single pass where it applies)           */
+    LINREC_VARIANT_AUTO = 0,       /* library picks: the single pass, or the walk for short,
+                                      wide problems                                           */
     LINREC_VARIANT_THREEPHASE = 1, /* Algorithm 1 as three kernels: reduce, scan, rescan     */
     LINREC_VARIANT_LOOKBACK = 2,   /* one kernel; chunk carries found by decoupled look-back */
     LINREC_VARIANT_SERIAL = 3,     /* one thread per column walks T (the paper's baseline of
