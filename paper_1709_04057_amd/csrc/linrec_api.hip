@@ -249,7 +249,8 @@ int auto_tile_form(int64_t T, int64_t C, bool bwd, int form)
 int auto_walk_tile(int64_t T, int64_t C, int vec, bool bwd)
 {
     const bool walk = (T <= 512 && C >= 4096) || (T <= 1024 && C >= 8192) || (T <= 2048 && C >= 24576) ||
-                      (T <= 4096 && C >= 32768 && !bwd);
+                      (T <= 4096 && C >= 32768 && !bwd) ||
+                      (T <= 2048 && C > 7168 && C <= 8192);  // 225 .. 256 workgroups of 1024 x 32 tiles
     if (!walk) return 0;
     if (C <= 8192) return 22;                      // 32 columns x 1024 rows, 512 threads
     if (C <= 16384) return vec >= 2 ? 16 : 20;     // 64 columns
