@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-tune", action="store_true", help="skip linrec_tune(); use the library's static plan")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0)
+    ap.add_argument("--walk-grid", action="store_true",
+                    help="short, wide problems: the walk variant against the single pass, and what the plan takes")
     ap.add_argument("--table1", action="store_true",
                     help="instead of the workload benchmark, time the parallel (single-pass) kernel against the "
                          "serial-over-T kernel on the grid of the paper's Table 1 (minibatch 1; 4, 32, 128 features; "
@@ -148,6 +150,49 @@ def table1(lr, torch):
                                     "speedup": times["serial"] / times["parallel"],
                                     "parallel_events_per_s": T / (times["parallel"] * 1e-6)}
     lr.linrec_set_option(lr.OPT_VARIANT, lr.VARIANT_AUTO)
+    return grid
+
+
+def walk_grid(lr, torch, wl):
+    """Short, wide problems: the walk (one workgroup per column group, no look-back) against the single pass,
+    each with the shape the library picks for it; microseconds per launch, forward / backward, and what the
+    automatic plan takes.  Plain fp32 recurrence, workload 2's value distributions."""
+    dev = "cuda:0"
+    stream = torch.cuda.current_stream()
+    names = {lr.VARIANT_LOOKBACK: "lookback", lr.VARIANT_WALK: "walk"}
+    grid = {}
+    for T in (256, 512, 1024, 2048, 4096, 8192):
+        for C in (4096, 8192, 16384, 32768, 65536):
+            if T * C > 1 << 27:
+                continue
+            B, n = 4, C // 4
+            inp = wl.make_inputs(2, T=T, B=B, n=n, device=dev)
+            h = torch.empty_like(inp["x"])
+            gx, gl = torch.empty_like(h), torch.empty_like(h)
+            gh0 = torch.empty((B, n), device=dev)
+            fwd = lambda: lr.linrec_forward(inp["lam"], inp["x"], inp["h0"], h_out=h, stream=stream)
+            bwd = lambda: lr.linrec_backward(inp["lam"], h, inp["h0"], inp["grad_h"], grad_x=gx, grad_lambda=gl,
+                                             grad_h0=gh0, stream=stream)
+            rec = {"auto_plan": [names.get(lr.linrec_plan(T, B, n, backward=b)[0], "other") for b in (False, True)]}
+            for variant in (lr.VARIANT_LOOKBACK, lr.VARIANT_WALK):
+                lr.linrec_set_option(lr.OPT_VARIANT, variant)
+                us = []
+                for call in (fwd, bwd):
+                    for _ in range(3):
+                        call()
+                    torch.cuda.synchronize()
+                    ev = [torch.cuda.Event(enable_timing=True) for _ in range(11)]
+                    ev[0].record(stream)
+                    for i in range(10):
+                        call()
+                        ev[i + 1].record(stream)
+                    torch.cuda.synchronize()
+                    us.append(sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(10))[5] * 1e3)
+                rec[names[variant] + "_us"] = us
+                rec[names[variant] + "_tile"] = [lr.linrec_plan(T, B, n, backward=b)[1] for b in (False, True)]
+            lr.linrec_set_option(lr.OPT_VARIANT, lr.VARIANT_AUTO)
+            rec["walk_speedup"] = [rec["lookback_us"][i] / rec["walk_us"][i] for i in (0, 1)]
+            grid[f"T={T},C={C}"] = rec
     return grid
 
 
@@ -357,6 +402,10 @@ def main():
     lr.linrec_set_option(lr.OPT_VARIANT, variant)
     lr.linrec_set_option(lr.OPT_HPREV_LATE, args.hprev_late)
 
+    if args.walk_grid:
+        print(json.dumps({"metric": "walk vs single-pass kernel on short, wide problems (median microseconds per launch, "
+                                    "[forward, backward], HIP events)", "walk_grid": walk_grid(lr, torch, wl)}), flush=True)
+        return
     if args.table1:
         print(json.dumps({"metric": "parallel / serial linear-recurrence kernel throughput ratio (paper's Table 1 grid, "
                                     "minibatch 1, forward pass, launches back to back)",

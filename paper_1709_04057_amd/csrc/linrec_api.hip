@@ -246,17 +246,20 @@ int auto_tile_form(int64_t T, int64_t C, bool bwd, int form)
 // widest problems up to T = 4096; it loses as soon as the columns alone do not fill the GPU.  It
 // wants about one workgroup per compute unit (256) to a few, all resident at once, so the width of
 // the tile follows C.
+int walk_tile(int64_t T, int64_t C, int vec, bool bwd)  // (the shape, wherever the walk is asked for)
+{
+    if (C <= 8192) return T <= 256 ? 18 : T <= 512 ? (vec >= 2 ? 13 : 17) : 22;  // 32 columns; 256, 512 or 1024 rows
+    if (C <= 16384) return vec >= 2 ? 16 : 20;     // 64 columns
+    if (C <= 24576) return 18;                     // 32 columns, three or four workgroups per compute unit
+    if (C <= 32768 || vec < 4) return 21;          // 64 columns
+    return bwd ? 6 : 10;                           // 256 columns (16-byte accesses)
+}
 int auto_walk_tile(int64_t T, int64_t C, int vec, bool bwd)
 {
     const bool walk = (T <= 512 && C >= 4096) || (T <= 1024 && C >= 8192) || (T <= 2048 && C >= 24576) ||
                       (T <= 4096 && C >= 32768 && !bwd) ||
                       (T <= 2048 && C > 7168 && C <= 8192);  // 225 .. 256 workgroups of 1024 x 32 tiles
-    if (!walk) return 0;
-    if (C <= 8192) return 22;                      // 32 columns x 1024 rows, 512 threads
-    if (C <= 16384) return vec >= 2 ? 16 : 20;     // 64 columns
-    if (C <= 24576) return 18;                     // 32 columns, three or four workgroups per compute unit
-    if (C <= 32768 || vec < 4) return 21;          // 64 columns
-    return bwd ? 6 : 10;                           // 256 columns (16-byte accesses)
+    return walk ? walk_tile(T, C, vec, bwd) : 0;
 }
 
 // The same for the gated layer, the LSTM cell (both: one-column shapes) and bf16 storage (two or four
@@ -347,7 +350,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     // (the walk asked for by option without a shape: the plain recurrence gets the shape the walk would
     // take at this width; the other families their single-pass shape, below)
     if (p.variant == LINREC_VARIANT_WALK && p.tile == 0 && !gated && !bf16)
-        p.tile = auto_walk_tile(1, std::max<int64_t>(C, 4096), vec, bwd);
+        p.tile = walk_tile(T, C, vec, bwd);
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && kTiles[p.tile - 1].vec < 2) p.tile = 0;
@@ -919,7 +922,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         int walk_c[3] = {0, 0, 0};
         if (C >= 4096) {
             if (entry_point == LINREC_ENTRY_PLAIN) {
-                walk_c[0] = auto_walk_tile(1, C, vec, bwd);
+                walk_c[0] = walk_tile(T, C, vec, bwd);
             } else if (bf16) {
                 walk_c[0] = T >= 768 ? 30 : 24;
                 walk_c[1] = vec >= 4 ? 8 : 28;
