@@ -272,7 +272,7 @@ int auto_walk_tile_form(int64_t T, int64_t C, bool bwd, int form)
         const bool walk = (T <= 256 && C >= 8192) || (T <= 512 && C >= 16384) ||
                           (!bwd && ((T <= 512 && C >= 8192) || (T <= 1024 && C >= 16384)));
         if (!walk) return 0;
-        if (C <= 8192) return 17;
+        if (C <= 8192) return T <= 256 ? 18 : 17;
         if (C <= 16384) return bwd ? 18 : 20;
         if (C <= 24576) return 18;
         return T <= 256 ? 1 : 21;
