@@ -394,6 +394,9 @@ def main():
     import paper_1709_04057_amd as lr
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    if not os.path.exists(lr.lib_path()):   # load what is built; build only if nothing is
+        from paper_1709_04057_amd import build as _build
+        _build.build()
     lr.lib()
     dev = "cuda:0"
     torch.cuda.set_device(0)
