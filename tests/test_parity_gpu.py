@@ -100,6 +100,13 @@ def test_configs_full_size(cfg, variant):
         fwd_bwd_check(inp, f"cfg{cfg} full {variant}")
 
 
+def test_config4_full_size_walk():
+    """Workload 4 (the widest one) at full size through the walk, which the plan would not take at this length."""
+    inp = wl.make_inputs(4, device=DEV)
+    with options(variant=lr.VARIANT_WALK):
+        fwd_bwd_check(inp, "cfg4 full walk")
+
+
 @pytest.mark.parametrize("shape", [(1024, 16, 1024), (512, 8, 1024), (200, 3, 5000), (2048, 6, 4096), (64, 16, 4096)])
 def test_short_wide_shapes_take_the_walk(shape):
     """Automatic plan on short, wide problems: one workgroup per column group walks the sequence (no
