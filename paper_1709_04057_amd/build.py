@@ -1,15 +1,25 @@
 """Builds liblinrec.so (HIP, gfx950 only) next to this file.
 
 One hipcc invocation per translation unit, run in parallel: the tile kernels are compiled once per
-tile shape (-DLINREC_TILE_ID=n), then everything is linked into one shared library.
+tile shape (-DLINREC_TILE_ID=n), then everything is linked into one shared library.  Each HIP unit
+is compiled in a directory of its own with the intermediate files kept, so that the device assembly
+of exactly the code that is linked can be checked (see isa_check.py) before the rest is deleted.
 """
 from __future__ import annotations
 
+import glob
 import os
 import re
+import shutil
 import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
+
+try:
+    from . import isa_check
+except ImportError:  # run as a script
+    sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+    import isa_check
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -36,23 +46,41 @@ def _run(cmd):
     return out
 
 
+def _compile_hip(job):
+    """Compiles one HIP unit, checks its device assembly, keeps the object file only."""
+    src, extra, obj = job
+    work = os.path.join(OBJ_DIR, obj[:-2] + ".tmp")
+    shutil.rmtree(work, ignore_errors=True)
+    os.makedirs(work)
+    tmp_obj = os.path.join(work, obj)
+    out = _run([HIPCC] + FLAGS + extra + ["-save-temps=obj", "-c", os.path.join(CSRC, src), "-o", tmp_obj])
+    asm = glob.glob(os.path.join(work, "*-hip-amdgcn-amd-amdhsa-gfx950.s"))
+    if len(asm) != 1:
+        raise RuntimeError("%s: expected one device assembly file, found %r" % (obj, asm))
+    with open(asm[0]) as f:
+        problems = isa_check.check_text(f.read(), obj[:-2] + ".s")
+    if problems:
+        raise RuntimeError("store-data hazard in %s (%s):\n%s" % (obj, " ".join(extra), "\n".join(problems[:20])))
+    os.replace(tmp_obj, os.path.join(OBJ_DIR, obj))
+    shutil.rmtree(work, ignore_errors=True)
+    return out
+
+
+def _compile_host(job):
+    src, _, obj = job
+    return _run(["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", "-I" + os.path.join(ROOT, "include"),
+                 "-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ_DIR, obj)])
+
+
 def build(verbose: bool = False, jobs: int | None = None) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     units = [("linrec_api.hip", [], "api.o"), ("linrec_scan.hip", [], "scan.o"),
              ("linrec_validate.cpp", ["-x", "c++"], "validate.o")]
     for i in tile_ids():
         units.append(("linrec_tiles.hip", ["-DLINREC_TILE_ID=%d" % i], "tile_%d.o" % i))
-    cmds = []
-    for src, extra, obj in units:
-        if src.endswith(".cpp"):
-            cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-Wall", "-I" + os.path.join(ROOT, "include"),
-                   "-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ_DIR, obj)]
-        else:
-            cmd = [HIPCC] + FLAGS + extra + ["-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ_DIR, obj)]
-        cmds.append(cmd)
     jobs = jobs or min(8, os.cpu_count() or 4)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
-        for out in ex.map(_run, cmds):
+        for out in ex.map(lambda u: (_compile_host if u[0].endswith(".cpp") else _compile_hip)(u), units):
             if verbose and out.strip():
                 print(out)
     objs = [os.path.join(OBJ_DIR, o) for _, _, o in units]

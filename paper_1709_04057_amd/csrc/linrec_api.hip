@@ -212,12 +212,13 @@ int auto_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
     return T >= 256 ? 16 : 15;
 }
 
-// The same for the gated layer and the LSTM cell, which exist for the one-column shapes 1, 2 and
-// 17 .. 23 (the cell: 1, 2, 18, 21).  They compute a sigmoid and a tanh per element before a tile can
-// publish its summary: shapes with 32 or 48 rows per thread (more resident workgroups than the 64-row
-// shapes) hide that better, and 256-byte row segments pay from fewer columns on than in the plain
-// recurrence.
-int auto_tile_form(int64_t T, int64_t C, bool bwd, int form)
+// The same for the gated layer and the LSTM cell, which exist for the shapes whose rows per thread are
+// a multiple of 8 (or fewer than 8); the cell for those of at most 32 elements per thread and operand.
+// They compute a sigmoid and a tanh per element before a tile can publish its summary: shapes with 32
+// or 48 rows per thread (more resident workgroups than the 64-row shapes) hide that better, 256-byte
+// row segments pay from fewer columns on than in the plain recurrence, and the backward passes (four
+// and six operands per row) like few rows per thread with 16-byte accesses on wide problems.
+int auto_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
 {
     const int plain = auto_tile(T, C, 1, bwd, 0);
     if (C <= 16) return plain;
@@ -227,16 +228,25 @@ int auto_tile_form(int64_t T, int64_t C, bool bwd, int form)
     if (form == FORM_GATED) {
         if (!bwd) {
             if (T < 2048) return plain;
+            if (C >= 12288 && C < 24576 && vec >= 2) return 14;  // 8-byte accesses
             if (C >= 16384) return 21;
             if (one_round_22 && T >= 32768) return 22;
             if (E >= ((int64_t)1 << 24)) return 19;
             return C >= 2048 ? 20 : 17;
         }
-        if (T < 2048) return C >= 1024 ? 21 : plain;
-        if (one_round_22) return 22;
-        return C >= 2048 ? 21 : 18;
+        if (T < 1024) return C >= 1024 ? 21 : plain;
+        if (one_round_22 && T >= 2048) return 22;
+        // (the backward pass has four operands per row in flight: few rows per thread, wide accesses)
+        if (C >= 16384) return vec >= 4 ? 4 : 21;
+        if (C >= 2048) return vec >= 4 ? 3 : vec >= 2 ? 15 : 21;
+        return T < 2048 ? (C >= 1024 ? 21 : plain) : vec >= 2 ? 15 : 18;
     }
-    if (!bwd) return C >= 8192 ? 21 : T >= 256 ? 18 : plain;
+    if (!bwd) {
+        if (C >= 16384) return vec >= 4 ? (C >= 32768 ? 4 : 3) : 21;
+        if (C >= 2048 && T >= 1024 && T <= 4096 && vec >= 4) return 3;
+        return C >= 8192 ? 21 : T >= 256 ? 18 : plain;
+    }
+    if (C >= 16384 && T >= 2048 && vec >= 4) return 4;
     return C >= 2048 ? 21 : T >= 256 ? 18 : plain;
 }
 
@@ -352,13 +362,14 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     if (p.variant == LINREC_VARIANT_WALK && p.tile == 0 && !gated && !bf16)
         p.tile = walk_tile(T, C, vec, bwd);
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
-    if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 0;
+    if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 0;
+    if (p.tile >= 1 && p.tile <= NUM_TILES && gated && kTiles[p.tile - 1].r % 8 != 0 && kTiles[p.tile - 1].r >= 8) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && kTiles[p.tile - 1].vec < 2) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && !bf16 && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 64) p.tile = 0;
     if (p.tile < 1 || p.tile > NUM_TILES) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
-        if (gated) p.tile = auto_tile_form(T, C, bwd, form);
-        if (form == FORM_LSTM && kTiles[p.tile - 1].r > 32) p.tile = 18;  // (the cell has no 48- or 64-row kernels)
+        if (gated) p.tile = auto_tile_form(T, C, vec, bwd, form);
+        if (form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 18;  // (the cell: at most 32 elements per thread and operand)
         if (bf16) p.tile = auto_tile_bf16(T, C, vec, bwd);
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
@@ -378,7 +389,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
 int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf16 = false)
 {
     const bool gated = form != FORM_PLAIN;
-    Plan plan = make_plan(A.T, A.C, gated ? 1 : vec, bwd, form, bf16);
+    Plan plan = make_plan(A.T, A.C, vec, bwd, form, bf16);
     if ((gated || bf16) && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
@@ -598,7 +609,7 @@ extern "C" int linrec_gilr_forward(const float *g_pre, const float *i_pre, const
     A.tau = tau;
     A.T = T;
     A.C = C;
-    return run(A, false, 1, (hipStream_t)stream, FORM_GATED);
+    return run(A, false, max_vec(C, {g_pre, i_pre, h0, h_out}), (hipStream_t)stream, FORM_GATED);
 }
 
 extern "C" int linrec_gilr_backward(const float *g_pre, const float *i_pre, const float *h, const float *h0,
@@ -631,7 +642,7 @@ extern "C" int linrec_gilr_backward(const float *g_pre, const float *i_pre, cons
     A.tau = tau;
     A.T = T;
     A.C = C;
-    return run(A, true, 1, s, FORM_GATED);
+    return run(A, true, max_vec(C, {g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0}), s, FORM_GATED);
 }
 
 extern "C" int linrec_lstm_cell_forward(const float *f_pre, const float *i_pre, const float *z_pre, const float *o_pre,
@@ -653,7 +664,7 @@ extern "C" int linrec_lstm_cell_forward(const float *f_pre, const float *i_pre, 
     A.out1 = h_out;
     A.T = T;
     A.C = C;
-    return run(A, false, 1, (hipStream_t)stream, FORM_LSTM);
+    return run(A, false, max_vec(C, {f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out}), (hipStream_t)stream, FORM_LSTM);
 }
 
 extern "C" int linrec_lstm_cell_backward(const float *f_pre, const float *i_pre, const float *z_pre, const float *o_pre,
@@ -691,7 +702,8 @@ extern "C" int linrec_lstm_cell_backward(const float *f_pre, const float *i_pre,
     A.gh0 = grad_c0;
     A.T = T;
     A.C = C;
-    return run(A, true, 1, s, FORM_LSTM);
+    return run(A, true, max_vec(C, {f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre, grad_z_pre, grad_o_pre, grad_c0}), s,
+               FORM_LSTM);
 }
 
 extern "C" int linrec_set_option(int option, int64_t value)
@@ -786,7 +798,7 @@ extern "C" int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n,
     const void *al = (const void *)(uintptr_t)(alignment_bytes > 0 ? alignment_bytes : 2);
     const bool bf16 = entry_point == LINREC_ENTRY_BF16;
     const int form = entry_point == LINREC_ENTRY_GILR ? FORM_GATED : entry_point == LINREC_ENTRY_LSTM_CELL ? FORM_LSTM : FORM_PLAIN;
-    const int vec = bf16 ? max_vec_bf16(C, {al}) : form != FORM_PLAIN ? 1 : max_vec(C, {al});
+    const int vec = bf16 ? max_vec_bf16(C, {al}) : max_vec(C, {al});
     Plan p = make_plan(T, C, vec, backward != 0, form, bf16);
     if ((form != FORM_PLAIN || bf16) && p.variant == LINREC_VARIANT_THREEPHASE) p.variant = LINREC_VARIANT_LOOKBACK;
     if (variant) *variant = p.variant;
@@ -880,7 +892,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
     TunedPlan best{0, -1, LINREC_VARIANT_LOOKBACK};
     float best_ms = 0.f;
     if (rc == LINREC_OK) {
-        const int vec = bf16 ? max_vec_bf16(C, {}) : entry_point == LINREC_ENTRY_PLAIN ? max_vec(C, {}) : 1;
+        const int vec = bf16 ? max_vec_bf16(C, {}) : max_vec(C, {});
         const Options saved = opts();
         opts().variant = LINREC_VARIANT_LOOKBACK;
         static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0}, gated_c[] = {18, 19, 21, 17, 20, 22, 0},

@@ -274,6 +274,14 @@ __device__ __forceinline__ void gst(rsrc_t rs, uint32_t voff, uint32_t soff, vec
     constexpr int N = G::VEC;
     if constexpr (G::IO == IO_F32) {
         buf_st<N>(rs, voff, soff, v);
+        // A store of more than 64 bits still reads its data registers during the next two cycles.  The
+        // epilogues of the gated forms compute the next row right behind each store, in the registers
+        // the stored temporaries just left, and the compiler does not space the two apart for this
+        // form of the instruction (a register as scalar offset): some lanes then stored the next
+        // row's intermediate values.  Two idle cycles per store are not measurable.  (The statement
+        // names the stored registers as its operand, so nothing that overwrites them can be scheduled
+        // between the store and the pause.)
+        if constexpr (N == 4) asm volatile("s_nop 1" : "+v"(v));
     } else if constexpr (N == 4) {
         const u32x2 w = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
         __builtin_amdgcn_raw_buffer_store_b64(w, rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);

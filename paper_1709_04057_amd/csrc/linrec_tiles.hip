@@ -43,10 +43,11 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
     //   bf16 storage       the plain recurrence's look-back kernels of the shapes with 2 or 4 columns per
     //                      thread (4- and 8-byte accesses); two elements share a register, so these go up
     //                      to 128 elements per thread
-    //   gated layer        look-back kernels of one-column-per-thread shapes
-    //   LSTM cell          the same, of at most 32 rows per thread (three operands per row in flight)
+    //   gated layer        look-back and walk kernels of the shapes with 8k (or fewer than 8) rows per thread
+    //                      (the epilogues work in chunks of 8 rows)
+    //   LSTM cell          the same, of at most 32 elements per thread and operand (three operands in flight)
     constexpr bool kHasF32 = G::R * G::VEC <= 64, kHasBf16 = G::VEC >= 2;
-    constexpr bool kHasGated = kHasF32 && G::VEC == 1, kHasLstm = kHasGated && G::R <= 32;
+    constexpr bool kHasGated = kHasF32 && (G::R % 8 == 0 || G::R < 8), kHasLstm = kHasGated && G::R * G::VEC <= 32;
     if (form < FORM_PLAIN || form > FORM_LSTM) return hipErrorInvalidValue;
     if ((form != FORM_PLAIN || bf16) && kind != KIND_LOOKBACK && kind != KIND_WALK) return hipErrorInvalidValue;
     if (bf16 ? (!kHasBf16 || form != FORM_PLAIN) : !kHasF32) return hipErrorInvalidValue;

@@ -1,0 +1,128 @@
+"""Checks the compiled kernels for one hazard of the vector memory unit.
+
+A buffer or global store of more than 64 bits reads its data registers over several cycles.  A vector
+ALU instruction that follows within two wait states and writes one of those registers can change what
+is stored.  The compiler spaces such pairs apart, except for buffer stores whose scalar offset is a
+register -- it takes that form to be safe, and on gfx950 it is not: the look-back kernels of the LSTM
+cell stored the next row's intermediate values in some lanes when it happened.  The kernels therefore
+end every wide store with an `s_nop`, and this check reads the assembly of every kernel the build
+produces and fails the build if a pair is closer than that anywhere.
+
+    python -m paper_1709_04057_amd.isa_check file.s ...
+"""
+from __future__ import annotations
+
+import re
+import sys
+
+WAIT_STATES = 2
+
+_STORE = re.compile(r"^\s*(buffer_store_dwordx[34]|buffer_store_format_xyzw?|global_store_dwordx[34]|"
+                    r"flat_store_dwordx[34]|scratch_store_dwordx[34])\s+(.*)$")
+_LABEL = re.compile(r"^([.\w$]+):")
+_REG = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
+
+
+def _regs(text):
+    out = set()
+    for m in _REG.finditer(text):
+        if m.group(1) is not None:
+            out.add(int(m.group(1)))
+        else:
+            out.update(range(int(m.group(2)), int(m.group(3)) + 1))
+    return out
+
+
+def _store_data(mnemonic, operands):
+    ops = [o.strip() for o in operands.split(",")]
+    # buffer stores: vdata first; global/flat/scratch stores: address first, data second
+    data = ops[0] if mnemonic.startswith("buffer") else ops[1]
+    return _regs(data)
+
+
+def _valu_dest(line):
+    """Vector registers a vector ALU instruction writes (empty for everything else)."""
+    m = re.match(r"^\s*(v_\w+)\s+([^,]+)", line)
+    if not m:
+        return set()
+    name = m.group(1)
+    if name.startswith(("v_cmp", "v_readlane", "v_readfirstlane", "v_nop")):
+        return set()
+    dest = _regs(m.group(2))
+    if name.startswith(("v_swap", "v_permlane16_swap", "v_permlane32_swap")):
+        rest = line.split(",")
+        if len(rest) > 1:
+            dest |= _regs(rest[1])
+    return dest
+
+
+def _instructions(lines):
+    """(index, text) of every instruction line, and label -> index of the instruction that follows it."""
+    instr, labels, pending = [], {}, []
+    for n, raw in enumerate(lines):
+        line = raw.split(";")[0].rstrip()
+        if not line.strip():
+            continue
+        m = _LABEL.match(line)
+        if m:
+            pending.append(m.group(1))
+            continue
+        if line.lstrip().startswith("."):
+            continue
+        for l in pending:
+            labels[l] = len(instr)
+        pending = []
+        instr.append((n + 1, line.strip()))
+    return instr, labels
+
+
+def check_text(text, name="<asm>"):
+    """Returns a list of messages, one per store whose data registers are written too early."""
+    lines = text.splitlines()
+    instr, labels = _instructions(lines)
+    problems = []
+
+    def walk(start, left, data, where, seen):
+        i = start
+        while left > 0 and i < len(instr):
+            if (i, left) in seen:
+                return
+            seen.add((i, left))
+            n, line = instr[i]
+            hit = _valu_dest(line) & data
+            if hit:
+                problems.append("%s:%d: `%s` writes v%s, data of the store at line %d, %d wait state(s) after it"
+                                % (name, n, line, sorted(hit), where, WAIT_STATES - left))
+                return
+            m = re.match(r"^s_nop\s+(\d+)", line)
+            left -= (int(m.group(1)) + 1) if m else 1
+            if line.startswith("s_endpgm"):
+                return
+            b = re.match(r"^s_c?branch\w*\s+([.\w$]+)", line)
+            if b and b.group(1) in labels and left > 0:
+                walk(labels[b.group(1)], left, data, where, seen)
+            if line.startswith("s_branch"):
+                return
+            i += 1
+
+    for i, (n, line) in enumerate(instr):
+        m = _STORE.match(line)
+        if m:
+            walk(i + 1, WAIT_STATES, _store_data(m.group(1), m.group(2)), n, set())
+    return problems
+
+
+def check_files(paths):
+    problems = []
+    for p in paths:
+        with open(p) as f:
+            problems += check_text(f.read(), p)
+    return problems
+
+
+if __name__ == "__main__":
+    found = check_files(sys.argv[1:])
+    for msg in found:
+        print(msg)
+    print("%d file(s), %d hazard(s)" % (len(sys.argv) - 1, len(found)))
+    sys.exit(1 if found else 0)

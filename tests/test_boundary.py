@@ -188,10 +188,12 @@ def test_plan_is_host_only_and_consistent(L):
     for (T, B, n) in [(65536, 4, 256), (4096, 16, 1024), (300, 1, 7), (5000, 2, 33)]:
         for bwd in (False, True):
             v, t = lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n, backward=bwd)
-            assert v in (lr.VARIANT_LOOKBACK, lr.VARIANT_SERIAL) and lr.linrec_tile_info(t)["cols_per_thread"] == 1
+            info = lr.linrec_tile_info(t)
+            assert v in (lr.VARIANT_LOOKBACK, lr.VARIANT_SERIAL) and (B * n) % info["cols_per_thread"] == 0
+            assert info["rows_per_thread"] % 8 == 0 or info["rows_per_thread"] < 8
             v, t = lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=bwd)
             info = lr.linrec_tile_info(t)
-            assert info["cols_per_thread"] == 1 and info["rows_per_thread"] <= 32
+            assert (B * n) % info["cols_per_thread"] == 0 and info["rows_per_thread"] * info["cols_per_thread"] <= 32
             v, t = lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, backward=bwd, alignment=4)
             if (B * n) % 2:
                 assert v == lr.VARIANT_SERIAL            # odd number of columns: no 4-byte rows
@@ -209,8 +211,8 @@ def test_plan_is_host_only_and_consistent(L):
             v, t = lr.linrec_plan_for(fam, 128, 16, 1024, backward=bwd)            # every family walks here
             info = lr.linrec_tile_info(t)
             assert v == lr.VARIANT_WALK
-            assert info["cols_per_thread"] >= 2 if fam == lr.ENTRY_BF16 else info["cols_per_thread"] == 1
-            assert fam != lr.ENTRY_LSTM_CELL or info["rows_per_thread"] <= 32
+            assert info["cols_per_thread"] >= 2 or fam != lr.ENTRY_BF16
+            assert fam != lr.ENTRY_LSTM_CELL or info["rows_per_thread"] * info["cols_per_thread"] <= 32
             assert lr.linrec_plan_for(fam, 16384, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
     with pytest.raises(lr.LinrecError):
         lr.linrec_plan_for(9, 10, 1, 1)

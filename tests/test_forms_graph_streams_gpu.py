@@ -131,10 +131,10 @@ def test_walk_variant_every_tile_shape(family):
     gated layer, the cell and bf16 storage: every tile shape the family has, ragged rows and columns, several
     tiles per column group, and the initial state."""
     from test_bf16_parity_gpu import BF16_TILES, bf16_check, to_bf16
-    from test_gilr_parity_gpu import ONE_COLUMN_TILES, gated_check
+    from test_gilr_parity_gpu import GATED_TILES, gated_check
     from test_lstm_parity_gpu import CELL_TILES, cell_check
 
-    tiles = {"gated": ONE_COLUMN_TILES, "lstm": CELL_TILES, "bf16": BF16_TILES}[family]
+    tiles = {"gated": GATED_TILES, "lstm": CELL_TILES, "bf16": BF16_TILES}[family]
     for tile in tiles:
         info = lr.linrec_tile_info(tile)
         T = 2 * info["rows"] + 37                      # three tiles per column group, the last one ragged

@@ -1,0 +1,43 @@
+"""The build's check of the device assembly: a wide store must not be followed, within two wait
+states, by a vector ALU write to the registers it stores."""
+from paper_1709_04057_amd import isa_check
+
+STORE = "\tbuffer_store_dwordx4 v[58:61], v198, s[76:79], s4 offen nt\n"
+
+
+def test_overwrite_right_behind_the_store_is_found():
+    asm = STORE + "\tv_mul_f32_e32 v59, 0x4038aa3b, v180\n\ts_endpgm\n"
+    found = isa_check.check_text(asm)
+    assert len(found) == 1 and "v[59]" in found[0]
+
+
+def test_second_wait_state_counts_too():
+    asm = STORE + "\ts_mul_i32 s4, s4, s15\n\tv_exp_f32_e32 v61, v3\n\ts_endpgm\n"
+    assert len(isa_check.check_text(asm)) == 1
+    asm = STORE + "\ts_mul_i32 s4, s4, s15\n\ts_add_i32 s4, s4, 1\n\tv_exp_f32_e32 v61, v3\n\ts_endpgm\n"
+    assert isa_check.check_text(asm) == []
+
+
+def test_pause_or_unrelated_registers_are_fine():
+    assert isa_check.check_text(STORE + "\ts_nop 1\n\tv_mul_f32_e32 v59, 2.0, v59\n\ts_endpgm\n") == []
+    assert isa_check.check_text(STORE + "\ts_nop 0\n\tv_mul_f32_e32 v59, 2.0, v59\n\ts_endpgm\n") != []
+    assert isa_check.check_text(STORE + "\tv_mul_f32_e32 v62, 2.0, v59\n\tv_mov_b32_e32 v57, v58\n\ts_endpgm\n") == []
+    # a compare writes a mask, a load's data arrives much later, a narrow store has read its data
+    assert isa_check.check_text(STORE + "\tv_cmp_lt_f32_e32 vcc, v59, v60\n\ts_endpgm\n") == []
+    assert isa_check.check_text(STORE + "\tbuffer_load_dwordx4 v[58:61], v198, s[76:79], s4 offen\n\ts_endpgm\n") == []
+    narrow = "\tbuffer_store_dwordx2 v[58:59], v198, s[76:79], s4 offen nt\n"
+    assert isa_check.check_text(narrow + "\tv_mul_f32_e32 v59, 2.0, v59\n\ts_endpgm\n") == []
+
+
+def test_labels_fall_through_and_branches_are_followed():
+    asm = STORE + ".LBB0_1:\n\tv_mov_b64_e32 v[60:61], v[2:3]\n\ts_endpgm\n"
+    assert len(isa_check.check_text(asm)) == 1
+    asm = (STORE + "\ts_cbranch_vccnz .LBB0_7\n\ts_nop 3\n\ts_endpgm\n"
+           ".LBB0_7:\n\tv_add_f32_e32 v58, 1.0, v58\n\ts_endpgm\n")
+    assert len(isa_check.check_text(asm)) == 1
+
+
+def test_global_store_names_its_data_second():
+    asm = "\tglobal_store_dwordx4 v[12:13], v[26:29], off nt\n\tv_mov_b32_e32 v12, 0\n\tv_mov_b32_e32 v27, 0\n\ts_endpgm\n"
+    found = isa_check.check_text(asm)
+    assert len(found) == 1 and "v[27]" in found[0]
