@@ -13,6 +13,7 @@
 #include <map>
 #include <mutex>
 #include <utility>
+#include <vector>
 
 namespace linrec {
 
@@ -272,8 +273,8 @@ int auto_walk_tile(int64_t T, int64_t C, int vec, bool bwd)
     return walk ? walk_tile(T, C, vec, bwd) : 0;
 }
 
-// The same for the gated layer, the LSTM cell (both: one-column shapes) and bf16 storage (two or four
-// columns per thread).  Their tiles take longer (activations; half the bytes per element), so the
+// The same for the gated layer, the LSTM cell (both: one-column shapes were swept) and bf16 storage (two
+// or four columns per thread).  Their tiles take longer (activations; half the bytes per element), so the
 // region where the walk wins is smaller: up to T = 256 for the cell, 512 .. 1024 for the gated layer,
 // 1024 .. 2048 with bf16 storage, by 1.1-2x.
 int auto_walk_tile_form(int64_t T, int64_t C, bool bwd, int form)
@@ -384,8 +385,9 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     return p;
 }
 
-// gated: the form of Section 3.1 (activations applied in the kernel); it exists as the single-pass
-// kernel of the one-column-per-thread tile shapes and as the serial kernel.
+// gated: the form of Section 3.1 (activations applied in the kernel); it exists as the single-pass and
+// walk kernels of the tile shapes with a multiple of 8 (or fewer than 8) rows per thread, and as the
+// serial kernel.
 int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf16 = false)
 {
     const bool gated = form != FORM_PLAIN;
@@ -895,12 +897,21 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         const int vec = bf16 ? max_vec_bf16(C, {}) : max_vec(C, {});
         const Options saved = opts();
         opts().variant = LINREC_VARIANT_LOOKBACK;
-        static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0}, gated_c[] = {18, 19, 21, 17, 20, 22, 0},
-                         lstm_c[] = {18, 21, 0}, bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 0};
-        const int *candidates = entry_point == LINREC_ENTRY_GILR ? gated_c : entry_point == LINREC_ENTRY_LSTM_CELL ? lstm_c
-                                                                 : bf16 ? bf16_c : plain_c;
-        for (; *candidates; ++candidates) {
-            const int tile = *candidates;
+        static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0},
+                         gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 0},
+                         bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 0};
+        const int *list = entry_point == LINREC_ENTRY_GILR ? gated_c : entry_point == LINREC_ENTRY_LSTM_CELL ? lstm_c
+                                                           : bf16 ? bf16_c : plain_c;
+        // the static rule's own choice goes first, so that what is remembered is never slower than it
+        const int form = entry_point == LINREC_ENTRY_GILR ? FORM_GATED : entry_point == LINREC_ENTRY_LSTM_CELL ? FORM_LSTM
+                                                                                                             : FORM_PLAIN;
+        std::vector<int> candidates{form != FORM_PLAIN ? auto_tile_form(T, C, vec, bwd, form)
+                                    : bf16            ? auto_tile_bf16(T, C, vec, bwd)
+                                                      : auto_tile(T, C, vec, bwd, LINREC_VARIANT_LOOKBACK)};
+        for (; *list; ++list)
+            if (*list != candidates[0]) candidates.push_back(*list);
+        for (const int tile : candidates) {
+            if (tile < 1 || tile > NUM_TILES) continue;
             const TileDesc &d = kTiles[tile - 1];
             if (d.vec > vec) continue;
             if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;

@@ -107,9 +107,9 @@ const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
 
 // Launches kernel `kind` for tile shape `id` with grid A.K * A.G.  hp_late (look-back, backward):
 // load h after the rescan instead of together with lambda and grad_h.  gated: the form of Section
-// 3.1 with sigmoid / tau applied in the kernel (look-back kernels of one-column-per-thread shapes
-// only; hipErrorInvalidValue otherwise).  `form` is FORM_PLAIN, FORM_GATED or FORM_LSTM (the latter
-// for shapes of at most 32 rows per thread).  bf16: the tensors hold bf16 (plain form, look-back kernels
+// 3.1 with sigmoid / tau applied in the kernel (look-back and walk kernels of the shapes whose rows per
+// thread are a multiple of 8, or fewer than 8; hipErrorInvalidValue otherwise).  `form` is FORM_PLAIN,
+// FORM_GATED or FORM_LSTM (the latter for shapes of at most 32 elements per thread and operand).  bf16: the tensors hold bf16 (plain form, look-back kernels
 // of shapes with 2 or 4 columns per thread).
 hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A,
                               hipStream_t s);
