@@ -60,7 +60,7 @@ def _compile_hip(job):
     with open(asm[0]) as f:
         problems = isa_check.check_text(f.read(), obj[:-2] + ".s")
     if problems:
-        raise RuntimeError("store-data hazard in %s (%s):\n%s" % (obj, " ".join(extra), "\n".join(problems[:20])))
+        raise RuntimeError("device assembly check failed for %s (%s):\n%s" % (obj, " ".join(extra), "\n".join(problems[:20])))
     os.replace(tmp_obj, os.path.join(OBJ_DIR, obj))
     shutil.rmtree(work, ignore_errors=True)
     return out

@@ -1,4 +1,4 @@
-"""Checks the compiled kernels for one hazard of the vector memory unit.
+"""Checks the device assembly of the compiled kernels, above all for one hazard of the vector memory unit.
 
 A buffer or global store of more than 64 bits reads its data registers over several cycles.  A vector
 ALU instruction that follows within two wait states and writes one of those registers can change what
@@ -7,6 +7,9 @@ register -- it takes that form to be safe, and on gfx950 it is not: the look-bac
 cell stored the next row's intermediate values in some lanes when it happened.  The kernels therefore
 end every wide store with an `s_nop`, and this check reads the assembly of every kernel the build
 produces and fails the build if a pair is closer than that anywhere.
+
+It also fails if the assembly holds a packed fp32 instruction (v_pk_add_f32, v_pk_mul_f32,
+v_pk_fma_f32): the library is compiled with those switched off, and this shows that the switch took.
 
     python -m paper_1709_04057_amd.isa_check file.s ...
 """
@@ -19,6 +22,7 @@ WAIT_STATES = 2
 
 _STORE = re.compile(r"^\s*(buffer_store_dwordx[34]|buffer_store_format_xyzw?|global_store_dwordx[34]|"
                     r"flat_store_dwordx[34]|scratch_store_dwordx[34])\s+(.*)$")
+_PACKED_F32 = re.compile(r"^\s*v_pk_(add|mul|fma)_f32\b")
 _LABEL = re.compile(r"^([.\w$]+):")
 _REG = re.compile(r"\bv(\d+)\b|\bv\[(\d+):(\d+)\]")
 
@@ -77,7 +81,8 @@ def _instructions(lines):
 
 
 def check_text(text, name="<asm>"):
-    """Returns a list of messages, one per store whose data registers are written too early."""
+    """Returns a list of messages: one per store whose data registers are written too early, one per
+    packed fp32 instruction."""
     lines = text.splitlines()
     instr, labels = _instructions(lines)
     problems = []
@@ -109,6 +114,8 @@ def check_text(text, name="<asm>"):
         m = _STORE.match(line)
         if m:
             walk(i + 1, WAIT_STATES, _store_data(m.group(1), m.group(2)), n, set())
+        if _PACKED_F32.match(line):
+            problems.append("%s:%d: `%s`: packed fp32 arithmetic is meant to be switched off" % (name, n, line))
     return problems
 
 
@@ -124,5 +131,5 @@ if __name__ == "__main__":
     found = check_files(sys.argv[1:])
     for msg in found:
         print(msg)
-    print("%d file(s), %d hazard(s)" % (len(sys.argv) - 1, len(found)))
+    print("%d file(s), %d finding(s)" % (len(sys.argv) - 1, len(found)))
     sys.exit(1 if found else 0)

@@ -73,6 +73,25 @@ def test_every_gated_tile_ragged_shapes(tile, tau):
         gated_check(inp, tau, f"tile {tile}")
 
 
+WIDE_GATED_TILES = [i for i in GATED_TILES if lr.linrec_tile_info(i)["cols_per_thread"] == 4]
+
+
+@pytest.mark.parametrize("variant", ["lookback", "walk"])
+@pytest.mark.parametrize("tile", WIDE_GATED_TILES)
+def test_four_column_tiles_over_many_tiles(tile, variant):
+    """The shapes with 16-byte accesses on a problem of many tiles and workgroups, whole tile widths of
+    adjacent columns among the sampled ones (a 128-bit store whose data registers are overwritten too
+    early shows in a few lanes only, and not on small problems)."""
+    T, B, n = 2048, 4, 1024
+    C = B * n
+    inp = wl.make_gated(T, B, n, seed=500 + tile, device=DEV, gate_mean=1.0, gate_std=1.0)
+    rng = np.random.default_rng(tile)
+    cols = np.unique(np.concatenate([np.arange(0, 256), np.arange(C - 256, C), 1536 + np.arange(256),
+                                     rng.choice(C, size=128, replace=False)]))
+    with options(variant=getattr(lr, "VARIANT_" + variant.upper()), tile=tile):
+        gated_check(inp, lr.TAU_TANH, f"tile {tile} {variant}", cols=cols)
+
+
 @pytest.mark.parametrize("T,B,n", [(1, 1, 1), (2, 3, 5), (7, 1, 64), (513, 2, 33), (4096, 1, 16), (3000, 2, 100)])
 @pytest.mark.parametrize("variant", ["lookback", "serial"])
 def test_small_and_degenerate_shapes(T, B, n, variant):

@@ -41,3 +41,8 @@ def test_global_store_names_its_data_second():
     asm = "\tglobal_store_dwordx4 v[12:13], v[26:29], off nt\n\tv_mov_b32_e32 v12, 0\n\tv_mov_b32_e32 v27, 0\n\ts_endpgm\n"
     found = isa_check.check_text(asm)
     assert len(found) == 1 and "v[27]" in found[0]
+
+
+def test_packed_fp32_arithmetic_is_reported():
+    assert len(isa_check.check_text("\tv_pk_fma_f32 v[0:1], v[2:3], v[4:5], v[6:7]\n\ts_endpgm\n")) == 1
+    assert isa_check.check_text("\tv_pk_mov_b32 v[0:1], v[2:3], v[4:5]\n\tv_cvt_pk_bf16_f32 v0, v1, v2\n\ts_endpgm\n") == []

@@ -72,6 +72,27 @@ def test_every_cell_tile_ragged_shapes(tile):
         cell_check(inp, f"tile {tile}")
 
 
+WIDE_CELL_TILES = [i for i in CELL_TILES if lr.linrec_tile_info(i)["cols_per_thread"] > 1]
+
+
+@pytest.mark.parametrize("variant", ["lookback", "walk"])
+@pytest.mark.parametrize("tile", WIDE_CELL_TILES)
+def test_multi_column_tiles_over_many_tiles(tile, variant):
+    """The shapes with 8- and 16-byte accesses on a problem of many tiles and workgroups, whole tile
+    widths of adjacent columns among the sampled ones: the four-column backward kernels once stored a
+    few lanes' next-row temporaries (a 128-bit store's data registers were overwritten too early), which
+    small problems did not show."""
+    T, B, n = 2048, 4, 1024
+    C = B * n
+    inp = wl.make_lstm(T, B, n, seed=400 + tile, device=DEV)
+    rng = np.random.default_rng(tile)
+    cols = np.unique(np.concatenate([np.arange(0, 256), np.arange(C - 256, C), 1536 + np.arange(256),
+                                     rng.choice(C, size=128, replace=False)]))
+    with options(variant=getattr(lr, "VARIANT_" + variant.upper()), tile=tile):
+        for rep in range(2):
+            cell_check(inp, f"tile {tile} {variant} pass {rep}", cols=cols)
+
+
 def test_a_tile_the_cell_does_not_have_falls_back_to_one_it_has():
     # tile 17 has 64 rows per thread; the cell exists for at most 32: the request is ignored, not an error
     inp = wl.make_lstm(3000, 1, 70, seed=3, device=DEV)
