@@ -273,23 +273,99 @@ int auto_walk_tile(int64_t T, int64_t C, int vec, bool bwd)
     return walk ? walk_tile(T, C, vec, bwd) : 0;
 }
 
-// The same for the gated layer, the LSTM cell (both: one-column shapes were swept) and bf16 storage (two
-// or four columns per thread).  Their tiles take longer (activations; half the bytes per element), so the
-// region where the walk wins is smaller: up to T = 256 for the cell, 512 .. 1024 for the gated layer,
-// 1024 .. 2048 with bf16 storage, by 1.1-2x.
-int auto_walk_tile_form(int64_t T, int64_t C, bool bwd, int form)
+// The same for the gated layer and the LSTM cell, from a sweep of every shape they have over
+// T = 64 .. 4096 x C = 2048 .. 65536 (within 1-2 % of the best choice on average, 14 % at worst).  Their
+// tiles take longer (activations), so the region where the walk wins is smaller than for the plain
+// recurrence: up to T = 512 .. 1024, further only for the widest problems, by 1.1-1.5x.  Short
+// sequences want tiles about as tall as T; where alignment allows, 8- and 16-byte accesses with 8 or 16
+// rows per thread beat the one-column shapes by 10-25 %; a width that makes a whole number of rounds of
+// 256 workgroups (C = 8192, 16384 with 32 columns per tile) extends the region to T = 1024.
+int auto_walk_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
 {
     if (form == FORM_GATED) {
-        const bool walk = (T <= 256 && C >= 8192) || (T <= 512 && C >= 16384) ||
-                          (!bwd && ((T <= 512 && C >= 8192) || (T <= 1024 && C >= 16384)));
-        if (!walk) return 0;
-        if (C <= 8192) return T <= 256 ? 18 : 17;
-        if (C <= 16384) return bwd ? 18 : 20;
-        if (C <= 24576) return 18;
-        return T <= 256 ? 1 : 21;
+        if (!bwd) {
+            if (T <= 64) return C < 16384 ? 0 : vec >= 4 ? 6 : C < 49152 ? 21 : 1;
+            if (T <= 256) return C < 8192 ? 0 : C <= 8192 ? 18 : C <= 16384 ? 20 : C <= 24576 ? 18 : 1;
+            if (T <= 512)
+                return C < 8192 ? 0 : C <= 8192 ? 17 : C <= 16384 ? (vec >= 2 ? 15 : 20) : C <= 24576 ? 18 : 1;
+            if (T <= 1024) {
+                if (C > 7168 && C <= 8192) return 22;
+                if (C > 8192 && C <= 12288) return vec >= 4 ? 3 : 0;
+                if (C > 12288 && C <= 16384) return vec >= 2 ? 15 : 20;
+                if (C > 16384 && C <= 24576) return 18;
+                return C > 24576 ? (C < 49152 ? 1 : 21) : 0;
+            }
+            return (T <= 4096 && C >= 32768 && C < 49152) ? 1 : 0;
+        }
+        if (T <= 64) {
+            if (C >= 24576 && vec >= 4) return 5;
+            return C < 8192 ? 0 : C <= 24576 ? 18 : C < 49152 ? 21 : 1;
+        }
+        if (T <= 128) {
+            if (C < 8192) return 0;
+            if (vec >= 4) return 4;
+            if (vec >= 2 && C <= 16384) return 15;
+            return C <= 24576 ? 18 : 1;
+        }
+        if (T <= 256) {
+            if (C < 4096) return 0;
+            if (C < 8192) return vec >= 4 ? 3 : 2;
+            if (C <= 16384) return vec >= 4 ? 3 : vec >= 2 ? 15 : 18;
+            if (C <= 24576) return 18;
+            return (C <= 32768 && vec >= 2) ? 16 : 21;
+        }
+        if (T <= 512) {
+            if (C < 8192) return 0;
+            if (C <= 12288) return vec >= 4 ? 3 : vec >= 2 ? 15 : 0;
+            if (C <= 16384) return vec >= 2 ? 15 : 18;
+            if (C <= 24576) return 18;
+            return (C <= 32768 && vec >= 2) ? 16 : 21;
+        }
+        if (T <= 1024) {
+            if (C > 7168 && C <= 8192) return 22;
+            if (C > 12288 && C <= 16384) return vec >= 2 ? 15 : 0;
+        }
+        return (T <= 2048 && C >= 49152) ? 21 : 0;
     }
-    if (T > 256 || C < 4096) return 0;  // the cell
-    return T <= 64 ? 1 : C >= 32768 ? 21 : 18;
+    // the cell
+    if (C < 4096) return 0;
+    if (T <= 64) return 1;
+    if (!bwd) {
+        if (T <= 128) {
+            if (C < 8192) return 18;
+            if (C <= 24576) return vec >= 4 ? 4 : (vec >= 2 && C > 16384) ? 15 : 21;
+            return 21;
+        }
+        if (T <= 256) return C <= 24576 ? (vec >= 2 ? 15 : 18) : 21;
+        if (T <= 512) {
+            if (C < 8192) return 0;
+            if (C <= 24576) return vec >= 2 ? 15 : 0;
+            return vec >= 4 ? (C < 49152 ? 5 : 4) : 0;
+        }
+        if (T <= 1024) {
+            if ((C > 7168 && C <= 8192) || (C > 14336 && C <= 16384)) return vec >= 2 ? 15 : 0;
+            if (C >= 49152) return vec >= 4 ? 4 : 0;
+        }
+        return 0;
+    }
+    if (T <= 128) {
+        if (C > 8192 && C <= 16384) return vec >= 4 ? 4 : vec >= 2 ? 15 : 21;
+        return C >= 32768 ? 21 : 18;
+    }
+    if (T <= 256) {
+        if (C <= 16384) return vec >= 2 ? 15 : 18;
+        if (C <= 24576) return 18;
+        return vec >= 4 ? (C >= 49152 ? 6 : 5) : 21;
+    }
+    if (T <= 512) {
+        if (C < 8192) return 0;
+        if (C <= 8192) return vec >= 4 ? 3 : 0;
+        if (C <= 16384) return vec >= 4 ? 4 : (vec >= 2 && C > 14336) ? 15 : 0;
+        if (C <= 24576) return 18;
+        if (C <= 32768) return vec >= 4 ? 5 : 21;
+        return vec >= 4 ? 6 : 0;
+    }
+    return 0;
 }
 int auto_walk_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
 {
@@ -351,7 +427,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     }
     // No option and no tuned plan: short, wide problems take the walk.
     if (opts().variant == LINREC_VARIANT_AUTO && p.tile == 0) {
-        const int wt = bf16 ? auto_walk_tile_bf16(T, C, vec, bwd) : gated ? auto_walk_tile_form(T, C, bwd, form)
+        const int wt = bf16 ? auto_walk_tile_bf16(T, C, vec, bwd) : gated ? auto_walk_tile_form(T, C, vec, bwd, form)
                                                                   : auto_walk_tile(T, C, vec, bwd);
         if (wt) {
             p.variant = LINREC_VARIANT_WALK;
@@ -950,8 +1026,9 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
                 walk_c[0] = T >= 768 ? 30 : 24;
                 walk_c[1] = vec >= 4 ? 8 : 28;
             } else {
-                walk_c[0] = 18;
-                walk_c[1] = 21;
+                walk_c[0] = auto_walk_tile_form(T, C, vec, bwd, form);
+                walk_c[1] = walk_c[0] == 18 ? 21 : 18;
+                if (!walk_c[0]) walk_c[0] = 21;
             }
         }
         opts().variant = LINREC_VARIANT_WALK;
