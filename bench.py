@@ -205,17 +205,22 @@ def gated_bench(args, lr, torch, wl):
     E = T * B * n
     inp = wl.make_gated(T, B, n, seed=sum(map(ord, args.gated)), device=dev, gate_mean=spec["gate_mean"],
                         gate_std=spec["gate_std"])
+    bf16 = args.dtype == "bf16"   # bf16 storage: half the bytes, the same arithmetic
+    if bf16:
+        inp = {k: (v.to(torch.bfloat16).contiguous() if torch.is_tensor(v) else v) for k, v in inp.items()}
     g_pre, i_pre, h0, e = inp["g_pre"], inp["i_pre"], inp["h0"], inp["grad_h"]
     h = torch.empty_like(g_pre)
     gg, gi = torch.empty_like(g_pre), torch.empty_like(g_pre)
-    gh0 = torch.empty((B, n), device=dev)
+    gh0 = torch.empty_like(h0)
     lam, x = torch.empty_like(g_pre), torch.empty_like(g_pre)
     stream = torch.cuda.current_stream()
     K = args.steps
+    family = lr.ENTRY_GILR_BF16 if bf16 else lr.ENTRY_GILR
+    bpe_f, bpe_b = (6.0, 12.0) if bf16 else (12.0, 24.0)
 
     if not args.no_tune:
-        lr.linrec_tune_for(lr.ENTRY_GILR, T, B, n, backward=False, stream=stream)
-        lr.linrec_tune_for(lr.ENTRY_GILR, T, B, n, backward=True, stream=stream)
+        lr.linrec_tune_for(family, T, B, n, backward=False, stream=stream)
+        lr.linrec_tune_for(family, T, B, n, backward=True, stream=stream)
 
     def fused_fwd():
         lr.linrec_gilr_forward(g_pre, i_pre, h0, h_out=h, stream=stream)
@@ -250,31 +255,33 @@ def gated_bench(args, lr, torch, wl):
     out = {
         "metric": "gated linrec (GILR) fwd+bwd elements/sec and achieved HBM GB/s (% of MI355X peak)",
         "value": E / ((f_avg + b_avg) * 1e-3), "unit": "elements/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
-        "ms_per_step": f_avg + b_avg, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "ms_per_step": f_avg + b_avg, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 arithmetic on bf16 storage" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{args.gated}: gated forward+backward, fp32, time-major [T={T}, B={B}, n={n}], tau=tanh; "
-                               + spec["note"],
-                   "tile_fwd": lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n, backward=False)[1],
-                   "tile_bwd": lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n, backward=True)[1]},
-        "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(12.0, f_avg), "frac_of_peak": gbs(12.0, f_avg) / HBM_PEAK_GBS},
-        "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(24.0, b_avg), "frac_of_peak": gbs(24.0, b_avg) / HBM_PEAK_GBS},
+        "config": {"workload": f"{args.gated}: gated forward+backward, {'bf16 storage' if bf16 else 'fp32'}, time-major "
+                               f"[T={T}, B={B}, n={n}], tau=tanh; " + spec["note"],
+                   "tile_fwd": lr.linrec_plan_for(family, T, B, n, backward=False)[1],
+                   "tile_bwd": lr.linrec_plan_for(family, T, B, n, backward=True)[1]},
+        "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(bpe_f, f_avg), "frac_of_peak": gbs(bpe_f, f_avg) / HBM_PEAK_GBS},
+        "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(bpe_b, b_avg), "frac_of_peak": gbs(bpe_b, b_avg) / HBM_PEAK_GBS},
         "unfused_forward": {"avg_ms": u_avg, "min_ms": u_min, "speedup_of_fused": u_avg / f_avg,
                             "what": "torch.sigmoid, torch.tanh, torch.addcmul, then linrec_forward"},
-        "roofline": {"bound": "hbm", "kernel": "gated backward pass (look-back kernel)", "achieved": gbs(24.0, b_avg),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(24.0, b_avg) / HBM_PEAK_GBS, "traffic": None,
-                     "bytes_per_element": 24.0, "algorithmic_bytes": 24.0 * E, "avg_ms": b_avg},
+        "roofline": {"bound": "hbm", "kernel": "gated backward pass (look-back kernel)", "achieved": gbs(bpe_b, b_avg),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(bpe_b, b_avg) / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_element": bpe_b, "algorithmic_bytes": bpe_b * E, "avg_ms": b_avg},
         "cpu_baseline": None,
     }
-    out["roofline"]["traffic"] = measured_traffic(args.gated, "backward", "gated:")
+    if not bf16:
+        out["roofline"]["traffic"] = measured_traffic(args.gated, "backward", "gated:")
     if args.probe:
         out["stream_probe"] = stream_probe(lr, torch, E, stream)
     if not args.no_cpu_baseline:
         import oracle
         threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
         C = B * n
-        f = lambda t: t.cpu().numpy().reshape(-1, C)
+        f = lambda t: t.float().cpu().numpy().reshape(-1, C)
         gp, ip, ee, hh = f(g_pre), f(i_pre), f(e), f(h)
-        h0v = h0.cpu().numpy().reshape(-1)
+        h0v = h0.float().cpu().numpy().reshape(-1)
         oracle.build()
         t0 = time.perf_counter()
         oracle.gilr_forward(gp, ip, h0v, threads=threads)
@@ -294,18 +301,23 @@ def lstm_bench(args, lr, torch, wl):
     T, B, n = spec["T"], spec["B"], spec["n"]
     E = T * B * n
     inp = wl.make_lstm(T, B, n, seed=sum(map(ord, args.lstm)), device=dev, forget_mean=spec["forget_mean"])
+    bf16 = args.dtype == "bf16"   # bf16 storage: half the bytes, the same arithmetic
+    if bf16:
+        inp = {k: (v.to(torch.bfloat16).contiguous() if torch.is_tensor(v) else v) for k, v in inp.items()}
     pre = [inp[k] for k in ("f_pre", "i_pre", "z_pre", "o_pre")]
     c0, e = inp["c0"], inp["grad_h"]
     c, h = torch.empty_like(e), torch.empty_like(e)
     grads = [torch.empty_like(e) for _ in range(4)]
-    gc0 = torch.empty((B, n), device=dev)
+    gc0 = torch.empty_like(c0)
     lam, x, og = torch.empty_like(e), torch.empty_like(e), torch.empty_like(e)
     stream = torch.cuda.current_stream()
     K = args.steps
+    family = lr.ENTRY_LSTM_CELL_BF16 if bf16 else lr.ENTRY_LSTM_CELL
+    bpe_f, bpe_b = (12.0, 20.0) if bf16 else (24.0, 40.0)
 
     if not args.no_tune:
-        lr.linrec_tune_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=False, stream=stream)
-        lr.linrec_tune_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=True, stream=stream)
+        lr.linrec_tune_for(family, T, B, n, backward=False, stream=stream)
+        lr.linrec_tune_for(family, T, B, n, backward=True, stream=stream)
 
     def fused_fwd():
         lr.linrec_lstm_cell_forward(*pre, c0, c_out=c, h_out=h, stream=stream)
@@ -343,31 +355,33 @@ def lstm_bench(args, lr, torch, wl):
     out = {
         "metric": "LSTM-cell linrec fwd+bwd elements/sec and achieved HBM GB/s (% of MI355X peak)",
         "value": E / ((f_avg + b_avg) * 1e-3), "unit": "elements/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
-        "ms_per_step": f_avg + b_avg, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "ms_per_step": f_avg + b_avg, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 arithmetic on bf16 storage" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{args.lstm}: LSTM cell forward+backward, fp32, time-major [T={T}, B={B}, n={n}]; "
-                               + spec["note"],
-                   "tile_fwd": lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=False)[1],
-                   "tile_bwd": lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=True)[1]},
-        "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(24.0, f_avg), "frac_of_peak": gbs(24.0, f_avg) / HBM_PEAK_GBS},
-        "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(40.0, b_avg), "frac_of_peak": gbs(40.0, b_avg) / HBM_PEAK_GBS},
+        "config": {"workload": f"{args.lstm}: LSTM cell forward+backward, {'bf16 storage' if bf16 else 'fp32'}, time-major "
+                               f"[T={T}, B={B}, n={n}]; " + spec["note"],
+                   "tile_fwd": lr.linrec_plan_for(family, T, B, n, backward=False)[1],
+                   "tile_bwd": lr.linrec_plan_for(family, T, B, n, backward=True)[1]},
+        "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(bpe_f, f_avg), "frac_of_peak": gbs(bpe_f, f_avg) / HBM_PEAK_GBS},
+        "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(bpe_b, b_avg), "frac_of_peak": gbs(bpe_b, b_avg) / HBM_PEAK_GBS},
         "unfused_forward": {"avg_ms": u_avg, "min_ms": u_min, "speedup_of_fused": u_avg / f_avg,
                             "what": "torch sigmoid x3, tanh, mul x2 around linrec_forward"},
-        "roofline": {"bound": "hbm", "kernel": "LSTM-cell backward pass (look-back kernel)", "achieved": gbs(40.0, b_avg),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(40.0, b_avg) / HBM_PEAK_GBS, "traffic": None,
-                     "bytes_per_element": 40.0, "algorithmic_bytes": 40.0 * E, "avg_ms": b_avg},
+        "roofline": {"bound": "hbm", "kernel": "LSTM-cell backward pass (look-back kernel)", "achieved": gbs(bpe_b, b_avg),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(bpe_b, b_avg) / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_element": bpe_b, "algorithmic_bytes": bpe_b * E, "avg_ms": b_avg},
         "cpu_baseline": None,
     }
-    out["roofline"]["traffic"] = measured_traffic(args.lstm, "backward", "lstm:")
+    if not bf16:
+        out["roofline"]["traffic"] = measured_traffic(args.lstm, "backward", "lstm:")
     if args.probe:
         out["stream_probe"] = stream_probe(lr, torch, E, stream)
     if not args.no_cpu_baseline:
         import oracle
         threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
         C = B * n
-        f = lambda t: t.cpu().numpy().reshape(-1, C)
+        f = lambda t: t.float().cpu().numpy().reshape(-1, C)
         pp = [f(p) for p in pre]
-        c0v = c0.cpu().numpy().reshape(-1)
+        c0v = c0.float().cpu().numpy().reshape(-1)
         ee, cc = f(e), f(c)
         oracle.build()
         t0 = time.perf_counter()

@@ -206,6 +206,30 @@ int linrec_lstm_cell_backward(const float *f_pre, const float *i_pre, const floa
                               float *grad_z_pre, float *grad_o_pre, float *grad_c0,
                               int64_t T, int64_t B, int64_t n, void *stream);
 
+/*
+ * The gated layer and the LSTM cell on bf16 STORAGE: every tensor holds bfloat16 (passed as uint16_t),
+ * values are widened exactly on load, the arithmetic is that of the fp32 entry points above (fp32
+ * activations and steps, fp64 chunk products), results are rounded to nearest even on store: 6 / 12
+ * bytes per element for the layer, 12 / 20 for the cell.  Like linrec_forward_bf16 a bandwidth option,
+ * not one of the paper's experiments (Section 2.3: fp32).  Same arguments, NULL and aliasing rules
+ * as the fp32 entry points.  The backward passes consume the ROUNDED h (c) they are given.  Tensors
+ * that are not 4-byte aligned, or an odd B*n, fall back to the serial kernel.
+ */
+int linrec_gilr_forward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h0,
+                             uint16_t *h_out, int tau, int64_t T, int64_t B, int64_t n, void *stream);
+int linrec_gilr_backward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h,
+                              const uint16_t *h0, const uint16_t *grad_h, uint16_t *grad_g_pre,
+                              uint16_t *grad_i_pre, uint16_t *grad_h0, int tau, int64_t T, int64_t B,
+                              int64_t n, void *stream);
+int linrec_lstm_cell_forward_bf16(const uint16_t *f_pre, const uint16_t *i_pre, const uint16_t *z_pre,
+                                  const uint16_t *o_pre, const uint16_t *c0, uint16_t *c_out,
+                                  uint16_t *h_out, int64_t T, int64_t B, int64_t n, void *stream);
+int linrec_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_t *i_pre, const uint16_t *z_pre,
+                                   const uint16_t *o_pre, const uint16_t *c, const uint16_t *c0,
+                                   const uint16_t *grad_h, uint16_t *grad_f_pre, uint16_t *grad_i_pre,
+                                   uint16_t *grad_z_pre, uint16_t *grad_o_pre, uint16_t *grad_c0,
+                                   int64_t T, int64_t B, int64_t n, void *stream);
+
 /* Process-wide tuning knobs (LINREC_OPT_*).  Environment variables LINREC_VARIANT
  * ("auto", "threephase", "lookback", "serial") and LINREC_TILE (integer id) give the
  * initial values.  Returns LINREC_OK or LINREC_ERR_OPTION.  Not thread-safe against
@@ -230,7 +254,9 @@ enum {
     LINREC_ENTRY_PLAIN = 0,     /* linrec_forward / linrec_backward (what linrec_plan reports) */
     LINREC_ENTRY_GILR = 1,      /* linrec_gilr_forward / linrec_gilr_backward                  */
     LINREC_ENTRY_LSTM_CELL = 2, /* linrec_lstm_cell_forward / linrec_lstm_cell_backward        */
-    LINREC_ENTRY_BF16 = 3       /* linrec_forward_bf16 / linrec_backward_bf16                  */
+    LINREC_ENTRY_BF16 = 3,      /* linrec_forward_bf16 / linrec_backward_bf16                  */
+    LINREC_ENTRY_GILR_BF16 = 4,      /* linrec_gilr_forward_bf16 / linrec_gilr_backward_bf16    */
+    LINREC_ENTRY_LSTM_CELL_BF16 = 5  /* linrec_lstm_cell_forward_bf16 / ..._backward_bf16       */
 };
 int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward,
                     int alignment_bytes, int *variant, int *tile_id);
@@ -277,6 +303,22 @@ int linrec_validate_lstm_cell_backward(const float *f_pre, const float *i_pre, c
                                        const float *grad_i_pre, const float *grad_z_pre,
                                        const float *grad_o_pre, const float *grad_c0,
                                        int64_t T, int64_t B, int64_t n);
+int linrec_validate_gilr_forward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h0,
+                                      const uint16_t *h_out, int tau, int64_t T, int64_t B, int64_t n);
+int linrec_validate_gilr_backward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h,
+                                       const uint16_t *h0, const uint16_t *grad_h,
+                                       const uint16_t *grad_g_pre, const uint16_t *grad_i_pre,
+                                       const uint16_t *grad_h0, int tau, int64_t T, int64_t B, int64_t n);
+int linrec_validate_lstm_cell_forward_bf16(const uint16_t *f_pre, const uint16_t *i_pre,
+                                           const uint16_t *z_pre, const uint16_t *o_pre,
+                                           const uint16_t *c0, const uint16_t *c_out,
+                                           const uint16_t *h_out, int64_t T, int64_t B, int64_t n);
+int linrec_validate_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_t *i_pre,
+                                            const uint16_t *z_pre, const uint16_t *o_pre,
+                                            const uint16_t *c, const uint16_t *c0, const uint16_t *grad_h,
+                                            const uint16_t *grad_f_pre, const uint16_t *grad_i_pre,
+                                            const uint16_t *grad_z_pre, const uint16_t *grad_o_pre,
+                                            const uint16_t *grad_c0, int64_t T, int64_t B, int64_t n);
 
 /*
  * Measurement aid, not part of the recurrence: a pure streaming kernel built from the same

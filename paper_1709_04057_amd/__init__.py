@@ -9,7 +9,9 @@ from .autograd import gilr, linear_recurrence, lstm_cell  # noqa: F401
 from .binding import (  # noqa: F401
     ENTRY_BF16,
     ENTRY_GILR,
+    ENTRY_GILR_BF16,
     ENTRY_LSTM_CELL,
+    ENTRY_LSTM_CELL_BF16,
     ENTRY_PLAIN,
     LinrecError,
     OPT_CHUNK_TILES,

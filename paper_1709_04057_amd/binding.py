@@ -73,6 +73,11 @@ def lib():
         L.linrec_validate_lstm_cell_forward.restype = ci
         L.linrec_validate_lstm_cell_backward.argtypes = [p] * 12 + [i64, i64, i64]
         L.linrec_validate_lstm_cell_backward.restype = ci
+        for name in ("gilr_forward", "gilr_backward", "lstm_cell_forward", "lstm_cell_backward"):
+            getattr(L, "linrec_%s_bf16" % name).argtypes = getattr(L, "linrec_" + name).argtypes
+            getattr(L, "linrec_%s_bf16" % name).restype = ci
+            getattr(L, "linrec_validate_%s_bf16" % name).argtypes = getattr(L, "linrec_validate_" + name).argtypes
+            getattr(L, "linrec_validate_%s_bf16" % name).restype = ci
         L.linrec_set_option.argtypes = [ci, i64]
         L.linrec_set_option.restype = ci
         L.linrec_get_option.argtypes = [ci]
@@ -205,17 +210,21 @@ def linrec_backward(lam, h, h0, grad_h, grad_x=None, grad_lambda=None, grad_h0=N
 
 
 def linrec_gilr_forward(g_pre, i_pre, h0=None, h_out=None, tau=TAU_TANH, stream=None):
-    """h[t] = g*h[t-1] + (1-g)*tau(i_pre[t]) with g = sigmoid(g_pre[t]); returns h_out."""
+    """h[t] = g*h[t-1] + (1-g)*tau(i_pre[t]) with g = sigmoid(g_pre[t]); returns h_out.
+
+    float32 tensors go to linrec_gilr_forward, bfloat16 tensors (all of them) to linrec_gilr_forward_bf16."""
     import torch
-    T, B, n = _tbn(g_pre, "g_pre")
-    if tuple(_tbn(i_pre, "i_pre")) != (T, B, n):
+    dt = g_pre.dtype if g_pre.dtype == torch.bfloat16 else torch.float32
+    T, B, n = _tbn(g_pre, "g_pre", dt)
+    if tuple(_tbn(i_pre, "i_pre", dt)) != (T, B, n):
         raise ValueError("i_pre must have g_pre's shape")
-    _bn(h0, "h0", B, n)
+    _bn(h0, "h0", B, n, dt)
     if h_out is None:
         h_out = torch.empty_like(i_pre)
-    elif tuple(_tbn(h_out, "h_out")) != (T, B, n):
+    elif tuple(_tbn(h_out, "h_out", dt)) != (T, B, n):
         raise ValueError("h_out must have g_pre's shape")
-    _check(lib().linrec_gilr_forward(_ptr(g_pre), _ptr(i_pre), _ptr(h0), _ptr(h_out), int(tau), T, B, n,
+    fn = lib().linrec_gilr_forward_bf16 if dt == torch.bfloat16 else lib().linrec_gilr_forward
+    _check(fn(_ptr(g_pre), _ptr(i_pre), _ptr(h0), _ptr(h_out), int(tau), T, B, n,
                                      _stream_ptr(stream)))
     return h_out
 
@@ -224,22 +233,24 @@ def linrec_gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre=None, grad_i_pr
                          stream=None, want_grad_g_pre=True, want_grad_i_pre=True, want_grad_h0=True):
     """Gradients of the gated layer w.r.t. its pre-activations; returns (grad_g_pre, grad_i_pre, grad_h0)."""
     import torch
-    T, B, n = _tbn(g_pre, "g_pre")
+    dt = g_pre.dtype if g_pre.dtype == torch.bfloat16 else torch.float32
+    T, B, n = _tbn(g_pre, "g_pre", dt)
     for name, t in (("i_pre", i_pre), ("h", h), ("grad_h", grad_h)):
-        if tuple(_tbn(t, name)) != (T, B, n):
+        if tuple(_tbn(t, name, dt)) != (T, B, n):
             raise ValueError(f"{name} must have g_pre's shape")
-    _bn(h0, "h0", B, n)
+    _bn(h0, "h0", B, n, dt)
     if grad_g_pre is None and want_grad_g_pre:
         grad_g_pre = torch.empty_like(grad_h)
     if grad_i_pre is None and want_grad_i_pre:
         grad_i_pre = torch.empty_like(grad_h)
     if grad_h0 is None and want_grad_h0:
-        grad_h0 = torch.empty((B, n), dtype=torch.float32, device=g_pre.device)
+        grad_h0 = torch.empty((B, n), dtype=dt, device=g_pre.device)
     for name, t in (("grad_g_pre", grad_g_pre), ("grad_i_pre", grad_i_pre)):
-        if t is not None and tuple(_tbn(t, name)) != (T, B, n):
+        if t is not None and tuple(_tbn(t, name, dt)) != (T, B, n):
             raise ValueError(f"{name} must have g_pre's shape")
-    _bn(grad_h0, "grad_h0", B, n)
-    _check(lib().linrec_gilr_backward(_ptr(g_pre), _ptr(i_pre), _ptr(h), _ptr(h0), _ptr(grad_h), _ptr(grad_g_pre),
+    _bn(grad_h0, "grad_h0", B, n, dt)
+    fn = lib().linrec_gilr_backward_bf16 if dt == torch.bfloat16 else lib().linrec_gilr_backward
+    _check(fn(_ptr(g_pre), _ptr(i_pre), _ptr(h), _ptr(h0), _ptr(grad_h), _ptr(grad_g_pre),
                                       _ptr(grad_i_pre), _ptr(grad_h0), int(tau), T, B, n, _stream_ptr(stream)))
     return grad_g_pre, grad_i_pre, grad_h0
 
@@ -248,19 +259,21 @@ def linrec_lstm_cell_forward(f_pre, i_pre, z_pre, o_pre, c0=None, c_out=None, h_
                              want_c=True, want_h=True):
     """c[t] = f*c[t-1] + i*z, h[t] = o*c[t] with f, i, o = sigmoid(pre-activations), z = tanh(z_pre); returns (c, h)."""
     import torch
-    T, B, n = _tbn(f_pre, "f_pre")
+    dt = f_pre.dtype if f_pre.dtype == torch.bfloat16 else torch.float32
+    T, B, n = _tbn(f_pre, "f_pre", dt)
     for name, t in (("i_pre", i_pre), ("z_pre", z_pre)) + ((("o_pre", o_pre),) if o_pre is not None else ()):
-        if tuple(_tbn(t, name)) != (T, B, n):
+        if tuple(_tbn(t, name, dt)) != (T, B, n):
             raise ValueError(f"{name} must have f_pre's shape")
-    _bn(c0, "c0", B, n)
+    _bn(c0, "c0", B, n, dt)
     if c_out is None and want_c:
         c_out = torch.empty_like(f_pre)
     if h_out is None and want_h:
         h_out = torch.empty_like(f_pre)
     for name, t in (("c_out", c_out), ("h_out", h_out)):
-        if t is not None and tuple(_tbn(t, name)) != (T, B, n):
+        if t is not None and tuple(_tbn(t, name, dt)) != (T, B, n):
             raise ValueError(f"{name} must have f_pre's shape")
-    _check(lib().linrec_lstm_cell_forward(_ptr(f_pre), _ptr(i_pre), _ptr(z_pre), _ptr(o_pre), _ptr(c0), _ptr(c_out),
+    fn = lib().linrec_lstm_cell_forward_bf16 if dt == torch.bfloat16 else lib().linrec_lstm_cell_forward
+    _check(fn(_ptr(f_pre), _ptr(i_pre), _ptr(z_pre), _ptr(o_pre), _ptr(c0), _ptr(c_out),
                                           _ptr(h_out), T, B, n, _stream_ptr(stream)))
     return c_out, h_out
 
@@ -271,23 +284,25 @@ def linrec_lstm_cell_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grads=N
 
     ``grads`` may hold four preallocated tensors (or None entries); ``want[k] = False`` skips output k."""
     import torch
-    T, B, n = _tbn(f_pre, "f_pre")
+    dt = f_pre.dtype if f_pre.dtype == torch.bfloat16 else torch.float32
+    T, B, n = _tbn(f_pre, "f_pre", dt)
     for name, t in (("i_pre", i_pre), ("z_pre", z_pre), ("o_pre", o_pre), ("c", c), ("grad_h", grad_h)):
-        if tuple(_tbn(t, name)) != (T, B, n):
+        if tuple(_tbn(t, name, dt)) != (T, B, n):
             raise ValueError(f"{name} must have f_pre's shape")
-    _bn(c0, "c0", B, n)
+    _bn(c0, "c0", B, n, dt)
     outs = list(grads) if grads is not None else [None] * 4
     for k in range(4):
         if outs[k] is None and want[k]:
             outs[k] = torch.empty_like(grad_h)
-        if outs[k] is not None and tuple(_tbn(outs[k], "grads[%d]" % k)) != (T, B, n):
+        if outs[k] is not None and tuple(_tbn(outs[k], "grads[%d]" % k, dt)) != (T, B, n):
             raise ValueError("gradient outputs must have f_pre's shape")
     if grad_c0 is None and want_grad_c0:
-        grad_c0 = torch.empty((B, n), dtype=torch.float32, device=f_pre.device)
-    _bn(grad_c0, "grad_c0", B, n)
-    _check(lib().linrec_lstm_cell_backward(_ptr(f_pre), _ptr(i_pre), _ptr(z_pre), _ptr(o_pre), _ptr(c), _ptr(c0),
-                                           _ptr(grad_h), _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]), _ptr(outs[3]),
-                                           _ptr(grad_c0), T, B, n, _stream_ptr(stream)))
+        grad_c0 = torch.empty((B, n), dtype=dt, device=f_pre.device)
+    _bn(grad_c0, "grad_c0", B, n, dt)
+    fn = lib().linrec_lstm_cell_backward_bf16 if dt == torch.bfloat16 else lib().linrec_lstm_cell_backward
+    _check(fn(_ptr(f_pre), _ptr(i_pre), _ptr(z_pre), _ptr(o_pre), _ptr(c), _ptr(c0),
+              _ptr(grad_h), _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]), _ptr(outs[3]),
+              _ptr(grad_c0), T, B, n, _stream_ptr(stream)))
     return outs[0], outs[1], outs[2], outs[3], grad_c0
 
 
@@ -316,7 +331,7 @@ def linrec_plan(T, B, n, backward=False, alignment=16):
     return v.value, t.value
 
 
-ENTRY_PLAIN, ENTRY_GILR, ENTRY_LSTM_CELL, ENTRY_BF16 = 0, 1, 2, 3
+ENTRY_PLAIN, ENTRY_GILR, ENTRY_LSTM_CELL, ENTRY_BF16, ENTRY_GILR_BF16, ENTRY_LSTM_CELL_BF16 = 0, 1, 2, 3, 4, 5
 
 
 def linrec_plan_for(entry_point, T, B, n, backward=False, alignment=16):

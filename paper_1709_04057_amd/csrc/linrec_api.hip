@@ -375,6 +375,47 @@ int auto_walk_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
     return vec >= 4 ? 8 : 28;
 }
 
+// First-guess shapes of the gated layer and the cell on bf16 storage (their kernels exist for the shapes
+// with two or four columns per thread; the register tile is the fp32 one, the bytes are half).
+int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
+{
+    if (form == FORM_LSTM) return (vec >= 4 && C >= 2048) ? (bwd ? 4 : 3) : 15;
+    if (T < 192) return 15;
+    if (!bwd) return (T >= 8192 && C <= 2048) ? 13 : 14;
+    return (vec >= 4 && C >= 2048) ? 3 : 15;
+}
+int auto_walk_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
+{
+    // the fp32 rule's region; where it lands on a one-column shape, the two- or four-column shape of the
+    // same width and height (the cell: of at most 32 elements per thread)
+    const int t = auto_walk_tile_form(T, C, vec, bwd, form);
+    if (t < 1 || kTiles[t - 1].vec >= 2) return t < 1 ? 0 : t;
+    const bool cell = form == FORM_LSTM;
+    switch (t) {
+    case 17: case 22: case 23: return cell ? 15 : 13;   // 32 columns, 512 rows and more
+    case 20: return cell ? 15 : 16;                     // 64 x 256
+    case 21: return vec >= 4 ? 4 : 15;                  // 64 x 128
+    default: return 15;                                 // 32 x 256
+    }
+}
+int entry_family(int form, bool bf16)
+{
+    if (form == FORM_GATED) return bf16 ? LINREC_ENTRY_GILR_BF16 : LINREC_ENTRY_GILR;
+    if (form == FORM_LSTM) return bf16 ? LINREC_ENTRY_LSTM_CELL_BF16 : LINREC_ENTRY_LSTM_CELL;
+    return bf16 ? LINREC_ENTRY_BF16 : LINREC_ENTRY_PLAIN;
+}
+int entry_form(int entry_point)
+{
+    return (entry_point == LINREC_ENTRY_GILR || entry_point == LINREC_ENTRY_GILR_BF16)             ? FORM_GATED
+           : (entry_point == LINREC_ENTRY_LSTM_CELL || entry_point == LINREC_ENTRY_LSTM_CELL_BF16) ? FORM_LSTM
+                                                                                                   : FORM_PLAIN;
+}
+bool entry_bf16(int entry_point)
+{
+    return entry_point == LINREC_ENTRY_BF16 || entry_point == LINREC_ENTRY_GILR_BF16 ||
+           entry_point == LINREC_ENTRY_LSTM_CELL_BF16;
+}
+
 struct Plan {
     int variant, tile;
     bool hp_late;
@@ -412,8 +453,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     p.tile = (int)opts().tile;
     p.persistent = (int)opts().persistent;
     if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK) {  // a tuned plan, if there is one for this shape
-        const int family = bf16 ? LINREC_ENTRY_BF16 : form == FORM_GATED ? LINREC_ENTRY_GILR
-                                                    : form == FORM_LSTM ? LINREC_ENTRY_LSTM_CELL : LINREC_ENTRY_PLAIN;
+        const int family = entry_family(form, bf16);
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess) {
             std::lock_guard<std::mutex> lock(g_tuned_mu);
@@ -427,8 +467,9 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     }
     // No option and no tuned plan: short, wide problems take the walk.
     if (opts().variant == LINREC_VARIANT_AUTO && p.tile == 0) {
-        const int wt = bf16 ? auto_walk_tile_bf16(T, C, vec, bwd) : gated ? auto_walk_tile_form(T, C, vec, bwd, form)
-                                                                  : auto_walk_tile(T, C, vec, bwd);
+        const int wt = gated ? (bf16 ? auto_walk_tile_form_bf16(T, C, vec, bwd, form) : auto_walk_tile_form(T, C, vec, bwd, form))
+                       : bf16 ? auto_walk_tile_bf16(T, C, vec, bwd)
+                              : auto_walk_tile(T, C, vec, bwd);
         if (wt) {
             p.variant = LINREC_VARIANT_WALK;
             p.tile = wt;
@@ -442,12 +483,12 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && gated && kTiles[p.tile - 1].r % 8 != 0 && kTiles[p.tile - 1].r >= 8) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && kTiles[p.tile - 1].vec < 2) p.tile = 0;
-    if (p.tile >= 1 && p.tile <= NUM_TILES && !bf16 && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 64) p.tile = 0;
+    if (p.tile >= 1 && p.tile <= NUM_TILES && (!bf16 || gated) && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 64) p.tile = 0;
     if (p.tile < 1 || p.tile > NUM_TILES) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
         if (gated) p.tile = auto_tile_form(T, C, vec, bwd, form);
         if (form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 18;  // (the cell: at most 32 elements per thread and operand)
-        if (bf16) p.tile = auto_tile_bf16(T, C, vec, bwd);
+        if (bf16) p.tile = gated ? auto_tile_form_bf16(T, C, vec, bwd, form) : auto_tile_bf16(T, C, vec, bwd);
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
     if (bf16 && vec < 2) p.variant = LINREC_VARIANT_SERIAL;
@@ -671,23 +712,131 @@ extern "C" int linrec_backward_bf16(const uint16_t *lambda, const uint16_t *h, c
     return run(A, true, max_vec_bf16(C, {lambda, h, grad_h, grad_x, grad_lambda}), s, FORM_PLAIN, true);
 }
 
-extern "C" int linrec_gilr_forward(const float *g_pre, const float *i_pre, const float *h0, float *h_out, int tau,
-                                   int64_t T, int64_t B, int64_t n, void *stream)
+// The gated layer and the LSTM cell in either storage type: E = float, or uint16_t holding bf16.  (The
+// kernels' argument block types every tensor float*; with bf16 storage they address 2-byte elements.)
+namespace {
+
+template <class E>
+constexpr bool is_bf16 = sizeof(E) == 2;
+template <class E>
+const float *in_ptr(const E *p) { return reinterpret_cast<const float *>(p); }
+template <class E>
+float *out_ptr(E *p) { return reinterpret_cast<float *>(p); }
+template <class E>
+int zero_state(E *p, int64_t C, hipStream_t s)
 {
-    const int rc = linrec_validate_gilr_forward(g_pre, i_pre, h0, h_out, tau, T, B, n);
-    if (rc != LINREC_OK) return rc;
+    const hipError_t e = is_bf16<E> ? launch_fill16(p, C, s) : launch_fill(reinterpret_cast<float *>(p), 0.0f, C, s);
+    return e == hipSuccess ? LINREC_OK : hip_fail(e, "launch(fill)");
+}
+// widest access the [T, C] tensors allow (the [C] vectors are read element by element with bf16 storage)
+template <class E>
+int form_vec(int64_t C, std::initializer_list<const void *> big, std::initializer_list<const void *> small_)
+{
+    if (is_bf16<E>) return max_vec_bf16(C, big);
+    return std::min(max_vec(C, big), max_vec(C, small_));
+}
+
+template <class E>
+int gilr_forward(const E *g_pre, const E *i_pre, const E *h0, E *h_out, int tau, int64_t T, int64_t B, int64_t n,
+                 hipStream_t s)
+{
     const int64_t C = B * n;
     if (T == 0 || C == 0) return LINREC_OK;
     Args A;
     memset(&A, 0, sizeof A);
-    A.a = g_pre;
-    A.b = i_pre;
-    A.h0 = h0;
-    A.out0 = h_out;
+    A.a = in_ptr(g_pre);
+    A.b = in_ptr(i_pre);
+    A.h0 = in_ptr(h0);
+    A.out0 = out_ptr(h_out);
     A.tau = tau;
     A.T = T;
     A.C = C;
-    return run(A, false, max_vec(C, {g_pre, i_pre, h0, h_out}), (hipStream_t)stream, FORM_GATED);
+    return run(A, false, form_vec<E>(C, {g_pre, i_pre, h_out}, {h0}), s, FORM_GATED, is_bf16<E>);
+}
+
+template <class E>
+int gilr_backward(const E *g_pre, const E *i_pre, const E *h, const E *h0, const E *grad_h, E *grad_g_pre, E *grad_i_pre,
+                  E *grad_h0, int tau, int64_t T, int64_t B, int64_t n, hipStream_t s)
+{
+    const int64_t C = B * n;
+    if (C == 0) return LINREC_OK;
+    if (T == 0) return grad_h0 ? zero_state(grad_h0, C, s) : LINREC_OK;
+    if (!grad_g_pre && !grad_i_pre && !grad_h0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = in_ptr(g_pre);
+    A.b = in_ptr(grad_h);
+    A.c = in_ptr(i_pre);
+    A.hprev = in_ptr(h);
+    A.h0 = in_ptr(h0);
+    A.out0 = out_ptr(grad_g_pre);
+    A.out1 = out_ptr(grad_i_pre);
+    A.gh0 = out_ptr(grad_h0);
+    A.tau = tau;
+    A.T = T;
+    A.C = C;
+    return run(A, true, form_vec<E>(C, {g_pre, i_pre, h, grad_h, grad_g_pre, grad_i_pre}, {h0, grad_h0}), s, FORM_GATED,
+               is_bf16<E>);
+}
+
+template <class E>
+int lstm_cell_forward(const E *f_pre, const E *i_pre, const E *z_pre, const E *o_pre, const E *c0, E *c_out, E *h_out,
+                      int64_t T, int64_t B, int64_t n, hipStream_t s)
+{
+    const int64_t C = B * n;
+    if (T == 0 || C == 0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = in_ptr(f_pre);
+    A.b = in_ptr(i_pre);
+    A.c = in_ptr(z_pre);
+    A.d = in_ptr(o_pre);
+    A.h0 = in_ptr(c0);
+    A.out0 = out_ptr(c_out);
+    A.out1 = out_ptr(h_out);
+    A.T = T;
+    A.C = C;
+    return run(A, false, form_vec<E>(C, {f_pre, i_pre, z_pre, o_pre, c_out, h_out}, {c0}), s, FORM_LSTM, is_bf16<E>);
+}
+
+template <class E>
+int lstm_cell_backward(const E *f_pre, const E *i_pre, const E *z_pre, const E *o_pre, const E *c, const E *c0,
+                       const E *grad_h, E *grad_f_pre, E *grad_i_pre, E *grad_z_pre, E *grad_o_pre, E *grad_c0, int64_t T,
+                       int64_t B, int64_t n, hipStream_t s)
+{
+    const int64_t C = B * n;
+    if (C == 0) return LINREC_OK;
+    if (T == 0) return grad_c0 ? zero_state(grad_c0, C, s) : LINREC_OK;
+    if (!grad_f_pre && !grad_i_pre && !grad_z_pre && !grad_o_pre && !grad_c0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = in_ptr(f_pre);
+    A.b = in_ptr(grad_h);
+    A.c = in_ptr(i_pre);
+    A.d = in_ptr(z_pre);
+    A.e = in_ptr(o_pre);
+    A.hprev = in_ptr(c);
+    A.h0 = in_ptr(c0);
+    A.out0 = out_ptr(grad_f_pre);
+    A.out1 = out_ptr(grad_i_pre);
+    A.out2 = out_ptr(grad_z_pre);
+    A.out3 = out_ptr(grad_o_pre);
+    A.gh0 = out_ptr(grad_c0);
+    A.T = T;
+    A.C = C;
+    return run(A, true,
+               form_vec<E>(C, {f_pre, i_pre, z_pre, o_pre, c, grad_h, grad_f_pre, grad_i_pre, grad_z_pre, grad_o_pre},
+                           {c0, grad_c0}),
+               s, FORM_LSTM, is_bf16<E>);
+}
+
+}  // namespace
+
+extern "C" int linrec_gilr_forward(const float *g_pre, const float *i_pre, const float *h0, float *h_out, int tau,
+                                   int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_gilr_forward(g_pre, i_pre, h0, h_out, tau, T, B, n);
+    return rc != LINREC_OK ? rc : gilr_forward(g_pre, i_pre, h0, h_out, tau, T, B, n, (hipStream_t)stream);
 }
 
 extern "C" int linrec_gilr_backward(const float *g_pre, const float *i_pre, const float *h, const float *h0,
@@ -695,32 +844,9 @@ extern "C" int linrec_gilr_backward(const float *g_pre, const float *i_pre, cons
                                     int64_t T, int64_t B, int64_t n, void *stream)
 {
     const int rc = linrec_validate_gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0, tau, T, B, n);
-    if (rc != LINREC_OK) return rc;
-    const int64_t C = B * n;
-    if (C == 0) return LINREC_OK;
-    hipStream_t s = (hipStream_t)stream;
-    if (T == 0) {
-        if (grad_h0) {
-            const hipError_t e = launch_fill(grad_h0, 0.0f, C, s);
-            if (e != hipSuccess) return hip_fail(e, "launch(fill)");
-        }
-        return LINREC_OK;
-    }
-    if (!grad_g_pre && !grad_i_pre && !grad_h0) return LINREC_OK;
-    Args A;
-    memset(&A, 0, sizeof A);
-    A.a = g_pre;
-    A.b = grad_h;
-    A.c = i_pre;
-    A.hprev = h;
-    A.h0 = h0;
-    A.out0 = grad_g_pre;
-    A.out1 = grad_i_pre;
-    A.gh0 = grad_h0;
-    A.tau = tau;
-    A.T = T;
-    A.C = C;
-    return run(A, true, max_vec(C, {g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0}), s, FORM_GATED);
+    return rc != LINREC_OK ? rc
+                           : gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0, tau, T, B, n,
+                                           (hipStream_t)stream);
 }
 
 extern "C" int linrec_lstm_cell_forward(const float *f_pre, const float *i_pre, const float *z_pre, const float *o_pre,
@@ -728,21 +854,7 @@ extern "C" int linrec_lstm_cell_forward(const float *f_pre, const float *i_pre, 
                                         void *stream)
 {
     const int rc = linrec_validate_lstm_cell_forward(f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out, T, B, n);
-    if (rc != LINREC_OK) return rc;
-    const int64_t C = B * n;
-    if (T == 0 || C == 0) return LINREC_OK;
-    Args A;
-    memset(&A, 0, sizeof A);
-    A.a = f_pre;
-    A.b = i_pre;
-    A.c = z_pre;
-    A.d = o_pre;
-    A.h0 = c0;
-    A.out0 = c_out;
-    A.out1 = h_out;
-    A.T = T;
-    A.C = C;
-    return run(A, false, max_vec(C, {f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out}), (hipStream_t)stream, FORM_LSTM);
+    return rc != LINREC_OK ? rc : lstm_cell_forward(f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out, T, B, n, (hipStream_t)stream);
 }
 
 extern "C" int linrec_lstm_cell_backward(const float *f_pre, const float *i_pre, const float *z_pre, const float *o_pre,
@@ -752,36 +864,47 @@ extern "C" int linrec_lstm_cell_backward(const float *f_pre, const float *i_pre,
 {
     const int rc = linrec_validate_lstm_cell_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre,
                                                       grad_z_pre, grad_o_pre, grad_c0, T, B, n);
-    if (rc != LINREC_OK) return rc;
-    const int64_t C = B * n;
-    if (C == 0) return LINREC_OK;
-    hipStream_t s = (hipStream_t)stream;
-    if (T == 0) {
-        if (grad_c0) {
-            const hipError_t e = launch_fill(grad_c0, 0.0f, C, s);
-            if (e != hipSuccess) return hip_fail(e, "launch(fill)");
-        }
-        return LINREC_OK;
-    }
-    if (!grad_f_pre && !grad_i_pre && !grad_z_pre && !grad_o_pre && !grad_c0) return LINREC_OK;
-    Args A;
-    memset(&A, 0, sizeof A);
-    A.a = f_pre;
-    A.b = grad_h;
-    A.c = i_pre;
-    A.d = z_pre;
-    A.e = o_pre;
-    A.hprev = c;
-    A.h0 = c0;
-    A.out0 = grad_f_pre;
-    A.out1 = grad_i_pre;
-    A.out2 = grad_z_pre;
-    A.out3 = grad_o_pre;
-    A.gh0 = grad_c0;
-    A.T = T;
-    A.C = C;
-    return run(A, true, max_vec(C, {f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre, grad_z_pre, grad_o_pre, grad_c0}), s,
-               FORM_LSTM);
+    return rc != LINREC_OK ? rc
+                           : lstm_cell_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre, grad_z_pre,
+                                                grad_o_pre, grad_c0, T, B, n, (hipStream_t)stream);
+}
+
+extern "C" int linrec_gilr_forward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h0, uint16_t *h_out,
+                                        int tau, int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_gilr_forward_bf16(g_pre, i_pre, h0, h_out, tau, T, B, n);
+    return rc != LINREC_OK ? rc : gilr_forward(g_pre, i_pre, h0, h_out, tau, T, B, n, (hipStream_t)stream);
+}
+
+extern "C" int linrec_gilr_backward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h, const uint16_t *h0,
+                                         const uint16_t *grad_h, uint16_t *grad_g_pre, uint16_t *grad_i_pre,
+                                         uint16_t *grad_h0, int tau, int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_gilr_backward_bf16(g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0, tau, T, B, n);
+    return rc != LINREC_OK ? rc
+                           : gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0, tau, T, B, n,
+                                           (hipStream_t)stream);
+}
+
+extern "C" int linrec_lstm_cell_forward_bf16(const uint16_t *f_pre, const uint16_t *i_pre, const uint16_t *z_pre,
+                                             const uint16_t *o_pre, const uint16_t *c0, uint16_t *c_out, uint16_t *h_out,
+                                             int64_t T, int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_lstm_cell_forward_bf16(f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out, T, B, n);
+    return rc != LINREC_OK ? rc : lstm_cell_forward(f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out, T, B, n, (hipStream_t)stream);
+}
+
+extern "C" int linrec_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_t *i_pre, const uint16_t *z_pre,
+                                              const uint16_t *o_pre, const uint16_t *c, const uint16_t *c0,
+                                              const uint16_t *grad_h, uint16_t *grad_f_pre, uint16_t *grad_i_pre,
+                                              uint16_t *grad_z_pre, uint16_t *grad_o_pre, uint16_t *grad_c0, int64_t T,
+                                              int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_lstm_cell_backward_bf16(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre,
+                                                           grad_z_pre, grad_o_pre, grad_c0, T, B, n);
+    return rc != LINREC_OK ? rc
+                           : lstm_cell_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre, grad_z_pre,
+                                                grad_o_pre, grad_c0, T, B, n, (hipStream_t)stream);
 }
 
 extern "C" int linrec_set_option(int option, int64_t value)
@@ -872,10 +995,10 @@ extern "C" int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n,
 {
     int64_t C = B * n;
     if (T <= 0 || B <= 0 || n <= 0) return LINREC_ERR_SHAPE;
-    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_BF16) return LINREC_ERR_OPTION;
+    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_LSTM_CELL_BF16) return LINREC_ERR_OPTION;
     const void *al = (const void *)(uintptr_t)(alignment_bytes > 0 ? alignment_bytes : 2);
-    const bool bf16 = entry_point == LINREC_ENTRY_BF16;
-    const int form = entry_point == LINREC_ENTRY_GILR ? FORM_GATED : entry_point == LINREC_ENTRY_LSTM_CELL ? FORM_LSTM : FORM_PLAIN;
+    const bool bf16 = entry_bf16(entry_point);
+    const int form = entry_form(entry_point);
     const int vec = bf16 ? max_vec_bf16(C, {al}) : max_vec(C, {al});
     Plan p = make_plan(T, C, vec, backward != 0, form, bf16);
     if ((form != FORM_PLAIN || bf16) && p.variant == LINREC_VARIANT_THREEPHASE) p.variant = LINREC_VARIANT_LOOKBACK;
@@ -903,7 +1026,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
 {
     if (T <= 0 || B <= 0 || n <= 0 || B > ((int64_t)1 << 40) / n || T > ((int64_t)1 << 40) / (B * n))
         return LINREC_ERR_SHAPE;
-    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_BF16) return LINREC_ERR_OPTION;
+    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_LSTM_CELL_BF16) return LINREC_ERR_OPTION;
     const int64_t C = B * n, E = T * C;
     hipStream_t s = (hipStream_t)stream;
     const bool bwd = backward != 0;
@@ -915,10 +1038,10 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
     // as lambda, 3.4 as a pre-activation (sigmoid = 0.968), so that products neither overflow nor vanish
     // within a tile; the other inputs are 1, the state vectors 0.  With bf16 storage the same fills are
     // written as 16-bit patterns (both constants are exact in bf16).
-    const bool bf16 = entry_point == LINREC_ENTRY_BF16;
-    const int n_in = entry_point == LINREC_ENTRY_LSTM_CELL ? (bwd ? 6 : 4) : entry_point == LINREC_ENTRY_GILR ? (bwd ? 4 : 2)
-                                                                                                              : (bwd ? 3 : 2);
-    const int n_out = entry_point == LINREC_ENTRY_LSTM_CELL ? (bwd ? 4 : 2) : (bwd ? 2 : 1);
+    const bool bf16 = entry_bf16(entry_point);
+    const int form = entry_form(entry_point);
+    const int n_in = form == FORM_LSTM ? (bwd ? 6 : 4) : form == FORM_GATED ? (bwd ? 4 : 2) : (bwd ? 3 : 2);
+    const int n_out = form == FORM_LSTM ? (bwd ? 4 : 2) : (bwd ? 2 : 1);
     const int n_big = n_in + n_out;
     float *big[10] = {}, *small_[2] = {nullptr, nullptr};
     hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -930,7 +1053,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
     if (rc == LINREC_OK && ((e = hipEventCreate(&ev0)) != hipSuccess || (e = hipEventCreate(&ev1)) != hipSuccess))
         rc = hip_fail(e, "hipEventCreate");
     if (rc == LINREC_OK) {
-        const float first = (entry_point == LINREC_ENTRY_GILR || entry_point == LINREC_ENTRY_LSTM_CELL) ? 3.40625f : 0.96875f;
+        const float first = form != FORM_PLAIN ? 3.40625f : 0.96875f;
         // a float whose two halves are the same bf16 pattern fills a bf16 tensor with that value
         auto both_halves = [](float v) {
             uint32_t b;
@@ -957,6 +1080,16 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
             return bwd ? linrec_lstm_cell_backward(big[0], big[1], big[2], big[3], big[4], small_[0], big[5], big[6], big[7],
                                                    big[8], big[9], small_[1], T, B, n, s)
                        : linrec_lstm_cell_forward(big[0], big[1], big[2], big[3], small_[0], big[4], big[5], T, B, n, s);
+        case LINREC_ENTRY_GILR_BF16:
+            return bwd ? linrec_gilr_backward_bf16((cb)big[0], (cb)big[1], (cb)big[2], (cb)small_[0], (cb)big[3], (mb)big[4],
+                                                   (mb)big[5], (mb)small_[1], LINREC_TAU_TANH, T, B, n, s)
+                       : linrec_gilr_forward_bf16((cb)big[0], (cb)big[1], (cb)small_[0], (mb)big[2], LINREC_TAU_TANH, T, B, n, s);
+        case LINREC_ENTRY_LSTM_CELL_BF16:
+            return bwd ? linrec_lstm_cell_backward_bf16((cb)big[0], (cb)big[1], (cb)big[2], (cb)big[3], (cb)big[4],
+                                                        (cb)small_[0], (cb)big[5], (mb)big[6], (mb)big[7], (mb)big[8],
+                                                        (mb)big[9], (mb)small_[1], T, B, n, s)
+                       : linrec_lstm_cell_forward_bf16((cb)big[0], (cb)big[1], (cb)big[2], (cb)big[3], (cb)small_[0],
+                                                       (mb)big[4], (mb)big[5], T, B, n, s);
         case LINREC_ENTRY_BF16:
             return bwd ? linrec_backward_bf16((cb)big[0], (cb)big[1], (cb)small_[0], (cb)big[2], (mb)big[3], (mb)big[4],
                                               (mb)small_[1], T, B, n, s)
@@ -976,12 +1109,12 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0},
                          gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 0},
                          bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 0};
-        const int *list = entry_point == LINREC_ENTRY_GILR ? gated_c : entry_point == LINREC_ENTRY_LSTM_CELL ? lstm_c
-                                                           : bf16 ? bf16_c : plain_c;
+        static const int gated16_c[] = {14, 15, 13, 16, 3, 4, 7, 8, 0}, lstm16_c[] = {15, 3, 4, 5, 0};
+        const int *list = form == FORM_GATED ? (bf16 ? gated16_c : gated_c) : form == FORM_LSTM ? (bf16 ? lstm16_c : lstm_c)
+                                                                          : bf16 ? bf16_c : plain_c;
         // the static rule's own choice goes first, so that what is remembered is never slower than it
-        const int form = entry_point == LINREC_ENTRY_GILR ? FORM_GATED : entry_point == LINREC_ENTRY_LSTM_CELL ? FORM_LSTM
-                                                                                                             : FORM_PLAIN;
-        std::vector<int> candidates{form != FORM_PLAIN ? auto_tile_form(T, C, vec, bwd, form)
+        std::vector<int> candidates{form != FORM_PLAIN ? (bf16 ? auto_tile_form_bf16(T, C, vec, bwd, form)
+                                                               : auto_tile_form(T, C, vec, bwd, form))
                                     : bf16            ? auto_tile_bf16(T, C, vec, bwd)
                                                       : auto_tile(T, C, vec, bwd, LINREC_VARIANT_LOOKBACK)};
         for (; *list; ++list)
@@ -1022,9 +1155,13 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         if (C >= 4096) {
             if (entry_point == LINREC_ENTRY_PLAIN) {
                 walk_c[0] = walk_tile(T, C, vec, bwd);
-            } else if (bf16) {
+            } else if (bf16 && form == FORM_PLAIN) {
                 walk_c[0] = T >= 768 ? 30 : 24;
                 walk_c[1] = vec >= 4 ? 8 : 28;
+            } else if (bf16) {
+                walk_c[0] = auto_walk_tile_form_bf16(T, C, vec, bwd, form);
+                if (!walk_c[0]) walk_c[0] = 15;
+                walk_c[1] = (vec >= 4 && walk_c[0] != 4) ? 4 : 0;
             } else {
                 walk_c[0] = auto_walk_tile_form(T, C, vec, bwd, form);
                 walk_c[1] = walk_c[0] == 18 ? 21 : 18;

@@ -31,7 +31,9 @@ namespace linrec {
 
 // Storage type of the [T, C] tensors and of the [C] state vectors: fp32, or bf16 (the upper half of an
 // fp32; widened exactly on load, rounded to nearest even on store).  Arithmetic is the same either way.
-enum IoType { IO_F32 = 0, IO_BF16 = 1 };
+// IO_BF16 keeps the rows packed in registers between the load and the store (the plain recurrence);
+// IO_BF16W widens them on load, for the gated forms, whose register tile holds computed fp32 values.
+enum IoType { IO_F32 = 0, IO_BF16 = 1, IO_BF16W = 2 };
 
 template <int VEC_, int R_, int WC_, int WT_, int IO_ = IO_F32>
 struct Geo {
@@ -341,7 +343,7 @@ using row_t = typename RowSel<G::VEC, G::IO>::type;
 template <class G>
 __device__ __forceinline__ vec<G::VEC> unpack(row_t<G> w)
 {
-    if constexpr (G::IO == IO_F32) {
+    if constexpr (G::IO != IO_BF16) {
         return w;
     } else {
         vec<G::VEC> v;
@@ -356,7 +358,7 @@ __device__ __forceinline__ vec<G::VEC> unpack(row_t<G> w)
 template <class G>
 __device__ __forceinline__ row_t<G> pack(vec<G::VEC> v)
 {
-    if constexpr (G::IO == IO_F32) {
+    if constexpr (G::IO != IO_BF16) {
         return v;
     } else {
         row_t<G> w;
@@ -385,7 +387,7 @@ __device__ __forceinline__ row_t<G> reread(row_t<G> w)
 template <class G>
 __device__ __forceinline__ row_t<G> row_const(float x)
 {
-    if constexpr (G::IO == IO_F32) {
+    if constexpr (G::IO != IO_BF16) {
         return splat<G::VEC>(x);
     } else {
         const unsigned int b = __float_as_uint(x);
@@ -395,8 +397,8 @@ __device__ __forceinline__ row_t<G> row_const(float x)
 template <class G>
 __device__ __forceinline__ row_t<G> rld(rsrc_t rs, uint32_t voff, uint32_t soff)
 {
-    if constexpr (G::IO == IO_F32) {
-        return buf_ld<G::VEC>(rs, voff, soff);
+    if constexpr (G::IO != IO_BF16) {
+        return gld<G>(rs, voff, soff);
     } else if constexpr (G::VEC == 4) {
         return __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soff, LINREC_NT_LOAD ? kBufNT : 0);
     } else {
@@ -408,6 +410,8 @@ __device__ __forceinline__ void rst(rsrc_t rs, uint32_t voff, uint32_t soff, row
 {
     if constexpr (G::IO == IO_F32) {
         buf_st<G::VEC>(rs, voff, soff, w);
+    } else if constexpr (G::IO == IO_BF16W) {
+        gst<G>(rs, voff, soff, w);
     } else if constexpr (G::VEC == 4) {
         __builtin_amdgcn_raw_buffer_store_b64(w, rs, voff, soff, LINREC_NT_STORE ? kBufNT : 0);
     } else {

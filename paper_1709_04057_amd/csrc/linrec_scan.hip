@@ -174,27 +174,41 @@ __global__ void k_fill16(unsigned short *p, int64_t n)
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
+// Element access of the serial form kernels in either storage type (E = float, or unsigned short for bf16).
+template <class E>
+__device__ __forceinline__ float el_in(const E *p, int64_t i)
+{
+    if constexpr (sizeof(E) == 4) return p[i];
+    else return bf16_in(p, i);
+}
+template <class E>
+__device__ __forceinline__ void el_out(E *p, int64_t i, float v)
+{
+    if constexpr (sizeof(E) == 4) p[i] = v;
+    else bf16_out(p, i, v);
+}
+
 // The gated form of Section 3.1 (sigmoid and tau applied here), serial over the sequence length.
-__global__ __launch_bounds__(256) void k_serial_gated_fwd(const float *__restrict__ g_pre, const float *i_pre,
-                                                          const float *__restrict__ h0, float *out, int tau, int64_t T,
-                                                          int64_t C)
+template <class E>
+__global__ __launch_bounds__(256) void k_serial_gated_fwd(const E *__restrict__ g_pre, const E *i_pre,
+                                                          const E *__restrict__ h0, E *out, int tau, int64_t T, int64_t C)
 {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
-    float s = h0 ? h0[c] : 0.0f;
+    float s = h0 ? el_in(h0, c) : 0.0f;
 #pragma unroll 4
     for (int64_t t = 0; t < T; ++t) {
-        const vec<1> cm = gate_complement<1>(vec<1>(g_pre[t * C + c]));
-        const vec<1> i = impulse<1>(vec<1>(i_pre[t * C + c]), tau);
+        const vec<1> cm = gate_complement<1>(vec<1>(el_in(g_pre, t * C + c)));
+        const vec<1> i = impulse<1>(vec<1>(el_in(i_pre, t * C + c)), tau);
         s = step<FORM_GATED, 1>(cm, vec<1>(s), cm * i)[0];
-        out[t * C + c] = s;
+        el_out(out, t * C + c, s);
     }
 }
 
-__global__ __launch_bounds__(256) void k_serial_gated_bwd(const float *__restrict__ g_pre,
-                                                          const float *__restrict__ i_pre, const float *__restrict__ h,
-                                                          const float *__restrict__ h0, const float *e, float *gg,
-                                                          float *gi, float *gh0, int tau, int64_t T, int64_t C)
+template <class E>
+__global__ __launch_bounds__(256) void k_serial_gated_bwd(const E *__restrict__ g_pre, const E *__restrict__ i_pre,
+                                                          const E *__restrict__ h, const E *__restrict__ h0, const E *e,
+                                                          E *gg, E *gi, E *gh0, int tau, int64_t T, int64_t C)
 {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
@@ -203,65 +217,66 @@ __global__ __launch_bounds__(256) void k_serial_gated_bwd(const float *__restric
     float g0 = 0.0f;
 #pragma unroll 2
     for (int64_t t = T - 1; t >= 0; --t) {
-        d = step<FORM_GATED, 1>(vec<1>(cnext), vec<1>(d), vec<1>(e[t * C + c]))[0];
-        const float cm = gate_complement<1>(vec<1>(g_pre[t * C + c]))[0];
+        d = step<FORM_GATED, 1>(vec<1>(cnext), vec<1>(d), vec<1>(el_in(e, t * C + c)))[0];
+        const float cm = gate_complement<1>(vec<1>(el_in(g_pre, t * C + c)))[0];
         const float g = 1.0f - cm;
-        const float i = impulse<1>(vec<1>(i_pre[t * C + c]), tau)[0];
-        const float hp = (t > 0) ? h[(t - 1) * C + c] : (h0 ? h0[c] : 0.0f);
-        if (gg) gg[t * C + c] = d * (hp - i) * (g * cm);
-        if (gi) gi[t * C + c] = tau ? d * cm * fmaf(-i, i, 1.0f) : d * cm;
+        const float i = impulse<1>(vec<1>(el_in(i_pre, t * C + c)), tau)[0];
+        const float hp = (t > 0) ? el_in(h, (t - 1) * C + c) : (h0 ? el_in(h0, c) : 0.0f);
+        if (gg) el_out(gg, t * C + c, d * (hp - i) * (g * cm));
+        if (gi) el_out(gi, t * C + c, tau ? d * cm * fmaf(-i, i, 1.0f) : d * cm);
         cnext = cm;
         g0 = g;
     }
-    if (gh0) gh0[c] = g0 * d;
+    if (gh0) el_out(gh0, c, g0 * d);
 }
 
 // The LSTM cell of Section 3.2 (c_t = f_t*c_{t-1} + i_t*z_t, h_t = o_t*c_t), serial over the sequence length.
-__global__ __launch_bounds__(256) void k_serial_lstm_fwd(const float *__restrict__ f_pre, const float *__restrict__ i_pre,
-                                                         const float *__restrict__ z_pre, const float *__restrict__ o_pre,
-                                                         const float *__restrict__ c0, float *c_out, float *h_out,
-                                                         int64_t T, int64_t C)
+template <class E>
+__global__ __launch_bounds__(256) void k_serial_lstm_fwd(const E *__restrict__ f_pre, const E *__restrict__ i_pre,
+                                                         const E *__restrict__ z_pre, const E *__restrict__ o_pre,
+                                                         const E *__restrict__ c0, E *c_out, E *h_out, int64_t T, int64_t C)
 {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
-    float s = c0 ? c0[c] : 0.0f;
+    float s = c0 ? el_in(c0, c) : 0.0f;
 #pragma unroll 2
     for (int64_t t = 0; t < T; ++t) {
-        const vec<1> cf = gate_complement<1>(vec<1>(f_pre[t * C + c]));
-        const vec<1> x = gate_value<1>(vec<1>(i_pre[t * C + c])) * impulse<1>(vec<1>(z_pre[t * C + c]), 1);
+        const vec<1> cf = gate_complement<1>(vec<1>(el_in(f_pre, t * C + c)));
+        const vec<1> x = gate_value<1>(vec<1>(el_in(i_pre, t * C + c))) * impulse<1>(vec<1>(el_in(z_pre, t * C + c)), 1);
         s = step<FORM_LSTM, 1>(cf, vec<1>(s), x)[0];
-        if (c_out) c_out[t * C + c] = s;
-        if (h_out) h_out[t * C + c] = gate_value<1>(vec<1>(o_pre[t * C + c]))[0] * s;
+        if (c_out) el_out(c_out, t * C + c, s);
+        if (h_out) el_out(h_out, t * C + c, gate_value<1>(vec<1>(el_in(o_pre, t * C + c)))[0] * s);
     }
 }
 
-__global__ __launch_bounds__(256) void k_serial_lstm_bwd(const float *__restrict__ f_pre, const float *__restrict__ i_pre,
-                                                         const float *__restrict__ z_pre, const float *__restrict__ o_pre,
-                                                         const float *__restrict__ cst, const float *__restrict__ c0,
-                                                         const float *__restrict__ e, float *gf, float *gi, float *gz,
-                                                         float *go, float *gc0, int64_t T, int64_t C)
+template <class E>
+__global__ __launch_bounds__(256) void k_serial_lstm_bwd(const E *__restrict__ f_pre, const E *__restrict__ i_pre,
+                                                         const E *__restrict__ z_pre, const E *__restrict__ o_pre,
+                                                         const E *__restrict__ cst, const E *__restrict__ c0,
+                                                         const E *__restrict__ e, E *gf, E *gi, E *gz, E *go, E *gc0,
+                                                         int64_t T, int64_t C)
 {
     const int64_t c = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (c >= C) return;
     float d = 0.0f, cnext = 1.0f, f0 = 0.0f;  // cnext: complement of the forget gate one row ahead
     for (int64_t t = T - 1; t >= 0; --t) {
         vec<1> og, oc, ig, ic;
-        gate_both<1>(vec<1>(o_pre[t * C + c]), og, oc);
-        gate_both<1>(vec<1>(i_pre[t * C + c]), ig, ic);
-        const float et = e[t * C + c];
+        gate_both<1>(vec<1>(el_in(o_pre, t * C + c)), og, oc);
+        gate_both<1>(vec<1>(el_in(i_pre, t * C + c)), ig, ic);
+        const float et = el_in(e, t * C + c);
         d = step<FORM_LSTM, 1>(vec<1>(cnext), vec<1>(d), vec<1>(et * og[0]))[0];
-        const float cf = gate_complement<1>(vec<1>(f_pre[t * C + c]))[0];
+        const float cf = gate_complement<1>(vec<1>(el_in(f_pre, t * C + c)))[0];
         const float f = 1.0f - cf;
-        const float z = tanh_f32(z_pre[t * C + c]);
-        const float cp = (t > 0) ? cst[(t - 1) * C + c] : (c0 ? c0[c] : 0.0f);
-        if (gf) gf[t * C + c] = d * cp * (f * cf);
-        if (gi) gi[t * C + c] = d * z * (ig[0] * ic[0]);
-        if (gz) gz[t * C + c] = d * ig[0] * fmaf(-z, z, 1.0f);
-        if (go) go[t * C + c] = et * cst[t * C + c] * (og[0] * oc[0]);
+        const float z = tanh_f32(el_in(z_pre, t * C + c));
+        const float cp = (t > 0) ? el_in(cst, (t - 1) * C + c) : (c0 ? el_in(c0, c) : 0.0f);
+        if (gf) el_out(gf, t * C + c, d * cp * (f * cf));
+        if (gi) el_out(gi, t * C + c, d * z * (ig[0] * ic[0]));
+        if (gz) el_out(gz, t * C + c, d * ig[0] * fmaf(-z, z, 1.0f));
+        if (go) el_out(go, t * C + c, et * el_in(cst, t * C + c) * (og[0] * oc[0]));
         cnext = cf;
         f0 = f;
     }
-    if (gc0) gc0[c] = f0 * d;
+    if (gc0) el_out(gc0, c, f0 * d);
 }
 
 __global__ void k_fill(float *p, float value, int64_t n)
@@ -318,11 +333,36 @@ hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const f
     return hipGetLastError();
 }
 
+template <class E>
+static hipError_t launch_serial_form(const Args &A, bool bwd, int form, unsigned grid, hipStream_t s)
+{
+    typedef const E *cp;
+    typedef E *mp;
+    if (form == FORM_LSTM) {
+        if (!bwd)
+            hipLaunchKernelGGL(k_serial_lstm_fwd<E>, dim3(grid), dim3(256), 0, s, (cp)A.a, (cp)A.b, (cp)A.c, (cp)A.d,
+                               (cp)A.h0, (mp)A.out0, (mp)A.out1, A.T, A.C);
+        else
+            hipLaunchKernelGGL(k_serial_lstm_bwd<E>, dim3(grid), dim3(256), 0, s, (cp)A.a, (cp)A.c, (cp)A.d, (cp)A.e,
+                               (cp)A.hprev, (cp)A.h0, (cp)A.b, (mp)A.out0, (mp)A.out1, (mp)A.out2, (mp)A.out3, (mp)A.gh0,
+                               A.T, A.C);
+    } else {
+        if (!bwd)
+            hipLaunchKernelGGL(k_serial_gated_fwd<E>, dim3(grid), dim3(256), 0, s, (cp)A.a, (cp)A.b, (cp)A.h0, (mp)A.out0,
+                               A.tau, A.T, A.C);
+        else
+            hipLaunchKernelGGL(k_serial_gated_bwd<E>, dim3(grid), dim3(256), 0, s, (cp)A.a, (cp)A.c, (cp)A.hprev, (cp)A.h0,
+                               (cp)A.b, (mp)A.out0, (mp)A.out1, (mp)A.gh0, A.tau, A.T, A.C);
+    }
+    return hipGetLastError();
+}
+
 hipError_t launch_serial(const Args &A, bool bwd, int form, bool bf16, hipStream_t s)
 {
     const unsigned grid = (unsigned)((A.C + 255) / 256);
+    if (form != FORM_PLAIN)
+        return bf16 ? launch_serial_form<unsigned short>(A, bwd, form, grid, s) : launch_serial_form<float>(A, bwd, form, grid, s);
     if (bf16) {
-        if (form != FORM_PLAIN) return hipErrorInvalidValue;
         typedef const unsigned short *cp;
         typedef unsigned short *mp;
         if (!bwd)
@@ -331,23 +371,6 @@ hipError_t launch_serial(const Args &A, bool bwd, int form, bool bf16, hipStream
         else
             hipLaunchKernelGGL(k_serial_bwd_bf16, dim3(grid), dim3(256), 0, s, (cp)A.a, (cp)A.hprev, (cp)A.h0, (cp)A.b,
                                (mp)A.out0, (mp)A.out1, (mp)A.gh0, A.T, A.C);
-        return hipGetLastError();
-    }
-    if (form == FORM_LSTM) {
-        if (!bwd)
-            hipLaunchKernelGGL(k_serial_lstm_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.c, A.d, A.h0, A.out0, A.out1, A.T,
-                               A.C);
-        else
-            hipLaunchKernelGGL(k_serial_lstm_bwd, dim3(grid), dim3(256), 0, s, A.a, A.c, A.d, A.e, A.hprev, A.h0, A.b,
-                               A.out0, A.out1, A.out2, A.out3, A.gh0, A.T, A.C);
-        return hipGetLastError();
-    }
-    if (form == FORM_GATED) {
-        if (!bwd)
-            hipLaunchKernelGGL(k_serial_gated_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.h0, A.out0, A.tau, A.T, A.C);
-        else
-            hipLaunchKernelGGL(k_serial_gated_bwd, dim3(grid), dim3(256), 0, s, A.a, A.c, A.hprev, A.h0, A.b, A.out0,
-                               A.out1, A.gh0, A.tau, A.T, A.C);
         return hipGetLastError();
     }
     if (!bwd) hipLaunchKernelGGL(k_serial_fwd, dim3(grid), dim3(256), 0, s, A.a, A.b, A.h0, A.out0, A.T, A.C);

@@ -46,11 +46,13 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
     //   gated layer        look-back and walk kernels of the shapes with 8k (or fewer than 8) rows per thread
     //                      (the epilogues work in chunks of 8 rows)
     //   LSTM cell          the same, of at most 32 elements per thread and operand (three operands in flight)
+    //   both on bf16       the same shapes among those with 2 or 4 columns per thread (the register tile holds
+    //   storage            computed fp32 values, so the limits are those of fp32 storage)
     constexpr bool kHasF32 = G::R * G::VEC <= 64, kHasBf16 = G::VEC >= 2;
     constexpr bool kHasGated = kHasF32 && (G::R % 8 == 0 || G::R < 8), kHasLstm = kHasGated && G::R * G::VEC <= 32;
     if (form < FORM_PLAIN || form > FORM_LSTM) return hipErrorInvalidValue;
     if ((form != FORM_PLAIN || bf16) && kind != KIND_LOOKBACK && kind != KIND_WALK) return hipErrorInvalidValue;
-    if (bf16 ? (!kHasBf16 || form != FORM_PLAIN) : !kHasF32) return hipErrorInvalidValue;
+    if (bf16 ? !kHasBf16 : !kHasF32) return hipErrorInvalidValue;
     if ((form == FORM_GATED && !kHasGated) || (form == FORM_LSTM && !kHasLstm)) return hipErrorInvalidValue;
     void (*kern)(const Args) = nullptr;
     if constexpr (kHasF32) {
@@ -76,14 +78,26 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
                               : (bwd ? k_lookback<GB, true, false> : k_lookback<GB, false, false>);
     }
     if constexpr (kHasGated) {
-        if (form == FORM_GATED)
+        if (form == FORM_GATED && !bf16)
             kern = walk ? (bwd ? k_walk<G, true, FORM_GATED> : k_walk<G, false, FORM_GATED>)
                         : (bwd ? k_lookback<G, true, true, FORM_GATED> : k_lookback<G, false, false, FORM_GATED>);
     }
     if constexpr (kHasLstm) {
-        if (form == FORM_LSTM)
+        if (form == FORM_LSTM && !bf16)
             kern = walk ? (bwd ? k_walk<G, true, FORM_LSTM> : k_walk<G, false, FORM_LSTM>)
                         : (bwd ? k_lookback<G, true, true, FORM_LSTM> : k_lookback<G, false, false, FORM_LSTM>);
+    }
+    if constexpr (kHasGated && kHasBf16) {
+        using GW = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16W>;
+        if (form == FORM_GATED && bf16)
+            kern = walk ? (bwd ? k_walk<GW, true, FORM_GATED> : k_walk<GW, false, FORM_GATED>)
+                        : (bwd ? k_lookback<GW, true, true, FORM_GATED> : k_lookback<GW, false, false, FORM_GATED>);
+    }
+    if constexpr (kHasLstm && kHasBf16) {
+        using GW = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16W>;
+        if (form == FORM_LSTM && bf16)
+            kern = walk ? (bwd ? k_walk<GW, true, FORM_LSTM> : k_walk<GW, false, FORM_LSTM>)
+                        : (bwd ? k_lookback<GW, true, true, FORM_LSTM> : k_lookback<GW, false, false, FORM_LSTM>);
     }
     if (!kern) return hipErrorInvalidValue;
     if (walk) {  // one workgroup per column group

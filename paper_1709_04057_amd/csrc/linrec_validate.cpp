@@ -97,17 +97,30 @@ extern "C" int linrec_validate_backward_bf16(const uint16_t *lambda, const uint1
     return validate_backward(lambda, h, h0, grad_h, grad_x, grad_lambda, grad_h0, T, B, n, sizeof(uint16_t));
 }
 
-extern "C" int linrec_validate_gilr_forward(const float *g_pre, const float *i_pre, const float *h0,
-                                            const float *h_out, int tau, int64_t T, int64_t B, int64_t n)
+// No output of these entry points may share memory with any other tensor of the call.
+static int check_disjoint(const void *const *outs, const int64_t *out_len, int n_out, const void *const *ins,
+                          const int64_t *in_len, int n_in, size_t es)
+{
+    for (int o = 0; o < n_out; ++o) {
+        for (int i = 0; i < n_in; ++i)
+            if (overlaps(outs[o], out_len[o], ins[i], in_len[i], es)) return LINREC_ERR_ALIAS;
+        for (int p = o + 1; p < n_out; ++p)
+            if (overlaps(outs[o], out_len[o], outs[p], out_len[p], es)) return LINREC_ERR_ALIAS;
+    }
+    return LINREC_OK;
+}
+
+static int validate_gilr_forward(const void *g_pre, const void *i_pre, const void *h0, const void *h_out, int tau,
+                                 int64_t T, int64_t B, int64_t n, size_t es)
 {
     if (tau != LINREC_TAU_IDENTITY && tau != LINREC_TAU_TANH) return LINREC_ERR_OPTION;
     // same shapes, NULL rules and aliasing as the plain forward pass (h_out may be i_pre itself)
-    return linrec_validate_forward(g_pre, i_pre, h0, h_out, T, B, n);
+    return validate_forward(g_pre, i_pre, h0, h_out, T, B, n, es);
 }
 
-extern "C" int linrec_validate_gilr_backward(const float *g_pre, const float *i_pre, const float *h, const float *h0,
-                                             const float *grad_h, const float *grad_g_pre, const float *grad_i_pre,
-                                             const float *grad_h0, int tau, int64_t T, int64_t B, int64_t n)
+static int validate_gilr_backward(const void *g_pre, const void *i_pre, const void *h, const void *h0,
+                                  const void *grad_h, const void *grad_g_pre, const void *grad_i_pre,
+                                  const void *grad_h0, int tau, int64_t T, int64_t B, int64_t n, size_t es)
 {
     if (tau != LINREC_TAU_IDENTITY && tau != LINREC_TAU_TANH) return LINREC_ERR_OPTION;
     int64_t C, E;
@@ -116,45 +129,62 @@ extern "C" int linrec_validate_gilr_backward(const float *g_pre, const float *i_
     if (!g_pre || !i_pre || !h || !grad_h) return LINREC_ERR_NULL;
     // A tile reads rows of g_pre and h that belong to its neighbours, so no output may share memory
     // with any input, nor with another output.
-    const float *outs[3] = {grad_g_pre, grad_i_pre, grad_h0};
+    const void *outs[3] = {grad_g_pre, grad_i_pre, grad_h0};
     const int64_t out_len[3] = {E, E, C};
-    const float *ins[5] = {g_pre, i_pre, h, grad_h, h0};
+    const void *ins[5] = {g_pre, i_pre, h, grad_h, h0};
     const int64_t in_len[5] = {E, E, E, E, C};
-    for (int o = 0; o < 3; ++o) {
-        for (int i = 0; i < 5; ++i)
-            if (overlaps(outs[o], out_len[o], ins[i], in_len[i])) return LINREC_ERR_ALIAS;
-        for (int p = o + 1; p < 3; ++p)
-            if (overlaps(outs[o], out_len[o], outs[p], out_len[p])) return LINREC_ERR_ALIAS;
-    }
-    return LINREC_OK;
+    return check_disjoint(outs, out_len, 3, ins, in_len, 5, es);
 }
 
-// No output of the cell entry points may share memory with any other tensor of the call.
-static int check_disjoint(const float *const *outs, const int64_t *out_len, int n_out, const float *const *ins,
-                          const int64_t *in_len, int n_in)
+static int validate_lstm_cell_forward(const void *f_pre, const void *i_pre, const void *z_pre, const void *o_pre,
+                                      const void *c0, const void *c_out, const void *h_out, int64_t T, int64_t B,
+                                      int64_t n, size_t es)
 {
-    for (int o = 0; o < n_out; ++o) {
-        for (int i = 0; i < n_in; ++i)
-            if (overlaps(outs[o], out_len[o], ins[i], in_len[i])) return LINREC_ERR_ALIAS;
-        for (int p = o + 1; p < n_out; ++p)
-            if (overlaps(outs[o], out_len[o], outs[p], out_len[p])) return LINREC_ERR_ALIAS;
-    }
-    return LINREC_OK;
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (E == 0) return LINREC_OK;
+    if (!f_pre || !i_pre || !z_pre || (h_out && !o_pre) || (!c_out && !h_out)) return LINREC_ERR_NULL;
+    const void *outs[2] = {c_out, h_out};
+    const int64_t out_len[2] = {E, E};
+    const void *ins[5] = {f_pre, i_pre, z_pre, o_pre, c0};
+    const int64_t in_len[5] = {E, E, E, E, C};
+    return check_disjoint(outs, out_len, 2, ins, in_len, 5, es);
+}
+
+static int validate_lstm_cell_backward(const void *f_pre, const void *i_pre, const void *z_pre, const void *o_pre,
+                                       const void *c, const void *c0, const void *grad_h, const void *grad_f_pre,
+                                       const void *grad_i_pre, const void *grad_z_pre, const void *grad_o_pre,
+                                       const void *grad_c0, int64_t T, int64_t B, int64_t n, size_t es)
+{
+    int64_t C, E;
+    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
+    if (C == 0 || T == 0) return LINREC_OK;
+    if (!f_pre || !i_pre || !z_pre || !o_pre || !c || !grad_h) return LINREC_ERR_NULL;
+    const void *outs[5] = {grad_f_pre, grad_i_pre, grad_z_pre, grad_o_pre, grad_c0};
+    const int64_t out_len[5] = {E, E, E, E, C};
+    const void *ins[7] = {f_pre, i_pre, z_pre, o_pre, c, grad_h, c0};
+    const int64_t in_len[7] = {E, E, E, E, E, E, C};
+    return check_disjoint(outs, out_len, 5, ins, in_len, 7, es);
+}
+
+extern "C" int linrec_validate_gilr_forward(const float *g_pre, const float *i_pre, const float *h0,
+                                            const float *h_out, int tau, int64_t T, int64_t B, int64_t n)
+{
+    return validate_gilr_forward(g_pre, i_pre, h0, h_out, tau, T, B, n, sizeof(float));
+}
+
+extern "C" int linrec_validate_gilr_backward(const float *g_pre, const float *i_pre, const float *h, const float *h0,
+                                             const float *grad_h, const float *grad_g_pre, const float *grad_i_pre,
+                                             const float *grad_h0, int tau, int64_t T, int64_t B, int64_t n)
+{
+    return validate_gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0, tau, T, B, n, sizeof(float));
 }
 
 extern "C" int linrec_validate_lstm_cell_forward(const float *f_pre, const float *i_pre, const float *z_pre,
                                                  const float *o_pre, const float *c0, const float *c_out,
                                                  const float *h_out, int64_t T, int64_t B, int64_t n)
 {
-    int64_t C, E;
-    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
-    if (E == 0) return LINREC_OK;
-    if (!f_pre || !i_pre || !z_pre || (h_out && !o_pre) || (!c_out && !h_out)) return LINREC_ERR_NULL;
-    const float *outs[2] = {c_out, h_out};
-    const int64_t out_len[2] = {E, E};
-    const float *ins[5] = {f_pre, i_pre, z_pre, o_pre, c0};
-    const int64_t in_len[5] = {E, E, E, E, C};
-    return check_disjoint(outs, out_len, 2, ins, in_len, 5);
+    return validate_lstm_cell_forward(f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out, T, B, n, sizeof(float));
 }
 
 extern "C" int linrec_validate_lstm_cell_backward(const float *f_pre, const float *i_pre, const float *z_pre,
@@ -164,15 +194,42 @@ extern "C" int linrec_validate_lstm_cell_backward(const float *f_pre, const floa
                                                   const float *grad_o_pre, const float *grad_c0, int64_t T, int64_t B,
                                                   int64_t n)
 {
-    int64_t C, E;
-    if (!shape_ok(T, B, n, &C, &E)) return LINREC_ERR_SHAPE;
-    if (C == 0 || T == 0) return LINREC_OK;
-    if (!f_pre || !i_pre || !z_pre || !o_pre || !c || !grad_h) return LINREC_ERR_NULL;
-    const float *outs[5] = {grad_f_pre, grad_i_pre, grad_z_pre, grad_o_pre, grad_c0};
-    const int64_t out_len[5] = {E, E, E, E, C};
-    const float *ins[7] = {f_pre, i_pre, z_pre, o_pre, c, grad_h, c0};
-    const int64_t in_len[7] = {E, E, E, E, E, E, C};
-    return check_disjoint(outs, out_len, 5, ins, in_len, 7);
+    return validate_lstm_cell_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre, grad_z_pre,
+                                       grad_o_pre, grad_c0, T, B, n, sizeof(float));
+}
+
+extern "C" int linrec_validate_gilr_forward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h0,
+                                                 const uint16_t *h_out, int tau, int64_t T, int64_t B, int64_t n)
+{
+    return validate_gilr_forward(g_pre, i_pre, h0, h_out, tau, T, B, n, sizeof(uint16_t));
+}
+
+extern "C" int linrec_validate_gilr_backward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h,
+                                                  const uint16_t *h0, const uint16_t *grad_h,
+                                                  const uint16_t *grad_g_pre, const uint16_t *grad_i_pre,
+                                                  const uint16_t *grad_h0, int tau, int64_t T, int64_t B, int64_t n)
+{
+    return validate_gilr_backward(g_pre, i_pre, h, h0, grad_h, grad_g_pre, grad_i_pre, grad_h0, tau, T, B, n,
+                                  sizeof(uint16_t));
+}
+
+extern "C" int linrec_validate_lstm_cell_forward_bf16(const uint16_t *f_pre, const uint16_t *i_pre,
+                                                      const uint16_t *z_pre, const uint16_t *o_pre, const uint16_t *c0,
+                                                      const uint16_t *c_out, const uint16_t *h_out, int64_t T,
+                                                      int64_t B, int64_t n)
+{
+    return validate_lstm_cell_forward(f_pre, i_pre, z_pre, o_pre, c0, c_out, h_out, T, B, n, sizeof(uint16_t));
+}
+
+extern "C" int linrec_validate_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_t *i_pre,
+                                                       const uint16_t *z_pre, const uint16_t *o_pre, const uint16_t *c,
+                                                       const uint16_t *c0, const uint16_t *grad_h,
+                                                       const uint16_t *grad_f_pre, const uint16_t *grad_i_pre,
+                                                       const uint16_t *grad_z_pre, const uint16_t *grad_o_pre,
+                                                       const uint16_t *grad_c0, int64_t T, int64_t B, int64_t n)
+{
+    return validate_lstm_cell_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, grad_f_pre, grad_i_pre, grad_z_pre,
+                                       grad_o_pre, grad_c0, T, B, n, sizeof(uint16_t));
 }
 
 extern "C" const char *linrec_status_string(int status)
@@ -189,4 +246,4 @@ extern "C" const char *linrec_status_string(int status)
     }
 }
 
-extern "C" int linrec_version(void) { return 103; }
+extern "C" int linrec_version(void) { return 104; }

@@ -86,8 +86,9 @@ def test_validate_bf16(L):
     assert L.linrec_backward_bf16(None, None, None, None, None, None, None, 10, 0, 2, None) == 0
 
 
-def test_validate_gilr(L):
-    vf, vb = L.linrec_validate_gilr_forward, L.linrec_validate_gilr_backward
+@pytest.mark.parametrize("suffix", ["", "_bf16"])
+def test_validate_gilr(L, suffix):
+    vf, vb = getattr(L, "linrec_validate_gilr_forward" + suffix), getattr(L, "linrec_validate_gilr_backward" + suffix)
     assert vf(_p(A0), _p(A1), _p(A2), _p(A3), 1, 1000, 4, 8) == 0
     assert vf(_p(A0), _p(A1), None, _p(A1), 0, 1000, 4, 8) == 0            # h_out in place on i_pre
     assert vf(_p(A0), _p(A1), None, _p(A0), 1, 1000, 4, 8) == -3           # h_out on g_pre
@@ -104,12 +105,17 @@ def test_validate_gilr(L):
     assert vb(_p(A0), _p(A1), _p(A2), None, _p(A4), _p(A5), _p(A5), None, 1, 1000, 4, 8) == -3  # outputs share memory
     assert vb(_p(A0), _p(A1), _p(A2), None, _p(A4), _p(A5), _p(A1), None, 1, 1000, 4, 8) == -3  # output on i_pre
     assert vb(*ok, 1, 1000, -4, 8) == -2
-    assert L.linrec_gilr_forward(_p(A0), _p(A1), None, _p(A0), 1, 10, 2, 2, None) == -3      # before any HIP call
-    assert L.linrec_gilr_backward(None, None, None, None, None, None, None, None, 1, 10, 0, 2, None) == 0
+    # an output that starts where a 1000 x 4 x 8 input ends: 2 bytes per element with bf16 storage, 4 with fp32
+    end16 = _p(A0 + 1000 * 4 * 8 * 2)
+    assert vf(_p(A0), _p(A1), None, end16, 1, 1000, 4, 8) == (0 if suffix else -3)
+    assert getattr(L, "linrec_gilr_forward" + suffix)(_p(A0), _p(A1), None, _p(A0), 1, 10, 2, 2, None) == -3   # before any HIP call
+    assert getattr(L, "linrec_gilr_backward" + suffix)(None, None, None, None, None, None, None, None, 1, 10, 0, 2, None) == 0
 
 
-def test_validate_lstm_cell(L):
-    vf, vb = L.linrec_validate_lstm_cell_forward, L.linrec_validate_lstm_cell_backward
+@pytest.mark.parametrize("suffix", ["", "_bf16"])
+def test_validate_lstm_cell(L, suffix):
+    vf = getattr(L, "linrec_validate_lstm_cell_forward" + suffix)
+    vb = getattr(L, "linrec_validate_lstm_cell_backward" + suffix)
     B0 = [0x10000000 + i * 0x1000000 for i in range(13)]
     P = [_p(a) for a in B0]
     assert vf(P[0], P[1], P[2], P[3], P[4], P[5], P[6], 1000, 4, 8) == 0
@@ -129,8 +135,10 @@ def test_validate_lstm_cell(L):
     assert vb(*P[:7], P[6], None, None, None, None, 1000, 4, 8) == -3          # output on grad_h
     assert vb(*P[:7], P[7], P[7], None, None, None, 1000, 4, 8) == -3          # outputs share memory
     assert vb(*P[:7], P[7], P[8], P[9], P[4], None, 1000, 4, 8) == -3          # output on the cell state
-    assert L.linrec_lstm_cell_forward(P[0], P[1], P[2], P[3], None, P[0], P[6], 10, 2, 2, None) == -3
-    assert L.linrec_lstm_cell_backward(*([None] * 12), 10, 0, 2, None) == 0
+    end16 = _p(B0[0] + 1000 * 4 * 8 * 2)   # where a bf16 f_pre ends (an fp32 one is twice as long)
+    assert vf(P[0], P[1], P[2], P[3], None, end16, P[6], 1000, 4, 8) == (0 if suffix else -3)
+    assert getattr(L, "linrec_lstm_cell_forward" + suffix)(P[0], P[1], P[2], P[3], None, P[0], P[6], 10, 2, 2, None) == -3
+    assert getattr(L, "linrec_lstm_cell_backward" + suffix)(*([None] * 12), 10, 0, 2, None) == 0
 
 
 def test_entry_points_validate_before_touching_the_gpu(L):
@@ -199,6 +207,15 @@ def test_plan_is_host_only_and_consistent(L):
                 assert v == lr.VARIANT_SERIAL            # odd number of columns: no 4-byte rows
             else:
                 assert v == lr.VARIANT_LOOKBACK and lr.linrec_tile_info(t)["cols_per_thread"] in (2, 4)
+            for fam, limit in ((lr.ENTRY_GILR_BF16, 64), (lr.ENTRY_LSTM_CELL_BF16, 32)):
+                v, t = lr.linrec_plan_for(fam, T, B, n, backward=bwd, alignment=4)
+                info = lr.linrec_tile_info(t)
+                if (B * n) % 2:
+                    assert v == lr.VARIANT_SERIAL
+                else:
+                    assert v == lr.VARIANT_LOOKBACK and info["cols_per_thread"] == 2
+                    assert info["rows_per_thread"] * info["cols_per_thread"] <= limit
+                    assert info["rows_per_thread"] % 8 == 0 or info["rows_per_thread"] < 8
             assert lr.linrec_plan_for(lr.ENTRY_PLAIN, T, B, n, backward=bwd) == lr.linrec_plan(T, B, n, backward=bwd)
     # short and wide: the plain fp32 recurrence walks (one workgroup per column group), the other
     # families and long sequences keep the single pass
@@ -207,12 +224,13 @@ def test_plan_is_host_only_and_consistent(L):
         assert lr.linrec_plan(256, 8, 1024, backward=bwd)[0] == lr.VARIANT_WALK
         assert lr.linrec_plan(65536, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
         assert lr.linrec_plan(1024, 4, 256, backward=bwd)[0] == lr.VARIANT_LOOKBACK
-        for fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16):
+        for fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16, lr.ENTRY_GILR_BF16, lr.ENTRY_LSTM_CELL_BF16):
             v, t = lr.linrec_plan_for(fam, 128, 16, 1024, backward=bwd)            # every family walks here
             info = lr.linrec_tile_info(t)
             assert v == lr.VARIANT_WALK
-            assert info["cols_per_thread"] >= 2 or fam != lr.ENTRY_BF16
-            assert fam != lr.ENTRY_LSTM_CELL or info["rows_per_thread"] * info["cols_per_thread"] <= 32
+            assert info["cols_per_thread"] >= 2 or fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL)
+            assert fam not in (lr.ENTRY_LSTM_CELL, lr.ENTRY_LSTM_CELL_BF16) or \
+                info["rows_per_thread"] * info["cols_per_thread"] <= 32
             assert lr.linrec_plan_for(fam, 16384, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
     with pytest.raises(lr.LinrecError):
         lr.linrec_plan_for(9, 10, 1, 1)
