@@ -213,7 +213,7 @@ int linrec_lstm_cell_backward(const float *f_pre, const float *i_pre, const floa
  * bytes per element for the layer, 12 / 20 for the cell.  Like linrec_forward_bf16 a bandwidth option,
  * not one of the paper's experiments (Section 2.3: fp32).  Same arguments, NULL and aliasing rules
  * as the fp32 entry points.  The backward passes consume the ROUNDED h (c) they are given.  Tensors
- * that are not 4-byte aligned, or an odd B*n, fall back to the serial kernel.
+ * that are not 4-byte aligned, or an odd B*n, use the tile shapes with 2-byte accesses.
  */
 int linrec_gilr_forward_bf16(const uint16_t *g_pre, const uint16_t *i_pre, const uint16_t *h0,
                              uint16_t *h_out, int tau, int64_t T, int64_t B, int64_t n, void *stream);

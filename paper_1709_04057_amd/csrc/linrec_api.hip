@@ -375,21 +375,43 @@ int auto_walk_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
     return vec >= 4 ? 8 : 28;
 }
 
-// First-guess shapes of the gated layer and the cell on bf16 storage (their kernels exist for the shapes
-// with two or four columns per thread; the register tile is the fp32 one, the bytes are half).
+// Shapes of the gated layer and the cell on bf16 storage (their kernels exist for the shapes with two or
+// four columns per thread; the register tile is the fp32 one, the bytes are half), from a sweep over
+// T = 256 .. 65536 x C = 256 .. 32768.  With half the bytes these kernels are limited by their arithmetic
+// (two to five activations per element), so the shapes with the most elements per thread, which spread
+// the per-tile scan and look-back over more elements, win: 64 elements per thread for the gated layer's
+// backward pass (8), 32 for the cell (4, the most it has).
 int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
 {
-    if (form == FORM_LSTM) return (vec >= 4 && C >= 2048) ? (bwd ? 4 : 3) : 15;
-    if (T < 192) return 15;
-    if (!bwd) return (T >= 8192 && C <= 2048) ? 13 : 14;
-    return (vec >= 4 && C >= 2048) ? 3 : 15;
+    const int64_t E = T * C;
+    if (vec < 2) return auto_tile_form(T, C, 1, bwd, form);  // 2-byte accesses: the one-column shapes
+    if (form == FORM_LSTM) {
+        if (vec < 4) return 15;
+        if (bwd) return C <= 512 ? (T >= 16384 ? 15 : 3) : 4;
+        if (C >= 4096) return 4;
+        if (C >= 2048) return T >= 16384 ? 15 : 3;
+        return T >= 4096 ? 15 : 3;
+    }
+    if (!bwd) {
+        // (large problems: the one-column shape with 128-byte row segments -- its 2-byte loads cost nothing
+        // that the arithmetic does not hide -- is 10-17 % ahead of the best multi-column shape)
+        if (C <= 512) return T >= 16384 ? 13 : 16;
+        return E >= ((int64_t)1 << 24) ? 21 : 16;
+    }
+    if (vec < 4) return E >= ((int64_t)1 << 23) ? 16 : 15;
+    if (E >= ((int64_t)1 << 23)) return (C <= 512 && T >= 32768) ? 7 : 8;
+    return C >= 4096 ? 4 : 3;
 }
+// The walk on bf16 storage pays only for the shortest sequences (the single pass is limited by
+// arithmetic there, not by what the walk saves): T <= 256, the gated layer's backward pass below
+// C = 32768, the cell's forward pass only.
 int auto_walk_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
 {
+    if (T > 256 || (bwd && (form == FORM_LSTM || C >= 32768))) return 0;
     // the fp32 rule's region; where it lands on a one-column shape, the two- or four-column shape of the
     // same width and height (the cell: of at most 32 elements per thread)
     const int t = auto_walk_tile_form(T, C, vec, bwd, form);
-    if (t < 1 || kTiles[t - 1].vec >= 2) return t < 1 ? 0 : t;
+    if (t < 1 || kTiles[t - 1].vec >= 2 || vec < 2) return t < 1 ? 0 : t;
     const bool cell = form == FORM_LSTM;
     switch (t) {
     case 17: case 22: case 23: return cell ? 15 : 13;   // 32 columns, 512 rows and more
@@ -482,7 +504,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && gated && kTiles[p.tile - 1].r % 8 != 0 && kTiles[p.tile - 1].r >= 8) p.tile = 0;
-    if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && kTiles[p.tile - 1].vec < 2) p.tile = 0;
+    if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && !gated && kTiles[p.tile - 1].vec < 2) p.tile = 0;
     if (p.tile >= 1 && p.tile <= NUM_TILES && (!bf16 || gated) && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 64) p.tile = 0;
     if (p.tile < 1 || p.tile > NUM_TILES) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
@@ -491,7 +513,8 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
         if (bf16) p.tile = gated ? auto_tile_form_bf16(T, C, vec, bwd, form) : auto_tile_bf16(T, C, vec, bwd);
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
-    if (bf16 && vec < 2) p.variant = LINREC_VARIANT_SERIAL;
+    // (the gated forms have one-column shapes with 2-byte accesses for those)
+    if (bf16 && !gated && vec < 2) p.variant = LINREC_VARIANT_SERIAL;
     const TileDesc &d = kTiles[p.tile - 1];
     // per-thread byte offsets inside a tile are 32-bit, tickets of a call are 31-bit
     const int64_t G = ceil_div(C, d.cols()), K = ceil_div(T, d.rows());
@@ -1109,7 +1132,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0},
                          gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 0},
                          bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 0};
-        static const int gated16_c[] = {14, 15, 13, 16, 3, 4, 7, 8, 0}, lstm16_c[] = {15, 3, 4, 5, 0};
+        static const int gated16_c[] = {21, 18, 16, 15, 13, 3, 4, 7, 8, 0}, lstm16_c[] = {15, 3, 4, 5, 18, 0};
         const int *list = form == FORM_GATED ? (bf16 ? gated16_c : gated_c) : form == FORM_LSTM ? (bf16 ? lstm16_c : lstm_c)
                                                                           : bf16 ? bf16_c : plain_c;
         // the static rule's own choice goes first, so that what is remembered is never slower than it

@@ -46,13 +46,13 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
     //   gated layer        look-back and walk kernels of the shapes with 8k (or fewer than 8) rows per thread
     //                      (the epilogues work in chunks of 8 rows)
     //   LSTM cell          the same, of at most 32 elements per thread and operand (three operands in flight)
-    //   both on bf16       the same shapes among those with 2 or 4 columns per thread (the register tile holds
-    //   storage            computed fp32 values, so the limits are those of fp32 storage)
+    //   both on bf16       the same shapes (the register tile holds computed fp32 values, so the limits are
+    //   storage            those of fp32 storage; one-column shapes make 2-byte accesses)
     constexpr bool kHasF32 = G::R * G::VEC <= 64, kHasBf16 = G::VEC >= 2;
     constexpr bool kHasGated = kHasF32 && (G::R % 8 == 0 || G::R < 8), kHasLstm = kHasGated && G::R * G::VEC <= 32;
     if (form < FORM_PLAIN || form > FORM_LSTM) return hipErrorInvalidValue;
     if ((form != FORM_PLAIN || bf16) && kind != KIND_LOOKBACK && kind != KIND_WALK) return hipErrorInvalidValue;
-    if (bf16 ? !kHasBf16 : !kHasF32) return hipErrorInvalidValue;
+    if (bf16 ? (form == FORM_PLAIN ? !kHasBf16 : !kHasF32) : !kHasF32) return hipErrorInvalidValue;
     if ((form == FORM_GATED && !kHasGated) || (form == FORM_LSTM && !kHasLstm)) return hipErrorInvalidValue;
     void (*kern)(const Args) = nullptr;
     if constexpr (kHasF32) {
@@ -87,13 +87,13 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
             kern = walk ? (bwd ? k_walk<G, true, FORM_LSTM> : k_walk<G, false, FORM_LSTM>)
                         : (bwd ? k_lookback<G, true, true, FORM_LSTM> : k_lookback<G, false, false, FORM_LSTM>);
     }
-    if constexpr (kHasGated && kHasBf16) {
+    if constexpr (kHasGated) {
         using GW = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16W>;
         if (form == FORM_GATED && bf16)
             kern = walk ? (bwd ? k_walk<GW, true, FORM_GATED> : k_walk<GW, false, FORM_GATED>)
                         : (bwd ? k_lookback<GW, true, true, FORM_GATED> : k_lookback<GW, false, false, FORM_GATED>);
     }
-    if constexpr (kHasLstm && kHasBf16) {
+    if constexpr (kHasLstm) {
         using GW = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16W>;
         if (form == FORM_LSTM && bf16)
             kern = walk ? (bwd ? k_walk<GW, true, FORM_LSTM> : k_walk<GW, false, FORM_LSTM>)
