@@ -226,6 +226,9 @@ int auto_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
     const int64_t E = T * C, n22 = ceil_div(T, 1024) * ceil_div(C, 32);  // (tiles of the tallest shape)
     const bool one_round_22 = n22 > 128 && n22 <= 256;  // one tile per compute unit
     if (bwd && E <= ((int64_t)1 << 19)) return 2;
+    // (a handful of column groups and a long sequence: the chain of tiles is what takes the time, and the
+    // tallest shape makes it shortest)
+    if (form == FORM_GATED && C <= 128 && T >= 65536) return 22;
     if (form == FORM_GATED) {
         if (!bwd) {
             if (T < 2048) return plain;

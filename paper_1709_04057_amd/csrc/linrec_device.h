@@ -628,7 +628,9 @@ __device__ __forceinline__ void local_reduce(const Rows<G> &r, dvec<G::VEC> &P, 
 #pragma unroll
     for (int j = 1; j < G::R; ++j) {
         const vec<G::VEC> a = unpack<G>(r.a[j]);
-        p *= factor<FORM, G::VEC>(a);
+        // (gated forms: p*(1 - a) as one fp64 fma, p - a*p; these kernels are short of ALU slots, not of bytes)
+        if constexpr (FORM == FORM_PLAIN) p *= factor<FORM, G::VEC>(a);
+        else p = dfma<G::VEC>(-widen<G::VEC>(a), p, p);
         s = step<FORM, G::VEC>(a, s, unpack<G>(r.b[j]));
     }
     P = p;
