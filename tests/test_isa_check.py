@@ -1,5 +1,13 @@
 """The build's check of the device assembly: a wide store must not be followed, within two wait
 states, by a vector ALU write to the registers it stores."""
+import os
+import shutil
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+
+import pytest
+
+from paper_1709_04057_amd import build as lr_build
 from paper_1709_04057_amd import isa_check
 
 STORE = "\tbuffer_store_dwordx4 v[58:61], v198, s[76:79], s4 offen nt\n"
@@ -46,3 +54,24 @@ def test_global_store_names_its_data_second():
 def test_packed_fp32_arithmetic_is_reported():
     assert len(isa_check.check_text("\tv_pk_fma_f32 v[0:1], v[2:3], v[4:5], v[6:7]\n\ts_endpgm\n")) == 1
     assert isa_check.check_text("\tv_pk_mov_b32 v[0:1], v[2:3], v[4:5]\n\tv_cvt_pk_bf16_f32 v0, v1, v2\n\ts_endpgm\n") == []
+
+
+@pytest.mark.skipif(shutil.which(lr_build.HIPCC) is None and not os.path.exists(lr_build.HIPCC), reason="needs hipcc")
+def test_the_check_finds_the_hazard_in_real_compiler_output(tmp_path):
+    """Tile 3 (four columns, 8 rows per thread) compiled to assembly twice: as the library builds it, and with the
+    pause behind the 128-bit stores of the gated forms taken out.  The first passes the check; in the second the
+    compiler schedules the next row's arithmetic into the registers just stored, and the check says so."""
+    def asm(extra, name):
+        out = str(tmp_path / name)
+        cmd = [lr_build.HIPCC] + lr_build.FLAGS + ["-DLINREC_TILE_ID=3"] + extra + [
+            "-S", "--cuda-device-only", os.path.join(lr_build.CSRC, "linrec_tiles.hip"), "-o", out]
+        p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        assert p.returncode == 0, p.stdout[-2000:]
+        with open(out) as f:
+            return f.read()
+
+    with ThreadPoolExecutor(max_workers=2) as ex:
+        good, bad = ex.map(lambda a: asm(*a), [([], "with_pause.s"), (["-DLINREC_NO_STORE_PAUSE"], "without_pause.s")])
+    assert "buffer_store_dwordx4" in good and isa_check.check_text(good, "tile 3") == []
+    found = isa_check.check_text(bad, "tile 3 without the pause")
+    assert len(found) >= 10 and all("data of the store" in m for m in found)
