@@ -512,8 +512,8 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     if (p.tile < 1 || p.tile > NUM_TILES) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
         if (gated) p.tile = auto_tile_form(T, C, vec, bwd, form);
-        if (form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 18;  // (the cell: at most 32 elements per thread and operand)
         if (bf16) p.tile = gated ? auto_tile_form_bf16(T, C, vec, bwd, form) : auto_tile_bf16(T, C, vec, bwd);
+        if (form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 18;  // (the cell: at most 32 elements per thread and operand)
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
     // (the gated forms have one-column shapes with 2-byte accesses for those)

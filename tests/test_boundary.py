@@ -235,3 +235,22 @@ def test_plan_is_host_only_and_consistent(L):
     # a tile whose rows would not fit 32-bit offsets falls back to the serial kernel
     variant, _ = lr.linrec_plan(64, 1, 1 << 26, alignment=16)
     assert variant == lr.VARIANT_SERIAL
+
+
+def test_every_plan_of_the_gated_families_names_a_shape_their_kernels_exist_for(L):
+    """The gated layer has kernels for shapes of at most 64 elements per thread whose rows per thread are a
+    multiple of 8 (or fewer), the cell for those of at most 32; whatever the problem and the alignment, the
+    automatic plan must land on one of them, with accesses no wider than the alignment allows."""
+    for fam, limit, es in ((lr.ENTRY_GILR, 64, 4), (lr.ENTRY_LSTM_CELL, 32, 4), (lr.ENTRY_GILR_BF16, 64, 2),
+                           (lr.ENTRY_LSTM_CELL_BF16, 32, 2)):
+        for T in (1, 7, 30, 100, 300, 1000, 5078, 20000, 70000, 300000, 2000000):
+            for C in (1, 2, 3, 15, 16, 17, 64, 100, 128, 255, 1024, 4096, 16384, 65536):
+                for bwd in (False, True):
+                    for align in (2, 4, 8, 16):
+                        if align < es:
+                            continue
+                        _, t = lr.linrec_plan_for(fam, T, 1, C, backward=bwd, alignment=align)
+                        info = lr.linrec_tile_info(t)
+                        r, v = info["rows_per_thread"], info["cols_per_thread"]
+                        assert r * v <= limit and (r % 8 == 0 or r < 8), (fam, T, C, bwd, align, t)
+                        assert C % v == 0 and v * es <= align, (fam, T, C, bwd, align, t)

@@ -181,6 +181,9 @@ def test_staggered_start_changes_timing_only():
     cell = wl.make_lstm(T, B, n, seed=42, device=DEV)
     pre = [cell[k] for k in ("f_pre", "i_pre", "z_pre", "o_pre")]
     half = {k: (v.to(torch.bfloat16) if torch.is_tensor(v) else v) for k, v in plain.items()}
+    gated16 = {k: (v.to(torch.bfloat16) if torch.is_tensor(v) else v) for k, v in gated.items()}
+    cell16 = {k: (v.to(torch.bfloat16) if torch.is_tensor(v) else v) for k, v in cell.items()}
+    pre16 = [cell16[k] for k in ("f_pre", "i_pre", "z_pre", "o_pre")]
 
     def run_all():
         h = lr.linrec_forward(plain["lam"], plain["x"], plain["h0"])
@@ -191,6 +194,10 @@ def test_staggered_start_changes_timing_only():
         out += [c, hc, *lr.linrec_lstm_cell_backward(*pre, c, cell["c0"], cell["grad_h"])]
         hb = lr.linrec_forward(half["lam"], half["x"], half["h0"])
         out += [hb, *lr.linrec_backward(half["lam"], hb, half["h0"], half["grad_h"])]
+        hg16 = lr.linrec_gilr_forward(gated16["g_pre"], gated16["i_pre"], gated16["h0"])
+        out += [hg16, *lr.linrec_gilr_backward(gated16["g_pre"], gated16["i_pre"], hg16, gated16["h0"], gated16["grad_h"])]
+        c16, hc16 = lr.linrec_lstm_cell_forward(*pre16, cell16["c0"])
+        out += [c16, hc16, *lr.linrec_lstm_cell_backward(*pre16, c16, cell16["c0"], cell16["grad_h"])]
         torch.cuda.synchronize()
         lr.linrec_check()
         return out
@@ -210,6 +217,8 @@ def test_rows_too_long_for_32_bit_tile_offsets_fall_back_to_the_serial_kernel():
     from test_bf16_parity_gpu import bf16_check, to_bf16
     from test_gilr_parity_gpu import gated_check
     from test_lstm_parity_gpu import cell_check
+    from test_forms_bf16_parity_gpu import cell16_check, gated16_check
+    from test_forms_bf16_parity_gpu import to_bf16 as forms_to_bf16
 
     big = 1 << 25                           # 128 MiB rows: no tile shape can address even 32 of them
     assert lr.linrec_plan(4, 1, big)[0] == lr.VARIANT_SERIAL
@@ -219,6 +228,12 @@ def test_rows_too_long_for_32_bit_tile_offsets_fall_back_to_the_serial_kernel():
     cell_check(wl.make_lstm(4, 1, big, seed=43, device=DEV), "long rows lstm", cols=list(range(0, big, big // 64)))
     bf16_check(to_bf16(wl.make_generic(4, 1, big, seed=44, device=DEV)), "long rows bf16",
                cols=list(range(0, big, big // 64)))
+    big16 = 1 << 26                         # (2-byte elements: twice the columns for the same row length)
+    assert lr.linrec_plan_for(lr.ENTRY_GILR_BF16, 4, 1, big16)[0] == lr.VARIANT_SERIAL
+    gated16_check(forms_to_bf16(wl.make_gated(4, 1, big16, seed=45, device=DEV)), lr.TAU_TANH, "long rows gated bf16",
+                  cols=list(range(0, big16, big16 // 64)))
+    cell16_check(forms_to_bf16(wl.make_lstm(4, 1, big16, seed=46, device=DEV)), "long rows lstm bf16",
+                 cols=list(range(0, big16, big16 // 64)))
 
 
 def test_tuned_plans_of_every_family_are_used_and_correct():
@@ -228,9 +243,12 @@ def test_tuned_plans_of_every_family_are_used_and_correct():
     from test_bf16_parity_gpu import bf16_check, to_bf16
     from test_gilr_parity_gpu import gated_check
     from test_lstm_parity_gpu import cell_check
+    from test_forms_bf16_parity_gpu import cell16_check, gated16_check
+    from test_forms_bf16_parity_gpu import to_bf16 as forms_to_bf16
 
     T, B, n = 20000, 2, 96
-    for family in (lr.ENTRY_PLAIN, lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16):
+    for family in (lr.ENTRY_PLAIN, lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16, lr.ENTRY_GILR_BF16,
+                   lr.ENTRY_LSTM_CELL_BF16):
         for bwd in (False, True):
             lr.linrec_tune_for(family, T, B, n, backward=bwd)
             v, t = lr.linrec_plan_for(family, T, B, n, backward=bwd, alignment=16)
@@ -240,5 +258,7 @@ def test_tuned_plans_of_every_family_are_used_and_correct():
     gated_check(wl.make_gated(T, B, n, seed=51, device=DEV, gate_mean=1.0), lr.TAU_TANH, "tuned gated")
     cell_check(wl.make_lstm(T, B, n, seed=52, device=DEV), "tuned lstm")
     bf16_check(to_bf16(wl.make_inputs(2, T=T, B=B, n=n, device=DEV)), "tuned bf16")
+    gated16_check(forms_to_bf16(wl.make_gated(T, B, n, seed=53, device=DEV, gate_mean=1.0)), lr.TAU_TANH, "tuned gated bf16")
+    cell16_check(forms_to_bf16(wl.make_lstm(T, B, n, seed=54, device=DEV)), "tuned lstm bf16")
     with pytest.raises(lr.LinrecError):
         lr.linrec_tune_for(7, T, B, n)

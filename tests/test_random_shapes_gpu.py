@@ -11,6 +11,8 @@ from parity import all_tiles, fwd_bwd_check, options, say
 from test_bf16_parity_gpu import bf16_check, to_bf16
 from test_gilr_parity_gpu import gated_check
 from test_lstm_parity_gpu import cell_check
+from test_forms_bf16_parity_gpu import cell16_check, gated16_check
+from test_forms_bf16_parity_gpu import to_bf16 as forms_to_bf16
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -31,9 +33,10 @@ def _cases(seed, n):
         yield i, T, B, n_, opts, int(rng.integers(1 << 30))
 
 
-@pytest.mark.parametrize("entry", ["plain", "gated", "lstm", "bf16"])
+@pytest.mark.parametrize("entry", ["plain", "gated", "lstm", "bf16", "gated_bf16", "lstm_bf16"])
 def test_random_shapes_and_options(entry):
-    for i, T, B, n, opts, seed in _cases({"plain": 1, "gated": 2, "lstm": 3, "bf16": 4}[entry], 40):
+    for i, T, B, n, opts, seed in _cases({"plain": 1, "gated": 2, "lstm": 3, "bf16": 4, "gated_bf16": 5,
+                                          "lstm_bf16": 6}[entry], 40):
         label = f"{entry} #{i} T={T} B={B} n={n} {opts}"
         say(label)
         with options(**opts):
@@ -46,6 +49,13 @@ def test_random_shapes_and_options(entry):
             elif entry == "lstm":
                 cell_check(wl.make_lstm(T, B, n, seed=seed, device=DEV, forget_mean=float(seed % 4), with_c0=bool(seed & 8)),
                            label)
+            elif entry == "gated_bf16":
+                gated16_check(forms_to_bf16(wl.make_gated(T, B, n, seed=seed, device=DEV, gate_mean=float(seed % 5) - 1.0,
+                                                          gate_std=2.0, with_h0=bool(seed & 8))),
+                              lr.TAU_TANH if seed & 16 else lr.TAU_IDENTITY, label)
+            elif entry == "lstm_bf16":
+                cell16_check(forms_to_bf16(wl.make_lstm(T, B, n, seed=seed, device=DEV, forget_mean=float(seed % 4),
+                                                        with_c0=bool(seed & 8))), label)
             else:
                 bf16_check(to_bf16(wl.make_generic(T, B, n, seed=seed, device=DEV, with_h0=bool(seed & 8))), label)
     torch.cuda.synchronize()
