@@ -47,6 +47,27 @@ def _calls():
         lr.linrec_forward(b["lam"], b["x"], b["h0"], h_out=hb)
         lr.linrec_backward(b["lam"], hb, b["h0"], b["grad_h"], grad_x=gx, grad_lambda=gl, grad_h0=gb0)
     out["bf16"] = (bf16, [hb, gx, gl, gb0])
+
+    half = lambda d: {k: (v.to(torch.bfloat16).contiguous() if torch.is_tensor(v) else v) for k, v in d.items()}
+    g16, c16 = half(g), half(c)
+    hg16 = torch.empty_like(g16["g_pre"]); gg16 = torch.empty_like(hg16); gi16 = torch.empty_like(hg16)
+    gh16 = torch.empty_like(g16["h0"])
+
+    def gated_bf16():
+        lr.linrec_gilr_forward(g16["g_pre"], g16["i_pre"], g16["h0"], h_out=hg16)
+        lr.linrec_gilr_backward(g16["g_pre"], g16["i_pre"], hg16, g16["h0"], g16["grad_h"], grad_g_pre=gg16,
+                                grad_i_pre=gi16, grad_h0=gh16)
+    out["gated_bf16"] = (gated_bf16, [hg16, gg16, gi16, gh16])
+
+    pre16 = [c16[k] for k in PRE]
+    cs16 = torch.empty_like(pre16[0]); hs16 = torch.empty_like(cs16)
+    grads16 = [torch.empty_like(cs16) for _ in range(4)]
+    gc16 = torch.empty_like(c16["c0"])
+
+    def cell_bf16():
+        lr.linrec_lstm_cell_forward(*pre16, c16["c0"], c_out=cs16, h_out=hs16)
+        lr.linrec_lstm_cell_backward(*pre16, cs16, c16["c0"], c16["grad_h"], grads=grads16, grad_c0=gc16)
+    out["lstm_bf16"] = (cell_bf16, [cs16, hs16] + grads16 + [gc16])
     return out
 
 
@@ -56,7 +77,7 @@ def _same(a, b):
                        b.view(torch.int16 if b.dtype == torch.bfloat16 else torch.int32))
 
 
-@pytest.mark.parametrize("name", ["gated", "lstm", "bf16"])
+@pytest.mark.parametrize("name", ["gated", "lstm", "bf16", "gated_bf16", "lstm_bf16"])
 def test_deterministic_on_interleaved_streams(name):
     calls = _calls()
     fn, outs = calls[name]
@@ -80,7 +101,7 @@ def test_deterministic_on_interleaved_streams(name):
         lr.linrec_check(s)
 
 
-@pytest.mark.parametrize("name", ["gated", "lstm", "bf16"])
+@pytest.mark.parametrize("name", ["gated", "lstm", "bf16", "gated_bf16", "lstm_bf16"])
 def test_hip_graph_replay(name):
     fn, outs = _calls()[name]
     s = torch.cuda.Stream()
@@ -116,6 +137,8 @@ def test_tapered_tail_tiles_every_entry_point(taper):
     from test_bf16_parity_gpu import bf16_check, to_bf16
     from test_gilr_parity_gpu import gated_check
     from test_lstm_parity_gpu import cell_check
+    from test_forms_bf16_parity_gpu import cell16_check, gated16_check
+    from test_forms_bf16_parity_gpu import to_bf16 as forms_to_bf16
 
     T = 40_000          # enough tiles per column for the tapered region to hold several short tiles
     with options(variant=lr.VARIANT_LOOKBACK, taper=taper):
@@ -123,6 +146,9 @@ def test_tapered_tail_tiles_every_entry_point(taper):
         gated_check(wl.make_gated(T, 1, 70, seed=32, device=DEV, gate_mean=1.0), lr.TAU_TANH, f"taper {taper} gated")
         cell_check(wl.make_lstm(T, 1, 70, seed=33, device=DEV), f"taper {taper} lstm")
         bf16_check(to_bf16(wl.make_generic(T, 1, 72, seed=34, device=DEV)), f"taper {taper} bf16")
+        gated16_check(forms_to_bf16(wl.make_gated(T, 1, 72, seed=35, device=DEV, gate_mean=1.0)), lr.TAU_TANH,
+                      f"taper {taper} gated bf16")
+        cell16_check(forms_to_bf16(wl.make_lstm(T, 1, 72, seed=36, device=DEV)), f"taper {taper} lstm bf16")
 
 
 @pytest.mark.parametrize("family", ["gated", "lstm", "bf16"])
