@@ -380,10 +380,9 @@ int auto_walk_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
 
 // Shapes of the gated layer and the cell on bf16 storage (their kernels exist for the shapes with two or
 // four columns per thread; the register tile is the fp32 one, the bytes are half), from a sweep over
-// T = 256 .. 65536 x C = 256 .. 32768.  With half the bytes these kernels are limited by their arithmetic
-// (two to five activations per element), so the shapes with the most elements per thread, which spread
-// the per-tile scan and look-back over more elements, win: 64 elements per thread for the gated layer's
-// backward pass (8), 32 for the cell (4, the most it has).
+// T = 256 .. 65536 x C = 256 .. 32768.  The fp32 register tile now stands for half the bytes in flight, so
+// these kernels take nearly the time of the fp32 ones, and the shapes with the most elements per thread
+// win: 64 elements per thread for the gated layer's backward pass (8), 32 for the cell (4, the most it has).
 int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
 {
     const int64_t E = T * C;
@@ -396,8 +395,8 @@ int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
         return T >= 4096 ? 15 : 3;
     }
     if (!bwd) {
-        // (large problems: the one-column shape with 128-byte row segments -- its 2-byte loads cost nothing
-        // that the arithmetic does not hide -- is 10-17 % ahead of the best multi-column shape)
+        // (large problems: the one-column shape with 128-byte row segments, 2-byte loads and all, is
+        // 10-17 % ahead of the best multi-column shape)
         if (C <= 512) return T >= 16384 ? 13 : 16;
         return E >= ((int64_t)1 << 24) ? 21 : 16;
     }
@@ -405,8 +404,7 @@ int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
     if (E >= ((int64_t)1 << 23)) return (C <= 512 && T >= 32768) ? 7 : 8;
     return C >= 4096 ? 4 : 3;
 }
-// The walk on bf16 storage pays only for the shortest sequences (the single pass is limited by
-// arithmetic there, not by what the walk saves): T <= 256, the gated layer's backward pass below
+// The walk on bf16 storage pays only for the shortest sequences: T <= 256, the gated layer's backward pass below
 // C = 32768, the cell's forward pass only.
 int auto_walk_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
 {
