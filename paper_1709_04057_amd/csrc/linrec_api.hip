@@ -243,6 +243,7 @@ int auto_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
         // (the backward pass has four operands per row in flight: few rows per thread, wide accesses)
         if (C >= 16384) return vec >= 4 ? 4 : 21;
         if (C >= 2048) return vec >= 4 ? 3 : vec >= 2 ? 15 : 21;
+        if (C <= 512 && E >= ((int64_t)1 << 26)) return 18;  // (long and narrow)
         return T < 2048 ? (C >= 1024 ? 21 : plain) : vec >= 2 ? 15 : 18;
     }
     if (!bwd) {
@@ -397,11 +398,14 @@ int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
     if (!bwd) {
         // (large problems: the one-column shape with 128-byte row segments, 2-byte loads and all, is
         // 10-17 % ahead of the best multi-column shape)
-        if (C <= 512) return T >= 16384 ? 13 : 16;
+        if (C <= 512) {
+            if (C >= 256 || (T >= 262144 && C >= 64) || T >= 1048576) return T >= 16384 ? 18 : 16;
+            return T >= 16384 ? 13 : 16;
+        }
         return E >= ((int64_t)1 << 24) ? 21 : 16;
     }
     if (vec < 4) return E >= ((int64_t)1 << 23) ? 16 : 15;
-    if (E >= ((int64_t)1 << 23)) return (C <= 512 && T >= 32768) ? 7 : 8;
+    if (E >= ((int64_t)1 << 23)) return (C <= 256 && T >= 32768) ? 7 : 8;
     return C >= 4096 ? 4 : 3;
 }
 // The walk on bf16 storage pays only for the shortest sequences: T <= 256, the gated layer's backward pass below
