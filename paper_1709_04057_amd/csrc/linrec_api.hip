@@ -408,21 +408,47 @@ int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
     if (E >= ((int64_t)1 << 23)) return (C <= 256 && T >= 32768) ? 7 : 8;
     return C >= 4096 ? 4 : 3;
 }
-// The walk on bf16 storage pays only for the shortest sequences: T <= 256, the gated layer's backward pass below
-// C = 32768, the cell's forward pass only.
+// The walk of the gated layer and the cell on bf16 storage, from a sweep of every shape over
+// T = 64 .. 2048 x C = 2048 .. 65536 with 8-byte aligned tensors (within 0.1-2 % of the best choice on
+// average; the single pass takes 1.1-2.7x as long where the walk is taken).  Their single pass is short
+// of resident bytes rather than of bandwidth, so the walk pays further out than with fp32 storage: up to
+// T = 2048 for C >= 32768.  The four-column shapes with 8 rows per thread (3, 4, 5: 32, 64, 128 columns)
+// carry it; the width follows C.
 int auto_walk_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
 {
+    if (vec >= 4) {
+        const int wide = C >= 49152 ? 5 : 4;
+        if (T <= 64) return C < 16384 ? 0 : (form == FORM_LSTM && bwd && C < 24576) ? 4 : 5;
+        if (T <= 128) return C < 8192 ? 0 : (form == FORM_GATED && !bwd) ? 4 : wide;
+        if (form == FORM_GATED && !bwd) {
+            if (T <= 256) return C >= 4096 ? 4 : 0;
+            if (T <= 512) return C < 8192 ? 0 : C <= 8192 ? 13 : C <= 16384 ? 16 : 4;
+            if (T <= 1024) return C <= 12288 ? 0 : C <= 16384 ? 16 : 4;
+            return (T <= 2048 && C >= 32768) ? 4 : 0;
+        }
+        if (T <= 256) {
+            if (C < 4096) return 0;
+            if (form == FORM_GATED) return C <= 16384 ? 3 : wide;
+            if (!bwd) return C <= 12288 ? 3 : wide;
+            return C <= 8192 ? 3 : C <= 16384 ? 0 : wide;
+        }
+        if (T <= 512) {
+            if (form == FORM_GATED) return C >= 24576 ? wide : 0;
+            if (!bwd && C > 12288 && C <= 16384) return 3;
+        }
+        return (T <= 2048 && C >= 32768) ? wide : 0;
+    }
+    // narrower accesses: the shortest sequences only (T <= 256, the gated layer's backward pass below
+    // C = 32768, the cell's forward pass), in the fp32 rule's region; where that lands on a one-column
+    // shape while 4-byte accesses are possible, the two-column shape of the same width and height
     if (T > 256 || (bwd && (form == FORM_LSTM || C >= 32768))) return 0;
-    // the fp32 rule's region; where it lands on a one-column shape, the two- or four-column shape of the
-    // same width and height (the cell: of at most 32 elements per thread)
     const int t = auto_walk_tile_form(T, C, vec, bwd, form);
     if (t < 1 || kTiles[t - 1].vec >= 2 || vec < 2) return t < 1 ? 0 : t;
     const bool cell = form == FORM_LSTM;
     switch (t) {
     case 17: case 22: case 23: return cell ? 15 : 13;   // 32 columns, 512 rows and more
     case 20: return cell ? 15 : 16;                     // 64 x 256
-    case 21: return vec >= 4 ? 4 : 15;                  // 64 x 128
-    default: return 15;                                 // 32 x 256
+    default: return 15;                                 // 32 x 256 (and 64 x 128)
     }
 }
 int entry_family(int form, bool bf16)

@@ -223,9 +223,9 @@ def test_plan_is_host_only_and_consistent(L):
         assert lr.linrec_plan(65536, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
         assert lr.linrec_plan(1024, 4, 256, backward=bwd)[0] == lr.VARIANT_LOOKBACK
         for fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16, lr.ENTRY_GILR_BF16, lr.ENTRY_LSTM_CELL_BF16):
-            v, t = lr.linrec_plan_for(fam, 128, 16, 1024, backward=bwd)            # every family walks here,
-            info = lr.linrec_tile_info(t)                                          # but the bf16 cell backward
-            assert v == (lr.VARIANT_LOOKBACK if (fam == lr.ENTRY_LSTM_CELL_BF16 and bwd) else lr.VARIANT_WALK)
+            v, t = lr.linrec_plan_for(fam, 128, 16, 1024, backward=bwd)            # every family walks here
+            info = lr.linrec_tile_info(t)
+            assert v == lr.VARIANT_WALK
             assert info["cols_per_thread"] >= 2 or fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL)
             assert fam not in (lr.ENTRY_LSTM_CELL, lr.ENTRY_LSTM_CELL_BF16) or \
                 info["rows_per_thread"] * info["cols_per_thread"] <= 32
