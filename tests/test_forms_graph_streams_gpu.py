@@ -196,6 +196,21 @@ def test_short_wide_problems_walk_in_every_family():
     for (T, B, n) in [(1000, 4, 3072), (2048, 8, 4096), (77, 2, 9000)]:
         assert lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, alignment=8)[0] == lr.VARIANT_WALK
         bf16_check(to_bf16(wl.make_generic(T, B, n, seed=53, device=DEV)), f"auto walk bf16 {T}x{B}x{n}")
+    # the gated layer and the cell on bf16 storage walk further out (their single pass is short of resident
+    # bytes): up to T = 2048 on the widest problems; whole column groups of the tile among the sampled columns
+    from test_forms_bf16_parity_gpu import cell16_check, gated16_check
+    from test_forms_bf16_parity_gpu import to_bf16 as forms_to_bf16
+    import numpy as np
+    for (T, B, n) in [(100, 8, 1024), (1000, 8, 4096), (2000, 16, 4096), (500, 6, 4096)]:
+        C = B * n
+        cols = np.unique(np.concatenate([np.arange(0, 256), np.arange(C - 256, C), np.arange(5, C, 997)]))
+        for bwd in (False, True):
+            assert lr.linrec_plan_for(lr.ENTRY_GILR_BF16, T, B, n, backward=bwd, alignment=8)[0] == lr.VARIANT_WALK
+            if T != 500:
+                assert lr.linrec_plan_for(lr.ENTRY_LSTM_CELL_BF16, T, B, n, backward=bwd, alignment=8)[0] == lr.VARIANT_WALK
+        gated16_check(forms_to_bf16(wl.make_gated(T, B, n, seed=54, device=DEV, gate_mean=1.0)), lr.TAU_TANH,
+                      f"auto walk gated bf16 {T}x{B}x{n}", cols=cols)
+        cell16_check(forms_to_bf16(wl.make_lstm(T, B, n, seed=55, device=DEV)), f"auto walk lstm bf16 {T}x{B}x{n}", cols=cols)
 
 
 def test_staggered_start_changes_timing_only():
