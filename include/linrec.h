@@ -231,7 +231,7 @@ int linrec_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_t *i_pre,
                                    int64_t T, int64_t B, int64_t n, void *stream);
 
 /* Process-wide tuning knobs (LINREC_OPT_*).  Environment variables LINREC_VARIANT
- * ("auto", "threephase", "lookback", "serial") and LINREC_TILE (integer id) give the
+ * ("auto", "threephase", "lookback", "serial", "walk") and LINREC_TILE (integer id) give the
  * initial values.  Returns LINREC_OK or LINREC_ERR_OPTION.  Not thread-safe against
  * concurrent linrec_forward/backward calls. */
 int linrec_set_option(int option, int64_t value);
