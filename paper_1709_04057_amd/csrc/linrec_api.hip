@@ -234,7 +234,7 @@ int auto_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
             if (T < 2048) return plain;
             if (C >= 12288 && C < 24576 && vec >= 2) return 14;  // 8-byte accesses
             if (C >= 16384) return 21;
-            if (one_round_22 && T >= 32768) return 22;
+            if (one_round_22) return 22;
             if (E >= ((int64_t)1 << 24)) return 19;
             return C >= 2048 ? 20 : 17;
         }
@@ -396,13 +396,10 @@ int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
         return T >= 4096 ? 15 : 3;
     }
     if (!bwd) {
-        // (large problems: the one-column shape with 128-byte row segments, 2-byte loads and all, is
-        // 10-17 % ahead of the best multi-column shape)
-        if (C <= 512) {
-            if (C >= 256 || (T >= 262144 && C >= 64) || T >= 1048576) return T >= 16384 ? 18 : 16;
-            return T >= 16384 ? 13 : 16;
-        }
-        return E >= ((int64_t)1 << 24) ? 21 : 16;
+        // (the two-column shapes of 64 elements per thread: 64 columns wide, or 32 for a handful of
+        // column groups; the widest problems take 16-byte accesses)
+        if (C <= 128) return T >= 16384 ? 13 : 16;
+        return (C >= 32768 && vec >= 4) ? 8 : 16;
     }
     if (vec < 4) return E >= ((int64_t)1 << 23) ? 16 : 15;
     if (E >= ((int64_t)1 << 23)) return (C <= 256 && T >= 32768) ? 7 : 8;

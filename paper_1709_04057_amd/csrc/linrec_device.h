@@ -540,7 +540,22 @@ __device__ __forceinline__ void tile_load_impl(const Args &A, const TileAddr<G, 
     // every load is issued before any arithmetic on the rows: the scheduler may not pull activation
     // math in between the loads
     if constexpr (FORM != FORM_PLAIN) __builtin_amdgcn_sched_barrier(0);
-    if constexpr (FORM == FORM_GATED) {
+    if constexpr (FORM == FORM_GATED && !BWD && G::R * G::VEC >= 64) {
+        // Shapes of 64 elements per thread: the gate complements in one in-place loop, then the impulse.
+        // (Written as below, the compiler hoists the exponentials that both branches share in front of
+        // the branch and keeps 64 of them alive next to the tile: 155 instead of 125 registers for a
+        // 32-element thread, more for these.  The 64-element shapes run 4-20 % faster this way; the
+        // smaller ones 2-6 % slower, although they gain a wavefront per SIMD, so they keep the form below.)
+#pragma unroll
+        for (int j = 0; j < R; ++j) r.a[j] = gate_complement<VEC>(r.a[j]);
+        if (A.tau) {
+#pragma unroll
+            for (int j = 0; j < R; ++j) r.b[j] = r.a[j] * impulse<VEC>(r.b[j], 1);
+        } else {
+#pragma unroll
+            for (int j = 0; j < R; ++j) r.b[j] = r.a[j] * r.b[j];
+        }
+    } else if constexpr (FORM == FORM_GATED) {
         // (the choice of tau stays outside the row loops: a branch per row would cut the straight line)
         if (BWD || A.tau) {
 #pragma unroll
