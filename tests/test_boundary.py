@@ -19,6 +19,13 @@ def test_exports_every_declared_symbol(L):
         assert hasattr(L, name), f"liblinrec.so does not export {name}"
 
 
+def test_the_binding_types_every_declared_function(L):
+    # without argtypes ctypes passes Python ints as 32-bit C ints: pointers and int64 sizes would be cut
+    for name in lr.declared_symbols():
+        fn = getattr(L, name)
+        assert fn.argtypes is not None, f"binding.py sets no argument types for {name}"
+
+
 def test_version_and_status_strings(L):
     assert lr.linrec_version() >= 100
     assert lr.linrec_status_string(0) == "ok"
