@@ -1,6 +1,7 @@
 """Seeded random sweep over shapes and launch options for every entry point, each case compared
 element by element with the fp64 oracle (arXiv 1709.04057: Sections 2, 2.2, 3.1, 3.2).  Complements the
-hand-picked edge shapes: ragged tiles, partial column groups, short sequences, option combinations."""
+hand-picked edge shapes: ragged tiles, partial column groups, short sequences, option combinations; a
+second set has thousands of columns."""
 import numpy as np
 import pytest
 import torch
@@ -33,10 +34,25 @@ def _cases(seed, n):
         yield i, T, B, n_, opts, int(rng.integers(1 << 30))
 
 
-@pytest.mark.parametrize("entry", ["plain", "gated", "lstm", "bf16", "gated_bf16", "lstm_bf16"])
-def test_random_shapes_and_options(entry):
-    for i, T, B, n, opts, seed in _cases({"plain": 1, "gated": 2, "lstm": 3, "bf16": 4, "gated_bf16": 5,
-                                          "lstm_bf16": 6}[entry], 40):
+def _wide_cases(seed, n):
+    """Thousands of columns (many column groups, the multi-column shapes, the walk) on short sequences."""
+    rng = np.random.default_rng(seed)
+    for i in range(n):
+        T, C, B = int(rng.integers(50, 2000)), int(rng.integers(1000, 12000)), int(rng.choice([1, 2, 4]))
+        opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_WALK])),
+                    tile=int(rng.integers(0, N_TILES + 1)), persistent=int(rng.integers(-1, 2)),
+                    taper=int(rng.choice([0, 0, 2])), hprev_late=int(rng.integers(-1, 2)))
+        yield i, T, B, max(1, C // B), opts, int(rng.integers(1 << 30))
+
+
+ENTRIES = {"plain": 1, "gated": 2, "lstm": 3, "bf16": 4, "gated_bf16": 5, "lstm_bf16": 6}
+
+
+@pytest.mark.parametrize("wide", [False, True])
+@pytest.mark.parametrize("entry", list(ENTRIES))
+def test_random_shapes_and_options(entry, wide):
+    cases = _wide_cases(100 + ENTRIES[entry], 12) if wide else _cases(ENTRIES[entry], 40)
+    for i, T, B, n, opts, seed in cases:
         label = f"{entry} #{i} T={T} B={B} n={n} {opts}"
         say(label)
         with options(**opts):
