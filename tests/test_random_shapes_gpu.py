@@ -1,7 +1,7 @@
 """Seeded random sweep over shapes and launch options for every entry point, each case compared
 element by element with the fp64 oracle (arXiv 1709.04057: Sections 2, 2.2, 3.1, 3.2).  Complements the
 hand-picked edge shapes: ragged tiles, partial column groups, short sequences, option combinations; a
-second set has thousands of columns."""
+second set has thousands of columns, a third tens to hundreds of thousands of steps on few columns."""
 import numpy as np
 import pytest
 import torch
@@ -45,13 +45,28 @@ def _wide_cases(seed, n):
         yield i, T, B, max(1, C // B), opts, int(rng.integers(1 << 30))
 
 
+def _long_cases(seed, n):
+    """Long sequences on few columns: hundreds of tiles along T, look-back windows over many predecessors,
+    the short tiles that end a sequence."""
+    rng = np.random.default_rng(seed)
+    for i in range(n):
+        C = int(rng.choice([rng.integers(1, 9), rng.integers(9, 70), rng.integers(70, 300)]))
+        T = int(rng.integers(20000, min(400000, 12_000_000 // C)))
+        B = int(rng.choice([1, 1, 2]))
+        opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_LOOKBACK, lr.VARIANT_THREEPHASE])),
+                    tile=int(rng.integers(0, N_TILES + 1)), persistent=int(rng.integers(-1, 2)),
+                    taper=int(rng.choice([0, 0, 2, 8])), hprev_late=int(rng.integers(-1, 2)))
+        yield i, T, B, max(1, C // B), opts, int(rng.integers(1 << 30))
+
+
 ENTRIES = {"plain": 1, "gated": 2, "lstm": 3, "bf16": 4, "gated_bf16": 5, "lstm_bf16": 6}
 
 
-@pytest.mark.parametrize("wide", [False, True])
+@pytest.mark.parametrize("shapes", ["mixed", "wide", "long"])
 @pytest.mark.parametrize("entry", list(ENTRIES))
-def test_random_shapes_and_options(entry, wide):
-    cases = _wide_cases(100 + ENTRIES[entry], 12) if wide else _cases(ENTRIES[entry], 40)
+def test_random_shapes_and_options(entry, shapes):
+    cases = {"mixed": lambda: _cases(ENTRIES[entry], 40), "wide": lambda: _wide_cases(100 + ENTRIES[entry], 12),
+             "long": lambda: _long_cases(200 + ENTRIES[entry], 10)}[shapes]()
     for i, T, B, n, opts, seed in cases:
         label = f"{entry} #{i} T={T} B={B} n={n} {opts}"
         say(label)
