@@ -101,6 +101,49 @@ def test_deterministic_on_interleaved_streams(name):
         lr.linrec_check(s)
 
 
+def test_host_threads_on_streams_of_their_own():
+    """One host thread per entry point, each enqueuing on its own stream at the same time (the binding's calls
+    run without the interpreter lock): the library's workspace table and plan cache are shared, the results
+    must be those of the same calls made alone."""
+    import threading
+    calls = _calls()
+    ref = {}
+    for name, (fn, outs) in calls.items():
+        fn()
+        torch.cuda.synchronize()
+        ref[name] = [t.clone() for t in outs]
+        for t in outs:
+            t.zero_()
+    torch.cuda.synchronize()
+    errors = []
+    start = threading.Barrier(len(calls))
+
+    def worker(name):
+        try:
+            torch.cuda.set_device(0)
+            s = torch.cuda.Stream()
+            start.wait(timeout=60)
+            with torch.cuda.stream(s):
+                for _ in range(20):
+                    calls[name][0]()
+            lr.linrec_check(s)
+        except Exception as e:  # reported by the main thread
+            errors.append(f"{name}: {e!r}")
+
+    threads = [threading.Thread(target=worker, args=(name,)) for name in calls]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=120)
+    assert not any(t.is_alive() for t in threads), "a host thread did not finish"
+    assert not errors, errors
+    torch.cuda.synchronize()
+    lr.linrec_check()
+    for name, (fn, outs) in calls.items():
+        assert all(_same(a, b) for a, b in zip(outs, ref[name])), f"{name}: differs from the call made alone"
+    lr.linrec_release_workspace()
+
+
 @pytest.mark.parametrize("name", ["gated", "lstm", "bf16", "gated_bf16", "lstm_bf16"])
 def test_hip_graph_replay(name):
     fn, outs = _calls()[name]
