@@ -173,9 +173,6 @@ def test_hip_graph_replay(name):
 def test_tapered_tail_tiles_every_entry_point(taper):
     """LINREC_OPT_TAPER (off by default) ends the sequence on half- and quarter-height tiles: same results
     to tolerance for every entry point that runs the single-pass kernel."""
-    import numpy as np
-
-    import oracle
     from parity import fwd_bwd_check
     from test_bf16_parity_gpu import bf16_check, to_bf16
     from test_gilr_parity_gpu import gated_check

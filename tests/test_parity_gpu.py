@@ -1,5 +1,4 @@
 """GPU parity tests: liblinrec (through the C ABI) against the fp64 oracle, element by element."""
-import numpy as np
 import pytest
 import torch
 
