@@ -261,3 +261,18 @@ def test_every_plan_of_the_gated_families_names_a_shape_their_kernels_exist_for(
                         r, v = info["rows_per_thread"], info["cols_per_thread"]
                         assert r * v <= limit and (r % 8 == 0 or r < 8), (fam, T, C, bwd, align, t)
                         assert C % v == 0 and v * es <= align, (fam, T, C, bwd, align, t)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asked for more (by flag or by a launcher's WORLD_SIZE) it says so and
+    exits before it touches a GPU."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for argv, env in ((["--gpus", "2"], {}), ([], {"WORLD_SIZE": "2"})):
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), *argv], capture_output=True, text=True,
+                           env={**os.environ, **env}, timeout=120)
+        assert r.returncode != 0
+        assert "ONE GPU" in r.stderr + r.stdout
+        assert not any(line.startswith("{") for line in r.stdout.splitlines())
