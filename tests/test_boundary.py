@@ -276,3 +276,27 @@ def test_bench_refuses_more_than_one_gpu():
         assert r.returncode != 0
         assert "ONE GPU" in r.stderr + r.stdout
         assert not any(line.startswith("{") for line in r.stdout.splitlines())
+
+
+def test_a_missing_library_is_an_error_not_a_fallback(tmp_path):
+    """Without liblinrec.so the binding raises on first use, and host tensors are refused outright: there is
+    no CPU path behind it."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import torch, paper_1709_04057_amd as lr\n"
+            "for call in (lr.lib, lr.linrec_version, lambda: lr.linrec_plan(64, 1, 64),\n"
+            "             lambda: lr.linrec_forward(torch.zeros(4, 1, 2), torch.zeros(4, 1, 2), None)):\n"
+            "    try:\n"
+            "        call()\n"
+            "    except Exception as e:\n"
+            "        print('RAISED', type(e).__name__, e)\n"
+            "    else:\n"
+            "        print('RETURNED')\n")
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, cwd=root, timeout=300,
+                       env={**os.environ, "LINREC_LIB_PATH": str(tmp_path / "no_such_liblinrec.so")})
+    lines = [l for l in r.stdout.splitlines() if l.startswith(("RAISED", "RETURNED"))]
+    assert len(lines) == 4 and all(l.startswith("RAISED") for l in lines), r.stdout + r.stderr
+    assert all("not built" in l for l in lines[:3])
+    assert "CUDA tensor" in lines[3]
