@@ -300,3 +300,29 @@ def test_a_missing_library_is_an_error_not_a_fallback(tmp_path):
     assert len(lines) == 4 and all(l.startswith("RAISED") for l in lines), r.stdout + r.stderr
     assert all("not built" in l for l in lines[:3])
     assert "CUDA tensor" in lines[3]
+
+
+def test_product_and_oracle_do_not_know_each_other():
+    """The oracle is test infrastructure: no file of the package (Python, HIP, C++) names it, the oracle names
+    nothing of the package, and the input generators hold none of the method's arithmetic calls."""
+    import os
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+    def sources(folder):
+        for base, _, files in os.walk(os.path.join(root, folder)):
+            if "_build" in base or "__pycache__" in base:
+                continue
+            for f in files:
+                if f.endswith((".py", ".h", ".hip", ".cpp", ".c")):
+                    yield os.path.join(base, f)
+
+    for path in list(sources("paper_1709_04057_amd")) + [os.path.join(root, "include", "linrec.h")]:
+        assert not re.search(r"\boracle\b", open(path).read()), f"{path} names the oracle"
+    for path in sources("oracle"):
+        text = open(path).read()
+        assert not re.search(r"paper_1709_04057_amd|liblinrec\.so|hip/hip_runtime|__global__|hipLaunch|torch\.cuda", text), \
+            f"{path} names the GPU path"
+    gen = open(os.path.join(root, "linrec_workloads.py")).read()
+    assert "import oracle" not in gen and "paper_1709_04057_amd" not in gen
+    assert not re.search(r"cumsum|cumprod|linrec_forward|linrec_backward", gen)
