@@ -24,7 +24,8 @@ DEV = "cuda:0"
 T, B, n = 1_056_801, 8, 512
 C = B * n
 COLS = np.concatenate([np.arange(0, 32), np.arange(2040, 2056), np.arange(C - 32, C)])
-VARIANTS = dict(lookback=lr.VARIANT_LOOKBACK, threephase=lr.VARIANT_THREEPHASE, walk=lr.VARIANT_WALK)
+VARIANTS = dict(lookback=lr.VARIANT_LOOKBACK, threephase=lr.VARIANT_THREEPHASE, walk=lr.VARIANT_WALK,
+                serial=lr.VARIANT_SERIAL)
 
 
 @pytest.fixture(autouse=True)
