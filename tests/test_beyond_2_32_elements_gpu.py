@@ -28,8 +28,15 @@ VARIANTS = dict(lookback=lr.VARIANT_LOOKBACK, threephase=lr.VARIANT_THREEPHASE, 
                 serial=lr.VARIANT_SERIAL)
 
 
+NEEDS_BYTES = 150 << 30  # the largest case holds 7 fp32 tensors of 17 GB, plus what the generators use meanwhile
+
+
 @pytest.fixture(autouse=True)
-def _release_device_memory():
+def _device_memory():
+    torch.cuda.empty_cache()
+    free, _ = torch.cuda.mem_get_info()
+    if free < NEEDS_BYTES:
+        pytest.skip(f"needs {NEEDS_BYTES >> 30} GiB of free device memory, {free >> 30} GiB are free")
     yield
     torch.cuda.empty_cache()
 
