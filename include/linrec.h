@@ -77,8 +77,10 @@ enum {
     LINREC_OPT_HPREV_LATE = 5, /* look-back backward: load h after the rescan (1), together
                                   with lambda and grad_h (0), or let the library decide (-1)  */
     LINREC_OPT_TAPER = 6,      /* look-back: cut this many eighths (0..8) of the last round of
-                                  tiles into half- and quarter-height tiles; 0 = none
-                                  (default: measured neutral to slightly harmful on MI355X) */
+                                  tiles into half- and quarter-height tiles; 0 = none (default:
+                                  neutral on most shapes); linrec_tune tries 2 on the plan it
+                                  found and remembers it where that is faster; a non-zero
+                                  value set here overrides what tuning remembered            */
     LINREC_OPT_PERSISTENT = 7, /* look-back: launch as many workgroups as the GPU holds and let
                                   each loop over tiles (1), one workgroup per tile (0), or
                                   let the library decide per pass (-1, default)              */
@@ -262,11 +264,11 @@ int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backwa
                     int alignment_bytes, int *variant, int *tile_id);
 
 /*
- * Optional: finds the fastest plan (single-pass kernel: tile shape, persistent workgroups or not;
- * for wide problems also the walk) for a [T, B, n] forward (backward = 0) or backward (1) pass by
+ * Optional: finds the fastest plan (single-pass kernel: tile shape, persistent workgroups or not,
+ * a tapered tail or not; for wide problems also the walk) for a [T, B, n] forward (backward = 0) or backward (1) pass by
  * timing the candidates on `stream`, on scratch tensors it allocates and frees, and remembers it for
- * later calls with this shape on the current device (when LINREC_OPT_TILE / LINREC_OPT_PERSISTENT
- * are automatic; a remembered walk only while LINREC_OPT_VARIANT is automatic too).
+ * later calls with this shape on the current device (when LINREC_OPT_TILE / LINREC_OPT_PERSISTENT /
+ * LINREC_OPT_TAPER are automatic; a remembered walk only while LINREC_OPT_VARIANT is automatic too).
  * Blocking; allocates 3 (forward) or 5 (backward) tensors of T*B*n floats.  Returns LINREC_OK,
  * LINREC_ERR_SHAPE or LINREC_ERR_HIP.  Must not run concurrently with other liblinrec calls.
  */

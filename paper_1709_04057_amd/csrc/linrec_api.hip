@@ -470,6 +470,7 @@ struct Plan {
     int variant, tile;
     bool hp_late;
     int persistent;  // -1: not decided by the plan
+    int taper;       // eighths of the last round cut into shorter tiles (LINREC_OPT_TAPER, or what tuning found)
 };
 
 // Plans found by linrec_tune, keyed by (device, T, C, pass).  Guarded by g_tuned_mu.
@@ -489,6 +490,7 @@ struct TunedKey {
 };
 struct TunedPlan {
     int tile, persistent, variant;
+    int taper = 0;
 };
 std::mutex g_tuned_mu;
 std::map<TunedKey, TunedPlan> g_tuned;
@@ -502,6 +504,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
     p.tile = (int)opts().tile;
     p.persistent = (int)opts().persistent;
+    p.taper = (int)opts().taper;
     if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK) {  // a tuned plan, if there is one for this shape
         const int family = entry_family(form, bf16);
         int dev = 0;
@@ -512,6 +515,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
                 p.tile = it->second.tile;
                 p.variant = it->second.variant;
                 if (p.persistent < 0) p.persistent = it->second.persistent;
+                if (p.taper == 0) p.taper = it->second.taper;
             }
         }
     }
@@ -612,13 +616,13 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
     A.K1 = tiles_t;
     A.K2 = 0;
     A.K = tiles_t;
-    if (opts().taper && d.r % 4 == 0 && d.r >= 8) {
+    if (plan.taper && d.r % 4 == 0 && d.r >= 8) {
         const int64_t rows = d.rows();
         const int64_t full = A.T / rows;                                   // complete full-height tiles
-        // full tiles per chain that are in flight at once; opts().taper eighths of them are cut up
+        // full tiles per chain that are in flight at once; plan.taper eighths of them are cut up
         const int64_t resident = (int64_t)resident_workgroups(dev) * (d.threads() >= 512 ? 1 : 3) / 3;
         const int64_t round = ceil_div(resident, A.G);
-        const int64_t taper_tiles = std::min(full / 2, (round * opts().taper + 7) / 8);
+        const int64_t taper_tiles = std::min(full / 2, (round * plan.taper + 7) / 8);
         if (taper_tiles > 0) {
             A.K1 = full - taper_tiles;
             const int64_t left = A.T - A.K1 * rows;                        // rows in the tapered region
@@ -1151,8 +1155,8 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         }
     };
 
-    TunedPlan best{0, -1, LINREC_VARIANT_LOOKBACK};
-    float best_ms = 0.f;
+    TunedPlan best{0, -1, LINREC_VARIANT_LOOKBACK}, second{0, -1, LINREC_VARIANT_LOOKBACK};
+    float best_ms = 0.f, second_ms = 0.f;
     if (rc == LINREC_OK) {
         const int vec = bf16 ? max_vec_bf16(C, {}) : max_vec(C, {});
         const Options saved = opts();
@@ -1195,11 +1199,52 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
                 if (rc != LINREC_OK) break;
                 std::sort(times, times + 5);
                 if (best.tile == 0 || times[2] < best_ms) {
+                    if (best.tile != tile) {  // (the runner-up is a different shape)
+                        second = best;
+                        second_ms = best_ms;
+                    }
                     best_ms = times[2];
                     best = TunedPlan{tile, persistent, LINREC_VARIANT_LOOKBACK};
+                } else if (tile != best.tile && (second.tile == 0 || times[2] < second_ms)) {
+                    second_ms = times[2];
+                    second = TunedPlan{tile, persistent, LINREC_VARIANT_LOOKBACK};
                 }
             }
         }
+        // The two best single-pass plans once more with a quarter of their last round cut into shorter
+        // tiles: a launch of few rounds ends sooner that way on some shapes (kept only if it is at least
+        // half a percent faster than the best so far; an explicit LINREC_OPT_TAPER overrides what is
+        // remembered).
+        const TunedPlan untapered[2] = {best, second};
+        for (int c = 0; c < 2 && rc == LINREC_OK && saved.taper == 0; ++c) {
+            const TunedPlan &u = untapered[c];
+            if (u.tile == 0 || kTiles[u.tile - 1].r % 4 != 0 || kTiles[u.tile - 1].r < 8) continue;
+            opts().tile = u.tile;
+            opts().persistent = u.persistent;
+            opts().taper = 2;
+            float times[5];
+            for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {
+                if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
+                rc = call();
+                if (rc != LINREC_OK) break;
+                float ms = 0.f;
+                if ((e = hipEventRecord(ev1, s)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
+                    (e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess) {
+                    rc = hip_fail(e, "tune: timing");
+                    break;
+                }
+                if (it >= 0) times[it] = ms;
+            }
+            if (rc == LINREC_OK) {
+                std::sort(times, times + 5);
+                if (times[2] < 0.995f * best_ms) {
+                    best_ms = times[2];
+                    best = u;
+                    best.taper = 2;
+                }
+            }
+        }
+        opts().taper = saved.taper;
         // The walk, where there are enough columns for it to stand a chance: the shapes its automatic
         // rule would take at this width.
         int walk_c[3] = {0, 0, 0};
