@@ -9,7 +9,7 @@
  *
  * Storage convention used by every function here
  *   - tensors are row-major [T, C]: element (t, c) at t*C + c, C = B*n
- *     independent columns ("T vectors each of b*n elements", Section 3.1.1);
+ *     independent columns (the layout of Section 3.1.1: T vectors of B*n elements);
  *   - 0-based row t holds the paper's lambda_{t+1}, x_{t+1}, h_{t+1};
  *     h0 is the paper's h_0 and is an input, never an output row
  *     (the SCAN definition in Section 1 returns n outputs for n inputs);
@@ -39,8 +39,8 @@
 #include <stdint.h>
 
 /*
- * Forward recurrence (Section 2, "h_t = lambda_t (.) h_{t-1} + x_t";
- * Algorithm 1 fixes the initial value: C_{-1} = h_0).
+ * Forward recurrence (Section 2: each state is the elementwise product of lambda_t
+ * with the previous state, plus x_t; Algorithm 1 fixes the initial value: C_{-1} = h_0).
  *
  *   state[c]      on entry: h at row t0-1 (h0 when t0 == 0), fp64
  *                 on exit : h at row t1-1
@@ -66,7 +66,7 @@ void linrec_oracle_forward(const float *lambda, const float *x,
 }
 
 /*
- * Backward pass (Section 2.2, "Backpropagation").  With e = dL/dh (the direct
+ * Backward pass (Section 2.2).  With e = dL/dh (the direct
  * upstream gradient) and g_t the accumulated gradient nabla_{h_t} L:
  *
  *   g_{T-1} = e_{T-1}                                   (last row: no successor)
@@ -113,8 +113,7 @@ void linrec_oracle_backward(const float *lambda, const float *h,
 }
 
 /*
- * Gated impulse linear recurrent layer (Section 3.1, "Gated impulse linear
- * recurrent layer"), the part after the two matrix products: from the
+ * Gated impulse linear recurrent layer (Section 3.1), the part after the two matrix products: from the
  * pre-activations g_pre = U x_t + b_g and i_pre = V x_t + b_z,
  *
  *   g_t = sigmoid(g_pre_t)        i_t = tau(i_pre_t)
@@ -194,7 +193,7 @@ void linrec_oracle_gilr_backward(const float *g_pre, const float *i_pre, int tau
 }
 
 /*
- * Cell of the GILR-LSTM (Section 3.2, "Linear surrogate RNNs": the LSTM equations with the
+ * Cell of the GILR-LSTM (Section 3.2: the LSTM equations with the
  * gates computed from the surrogate state), the part after the matrix products.  From the
  * pre-activations of the forget, input and output gates and of the candidate,
  *
