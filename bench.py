@@ -2,14 +2,22 @@
 """Benchmark of the linear-recurrence hot path on one MI355X.
 
 A step is one forward pass plus one backward pass of h_t = lambda_t*h_{t-1} + x_t over one batch of
-synthetic, HBM-resident inputs (default workload: [T=65536, B=4, n=256] fp32, the configuration the
-metric is quoted on).  Prints ONE JSON line:
+synthetic, HBM-resident inputs.  The headline workload is the largest of the five that fits one GPU,
+workload 5 ([T=262144, B=8, n=512] fp32, 1.07e9 elements); workloads 2 and 3 (the other two with
+T >= 65536: 65536 steps at 256 hidden units, and the one-million-step regime of Section 4.2) are timed in
+the same run and reported beside it.  Prints ONE JSON line:
 
-  value        elements/s of forward+backward together, E / ms_per_step, E = T*B*n (K steps, wall clock
-               between two device synchronisations, nothing else on the stream)
-  roofline     the dominant kernel (the backward pass, 20 B/element) against the 8 TB/s HBM peak, its
-               duration measured with HIP events on the launch stream over a second run of the K steps
-  cpu_baseline the fp64 oracle timed on the host cores on the same workload (a baseline, not a target)
+  value         elements/s of forward+backward together on the headline workload, E / ms_per_step, E = T*B*n
+                (K steps, wall clock between two device synchronisations, nothing else on the stream)
+  roofline      the dominant kernel (the backward pass, 20 B/element) against the 8 TB/s HBM peak, its
+                duration measured with HIP events on the launch stream over a second run of the K steps;
+                frac_of_stream_probe relates it to what the library's pure streaming kernel reaches on this machine
+  per_workload  forward / backward time and fraction of the HBM peak for workloads 2, 3 and 5
+  cpu_baseline  the fp64 oracle timed on the host cores on a bounded sample of the headline workload, streamed
+                in slabs of rows with a carried fp64 state, once on one thread and once on all the cores this
+                process may use (a baseline, not a target)
+
+The library's static plan is what is timed: no tuning run precedes the measurement (--tune adds one).
 """
 import argparse
 import json
@@ -29,16 +37,24 @@ BWD_BYTES_PER_EL = 20.0   # read lambda, h, grad_h; write grad_x, grad_lambda
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2)")
+    ap.add_argument("--config", type=int, default=5, help="headline workload 1..5 (default 5, the largest)")
+    ap.add_argument("--also", default="auto",
+                    help="comma-separated workloads timed beside the headline one and reported in per_workload "
+                         "(default: 2,3 when the headline is workload 5 in fp32, else none; '' for none)")
     ap.add_argument("--variant", default="auto", choices=["auto", "threephase", "lookback", "serial", "walk"])
-    ap.add_argument("--tile-fwd", type=int, default=0)
-    ap.add_argument("--tile-bwd", type=int, default=0)
+    ap.add_argument("--tile-fwd", type=int, default=0, help="pin this tile shape for the headline workload's forward pass")
+    ap.add_argument("--tile-bwd", type=int, default=0, help="pin this tile shape for the headline workload's backward pass")
     ap.add_argument("--hprev-late", type=int, default=-1)
-    ap.add_argument("--no-tune", action="store_true", help="skip linrec_tune(); use the library's static plan")
+    ap.add_argument("--tune", action="store_true",
+                    help="run linrec_tune() on every timed shape first and time the plan it remembers "
+                         "(default: the library's static plan)")
+    ap.add_argument("--no-tune", action="store_true", help="accepted for older command lines; the default now")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0)
+    ap.add_argument("--cpu-sample-elements", type=int, default=1 << 28,
+                    help="elements of the headline workload (whole rows from row 0) the oracle is timed on")
     ap.add_argument("--walk-grid", action="store_true",
                     help="short, wide problems: the walk variant against the single pass, and what the plan takes")
     ap.add_argument("--table1", action="store_true",
@@ -55,54 +71,99 @@ def parse():
     ap.add_argument("--lstm", default="", choices=["", "l2", "l4"],
                     help="time the LSTM-cell entry points on this workload instead (24 B/element forward, 40 backward), "
                          "next to the unfused forward")
-    ap.add_argument("--probe", action="store_true",
-                    help="also time the library's pure streaming kernels (copy, 2-in/1-out, 3-in/2-out) on arrays "
-                         "of the workload's size; the copy doubles as the calibration kernel for byte counters")
+    ap.add_argument("--probe", action="store_true", help="accepted for older command lines; the default now")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="skip the library's pure streaming kernels (copy, 2-in/1-out, 3-in/2-out); the copy doubles "
+                         "as the calibration kernel for byte counters, so counter runs keep it")
     return ap.parse_args()
 
 
-def cpu_baseline(inp, threads):
-    """Times the fp64 oracle (forward + backward, one pass) on the host; returns the JSON object."""
+def host_cores():
+    """(cores of the box, cores this process may run on, threads the oracle's all-core leg uses)."""
+    box = os.cpu_count() or 1
+    mine = len(os.sched_getaffinity(0))
+    return box, mine, max(1, min(16, mine))
+
+
+def cpu_baseline(inp, h_gpu, threads, sample_elements):
+    """Times the fp64 oracle (forward + backward) on the host over the first rows of the workload, streamed
+    in slabs of rows with the fp64 state carried from slab to slab (so no full-size fp64 tensor exists), once
+    on one thread and once on `threads`.  Only the time inside the oracle's C loops is counted.  The sample is
+    treated as a sequence of its own (the backward pass starts at its last row)."""
     import numpy as np
 
     import oracle
     T, B, n = inp["T"], inp["B"], inp["n"]
     C = B * n
-    f = lambda t: None if t is None else t.float().cpu().numpy().reshape(-1, C)   # (bf16 values widen exactly)
-    lam, x, e = f(inp["lam"]), f(inp["x"]), f(inp["grad_h"])
+    Ts = max(1, min(T, sample_elements // C))
+    f = lambda t: None if t is None else t[:Ts].float().cpu().numpy().reshape(Ts, C)   # (bf16 values widen exactly)
+    lam, x, e, h32 = f(inp["lam"]), f(inp["x"]), f(inp["grad_h"]), f(h_gpu)
     h0 = None if inp["h0"] is None else inp["h0"].float().cpu().numpy().reshape(-1)
     oracle.build()
-    t0 = time.perf_counter()
-    h = oracle.forward(lam, x, h0, threads=threads)
-    t1 = time.perf_counter()
-    h32 = h.astype(np.float32)
-    del h
-    t2 = time.perf_counter()
-    if e is not None:
-        oracle.backward(lam, h32, h0, e, threads=threads)
-    t3 = time.perf_counter()
-    sec = (t1 - t0) + (t3 - t2)
-    return {"value": T * C / sec, "unit": "elements/s", "cores": threads, "kind": "oracle",
-            "sample": "the full workload, one forward + one backward pass of the fp64 oracle, columns split "
-                      f"over {threads} host threads; forward {t1 - t0:.3f} s, backward {t3 - t2:.3f} s"}
+    slab = max(1, min(Ts, (1 << 24) // C))
+    href = np.empty((slab, C), np.float64)
+    gx, gl = np.empty((slab + 2, C), np.float64), np.empty((slab + 2, C), np.float64)
+
+    def one_pass(nthreads):
+        state = np.zeros(C, np.float64) if h0 is None else h0.astype(np.float64)
+        t_fwd = t_bwd = 0.0
+        for t0 in range(0, Ts, slab):
+            t1 = min(Ts, t0 + slab)
+            t = time.perf_counter()
+            oracle.forward_slab(lam[t0:t1], x[t0:t1], state, href, 0, t1 - t0, nthreads)
+            t_fwd += time.perf_counter() - t
+        if e is not None:
+            g, gh0 = np.zeros(C, np.float64), np.zeros(C, np.float64)
+            t1 = Ts
+            while t1 > 0:
+                t0 = max(0, t1 - slab)
+                base, top = max(t0 - 1, 0), min(t1 + 1, Ts)     # one row of halo either side (lambda[t+1], h[t-1])
+                t = time.perf_counter()
+                oracle.backward_slab(lam[base:top], h32[base:top], h0 if t0 == 0 else None, e[base:top], g, gx, gl, gh0,
+                                     t0 - base, t1 - base, nthreads)
+                t_bwd += time.perf_counter() - t
+                t1 = t0
+        return t_fwd, t_bwd
+
+    f1, b1 = one_pass(1)
+    fa, ba = one_pass(threads)
+    box, mine, _ = host_cores()
+    Es = Ts * C
+    return {"value": Es / (fa + ba), "unit": "elements/s", "cores": threads, "kind": "oracle",
+            "value_1thread": Es / (f1 + b1), "host_cores": box, "cores_available_to_this_process": mine,
+            "sample": f"rows 0..{Ts - 1} of the workload ({Es} of {T * C} elements, all {C} columns), one forward + one "
+                      f"backward pass of the fp64 oracle streamed in slabs of {slab} rows with a carried fp64 state; "
+                      f"{threads} threads (columns split): forward {fa:.3f} s, backward {ba:.3f} s; "
+                      f"1 thread: forward {f1:.3f} s, backward {b1:.3f} s"}
 
 
-def measured_traffic(cfg, direction, form=""):
+def measured_traffic(cfg, direction, form="", expect=None):
     """HBM bytes per launch of the look-back kernel from the committed rocprofv3 counter summary
     (profiles/hbm_traffic_cfg<N>.json or hbm_traffic_<gated/lstm workload>.json, written by
-    paper_1709_04057_amd/traffic.py), or None."""
+    profile_summary.py traffic), or None.  `expect` is the tile geometry "vec, rows, wc, wt" of the plan
+    that was just timed: a summary taken on another kernel instance says nothing about this run and is not
+    reported."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{cfg}.json" if form else f"hbm_traffic_cfg{cfg}.json")
     try:
         with open(path) as f:
             d = json.load(f)
-        return d["kernels"][form + "k_lookback/" + direction]["hbm_bytes"]
+        k = d["kernels"][form + "k_lookback/" + direction]
+        if expect is not None and f"Geo<{expect}," not in k["name"]:
+            return None
+        return k["hbm_bytes"]
     except (OSError, KeyError, ValueError):
         return None
 
 
+def tile_geometry(lr, tile_id):
+    """ "vec, rows per thread, threads along columns, threads along time" as the kernel names spell it."""
+    i = lr.linrec_tile_info(tile_id)
+    return None if i is None else f"{i['cols_per_thread']}, {i['rows_per_thread']}, {i['threads_cols']}, {i['threads_time']}"
+
+
 def stream_probe(lr, torch, E, stream, iters=10):
     """GB/s of the library's streaming kernels on E-element arrays (no recurrence, same access instructions)."""
-    bufs = [torch.randn(E, device="cuda:0") for _ in range(3)] + [torch.empty(E, device="cuda:0") for _ in range(2)]
+    bufs = [torch.rand(E, device="cuda:0") for _ in range(3)] + [torch.empty(E, device="cuda:0") for _ in range(2)]
     a, b, c, o0, o1 = bufs
     res = {}
     for name, argv, nbytes in (("copy_1in_1out", (a, None, None, o0, None), 8), ("fwd_like_2in_1out", (a, b, None, o0, None), 12),
@@ -218,7 +279,7 @@ def gated_bench(args, lr, torch, wl):
     family = lr.ENTRY_GILR_BF16 if bf16 else lr.ENTRY_GILR
     bpe_f, bpe_b = (6.0, 12.0) if bf16 else (12.0, 24.0)
 
-    if not args.no_tune:
+    if args.tune:
         lr.linrec_tune_for(family, T, B, n, backward=False, stream=stream)
         lr.linrec_tune_for(family, T, B, n, backward=True, stream=stream)
 
@@ -272,8 +333,9 @@ def gated_bench(args, lr, torch, wl):
         "cpu_baseline": None,
     }
     if not bf16:
-        out["roofline"]["traffic"] = measured_traffic(args.gated, "backward", "gated:")
-    if args.probe:
+        out["roofline"]["traffic"] = measured_traffic(args.gated, "backward", "gated:",
+                                                      tile_geometry(lr, out["config"]["tile_bwd"]))
+    if not args.no_probe:
         out["stream_probe"] = stream_probe(lr, torch, E, stream)
     if not args.no_cpu_baseline:
         import oracle
@@ -315,7 +377,7 @@ def lstm_bench(args, lr, torch, wl):
     family = lr.ENTRY_LSTM_CELL_BF16 if bf16 else lr.ENTRY_LSTM_CELL
     bpe_f, bpe_b = (12.0, 20.0) if bf16 else (24.0, 40.0)
 
-    if not args.no_tune:
+    if args.tune:
         lr.linrec_tune_for(family, T, B, n, backward=False, stream=stream)
         lr.linrec_tune_for(family, T, B, n, backward=True, stream=stream)
 
@@ -372,8 +434,9 @@ def lstm_bench(args, lr, torch, wl):
         "cpu_baseline": None,
     }
     if not bf16:
-        out["roofline"]["traffic"] = measured_traffic(args.lstm, "backward", "lstm:")
-    if args.probe:
+        out["roofline"]["traffic"] = measured_traffic(args.lstm, "backward", "lstm:",
+                                                      tile_geometry(lr, out["config"]["tile_bwd"]))
+    if not args.no_probe:
         out["stream_probe"] = stream_probe(lr, torch, E, stream)
     if not args.no_cpu_baseline:
         import oracle
@@ -440,123 +503,160 @@ def main():
         lstm_bench(args, lr, torch, wl)
         return
 
-    inp = wl.make_inputs(args.config, device=dev)
     bf16 = args.dtype == "bf16"
+    family = lr.ENTRY_BF16 if bf16 else lr.ENTRY_PLAIN
     fwd_bpe, bwd_bpe = (FWD_BYTES_PER_EL / 2, BWD_BYTES_PER_EL / 2) if bf16 else (FWD_BYTES_PER_EL, BWD_BYTES_PER_EL)
-    if bf16:
-        for k in ("lam", "x", "h0", "grad_h"):
-            if inp[k] is not None:
-                inp[k] = inp[k].to(torch.bfloat16).contiguous()
-    T, B, n = inp["T"], inp["B"], inp["n"]
-    E = T * B * n
-    lam, x, h0 = inp["lam"], inp["x"], inp["h0"]
-    do_bwd = inp["grad_h"] is not None
-    e = inp["grad_h"]
-    h = torch.empty_like(x)
-    gx = torch.empty_like(x) if do_bwd else None
-    gl = torch.empty_like(x) if do_bwd else None
-    gh0 = torch.empty((B, n), device=dev, dtype=x.dtype) if do_bwd else None
     stream = torch.cuda.current_stream()
-
-    def fwd():
-        lr.linrec_set_option(lr.OPT_TILE, args.tile_fwd)
-        lr.linrec_forward(lam, x, h0, h_out=h, stream=stream)
-
-    def bwd():
-        lr.linrec_set_option(lr.OPT_TILE, args.tile_bwd)
-        lr.linrec_backward(lam, h, h0, e, grad_x=gx, grad_lambda=gl, grad_h0=gh0, stream=stream)
-
-    if not args.no_tune and args.variant in ("auto", "lookback"):
-        family = lr.ENTRY_BF16 if bf16 else lr.ENTRY_PLAIN
-        if not args.tile_fwd:
-            lr.linrec_tune_for(family, T, B, n, backward=False, stream=stream)
-        if do_bwd and not args.tile_bwd:
-            lr.linrec_tune_for(family, T, B, n, backward=True, stream=stream)
-    for _ in range(args.warmup):
-        fwd()
-        if do_bwd:
-            bwd()
-    torch.cuda.synchronize()
-
     K = args.steps
-    # Timed region: exactly K steps, nothing but the library's launches on the stream.
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(K):
-        fwd()
-        if do_bwd:
-            bwd()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    lr.linrec_check(stream)
-    ms_per_step = (t1 - t0) * 1e3 / K
+    plan_kind = "tuned (linrec_tune ran first)" if args.tune else "static (no tuning run)"
 
-    # Per-kernel durations: the same K steps again with HIP events on the launch stream around each
-    # launch (the event records themselves put ~5 us between consecutive kernels, which is why this is
-    # a region of its own and not the one the throughput comes from).
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
-    torch.cuda.synchronize()
-    for i in range(K):
-        ev[i][0].record(stream)
-        fwd()
-        ev[i][1].record(stream)
-        if do_bwd:
-            bwd()
-        ev[i][2].record(stream)
-    torch.cuda.synchronize()
-    lr.linrec_check(stream)
+    def time_workload(cfg, headline):
+        """Generates workload `cfg` on the device, times K steps (wall clock, then once more with HIP events
+        around every launch) and returns its record; the tensors are freed on return unless `headline`."""
+        inp = wl.make_inputs(cfg, device=dev)
+        if bf16:
+            for k in ("lam", "x", "h0", "grad_h"):
+                if inp[k] is not None:
+                    inp[k] = inp[k].to(torch.bfloat16).contiguous()
+        T, B, n = inp["T"], inp["B"], inp["n"]
+        E = T * B * n
+        lam, x, h0, e = inp["lam"], inp["x"], inp["h0"], inp["grad_h"]
+        do_bwd = e is not None
+        h = torch.empty_like(x)
+        gx = torch.empty_like(x) if do_bwd else None
+        gl = torch.empty_like(x) if do_bwd else None
+        gh0 = torch.empty((B, n), device=dev, dtype=x.dtype) if do_bwd else None
 
-    fwd_ms = sorted(ev[i][0].elapsed_time(ev[i][1]) for i in range(K))
-    bwd_ms = sorted(ev[i][1].elapsed_time(ev[i][2]) for i in range(K))
-    fwd_avg, bwd_avg = sum(fwd_ms) / K, sum(bwd_ms) / K
-    fwd_gbs = fwd_bpe * E / (fwd_avg * 1e-3) / 1e9
-    bwd_gbs = bwd_bpe * E / (bwd_avg * 1e-3) / 1e9 if do_bwd else None
+        def fwd():
+            lr.linrec_forward(lam, x, h0, h_out=h, stream=stream)
 
-    vf, tf = lr.linrec_plan(T, B, n, backward=False) if not args.tile_fwd else (variant, args.tile_fwd)
-    vb, tb = lr.linrec_plan(T, B, n, backward=True) if not args.tile_bwd else (variant, args.tile_bwd)
-    if bf16 and not args.tile_fwd:
-        vf, tf = lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, backward=False)
-        vb, tb = lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, backward=True)
-    traffic = None if bf16 else measured_traffic(args.config, "backward" if do_bwd else "forward")
-    if do_bwd:
-        roof = {"bound": "hbm", "kernel": "backward pass (look-back kernel)" if vb == lr.VARIANT_LOOKBACK else "backward pass",
-                "achieved": bwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": bwd_gbs / HBM_PEAK_GBS,
-                "traffic": traffic, "bytes_per_element": bwd_bpe, "algorithmic_bytes": bwd_bpe * E,
-                "avg_ms": bwd_avg}
-    else:
-        roof = {"bound": "hbm", "kernel": "forward pass", "achieved": fwd_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": fwd_gbs / HBM_PEAK_GBS, "traffic": traffic, "bytes_per_element": fwd_bpe,
-                "algorithmic_bytes": fwd_bpe * E, "avg_ms": fwd_avg}
+        def bwd():
+            lr.linrec_backward(lam, h, h0, e, grad_x=gx, grad_lambda=gl, grad_h0=gh0, stream=stream)
 
+        # the plan: pinned by --tile-fwd/--tile-bwd (headline only), tuned on request, else the library's own
+        if headline and args.tile_fwd:
+            lr.linrec_pin_plan(family, T, B, n, False, lr.VARIANT_LOOKBACK, args.tile_fwd)
+        if headline and args.tile_bwd and do_bwd:
+            lr.linrec_pin_plan(family, T, B, n, True, lr.VARIANT_LOOKBACK, args.tile_bwd)
+        if args.tune and args.variant in ("auto", "lookback"):
+            if not (headline and args.tile_fwd):
+                lr.linrec_tune_for(family, T, B, n, backward=False, stream=stream)
+            if do_bwd and not (headline and args.tile_bwd):
+                lr.linrec_tune_for(family, T, B, n, backward=True, stream=stream)
+        for _ in range(args.warmup):
+            fwd()
+            if do_bwd:
+                bwd()
+        # Timed region: exactly K steps, nothing but the library's launches on the stream.
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(K):
+            fwd()
+            if do_bwd:
+                bwd()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        lr.linrec_check(stream)
+        ms_per_step = (t1 - t0) * 1e3 / K
+        # Per-kernel durations: the same K steps again with HIP events on the launch stream around each
+        # launch (the event records themselves put ~5 us between consecutive kernels, which is why this is
+        # a region of its own and not the one the throughput comes from).
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(K)]
+        torch.cuda.synchronize()
+        for i in range(K):
+            ev[i][0].record(stream)
+            fwd()
+            ev[i][1].record(stream)
+            if do_bwd:
+                bwd()
+            ev[i][2].record(stream)
+        torch.cuda.synchronize()
+        lr.linrec_check(stream)
+        fwd_ms = sorted(ev[i][0].elapsed_time(ev[i][1]) for i in range(K))
+        bwd_ms = sorted(ev[i][1].elapsed_time(ev[i][2]) for i in range(K))
+        fwd_avg, bwd_avg = sum(fwd_ms) / K, sum(bwd_ms) / K
+        gbs = lambda bpe, ms: bpe * E / (ms * 1e-3) / 1e9
+        vf, tf = lr.linrec_plan_for(family, T, B, n, backward=False)
+        vb, tb = lr.linrec_plan_for(family, T, B, n, backward=True)
+        names = {lr.VARIANT_LOOKBACK: "lookback", lr.VARIANT_WALK: "walk", lr.VARIANT_THREEPHASE: "threephase",
+                 lr.VARIANT_SERIAL: "serial"}
+        rec = {
+            "workload": f"cfg{cfg}: forward{'+backward' if do_bwd else ''}, {'bf16 storage' if bf16 else 'fp32'}, time-major "
+                        f"[T={T}, B={B}, n={n}]; {wl.CONFIGS[cfg]['note']}",
+            "T": T, "B": B, "n": n, "elements": E, "ms_per_step": ms_per_step, "elements/s": E / (ms_per_step * 1e-3),
+            "kernel_fwd": names.get(vf, "?"), "tile_fwd": tf, "kernel_bwd": names.get(vb, "?") if do_bwd else None,
+            "tile_bwd": tb if do_bwd else None,
+            "forward": {"avg_ms": fwd_avg, "min_ms": fwd_ms[0], "median_ms": fwd_ms[K // 2], "GB/s": gbs(fwd_bpe, fwd_avg),
+                        "frac_of_peak": gbs(fwd_bpe, fwd_avg) / HBM_PEAK_GBS, "elements/s": E / (fwd_avg * 1e-3)},
+            "backward": None if not do_bwd else {
+                "avg_ms": bwd_avg, "min_ms": bwd_ms[0], "median_ms": bwd_ms[K // 2], "GB/s": gbs(bwd_bpe, bwd_avg),
+                "frac_of_peak": gbs(bwd_bpe, bwd_avg) / HBM_PEAK_GBS, "elements/s": E / (bwd_avg * 1e-3)},
+            "combined_GB/s": (fwd_bpe + (bwd_bpe if do_bwd else 0)) * E / (ms_per_step * 1e-3) / 1e9,
+        }
+        if headline and (args.tile_fwd or args.tile_bwd):   # (pins are for this run only)
+            lr.linrec_pin_plan(family, T, B, n, False, lr.VARIANT_LOOKBACK, 0)
+            lr.linrec_pin_plan(family, T, B, n, True, lr.VARIANT_LOOKBACK, 0)
+        return rec, (inp, h) if headline else None
+
+    head, kept = time_workload(args.config, True)
+    inp, h_gpu = kept
+    E = head["elements"]
+    do_bwd = head["backward"] is not None
+    also = ("2,3" if args.config == 5 and not bf16 else "") if args.also == "auto" else args.also
+    per = {f"cfg{args.config}": head}
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(inp, h_gpu, args.cpu_threads or host_cores()[2], args.cpu_sample_elements)
+    del inp, h_gpu, kept
+    torch.cuda.empty_cache()
+    for c in [int(v) for v in also.split(",") if v.strip()]:
+        if c != args.config:
+            per[f"cfg{c}"] = time_workload(c, False)[0]
+            torch.cuda.empty_cache()
+
+    probe = None if args.no_probe else stream_probe(lr, torch, min(E, 1 << 28), stream)
+    dom = "backward" if do_bwd else "forward"
+    bpe = bwd_bpe if do_bwd else fwd_bpe
+    tile = head["tile_bwd"] if do_bwd else head["tile_fwd"]
+    kernel = head["kernel_bwd"] if do_bwd else head["kernel_fwd"]
+    traffic = None
+    if not bf16 and kernel == "lookback":
+        traffic = measured_traffic(args.config, dom, expect=tile_geometry(lr, tile))
+    roof = {"bound": "hbm", "kernel": f"{dom} pass ({kernel} kernel, tile shape {tile})", "achieved": head[dom]["GB/s"],
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head[dom]["GB/s"] / HBM_PEAK_GBS, "traffic": traffic,
+            "bytes_per_element": bpe, "algorithmic_bytes": bpe * E, "avg_ms": head[dom]["avg_ms"]}
+    if probe is not None:
+        like = probe["bwd_like_3in_2out" if do_bwd else "fwd_like_2in_1out"]["GB/s"]
+        roof["stream_probe_GB/s"] = like
+        roof["frac_of_stream_probe"] = head[dom]["GB/s"] / like
+
+    short = lambda r: {"T": r["T"], "B": r["B"], "n": r["n"], "elements": r["elements"],
+                       "forward_ms": r["forward"]["avg_ms"], "forward_frac_of_peak": r["forward"]["frac_of_peak"],
+                       "backward_ms": r["backward"] and r["backward"]["avg_ms"],
+                       "backward_frac_of_peak": r["backward"] and r["backward"]["frac_of_peak"],
+                       "ms_per_step": r["ms_per_step"], "elements/s": r["elements/s"], "combined_GB/s": r["combined_GB/s"],
+                       "kernel_fwd": r["kernel_fwd"], "tile_fwd": r["tile_fwd"], "kernel_bwd": r["kernel_bwd"],
+                       "tile_bwd": r["tile_bwd"]}
     out = {
         "metric": "linrec fwd+bwd elements/sec and achieved HBM GB/s (% of MI355X peak)",
-        "value": E / (ms_per_step * 1e-3), "unit": "elements/s",
-        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "value": head["elements/s"], "unit": "elements/s",
+        "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32 arithmetic on bf16 storage" if bf16 else "f32", "data": "synthetic",
-        "config": {"workload": f"cfg{args.config}: forward{'+backward' if do_bwd else ''}, {'bf16 storage' if bf16 else 'fp32'}, time-major "
-                               f"[T={T}, B={B}, n={n}]; {wl.CONFIGS[args.config]['note']}",
-                   "variant": args.variant, "tile_fwd": tf, "tile_bwd": tb},
-        "forward": {"avg_ms": fwd_avg, "min_ms": fwd_ms[0], "median_ms": fwd_ms[K // 2], "GB/s": fwd_gbs,
-                    "frac_of_peak": fwd_gbs / HBM_PEAK_GBS, "elements/s": E / (fwd_avg * 1e-3)},
-        "backward": None if not do_bwd else {
-            "avg_ms": bwd_avg, "min_ms": bwd_ms[0], "median_ms": bwd_ms[K // 2], "GB/s": bwd_gbs,
-            "frac_of_peak": bwd_gbs / HBM_PEAK_GBS, "elements/s": E / (bwd_avg * 1e-3)},
-        "combined_GB/s": (fwd_bpe + (bwd_bpe if do_bwd else 0)) * E / (ms_per_step * 1e-3) / 1e9,
+        "config": {"workload": head["workload"], "variant": args.variant, "plan": plan_kind,
+                   "tile_fwd": head["tile_fwd"], "tile_bwd": head["tile_bwd"]},
+        "forward": head["forward"], "backward": head["backward"], "combined_GB/s": head["combined_GB/s"],
         "roofline": roof,
+        "per_workload": {k: short(r) for k, r in sorted(per.items())},
         # context only (another machine, a ratio not a rate): the paper's Table 1, parallel kernel over serial kernel
         "paper_context": {"source": "arXiv 1709.04057, Table 1 (Section 4.1.1): parallel / serial kernel throughput, minibatch 1, "
                                     "NVIDIA GPU of 2017 (a K80 is named for 'all experiments' in Section 4.2)",
                           "speedup_at_T=65536_for_m=4,32,128": [38.5, 41.8, 17.5],
                           "ours": "bench.py --table1 measures the same grid on the MI355X (profiles/table1_parallel_vs_serial_mi355x.txt)"},
+        "cpu_baseline": cpu,
     }
-    if args.probe:
-        out["stream_probe"] = stream_probe(lr, torch, E, stream)
-    if not args.no_cpu_baseline:
-        threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
-        out["cpu_baseline"] = cpu_baseline(inp, threads)
-    else:
-        out["cpu_baseline"] = None
+    if probe is not None:
+        out["stream_probe"] = dict(probe, elements=min(E, 1 << 28))
     print(json.dumps(out), flush=True)
 
 

@@ -7,12 +7,12 @@
  * (lambda_t, x_t) under  (a1,b1) (+) (a2,b2) = (a1*a2, a2*b1 + b2)  (Algorithm 1 of the
  * paper: per-chunk reduce, scan of the chunk summaries, per-chunk rescan from the carry),
  * and its backward pass, the same recurrence run in reverse over the upstream gradient
- * (Section 2.2, "Backpropagation").  AMD MI355X (gfx950) only.
+ * (Section 2.2).  AMD MI355X (gfx950) only.
  *
  * Conventions shared by every entry point
  *   - Tensors are fp32, contiguous, time-major [T, B, n]: element (t, b, i) lives at
- *     (t*B + b)*n + i.  The C = B*n columns are independent recurrences ("T vectors each of
- *     b*n elements", Section 3.1.1); time runs down the rows.
+ *     (t*B + b)*n + i.  The C = B*n columns are independent recurrences (the layout of
+ *     Section 3.1.1: T vectors of B*n elements); time runs down the rows.
  *   - Row t (0-based) holds the paper's lambda_{t+1}, x_{t+1}, h_{t+1}.  h0 [B, n] is the
  *     paper's h_0: an input, never an output row (the SCAN of Section 1 returns T outputs
  *     for T inputs).
@@ -24,15 +24,24 @@
  *     enqueue work and return: there is no host synchronisation, device-side faults surface
  *     at the caller's next synchronisation.
  *   - The library keeps one cached device workspace (chunk summaries, carries, look-back
- *     flags) per (device, stream); it is allocated on first use and grown on demand (this is
- *     the only place a call may block), and freed by linrec_release_workspace().  Calls that
- *     use the same stream from several host threads at once are not supported; calls on
- *     different streams are independent.
+ *     flags) per (device, stream); it is allocated on first use and grown on demand, and
+ *     linrec_reserve_workspace() sizes it ahead of time.  Growing allocates a new block
+ *     (hipMalloc: the only place a call may block) and RETIRES the old one, which stays
+ *     allocated until linrec_release_workspace(): kernels still queued on the stream, and
+ *     launches recorded in a HIP graph, keep pointing at memory that exists.  A call that
+ *     would have to grow the workspace while its stream is being captured returns
+ *     LINREC_ERR_CAPTURE and enqueues nothing: reserve, or make one eager call of the largest
+ *     shape, before capturing.  Calls that use the same stream from several host threads at
+ *     once are not supported; calls on different streams are independent.
  *   - Return value: LINREC_OK (0) or a negative LINREC_ERR_* code.  Arguments are validated
  *     before any HIP call is made.  T == 0 or B*n == 0 is a successful no-op (for T == 0 a
  *     non-NULL grad_h0 is zero-filled).
- *   - Results are deterministic for a fixed variant and tile shape (no floating-point
- *     atomics); different variants / tile shapes may differ in the last bits.
+ *   - No floating-point atomics anywhere.  The three-phase, walk and serial variants are
+ *     bitwise reproducible for a fixed tile shape.  The single pass (look-back) composes a
+ *     tile's carry-in from whichever predecessor summaries and states are published when
+ *     it looks, so two runs may associate the same terms differently and differ in the last
+ *     bit or two of a row; every such result is within the stated tolerances.  Different
+ *     variants / tile shapes differ in the last bits too.
  *   - Domain: finite inputs whose partial products of lambda stay finite (|lambda| <= 1 is
  *     always safe).  NaN/Inf propagate along their own column only.
  */
@@ -52,7 +61,8 @@ enum {
     LINREC_ERR_ALIAS = -3,  /* forbidden overlap between an output and another tensor       */
     LINREC_ERR_HIP = -4,    /* a HIP allocation or launch failed; see linrec_last_hip_error */
     LINREC_ERR_OPTION = -5, /* unknown option or value out of range                         */
-    LINREC_ERR_DEVICE = -6  /* a kernel reported a look-back wait that exceeded its limit   */
+    LINREC_ERR_DEVICE = -6, /* a kernel reported a look-back wait that exceeded its limit   */
+    LINREC_ERR_CAPTURE = -7 /* the workspace would have to grow while the stream is capturing */
 };
 
 /* Which kernel family evaluates the scan (linrec_set_option(LINREC_OPT_VARIANT, ...)). */
@@ -61,8 +71,9 @@ enum {
                                       wide problems                                           */
     LINREC_VARIANT_THREEPHASE = 1, /* Algorithm 1 as three kernels: reduce, scan, rescan     */
     LINREC_VARIANT_LOOKBACK = 2,   /* one kernel; chunk carries found by decoupled look-back */
-    LINREC_VARIANT_SERIAL = 3,     /* one thread per column walks T (the paper's baseline of
-                                      Section 4.1.1, "in serial over sequence length")       */
+    LINREC_VARIANT_SERIAL = 3,     /* one thread per column walks T: serial over the sequence,
+                                      parallel over features and minibatch (the comparison
+                                      kernel of Section 4.1.1)                               */
     LINREC_VARIANT_WALK = 4        /* one workgroup per group of columns walks T tile by tile:
                                       parallel over the sequence inside a tile only, nothing is
                                       exchanged between workgroups; what the library picks for
@@ -86,10 +97,19 @@ enum {
                                   let the library decide per pass (-1, default)              */
     LINREC_OPT_GRID_CAP = 8,   /* look-back, persistent: at most this many workgroups per
                                   compute unit; 0 (default) = as many as fit                 */
-    LINREC_OPT_STAGGER = 9     /* look-back: every other workgroup of the first round starts
+    LINREC_OPT_STAGGER = 9,    /* look-back: every other workgroup of the first round starts
                                   this many microseconds (roughly; 0..16) late, so that the
                                   workgroups do not load, scan and store in lock-step;
                                   only launches of two rounds or more; default 3, 0 = off    */
+    /* Test aids for the workspace-reuse paths of the single pass (no use outside tests): */
+    LINREC_OPT_TEST_FILL = 10, /* 32-bit pattern that the words of a NEWLY allocated look-back
+                                  workspace are filled with instead of zeros (stale words with
+                                  foreign tags); default 0                                    */
+    LINREC_OPT_TEST_EPOCH = 11 /* 0 .. 2^31-3: the thread's next single-pass call first sets its
+                                  workspace's stored epoch (calls completed; it wraps to 0 after
+                                  2^31-2) to this value and schedules the periodic clearing of
+                                  stale words for two calls later, i.e. before a small epoch can
+                                  run again; consumed by that call (-1 = none)                 */
 };
 
 /*
@@ -128,7 +148,7 @@ int linrec_backward(const float *lambda, const float *h, const float *h0, const 
  * nearest even on store.  6 bytes per element forward, 10 backward.  The paper's kernel is fp32 only
  * (Section 2.3): this is a bandwidth option, not one of its experiments.  Same layout, NULL and
  * aliasing rules as above.  Accuracy: each stored value is within half a bf16 unit in the last place
- * (2^-9 relative) of what the fp32 entry points would store for the same (bf16-valued) inputs, up
+ * (2^-8 relative at worst: bf16 keeps 8 significant bits) of what the fp32 entry points would store for the same (bf16-valued) inputs, up
  * to their own tolerance; the backward pass consumes the ROUNDED h it is given.
  * 4-byte aligned tensors with an even B*n use 4-byte accesses (8-byte ones when 8-byte aligned and
  * B*n is a multiple of 4); anything else falls back to the serial kernel.
@@ -144,8 +164,7 @@ enum { LINREC_TAU_IDENTITY = 0, LINREC_TAU_TANH = 1 };
 
 /*
  * Gated impulse linear recurrent layer, the part after its two matrix products, with the
- * activations applied inside the scan kernel (Section 3.1, "Gated impulse linear recurrent
- * layer"):
+ * activations applied inside the scan kernel (Section 3.1):
  *     g_t = sigmoid(g_pre[t]),   i_t = tau(i_pre[t]),   h_t = g_t * h_{t-1} + (1 - g_t) * i_t
  *   g_pre, i_pre : [T, B, n] pre-activations (U x_t + b_g and V x_t + b_z in the paper).
  *   h0           : [B, n] or NULL (zero state).      h_out : [T, B, n].
@@ -177,7 +196,7 @@ int linrec_gilr_backward(const float *g_pre, const float *i_pre, const float *h,
 
 /*
  * Cell of the GILR-LSTM, the part after its matrix products, with the activations applied inside
- * the scan kernel (Section 3.2, "Linear surrogate RNNs": the LSTM whose gates are computed from
+ * the scan kernel (Section 3.2: the LSTM whose gates are computed from
  * the surrogate state, so that c_t depends only linearly on c_{t-1}):
  *     f, i, o = sigmoid(f_pre, i_pre, o_pre)[t],   z = tanh(z_pre[t]),
  *     c_t = f * c_{t-1} + i * z,                    h_t = o * c_t
@@ -232,10 +251,11 @@ int linrec_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_t *i_pre,
                                    uint16_t *grad_z_pre, uint16_t *grad_o_pre, uint16_t *grad_c0,
                                    int64_t T, int64_t B, int64_t n, void *stream);
 
-/* Process-wide tuning knobs (LINREC_OPT_*).  Environment variables LINREC_VARIANT
- * ("auto", "threephase", "lookback", "serial", "walk") and LINREC_TILE (integer id) give the
- * initial values.  Returns LINREC_OK or LINREC_ERR_OPTION.  Not thread-safe against
- * concurrent linrec_forward/backward calls. */
+/* Tuning knobs (LINREC_OPT_*), one set PER HOST THREAD: a call uses the options of the thread
+ * that makes it, so a thread that changes them cannot disturb the calls of another.  Every
+ * thread starts from the environment variables LINREC_VARIANT ("auto", "threephase",
+ * "lookback", "serial", "walk") and LINREC_TILE (integer id), else the defaults.  Returns
+ * LINREC_OK or LINREC_ERR_OPTION.  For a plan that holds for all threads use linrec_pin_plan. */
 int linrec_set_option(int option, int64_t value);
 int64_t linrec_get_option(int option);
 
@@ -263,6 +283,24 @@ enum {
 int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward,
                     int alignment_bytes, int *variant, int *tile_id);
 
+/* Fixes the plan of one shape for every thread: later calls of entry-point family `entry_point`
+ * (LINREC_ENTRY_*) with exactly this [T, B, n] and pass on the current device use variant
+ * LINREC_VARIANT_LOOKBACK or LINREC_VARIANT_WALK with tile shape `tile_id`, `persistent` (-1, 0, 1 as
+ * LINREC_OPT_PERSISTENT) and `taper` (0..8 as LINREC_OPT_TAPER) -- the table linrec_tune writes; a
+ * thread's own LINREC_OPT_TILE / LINREC_OPT_VARIANT still take precedence.  A shape the family has no
+ * kernel for falls back to the automatic choice.  tile_id == 0 forgets the shape's entry.  Host-only
+ * apart from asking for the current device. */
+int linrec_pin_plan(int entry_point, int64_t T, int64_t B, int64_t n, int backward, int variant,
+                    int tile_id, int persistent, int taper);
+
+/* Sizes the cached workspace of (current device, stream) for a later call of this family, shape and
+ * pass, under the calling thread's options and the plans pinned or tuned so far and whatever the
+ * alignment of its tensors, so that the call itself allocates nothing (and can be captured in a HIP
+ * graph without an eager warm-up).  May allocate (blocking in hipMalloc) and enqueues a fill kernel
+ * on `stream`; must not be called while `stream` is capturing (LINREC_ERR_CAPTURE). */
+int linrec_reserve_workspace(int entry_point, int64_t T, int64_t B, int64_t n, int backward,
+                             void *stream);
+
 /*
  * Optional: finds the fastest plan (single-pass kernel: tile shape, persistent workgroups or not,
  * a tapered tail or not; for wide problems also the walk) for a [T, B, n] forward (backward = 0) or backward (1) pass by
@@ -270,7 +308,8 @@ int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backwa
  * later calls with this shape on the current device (when LINREC_OPT_TILE / LINREC_OPT_PERSISTENT /
  * LINREC_OPT_TAPER are automatic; a remembered walk only while LINREC_OPT_VARIANT is automatic too).
  * Blocking; allocates 3 (forward) or 5 (backward) tensors of T*B*n floats.  Returns LINREC_OK,
- * LINREC_ERR_SHAPE or LINREC_ERR_HIP.  Must not run concurrently with other liblinrec calls.
+ * LINREC_ERR_SHAPE or LINREC_ERR_HIP.  The candidates are forced on the calling thread's calls only;
+ * calls other threads make meanwhile keep their own plans (and disturb the timings).
  */
 int linrec_tune(int64_t T, int64_t B, int64_t n, int backward, void *stream);
 /* The same for one of the entry-point families LINREC_ENTRY_* (linrec_tune is LINREC_ENTRY_PLAIN);
@@ -340,8 +379,9 @@ int linrec_stream_probe(const float *in0, const float *in1, const float *in2, fl
  * itself failed, else LINREC_OK.  Optional: a healthy run never needs it. */
 int linrec_check(void *stream);
 
-/* Frees every cached workspace of the calling process (all devices, all streams).  The
- * caller must make sure no linrec call is still running on the GPU. */
+/* Frees every cached workspace of the calling process (all devices, all streams), retired blocks
+ * included.  The caller must make sure no linrec call is still running on the GPU and that no HIP
+ * graph holding a recorded linrec launch is replayed afterwards. */
 int linrec_release_workspace(void);
 
 /* Static strings; never NULL. */

@@ -170,10 +170,13 @@ def _slab_rows(T, C, slab_elems):
     return max(1, min(T, slab_elems // max(C, 1)))
 
 
-def forward_compare(lam, x, h0, h_cand, threads=1, slab_elems=1 << 24):
+def forward_compare(lam, x, h0, h_cand, threads=1, slab_elems=1 << 24, rel=0.0):
     """Stream the forward oracle in row slabs and fold error norms against the candidate ``h_cand``.
 
     Returns ``{"max_abs_err", "max_abs_ref", "worst_index"}``; never holds more than one fp64 slab.
+    With ``rel > 0`` the folded error is ``max(|cand - ref| - rel*|ref|)``: what is left of each element's
+    error after an allowance proportional to its own reference value (the rounding of a result that is
+    stored in a narrower type), so that a per-element bound ``rel*|ref| + tol`` can be checked at any size.
     """
     lam2 = _f32_2d(lam, "lambda")
     x2 = _f32_2d(x, "x")
@@ -196,6 +199,8 @@ def forward_compare(lam, x, h0, h_cand, threads=1, slab_elems=1 << 24):
 
         _run_over_columns(work, C, threads)
         err = np.abs(hc2[t0:t1].astype(np.float64) - slab)
+        if rel:
+            err -= rel * np.abs(slab)
         # NaN in either side must fail the comparison, not vanish in a max()
         if not np.all(np.isfinite(err)):
             bad = np.argwhere(~np.isfinite(err))[0]
@@ -209,10 +214,11 @@ def forward_compare(lam, x, h0, h_cand, threads=1, slab_elems=1 << 24):
     return {"max_abs_err": max_err, "max_abs_ref": max_ref, "worst_index": worst}
 
 
-def backward_compare(lam, h, h0, grad_h, gx_cand, glam_cand, gh0_cand, threads=1, slab_elems=1 << 24):
+def backward_compare(lam, h, h0, grad_h, gx_cand, glam_cand, gh0_cand, threads=1, slab_elems=1 << 24, rel=0.0):
     """Stream the backward oracle (last rows first) and fold error norms against candidates.
 
-    Returns a dict ``{name: {"max_abs_err", "max_abs_ref"}}`` for grad_x, grad_lambda, grad_h0.
+    Returns a dict ``{name: {"max_abs_err", "max_abs_ref"}}`` for grad_x, grad_lambda, grad_h0
+    (``rel`` as in :func:`forward_compare`).
     """
     lam2 = _f32_2d(lam, "lambda")
     h2 = _f32_2d(h, "h")
@@ -228,6 +234,8 @@ def backward_compare(lam, h, h0, grad_h, gx_cand, glam_cand, gh0_cand, threads=1
 
     def fold(name, cand, ref):
         err = np.abs(cand.astype(np.float64) - ref)
+        if rel:
+            err -= rel * np.abs(ref)
         m = float(np.max(err)) if err.size else 0.0
         if not np.all(np.isfinite(err)):
             m = float("inf")
@@ -353,3 +361,90 @@ def lstm_backward(f_pre, i_pre, z_pre, o_pre, c, c0, grad_h, threads=1):
             _ptr(outs[0]), _ptr(outs[1]), _ptr(outs[2]), _ptr(outs[3]), _ptr(gc0), T, C, 0, T, x0, x1), C, threads)
     shp = np.asarray(f_pre).shape
     return tuple(o.reshape(shp) for o in outs) + (gc0.reshape(shp[1:]),)
+
+
+# ---------------------------------------------------------------------------------------------
+# Element-complete comparison of the gated layer and the cell at sizes whose fp64 tensors would not
+# fit: the columns are independent recurrences, so the one-shot functions above are run on blocks of
+# whole columns (all T rows of each) and the error norms are folded block by block.
+# ---------------------------------------------------------------------------------------------
+def _fold(out, name, cand, ref, rel=0.0):
+    err = np.abs(np.asarray(cand, dtype=np.float64) - ref)
+    if rel:
+        err -= rel * np.abs(ref)
+    m = float(np.max(err)) if err.size else 0.0
+    if err.size and not np.all(np.isfinite(err)):   # NaN / Inf on either side fails the comparison
+        m = float("inf")
+    rec = out.setdefault(name, {"max_abs_err": 0.0, "max_abs_ref": 0.0})
+    rec["max_abs_err"] = max(rec["max_abs_err"], m)
+    rec["max_abs_ref"] = max(rec["max_abs_ref"], float(np.max(np.abs(ref))) if ref.size else 0.0)
+
+
+def _col_blocks(T, C, block_elems):
+    w = max(1, min(C, block_elems // max(T, 1)))
+    return [(c0, min(C, c0 + w)) for c0 in range(0, C, w)]
+
+
+def _cols(a, c0, c1):
+    return None if a is None else np.ascontiguousarray(a[..., c0:c1])
+
+
+def gilr_compare(g_pre, i_pre, h0, grad_h, h_cand, gg_cand, gi_cand, gh0_cand, tau=TAU_TANH, threads=1,
+                 block_elems=1 << 23, rel=0.0):
+    """Every element of a gated-layer result against :func:`gilr_forward` / :func:`gilr_backward`.
+
+    ``h_cand`` (fp32 values, [T, C]) is compared with the forward oracle and is also the ``h`` the
+    backward oracle is given, as the GPU backward pass is.  Gradient candidates may be None (skipped).
+    Returns ``{name: {"max_abs_err", "max_abs_ref"}}`` for h and the gradients that were given
+    (``rel`` as in :func:`forward_compare`)."""
+    g2, i2, hc, e2 = _f32_2d(g_pre, "g_pre"), _f32_2d(i_pre, "i_pre"), _f32_2d(h_cand, "h_cand"), None
+    T, C = g2.shape
+    h0v = _f32_1d(h0, C, "h0")
+    backward = grad_h is not None and any(c is not None for c in (gg_cand, gi_cand, gh0_cand))
+    if backward:
+        e2 = _f32_2d(grad_h, "grad_h")
+    out = {}
+    for c0, c1 in _col_blocks(T, C, block_elems):
+        gb, ib, hb, h0b = _cols(g2, c0, c1), _cols(i2, c0, c1), _cols(hc, c0, c1), _cols(h0v, c0, c1)
+        _fold(out, "h", hb, gilr_forward(gb, ib, h0b, tau, threads=threads), rel)
+        if backward:
+            refs = gilr_backward(gb, ib, hb, h0b, _cols(e2, c0, c1), tau, threads=threads)
+            for name, cand, ref in zip(("grad_g_pre", "grad_i_pre"), (gg_cand, gi_cand), refs[:2]):
+                if cand is not None:
+                    _fold(out, name, np.asarray(cand).reshape(T, C)[:, c0:c1], ref, rel)
+            if gh0_cand is not None:
+                _fold(out, "grad_h0", np.asarray(gh0_cand).reshape(C)[c0:c1], refs[2], rel)
+    return out
+
+
+def lstm_compare(f_pre, i_pre, z_pre, o_pre, c0, grad_h, c_cand, h_cand, grad_cands, gc0_cand, threads=1,
+                 block_elems=1 << 22, rel=0.0):
+    """Every element of an LSTM-cell result against :func:`lstm_forward` / :func:`lstm_backward`.
+
+    ``c_cand`` is compared with the forward oracle and is the cell state the backward oracle is given;
+    ``grad_cands`` holds the four pre-activation gradients (None entries are skipped)."""
+    pre = [_f32_2d(v, n) for v, n in ((f_pre, "f_pre"), (i_pre, "i_pre"), (z_pre, "z_pre"), (o_pre, "o_pre"))]
+    T, C = pre[0].shape
+    cc = _f32_2d(c_cand, "c_cand")
+    hc = None if h_cand is None else np.asarray(h_cand).reshape(T, C)
+    c0v = _f32_1d(c0, C, "c0")
+    grad_cands = [None] * 4 if grad_cands is None else list(grad_cands)
+    backward = grad_h is not None and (any(g is not None for g in grad_cands) or gc0_cand is not None)
+    e2 = _f32_2d(grad_h, "grad_h") if backward else None
+    out = {}
+    names = ("grad_f_pre", "grad_i_pre", "grad_z_pre", "grad_o_pre")
+    for a, b in _col_blocks(T, C, block_elems):
+        pb = [_cols(p, a, b) for p in pre]
+        cb, c0b = _cols(cc, a, b), _cols(c0v, a, b)
+        cref, href = lstm_forward(*pb, c0b, threads=threads)
+        _fold(out, "c", cb, cref, rel)
+        if hc is not None:
+            _fold(out, "h", hc[:, a:b], href, rel)
+        if backward:
+            refs = lstm_backward(*pb, cb, c0b, _cols(e2, a, b), threads=threads)
+            for name, cand, ref in zip(names, grad_cands, refs[:4]):
+                if cand is not None:
+                    _fold(out, name, np.asarray(cand).reshape(T, C)[:, a:b], ref, rel)
+            if gc0_cand is not None:
+                _fold(out, "grad_c0", np.asarray(gc0_cand).reshape(C)[a:b], refs[4], rel)
+    return out

@@ -14,6 +14,8 @@ VARIANT_AUTO, VARIANT_THREEPHASE, VARIANT_LOOKBACK, VARIANT_SERIAL, VARIANT_WALK
 TAU_IDENTITY, TAU_TANH = 0, 1
 OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE, OPT_TAPER, OPT_PERSISTENT, OPT_GRID_CAP = 1, 2, 3, 4, 5, 6, 7, 8
 OPT_STAGGER = 9
+OPT_TEST_FILL, OPT_TEST_EPOCH = 10, 11
+ERR_CAPTURE = -7
 
 
 class LinrecError(RuntimeError):
@@ -44,6 +46,10 @@ def lib():
         L.linrec_forward.restype = ci
         L.linrec_backward.argtypes = [p, p, p, p, p, p, p, i64, i64, i64, p]
         L.linrec_backward.restype = ci
+        L.linrec_pin_plan.argtypes = [ci, i64, i64, i64, ci, ci, ci, ci, ci]
+        L.linrec_pin_plan.restype = ci
+        L.linrec_reserve_workspace.argtypes = [ci, i64, i64, i64, ci, p]
+        L.linrec_reserve_workspace.restype = ci
         for fn in (L.linrec_forward_bf16,):
             fn.argtypes = [p, p, p, p, i64, i64, i64, p]
             fn.restype = ci
@@ -340,6 +346,18 @@ def linrec_plan_for(entry_point, T, B, n, backward=False, alignment=16):
     _check(lib().linrec_plan_for(int(entry_point), int(T), int(B), int(n), int(bool(backward)), int(alignment),
                                  ctypes.byref(v), ctypes.byref(t)))
     return v.value, t.value
+
+
+def linrec_pin_plan(entry_point, T, B, n, backward, variant, tile_id, persistent=-1, taper=0) -> None:
+    """Fixes the plan of one shape for all threads (``tile_id = 0`` forgets it); see include/linrec.h."""
+    _check(lib().linrec_pin_plan(int(entry_point), int(T), int(B), int(n), int(bool(backward)), int(variant),
+                                 int(tile_id), int(persistent), int(taper)))
+
+
+def linrec_reserve_workspace(entry_point, T, B, n, backward=False, stream=None) -> None:
+    """Sizes the stream's cached workspace for a later call of this shape, so that the call allocates nothing."""
+    _check(lib().linrec_reserve_workspace(int(entry_point), int(T), int(B), int(n), int(bool(backward)),
+                                          _stream_ptr(stream)))
 
 
 def linrec_stream_probe(in0, in1, in2, out0, out1, stream=None) -> None:

@@ -42,7 +42,9 @@ hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int for
 
 namespace {
 
-// ---- process-wide options ------------------------------------------------------------------
+// ---- options: one set per host thread ------------------------------------------------------
+// (A call reads the options of the thread that makes it, so a thread that changes them -- a sweep, the
+// tuner -- cannot change the plan of a call another thread is making.)
 struct Options {
     int64_t variant = LINREC_VARIANT_AUTO;
     int64_t tile = 0;
@@ -53,6 +55,10 @@ struct Options {
     int64_t grid_cap = 0;
     int64_t stagger = 3;
     int64_t persistent = -1;  // -1 automatic: forward persistent, backward one workgroup per tile (measured)
+    // test aids (see linrec.h): what a fresh look-back workspace is filled with, and a stored epoch to
+    // plant into the workspace of the thread's next single-pass call (-1: none)
+    int64_t test_fill = 0;
+    int64_t test_epoch = -1;
     Options()
     {
         if (const char *v = getenv("LINREC_VARIANT")) {
@@ -69,8 +75,20 @@ struct Options {
 };
 Options &opts()
 {
-    static Options o;
+    static thread_local Options o;
     return o;
+}
+
+// A plan handed to the calls of this thread explicitly (the tuner times its candidates this way):
+// takes the place of the variant / tile / persistent / taper options while `active`.
+struct ForcedPlan {
+    bool active = false;
+    int variant = LINREC_VARIANT_LOOKBACK, tile = 0, persistent = -1, taper = 0;
+};
+ForcedPlan &forced()
+{
+    static thread_local ForcedPlan f;
+    return f;
 }
 
 char g_hip_error[256] = "";
@@ -84,14 +102,18 @@ int hip_fail(hipError_t e, const char *what)
 // ---- workspace -----------------------------------------------------------------------------
 // One per (device, stream).  The look-back words live in their own allocation that nothing else
 // ever writes, because a stale word is told from a fresh one only by its epoch.
+// A block that has been handed to a launch is never freed before linrec_release_workspace(): when a
+// larger problem arrives a new block is allocated and the old one is retired, so kernels still queued
+// on the stream, and launches recorded in a HIP graph, keep pointing at memory that exists.
 struct Workspace {
-    // look-back: [LookbackHeader, padded to 256 B][3*K*C u64 words]
+    // look-back: [LookbackHeader, padded to kLbHeader bytes][3*K*C u64 words]
     void *lb = nullptr;
     size_t lb_bytes = 0;
     unsigned long long calls_since_clear = 0;
     // three-phase: aggP, aggS, carry, each K*C fp64
     void *tp = nullptr;
     size_t tp_bytes = 0;
+    std::vector<void *> retired_lb, retired_tp;
 };
 std::mutex g_mu;
 std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
@@ -99,29 +121,46 @@ std::map<std::pair<int, hipStream_t>, Workspace> g_ws;
 constexpr size_t kLbHeader = 512;
 static_assert(sizeof(LookbackHeader) <= kLbHeader, "header must fit its slot");
 
-// Grows the buffer if needed.  Growing waits for the stream (older kernels may still use the old
-// buffer), which only happens while the problem sizes seen on a stream are still increasing.
-int ensure(void **buf, size_t *have, size_t need, bool zero, hipStream_t s)
+// Grows the block if needed: a new allocation (at least half as large again as the old one, so that
+// the retired blocks of a stream whose problems keep growing add up to less than twice the live one),
+// filled on the stream.  Nothing waits: the old block stays valid for whatever still uses it.  Look-back
+// blocks start as zeros (header and words: the kernels' epoch convention makes that a valid start), or,
+// for the reuse tests, with the words holding LINREC_OPT_TEST_FILL.
+int ensure(Workspace &ws, void **buf, size_t *have, size_t need, bool lookback, hipStream_t s)
 {
     if (*have >= need) return LINREC_OK;
     hipError_t e;
-    if (*buf) {
-        if ((e = hipStreamSynchronize(s)) != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
-        if ((e = hipFree(*buf)) != hipSuccess) return hip_fail(e, "hipFree");
-        *buf = nullptr;
-        *have = 0;
-    }
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &cap) == hipSuccess && cap != hipStreamCaptureStatusNone) return LINREC_ERR_CAPTURE;
+    need = std::max(need, *have + *have / 2);
     need = (need + ((size_t)1 << 20) - 1) & ~(((size_t)1 << 20) - 1);
-    if ((e = hipMalloc(buf, need)) != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
-    if (zero && (e = hipMemset(*buf, 0, need)) != hipSuccess) return hip_fail(e, "hipMemset(workspace)");
+    void *fresh = nullptr;
+    if ((e = hipMalloc(&fresh, need)) != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
+    if (lookback) {
+        e = launch_fill((float *)fresh, 0.0f, (int64_t)(kLbHeader / sizeof(float)), s);
+        uint32_t bits = (uint32_t)opts().test_fill;
+        float pattern;
+        memcpy(&pattern, &bits, sizeof pattern);
+        if (e == hipSuccess)
+            e = launch_fill((float *)((char *)fresh + kLbHeader), pattern, (int64_t)((need - kLbHeader) / sizeof(float)), s);
+        if (e != hipSuccess) {
+            (void)hipFree(fresh);
+            return hip_fail(e, "launch(fill workspace)");
+        }
+    }
+    if (*buf) (lookback ? ws.retired_lb : ws.retired_tp).push_back(*buf);
+    *buf = fresh;
     *have = need;
+    if (lookback) ws.calls_since_clear = 0;
     return LINREC_OK;
 }
 
 // Workgroups the device holds at once, for sizing the tail of short tiles: compute units x 3.
 int resident_workgroups(int dev)
 {
-    static std::map<int, int> cache;  // guarded by g_mu (callers hold it)
+    static std::mutex mu;
+    static std::map<int, int> cache;
+    std::lock_guard<std::mutex> lock(mu);
     auto it = cache.find(dev);
     if (it != cache.end()) return it->second;
     int cus = 0;
@@ -500,18 +539,21 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
 {
     const bool gated = form != FORM_PLAIN;
     Plan p;
-    p.variant = (int)opts().variant;
+    // what the caller asked for: the thread's options, or the plan a tuner forces on this thread's calls
+    const ForcedPlan &fp = forced();
+    const int want_variant = fp.active ? fp.variant : (int)opts().variant;
+    p.variant = want_variant;
     if (p.variant == LINREC_VARIANT_AUTO) p.variant = LINREC_VARIANT_LOOKBACK;
-    p.tile = (int)opts().tile;
-    p.persistent = (int)opts().persistent;
-    p.taper = (int)opts().taper;
-    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK) {  // a tuned plan, if there is one for this shape
+    p.tile = fp.active ? fp.tile : (int)opts().tile;
+    p.persistent = fp.active ? fp.persistent : (int)opts().persistent;
+    p.taper = fp.active ? fp.taper : (int)opts().taper;
+    if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK) {  // a pinned or tuned plan, if there is one for this shape
         const int family = entry_family(form, bf16);
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess) {
             std::lock_guard<std::mutex> lock(g_tuned_mu);
             auto it = g_tuned.find(TunedKey{dev, T, C, bwd, family});
-            if (it != g_tuned.end() && (it->second.variant == LINREC_VARIANT_LOOKBACK || opts().variant == LINREC_VARIANT_AUTO)) {
+            if (it != g_tuned.end() && (it->second.variant == LINREC_VARIANT_LOOKBACK || want_variant == LINREC_VARIANT_AUTO)) {
                 p.tile = it->second.tile;
                 p.variant = it->second.variant;
                 if (p.persistent < 0) p.persistent = it->second.persistent;
@@ -520,7 +562,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
         }
     }
     // No option and no tuned plan: short, wide problems take the walk.
-    if (opts().variant == LINREC_VARIANT_AUTO && p.tile == 0) {
+    if (want_variant == LINREC_VARIANT_AUTO && p.tile == 0) {
         const int wt = gated ? (bf16 ? auto_walk_tile_form_bf16(T, C, vec, bwd, form) : auto_walk_tile_form(T, C, vec, bwd, form))
                        : bf16 ? auto_walk_tile_bf16(T, C, vec, bwd)
                               : auto_walk_tile(T, C, vec, bwd);
@@ -557,6 +599,59 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     return p;
 }
 
+// Tiles along time of a single-pass launch: K1 of full height, then K2 of half height, the rest a quarter
+// (the tapered tail; K2 = 0 and K = K1 without it).
+struct TimeTiles {
+    int64_t K, K1, K2;
+};
+TimeTiles time_tiles(int64_t T, int64_t G, const TileDesc &d, int taper, int dev)
+{
+    const int64_t tiles_t = ceil_div(T, d.rows());
+    TimeTiles tt{tiles_t, tiles_t, 0};
+    if (taper && d.r % 4 == 0 && d.r >= 8) {
+        const int64_t rows = d.rows();
+        const int64_t full = T / rows;                                   // complete full-height tiles
+        // full tiles per chain that are in flight at once; `taper` eighths of them are cut up
+        const int64_t resident = (int64_t)resident_workgroups(dev) * (d.threads() >= 512 ? 1 : 3) / 3;
+        const int64_t round = ceil_div(resident, G);
+        const int64_t taper_tiles = std::min(full / 2, (round * taper + 7) / 8);
+        if (taper_tiles > 0) {
+            tt.K1 = full - taper_tiles;
+            const int64_t left = T - tt.K1 * rows;                        // rows in the tapered region
+            tt.K2 = (left / 2) / (rows / 2);
+            const int64_t rest = left - tt.K2 * (rows / 2);
+            tt.K = tt.K1 + tt.K2 + ceil_div(rest, rows / 4);
+        }
+    }
+    return tt;
+}
+
+size_t lookback_bytes(int64_t K, int64_t C) { return kLbHeader + 3 * (size_t)K * (size_t)C * sizeof(unsigned long long); }
+
+// Hands a single-pass launch its look-back block: clears it when its tags are about to come round, and
+// plants the stored epoch a reuse test asked for.  `calls` is the block's count of calls since it was
+// last cleared.
+int prepare_lookback(Args &A, void *block, size_t bytes, unsigned long long *calls, hipStream_t s)
+{
+    hipError_t e;
+    // The 31-bit epoch wraps after 2^31 - 1 calls; long before that, forget every stale word so that a
+    // slot untouched for that long cannot be mistaken for a fresh one.
+    if (++*calls >= (1ull << 30)) {
+        if ((e = launch_fill((float *)((char *)block + kLbHeader), 0.0f, (int64_t)((bytes - kLbHeader) / sizeof(float)), s)) != hipSuccess)
+            return hip_fail(e, "launch(fill)");
+        *calls = 0;
+    }
+    if (opts().test_epoch >= 0) {  // test aid: the next clear comes two calls from now, before the planted epoch can wrap
+        if ((e = launch_set_epoch((LookbackHeader *)block, (uint32_t)opts().test_epoch, s)) != hipSuccess)
+            return hip_fail(e, "launch(set_epoch)");
+        *calls = (1ull << 30) - 2;
+        opts().test_epoch = -1;
+    }
+    A.hdr = (LookbackHeader *)block;
+    A.lbAgg = (unsigned long long *)((char *)block + kLbHeader);
+    return LINREC_OK;
+}
+
 // gated: the form of Section 3.1 (activations applied in the kernel); it exists as the single-pass and
 // walk kernels of the tile shapes with a multiple of 8 (or fewer than 8) rows per thread, and as the
 // serial kernel.
@@ -584,8 +679,6 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
 
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e, "hipGetDevice");
-    std::lock_guard<std::mutex> lock(g_mu);
-    Workspace &ws = g_ws[std::make_pair(dev, s)];
 
     if (plan.variant == LINREC_VARIANT_THREEPHASE) {
         // enough chunks to fill the GPU several times over, few enough that phase 2 stays small
@@ -596,9 +689,13 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
         A.M = (int32_t)M;
         A.K = ceil_div(tiles_t, M);
         const size_t kc = (size_t)A.K * (size_t)A.C;
-        int rc = ensure(&ws.tp, &ws.tp_bytes, 3 * kc * sizeof(double), false, s);
-        if (rc != LINREC_OK) return rc;
-        A.aggP = (double *)ws.tp;
+        {
+            std::lock_guard<std::mutex> lock(g_mu);  // (the workspace table only; launches run unlocked)
+            Workspace &ws = g_ws[std::make_pair(dev, s)];
+            const int rc = ensure(ws, &ws.tp, &ws.tp_bytes, 3 * kc * sizeof(double), false, s);
+            if (rc != LINREC_OK) return rc;
+            A.aggP = (double *)ws.tp;
+        }
         A.aggS = A.aggP + kc;
         A.carry = A.aggS + kc;
         if ((e = launch_tile_kernel(plan.tile, KIND_REDUCE, bwd, false, FORM_PLAIN, false, A, s)) != hipSuccess)
@@ -611,48 +708,20 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
     }
 
     // Single pass with look-back.  The rows that the last "round" of resident workgroups would take
-    // as full tiles are cut into half- and quarter-height tiles instead (see k_lookback).
+    // as full tiles are cut into half- and quarter-height tiles instead when the plan says so (see k_lookback).
     A.M = 1;
-    A.K1 = tiles_t;
-    A.K2 = 0;
-    A.K = tiles_t;
-    if (plan.taper && d.r % 4 == 0 && d.r >= 8) {
-        const int64_t rows = d.rows();
-        const int64_t full = A.T / rows;                                   // complete full-height tiles
-        // full tiles per chain that are in flight at once; plan.taper eighths of them are cut up
-        const int64_t resident = (int64_t)resident_workgroups(dev) * (d.threads() >= 512 ? 1 : 3) / 3;
-        const int64_t round = ceil_div(resident, A.G);
-        const int64_t taper_tiles = std::min(full / 2, (round * plan.taper + 7) / 8);
-        if (taper_tiles > 0) {
-            A.K1 = full - taper_tiles;
-            const int64_t left = A.T - A.K1 * rows;                        // rows in the tapered region
-            A.K2 = (left / 2) / (rows / 2);
-            const int64_t rest = left - A.K2 * (rows / 2);
-            A.K = A.K1 + A.K2 + ceil_div(rest, rows / 4);
-        }
+    const TimeTiles tt = time_tiles(A.T, A.G, d, plan.taper, dev);
+    A.K = tt.K;
+    A.K1 = tt.K1;
+    A.K2 = tt.K2;
+    const size_t need = lookback_bytes(A.K, A.C);
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        Workspace &ws = g_ws[std::make_pair(dev, s)];
+        int rc = ensure(ws, &ws.lb, &ws.lb_bytes, need, true, s);
+        if (rc == LINREC_OK) rc = prepare_lookback(A, ws.lb, ws.lb_bytes, &ws.calls_since_clear, s);
+        if (rc != LINREC_OK) return rc;
     }
-    const size_t kc = (size_t)A.K * (size_t)A.C;
-    const size_t old_bytes = ws.lb_bytes;
-    int rc = ensure(&ws.lb, &ws.lb_bytes, kLbHeader + 3 * kc * sizeof(unsigned long long), true, s);
-    if (rc != LINREC_OK) return rc;
-    // The 31-bit epoch wraps after 2^31 calls; long before that, forget every stale word so that a
-    // slot untouched for that long cannot be mistaken for a fresh one.
-    const bool fresh = ws.lb_bytes != old_bytes;
-    if (fresh || ++ws.calls_since_clear >= (1ull << 30)) {
-        if (!fresh && (e = launch_fill((float *)((char *)ws.lb + kLbHeader), 0.0f,
-                                       (int64_t)((ws.lb_bytes - kLbHeader) / sizeof(float)), s)) != hipSuccess)
-            return hip_fail(e, "launch(fill)");
-        if (fresh) {  // a zeroed buffer: start at epoch 1 (tag 0 is what untouched words carry)
-            LookbackHeader h0;
-            memset(&h0, 0, sizeof h0);
-            h0.epoch = 1;
-            if ((e = hipMemcpy(ws.lb, &h0, sizeof h0, hipMemcpyHostToDevice)) != hipSuccess)
-                return hip_fail(e, "hipMemcpy(workspace header)");
-        }
-        ws.calls_since_clear = 0;
-    }
-    A.hdr = (LookbackHeader *)ws.lb;
-    A.lbAgg = (unsigned long long *)((char *)ws.lb + kLbHeader);
     A.spin_limit = (uint32_t)opts().spin_limit;
     A.persistent = plan.persistent < 0 ? ((bwd && !gated) ? 0 : 1) : plan.persistent;
     A.grid_cap = (int32_t)opts().grid_cap;
@@ -1001,6 +1070,14 @@ extern "C" int linrec_set_option(int option, int64_t value)
         if (value < 0 || value > 16) return LINREC_ERR_OPTION;
         opts().stagger = value;
         return LINREC_OK;
+    case LINREC_OPT_TEST_FILL:
+        if (value < 0 || value > 0xffffffffll) return LINREC_ERR_OPTION;
+        opts().test_fill = value;
+        return LINREC_OK;
+    case LINREC_OPT_TEST_EPOCH:
+        if (value < -1 || value > 0x7ffffffdll) return LINREC_ERR_OPTION;
+        opts().test_epoch = value;
+        return LINREC_OK;
     default: return LINREC_ERR_OPTION;
     }
 }
@@ -1017,6 +1094,8 @@ extern "C" int64_t linrec_get_option(int option)
     case LINREC_OPT_PERSISTENT: return opts().persistent;
     case LINREC_OPT_GRID_CAP: return opts().grid_cap;
     case LINREC_OPT_STAGGER: return opts().stagger;
+    case LINREC_OPT_TEST_FILL: return opts().test_fill;
+    case LINREC_OPT_TEST_EPOCH: return opts().test_epoch;
     default: return LINREC_ERR_OPTION;
     }
 }
@@ -1159,8 +1238,12 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
     float best_ms = 0.f, second_ms = 0.f;
     if (rc == LINREC_OK) {
         const int vec = bf16 ? max_vec_bf16(C, {}) : max_vec(C, {});
-        const Options saved = opts();
-        opts().variant = LINREC_VARIANT_LOOKBACK;
+        // (candidates are forced on this thread's calls only; the options stay as they are)
+        const int64_t saved_taper = opts().taper;
+        ForcedPlan &fp = forced();
+        fp = ForcedPlan{};
+        fp.active = true;
+        fp.variant = LINREC_VARIANT_LOOKBACK;
         static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0},
                          gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 0},
                          bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 0};
@@ -1181,8 +1264,9 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
             if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
             if (d.rows() > 2 * T && tile != 18) continue;  // far taller than the problem
             for (int persistent = 0; persistent <= 1 && rc == LINREC_OK; ++persistent) {
-                opts().tile = tile;
-                opts().persistent = persistent;
+                fp.tile = tile;
+                fp.persistent = persistent;
+                fp.taper = (int)saved_taper;
                 float times[5];
                 for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {  // two warm-up launches, five timed
                     if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
@@ -1216,12 +1300,12 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         // half a percent faster than the best so far; an explicit LINREC_OPT_TAPER overrides what is
         // remembered).
         const TunedPlan untapered[2] = {best, second};
-        for (int c = 0; c < 2 && rc == LINREC_OK && saved.taper == 0; ++c) {
+        for (int c = 0; c < 2 && rc == LINREC_OK && saved_taper == 0; ++c) {
             const TunedPlan &u = untapered[c];
             if (u.tile == 0 || kTiles[u.tile - 1].r % 4 != 0 || kTiles[u.tile - 1].r < 8) continue;
-            opts().tile = u.tile;
-            opts().persistent = u.persistent;
-            opts().taper = 2;
+            fp.tile = u.tile;
+            fp.persistent = u.persistent;
+            fp.taper = 2;
             float times[5];
             for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {
                 if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
@@ -1244,7 +1328,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
                 }
             }
         }
-        opts().taper = saved.taper;
+        fp.taper = (int)saved_taper;
         // The walk, where there are enough columns for it to stand a chance: the shapes its automatic
         // rule would take at this width.
         int walk_c[3] = {0, 0, 0};
@@ -1264,13 +1348,13 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
                 if (!walk_c[0]) walk_c[0] = 21;
             }
         }
-        opts().variant = LINREC_VARIANT_WALK;
-        opts().persistent = -1;
+        fp.variant = LINREC_VARIANT_WALK;
+        fp.persistent = -1;
         for (int i = 0; walk_c[i] && rc == LINREC_OK; ++i) {
             const int tile = walk_c[i];
             const TileDesc &d = kTiles[tile - 1];
             if (d.vec > vec || ((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
-            opts().tile = tile;
+            fp.tile = tile;
             float times[5];
             for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {
                 if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
@@ -1291,7 +1375,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
                 best = TunedPlan{tile, -1, LINREC_VARIANT_WALK};
             }
         }
-        opts() = saved;
+        fp = ForcedPlan{};
     }
     if (ev0) (void)hipEventDestroy(ev0);
     if (ev1) (void)hipEventDestroy(ev1);
@@ -1304,6 +1388,71 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         std::lock_guard<std::mutex> lock(g_tuned_mu);
         g_tuned[TunedKey{dev, T, C, bwd, entry_point}] = best;
     }
+    return rc;
+}
+
+extern "C" int linrec_pin_plan(int entry_point, int64_t T, int64_t B, int64_t n, int backward, int variant, int tile_id,
+                               int persistent, int taper)
+{
+    if (T <= 0 || B <= 0 || n <= 0 || B > ((int64_t)1 << 40) / n || T > ((int64_t)1 << 40) / (B * n))
+        return LINREC_ERR_SHAPE;
+    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_LSTM_CELL_BF16) return LINREC_ERR_OPTION;
+    if (tile_id < 0 || tile_id > NUM_TILES || persistent < -1 || persistent > 1 || taper < 0 || taper > 8)
+        return LINREC_ERR_OPTION;
+    if (tile_id != 0 && variant != LINREC_VARIANT_LOOKBACK && variant != LINREC_VARIANT_WALK) return LINREC_ERR_OPTION;
+    int dev = 0;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    const TunedKey key{dev, T, B * n, backward != 0, entry_point};
+    std::lock_guard<std::mutex> lock(g_tuned_mu);
+    if (tile_id == 0) {
+        g_tuned.erase(key);
+    } else {
+        TunedPlan tp{tile_id, persistent, variant};
+        tp.taper = taper;
+        g_tuned[key] = tp;
+    }
+    return LINREC_OK;
+}
+
+extern "C" int linrec_reserve_workspace(int entry_point, int64_t T, int64_t B, int64_t n, int backward, void *stream)
+{
+    if (T <= 0 || B <= 0 || n <= 0 || B > ((int64_t)1 << 40) / n || T > ((int64_t)1 << 40) / (B * n))
+        return LINREC_ERR_SHAPE;
+    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_LSTM_CELL_BF16) return LINREC_ERR_OPTION;
+    const int64_t C = B * n;
+    hipStream_t s = (hipStream_t)stream;
+    int dev = 0;
+    const hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    // Room for what a call of this shape would use under the calling thread's options and the plans pinned
+    // or tuned so far, whatever the alignment of its tensors turns out to be (the widest access a plan may
+    // use depends on it).
+    const bool bf16 = entry_bf16(entry_point), bwd = backward != 0;
+    const int form = entry_form(entry_point);
+    size_t need_lb = 0, need_tp = 0;
+    for (int vec = 1; vec <= 4; vec *= 2) {
+        if (vec > 1 && C % vec != 0) continue;
+        Plan plan = make_plan(T, C, vec, bwd, form, bf16);
+        if ((form != FORM_PLAIN || bf16) && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
+        if (plan.variant != LINREC_VARIANT_LOOKBACK && plan.variant != LINREC_VARIANT_THREEPHASE) continue;
+        const TileDesc &d = kTiles[plan.tile - 1];
+        const int64_t G = ceil_div(C, d.cols());
+        if (plan.variant == LINREC_VARIANT_LOOKBACK) {
+            need_lb = std::max(need_lb, lookback_bytes(time_tiles(T, G, d, plan.taper, dev).K, C));
+        } else {
+            const int64_t tiles_t = ceil_div(T, d.rows());
+            int64_t M = opts().chunk_tiles;
+            if (M <= 0) M = ceil_div(tiles_t * G, 4096);
+            M = std::max<int64_t>(1, std::min<int64_t>(M, 1 << 20));
+            need_tp = std::max(need_tp, 3 * (size_t)ceil_div(tiles_t, M) * (size_t)C * sizeof(double));
+        }
+    }
+    std::lock_guard<std::mutex> lock(g_mu);
+    Workspace &ws = g_ws[std::make_pair(dev, s)];
+    int rc = LINREC_OK;
+    if (need_lb) rc = ensure(ws, &ws.lb, &ws.lb_bytes, need_lb, true, s);
+    if (rc == LINREC_OK && need_tp) rc = ensure(ws, &ws.tp, &ws.tp_bytes, need_tp, false, s);
     return rc;
 }
 
@@ -1324,15 +1473,27 @@ extern "C" int linrec_check(void *stream)
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e, "hipGetDevice");
-    std::lock_guard<std::mutex> lock(g_mu);
-    auto it = g_ws.find(std::make_pair(dev, s));
-    if (it == g_ws.end() || !it->second.lb) return LINREC_OK;
-    uint32_t flag = 0;
-    char *p = (char *)it->second.lb + offsetof(LookbackHeader, err);
-    if ((e = hipMemcpy(&flag, p, sizeof flag, hipMemcpyDeviceToHost)) != hipSuccess) return hip_fail(e, "hipMemcpy");
-    if (!flag) return LINREC_OK;
-    if ((e = hipMemset(p, 0, sizeof flag)) != hipSuccess) return hip_fail(e, "hipMemset");
-    return LINREC_ERR_DEVICE;
+    // every block that may hold the header of a launch on this stream: the live look-back block and the
+    // retired ones
+    std::vector<void *> headers;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_ws.find(std::make_pair(dev, s));
+        if (it != g_ws.end()) {
+            if (it->second.lb) headers.push_back(it->second.lb);
+            headers.insert(headers.end(), it->second.retired_lb.begin(), it->second.retired_lb.end());
+        }
+    }
+    int rc = LINREC_OK;
+    for (void *h : headers) {
+        uint32_t flag = 0;
+        char *p = (char *)h + offsetof(LookbackHeader, err);
+        if ((e = hipMemcpy(&flag, p, sizeof flag, hipMemcpyDeviceToHost)) != hipSuccess) return hip_fail(e, "hipMemcpy");
+        if (!flag) continue;
+        if ((e = hipMemset(p, 0, sizeof flag)) != hipSuccess) return hip_fail(e, "hipMemset");
+        rc = LINREC_ERR_DEVICE;
+    }
+    return rc;
 }
 
 extern "C" int linrec_release_workspace(void)
@@ -1345,6 +1506,10 @@ extern "C" int linrec_release_workspace(void)
         if (hipSetDevice(kv.first.first) != hipSuccess) { rc = LINREC_ERR_HIP; continue; }
         if (kv.second.lb && hipFree(kv.second.lb) != hipSuccess) rc = LINREC_ERR_HIP;
         if (kv.second.tp && hipFree(kv.second.tp) != hipSuccess) rc = LINREC_ERR_HIP;
+        for (void *p : kv.second.retired_lb)
+            if (hipFree(p) != hipSuccess) rc = LINREC_ERR_HIP;
+        for (void *p : kv.second.retired_tp)
+            if (hipFree(p) != hipSuccess) rc = LINREC_ERR_HIP;
     }
     g_ws.clear();
     if (have_cur) (void)hipSetDevice(cur);

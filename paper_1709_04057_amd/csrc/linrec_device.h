@@ -1214,7 +1214,10 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         sEpoch = __hip_atomic_load(&A.hdr->epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    const uint32_t epoch = __builtin_amdgcn_readfirstlane(sEpoch);
+    // The header stores the number of calls completed so far (modulo 2^31 - 1); the call's epoch is one
+    // more, 1 .. 2^31-1, so that a zero-filled workspace -- header and words -- is a valid start: tag 0 is
+    // what untouched words carry and no call ever uses it.
+    const uint32_t epoch = __builtin_amdgcn_readfirstlane(sEpoch) + 1u;
     const uint32_t tag_agg = epoch << 1, tag_incl = tag_agg | 1u;
     uint32_t ticket = __builtin_amdgcn_readfirstlane(sTicket[0]);
     int slot = 0;
@@ -1417,7 +1420,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
         if (finished == (unsigned long long)gridDim.x) {
             __hip_atomic_store(&A.hdr->done, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             __hip_atomic_store(&A.hdr->ticket, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&A.hdr->epoch, epoch >= 0x7fffffffu ? 1u : epoch + 1u, __ATOMIC_RELAXED,
+            __hip_atomic_store(&A.hdr->epoch, epoch >= 0x7fffffffu ? 0u : epoch, __ATOMIC_RELAXED,
                                __HIP_MEMORY_SCOPE_AGENT);
         }
     }

@@ -16,7 +16,8 @@ struct LookbackHeader {
     unsigned long long pad0[15];
     unsigned long long done;    // workgroups of the running call that have finished their look-back
     unsigned long long pad1[15];
-    uint32_t epoch;             // 1 .. 2^31-1; tags are epoch<<1 (summary) and epoch<<1|1 (inclusive state)
+    uint32_t epoch;             // calls completed, 0 .. 2^31-2; the running call's epoch is this + 1, and its
+                                // tags are epoch<<1 (summary) and epoch<<1|1 (inclusive state)
     uint32_t err;               // set when a look-back wait gave up
     unsigned long long pad2[15];
 };
@@ -118,6 +119,7 @@ hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const f
                                  int64_t C, hipStream_t s);
 hipError_t launch_serial(const Args &A, bool bwd, int form, bool bf16, hipStream_t s);
 hipError_t launch_fill(float *p, float value, int64_t n, hipStream_t s);
+hipError_t launch_set_epoch(LookbackHeader *hdr, uint32_t stored_epoch, hipStream_t s);  // test aid
 hipError_t launch_fill16(void *p, int64_t n, hipStream_t s);  // n 16-bit zeros
 hipError_t launch_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
                                int64_t n, hipStream_t s);

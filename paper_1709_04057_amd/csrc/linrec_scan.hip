@@ -285,6 +285,13 @@ __global__ void k_fill(float *p, float value, int64_t n)
         p[i] = value;
 }
 
+// Test aid: plants a stored epoch (calls completed so far) into a look-back header, so that the
+// reuse paths close to the epoch's wrap can be exercised without 2^31 calls.
+__global__ void k_set_epoch(LookbackHeader *hdr, uint32_t stored_epoch)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) hdr->epoch = stored_epoch;
+}
+
 // Streaming probe: the bandwidth a kernel with this library's access instructions reaches when it
 // does nothing but move data.  Reads the non-null inputs, writes the non-null outputs, 16 bytes per
 // lane per access, PROBE_R independent accesses per tensor in flight per thread.
@@ -385,6 +392,12 @@ hipError_t launch_fill16(void *p, int64_t n, hipStream_t s)
     if (n <= 0) return hipSuccess;
     const int64_t blocks = std::min<int64_t>((n + 255) / 256, 65536);
     hipLaunchKernelGGL(k_fill16, dim3((unsigned)blocks), dim3(256), 0, s, (unsigned short *)p, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_set_epoch(LookbackHeader *hdr, uint32_t stored_epoch, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_set_epoch, dim3(1), dim3(64), 0, s, hdr, stored_epoch);
     return hipGetLastError();
 }
 

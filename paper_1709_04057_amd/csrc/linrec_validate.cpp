@@ -242,8 +242,9 @@ extern "C" const char *linrec_status_string(int status)
     case LINREC_ERR_HIP: return "HIP allocation or launch failed";
     case LINREC_ERR_OPTION: return "unknown option or value out of range";
     case LINREC_ERR_DEVICE: return "a look-back wait exceeded its spin limit";
+    case LINREC_ERR_CAPTURE: return "the workspace would have to grow while the stream is capturing";
     default: return "unknown status";
     }
 }
 
-extern "C" int linrec_version(void) { return 104; }
+extern "C" int linrec_version(void) { return 105; }

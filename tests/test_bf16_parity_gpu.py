@@ -14,7 +14,7 @@ import torch
 import linrec_workloads as wl
 import oracle
 import paper_1709_04057_amd as lr
-from parity import FWD_TOL, GRAD_TOL, ORACLE_THREADS, all_tiles, options, say
+from parity import FWD_TOL, GRAD_TOL, ORACLE_THREADS, all_tiles, check_norms, host_f32, options, say, reruns_agree
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -114,12 +114,12 @@ def test_unaligned_views_and_optional_outputs():
     gx, gl, gh0 = lr.linrec_backward(inp["lam"], want, None, inp["grad_h"], want_grad_lambda=False, want_grad_h0=False)
     full = lr.linrec_backward(inp["lam"], want, None, inp["grad_h"])
     torch.cuda.synchronize()
-    assert gl is None and gh0 is None and torch.equal(gx, full[0])
+    assert gl is None and gh0 is None and reruns_agree(gx, full[0])
     # in place on x, and grad_x in place on grad_h
     xb = inp["x"].clone()
-    assert torch.equal(lr.linrec_forward(inp["lam"], xb, None, h_out=xb), want)
+    assert reruns_agree(lr.linrec_forward(inp["lam"], xb, None, h_out=xb), want)
     eb = inp["grad_h"].clone()
-    assert torch.equal(lr.linrec_backward(inp["lam"], want, None, eb, grad_x=eb)[0], full[0])
+    assert reruns_agree(lr.linrec_backward(inp["lam"], want, None, eb, grad_x=eb)[0], full[0])
     # empty problems
     e = torch.empty((0, 2, 64), dtype=torch.bfloat16, device=DEV)
     g0 = torch.ones((2, 64), dtype=torch.bfloat16, device=DEV)
@@ -145,13 +145,21 @@ def test_lambda_zero_is_a_copy_and_lambda_one_a_prefix_sum():
 
 
 @pytest.mark.parametrize("cfg", [2, 4])
-def test_full_size_workloads_on_sampled_columns(cfg):
+def test_full_size_workloads_every_element(cfg):
+    # every element, through the oracle's slab-streaming comparison on the exactly widened bf16 values, each
+    # allowed half a bf16 unit in the last place of its reference on top of the fp32 path's tolerance
     spec = wl.CONFIGS[cfg]
     inp = to_bf16(wl.make_inputs(cfg, device=DEV))
     T, C = spec["T"], spec["B"] * spec["n"]
-    rng = np.random.default_rng(cfg)
-    k = max(8, min(C, (1 << 23) // T))
-    cols = np.sort(rng.choice(C, size=min(k, C), replace=False))
-    cols[0], cols[-1] = 0, C - 1
-    r = bf16_check(inp, f"workload {cfg} in bf16 ({len(cols)} columns)", cols=cols)
-    say(f"workload {cfg} bf16: {r}")
+    say(f"workload {cfg} in bf16: forward + backward")
+    h = lr.linrec_forward(inp["lam"], inp["x"], inp["h0"])
+    gx, gl, gh0 = lr.linrec_backward(inp["lam"], h, inp["h0"], inp["grad_h"])
+    torch.cuda.synchronize()
+    lr.linrec_check()
+    assert all(t.dtype == torch.bfloat16 for t in (h, gx, gl, gh0))
+    f = lambda t: host_f32(t, T, C)
+    lam, hh, h0 = f(inp["lam"]), f(h), host_f32(inp["h0"])
+    r = {"h": oracle.forward_compare(lam, f(inp["x"]), h0, hh, threads=ORACLE_THREADS, rel=HALF_ULP)}
+    r.update(oracle.backward_compare(lam, hh, h0, f(inp["grad_h"]), f(gx), f(gl), host_f32(gh0), threads=ORACLE_THREADS,
+                                     rel=HALF_ULP))
+    say(f"workload {cfg} bf16: {check_norms(r, f'workload {cfg} bf16')}")

@@ -15,7 +15,7 @@ import torch
 import linrec_workloads as wl
 import oracle
 import paper_1709_04057_amd as lr
-from parity import FWD_TOL, GRAD_TOL, ORACLE_THREADS, all_tiles, options, say
+from parity import FWD_TOL, GRAD_TOL, ORACLE_THREADS, all_tiles, check_norms, host_f32, options, say, reruns_agree
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -151,8 +151,8 @@ def test_optional_outputs_no_initial_state_and_empty_problems():
     full = lr.linrec_lstm_cell_backward(*pre, c, None, inp["grad_h"], want_grad_c0=False)
     part = lr.linrec_lstm_cell_backward(*pre, c, None, inp["grad_h"], want=(True, False, False, True), want_grad_c0=False)
     torch.cuda.synchronize()
-    assert none is None and torch.equal(c_only, c)
-    assert part[1] is None and part[2] is None and torch.equal(part[0], full[0]) and torch.equal(part[3], full[3])
+    assert none is None and reruns_agree(c_only, c)
+    assert part[1] is None and part[2] is None and reruns_agree(part[0], full[0]) and reruns_agree(part[3], full[3])
     g = to_bf16(wl.make_gated(1800, 2, 48, seed=6, device=DEV, with_h0=False))
     gated16_check(g, lr.TAU_TANH, "no h0")
     # T == 0: nothing is launched but the state gradient, which is zero
@@ -174,23 +174,37 @@ def test_gates_close_to_one_keep_their_decay_rate():
 
 
 @pytest.mark.parametrize("name", ["g2", "g4", "l2", "l4"])
-def test_full_size_workloads_on_sampled_columns(name):
+def test_full_size_workloads_every_element(name):
+    # The benchmarked shapes on bf16 storage, every element of every output: the oracle runs on the exactly
+    # widened inputs in blocks of whole columns, and each element is allowed half a bf16 unit in the last
+    # place of its reference value on top of the fp32 path's tolerance.
     gated = name[0] == "g"
     spec = (wl.GATED if gated else wl.LSTM)[name]
     T, B, n = spec["T"], spec["B"], spec["n"]
     C = B * n
-    rng = np.random.default_rng(7)
-    k = max(8, min(C, (1 << 22) // T))
-    cols = np.sort(rng.choice(C, size=min(k, C), replace=False))
-    cols[0], cols[-1] = 0, C - 1
+    f = lambda t: host_f32(t, T, C)
     if gated:
         inp = to_bf16(wl.make_gated(T, B, n, seed=sum(map(ord, name)), device=DEV, gate_mean=spec["gate_mean"],
                                     gate_std=spec["gate_std"]))
-        r = gated16_check(inp, lr.TAU_TANH, f"workload {name} bf16 ({len(cols)} columns)", cols=cols)
+        say(f"workload {name} bf16: gilr forward + backward T={T} B={B} n={n}")
+        h = lr.linrec_gilr_forward(inp["g_pre"], inp["i_pre"], inp["h0"], tau=lr.TAU_TANH)
+        gg, gi, gh0 = lr.linrec_gilr_backward(inp["g_pre"], inp["i_pre"], h, inp["h0"], inp["grad_h"], tau=lr.TAU_TANH)
+        torch.cuda.synchronize()
+        lr.linrec_check()
+        assert all(t.dtype == torch.bfloat16 for t in (h, gg, gi, gh0))
+        r = oracle.gilr_compare(f(inp["g_pre"]), f(inp["i_pre"]), host_f32(inp["h0"]), f(inp["grad_h"]), f(h), f(gg), f(gi),
+                                host_f32(gh0), lr.TAU_TANH, threads=ORACLE_THREADS, rel=HALF_ULP)
     else:
         inp = to_bf16(wl.make_lstm(T, B, n, seed=sum(map(ord, name)), device=DEV, forget_mean=spec["forget_mean"]))
-        r = cell16_check(inp, f"workload {name} bf16 ({len(cols)} columns)", cols=cols)
-    say(f"workload {name} bf16: {r}")
+        say(f"workload {name} bf16: lstm cell forward + backward T={T} B={B} n={n}")
+        c, h = lr.linrec_lstm_cell_forward(*(inp[k] for k in PRE), inp["c0"])
+        grads = lr.linrec_lstm_cell_backward(*(inp[k] for k in PRE), c, inp["c0"], inp["grad_h"])
+        torch.cuda.synchronize()
+        lr.linrec_check()
+        assert all(t.dtype == torch.bfloat16 for t in (c, h) + tuple(grads))
+        r = oracle.lstm_compare(*(f(inp[k]) for k in PRE), host_f32(inp["c0"]), f(inp["grad_h"]), f(c), f(h),
+                                [f(g) for g in grads[:4]], host_f32(grads[4]), threads=ORACLE_THREADS, rel=HALF_ULP)
+    say(f"workload {name} bf16: {check_norms(r, 'workload ' + name + ' bf16')}")
 
 
 def test_autograd_wrappers_take_bf16():
@@ -200,4 +214,4 @@ def test_autograd_wrappers_take_bf16():
     (h.float() * inp["grad_h"].float()).sum().backward()
     want = lr.linrec_gilr_backward(g_pre.detach(), i_pre.detach(), h.detach(), inp["h0"], inp["grad_h"])
     torch.cuda.synchronize()
-    assert h.dtype == torch.bfloat16 and torch.equal(g_pre.grad, want[0]) and torch.equal(i_pre.grad, want[1])
+    assert h.dtype == torch.bfloat16 and reruns_agree(g_pre.grad, want[0]) and reruns_agree(i_pre.grad, want[1])

@@ -300,3 +300,38 @@ def test_gilr_pins_catch_planted_mistakes(name):
         assert not failed, f"the unmutated replica fails {failed}: the pins are wrong"
     else:
         assert failed, f"no pin notices the planted mistake {name}"
+
+
+# --------------------------------------------------------------------------- the column-block comparison
+def test_gilr_compare_agrees_with_one_shot(oracle):
+    """gilr_compare (whole-column blocks, folded error norms) reports exactly what the one-shot functions
+    give, finds a planted error in any block, and fails on a NaN instead of swallowing it."""
+    rng = _rng(77)
+    T, C = 300, 11
+    gp, ip = _f32(rng.normal(1.0, 1.5, (T, C))), _f32(rng.normal(size=(T, C)))
+    h0, e = _f32(rng.normal(size=C)), _f32(rng.normal(size=(T, C)))
+    for tau in (IDENT, TANH):
+        h = oracle.gilr_forward(gp, ip, h0, tau)
+        hc = _f32(h)
+        gg, gi, gh0 = oracle.gilr_backward(gp, ip, hc, h0, e, tau)
+        ggc, gic, gh0c = _f32(gg), _f32(gi), _f32(gh0)
+        hc2 = hc.copy()
+        # (the backward reference is evaluated on the candidate h, so plant the forward error in a copy)
+        r = oracle.gilr_compare(gp, ip, h0, e, hc, ggc, gic, gh0c, tau, threads=2, block_elems=3 * T)
+        assert r["h"]["max_abs_err"] == np.abs(hc.astype(np.float64) - h).max()
+        assert r["h"]["max_abs_ref"] == np.abs(h).max()
+        assert r["grad_g_pre"]["max_abs_err"] == np.abs(ggc.astype(np.float64) - gg).max()
+        assert r["grad_i_pre"]["max_abs_err"] == np.abs(gic.astype(np.float64) - gi).max()
+        assert r["grad_h0"]["max_abs_err"] == np.abs(gh0c.astype(np.float64) - gh0).max()
+        assert r["grad_g_pre"]["max_abs_ref"] == np.abs(gg).max()
+        for col in (0, 5, C - 1):                       # a planted error in the first, a middle and the last block
+            bad = ggc.copy()
+            bad[17, col] += np.float32(0.5)
+            rb = oracle.gilr_compare(gp, ip, h0, e, hc, bad, gic, gh0c, tau, block_elems=3 * T)
+            assert abs(rb["grad_g_pre"]["max_abs_err"] - abs(float(bad[17, col]) - gg[17, col])) < 1e-12
+        hc2[T - 1, C - 1] = np.nan
+        assert oracle.gilr_compare(gp, ip, h0, None, hc2, None, None, None, tau)["h"]["max_abs_err"] == float("inf")
+    # no initial state, forward only
+    h = oracle.gilr_forward(gp, ip, None, TANH)
+    r = oracle.gilr_compare(gp, ip, None, None, _f32(h), None, None, None, TANH, block_elems=T)
+    assert set(r) == {"h"} and r["h"]["max_abs_err"] < 1e-6

@@ -269,3 +269,34 @@ def test_lstm_pins_catch_planted_mistakes(name):
         assert not failed, f"the unmutated replica fails {failed}: the pins are wrong"
     else:
         assert failed, f"no pin notices the planted mistake {name}"
+
+
+# --------------------------------------------------------------------------- the column-block comparison
+def test_lstm_compare_agrees_with_one_shot(oracle):
+    """lstm_compare reports exactly what the one-shot functions give, block by block."""
+    rng = np.random.default_rng(78)
+    f32 = lambda a: np.ascontiguousarray(np.asarray(a, dtype=np.float32))
+    T, C = 250, 9
+    pre = [f32(rng.normal(m, 1.0, (T, C))) for m in (1.0, 0.0, 0.0, 0.0)]
+    c0, e = f32(rng.normal(size=C)), f32(rng.normal(size=(T, C)))
+    c, h = oracle.lstm_forward(*pre, c0)
+    cc, hc = f32(c), f32(h)
+    grads = oracle.lstm_backward(*pre, cc, c0, e)
+    gc = [f32(g) for g in grads]
+    r = oracle.lstm_compare(*pre, c0, e, cc, hc, gc[:4], gc[4], threads=2, block_elems=2 * T)
+    assert r["c"]["max_abs_err"] == np.abs(cc.astype(np.float64) - c).max()
+    assert r["h"]["max_abs_err"] == np.abs(hc.astype(np.float64) - h).max()
+    for k, name in enumerate(("grad_f_pre", "grad_i_pre", "grad_z_pre", "grad_o_pre", "grad_c0")):
+        assert r[name]["max_abs_err"] == np.abs(gc[k].astype(np.float64) - grads[k]).max(), name
+        assert r[name]["max_abs_ref"] == np.abs(grads[k]).max(), name
+    for col in (0, 4, C - 1):
+        bad = gc[2].copy()
+        bad[3, col] -= np.float32(0.25)
+        rb = oracle.lstm_compare(*pre, c0, e, cc, hc, [gc[0], gc[1], bad, gc[3]], gc[4], block_elems=2 * T)
+        assert abs(rb["grad_z_pre"]["max_abs_err"] - abs(float(bad[3, col]) - grads[2][3, col])) < 1e-12
+    hb = hc.copy()
+    hb[0, 0] = np.inf
+    assert oracle.lstm_compare(*pre, c0, None, cc, hb, None, None)["h"]["max_abs_err"] == float("inf")
+    # outputs that were skipped are skipped here too
+    r = oracle.lstm_compare(*pre, None, e, f32(oracle.lstm_forward(*pre, None)[0]), None, [None, gc[1], None, None], None)
+    assert "h" not in r and "grad_f_pre" not in r and "grad_c0" not in r and "grad_i_pre" in r

@@ -476,6 +476,16 @@ def test_compare_helpers_agree_with_one_shot(oracle):
     # NaN in the candidate must be reported as a failure, not swallowed
     cand2 = _f32(h); cand2[5, 0] = np.nan
     assert oracle.forward_compare(lam, x, h0, cand2)["max_abs_err"] == float("inf")
+    # the per-element allowance: an error of exactly rel*|ref| everywhere leaves nothing; one element
+    # pushed further leaves exactly its excess
+    scaled = h * (1 + 2.0 ** -8)
+    r = oracle.forward_compare(lam, x, h0, scaled, slab_elems=64 * C, rel=2.0 ** -8)
+    assert r["max_abs_err"] <= 1e-12 * np.abs(h).max()
+    scaled[77, 3] += np.copysign(0.125, h[77, 3])
+    r = oracle.forward_compare(lam, x, h0, scaled, slab_elems=64 * C, rel=2.0 ** -8)
+    assert r["worst_index"] == (77, 3) and abs(r["max_abs_err"] - 0.125) < 1e-9
+    rb = oracle.backward_compare(lam, h32, h0, e, gx * (1 - 2.0 ** -8), gl, gh0, slab_elems=37 * C, rel=2.0 ** -8)
+    assert rb["grad_x"]["max_abs_err"] <= 1e-12 * np.abs(gx).max() and rb["grad_lambda"]["max_abs_err"] == 0.0
 
 
 def test_empty_shapes(oracle):
