@@ -62,7 +62,8 @@ enum {
     LINREC_ERR_HIP = -4,    /* a HIP allocation or launch failed; see linrec_last_hip_error */
     LINREC_ERR_OPTION = -5, /* unknown option or value out of range                         */
     LINREC_ERR_DEVICE = -6, /* a kernel reported a look-back wait that exceeded its limit   */
-    LINREC_ERR_CAPTURE = -7 /* the workspace would have to grow while the stream is capturing */
+    LINREC_ERR_CAPTURE = -7,/* the workspace would have to grow while the stream is capturing */
+    LINREC_ERR_SCRATCH = -8 /* linrec_forward_noalloc: problem too large for the fixed scratch */
 };
 
 /* Which kernel family evaluates the scan (linrec_set_option(LINREC_OPT_VARIANT, ...)). */
@@ -140,6 +141,28 @@ int linrec_forward(const float *lambda, const float *x, const float *h0, float *
 int linrec_backward(const float *lambda, const float *h, const float *h0, const float *grad_h,
                     float *grad_x, float *grad_lambda, float *grad_h0,
                     int64_t T, int64_t B, int64_t n, void *stream);
+
+/*
+ * linrec_forward for callers that cannot allocate device memory -- code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, layout, NULL and aliasing
+ * rules and results (to the tolerances above) as linrec_forward, but the single pass keeps its
+ * look-back words in a fixed array of LINREC_NOALLOC_SCRATCH_BYTES inside the library's device image
+ * instead of the cached workspace: the call makes no hipMalloc / hipFree and touches no allocator.
+ * Every GPU the library runs on holds its own copy of the array until the process ends.
+ *   - A problem whose look-back words do not fit -- 512 + 24 * K * B*n bytes, K = tiles along T of
+ *     the plan in force (linrec_plan; ceil(T / 1024) for long sequences) -- returns
+ *     LINREC_ERR_SCRATCH and enqueues nothing.  All five benchmark workloads fit.
+ *   - The three-phase variant is not available here (an explicit request runs the single pass).
+ *   - All calls on one GPU share that GPU's array, on whatever stream: calls that may overlap in time
+ *     on one GPU race on it and give wrong results.  Serialise them (one stream, or events).
+ *   - The array keeps the previous call's words; they are told from the running call's by their epoch,
+ *     as in the cached workspace, so nothing is cleared between calls.
+ */
+#define LINREC_NOALLOC_SCRATCH_BYTES (32u << 20)
+int linrec_forward_noalloc(const float *lambda, const float *x, const float *h0, float *h_out,
+                           int64_t T, int64_t B, int64_t n, void *stream);
+/* LINREC_NOALLOC_SCRATCH_BYTES as the library was built with. */
+int64_t linrec_noalloc_scratch_bytes(void);
 
 /*
  * The same two passes on bf16 STORAGE: every tensor (and h0, grad_h0) holds bfloat16, i.e. the upper

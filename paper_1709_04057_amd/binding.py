@@ -15,7 +15,7 @@ TAU_IDENTITY, TAU_TANH = 0, 1
 OPT_VARIANT, OPT_TILE, OPT_CHUNK_TILES, OPT_SPIN_LIMIT, OPT_HPREV_LATE, OPT_TAPER, OPT_PERSISTENT, OPT_GRID_CAP = 1, 2, 3, 4, 5, 6, 7, 8
 OPT_STAGGER = 9
 OPT_TEST_FILL, OPT_TEST_EPOCH = 10, 11
-ERR_CAPTURE = -7
+ERR_CAPTURE, ERR_SCRATCH = -7, -8
 
 
 class LinrecError(RuntimeError):
@@ -46,6 +46,10 @@ def lib():
         L.linrec_forward.restype = ci
         L.linrec_backward.argtypes = [p, p, p, p, p, p, p, i64, i64, i64, p]
         L.linrec_backward.restype = ci
+        L.linrec_forward_noalloc.argtypes = [p, p, p, p, i64, i64, i64, p]
+        L.linrec_forward_noalloc.restype = ci
+        L.linrec_noalloc_scratch_bytes.argtypes = []
+        L.linrec_noalloc_scratch_bytes.restype = i64
         L.linrec_pin_plan.argtypes = [ci, i64, i64, i64, ci, ci, ci, ci, ci]
         L.linrec_pin_plan.restype = ci
         L.linrec_reserve_workspace.argtypes = [ci, i64, i64, i64, ci, p]
@@ -183,6 +187,20 @@ def linrec_forward(lam, x, h0=None, h_out=None, stream=None):
     fn = lib().linrec_forward_bf16 if dt == torch.bfloat16 else lib().linrec_forward
     _check(fn(_ptr(lam), _ptr(x), _ptr(h0), _ptr(h_out), T, B, n, _stream_ptr(stream)))
     return h_out
+
+
+def linrec_forward_noalloc(lam, x, h0, h_out, stream=None):
+    """linrec_forward through the entry point that allocates nothing; ``h_out`` must be given (float32 only)."""
+    T, B, n = _tbn(lam, "lambda")
+    if tuple(_tbn(x, "x")) != (T, B, n) or tuple(_tbn(h_out, "h_out")) != (T, B, n):
+        raise ValueError("x and h_out must have lambda's shape")
+    _bn(h0, "h0", B, n)
+    _check(lib().linrec_forward_noalloc(_ptr(lam), _ptr(x), _ptr(h0), _ptr(h_out), T, B, n, _stream_ptr(stream)))
+    return h_out
+
+
+def linrec_noalloc_scratch_bytes() -> int:
+    return int(lib().linrec_noalloc_scratch_bytes())
 
 
 def linrec_backward(lam, h, h0, grad_h, grad_x=None, grad_lambda=None, grad_h0=None, stream=None,

@@ -155,6 +155,34 @@ int ensure(Workspace &ws, void **buf, size_t *have, size_t need, bool lookback, 
     return LINREC_OK;
 }
 
+// Look-back workspace for callers that cannot allocate (linrec_forward_noalloc): one array in the
+// library's device image, so every GPU the library runs on holds its own copy, zero-initialised when
+// the image is loaded -- which is a valid start, as for an allocated block.  Host code never uses the
+// array's name for anything but the address query below; kernels get the queried address as an argument.
+constexpr size_t kScratchBytes = LINREC_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned long long g_noalloc_scratch[kScratchBytes / sizeof(unsigned long long)];
+constexpr int kMaxDevices = 64;
+struct ScratchOfDevice {
+    void *ptr = nullptr;  // this device's address of g_noalloc_scratch
+    unsigned long long calls_since_clear = 0;
+};
+ScratchOfDevice g_scratch[kMaxDevices];  // guarded by g_mu
+
+// The address of the current device's scratch array (queried once per device, with that device current).
+int scratch_of_current_device(int dev, ScratchOfDevice **out)
+{
+    if (dev < 0 || dev >= kMaxDevices) return hip_fail(hipErrorInvalidDevice, "linrec_forward_noalloc: device index");
+    ScratchOfDevice &sd = g_scratch[dev];
+    if (!sd.ptr) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch));
+        if (e != hipSuccess || !p) return hip_fail(e != hipSuccess ? e : hipErrorInvalidSymbol, "hipGetSymbolAddress(scratch)");
+        sd.ptr = p;
+    }
+    *out = &sd;
+    return LINREC_OK;
+}
+
 // Workgroups the device holds at once, for sizing the tail of short tiles: compute units x 3.
 int resident_workgroups(int dev)
 {
@@ -654,12 +682,13 @@ int prepare_lookback(Args &A, void *block, size_t bytes, unsigned long long *cal
 
 // gated: the form of Section 3.1 (activations applied in the kernel); it exists as the single-pass and
 // walk kernels of the tile shapes with a multiple of 8 (or fewer than 8) rows per thread, and as the
-// serial kernel.
-int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf16 = false)
+// serial kernel.  noalloc: the look-back words live in the device-resident scratch array instead of a
+// cached allocation, and nothing is allocated (LINREC_ERR_SCRATCH when they do not fit).
+int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf16 = false, bool noalloc = false)
 {
     const bool gated = form != FORM_PLAIN;
     Plan plan = make_plan(A.T, A.C, vec, bwd, form, bf16);
-    if ((gated || bf16) && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
+    if ((gated || bf16 || noalloc) && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
     hipError_t e;
     if (plan.variant == LINREC_VARIANT_SERIAL) {
         if ((e = launch_serial(A, bwd, form, bf16, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
@@ -717,9 +746,17 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
     const size_t need = lookback_bytes(A.K, A.C);
     {
         std::lock_guard<std::mutex> lock(g_mu);
-        Workspace &ws = g_ws[std::make_pair(dev, s)];
-        int rc = ensure(ws, &ws.lb, &ws.lb_bytes, need, true, s);
-        if (rc == LINREC_OK) rc = prepare_lookback(A, ws.lb, ws.lb_bytes, &ws.calls_since_clear, s);
+        int rc;
+        if (noalloc) {
+            if (need > kScratchBytes) return LINREC_ERR_SCRATCH;
+            ScratchOfDevice *sd = nullptr;
+            if ((rc = scratch_of_current_device(dev, &sd)) != LINREC_OK) return rc;
+            rc = prepare_lookback(A, sd->ptr, kScratchBytes, &sd->calls_since_clear, s);
+        } else {
+            Workspace &ws = g_ws[std::make_pair(dev, s)];
+            if ((rc = ensure(ws, &ws.lb, &ws.lb_bytes, need, true, s)) != LINREC_OK) return rc;
+            rc = prepare_lookback(A, ws.lb, ws.lb_bytes, &ws.calls_since_clear, s);
+        }
         if (rc != LINREC_OK) return rc;
     }
     A.spin_limit = (uint32_t)opts().spin_limit;
@@ -755,6 +792,26 @@ extern "C" int linrec_forward(const float *lambda, const float *x, const float *
     A.C = C;
     return run(A, false, max_vec(C, {lambda, x, h0, h_out}), (hipStream_t)stream);
 }
+
+extern "C" int linrec_forward_noalloc(const float *lambda, const float *x, const float *h0, float *h_out, int64_t T,
+                                      int64_t B, int64_t n, void *stream)
+{
+    const int rc = linrec_validate_forward(lambda, x, h0, h_out, T, B, n);
+    if (rc != LINREC_OK) return rc;
+    const int64_t C = B * n;
+    if (T == 0 || C == 0) return LINREC_OK;
+    Args A;
+    memset(&A, 0, sizeof A);
+    A.a = lambda;
+    A.b = x;
+    A.h0 = h0;
+    A.out0 = h_out;
+    A.T = T;
+    A.C = C;
+    return run(A, false, max_vec(C, {lambda, x, h0, h_out}), (hipStream_t)stream, FORM_PLAIN, false, /*noalloc=*/true);
+}
+
+extern "C" int64_t linrec_noalloc_scratch_bytes(void) { return (int64_t)kScratchBytes; }
 
 extern "C" int linrec_backward(const float *lambda, const float *h, const float *h0, const float *grad_h, float *grad_x,
                                float *grad_lambda, float *grad_h0, int64_t T, int64_t B, int64_t n, void *stream)
@@ -1473,8 +1530,8 @@ extern "C" int linrec_check(void *stream)
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     int dev = 0;
     if ((e = hipGetDevice(&dev)) != hipSuccess) return hip_fail(e, "hipGetDevice");
-    // every block that may hold the header of a launch on this stream: the live look-back block and the
-    // retired ones
+    // every block that may hold the header of a launch on this stream: the live look-back block, the
+    // retired ones, and this device's no-allocation scratch
     std::vector<void *> headers;
     {
         std::lock_guard<std::mutex> lock(g_mu);
@@ -1483,6 +1540,7 @@ extern "C" int linrec_check(void *stream)
             if (it->second.lb) headers.push_back(it->second.lb);
             headers.insert(headers.end(), it->second.retired_lb.begin(), it->second.retired_lb.end());
         }
+        if (dev >= 0 && dev < kMaxDevices && g_scratch[dev].ptr) headers.push_back(g_scratch[dev].ptr);
     }
     int rc = LINREC_OK;
     for (void *h : headers) {

@@ -243,6 +243,7 @@ extern "C" const char *linrec_status_string(int status)
     case LINREC_ERR_OPTION: return "unknown option or value out of range";
     case LINREC_ERR_DEVICE: return "a look-back wait exceeded its spin limit";
     case LINREC_ERR_CAPTURE: return "the workspace would have to grow while the stream is capturing";
+    case LINREC_ERR_SCRATCH: return "problem too large for the fixed scratch of linrec_forward_noalloc";
     default: return "unknown status";
     }
 }

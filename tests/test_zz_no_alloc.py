@@ -1,0 +1,69 @@
+"""linrec_forward_noalloc: the forward pass for callers that cannot allocate (its look-back words live in
+a fixed array inside the library's device image).  Checked against linrec_forward's output and against
+the oracle, to the forward tolerance, on consecutive calls that share the array."""
+import pytest
+import torch
+
+import linrec_workloads as wl
+import paper_1709_04057_amd as lr
+from parity import FWD_TOL, check_forward, options, say
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _both(inp, label):
+    say(f"{label}: T={inp['T']} B={inp['B']} n={inp['n']}")
+    want = lr.linrec_forward(inp["lam"], inp["x"], inp["h0"])
+    got = torch.full_like(inp["x"], float("nan"))
+    lr.linrec_forward_noalloc(inp["lam"], inp["x"], inp["h0"], got)
+    torch.cuda.synchronize()
+    lr.linrec_check()
+    scale = 1.0 + float(want.abs().max())
+    err = float((got - want).abs().max())
+    assert err <= FWD_TOL * scale, f"{label}: differs from linrec_forward by {err:.3e} > {FWD_TOL * scale:.3e}"
+    check_forward(inp, got, label)
+
+
+def test_two_calls_in_a_row_the_second_smaller():
+    with options(variant=lr.VARIANT_LOOKBACK):
+        _both(wl.make_inputs(5, T=70000, B=2, n=192, device=DEV), "no-alloc, first call")
+        _both(wl.make_inputs(2, T=9000, B=1, n=100, device=DEV), "no-alloc, second (smaller) call")
+        _both(wl.make_inputs(3, T=131072, B=1, n=128, device=DEV), "no-alloc, third call, long and narrow")
+
+
+def test_automatic_plan_side_stream_and_no_initial_state():
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        for T, B, n in ((4096, 2, 64), (300, 16, 1024), (1, 1, 1), (65536, 4, 256)):
+            inp = wl.make_inputs(1, T=T, B=B, n=n, device=DEV)      # h0 is None
+            _both(inp, f"no-alloc auto plan {T}x{B}x{n}")
+    s.synchronize()
+
+
+def test_too_large_is_refused_and_nothing_is_enqueued():
+    T, B, n = 65536, 4, 256          # on 32-row tiles: 2048 tiles x 1024 columns x 24 bytes, beyond the array
+    assert 24 * (T // 32) * B * n > lr.linrec_noalloc_scratch_bytes()
+    lam = torch.rand((T, B, n), device=DEV)
+    out = torch.zeros_like(lam)
+    with options(variant=lr.VARIANT_LOOKBACK, tile=1):
+        with pytest.raises(lr.LinrecError) as err:
+            lr.linrec_forward_noalloc(lam, lam, None, out)
+        assert err.value.status == lr.ERR_SCRATCH
+        torch.cuda.synchronize()
+        assert float(out.abs().max()) == 0.0
+    # with the plan the library picks itself the same problem fits
+    lr.linrec_forward_noalloc(lam, lam, None, out)
+    torch.cuda.synchronize()
+    assert float(out.abs().max()) > 0.0
+    # the ordinary argument checks come first
+    with pytest.raises(lr.LinrecError) as err:
+        lr.linrec_forward_noalloc(lam, lam, None, lam)
+    assert err.value.status == -3
+
+
+def test_empty_problem():
+    z = torch.empty((0, 2, 8), device=DEV)
+    lr.linrec_forward_noalloc(z, z, None, z.clone())
+    torch.cuda.synchronize()
