@@ -93,11 +93,14 @@ enum {
                                   neutral on most shapes); linrec_tune tries 2 on the plan it
                                   found and remembers it where that is faster; a non-zero
                                   value set here overrides what tuning remembered            */
-    LINREC_OPT_PERSISTENT = 7, /* look-back: launch as many workgroups as the GPU holds and let
-                                  each loop over tiles (1), one workgroup per tile (0), or
-                                  let the library decide per pass (-1, default)              */
-    LINREC_OPT_GRID_CAP = 8,   /* look-back, persistent: at most this many workgroups per
-                                  compute unit; 0 (default) = as many as fit                 */
+    LINREC_OPT_PERSISTENT = 7, /* look-back: launch as many workgroups as LINREC_OPT_GRID_CAP
+                                  allows and let each loop over tiles (1; also what -1, the
+                                  default, means), or one workgroup per tile (0)               */
+    LINREC_OPT_GRID_CAP = 8,   /* look-back, persistent: workgroups per compute unit.  0
+                                  (default): eight wavefronts per unit, i.e. one workgroup of
+                                  512 threads or two of 256 -- more resident tiles than the
+                                  memory system needs only lengthen the start and the end of
+                                  a launch; n > 0: at most n; -1: as many as fit               */
     LINREC_OPT_STAGGER = 9,    /* look-back: every other workgroup of the first round starts
                                   this many microseconds (roughly; 0..16) late, so that the
                                   workgroups do not load, scan and store in lock-step;

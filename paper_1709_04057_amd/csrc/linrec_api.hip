@@ -21,13 +21,19 @@ namespace linrec {
 LINREC_TILES(X)
 #undef X
 
-static const TileDesc kTiles[NUM_TILES] = {
-#define X(ID, VEC, R, WC, WT) {VEC, R, WC, WT},
-    LINREC_TILES(X)
+struct TileTable {  // indexed by id; unassigned ids hold zeros
+    TileDesc t[MAX_TILE_ID + 1];
+    constexpr TileTable() : t{}
+    {
+#define X(ID, VEC, R, WC, WT) t[ID] = TileDesc{VEC, R, WC, WT};
+        LINREC_TILES(X)
 #undef X
+    }
 };
+static constexpr TileTable kTable{};
 
-const TileDesc &tile_desc(int id) { return kTiles[id - 1]; }
+bool tile_exists(int id) { return id >= 1 && id <= MAX_TILE_ID && kTable.t[id].vec != 0; }
+const TileDesc &tile_desc(int id) { return kTable.t[id]; }
 
 hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A, hipStream_t s)
 {
@@ -54,7 +60,7 @@ struct Options {
     int64_t taper = 0;
     int64_t grid_cap = 0;
     int64_t stagger = 3;
-    int64_t persistent = -1;  // -1 automatic: forward persistent, backward one workgroup per tile (measured)
+    int64_t persistent = -1;  // -1 automatic (persistent)
     // test aids (see linrec.h): what a fresh look-back workspace is filled with, and a stored epoch to
     // plant into the workspace of the thread's next single-pass call (-1: none)
     int64_t test_fill = 0;
@@ -69,7 +75,7 @@ struct Options {
         }
         if (const char *v = getenv("LINREC_TILE")) {
             const long t = strtol(v, nullptr, 10);
-            if (t >= 0 && t <= NUM_TILES) tile = t;
+            if (t == 0 || tile_exists((int)t)) tile = t;
         }
     }
 };
@@ -183,8 +189,8 @@ int scratch_of_current_device(int dev, ScratchOfDevice **out)
     return LINREC_OK;
 }
 
-// Workgroups the device holds at once, for sizing the tail of short tiles: compute units x 3.
-int resident_workgroups(int dev)
+// Compute units of a device (256 on an MI355X; also what is assumed when the device cannot be asked).
+int compute_units(int dev)
 {
     static std::mutex mu;
     static std::map<int, int> cache;
@@ -193,7 +199,7 @@ int resident_workgroups(int dev)
     if (it != cache.end()) return it->second;
     int cus = 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    return cache[dev] = 3 * cus;
+    return cache[dev] = cus;
 }
 
 bool aligned16(const void *p) { return p == nullptr || ((uintptr_t)p & 15u) == 0; }
@@ -216,46 +222,80 @@ int max_vec_bf16(int64_t C, std::initializer_list<const void *> ptrs)
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Tile shape for a [T, C] problem when the caller did not fix one.  The rules condense a sweep of
-// every shape over T = 64 .. 262144 x C = 32 .. 32768 on an MI355X (the choice is within 3 % of the
-// best shape on average, 5 % backward, and within 20-25 % at worst; linrec_tune() closes the rest
-// for a given shape and box):
-//   * one column per thread with many rows per thread, and tiles as tall as T allows (the taller the
-//     tile, the fewer summaries the look-back moves per element) once the sequence is long;
-//   * 256-byte row segments (64 threads side by side) when there are many columns;
-//   * the shapes with 16-byte (8-byte) accesses for very wide problems, where alignment allows;
-//   * the backward pass carries a third operand per row and prefers 48- or 32-row threads.
+// Tiles a shape cuts a [T, C] problem into.
+int64_t tile_count(int id, int64_t T, int64_t C)
+{
+    const TileDesc &d = kTable.t[id];
+    return ceil_div(T, d.rows()) * ceil_div(C, d.cols());
+}
+
+// Of the shapes in `family` (tallest first), the one that covers the problem in ONE round of workgroups --
+// at most one tile per compute unit, and at least 60 % of the units busy -- with the most tiles; 0 if none
+// does.  A problem of that size is over in a single tile life whatever the shape, so the shape that puts
+// the most units to work wins; every mid-sized problem in the sweeps behind these rules ran best that way.
+int one_round_shape(std::initializer_list<int> family, int64_t T, int64_t C, int64_t units)
+{
+    int best = 0;
+    int64_t best_n = 0;
+    for (const int id : family) {
+        const int64_t n = tile_count(id, T, C);
+        if (n <= units && 10 * n >= 6 * units && n > best_n) {
+            best = id;
+            best_n = n;
+        }
+    }
+    return best;
+}
+
+// Tile shape for a [T, C] problem of the plain fp32 recurrence when the caller did not fix one.  All the
+// shapes it takes keep one column per thread and eight wavefronts per compute unit (see the launch code),
+// and differ in three ways only:
+//   * width: 64 threads side by side (256-byte row segments) once there are 512 columns, else 32;
+//   * rows per thread R, i.e. bytes in flight per compute unit: the forward pass (two operands per row in
+//     registers, 12 B/element) wants R = 64, or 48 when rows are long (C >= 8192); the backward pass
+//     (three operands, 20 B/element) R = 40, or 32 when rows are long (C >= 4096).  About 300-400 KB per unit either way: enough to keep the
+//     memory system busy, and no more, because a tile's life is bytes in flight over bandwidth and a launch
+//     spends about one tile life below full bandwidth while it starts and ends;
+//   * threads along time: 8 or 16 per 512-thread workgroup (one per unit); very wide problems
+//     (C >= 16384) run better on 256-thread workgroups, two per unit, of short tiles.
+// Narrow problems (few column groups) take the tallest tiles: the chain of tiles along T is what they
+// wait for.  Problems that fit one round of workgroups take the shape that makes the fullest round.
+// Condensed from a sweep of 17 shapes over T = 256 .. 1048576 x C = 128 .. 65536 on an MI355X: within
+// 1.1 % (forward) and 1.7 % (backward) of the best shape on average; linrec_tune() closes the rest for a
+// given shape and box.
 int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
 {
     (void)variant;
     if (C <= 16) return T >= 4096 ? 23 : 2;
-    const int short_wide = vec >= 4 ? 10 : 21;  // (T < 192: a few rows per thread)
+    if (T < 192) return vec >= 4 ? 10 : 21;  // a few rows per thread
+    int dev = 0, units = 256;
+    if (hipGetDevice(&dev) == hipSuccess) units = compute_units(dev);
+    const bool narrow = C < 512;
     if (!bwd) {
+        if (C >= 32768) return 21;
+        if (narrow) {
+            if (const int t = one_round_shape({22, 35, 34}, T, C, units)) return t;
+            return T >= 32768 ? 22 : T >= 6144 ? 35 : T >= 1536 ? 19 : T >= 512 ? 18 : C >= 48 ? 1 : 2;
+        }
         if (C >= 8192) {
-            if (T >= 1536) return vec >= 4 ? 11 : vec >= 2 ? 14 : 20;
-            return T >= 192 ? 20 : short_wide;
+            if (const int t = one_round_shape({43, 42, 38, 41}, T, C, units)) return t;
+            return T >= 512 ? 43 : 21;
         }
-        if (T >= 65536) return 22;
-        if (T >= 32768) return C <= 128 ? 17 : 22;
-        if (C >= 1024) return T >= 192 ? 20 : 1;
-        if (T >= 16384 && C >= 512) return 22;
-        if (T >= 8192) return 17;
-    } else {
-        if (C >= 8192) {
-            if (T >= 2048) return 21;
-            return T >= 192 ? (vec >= 4 ? 8 : 20) : short_wide;
-        }
-        if (C >= 1024) {
-            if (T >= 8192) return C >= 4096 ? 18 : 19;
-            if (T < 192) return 1;
-            return T * C <= ((int64_t)1 << 21) ? 21 : 20;
-        }
-        if (T >= 131072) return C <= 32 ? 22 : 19;
-        if (T >= 8192) return C >= 256 ? 20 : T >= 65536 ? 17 : 18;
+        if (const int t = one_round_shape({44, 43, 42, 38, 41}, T, C, units)) return t;
+        for (const int id : {44, 43, 42, 38})
+            if (tile_count(id, T, C) >= 3 * (int64_t)units) return id;
+        return T >= 512 ? 38 : 21;
     }
-    if (T >= 1536) return 19;
-    if (T >= 512) return 18;
-    return C >= 48 ? 1 : 2;
+    if (C >= 16384) return C >= 32768 ? 21 : 45;
+    if (narrow) {
+        if (const int t = one_round_shape({22, 35, 34}, T, C, units)) return t;
+        if (tile_count(35, T, C) >= 4 * (int64_t)units) return 35;
+        return T >= 32768 ? 22 : T >= 6144 ? 34 : T >= 1536 ? 19 : T >= 512 ? 18 : C >= 48 ? 1 : 2;
+    }
+    if (const int t = one_round_shape({43, 42, 38, 41}, T, C, units)) return t;
+    // (rows of 16 KB and more: 32 rows per thread measure 1-2 % ahead of 40)
+    if (tile_count(42, T, C) >= 2 * (int64_t)units) return C >= 4096 ? 38 : 42;
+    return T >= 512 ? 38 : 21;
 }
 
 // The same for bf16 storage (shapes with 2 or 4 columns per thread), from the same kind of sweep:
@@ -264,6 +304,10 @@ int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
 int auto_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
 {
     if (T < 192) return C >= 16384 ? (vec >= 4 ? 9 : 16) : 15;  // a few rows per thread
+    // (512 or more columns: 64 threads side by side, 512-thread workgroups of 64 or 48 rows per thread)
+    if (!bwd && C >= 512 && T * C >= ((int64_t)1 << 22)) return 47;
+    if (bwd && C >= 512 && T >= 2048 && T * C >= ((int64_t)1 << 23)) return 48;
+    if (bwd && C <= 128 && T >= 65536) return 51;
     if (!bwd) {
         const int small = T >= 1024 ? 16 : 15;
         if (C >= 32768 || (C >= 16384 && T >= 4096)) return 28;
@@ -313,6 +357,10 @@ int auto_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
         if (C <= 512 && E >= ((int64_t)1 << 26)) return 18;  // (long and narrow)
         return T < 2048 ? (C >= 1024 ? 21 : plain) : vec >= 2 ? 15 : 18;
     }
+    // (the cell on long sequences: 512-thread workgroups, 16 rows per thread forward -- three operands per
+    // row -- and 32 backward; 6-12 % forward and 2-4 % backward over the 256-thread shapes)
+    if (!bwd && T >= 8192 && C < 16384) return C <= 256 ? 34 : 33;
+    if (bwd && T >= 8192 && C < 16384) return C <= 256 ? 35 : 38;
     if (!bwd) {
         if (C >= 16384) return vec >= 4 ? (C >= 32768 ? 4 : 3) : 21;
         if (C >= 2048 && T >= 1024 && T <= 4096 && vec >= 4) return 3;
@@ -507,7 +555,7 @@ int auto_walk_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
     // shape while 4-byte accesses are possible, the two-column shape of the same width and height
     if (T > 256 || (bwd && (form == FORM_LSTM || C >= 32768))) return 0;
     const int t = auto_walk_tile_form(T, C, vec, bwd, form);
-    if (t < 1 || kTiles[t - 1].vec >= 2 || vec < 2) return t < 1 ? 0 : t;
+    if (t < 1 || kTable.t[t].vec >= 2 || vec < 2) return t < 1 ? 0 : t;
     const bool cell = form == FORM_LSTM;
     switch (t) {
     case 17: case 22: case 23: return cell ? 15 : 13;   // 32 columns, 512 rows and more
@@ -603,21 +651,22 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     // take at this width; the other families their single-pass shape, below)
     if (p.variant == LINREC_VARIANT_WALK && p.tile == 0 && !gated && !bf16)
         p.tile = walk_tile(T, C, vec, bwd);
-    if (p.tile >= 1 && p.tile <= NUM_TILES && kTiles[p.tile - 1].vec > vec) p.tile = 0;
-    if (p.tile >= 1 && p.tile <= NUM_TILES && form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 0;
-    if (p.tile >= 1 && p.tile <= NUM_TILES && gated && kTiles[p.tile - 1].r % 8 != 0 && kTiles[p.tile - 1].r >= 8) p.tile = 0;
-    if (p.tile >= 1 && p.tile <= NUM_TILES && bf16 && !gated && kTiles[p.tile - 1].vec < 2) p.tile = 0;
-    if (p.tile >= 1 && p.tile <= NUM_TILES && (!bf16 || gated) && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 64) p.tile = 0;
-    if (p.tile < 1 || p.tile > NUM_TILES) {
+    if (!tile_exists(p.tile)) p.tile = 0;
+    if (p.tile && kTable.t[p.tile].vec > vec) p.tile = 0;
+    if (p.tile && form == FORM_LSTM && kTable.t[p.tile].r * kTable.t[p.tile].vec > 32) p.tile = 0;
+    if (p.tile && gated && kTable.t[p.tile].r % 8 != 0 && kTable.t[p.tile].r >= 8) p.tile = 0;
+    if (p.tile && bf16 && !gated && kTable.t[p.tile].vec < 2) p.tile = 0;
+    if (p.tile && (!bf16 || gated) && kTable.t[p.tile].r * kTable.t[p.tile].vec > 64) p.tile = 0;
+    if (!p.tile) {
         p.tile = auto_tile(T, C, vec, bwd, p.variant);
         if (gated) p.tile = auto_tile_form(T, C, vec, bwd, form);
         if (bf16) p.tile = gated ? auto_tile_form_bf16(T, C, vec, bwd, form) : auto_tile_bf16(T, C, vec, bwd);
-        if (form == FORM_LSTM && kTiles[p.tile - 1].r * kTiles[p.tile - 1].vec > 32) p.tile = 18;  // (the cell: at most 32 elements per thread and operand)
+        if (form == FORM_LSTM && kTable.t[p.tile].r * kTable.t[p.tile].vec > 32) p.tile = 18;  // (the cell: at most 32 elements per thread and operand)
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
     // (the gated forms have one-column shapes with 2-byte accesses for those)
     if (bf16 && !gated && vec < 2) p.variant = LINREC_VARIANT_SERIAL;
-    const TileDesc &d = kTiles[p.tile - 1];
+    const TileDesc &d = kTable.t[p.tile];
     // per-thread byte offsets inside a tile are 32-bit, tickets of a call are 31-bit
     const int64_t G = ceil_div(C, d.cols()), K = ceil_div(T, d.rows());
     // (the short tiles that end a look-back sequence can raise the tile count, by less than 4x)
@@ -640,7 +689,8 @@ TimeTiles time_tiles(int64_t T, int64_t G, const TileDesc &d, int taper, int dev
         const int64_t rows = d.rows();
         const int64_t full = T / rows;                                   // complete full-height tiles
         // full tiles per chain that are in flight at once; `taper` eighths of them are cut up
-        const int64_t resident = (int64_t)resident_workgroups(dev) * (d.threads() >= 512 ? 1 : 3) / 3;
+        // (a launch holds eight wavefronts per compute unit)
+        const int64_t resident = (int64_t)compute_units(dev) * std::max(1, 8 / std::max(1, d.threads() / 64));
         const int64_t round = ceil_div(resident, G);
         const int64_t taper_tiles = std::min(full / 2, (round * taper + 7) / 8);
         if (taper_tiles > 0) {
@@ -694,7 +744,7 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
         if ((e = launch_serial(A, bwd, form, bf16, s)) != hipSuccess) return hip_fail(e, "launch(serial)");
         return LINREC_OK;
     }
-    const TileDesc &d = kTiles[plan.tile - 1];
+    const TileDesc &d = kTable.t[plan.tile];
     A.G = (int32_t)ceil_div(A.C, d.cols());
     const int64_t tiles_t = ceil_div(A.T, d.rows());
 
@@ -760,8 +810,11 @@ int run(Args A, bool bwd, int vec, hipStream_t s, int form = FORM_PLAIN, bool bf
         if (rc != LINREC_OK) return rc;
     }
     A.spin_limit = (uint32_t)opts().spin_limit;
-    A.persistent = plan.persistent < 0 ? ((bwd && !gated) ? 0 : 1) : plan.persistent;
-    A.grid_cap = (int32_t)opts().grid_cap;
+    A.persistent = plan.persistent < 0 ? 1 : plan.persistent;
+    // Workgroups per compute unit: eight wavefronts for the plain fp32 recurrence (see the launch code); the
+    // other families compute activations per element or hold half the bytes per register and keep as many
+    // workgroups resident as fit, which measures 5-18 % faster for them.
+    A.grid_cap = opts().grid_cap != 0 ? (int32_t)opts().grid_cap : (form == FORM_PLAIN && !bf16) ? 0 : -1;
     A.stagger = (int32_t)opts().stagger;
     A.stagger_n = 0;
     A.trace = g_trace;
@@ -1096,7 +1149,7 @@ extern "C" int linrec_set_option(int option, int64_t value)
         opts().variant = value;
         return LINREC_OK;
     case LINREC_OPT_TILE:
-        if (value < 0 || value > NUM_TILES) return LINREC_ERR_OPTION;
+        if (value != 0 && !tile_exists((int)value)) return LINREC_ERR_OPTION;
         opts().tile = value;
         return LINREC_OK;
     case LINREC_OPT_CHUNK_TILES:
@@ -1120,7 +1173,7 @@ extern "C" int linrec_set_option(int option, int64_t value)
         opts().persistent = value;
         return LINREC_OK;
     case LINREC_OPT_GRID_CAP:
-        if (value < 0 || value > 64) return LINREC_ERR_OPTION;
+        if (value < -1 || value > 64) return LINREC_ERR_OPTION;
         opts().grid_cap = value;
         return LINREC_OK;
     case LINREC_OPT_STAGGER:
@@ -1160,7 +1213,7 @@ extern "C" int64_t linrec_get_option(int option)
 extern "C" int linrec_tile_info(int tile_id, int *threads_cols, int *threads_time, int *rows_per_thread,
                                 int *cols_per_thread)
 {
-    if (tile_id < 1 || tile_id > NUM_TILES) return LINREC_ERR_OPTION;
+    if (!tile_exists(tile_id)) return LINREC_ERR_OPTION;
     const TileDesc &d = tile_desc(tile_id);
     if (threads_cols) *threads_cols = d.wc;
     if (threads_time) *threads_time = d.wt;
@@ -1301,9 +1354,9 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         fp = ForcedPlan{};
         fp.active = true;
         fp.variant = LINREC_VARIANT_LOOKBACK;
-        static const int plain_c[] = {17, 18, 19, 20, 21, 22, 11, 12, 14, 0},
-                         gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 0},
-                         bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 0};
+        static const int plain_c[] = {44, 43, 42, 38, 41, 22, 35, 34, 21, 45, 0},
+                         gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 33, 34, 35, 38, 41, 0},
+                         bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 47, 48, 51, 0};
         static const int gated16_c[] = {21, 18, 16, 15, 13, 3, 4, 7, 8, 0}, lstm16_c[] = {15, 3, 4, 5, 18, 0};
         const int *list = form == FORM_GATED ? (bf16 ? gated16_c : gated_c) : form == FORM_LSTM ? (bf16 ? lstm16_c : lstm_c)
                                                                           : bf16 ? bf16_c : plain_c;
@@ -1315,8 +1368,8 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         for (; *list; ++list)
             if (*list != candidates[0]) candidates.push_back(*list);
         for (const int tile : candidates) {
-            if (tile < 1 || tile > NUM_TILES) continue;
-            const TileDesc &d = kTiles[tile - 1];
+            if (!tile_exists(tile)) continue;
+            const TileDesc &d = kTable.t[tile];
             if (d.vec > vec) continue;
             if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
             if (d.rows() > 2 * T && tile != 18) continue;  // far taller than the problem
@@ -1359,7 +1412,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         const TunedPlan untapered[2] = {best, second};
         for (int c = 0; c < 2 && rc == LINREC_OK && saved_taper == 0; ++c) {
             const TunedPlan &u = untapered[c];
-            if (u.tile == 0 || kTiles[u.tile - 1].r % 4 != 0 || kTiles[u.tile - 1].r < 8) continue;
+            if (u.tile == 0 || kTable.t[u.tile].r % 4 != 0 || kTable.t[u.tile].r < 8) continue;
             fp.tile = u.tile;
             fp.persistent = u.persistent;
             fp.taper = 2;
@@ -1409,7 +1462,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         fp.persistent = -1;
         for (int i = 0; walk_c[i] && rc == LINREC_OK; ++i) {
             const int tile = walk_c[i];
-            const TileDesc &d = kTiles[tile - 1];
+            const TileDesc &d = kTable.t[tile];
             if (d.vec > vec || ((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
             fp.tile = tile;
             float times[5];
@@ -1454,7 +1507,7 @@ extern "C" int linrec_pin_plan(int entry_point, int64_t T, int64_t B, int64_t n,
     if (T <= 0 || B <= 0 || n <= 0 || B > ((int64_t)1 << 40) / n || T > ((int64_t)1 << 40) / (B * n))
         return LINREC_ERR_SHAPE;
     if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_LSTM_CELL_BF16) return LINREC_ERR_OPTION;
-    if (tile_id < 0 || tile_id > NUM_TILES || persistent < -1 || persistent > 1 || taper < 0 || taper > 8)
+    if ((tile_id != 0 && !tile_exists(tile_id)) || persistent < -1 || persistent > 1 || taper < 0 || taper > 8)
         return LINREC_ERR_OPTION;
     if (tile_id != 0 && variant != LINREC_VARIANT_LOOKBACK && variant != LINREC_VARIANT_WALK) return LINREC_ERR_OPTION;
     int dev = 0;
@@ -1493,7 +1546,7 @@ extern "C" int linrec_reserve_workspace(int entry_point, int64_t T, int64_t B, i
         Plan plan = make_plan(T, C, vec, bwd, form, bf16);
         if ((form != FORM_PLAIN || bf16) && plan.variant == LINREC_VARIANT_THREEPHASE) plan.variant = LINREC_VARIANT_LOOKBACK;
         if (plan.variant != LINREC_VARIANT_LOOKBACK && plan.variant != LINREC_VARIANT_THREEPHASE) continue;
-        const TileDesc &d = kTiles[plan.tile - 1];
+        const TileDesc &d = kTable.t[plan.tile];
         const int64_t G = ceil_div(C, d.cols());
         if (plan.variant == LINREC_VARIANT_LOOKBACK) {
             need_lb = std::max(need_lb, lookback_bytes(time_tiles(T, G, d, plan.taper, dev).K, C));

@@ -66,11 +66,16 @@ struct TileDesc {
     int threads() const { return wc * wt; }
 };
 
-// Tile shapes, 1-based ids as used by LINREC_OPT_TILE: (id, columns per thread, rows per thread,
-// threads along columns, threads along time).  A shape with v columns per thread makes 4v-byte
-// accesses and needs C % v == 0 and 4v-byte aligned tensors; v = 1 works for any C and alignment.
-// (With bf16 storage the accesses are 2v bytes and v is 2 or 4.)  Shapes with more than 64 elements per
-// thread (ids 24 and up) exist for bf16 storage only, where two elements share a register.
+// Tile shapes by id, as used by LINREC_OPT_TILE: (id, columns per thread, rows per thread, threads along
+// columns, threads along time).  A shape with v columns per thread makes 4v-byte accesses and needs
+// C % v == 0 and 4v-byte aligned tensors; v = 1 works for any C and alignment.  (With bf16 storage the
+// accesses are 2v bytes and v is 2 or 4.)  Shapes with more than 64 elements per thread exist for bf16
+// storage only, where two elements share a register.  Ids are stable across versions of the library; ids of
+// shapes that no plan takes any more are left unassigned.
+//   one column per thread, 512 threads (one workgroup per compute unit): 44, 43, 42, 38, 41 (64 wide, 64 ..
+//   24 rows per thread), 22, 35, 34, 33 (32 wide); 256 threads: 20, 21, 45 (64 wide), 17, 19, 18 (32 wide),
+//   1, 2 (8 rows per thread), 23 (16 wide, for a handful of columns)
+//   two and four columns per thread (8- and 16-byte accesses; 4- and 8-byte with bf16 storage): the rest
 #define LINREC_TILES(X) \
     X(1, 1, 8, 64, 4)   \
     X(2, 1, 8, 16, 16)  \
@@ -82,8 +87,6 @@ struct TileDesc {
     X(8, 4, 16, 16, 16) \
     X(9, 4, 16, 32, 8)  \
     X(10, 4, 16, 64, 4) \
-    X(11, 4, 12, 8, 32) \
-    X(12, 4, 12, 16, 16) \
     X(13, 2, 32, 16, 16) \
     X(14, 2, 24, 16, 16) \
     X(15, 2, 16, 16, 16) \
@@ -101,10 +104,23 @@ struct TileDesc {
     X(27, 4, 32, 32, 8)  \
     X(28, 2, 64, 64, 4)  \
     X(29, 2, 48, 32, 8)  \
-    X(30, 2, 64, 32, 16)
-constexpr int NUM_TILES = 30;
+    X(30, 2, 64, 32, 16) \
+    X(33, 1, 16, 32, 16) \
+    X(34, 1, 24, 32, 16) \
+    X(35, 1, 32, 32, 16) \
+    X(38, 1, 32, 64, 8)  \
+    X(41, 1, 24, 64, 8)  \
+    X(42, 1, 40, 64, 8)  \
+    X(43, 1, 48, 64, 8)  \
+    X(44, 1, 64, 64, 8)  \
+    X(45, 1, 24, 64, 4)  \
+    X(47, 2, 64, 64, 8)  \
+    X(48, 2, 48, 64, 8)  \
+    X(51, 2, 48, 32, 16)
+constexpr int MAX_TILE_ID = 51;
 
-const TileDesc &tile_desc(int id);  // 1 <= id <= NUM_TILES
+bool tile_exists(int id);           // 1 <= id <= MAX_TILE_ID and the id is assigned
+const TileDesc &tile_desc(int id);  // an id for which tile_exists()
 
 // Launches kernel `kind` for tile shape `id` with grid A.K * A.G.  hp_late (look-back, backward):
 // load h after the rescan instead of together with lambda and grad_h.  gated: the form of Section

@@ -13,7 +13,13 @@
 
 namespace linrec {
 
-// Workgroups of `kernel` that fit the current device at once (compute units x blocks per unit).
+// Persistent workgroups of `kernel` to launch on the current device: compute units x workgroups per unit.
+// cap_per_cu > 0 asks for at most that many per unit, < 0 for as many as fit; 0 is the library's own
+// choice, 8 wavefronts per unit (two per SIMD): one workgroup of 512 threads or two of 256.  More
+// resident tiles than it takes to keep the memory system busy only lengthen a tile's life -- bytes in
+// flight over bandwidth -- and with it the start and the end of a launch, when that life is spent at
+// less than full bandwidth (measured on an MI355X: 2-10 % on launches of a few hundred microseconds for
+// the shapes of which three or more would fit a unit, nothing lost anywhere).
 static int64_t resident_capacity(const void *kernel, int threads, int cap_per_cu)
 {
     static std::mutex mu;
@@ -30,8 +36,10 @@ static int64_t resident_capacity(const void *kernel, int threads, int cap_per_cu
         cu_count[dev] = cus;
         it = cache.emplace(std::make_pair(dev, kernel), (int64_t)per_cu).first;
     }
-    const int64_t per_cu = (cap_per_cu > 0 && cap_per_cu < it->second) ? cap_per_cu : it->second;
-    return per_cu * cu_count[dev];
+    int64_t want = it->second;
+    if (cap_per_cu > 0) want = cap_per_cu;
+    else if (cap_per_cu == 0) want = std::max(1, 8 / std::max(1, threads / 64));
+    return std::min(want, it->second) * cu_count[dev];
 }
 
 template <class G>

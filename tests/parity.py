@@ -143,9 +143,5 @@ class options:
 
 
 def all_tiles():
-    out = []
-    i = 1
-    while (info := lr.linrec_tile_info(i)) is not None:
-        out.append((i, info))
-        i += 1
-    return out
+    """(id, description) of every tile shape the library has (ids are stable, so there are gaps)."""
+    return [(i, info) for i in range(1, 129) if (info := lr.linrec_tile_info(i)) is not None]

@@ -17,7 +17,7 @@ from test_forms_bf16_parity_gpu import to_bf16 as forms_to_bf16
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-N_TILES = len(all_tiles())
+TILE_CHOICES = [0] + [i for i, _ in all_tiles()]     # 0 = the library's own choice
 
 
 def _cases(seed, n):
@@ -29,7 +29,7 @@ def _cases(seed, n):
         n_ = max(1, C // B)
         opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_LOOKBACK, lr.VARIANT_THREEPHASE,
                                             lr.VARIANT_SERIAL, lr.VARIANT_WALK])),
-                    tile=int(rng.integers(0, N_TILES + 1)), persistent=int(rng.integers(-1, 2)),
+                    tile=int(rng.choice(TILE_CHOICES)), persistent=int(rng.integers(-1, 2)),
                     taper=int(rng.choice([0, 0, 2, 8])), hprev_late=int(rng.integers(-1, 2)))
         yield i, T, B, n_, opts, int(rng.integers(1 << 30))
 
@@ -40,7 +40,7 @@ def _wide_cases(seed, n):
     for i in range(n):
         T, C, B = int(rng.integers(50, 2000)), int(rng.integers(1000, 12000)), int(rng.choice([1, 2, 4]))
         opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_WALK])),
-                    tile=int(rng.integers(0, N_TILES + 1)), persistent=int(rng.integers(-1, 2)),
+                    tile=int(rng.choice(TILE_CHOICES)), persistent=int(rng.integers(-1, 2)),
                     taper=int(rng.choice([0, 0, 2])), hprev_late=int(rng.integers(-1, 2)))
         yield i, T, B, max(1, C // B), opts, int(rng.integers(1 << 30))
 
@@ -54,7 +54,7 @@ def _long_cases(seed, n):
         T = int(rng.integers(20000, min(400000, 12_000_000 // C)))
         B = int(rng.choice([1, 1, 2]))
         opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_LOOKBACK, lr.VARIANT_THREEPHASE])),
-                    tile=int(rng.integers(0, N_TILES + 1)), persistent=int(rng.integers(-1, 2)),
+                    tile=int(rng.choice(TILE_CHOICES)), persistent=int(rng.integers(-1, 2)),
                     taper=int(rng.choice([0, 0, 2, 8])), hprev_late=int(rng.integers(-1, 2)))
         yield i, T, B, max(1, C // B), opts, int(rng.integers(1 << 30))
 
