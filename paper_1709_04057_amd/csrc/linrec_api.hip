@@ -357,10 +357,9 @@ int auto_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
         if (C <= 512 && E >= ((int64_t)1 << 26)) return 18;  // (long and narrow)
         return T < 2048 ? (C >= 1024 ? 21 : plain) : vec >= 2 ? 15 : 18;
     }
-    // (the cell on long sequences: 512-thread workgroups, 16 rows per thread forward -- three operands per
-    // row -- and 32 backward; 6-12 % forward and 2-4 % backward over the 256-thread shapes)
+    // (the cell's forward pass on long sequences: 512-thread workgroups of 16 or 24 rows per thread -- three
+    // operands per row -- measure 1-12 % ahead of the 256-thread shapes)
     if (!bwd && T >= 8192 && C < 16384) return C <= 256 ? 34 : 33;
-    if (bwd && T >= 8192 && C < 16384) return C <= 256 ? 35 : 38;
     if (!bwd) {
         if (C >= 16384) return vec >= 4 ? (C >= 32768 ? 4 : 3) : 21;
         if (C >= 2048 && T >= 1024 && T <= 4096 && vec >= 4) return 3;
@@ -1355,7 +1354,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         fp.active = true;
         fp.variant = LINREC_VARIANT_LOOKBACK;
         static const int plain_c[] = {44, 43, 42, 38, 41, 22, 35, 34, 21, 45, 0},
-                         gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 33, 34, 35, 38, 41, 0},
+                         gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 33, 34, 35, 38, 0},
                          bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 47, 48, 51, 0};
         static const int gated16_c[] = {21, 18, 16, 15, 13, 3, 4, 7, 8, 0}, lstm16_c[] = {15, 3, 4, 5, 18, 0};
         const int *list = form == FORM_GATED ? (bf16 ? gated16_c : gated_c) : form == FORM_LSTM ? (bf16 ? lstm16_c : lstm_c)
