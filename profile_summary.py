@@ -120,8 +120,7 @@ def traffic_main(argv):
                          f"(x{d['hbm_bytes'] / alg:.3f})   [{d['name']}]")
     with open(a.out + ".json", "w") as f:
         json.dump(res, f, indent=1)
-    bench = ("bench.py " + a.bench_args.strip() + " --steps 10 --warmup 2") if a.bench_args.strip() else \
-        "bench.py --steps 10 --warmup 2 --no-cpu-baseline"
+    bench = "bench.py " + (a.bench_args.strip() + " " if a.bench_args.strip() else "") + "--steps 10 --warmup 2 --no-cpu-baseline"
     head = ("HBM bytes per launch from two rocprofv3 counter runs (one MI355X), each counter scaled by what it reads for the\n"
             "library's copy kernel of known size.  Commands, from the repository root on the GPU box:\n"
             "  cd /tmp && export TMPDIR=/tmp && cd $REPO\n"
