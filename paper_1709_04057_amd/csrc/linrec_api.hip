@@ -351,11 +351,12 @@ int auto_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
         }
         if (T < 1024) return C >= 1024 ? 21 : plain;
         if (one_round_22 && T >= 2048) return 22;
-        // (the backward pass has four operands per row in flight: few rows per thread, wide accesses)
-        if (C >= 16384) return vec >= 4 ? 4 : 21;
-        if (C >= 2048) return vec >= 4 ? 3 : vec >= 2 ? 15 : 21;
-        if (C <= 512 && E >= ((int64_t)1 << 26)) return 18;  // (long and narrow)
-        return T < 2048 ? (C >= 1024 ? 21 : plain) : vec >= 2 ? 15 : 18;
+        // (The backward pass has four operands per row.  The shapes of at most 32 elements per thread hold all
+        // four in registers and form the carry-independent part of the epilogue in front of the look-back;
+        // among them one column per thread is ahead of the 8- and 16-byte shapes by 2-4 %.)
+        if (C >= 8192) return 45;
+        if (C <= 256 && T >= 8192) return 34;
+        return 18;
     }
     // (the cell's forward pass on long sequences: 512-thread workgroups of 16 or 24 rows per thread -- three
     // operands per row -- measure 1-12 % ahead of the 256-thread shapes)
@@ -515,8 +516,12 @@ int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
         if (C <= 128) return T >= 16384 ? 13 : 16;
         return (C >= 32768 && vec >= 4) ? 8 : 16;
     }
-    if (vec < 4) return E >= ((int64_t)1 << 23) ? 16 : 15;
-    if (E >= ((int64_t)1 << 23)) return (C <= 256 && T >= 32768) ? 7 : 8;
+    // (backward, gated layer: the 32-row one-column shapes hold the four operand tiles in registers and form the
+    // carry-independent part of the epilogue in front of the look-back -- 4 % ahead of the 16-byte shape of 64
+    // elements per thread on long sequences, 30 % on a handful of columns; very wide problems keep the latter)
+    if (C >= 8192 && vec >= 4 && E >= ((int64_t)1 << 23)) return 8;
+    if (E >= ((int64_t)1 << 23)) return C >= 8192 ? 45 : 38;
+    if (vec < 4) return 15;
     return C >= 4096 ? 4 : 3;
 }
 // The walk of the gated layer and the cell on bf16 storage, from a sweep of every shape over

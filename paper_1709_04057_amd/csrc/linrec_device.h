@@ -778,6 +778,112 @@ __device__ __forceinline__ void tile_store_gated_bwd(const Args &A, const TileAd
     }
 }
 
+// The same epilogue in three steps for the shapes of at most 32 elements per thread, whose registers hold
+// all four operand tiles at once.  Everything of it that does not depend on the carry-in is moved in front of
+// the look-back: the loads of h one row behind and of the impulse pre-activations are issued with the tile's
+// own (gated_bwd_early_load), the activations and the factors
+//     ga = (h_{t-1} - i) * g * (1-g)        gb = (1-g) * tau'(i_pre)
+// are formed after the tile's summary has been published, while its predecessors are still being waited for
+// (gated_bwd_early_math), and what is left behind the rescan is two products and two stores per element
+// (gated_bwd_early_store).  With the loads and the tanh behind the rescan a tile spent 60 % of its life in
+// its epilogue (per-tile timeline of the bf16-storage kernel: 20 of 33 us).
+template <class G>
+struct GatedBwdEarly {
+    vec<G::VEC> ga[G::R], gb[G::R];
+    vec<G::VEC> c_last;  // gate complement of the thread's last existing row (its successor in time holds no copy)
+};
+#ifndef LINREC_GATED_BWD_EARLY
+#define LINREC_GATED_BWD_EARLY 1
+#endif
+template <class G>
+constexpr bool kGatedBwdEarly = LINREC_GATED_BWD_EARLY && G::R * G::VEC <= 32;
+struct NoEarly {};
+template <class G, bool ON>
+struct EarlySel { using type = GatedBwdEarly<G>; };
+template <class G>
+struct EarlySel<G, false> { using type = NoEarly; };
+
+// (Two instances, as for tile_load: in the interior one the loads are unconditional straight-line code; inside
+// run-time conditions the compiler waits for every load before it issues the next.)
+template <class G, bool INTERIOR>
+__device__ __forceinline__ void gated_bwd_early_load_impl(const Args &A, const TileAddr<G, true> &ad,
+                                                          const RowMask<G, true> &mk, int64_t col, GatedBwdEarly<G> &e)
+{
+    constexpr int R = G::R, VEC = G::VEC;
+    const rsrc_t rh = ad.rsrc(A.hprev, -1), ri = ad.rsrc(A.c), rg = ad.rsrc(A.a);
+    const int nv = INTERIOR ? R : mk.n;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        e.ga[j] = splat<VEC>(0.0f);
+        e.gb[j] = splat<VEC>(0.0f);
+        if (INTERIOR || j < mk.n) {
+            e.gb[j] = gld<G>(ri, ad.toff, ad.soff(j));
+            if (INTERIOR || j < mk.nh) e.ga[j] = gld<G>(rh, ad.toff, ad.soff(j));
+            else if (A.h0) e.ga[j] = pld<G>(A.h0, col);  // row t == 0
+        }
+    }
+    e.c_last = splat<VEC>(__builtin_inff());
+    if (INTERIOR) e.c_last = gld<G>(rg, ad.toff, ad.soff(R - 1));
+    else if (nv > 0) e.c_last = gld<G>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
+}
+template <class G>
+__device__ __forceinline__ void gated_bwd_early_load(const Args &A, const TileAddr<G, true> &ad, const RowMask<G, true> &mk,
+                                                     int64_t col, bool interior, GatedBwdEarly<G> &e)
+{
+    if (interior) gated_bwd_early_load_impl<G, true>(A, ad, mk, col, e);
+    else gated_bwd_early_load_impl<G, false>(A, ad, mk, col, e);
+}
+template <class G>
+__device__ __forceinline__ vec<G::VEC> gated_own_complement(const Rows<G> &r, const GatedBwdEarly<G> &e, int j, int nv)
+{
+    // r.a[j] is the complement of row t+1; the row's own is the next entry (the thread's next row is t-1)
+    if (j + 1 < G::R) return (j + 1 < nv) ? r.a[j + 1] : e.c_last;
+    return e.c_last;
+}
+template <class G>
+__device__ __forceinline__ void gated_bwd_early_math(const Args &A, const RowMask<G, true> &mk, bool interior,
+                                                     const Rows<G> &r, GatedBwdEarly<G> &e)
+{
+    constexpr int R = G::R, VEC = G::VEC;
+    const int nv = interior ? R : mk.n;
+    e.c_last = gate_complement<VEC>(e.c_last);
+    if (A.tau) {  // (the choice of tau stays outside the row loop)
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const vec<VEC> c = gated_own_complement<G>(r, e, j, nv), g = splat<VEC>(1.0f) - c;
+            const vec<VEC> i = impulse<VEC>(e.gb[j], 1);
+            e.ga[j] = (e.ga[j] - i) * (g * c);
+            e.gb[j] = c * vfma<VEC>(-i, i, splat<VEC>(1.0f));
+        }
+    } else {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const vec<VEC> c = gated_own_complement<G>(r, e, j, nv), g = splat<VEC>(1.0f) - c;
+            e.ga[j] = (e.ga[j] - e.gb[j]) * (g * c);
+            e.gb[j] = c;
+        }
+    }
+}
+template <class G>
+__device__ __forceinline__ void gated_bwd_early_store(const Args &A, const TileAddr<G, true> &ad, const RowMask<G, true> &mk,
+                                                      int64_t col, bool interior, const Rows<G> &r,
+                                                      const GatedBwdEarly<G> &e)
+{
+    constexpr int R = G::R, VEC = G::VEC;
+    const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(A.out1);
+    const int nv = interior ? R : mk.n;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const vec<VEC> d = r.b[j];
+        if (interior || j < mk.n) {
+            if (A.out0) gst<G>(r0, ad.toff, ad.soff(j), d * e.ga[j]);
+            if (A.out1) gst<G>(r1, ad.toff, ad.soff(j), d * e.gb[j]);
+            if (!interior && j == mk.nh && A.gh0)
+                pst<G>(A.gh0, col, (splat<VEC>(1.0f) - gated_own_complement<G>(r, e, j, nv)) * d);
+        }
+    }
+}
+
 // Forward epilogue of the LSTM cell: r.b[j] = c_t; the output gate's pre-activation is loaded here, in
 // chunks, and c_t and h_t = sigmoid(o_pre)*c_t are stored (either output may be absent).
 template <class G>
@@ -1125,11 +1231,15 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_walk(const Args A)
         if constexpr (BWD && FORM == FORM_PLAIN) {
             if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
         }
+        constexpr bool EARLY = BWD && FORM == FORM_GATED && kGatedBwdEarly<G>;
+        typename EarlySel<G, EARLY>::type early[1];
+        if constexpr (EARLY) gated_bwd_early_load<G>(A, ad, mk, col, interior, early[0]);
         vec<VEC> S, Se, St;
         dvec<VEC> P, Pe, Pt;
         local_reduce<G, FORM>(r, P, S);
         if (m > 0) __syncthreads();  // the previous tile's wavefront totals have been consumed
         tile_scan<G>(lds, tid, P, S, Pe, Se, Pt, St);
+        if constexpr (EARLY) gated_bwd_early_math<G>(A, mk, interior, r, early[0]);
         const vec<VEC> carry_in = narrow<VEC>(dfma<VEC>(Pe, cc, widen<VEC>(Se)));
         if constexpr (BWD && G::IO == IO_BF16) {
             static_assert(FORM == FORM_PLAIN, "bf16 storage: the plain recurrence");
@@ -1137,7 +1247,9 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_walk(const Args A)
         } else {
             rescan<G, FORM>(r, carry_in);
         }
-        if constexpr (BWD && FORM == FORM_GATED) {
+        if constexpr (EARLY) {
+            gated_bwd_early_store<G>(A, ad, mk, col, interior, r, early[0]);
+        } else if constexpr (BWD && FORM == FORM_GATED) {
             __builtin_amdgcn_sched_barrier(0);  // the epilogue's loads stay behind the rescan
             tile_store_gated_bwd<G>(A, ad, mk, col, interior, r);
         } else if constexpr (FORM == FORM_LSTM) {
@@ -1264,6 +1376,9 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     if constexpr (BWD && !HP_LATE && FORM == FORM_PLAIN) {
         if (A.out1) tile_load_hprev<G>(A, ad, mk, col, interior, hp);
     }
+    constexpr bool EARLY = BWD && FORM == FORM_GATED && kGatedBwdEarly<G>;
+    typename EarlySel<G, EARLY>::type early[1];
+    if constexpr (EARLY) gated_bwd_early_load<G>(A, ad, mk, col, interior, early[0]);
     // thread-exclusive prefix inside the tile; rounded to fp32 once (it is used once, in the
     // rescan's carry-in, and is not fed on along the chain of tiles)
     vec<VEC> Pe32, Se32;
@@ -1295,6 +1410,9 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
             }
         }
     }
+    // (the carry-independent part of the gated backward epilogue: behind the publication, so that it does not
+    // delay the tiles that wait for this one, and in front of this tile's own waits)
+    if constexpr (EARLY) gated_bwd_early_math<G>(A, mk, interior, r, early[0]);
     LINREC_TRACE_MARK(2);
     [[maybe_unused]] int n_windows = 0;  // (read by trace builds)
     unsigned long long next_ticket = 0xffffffffull;
@@ -1401,7 +1519,9 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     } else {
         rescan<G, FORM>(r, vfma<VEC>(Pe32, Sr, Se32));
     }
-    if constexpr (BWD && FORM == FORM_GATED) {
+    if constexpr (EARLY) {
+        gated_bwd_early_store<G>(A, ad, mk, col, interior, r, early[0]);
+    } else if constexpr (BWD && FORM == FORM_GATED) {
         __builtin_amdgcn_sched_barrier(0);  // the epilogue's loads stay behind the rescan
         tile_store_gated_bwd<G>(A, ad, mk, col, interior, r);
     } else if constexpr (FORM == FORM_LSTM) {
