@@ -64,11 +64,11 @@ def parse():
     ap.add_argument("--dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of the tensors (bf16: linrec_forward_bf16 / linrec_backward_bf16, 6 and 10 "
                          "bytes per element; the arithmetic is fp32 either way)")
-    ap.add_argument("--gated", default="", choices=["", "g2", "g3", "g4"],
+    ap.add_argument("--gated", default="", choices=["", "g2", "g3", "g4", "g5"],
                     help="time the gated (GILR) entry points on this workload instead (sigmoid / tanh applied in the "
                          "scan kernel: 12 B/element forward, 24 backward), next to the unfused sequence "
                          "elementwise kernels + linrec_forward")
-    ap.add_argument("--lstm", default="", choices=["", "l2", "l4"],
+    ap.add_argument("--lstm", default="", choices=["", "l2", "l4", "l5"],
                     help="time the LSTM-cell entry points on this workload instead (24 B/element forward, 40 backward), "
                          "next to the unfused forward")
     ap.add_argument("--probe", action="store_true", help="accepted for older command lines; the default now")
@@ -341,7 +341,8 @@ def gated_bench(args, lr, torch, wl):
         import oracle
         threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
         C = B * n
-        f = lambda t: t.float().cpu().numpy().reshape(-1, C)
+        Ts = min(T, (1 << 27) // C)               # a bounded sample: the first rows, at most 2^27 elements
+        f = lambda t: t[:Ts].float().cpu().numpy().reshape(-1, C)
         gp, ip, ee, hh = f(g_pre), f(i_pre), f(e), f(h)
         h0v = h0.float().cpu().numpy().reshape(-1)
         oracle.build()
@@ -350,9 +351,10 @@ def gated_bench(args, lr, torch, wl):
         t1 = time.perf_counter()
         oracle.gilr_backward(gp, ip, hh, h0v, ee, threads=threads)
         t2 = time.perf_counter()
-        out["cpu_baseline"] = {"value": E / (t2 - t0), "unit": "elements/s", "cores": threads, "kind": "oracle",
-                               "sample": f"the full workload, one forward + one backward pass of the fp64 oracle of the gated "
-                                         f"layer over {threads} host threads; forward {t1 - t0:.3f} s, backward {t2 - t1:.3f} s"}
+        out["cpu_baseline"] = {"value": Ts * C / (t2 - t0), "unit": "elements/s", "cores": threads, "kind": "oracle",
+                               "sample": f"{'the full workload' if Ts == T else f'the first {Ts} of {T} rows'}, one forward + one "
+                                         f"backward pass of the fp64 oracle of the gated layer over {threads} host threads; "
+                                         f"forward {t1 - t0:.3f} s, backward {t2 - t1:.3f} s"}
     print(json.dumps(out), flush=True)
 
 
@@ -442,7 +444,8 @@ def lstm_bench(args, lr, torch, wl):
         import oracle
         threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
         C = B * n
-        f = lambda t: t.float().cpu().numpy().reshape(-1, C)
+        Ts = min(T, (1 << 27) // C)               # a bounded sample: the first rows, at most 2^27 elements
+        f = lambda t: t[:Ts].float().cpu().numpy().reshape(-1, C)
         pp = [f(p) for p in pre]
         c0v = c0.float().cpu().numpy().reshape(-1)
         ee, cc = f(e), f(c)
@@ -452,9 +455,10 @@ def lstm_bench(args, lr, torch, wl):
         t1 = time.perf_counter()
         oracle.lstm_backward(*pp, cc, c0v, ee, threads=threads)
         t2 = time.perf_counter()
-        out["cpu_baseline"] = {"value": E / (t2 - t0), "unit": "elements/s", "cores": threads, "kind": "oracle",
-                               "sample": f"the full workload, one forward + one backward pass of the fp64 oracle of the LSTM "
-                                         f"cell over {threads} host threads; forward {t1 - t0:.3f} s, backward {t2 - t1:.3f} s"}
+        out["cpu_baseline"] = {"value": Ts * C / (t2 - t0), "unit": "elements/s", "cores": threads, "kind": "oracle",
+                               "sample": f"{'the full workload' if Ts == T else f'the first {Ts} of {T} rows'}, one forward + one "
+                                         f"backward pass of the fp64 oracle of the LSTM cell over {threads} host threads; "
+                                         f"forward {t1 - t0:.3f} s, backward {t2 - t1:.3f} s"}
     print(json.dumps(out), flush=True)
 
 

@@ -285,9 +285,10 @@ int linrec_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_t *i_pre,
 int linrec_set_option(int option, int64_t value);
 int64_t linrec_get_option(int option);
 
-/* Describes tile shape `tile_id` (1-based): threads along columns, threads along time, rows
- * per thread, columns per thread.  Returns LINREC_ERR_OPTION past the last id.  Any output
- * pointer may be NULL.  Host-only; makes no HIP call. */
+/* Describes tile shape `tile_id`: threads along columns, threads along time, rows per thread,
+ * columns per thread.  Ids are stable across versions and have gaps: the library is built for the
+ * shapes that measured fastest somewhere (plan_sweep.py), and LINREC_ERR_OPTION is returned for an
+ * id it has no kernel of.  Any output pointer may be NULL.  Host-only; makes no HIP call. */
 int linrec_tile_info(int tile_id, int *threads_cols, int *threads_time, int *rows_per_thread,
                      int *cols_per_thread);
 
@@ -308,6 +309,12 @@ enum {
 };
 int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward,
                     int alignment_bytes, int *variant, int *tile_id);
+
+/* 1 if the library has kernels of tile shape `tile_id` for entry-point family `entry_point`
+ * (LINREC_ENTRY_*), else 0: each family is built for the shapes its static plans use.  A
+ * LINREC_OPT_TILE or pinned plan that names another shape falls back to the automatic choice.
+ * Host-only; makes no HIP call. */
+int linrec_tile_has(int tile_id, int entry_point);
 
 /* Fixes the plan of one shape for every thread: later calls of entry-point family `entry_point`
  * (LINREC_ENTRY_*) with exactly this [T, B, n] and pass on the current device use variant

@@ -150,6 +150,8 @@ GATED = {
     "g2": dict(T=65536, B=4, n=256, gate_mean=2.0, gate_std=1.0, note="workload 2's shape, gates sigmoid(N(2,1))"),
     "g3": dict(T=1048576, B=1, n=128, gate_mean=7.0, gate_std=2.0,
                note="one million steps, gates mostly within 1e-2..1e-5 of one (long memory)"),
+    "g5": dict(T=262144, B=8, n=512, gate_mean=1.0, gate_std=1.5,
+               note="workload 5's shape (1.07e9 elements): the layer at the size the headline is measured on"),
 }
 
 
@@ -180,6 +182,7 @@ def make_gated(T, B, n, seed, device="cpu", gate_mean=0.0, gate_std=1.0, with_h0
 LSTM = {
     "l4": dict(T=4096, B=16, n=1024, forget_mean=1.0, note="workload 4's shape; forget gates sigmoid(N(1,1))"),
     "l2": dict(T=65536, B=4, n=256, forget_mean=2.0, note="workload 2's shape; forget gates sigmoid(N(2,1))"),
+    "l5": dict(T=262144, B=8, n=512, forget_mean=1.5, note="workload 5's shape (1.07e9 elements)"),
 }
 
 

@@ -94,6 +94,8 @@ def lib():
         L.linrec_get_option.restype = i64
         L.linrec_tile_info.argtypes = [ci, pi, pi, pi, pi]
         L.linrec_tile_info.restype = ci
+        L.linrec_tile_has.argtypes = [ci, ci]
+        L.linrec_tile_has.restype = ci
         L.linrec_plan.argtypes = [i64, i64, i64, ci, ci, pi, pi]
         L.linrec_plan.restype = ci
         L.linrec_plan_for.argtypes = [ci, i64, i64, i64, ci, ci, pi, pi]
@@ -339,13 +341,19 @@ def linrec_get_option(option: int) -> int:
 
 
 def linrec_tile_info(tile_id: int):
-    """Returns dict(threads_cols, threads_time, rows_per_thread, cols_per_thread, rows, cols) or None past the end."""
+    """Returns dict(threads_cols, threads_time, rows_per_thread, cols_per_thread, rows, cols), or None for an id
+    the library has no kernel of."""
     a, b, c, d = (ctypes.c_int() for _ in range(4))
     rc = lib().linrec_tile_info(int(tile_id), ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(d))
     if rc != 0:
         return None
     return dict(threads_cols=a.value, threads_time=b.value, rows_per_thread=c.value, cols_per_thread=d.value,
                 rows=b.value * c.value, cols=a.value * d.value)
+
+
+def linrec_tile_has(tile_id: int, entry_point: int) -> bool:
+    """Whether the library has kernels of this tile shape for entry-point family ``entry_point`` (ENTRY_*)."""
+    return bool(lib().linrec_tile_has(int(tile_id), int(entry_point)))
 
 
 def linrec_plan(T, B, n, backward=False, alignment=16):

@@ -32,7 +32,17 @@ struct TileTable {  // indexed by id; unassigned ids hold zeros
 };
 static constexpr TileTable kTable{};
 
-bool tile_exists(int id) { return id >= 1 && id <= MAX_TILE_ID && kTable.t[id].vec != 0; }
+struct FamilyTable {  // indexed by id: the families this build has kernels of that shape for
+    unsigned m[MAX_TILE_ID + 1];
+    constexpr FamilyTable() : m{}
+    {
+        for (int id = 0; id <= MAX_TILE_ID; ++id) m[id] = tile_families(id);
+    }
+};
+static constexpr FamilyTable kFamilies{};
+
+bool tile_has(int id, int family) { return id >= 1 && id <= MAX_TILE_ID && (kFamilies.m[id] >> family & 1u); }
+bool tile_exists(int id) { return id >= 1 && id <= MAX_TILE_ID && kFamilies.m[id] != 0; }
 const TileDesc &tile_desc(int id) { return kTable.t[id]; }
 
 hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A, hipStream_t s)
@@ -222,351 +232,48 @@ int max_vec_bf16(int64_t C, std::initializer_list<const void *> ptrs)
 
 int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
-// Tiles a shape cuts a [T, C] problem into.
-int64_t tile_count(int id, int64_t T, int64_t C)
+// ---- static plans --------------------------------------------------------------------------
+// What a first call on a shape gets: per entry-point family, pass and problem size the variant and tile
+// shape that measured fastest on an MI355X, from a table written by plan_sweep.py (a grid of powers of
+// two in T, half octaves in C; per cell the best shape among those whose accesses are 1, 2 or 4 columns
+// wide, and the walk's shape where the walk was ahead).  A problem between grid points takes the plan of
+// the nearest one (in ratio); one smaller or larger than everything measured at its width, the nearest
+// measured size.  After a change of driver, compiler or clocks the table is measured again, not edited.
+#include "linrec_plan_table.inc"
+static_assert(sizeof kPlanCells / sizeof kPlanCells[0] == LINREC_ENTRY_LSTM_CELL_BF16 + 1, "one table per family");
+static_assert(LINREC_ENTRY_PLAIN == 0 && LINREC_ENTRY_GILR == 1 && LINREC_ENTRY_LSTM_CELL == 2 && LINREC_ENTRY_BF16 == 3 &&
+                  LINREC_ENTRY_GILR_BF16 == 4 && LINREC_ENTRY_LSTM_CELL_BF16 == 5,
+              "the family masks of tile_families() are indexed by LINREC_ENTRY_*");
+
+struct StaticPlan {
+    int lookback;  // the single pass's tile shape (0: the family has no kernel at this access width)
+    int walk;      // the walk's, where the walk is the better variant; else 0
+};
+StaticPlan static_plan(int family, bool bwd, int64_t T, int64_t C, int vec)
 {
-    const TileDesc &d = kTable.t[id];
-    return ceil_div(T, d.rows()) * ceil_div(C, d.cols());
+    const int w = vec >= 4 ? 2 : vec >= 2 ? 1 : 0;
+    int ci = 0;  // nearest column count of the grid, in ratio
+    for (int i = 1; i < kPlanNc; ++i)
+        if ((double)C * C >= (double)kPlanC[i - 1] * kPlanC[i]) ci = i;
+    int lt = kPlanLtMin;  // nearest power of two
+    while (lt < kPlanLtMax && (double)T * T >= (double)((int64_t)1 << lt) * (double)((int64_t)2 << lt)) ++lt;
+    const int nt = kPlanLtMax - kPlanLtMin + 1;
+    for (int d = 0; d < nt; ++d) {
+        for (const int l : {lt - d, lt + d}) {
+            if (l < kPlanLtMin || l > kPlanLtMax) continue;
+            const PlanCell &c = kPlanCells[family][bwd ? 1 : 0][l - kPlanLtMin][ci];
+            // (the walk keeps one workgroup per column group busy for the whole sequence: a plan measured on a
+            // much shorter or longer sequence says nothing about it)
+            if (c.lookback[w] && tile_has(c.lookback[w], family))
+                return StaticPlan{c.lookback[w], (d <= 1 && tile_has(c.walk[w], family)) ? c.walk[w] : 0};
+        }
+    }
+    // nothing measured at this width: any shape the family has
+    for (int id = 1; id <= MAX_TILE_ID; ++id)
+        if (tile_has(id, family) && kTable.t[id].vec <= vec) return StaticPlan{id, 0};
+    return StaticPlan{0, 0};
 }
 
-// Of the shapes in `family` (tallest first), the one that covers the problem in ONE round of workgroups --
-// at most one tile per compute unit, and at least 60 % of the units busy -- with the most tiles; 0 if none
-// does.  A problem of that size is over in a single tile life whatever the shape, so the shape that puts
-// the most units to work wins; every mid-sized problem in the sweeps behind these rules ran best that way.
-int one_round_shape(std::initializer_list<int> family, int64_t T, int64_t C, int64_t units)
-{
-    int best = 0;
-    int64_t best_n = 0;
-    for (const int id : family) {
-        const int64_t n = tile_count(id, T, C);
-        if (n <= units && 10 * n >= 6 * units && n > best_n) {
-            best = id;
-            best_n = n;
-        }
-    }
-    return best;
-}
-
-// Tile shape for a [T, C] problem of the plain fp32 recurrence when the caller did not fix one.  All the
-// shapes it takes keep one column per thread and eight wavefronts per compute unit (see the launch code),
-// and differ in three ways only:
-//   * width: 64 threads side by side (256-byte row segments) once there are 512 columns, else 32;
-//   * rows per thread R, i.e. bytes in flight per compute unit: the forward pass (two operands per row in
-//     registers, 12 B/element) wants R = 64, or 48 when rows are long (C >= 8192); the backward pass
-//     (three operands, 20 B/element) R = 40, or 32 when rows are long (C >= 4096).  About 300-400 KB per unit either way: enough to keep the
-//     memory system busy, and no more, because a tile's life is bytes in flight over bandwidth and a launch
-//     spends about one tile life below full bandwidth while it starts and ends;
-//   * threads along time: 8 or 16 per 512-thread workgroup (one per unit); very wide problems
-//     (C >= 16384) run better on 256-thread workgroups, two per unit, of short tiles.
-// Narrow problems (few column groups) take the tallest tiles: the chain of tiles along T is what they
-// wait for.  Problems that fit one round of workgroups take the shape that makes the fullest round.
-// Condensed from a sweep of 17 shapes over T = 256 .. 1048576 x C = 128 .. 65536 on an MI355X: within
-// 1.1 % (forward) and 1.7 % (backward) of the best shape on average; linrec_tune() closes the rest for a
-// given shape and box.
-int auto_tile(int64_t T, int64_t C, int vec, bool bwd, int variant)
-{
-    (void)variant;
-    if (C <= 16) return T >= 4096 ? 23 : 2;
-    if (T < 192) return vec >= 4 ? 10 : 21;  // a few rows per thread
-    int dev = 0, units = 256;
-    if (hipGetDevice(&dev) == hipSuccess) units = compute_units(dev);
-    const bool narrow = C < 512;
-    if (!bwd) {
-        if (C >= 32768) return 21;
-        if (narrow) {
-            if (const int t = one_round_shape({22, 35, 34}, T, C, units)) return t;
-            return T >= 32768 ? 22 : T >= 6144 ? 35 : T >= 1536 ? 19 : T >= 512 ? 18 : C >= 48 ? 1 : 2;
-        }
-        if (C >= 8192) {
-            if (const int t = one_round_shape({43, 42, 38, 41}, T, C, units)) return t;
-            return T >= 512 ? 43 : 21;
-        }
-        if (const int t = one_round_shape({44, 43, 42, 38, 41}, T, C, units)) return t;
-        for (const int id : {44, 43, 42, 38})
-            if (tile_count(id, T, C) >= 3 * (int64_t)units) return id;
-        return T >= 512 ? 38 : 21;
-    }
-    if (C >= 16384) return C >= 32768 ? 21 : 45;
-    if (narrow) {
-        if (const int t = one_round_shape({22, 35, 34}, T, C, units)) return t;
-        if (tile_count(35, T, C) >= 4 * (int64_t)units) return 35;
-        return T >= 32768 ? 22 : T >= 6144 ? 34 : T >= 1536 ? 19 : T >= 512 ? 18 : C >= 48 ? 1 : 2;
-    }
-    if (const int t = one_round_shape({43, 42, 38, 41}, T, C, units)) return t;
-    // (rows of 16 KB and more: 32 rows per thread measure 1-2 % ahead of 40)
-    if (tile_count(42, T, C) >= 2 * (int64_t)units) return C >= 4096 ? 38 : 42;
-    return T >= 512 ? 38 : 21;
-}
-
-// The same for bf16 storage (shapes with 2 or 4 columns per thread), from the same kind of sweep:
-// 1.7 % (forward) and 5 % (backward) from the best shape on average.  Mid-sized problems run best as
-// ONE round of workgroups, one tile per compute unit, hence the rules on the number of tiles.
-int auto_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
-{
-    if (T < 192) return C >= 16384 ? (vec >= 4 ? 9 : 16) : 15;  // a few rows per thread
-    // (512 or more columns: 64 threads side by side, 512-thread workgroups of 64 or 48 rows per thread)
-    if (!bwd && C >= 512 && T * C >= ((int64_t)1 << 22)) return 47;
-    if (bwd && C >= 512 && T >= 2048 && T * C >= ((int64_t)1 << 23)) return 48;
-    if (bwd && C <= 128 && T >= 65536) return 51;
-    if (!bwd) {
-        const int small = T >= 1024 ? 16 : 15;
-        if (C >= 32768 || (C >= 16384 && T >= 4096)) return 28;
-        if (T >= 32768 && C <= 128 && (T < 131072 || C <= 32)) return 25;
-        if (T >= 32768 && C <= 512) return 30;
-        const int64_t n30 = ceil_div(T, 1024) * ceil_div(C, 64);  // tiles of the tallest shape
-        if (n30 > 128 && n30 <= 256) return 30;
-        if (T * C >= ((int64_t)1 << 22)) return 24;
-        return small;
-    }
-    if (C <= 128 && T >= 8192) return T <= 32768 ? 14 : 25;
-    if (T >= 4096) return (T * C >= ((int64_t)1 << 23) && T * C <= ((int64_t)1 << 24)) ? 24 : 29;
-    if (T * C >= ((int64_t)1 << 23)) return vec >= 4 ? 27 : 28;
-    return T >= 256 ? 16 : 15;
-}
-
-// The same for the gated layer and the LSTM cell, which exist for the shapes whose rows per thread are
-// a multiple of 8 (or fewer than 8); the cell for those of at most 32 elements per thread and operand.
-// They compute a sigmoid and a tanh per element before a tile can publish its summary: shapes with 32
-// or 48 rows per thread (more resident workgroups than the 64-row shapes) hide that better, 256-byte
-// row segments pay from fewer columns on than in the plain recurrence, and the backward passes (four
-// and six operands per row) like few rows per thread with 16-byte accesses on wide problems.
-int auto_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
-{
-    const int plain = auto_tile(T, C, 1, bwd, 0);
-    if (C <= 16) return plain;
-    const int64_t E = T * C, n22 = ceil_div(T, 1024) * ceil_div(C, 32);  // (tiles of the tallest shape)
-    const bool one_round_22 = n22 > 128 && n22 <= 256;  // one tile per compute unit
-    if (bwd && E <= ((int64_t)1 << 19)) return 2;
-    // (a handful of column groups and a long sequence: the chain of tiles is what takes the time, and the
-    // tallest shape makes it shortest)
-    if (form == FORM_GATED && C <= 128 && T >= 65536) return 22;
-    if (form == FORM_GATED) {
-        if (!bwd) {
-            if (T < 2048) return plain;
-            if (C >= 12288 && C < 24576 && vec >= 2) return 14;  // 8-byte accesses
-            if (C >= 16384) return 21;
-            if (one_round_22) return 22;
-            if (E >= ((int64_t)1 << 24)) return 19;
-            return C >= 2048 ? 20 : 17;
-        }
-        if (T < 1024) return C >= 1024 ? 21 : plain;
-        if (one_round_22 && T >= 2048) return 22;
-        // (The backward pass has four operands per row.  The shapes of at most 32 elements per thread hold all
-        // four in registers and form the carry-independent part of the epilogue in front of the look-back;
-        // among them one column per thread is ahead of the 8- and 16-byte shapes by 2-4 %.)
-        if (C >= 8192) return 45;
-        if (C <= 256 && T >= 8192) return 34;
-        return 18;
-    }
-    // (the cell's forward pass on long sequences: 512-thread workgroups of 16 or 24 rows per thread -- three
-    // operands per row -- measure 1-12 % ahead of the 256-thread shapes)
-    if (!bwd && T >= 8192 && C < 16384) return C <= 256 ? 34 : 33;
-    if (!bwd) {
-        if (C >= 16384) return vec >= 4 ? (C >= 32768 ? 4 : 3) : 21;
-        if (C >= 2048 && T >= 1024 && T <= 4096 && vec >= 4) return 3;
-        return C >= 8192 ? 21 : T >= 256 ? 18 : plain;
-    }
-    if (C >= 16384 && T >= 2048 && vec >= 4) return 4;
-    return C >= 2048 ? 21 : T >= 256 ? 18 : plain;
-}
-
-// Tile shape for the walk variant (one workgroup per column group, nothing between workgroups), or 0
-// where the single pass is the better choice.  Measured on an MI355X over T = 64 .. 16384 x
-// C = 1024 .. 65536: the walk wins by 1.2-1.7x for T <= 1024 and C >= 8192 and by 1.05-1.15x for the
-// widest problems up to T = 4096; it loses as soon as the columns alone do not fill the GPU.  It
-// wants about one workgroup per compute unit (256) to a few, all resident at once, so the width of
-// the tile follows C.
-int walk_tile(int64_t T, int64_t C, int vec, bool bwd)  // (the shape, wherever the walk is asked for)
-{
-    if (C <= 8192) return T <= 256 ? 18 : T <= 512 ? (vec >= 2 ? 13 : 17) : 22;  // 32 columns; 256, 512 or 1024 rows
-    if (C <= 16384) return vec >= 2 ? 16 : 20;     // 64 columns
-    if (C <= 24576) return 18;                     // 32 columns, three or four workgroups per compute unit
-    if (C <= 32768 || vec < 4) return 21;          // 64 columns
-    return bwd ? 6 : 10;                           // 256 columns (16-byte accesses)
-}
-int auto_walk_tile(int64_t T, int64_t C, int vec, bool bwd)
-{
-    const bool walk = (T <= 512 && C >= 4096) || (T <= 1024 && C >= 8192) || (T <= 2048 && C >= 24576) ||
-                      (T <= 4096 && C >= 32768 && !bwd) ||
-                      (T <= 2048 && C > 7168 && C <= 8192);  // 225 .. 256 workgroups of 1024 x 32 tiles
-    return walk ? walk_tile(T, C, vec, bwd) : 0;
-}
-
-// The same for the gated layer and the LSTM cell, from a sweep of every shape they have over
-// T = 64 .. 4096 x C = 2048 .. 65536 (within 1-2 % of the best choice on average, 14 % at worst).  Their
-// tiles take longer (activations), so the region where the walk wins is smaller than for the plain
-// recurrence: up to T = 512 .. 1024, further only for the widest problems, by 1.1-1.5x.  Short
-// sequences want tiles about as tall as T; where alignment allows, 8- and 16-byte accesses with 8 or 16
-// rows per thread beat the one-column shapes by 10-25 %; a width that makes a whole number of rounds of
-// 256 workgroups (C = 8192, 16384 with 32 columns per tile) extends the region to T = 1024.
-int auto_walk_tile_form(int64_t T, int64_t C, int vec, bool bwd, int form)
-{
-    if (form == FORM_GATED) {
-        if (!bwd) {
-            if (T <= 64) return C < 16384 ? 0 : vec >= 4 ? 6 : C < 49152 ? 21 : 1;
-            if (T <= 256) return C < 8192 ? 0 : C <= 8192 ? 18 : C <= 16384 ? 20 : C <= 24576 ? 18 : 1;
-            if (T <= 512)
-                return C < 8192 ? 0 : C <= 8192 ? 17 : C <= 16384 ? (vec >= 2 ? 15 : 20) : C <= 24576 ? 18 : 1;
-            if (T <= 1024) {
-                if (C > 7168 && C <= 8192) return 22;
-                if (C > 8192 && C <= 12288) return vec >= 4 ? 3 : 0;
-                if (C > 12288 && C <= 16384) return vec >= 2 ? 15 : 20;
-                if (C > 16384 && C <= 24576) return 18;
-                return C > 24576 ? (C < 49152 ? 1 : 21) : 0;
-            }
-            return (T <= 4096 && C >= 32768 && C < 49152) ? 1 : 0;
-        }
-        if (T <= 64) {
-            if (C >= 24576 && vec >= 4) return 5;
-            return C < 8192 ? 0 : C <= 24576 ? 18 : C < 49152 ? 21 : 1;
-        }
-        if (T <= 128) {
-            if (C < 8192) return 0;
-            if (vec >= 4) return 4;
-            if (vec >= 2 && C <= 16384) return 15;
-            return C <= 24576 ? 18 : 1;
-        }
-        if (T <= 256) {
-            if (C < 4096) return 0;
-            if (C < 8192) return vec >= 4 ? 3 : 2;
-            if (C <= 16384) return vec >= 4 ? 3 : vec >= 2 ? 15 : 18;
-            if (C <= 24576) return 18;
-            return (C <= 32768 && vec >= 2) ? 16 : 21;
-        }
-        if (T <= 512) {
-            if (C < 8192) return 0;
-            if (C <= 12288) return vec >= 4 ? 3 : vec >= 2 ? 15 : 0;
-            if (C <= 16384) return vec >= 2 ? 15 : 18;
-            if (C <= 24576) return 18;
-            return (C <= 32768 && vec >= 2) ? 16 : 21;
-        }
-        if (T <= 1024) {
-            if (C > 7168 && C <= 8192) return 22;
-            if (C > 12288 && C <= 16384) return vec >= 2 ? 15 : 0;
-        }
-        return (T <= 2048 && C >= 49152) ? 21 : 0;
-    }
-    // the cell
-    if (C < 4096) return 0;
-    if (T <= 64) return 1;
-    if (!bwd) {
-        if (T <= 128) {
-            if (C < 8192) return 18;
-            if (C <= 24576) return vec >= 4 ? 4 : (vec >= 2 && C > 16384) ? 15 : 21;
-            return 21;
-        }
-        if (T <= 256) return C <= 24576 ? (vec >= 2 ? 15 : 18) : 21;
-        if (T <= 512) {
-            if (C < 8192) return 0;
-            if (C <= 24576) return vec >= 2 ? 15 : 0;
-            return vec >= 4 ? (C < 49152 ? 5 : 4) : 0;
-        }
-        if (T <= 1024) {
-            if ((C > 7168 && C <= 8192) || (C > 14336 && C <= 16384)) return vec >= 2 ? 15 : 0;
-            if (C >= 49152) return vec >= 4 ? 4 : 0;
-        }
-        return 0;
-    }
-    if (T <= 128) {
-        if (C > 8192 && C <= 16384) return vec >= 4 ? 4 : vec >= 2 ? 15 : 21;
-        return C >= 32768 ? 21 : 18;
-    }
-    if (T <= 256) {
-        if (C <= 16384) return vec >= 2 ? 15 : 18;
-        if (C <= 24576) return 18;
-        return vec >= 4 ? (C >= 49152 ? 6 : 5) : 21;
-    }
-    if (T <= 512) {
-        if (C < 8192) return 0;
-        if (C <= 8192) return vec >= 4 ? 3 : 0;
-        if (C <= 16384) return vec >= 4 ? 4 : (vec >= 2 && C > 14336) ? 15 : 0;
-        if (C <= 24576) return 18;
-        if (C <= 32768) return vec >= 4 ? 5 : 21;
-        return vec >= 4 ? 6 : 0;
-    }
-    return 0;
-}
-int auto_walk_tile_bf16(int64_t T, int64_t C, int vec, bool bwd)
-{
-    const bool walk = (T <= 1024 && C >= 12288) || (T <= 2048 && C >= 32768);
-    if (!walk || vec < 2) return 0;
-    if (C <= 16384) return T >= 768 ? 30 : (bwd && vec >= 4) ? 26 : 24;
-    return vec >= 4 ? 8 : 28;
-}
-
-// Shapes of the gated layer and the cell on bf16 storage (their kernels exist for the shapes with two or
-// four columns per thread; the register tile is the fp32 one, the bytes are half), from a sweep over
-// T = 256 .. 65536 x C = 256 .. 32768.  The fp32 register tile now stands for half the bytes in flight, so
-// these kernels take nearly the time of the fp32 ones, and the shapes with the most elements per thread
-// win: 64 elements per thread for the gated layer's backward pass (8), 32 for the cell (4, the most it has).
-int auto_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
-{
-    const int64_t E = T * C;
-    if (vec < 2) return auto_tile_form(T, C, 1, bwd, form);  // 2-byte accesses: the one-column shapes
-    if (form == FORM_LSTM) {
-        if (vec < 4) return 15;
-        if (bwd) return C <= 512 ? (T >= 16384 ? 15 : 3) : 4;
-        if (C >= 4096) return 4;
-        if (C >= 2048) return T >= 16384 ? 15 : 3;
-        return T >= 4096 ? 15 : 3;
-    }
-    if (!bwd) {
-        // (the two-column shapes of 64 elements per thread: 64 columns wide, or 32 for a handful of
-        // column groups; the widest problems take 16-byte accesses)
-        if (C <= 128) return T >= 16384 ? 13 : 16;
-        return (C >= 32768 && vec >= 4) ? 8 : 16;
-    }
-    // (backward, gated layer: the 32-row one-column shapes hold the four operand tiles in registers and form the
-    // carry-independent part of the epilogue in front of the look-back -- 4 % ahead of the 16-byte shape of 64
-    // elements per thread on long sequences, 30 % on a handful of columns; very wide problems keep the latter)
-    if (C >= 8192 && vec >= 4 && E >= ((int64_t)1 << 23)) return 8;
-    if (E >= ((int64_t)1 << 23)) return C >= 8192 ? 45 : 38;
-    if (vec < 4) return 15;
-    return C >= 4096 ? 4 : 3;
-}
-// The walk of the gated layer and the cell on bf16 storage, from a sweep of every shape over
-// T = 64 .. 2048 x C = 2048 .. 65536 with 8-byte aligned tensors (within 0.1-2 % of the best choice on
-// average; the single pass takes 1.1-2.7x as long where the walk is taken).  Their single pass is short
-// of resident bytes rather than of bandwidth, so the walk pays further out than with fp32 storage: up to
-// T = 2048 for C >= 32768.  The four-column shapes with 8 rows per thread (3, 4, 5: 32, 64, 128 columns)
-// carry it; the width follows C.
-int auto_walk_tile_form_bf16(int64_t T, int64_t C, int vec, bool bwd, int form)
-{
-    if (vec >= 4) {
-        const int wide = C >= 49152 ? 5 : 4;
-        if (T <= 64) return C < 16384 ? 0 : (form == FORM_LSTM && bwd && C < 24576) ? 4 : 5;
-        if (T <= 128) return C < 8192 ? 0 : (form == FORM_GATED && !bwd) ? 4 : wide;
-        if (form == FORM_GATED && !bwd) {
-            if (T <= 256) return C >= 4096 ? 4 : 0;
-            if (T <= 512) return C < 8192 ? 0 : C <= 8192 ? 13 : C <= 16384 ? 16 : 4;
-            if (T <= 1024) return C <= 12288 ? 0 : C <= 16384 ? 16 : 4;
-            return (T <= 2048 && C >= 32768) ? 4 : 0;
-        }
-        if (T <= 256) {
-            if (C < 4096) return 0;
-            if (form == FORM_GATED) return C <= 16384 ? 3 : wide;
-            if (!bwd) return C <= 12288 ? 3 : wide;
-            return C <= 8192 ? 3 : C <= 16384 ? 0 : wide;
-        }
-        if (T <= 512) {
-            if (form == FORM_GATED) return C >= 24576 ? wide : 0;
-            if (!bwd && C > 12288 && C <= 16384) return 3;
-        }
-        return (T <= 2048 && C >= 32768) ? wide : 0;
-    }
-    // narrower accesses: the shortest sequences only (T <= 256, the gated layer's backward pass below
-    // C = 32768, the cell's forward pass), in the fp32 rule's region; where that lands on a one-column
-    // shape while 4-byte accesses are possible, the two-column shape of the same width and height
-    if (T > 256 || (bwd && (form == FORM_LSTM || C >= 32768))) return 0;
-    const int t = auto_walk_tile_form(T, C, vec, bwd, form);
-    if (t < 1 || kTable.t[t].vec >= 2 || vec < 2) return t < 1 ? 0 : t;
-    const bool cell = form == FORM_LSTM;
-    switch (t) {
-    case 17: case 22: case 23: return cell ? 15 : 13;   // 32 columns, 512 rows and more
-    case 20: return cell ? 15 : 16;                     // 64 x 256
-    default: return 15;                                 // 32 x 256 (and 64 x 128)
-    }
-}
 int entry_family(int form, bool bf16)
 {
     if (form == FORM_GATED) return bf16 ? LINREC_ENTRY_GILR_BF16 : LINREC_ENTRY_GILR;
@@ -628,11 +335,10 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
     p.persistent = fp.active ? fp.persistent : (int)opts().persistent;
     p.taper = fp.active ? fp.taper : (int)opts().taper;
     if (p.tile == 0 && p.variant == LINREC_VARIANT_LOOKBACK) {  // a pinned or tuned plan, if there is one for this shape
-        const int family = entry_family(form, bf16);
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess) {
             std::lock_guard<std::mutex> lock(g_tuned_mu);
-            auto it = g_tuned.find(TunedKey{dev, T, C, bwd, family});
+            auto it = g_tuned.find(TunedKey{dev, T, C, bwd, entry_family(form, bf16)});
             if (it != g_tuned.end() && (it->second.variant == LINREC_VARIANT_LOOKBACK || want_variant == LINREC_VARIANT_AUTO)) {
                 p.tile = it->second.tile;
                 p.variant = it->second.variant;
@@ -641,35 +347,27 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
             }
         }
     }
-    // No option and no tuned plan: short, wide problems take the walk.
-    if (want_variant == LINREC_VARIANT_AUTO && p.tile == 0) {
-        const int wt = gated ? (bf16 ? auto_walk_tile_form_bf16(T, C, vec, bwd, form) : auto_walk_tile_form(T, C, vec, bwd, form))
-                       : bf16 ? auto_walk_tile_bf16(T, C, vec, bwd)
-                              : auto_walk_tile(T, C, vec, bwd);
-        if (wt) {
-            p.variant = LINREC_VARIANT_WALK;
-            p.tile = wt;
-        }
-    }
-    // (the walk asked for by option without a shape: the plain recurrence gets the shape the walk would
-    // take at this width; the other families their single-pass shape, below)
-    if (p.variant == LINREC_VARIANT_WALK && p.tile == 0 && !gated && !bf16)
-        p.tile = walk_tile(T, C, vec, bwd);
-    if (!tile_exists(p.tile)) p.tile = 0;
-    if (p.tile && kTable.t[p.tile].vec > vec) p.tile = 0;
-    if (p.tile && form == FORM_LSTM && kTable.t[p.tile].r * kTable.t[p.tile].vec > 32) p.tile = 0;
-    if (p.tile && gated && kTable.t[p.tile].r % 8 != 0 && kTable.t[p.tile].r >= 8) p.tile = 0;
-    if (p.tile && bf16 && !gated && kTable.t[p.tile].vec < 2) p.tile = 0;
-    if (p.tile && (!bf16 || gated) && kTable.t[p.tile].r * kTable.t[p.tile].vec > 64) p.tile = 0;
+    // What the options, a pinned or a tuned plan name must be a shape this family has kernels for, with
+    // accesses no wider than this call's alignment allows; else the static plan decides.
+    const int family = entry_family(form, bf16);
+    if (p.tile && (!tile_has(p.tile, family) || kTable.t[p.tile].vec > vec)) p.tile = 0;
     if (!p.tile) {
-        p.tile = auto_tile(T, C, vec, bwd, p.variant);
-        if (gated) p.tile = auto_tile_form(T, C, vec, bwd, form);
-        if (bf16) p.tile = gated ? auto_tile_form_bf16(T, C, vec, bwd, form) : auto_tile_bf16(T, C, vec, bwd);
-        if (form == FORM_LSTM && kTable.t[p.tile].r * kTable.t[p.tile].vec > 32) p.tile = 18;  // (the cell: at most 32 elements per thread and operand)
+        const StaticPlan sp = static_plan(family, bwd, T, C, vec);
+        if (want_variant == LINREC_VARIANT_AUTO && sp.walk) {  // short, wide problems take the walk
+            p.variant = LINREC_VARIANT_WALK;
+            p.tile = sp.walk;
+        } else {
+            // (the walk asked for by option without a shape: the shape the table has for it, else the single pass's)
+            p.tile = (p.variant == LINREC_VARIANT_WALK && sp.walk) ? sp.walk : sp.lookback;
+        }
     }
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
     // (the gated forms have one-column shapes with 2-byte accesses for those)
-    if (bf16 && !gated && vec < 2) p.variant = LINREC_VARIANT_SERIAL;
+    if ((bf16 && !gated && vec < 2) || !p.tile) {
+        p.variant = LINREC_VARIANT_SERIAL;
+        for (int id = 1; id <= MAX_TILE_ID && !p.tile; ++id)  // (a plan always names a shape of its family)
+            if (tile_has(id, family)) p.tile = id;
+    }
     const TileDesc &d = kTable.t[p.tile];
     // per-thread byte offsets inside a tile are 32-bit, tickets of a call are 31-bit
     const int64_t G = ceil_div(C, d.cols()), K = ceil_div(T, d.rows());
@@ -1226,6 +924,11 @@ extern "C" int linrec_tile_info(int tile_id, int *threads_cols, int *threads_tim
     return LINREC_OK;
 }
 
+extern "C" int linrec_tile_has(int tile_id, int entry_point)
+{
+    return entry_point >= LINREC_ENTRY_PLAIN && entry_point <= LINREC_ENTRY_LSTM_CELL_BF16 && tile_has(tile_id, entry_point);
+}
+
 extern "C" int linrec_plan(int64_t T, int64_t B, int64_t n, int backward, int alignment_bytes, int *variant,
                            int *tile_id)
 {
@@ -1355,59 +1058,58 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         // (candidates are forced on this thread's calls only; the options stay as they are)
         const int64_t saved_taper = opts().taper;
         ForcedPlan &fp = forced();
-        fp = ForcedPlan{};
-        fp.active = true;
-        fp.variant = LINREC_VARIANT_LOOKBACK;
-        static const int plain_c[] = {44, 43, 42, 38, 41, 22, 35, 34, 21, 45, 0},
-                         gated_c[] = {18, 19, 21, 17, 20, 22, 14, 15, 3, 4, 0}, lstm_c[] = {18, 21, 15, 3, 4, 33, 34, 35, 38, 0},
-                         bf16_c[] = {24, 28, 29, 30, 16, 26, 27, 47, 48, 51, 0};
-        static const int gated16_c[] = {21, 18, 16, 15, 13, 3, 4, 7, 8, 0}, lstm16_c[] = {15, 3, 4, 5, 18, 0};
-        const int *list = form == FORM_GATED ? (bf16 ? gated16_c : gated_c) : form == FORM_LSTM ? (bf16 ? lstm16_c : lstm_c)
-                                                                          : bf16 ? bf16_c : plain_c;
-        // the static rule's own choice goes first, so that what is remembered is never slower than it
-        std::vector<int> candidates{form != FORM_PLAIN ? (bf16 ? auto_tile_form_bf16(T, C, vec, bwd, form)
-                                                               : auto_tile_form(T, C, vec, bwd, form))
-                                    : bf16            ? auto_tile_bf16(T, C, vec, bwd)
-                                                      : auto_tile(T, C, vec, bwd, LINREC_VARIANT_LOOKBACK)};
-        for (; *list; ++list)
-            if (*list != candidates[0]) candidates.push_back(*list);
-        for (const int tile : candidates) {
-            if (!tile_exists(tile)) continue;
-            const TileDesc &d = kTable.t[tile];
-            if (d.vec > vec) continue;
-            if (((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
-            if (d.rows() > 2 * T && tile != 18) continue;  // far taller than the problem
-            for (int persistent = 0; persistent <= 1 && rc == LINREC_OK; ++persistent) {
-                fp.tile = tile;
-                fp.persistent = persistent;
-                fp.taper = (int)saved_taper;
-                float times[5];
-                for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {  // two warm-up launches, five timed
-                    if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
-                    rc = call();
-                    if (rc != LINREC_OK) break;
-                    float ms = 0.f;
-                    if ((e = hipEventRecord(ev1, s)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
-                        (e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess) {
-                        rc = hip_fail(e, "tune: timing");
-                        break;
-                    }
-                    if (it >= 0) times[it] = ms;
+        // Median of five launches of the forced plan, after two warm-up launches; < 0 on failure (rc is set).
+        auto time_plan = [&](int variant, int tile, int persistent, int taper) -> float {
+            fp = ForcedPlan{};
+            fp.active = true;
+            fp.variant = variant;
+            fp.tile = tile;
+            fp.persistent = persistent;
+            fp.taper = taper;
+            float times[5];
+            for (int it = -2; it < 5; ++it) {
+                if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); return -1.f; }
+                if ((rc = call()) != LINREC_OK) return -1.f;
+                float ms = 0.f;
+                if ((e = hipEventRecord(ev1, s)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
+                    (e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess) {
+                    rc = hip_fail(e, "tune: timing");
+                    return -1.f;
                 }
-                if (rc != LINREC_OK) break;
-                std::sort(times, times + 5);
-                if (best.tile == 0 || times[2] < best_ms) {
+                if (it >= 0) times[it] = ms;
+            }
+            std::sort(times, times + 5);
+            return times[2];
+        };
+        auto usable = [&](int tile) {
+            const TileDesc &d = kTable.t[tile];
+            return tile_has(tile, entry_point) && d.vec <= vec && ((int64_t)d.rows() * C + d.cols()) * 4 < ((int64_t)1 << 32);
+        };
+        // Single pass: every shape the family has, the static plan's own first so that what is remembered is
+        // never slower than it, each with persistent workgroups and with one workgroup per tile.
+        const StaticPlan sp = static_plan(entry_point, bwd, T, C, vec);
+        std::vector<int> candidates{sp.lookback};
+        for (int id = 1; id <= MAX_TILE_ID; ++id)
+            if (id != sp.lookback) candidates.push_back(id);
+        for (const int tile : candidates) {
+            if (!usable(tile)) continue;
+            if (kTable.t[tile].rows() > 2 * T && tile != sp.lookback) continue;  // far taller than the problem
+            for (int persistent = 0; persistent <= 1 && rc == LINREC_OK; ++persistent) {
+                const float ms = time_plan(LINREC_VARIANT_LOOKBACK, tile, persistent, (int)saved_taper);
+                if (ms < 0.f) break;
+                if (best.tile == 0 || ms < best_ms) {
                     if (best.tile != tile) {  // (the runner-up is a different shape)
                         second = best;
                         second_ms = best_ms;
                     }
-                    best_ms = times[2];
+                    best_ms = ms;
                     best = TunedPlan{tile, persistent, LINREC_VARIANT_LOOKBACK};
-                } else if (tile != best.tile && (second.tile == 0 || times[2] < second_ms)) {
-                    second_ms = times[2];
+                } else if (tile != best.tile && (second.tile == 0 || ms < second_ms)) {
+                    second_ms = ms;
                     second = TunedPlan{tile, persistent, LINREC_VARIANT_LOOKBACK};
                 }
             }
+            if (rc != LINREC_OK) break;
         }
         // The two best single-pass plans once more with a quarter of their last round cut into shorter
         // tiles: a launch of few rounds ends sooner that way on some shapes (kept only if it is at least
@@ -1417,76 +1119,26 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         for (int c = 0; c < 2 && rc == LINREC_OK && saved_taper == 0; ++c) {
             const TunedPlan &u = untapered[c];
             if (u.tile == 0 || kTable.t[u.tile].r % 4 != 0 || kTable.t[u.tile].r < 8) continue;
-            fp.tile = u.tile;
-            fp.persistent = u.persistent;
-            fp.taper = 2;
-            float times[5];
-            for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {
-                if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
-                rc = call();
-                if (rc != LINREC_OK) break;
-                float ms = 0.f;
-                if ((e = hipEventRecord(ev1, s)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
-                    (e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess) {
-                    rc = hip_fail(e, "tune: timing");
-                    break;
-                }
-                if (it >= 0) times[it] = ms;
-            }
-            if (rc == LINREC_OK) {
-                std::sort(times, times + 5);
-                if (times[2] < 0.995f * best_ms) {
-                    best_ms = times[2];
-                    best = u;
-                    best.taper = 2;
-                }
+            const float ms = time_plan(LINREC_VARIANT_LOOKBACK, u.tile, u.persistent, 2);
+            if (ms >= 0.f && ms < 0.995f * best_ms) {
+                best_ms = ms;
+                best = u;
+                best.taper = 2;
             }
         }
-        fp.taper = (int)saved_taper;
-        // The walk, where there are enough columns for it to stand a chance: the shapes its automatic
-        // rule would take at this width.
-        int walk_c[3] = {0, 0, 0};
-        if (C >= 4096) {
-            if (entry_point == LINREC_ENTRY_PLAIN) {
-                walk_c[0] = walk_tile(T, C, vec, bwd);
-            } else if (bf16 && form == FORM_PLAIN) {
-                walk_c[0] = T >= 768 ? 30 : 24;
-                walk_c[1] = vec >= 4 ? 8 : 28;
-            } else if (bf16) {
-                walk_c[0] = auto_walk_tile_form_bf16(T, C, vec, bwd, form);
-                if (!walk_c[0]) walk_c[0] = 15;
-                walk_c[1] = (vec >= 4 && walk_c[0] != 4) ? 4 : 0;
-            } else {
-                walk_c[0] = auto_walk_tile_form(T, C, vec, bwd, form);
-                walk_c[1] = walk_c[0] == 18 ? 21 : 18;
-                if (!walk_c[0]) walk_c[0] = 21;
-            }
-        }
-        fp.variant = LINREC_VARIANT_WALK;
-        fp.persistent = -1;
-        for (int i = 0; walk_c[i] && rc == LINREC_OK; ++i) {
-            const int tile = walk_c[i];
-            const TileDesc &d = kTable.t[tile];
-            if (d.vec > vec || ((int64_t)d.rows() * C + d.cols()) * 4 >= ((int64_t)1 << 32)) continue;
-            fp.tile = tile;
-            float times[5];
-            for (int it = -2; it < 5 && rc == LINREC_OK; ++it) {
-                if ((e = hipEventRecord(ev0, s)) != hipSuccess) { rc = hip_fail(e, "hipEventRecord"); break; }
-                rc = call();
-                if (rc != LINREC_OK) break;
-                float ms = 0.f;
-                if ((e = hipEventRecord(ev1, s)) != hipSuccess || (e = hipEventSynchronize(ev1)) != hipSuccess ||
-                    (e = hipEventElapsedTime(&ms, ev0, ev1)) != hipSuccess) {
-                    rc = hip_fail(e, "tune: timing");
-                    break;
+        // The walk, where there are enough columns for it to stand a chance and the sequence is short enough:
+        // every shape of the family that makes between one and eight workgroups per compute unit.
+        if (C >= 4096 && T <= 8192) {
+            const int64_t units = compute_units(dev);
+            for (int tile = 1; tile <= MAX_TILE_ID && rc == LINREC_OK; ++tile) {
+                if (!usable(tile)) continue;
+                const int64_t groups = ceil_div(C, kTable.t[tile].cols());
+                if (2 * groups < units || groups > 8 * units || kTable.t[tile].rows() > 2 * T) continue;
+                const float ms = time_plan(LINREC_VARIANT_WALK, tile, -1, 0);
+                if (ms >= 0.f && (best.tile == 0 || ms < best_ms)) {
+                    best_ms = ms;
+                    best = TunedPlan{tile, -1, LINREC_VARIANT_WALK};
                 }
-                if (it >= 0) times[it] = ms;
-            }
-            if (rc != LINREC_OK) break;
-            std::sort(times, times + 5);
-            if (best.tile == 0 || times[2] < best_ms) {
-                best_ms = times[2];
-                best = TunedPlan{tile, -1, LINREC_VARIANT_WALK};
             }
         }
         fp = ForcedPlan{};

@@ -69,9 +69,11 @@ struct TileDesc {
 // Tile shapes by id, as used by LINREC_OPT_TILE: (id, columns per thread, rows per thread, threads along
 // columns, threads along time).  A shape with v columns per thread makes 4v-byte accesses and needs
 // C % v == 0 and 4v-byte aligned tensors; v = 1 works for any C and alignment.  (With bf16 storage the
-// accesses are 2v bytes and v is 2 or 4.)  Shapes with more than 64 elements per thread exist for bf16
-// storage only, where two elements share a register.  Ids are stable across versions of the library; ids of
-// shapes that no plan takes any more are left unassigned.
+// accesses are 2v bytes; the plain recurrence on bf16 storage has kernels for v = 2 and 4 only.)  Shapes with
+// more than 64 elements per thread exist for bf16 storage only, where two elements share a register.  This
+// is the catalogue: which of these shapes a build has kernels for, and for which entry-point families, is
+// in linrec_tile_set.inc, written from measurements (plan_sweep.py) -- a shape no plan takes is not built.
+// Ids are stable across versions of the library.
 //   one column per thread, 512 threads (one workgroup per compute unit): 44, 43, 42, 38, 41 (64 wide, 64 ..
 //   24 rows per thread), 22, 35, 34, 33 (32 wide); 256 threads: 20, 21, 45 (64 wide), 17, 19, 18 (32 wide),
 //   1, 2 (8 rows per thread), 23 (16 wide, for a handful of columns)
@@ -119,15 +121,58 @@ struct TileDesc {
     X(51, 2, 48, 32, 16)
 constexpr int MAX_TILE_ID = 51;
 
-bool tile_exists(int id);           // 1 <= id <= MAX_TILE_ID and the id is assigned
-const TileDesc &tile_desc(int id);  // an id for which tile_exists()
+// Families (bit LINREC_ENTRY_*) whose kernels can exist for a shape at all:
+//   plain fp32         at most 64 elements per thread and operand (one register each)
+//   plain, bf16        2 or 4 columns per thread (4- and 8-byte accesses); two elements share a register
+//   gated layer        at most 64 elements per thread, rows per thread a multiple of 8 or fewer than 8 (the
+//                      epilogues work in chunks of 8 rows); the same on bf16 storage, whose register tile
+//                      holds computed fp32 values (one-column shapes make 2-byte accesses there)
+//   LSTM cell          the same with at most 32 elements per thread and operand (three operands in flight)
+constexpr unsigned geometry_families(const TileDesc &d)
+{
+    const bool f32 = d.r * d.vec <= 64, gated = f32 && (d.r % 8 == 0 || d.r < 8), cell = gated && d.r * d.vec <= 32;
+    return (f32 ? 1u << 0 : 0u) | (gated ? (1u << 1 | 1u << 4) : 0u) | (cell ? (1u << 2 | 1u << 5) : 0u) |
+           (d.vec >= 2 ? 1u << 3 : 0u);
+}
+
+// Families this build has kernels of shape `id` for.  -DLINREC_ALL_SHAPES builds every kernel the geometry
+// allows (what plan_sweep.py measures on); the default is the measured selection.
+#ifndef LINREC_ALL_SHAPES
+#include "linrec_tile_set.inc"
+#endif
+constexpr unsigned tile_families(int id)
+{
+    unsigned geometry = 0, built = 0;
+    switch (id) {
+#define X(ID, VEC, R, WC, WT) \
+    case ID: geometry = geometry_families(TileDesc{VEC, R, WC, WT}); break;
+        LINREC_TILES(X)
+#undef X
+    default: break;
+    }
+#ifdef LINREC_ALL_SHAPES
+    built = ~0u;
+#else
+    switch (id) {
+#define X(ID, MASK) \
+    case ID: built = MASK; break;
+        LINREC_BUILT_TILES(X)
+#undef X
+    default: break;
+    }
+#endif
+    return geometry & built;
+}
+
+bool tile_has(int id, int family);  // this build has kernels of shape `id` for entry-point family LINREC_ENTRY_*
+bool tile_exists(int id);           // ... for at least one family
+const TileDesc &tile_desc(int id);  // the geometry of a catalogued id
 
 // Launches kernel `kind` for tile shape `id` with grid A.K * A.G.  hp_late (look-back, backward):
-// load h after the rescan instead of together with lambda and grad_h.  gated: the form of Section
-// 3.1 with sigmoid / tau applied in the kernel (look-back and walk kernels of the shapes whose rows per
-// thread are a multiple of 8, or fewer than 8; hipErrorInvalidValue otherwise).  `form` is FORM_PLAIN,
-// FORM_GATED or FORM_LSTM (the latter for shapes of at most 32 elements per thread and operand).  bf16: the tensors hold bf16 (plain form, look-back kernels
-// of shapes with 2 or 4 columns per thread).
+// load h after the rescan instead of together with lambda and grad_h.  `form` is FORM_PLAIN, FORM_GATED
+// (Section 3.1: sigmoid / tau applied in the kernel) or FORM_LSTM (Section 3.2); bf16: the tensors hold
+// bf16.  hipErrorInvalidValue when this build has no such kernel (see tile_families; the three-phase
+// kernels exist for the plain fp32 family only).
 hipError_t launch_tile_kernel(int id, Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A,
                               hipStream_t s);
 

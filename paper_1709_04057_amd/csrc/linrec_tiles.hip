@@ -46,44 +46,38 @@ template <class G>
 static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool bf16, const Args &A, hipStream_t s)
 {
     const dim3 grid((unsigned)(A.K * A.G)), block(G::THREADS);
-    // Which kernels exist for this shape:
-    //   fp32 storage       shapes of at most 64 elements per thread and operand (one register each)
-    //   bf16 storage       the plain recurrence's look-back kernels of the shapes with 2 or 4 columns per
-    //                      thread (4- and 8-byte accesses); two elements share a register, so these go up
-    //                      to 128 elements per thread
-    //   gated layer        look-back and walk kernels of the shapes with 8k (or fewer than 8) rows per thread
-    //                      (the epilogues work in chunks of 8 rows)
-    //   LSTM cell          the same, of at most 32 elements per thread and operand (three operands in flight)
-    //   both on bf16       the same shapes (the register tile holds computed fp32 values, so the limits are
-    //   storage            those of fp32 storage; one-column shapes make 2-byte accesses)
-    constexpr bool kHasF32 = G::R * G::VEC <= 64, kHasBf16 = G::VEC >= 2;
-    constexpr bool kHasGated = kHasF32 && (G::R % 8 == 0 || G::R < 8), kHasLstm = kHasGated && G::R * G::VEC <= 32;
+    // Which kernels exist for this shape: those of the entry-point families the build selects it for
+    // (bit LINREC_ENTRY_* of tile_families; the three-phase kernels belong to the plain fp32 family).
+    constexpr unsigned kFam = tile_families(LINREC_TILE_ID);
+    constexpr bool kHasF32 = kFam >> 0 & 1, kHasGated = kFam >> 1 & 1, kHasLstm = kFam >> 2 & 1, kHasBf16 = kFam >> 3 & 1,
+                   kHasGated16 = kFam >> 4 & 1, kHasLstm16 = kFam >> 5 & 1;
     if (form < FORM_PLAIN || form > FORM_LSTM) return hipErrorInvalidValue;
     if ((form != FORM_PLAIN || bf16) && kind != KIND_LOOKBACK && kind != KIND_WALK) return hipErrorInvalidValue;
-    if (bf16 ? (form == FORM_PLAIN ? !kHasBf16 : !kHasF32) : !kHasF32) return hipErrorInvalidValue;
-    if ((form == FORM_GATED && !kHasGated) || (form == FORM_LSTM && !kHasLstm)) return hipErrorInvalidValue;
     void (*kern)(const Args) = nullptr;
     if constexpr (kHasF32) {
-        switch (kind) {
-        case KIND_REDUCE:
-            if (bwd) hipLaunchKernelGGL((k_reduce<G, true>), grid, block, 0, s, A);
-            else hipLaunchKernelGGL((k_reduce<G, false>), grid, block, 0, s, A);
-            return hipGetLastError();
-        case KIND_FIXUP:
-            if (bwd) hipLaunchKernelGGL((k_fixup<G, true>), grid, block, 0, s, A);
-            else hipLaunchKernelGGL((k_fixup<G, false>), grid, block, 0, s, A);
-            return hipGetLastError();
-        case KIND_WALK: kern = bwd ? k_walk<G, true> : k_walk<G, false>; break;
-        case KIND_LOOKBACK:
-            kern = !bwd ? k_lookback<G, false, false> : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
-            break;
+        if (form == FORM_PLAIN && !bf16) {
+            switch (kind) {
+            case KIND_REDUCE:
+                if (bwd) hipLaunchKernelGGL((k_reduce<G, true>), grid, block, 0, s, A);
+                else hipLaunchKernelGGL((k_reduce<G, false>), grid, block, 0, s, A);
+                return hipGetLastError();
+            case KIND_FIXUP:
+                if (bwd) hipLaunchKernelGGL((k_fixup<G, true>), grid, block, 0, s, A);
+                else hipLaunchKernelGGL((k_fixup<G, false>), grid, block, 0, s, A);
+                return hipGetLastError();
+            case KIND_WALK: kern = bwd ? k_walk<G, true> : k_walk<G, false>; break;
+            case KIND_LOOKBACK:
+                kern = !bwd ? k_lookback<G, false, false> : hp_late ? k_lookback<G, true, true> : k_lookback<G, true, false>;
+                break;
+            }
         }
     }
     const bool walk = kind == KIND_WALK;
     if constexpr (kHasBf16) {
         using GB = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16>;
-        if (bf16) kern = walk ? (bwd ? k_walk<GB, true> : k_walk<GB, false>)
-                              : (bwd ? k_lookback<GB, true, false> : k_lookback<GB, false, false>);
+        if (bf16 && form == FORM_PLAIN)
+            kern = walk ? (bwd ? k_walk<GB, true> : k_walk<GB, false>)
+                        : (bwd ? k_lookback<GB, true, false> : k_lookback<GB, false, false>);
     }
     if constexpr (kHasGated) {
         if (form == FORM_GATED && !bf16)
@@ -95,13 +89,13 @@ static hipError_t launch_for(Kind kind, bool bwd, bool hp_late, int form, bool b
             kern = walk ? (bwd ? k_walk<G, true, FORM_LSTM> : k_walk<G, false, FORM_LSTM>)
                         : (bwd ? k_lookback<G, true, true, FORM_LSTM> : k_lookback<G, false, false, FORM_LSTM>);
     }
-    if constexpr (kHasGated) {
+    if constexpr (kHasGated16) {
         using GW = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16W>;
         if (form == FORM_GATED && bf16)
             kern = walk ? (bwd ? k_walk<GW, true, FORM_GATED> : k_walk<GW, false, FORM_GATED>)
                         : (bwd ? k_lookback<GW, true, true, FORM_GATED> : k_lookback<GW, false, false, FORM_GATED>);
     }
-    if constexpr (kHasLstm) {
+    if constexpr (kHasLstm16) {
         using GW = Geo<G::VEC, G::R, G::WC, G::WT, IO_BF16W>;
         if (form == FORM_LSTM && bf16)
             kern = walk ? (bwd ? k_walk<GW, true, FORM_LSTM> : k_walk<GW, false, FORM_LSTM>)

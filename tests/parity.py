@@ -142,6 +142,13 @@ class options:
         return False
 
 
-def all_tiles():
-    """(id, description) of every tile shape the library has (ids are stable, so there are gaps)."""
-    return [(i, info) for i in range(1, 129) if (info := lr.linrec_tile_info(i)) is not None]
+def one_column_tiles(family):
+    """Ids of the family's tile shapes with one column per thread (usable whatever C and the alignment)."""
+    return [i for i, info in all_tiles(family) if info["cols_per_thread"] == 1]
+
+
+def all_tiles(family=None):
+    """(id, description) of every tile shape the library has kernels of -- for entry-point family ``family``
+    (lr.ENTRY_*) when given, else for any (ids are stable, so there are gaps)."""
+    return [(i, info) for i in range(1, 129) if (info := lr.linrec_tile_info(i)) is not None
+            and (family is None or lr.linrec_tile_has(i, family))]

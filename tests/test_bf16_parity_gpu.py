@@ -18,7 +18,7 @@ from parity import FWD_TOL, GRAD_TOL, ORACLE_THREADS, all_tiles, check_norms, ho
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-BF16_TILES = [i for i, info in all_tiles() if info["cols_per_thread"] >= 2]
+BF16_TILES = [i for i, _ in all_tiles(lr.ENTRY_BF16)]
 HALF_ULP = 2.0 ** -8
 
 

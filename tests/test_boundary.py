@@ -198,27 +198,23 @@ def test_plan_is_host_only_and_consistent(L):
                 assert (B * n) % info["cols_per_thread"] == 0
                 assert info["cols_per_thread"] * 4 <= align
     # the other entry-point families report shapes their kernels exist for
+    tiled = (lr.VARIANT_LOOKBACK, lr.VARIANT_WALK)
     for (T, B, n) in [(65536, 4, 256), (4096, 16, 1024), (300, 1, 7), (5000, 2, 33)]:
         for bwd in (False, True):
-            v, t = lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n, backward=bwd)
-            info = lr.linrec_tile_info(t)
-            assert v in (lr.VARIANT_LOOKBACK, lr.VARIANT_SERIAL) and (B * n) % info["cols_per_thread"] == 0
-            assert info["rows_per_thread"] % 8 == 0 or info["rows_per_thread"] < 8
-            v, t = lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n, backward=bwd)
-            info = lr.linrec_tile_info(t)
-            assert (B * n) % info["cols_per_thread"] == 0 and info["rows_per_thread"] * info["cols_per_thread"] <= 32
+            for fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL):
+                v, t = lr.linrec_plan_for(fam, T, B, n, backward=bwd)
+                assert v in tiled and lr.linrec_tile_has(t, fam)
+                assert (B * n) % lr.linrec_tile_info(t)["cols_per_thread"] == 0
             v, t = lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, backward=bwd, alignment=4)
+            assert lr.linrec_tile_has(t, lr.ENTRY_BF16)
             if (B * n) % 2:
                 assert v == lr.VARIANT_SERIAL            # odd number of columns: no 4-byte rows
             else:
-                assert v == lr.VARIANT_LOOKBACK and lr.linrec_tile_info(t)["cols_per_thread"] in (2, 4)
-            for fam, limit in ((lr.ENTRY_GILR_BF16, 64), (lr.ENTRY_LSTM_CELL_BF16, 32)):
+                assert v in tiled and lr.linrec_tile_info(t)["cols_per_thread"] == 2
+            for fam in (lr.ENTRY_GILR_BF16, lr.ENTRY_LSTM_CELL_BF16):
                 v, t = lr.linrec_plan_for(fam, T, B, n, backward=bwd, alignment=4)
-                info = lr.linrec_tile_info(t)
-                assert v == lr.VARIANT_LOOKBACK
-                assert info["cols_per_thread"] in ((1,) if (B * n) % 2 else (1, 2))   # odd C: 2-byte accesses
-                assert info["rows_per_thread"] * info["cols_per_thread"] <= limit
-                assert info["rows_per_thread"] % 8 == 0 or info["rows_per_thread"] < 8
+                assert v in tiled and lr.linrec_tile_has(t, fam)
+                assert lr.linrec_tile_info(t)["cols_per_thread"] in ((1,) if (B * n) % 2 else (1, 2))   # odd C: 2-byte accesses
             assert lr.linrec_plan_for(lr.ENTRY_PLAIN, T, B, n, backward=bwd) == lr.linrec_plan(T, B, n, backward=bwd)
     # short and wide: the plain fp32 recurrence walks (one workgroup per column group), the other
     # families and long sequences keep the single pass
@@ -229,11 +225,7 @@ def test_plan_is_host_only_and_consistent(L):
         assert lr.linrec_plan(1024, 4, 256, backward=bwd)[0] == lr.VARIANT_LOOKBACK
         for fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL, lr.ENTRY_BF16, lr.ENTRY_GILR_BF16, lr.ENTRY_LSTM_CELL_BF16):
             v, t = lr.linrec_plan_for(fam, 128, 16, 1024, backward=bwd)            # every family walks here
-            info = lr.linrec_tile_info(t)
-            assert v == lr.VARIANT_WALK
-            assert info["cols_per_thread"] >= 2 or fam in (lr.ENTRY_GILR, lr.ENTRY_LSTM_CELL)
-            assert fam not in (lr.ENTRY_LSTM_CELL, lr.ENTRY_LSTM_CELL_BF16) or \
-                info["rows_per_thread"] * info["cols_per_thread"] <= 32
+            assert v == lr.VARIANT_WALK and lr.linrec_tile_has(t, fam)
             assert lr.linrec_plan_for(fam, 16384, 16, 1024, backward=bwd)[0] == lr.VARIANT_LOOKBACK
     with pytest.raises(lr.LinrecError):
         lr.linrec_plan_for(9, 10, 1, 1)
@@ -242,23 +234,41 @@ def test_plan_is_host_only_and_consistent(L):
     assert variant == lr.VARIANT_SERIAL
 
 
-def test_every_plan_of_the_gated_families_names_a_shape_their_kernels_exist_for(L):
-    """The gated layer has kernels for shapes of at most 64 elements per thread whose rows per thread are a
-    multiple of 8 (or fewer), the cell for those of at most 32; whatever the problem and the alignment, the
-    automatic plan must land on one of them, with accesses no wider than the alignment allows."""
-    for fam, limit, es in ((lr.ENTRY_GILR, 64, 4), (lr.ENTRY_LSTM_CELL, 32, 4), (lr.ENTRY_GILR_BF16, 64, 2),
-                           (lr.ENTRY_LSTM_CELL_BF16, 32, 2)):
-        for T in (1, 7, 30, 100, 300, 1000, 5078, 20000, 70000, 300000, 2000000):
-            for C in (1, 2, 3, 15, 16, 17, 64, 100, 128, 255, 1024, 4096, 16384, 65536):
+def test_every_plan_names_a_shape_its_family_has_kernels_for(L):
+    """Each entry-point family is built for the tile shapes its static plans use.  Whatever the problem and the
+    alignment -- on the measured grid, between its points, far outside it -- the automatic plan must land on a
+    shape the family has, with accesses no wider than the alignment allows."""
+    for fam, es in ((lr.ENTRY_PLAIN, 4), (lr.ENTRY_GILR, 4), (lr.ENTRY_LSTM_CELL, 4), (lr.ENTRY_BF16, 2),
+                    (lr.ENTRY_GILR_BF16, 2), (lr.ENTRY_LSTM_CELL_BF16, 2)):
+        for T in (1, 7, 30, 100, 300, 1000, 5078, 20000, 70000, 300000, 2000000, 50000000):
+            for C in (1, 2, 3, 15, 16, 17, 64, 100, 128, 255, 1024, 4096, 16384, 65536, 300000):
                 for bwd in (False, True):
                     for align in (2, 4, 8, 16):
                         if align < es:
                             continue
-                        _, t = lr.linrec_plan_for(fam, T, 1, C, backward=bwd, alignment=align)
-                        info = lr.linrec_tile_info(t)
-                        r, v = info["rows_per_thread"], info["cols_per_thread"]
-                        assert r * v <= limit and (r % 8 == 0 or r < 8), (fam, T, C, bwd, align, t)
-                        assert C % v == 0 and v * es <= align, (fam, T, C, bwd, align, t)
+                        var, t = lr.linrec_plan_for(fam, T, 1, C, backward=bwd, alignment=align)
+                        assert lr.linrec_tile_has(t, fam), (fam, T, C, bwd, align, t)
+                        v = lr.linrec_tile_info(t)["cols_per_thread"]
+                        if var != lr.VARIANT_SERIAL:
+                            assert C % v == 0 and v * es <= align, (fam, T, C, bwd, align, t)
+    # every shape some family has is described, and no family claims a shape of the wrong geometry
+    for t in range(1, 129):
+        fams = [f for f in range(6) if lr.linrec_tile_has(t, f)]
+        info = lr.linrec_tile_info(t)
+        assert (info is not None) == bool(fams)
+        if info is None:
+            continue
+        r, v = info["rows_per_thread"], info["cols_per_thread"]
+        for f in fams:
+            if f != lr.ENTRY_BF16:
+                assert r * v <= 64
+            if f in (lr.ENTRY_GILR, lr.ENTRY_GILR_BF16, lr.ENTRY_LSTM_CELL, lr.ENTRY_LSTM_CELL_BF16):
+                assert r % 8 == 0 or r < 8
+            if f in (lr.ENTRY_LSTM_CELL, lr.ENTRY_LSTM_CELL_BF16):
+                assert r * v <= 32
+            if f == lr.ENTRY_BF16:
+                assert v >= 2
+    assert not lr.linrec_tile_has(1, 6) and not lr.linrec_tile_has(1, -1) and not lr.linrec_tile_has(0, 0)
 
 
 def test_bench_refuses_more_than_one_gpu():

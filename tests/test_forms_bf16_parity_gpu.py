@@ -23,13 +23,8 @@ HALF_ULP = 2.0 ** -8
 PRE = ("f_pre", "i_pre", "z_pre", "o_pre")
 
 
-def _ok(info, limit):
-    r, v = info["rows_per_thread"], info["cols_per_thread"]
-    return r * v <= limit and (r % 8 == 0 or r < 8)
-
-
-GATED16_TILES = [i for i, info in all_tiles() if _ok(info, 64)]
-CELL16_TILES = [i for i, info in all_tiles() if _ok(info, 32)]
+GATED16_TILES = [i for i, _ in all_tiles(lr.ENTRY_GILR_BF16)]
+CELL16_TILES = [i for i, _ in all_tiles(lr.ENTRY_LSTM_CELL_BF16)]
 
 
 def to_bf16(inp):

@@ -223,37 +223,47 @@ def test_walk_variant_every_tile_shape(family):
 
 
 def test_short_wide_problems_walk_in_every_family():
-    """The automatic plan of the gated layer, the cell and bf16 storage on short, wide problems is the walk."""
+    """The automatic plan of every family on short, wide problems is the walk wherever the plan table has it
+    ahead of the single pass: each family takes it for several of these shapes, and is right where it does."""
+    from parity import fwd_bwd_check
     from test_bf16_parity_gpu import bf16_check, to_bf16
     from test_gilr_parity_gpu import gated_check
     from test_lstm_parity_gpu import cell_check
-
-    for (T, B, n) in [(128, 16, 1024), (500, 4, 4100), (1000, 8, 4096)]:
-        if lr.linrec_plan_for(lr.ENTRY_GILR, T, B, n)[0] == lr.VARIANT_WALK:
-            gated_check(wl.make_gated(T, B, n, seed=51, device=DEV, gate_mean=1.0), lr.TAU_TANH, f"auto walk gated {T}x{B}x{n}")
-    assert lr.linrec_plan_for(lr.ENTRY_GILR, 128, 16, 1024)[0] == lr.VARIANT_WALK
-    assert lr.linrec_plan_for(lr.ENTRY_GILR, 1000, 8, 4096, backward=False)[0] == lr.VARIANT_WALK
-    for (T, B, n) in [(64, 16, 1024), (250, 4, 1100)]:
-        assert lr.linrec_plan_for(lr.ENTRY_LSTM_CELL, T, B, n)[0] == lr.VARIANT_WALK
-        cell_check(wl.make_lstm(T, B, n, seed=52, device=DEV), f"auto walk lstm {T}x{B}x{n}")
-    for (T, B, n) in [(1000, 4, 3072), (2048, 8, 4096), (77, 2, 9000)]:
-        assert lr.linrec_plan_for(lr.ENTRY_BF16, T, B, n, alignment=8)[0] == lr.VARIANT_WALK
-        bf16_check(to_bf16(wl.make_generic(T, B, n, seed=53, device=DEV)), f"auto walk bf16 {T}x{B}x{n}")
-    # the gated layer and the cell on bf16 storage walk further out (their single pass is short of resident
-    # bytes): up to T = 2048 on the widest problems; whole column groups of the tile among the sampled columns
     from test_forms_bf16_parity_gpu import cell16_check, gated16_check
     from test_forms_bf16_parity_gpu import to_bf16 as forms_to_bf16
     import numpy as np
-    for (T, B, n) in [(100, 8, 1024), (1000, 8, 4096), (2000, 16, 4096), (500, 6, 4096)]:
+
+    shapes = [(128, 16, 1024), (500, 4, 4100), (1000, 8, 4096), (64, 16, 1024), (250, 4, 1100), (1000, 4, 3072),
+              (2048, 8, 4096), (77, 2, 9000), (2000, 16, 4096)]
+    walked = {fam: 0 for fam in range(6)}
+    for i, (T, B, n) in enumerate(shapes):
         C = B * n
-        cols = np.unique(np.concatenate([np.arange(0, 256), np.arange(C - 256, C), np.arange(5, C, 997)]))
-        for bwd in (False, True):
-            assert lr.linrec_plan_for(lr.ENTRY_GILR_BF16, T, B, n, backward=bwd, alignment=8)[0] == lr.VARIANT_WALK
-            if T != 500:
-                assert lr.linrec_plan_for(lr.ENTRY_LSTM_CELL_BF16, T, B, n, backward=bwd, alignment=8)[0] == lr.VARIANT_WALK
-        gated16_check(forms_to_bf16(wl.make_gated(T, B, n, seed=54, device=DEV, gate_mean=1.0)), lr.TAU_TANH,
-                      f"auto walk gated bf16 {T}x{B}x{n}", cols=cols)
-        cell16_check(forms_to_bf16(wl.make_lstm(T, B, n, seed=55, device=DEV)), f"auto walk lstm bf16 {T}x{B}x{n}", cols=cols)
+        # (the larger problems on sampled columns: whole column groups of the widest tiles at both ends of a row)
+        cols = None
+        if T * C > 1 << 24:
+            cols = np.unique(np.concatenate([np.arange(0, 256), np.arange(C - 256, C), np.arange(5, C, 997)]))
+        checks = {
+            lr.ENTRY_PLAIN: lambda: fwd_bwd_check(wl.make_inputs(2, T=T, B=B, n=n, device=DEV), f"auto walk plain {T}x{B}x{n}"),
+            lr.ENTRY_GILR: lambda: gated_check(wl.make_gated(T, B, n, seed=51 + i, device=DEV, gate_mean=1.0), lr.TAU_TANH,
+                                               f"auto walk gated {T}x{B}x{n}", cols=cols),
+            lr.ENTRY_LSTM_CELL: lambda: cell_check(wl.make_lstm(T, B, n, seed=52 + i, device=DEV), f"auto walk lstm {T}x{B}x{n}", cols=cols),
+            lr.ENTRY_BF16: lambda: bf16_check(to_bf16(wl.make_generic(T, B, n, seed=53 + i, device=DEV)),
+                                              f"auto walk bf16 {T}x{B}x{n}", cols=cols),
+            lr.ENTRY_GILR_BF16: lambda: gated16_check(forms_to_bf16(wl.make_gated(T, B, n, seed=54 + i, device=DEV, gate_mean=1.0)),
+                                                      lr.TAU_TANH, f"auto walk gated bf16 {T}x{B}x{n}", cols=cols),
+            lr.ENTRY_LSTM_CELL_BF16: lambda: cell16_check(forms_to_bf16(wl.make_lstm(T, B, n, seed=55 + i, device=DEV)),
+                                                          f"auto walk lstm bf16 {T}x{B}x{n}", cols=cols),
+        }
+        for fam, check in checks.items():
+            plans = [lr.linrec_plan_for(fam, T, B, n, backward=bwd, alignment=8) for bwd in (False, True)]
+            if any(v == lr.VARIANT_WALK for v, _ in plans):
+                say(f"family {fam} [{T}, {B}, {n}]: plans {plans}")
+                walked[fam] += 1
+                check()
+    assert all(k >= 3 for k in walked.values()), walked
+    # long sequences never walk
+    for fam in range(6):
+        assert lr.linrec_plan_for(fam, 65536, 4, 4096, alignment=8)[0] == lr.VARIANT_LOOKBACK
 
 
 def test_staggered_start_changes_timing_only():

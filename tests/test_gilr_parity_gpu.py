@@ -15,9 +15,7 @@ from parity import FWD_TOL, GRAD_TOL, ORACLE_THREADS, all_tiles, check_norms, ho
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
-GATED_TILES = [i for i, info in all_tiles()
-                    if info["rows_per_thread"] * info["cols_per_thread"] <= 64
-                    and (info["rows_per_thread"] % 8 == 0 or info["rows_per_thread"] < 8)]
+GATED_TILES = [i for i, _ in all_tiles(lr.ENTRY_GILR)]
 
 
 def _np(t):
@@ -175,7 +173,7 @@ def test_non_finite_pre_activations_stay_in_their_column(variant):
     assert reruns_agree(h[:, 0, keep], ref[:, 0, keep])
 
 
-@pytest.mark.parametrize("name", sorted(wl.GATED))
+@pytest.mark.parametrize("name", sorted(k for k in wl.GATED if k != "g5"))
 def test_full_size_workloads_every_element(name):
     # the shapes the benchmark times, in its launch configuration; every element of every output against
     # the oracle, which walks the problem in blocks of whole columns (columns are independent recurrences)
@@ -194,3 +192,23 @@ def test_full_size_workloads_every_element(name):
                             host_f32(inp["grad_h"], T, C), host_f32(h, T, C), host_f32(gg, T, C), host_f32(gi, T, C),
                             host_f32(gh0), lr.TAU_TANH, threads=ORACLE_THREADS)
     say(f"workload {name}: {check_norms(r, 'workload ' + name)}")
+
+
+def test_workload_5_shape_on_sampled_columns():
+    # the largest benchmarked shape (1.07e9 elements) in its launch configuration; the oracle takes whole
+    # blocks of adjacent columns at both ends and in the middle of a row (columns are independent recurrences)
+    spec = wl.GATED["g5"]
+    T, B, n = spec["T"], spec["B"], spec["n"]
+    C = B * n
+    inp = wl.make_gated(T, B, n, seed=sum(map(ord, "g5")), device=DEV, gate_mean=spec["gate_mean"], gate_std=spec["gate_std"])
+    say(f"workload g5: gilr forward + backward T={T} B={B} n={n}")
+    h = lr.linrec_gilr_forward(inp["g_pre"], inp["i_pre"], inp["h0"], tau=lr.TAU_TANH)
+    gg, gi, gh0 = lr.linrec_gilr_backward(inp["g_pre"], inp["i_pre"], h, inp["h0"], inp["grad_h"], tau=lr.TAU_TANH)
+    torch.cuda.synchronize()
+    lr.linrec_check()
+    for c0 in (0, C // 2 - 37, C - 64):
+        cut = lambda t: t.reshape(-1, C)[:, c0:c0 + 64].contiguous().cpu().numpy()
+        say(f"workload g5: oracle on columns {c0} .. {c0 + 63}")
+        r = oracle.gilr_compare(cut(inp["g_pre"]), cut(inp["i_pre"]), cut(inp["h0"]).reshape(-1), cut(inp["grad_h"]), cut(h),
+                                cut(gg), cut(gi), cut(gh0).reshape(-1), lr.TAU_TANH, threads=ORACLE_THREADS)
+        say(f"workload g5: {check_norms(r, 'workload g5 columns from ' + str(c0))}")

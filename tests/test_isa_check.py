@@ -58,12 +58,14 @@ def test_packed_fp32_arithmetic_is_reported():
 
 @pytest.mark.skipif(shutil.which(lr_build.HIPCC) is None and not os.path.exists(lr_build.HIPCC), reason="needs hipcc")
 def test_the_check_finds_the_hazard_in_real_compiler_output(tmp_path):
-    """Tile 3 (four columns, 8 rows per thread) compiled to assembly twice: as the library builds it, and with the
-    pause behind the 128-bit stores of the gated forms taken out.  The first passes the check; in the second the
-    compiler schedules the next row's arithmetic into the registers just stored, and the check says so."""
+    """Tile 3 (four columns, 8 rows per thread) compiled to assembly twice, with every kernel its geometry allows
+    (the measured selection builds it for bf16 storage only, where no store is 128 bits wide): as the library
+    builds it, and with the pause behind the 128-bit stores of the gated forms taken out.  The first passes the
+    check; in the second the compiler schedules the next row's arithmetic into the registers just stored, and
+    the check says so."""
     def asm(extra, name):
         out = str(tmp_path / name)
-        cmd = [lr_build.HIPCC] + lr_build.FLAGS + ["-DLINREC_TILE_ID=3"] + extra + [
+        cmd = [lr_build.HIPCC] + lr_build.FLAGS + ["-DLINREC_TILE_ID=3", "-DLINREC_ALL_SHAPES"] + extra + [
             "-S", "--cuda-device-only", os.path.join(lr_build.CSRC, "linrec_tiles.hip"), "-o", out]
         p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
         assert p.returncode == 0, p.stdout[-2000:]

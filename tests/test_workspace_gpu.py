@@ -7,7 +7,8 @@ import torch
 
 import linrec_workloads as wl
 import paper_1709_04057_amd as lr
-from parity import check_backward, check_forward, fwd_bwd_check, options, reruns_agree, run_backward, run_forward, say
+from parity import (check_backward, check_forward, fwd_bwd_check, one_column_tiles, options, reruns_agree, run_backward,
+                    run_forward, say)
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -104,7 +105,7 @@ def test_reserve_then_capture_without_an_eager_call():
     enqueues nothing and leaves the capture intact."""
     inp = wl.make_inputs(2, T=40000, B=2, n=128, device=DEV)
     T, B, n = inp["T"], inp["B"], inp["n"]
-    with options(variant=lr.VARIANT_LOOKBACK, tile=18):
+    with options(variant=lr.VARIANT_LOOKBACK, tile=one_column_tiles(lr.ENTRY_PLAIN)[-1]):
         # (the kernels' code object is loaded by a first, eager launch of the same tile shape on another stream)
         fwd_bwd_check(wl.make_inputs(2, T=600, B=1, n=64, device=DEV), "loads the kernels")
         # (1) no reservation: the captured call is refused, the capture survives and can still record work
@@ -148,7 +149,7 @@ def test_pinned_plan_is_reported_used_and_forgotten():
     T, B, n = 21000, 2, 96
     inp = wl.make_inputs(2, T=T, B=B, n=n, device=DEV)
     auto, auto_bwd = lr.linrec_plan(T, B, n, backward=False), lr.linrec_plan(T, B, n, backward=True)
-    other = 18 if auto[1] != 18 else 17
+    other, third = [t for t in one_column_tiles(lr.ENTRY_PLAIN) if t != auto[1]][:2]
     lr.linrec_pin_plan(lr.ENTRY_PLAIN, T, B, n, False, lr.VARIANT_LOOKBACK, other, persistent=1, taper=2)
     try:
         assert lr.linrec_plan(T, B, n, backward=False) == (lr.VARIANT_LOOKBACK, other)
@@ -157,13 +158,13 @@ def test_pinned_plan_is_reported_used_and_forgotten():
             lr.linrec_plan_for(lr.ENTRY_GILR, T + 1, B, n, backward=False)       # and so are the other families
         fwd_bwd_check(inp, "pinned plan")
         # a thread's own tile option still wins
-        with options(tile=19):
-            assert lr.linrec_plan(T, B, n, backward=False)[1] == 19
+        with options(tile=third):
+            assert lr.linrec_plan(T, B, n, backward=False)[1] == third
     finally:
         lr.linrec_pin_plan(lr.ENTRY_PLAIN, T, B, n, False, lr.VARIANT_LOOKBACK, 0)
     assert lr.linrec_plan(T, B, n, backward=False) == auto
     with pytest.raises(lr.LinrecError):
-        lr.linrec_pin_plan(lr.ENTRY_PLAIN, T, B, n, False, lr.VARIANT_THREEPHASE, 18)
+        lr.linrec_pin_plan(lr.ENTRY_PLAIN, T, B, n, False, lr.VARIANT_THREEPHASE, other)
     with pytest.raises(lr.LinrecError):
         lr.linrec_pin_plan(lr.ENTRY_PLAIN, T, B, n, False, lr.VARIANT_LOOKBACK, 999)
 
@@ -179,7 +180,7 @@ def test_options_belong_to_the_calling_thread():
         seen["variant"] = lr.linrec_get_option(lr.OPT_VARIANT)
         seen["plan"] = lr.linrec_plan(T, B, n, backward=False)
 
-    with options(variant=lr.VARIANT_SERIAL, tile=1):
+    with options(variant=lr.VARIANT_SERIAL, tile=one_column_tiles(lr.ENTRY_PLAIN)[0]):
         t = threading.Thread(target=worker)
         t.start()
         t.join()

@@ -6,7 +6,7 @@ import torch
 
 import linrec_workloads as wl
 import paper_1709_04057_amd as lr
-from parity import FWD_TOL, check_forward, options, say
+from parity import FWD_TOL, all_tiles, check_forward, options, say
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -43,11 +43,16 @@ def test_automatic_plan_side_stream_and_no_initial_state():
 
 
 def test_too_large_is_refused_and_nothing_is_enqueued():
-    T, B, n = 65536, 4, 256          # on 32-row tiles: 2048 tiles x 1024 columns x 24 bytes, beyond the array
-    assert 24 * (T // 32) * B * n > lr.linrec_noalloc_scratch_bytes()
+    # on the shortest tiles the library has for this entry point the look-back words -- 24 bytes per tile and
+    # column -- do not fit the array
+    short = min(all_tiles(lr.ENTRY_PLAIN), key=lambda t: t[1]["rows"] * 8 + t[1]["cols_per_thread"])
+    B, n = 4, 256
+    T = 2 * short[1]["rows"] * (lr.linrec_noalloc_scratch_bytes() // (24 * B * n))
+    assert 24 * (T // short[1]["rows"]) * B * n > lr.linrec_noalloc_scratch_bytes()
     lam = torch.rand((T, B, n), device=DEV)
     out = torch.zeros_like(lam)
-    with options(variant=lr.VARIANT_LOOKBACK, tile=1):
+    with options(variant=lr.VARIANT_LOOKBACK, tile=short[0]):
+        assert lr.linrec_plan(T, B, n) == (lr.VARIANT_LOOKBACK, short[0])
         with pytest.raises(lr.LinrecError) as err:
             lr.linrec_forward_noalloc(lam, lam, None, out)
         assert err.value.status == lr.ERR_SCRATCH
