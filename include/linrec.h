@@ -83,7 +83,8 @@ enum {
 
 enum {
     LINREC_OPT_VARIANT = 1,    /* LINREC_VARIANT_*                                           */
-    LINREC_OPT_TILE = 2,       /* tile-shape id, 0 = automatic (see linrec_tile_info)        */
+    LINREC_OPT_TILE = 2,       /* tile-shape id, 0 = automatic (see linrec_tile_info; an id the
+                                  entry point has no kernel of -- linrec_tile_has -- is ignored) */
     LINREC_OPT_CHUNK_TILES = 3,/* three-phase: tiles walked per chunk, 0 = automatic         */
     LINREC_OPT_SPIN_LIMIT = 4, /* look-back: polls before a wait is declared failed          */
     LINREC_OPT_HPREV_LATE = 5, /* look-back backward: load h after the rescan (1), together

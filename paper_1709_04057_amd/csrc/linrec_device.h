@@ -914,6 +914,58 @@ __device__ __forceinline__ void tile_store_lstm_fwd(const Args &A, const TileAdd
     }
 }
 
+// The same with the output gate formed early (single-pass kernel, shapes of few elements per thread).  The
+// output gate does not depend on the scan, so its pre-activation is loaded together with the tile's operands
+// (lstm_fwd_early_load: the latency of a load behind the rescan is otherwise spent in full, once per chunk),
+// turned into the gate after the tile's summary has been published, while its predecessors are waited for,
+// and what is left behind the rescan is one product and two stores per element.  Costs R*VEC registers
+// from the loads to the stores, so it is compiled for the shapes where that does not cost a wavefront per SIMD.
+#ifndef LINREC_LSTM_FWD_EARLY_MAX
+#define LINREC_LSTM_FWD_EARLY_MAX 32
+#endif
+template <class G>
+constexpr bool kLstmFwdEarly = G::R * G::VEC <= LINREC_LSTM_FWD_EARLY_MAX;
+
+// (an interior instance of its own: inside run-time conditions the compiler waits for every load before it
+// issues the next)
+template <class G, bool INTERIOR>
+__device__ __forceinline__ void lstm_fwd_early_load_impl(const Args &A, const TileAddr<G, false> &ad,
+                                                         const RowMask<G, false> &mk, vec<G::VEC> (&og)[G::R])
+{
+    const rsrc_t ro = ad.rsrc(A.d);
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) {
+        og[j] = splat<G::VEC>(0.0f);
+        if (INTERIOR || j < mk.n) og[j] = gld<G>(ro, ad.toff, ad.soff(j));
+    }
+}
+template <class G>
+__device__ __forceinline__ void lstm_fwd_early_load(const Args &A, const TileAddr<G, false> &ad, const RowMask<G, false> &mk,
+                                                    bool interior, vec<G::VEC> (&og)[G::R])
+{
+    if (interior) lstm_fwd_early_load_impl<G, true>(A, ad, mk, og);
+    else lstm_fwd_early_load_impl<G, false>(A, ad, mk, og);
+}
+template <class G>
+__device__ __forceinline__ void lstm_fwd_early_gate(vec<G::VEC> (&og)[G::R])
+{
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) og[j] = gate_value<G::VEC>(og[j]);
+}
+template <class G>
+__device__ __forceinline__ void lstm_fwd_early_store(const Args &A, const TileAddr<G, false> &ad, const RowMask<G, false> &mk,
+                                                     bool interior, const Rows<G> &r, const vec<G::VEC> (&og)[G::R])
+{
+    const rsrc_t r0 = ad.rsrc(A.out0), r1 = ad.rsrc(A.out1);
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) {
+        if (interior || j < mk.n) {
+            if (A.out0) gst<G>(r0, ad.toff, ad.soff(j), r.b[j]);
+            if (A.out1) gst<G>(r1, ad.toff, ad.soff(j), og[j] * r.b[j]);
+        }
+    }
+}
+
 // Backward epilogue of the LSTM cell.  After the rescan r.b[j] = d_t (accumulated gradient of c_t) and
 // r.a[j] is the forget gate's complement of row t+1, so the row's own is r.a[j+1] (see the gated form).
 //   grad_f_pre = d * c_{t-1} * f(1-f)   (c_{-1} = c0)      grad_i_pre = d * z * i(1-i)
@@ -970,6 +1022,108 @@ __device__ __forceinline__ void tile_store_lstm_bwd(const Args &A, const TileAdd
                 if (A.out2) gst<G>(rz, ad.toff, ad.soff(j), d * ig * vfma<VEC>(-z, z, splat<VEC>(1.0f)));
                 if (!interior && j == mk.nh && A.gh0) pst<G>(A.gh0, col, f * d);
             }
+        }
+    }
+}
+
+// The same with everything that does not depend on the carry-in moved in front of the look-back (single-pass
+// kernel), as for the gated layer's backward pass.  i_pre and z_pre are loaded behind the prologue
+// (lstm_bwd_early_load, with the two values the thread's last row needs); after the tile's summary has been
+// published, while its predecessors are waited for, the three factors
+//   c_{t-1} * f(1-f)        z * i(1-i)        i * (1 - z^2)
+// are formed in place of c_t, i_pre and z_pre (lstm_bwd_early_math); behind the rescan three products and three
+// stores per element are left (lstm_bwd_early_store).  Costs two more register tiles across the look-back.
+#ifndef LINREC_LSTM_BWD_EARLY_MAX
+#define LINREC_LSTM_BWD_EARLY_MAX 24
+#endif
+template <class G>
+constexpr bool kLstmBwdEarly = G::R * G::VEC <= LINREC_LSTM_BWD_EARLY_MAX;
+template <class G>
+struct LstmBwdEarly {
+    vec<G::VEC> ei[G::R], ez[G::R];  // i_pre, z_pre; then z * i(1-i), i * (1 - z^2)
+    vec<G::VEC> c_last, cp_last;     // the thread's last existing row: its forget-gate pre-activation (then complement)
+                                     // and the cell state before it (c0 when that row is t == 0)
+    vec<G::VEC> f_first;             // the forget gate of row t == 0, where the thread holds it (grad_c0)
+};
+template <class G, bool ON>
+struct LstmEarlySel { using type = LstmBwdEarly<G>; };
+template <class G>
+struct LstmEarlySel<G, false> { using type = NoEarly; };
+
+template <class G, bool INTERIOR>
+__device__ __forceinline__ void lstm_bwd_early_load_impl(const Args &A, const TileAddr<G, true> &ad,
+                                                         const RowMask<G, true> &mk, int64_t col, LstmBwdEarly<G> &e)
+{
+    constexpr int R = G::R, VEC = G::VEC;
+    const rsrc_t rcp = ad.rsrc(A.hprev, -1), rip = ad.rsrc(A.c), rzp = ad.rsrc(A.d), rg = ad.rsrc(A.a);
+    const int nv = INTERIOR ? R : mk.n;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        e.ei[j] = e.ez[j] = splat<VEC>(0.0f);
+        if (INTERIOR || j < mk.n) {
+            e.ei[j] = gld<G>(rip, ad.toff, ad.soff(j));
+            e.ez[j] = gld<G>(rzp, ad.toff, ad.soff(j));
+        }
+    }
+    e.c_last = splat<VEC>(__builtin_inff());
+    e.cp_last = splat<VEC>(0.0f);
+    if (INTERIOR) {
+        e.c_last = gld<G>(rg, ad.toff, ad.soff(R - 1));
+        e.cp_last = gld<G>(rcp, ad.toff, ad.soff(R - 1));
+    } else if (nv > 0) {
+        e.c_last = gld<G>(rg, ad.toff + ad.soff_rt(nv - 1), 0);
+        if (nv - 1 < mk.nh) e.cp_last = gld<G>(rcp, ad.toff + ad.soff_rt(nv - 1), 0);
+        else if (A.h0) e.cp_last = pld<G>(A.h0, col);
+    }
+}
+template <class G>
+__device__ __forceinline__ void lstm_bwd_early_load(const Args &A, const TileAddr<G, true> &ad, const RowMask<G, true> &mk,
+                                                    int64_t col, bool interior, LstmBwdEarly<G> &e)
+{
+    if (interior) lstm_bwd_early_load_impl<G, true>(A, ad, mk, col, e);
+    else lstm_bwd_early_load_impl<G, false>(A, ad, mk, col, e);
+}
+// r.a[j] is the forget gate's complement of row t+1, so the row's own is r.a[j+1], and c_{t-1} is cst[j+1]
+// (the thread's next row is t-1); cst[j] becomes c_{t-1} * f(1-f).
+template <class G>
+__device__ __forceinline__ void lstm_bwd_early_math(const RowMask<G, true> &mk, bool interior, const Rows<G> &r,
+                                                    vec<G::VEC> (&cst)[G::R], LstmBwdEarly<G> &e)
+{
+    constexpr int R = G::R, VEC = G::VEC;
+    const int nv = interior ? R : mk.n;
+    e.c_last = gate_complement<VEC>(e.c_last);
+    e.f_first = splat<VEC>(0.0f);
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        vec<VEC> cf = e.c_last, cp = e.cp_last;
+        if (j + 1 < R) {
+            cf = (j + 1 < nv) ? r.a[j + 1] : e.c_last;
+            cp = (j + 1 < nv) ? cst[j + 1] : e.cp_last;
+        }
+        const vec<VEC> f = splat<VEC>(1.0f) - cf;
+        if (!interior && j == mk.nh) e.f_first = f;
+        vec<VEC> ig, ic;
+        gate_both<VEC>(e.ei[j], ig, ic);
+        const vec<VEC> z = impulse<VEC>(e.ez[j], 1);
+        cst[j] = cp * (f * cf);  // (row j-1, which read cst[j], is done)
+        e.ei[j] = z * (ig * ic);
+        e.ez[j] = ig * vfma<VEC>(-z, z, splat<VEC>(1.0f));
+    }
+}
+template <class G>
+__device__ __forceinline__ void lstm_bwd_early_store(const Args &A, const TileAddr<G, true> &ad, const RowMask<G, true> &mk,
+                                                     int64_t col, bool interior, const Rows<G> &r,
+                                                     const vec<G::VEC> (&cst)[G::R], const LstmBwdEarly<G> &e)
+{
+    const rsrc_t rf = ad.rsrc(A.out0), ri = ad.rsrc(A.out1), rz = ad.rsrc(A.out2);
+#pragma unroll
+    for (int j = 0; j < G::R; ++j) {
+        const vec<G::VEC> d = r.b[j];
+        if (interior || j < mk.n) {
+            if (A.out0) gst<G>(rf, ad.toff, ad.soff(j), d * cst[j]);
+            if (A.out1) gst<G>(ri, ad.toff, ad.soff(j), d * e.ei[j]);
+            if (A.out2) gst<G>(rz, ad.toff, ad.soff(j), d * e.ez[j]);
+            if (!interior && j == mk.nh && A.gh0) pst<G>(A.gh0, col, e.f_first * d);
         }
     }
 }
@@ -1379,6 +1533,14 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     constexpr bool EARLY = BWD && FORM == FORM_GATED && kGatedBwdEarly<G>;
     typename EarlySel<G, EARLY>::type early[1];
     if constexpr (EARLY) gated_bwd_early_load<G>(A, ad, mk, col, interior, early[0]);
+    constexpr bool EARLY_L = BWD && FORM == FORM_LSTM && kLstmBwdEarly<G>;
+    typename LstmEarlySel<G, EARLY_L>::type early_l[1];
+    if constexpr (EARLY_L) lstm_bwd_early_load<G>(A, ad, mk, col, interior, early_l[0]);
+    constexpr bool EARLY_O = !BWD && FORM == FORM_LSTM && kLstmFwdEarly<G>;
+    vec<VEC> og[EARLY_O ? R : 1];  // the cell's output gate (pre-activations until the summary is out)
+    if constexpr (EARLY_O) {
+        if (A.out1) lstm_fwd_early_load<G>(A, ad, mk, interior, og);
+    }
     // thread-exclusive prefix inside the tile; rounded to fp32 once (it is used once, in the
     // rescan's carry-in, and is not fed on along the chain of tiles)
     vec<VEC> Pe32, Se32;
@@ -1413,6 +1575,10 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     // (the carry-independent part of the gated backward epilogue: behind the publication, so that it does not
     // delay the tiles that wait for this one, and in front of this tile's own waits)
     if constexpr (EARLY) gated_bwd_early_math<G>(A, mk, interior, r, early[0]);
+    if constexpr (EARLY_L) lstm_bwd_early_math<G>(mk, interior, r, cst, early_l[0]);
+    if constexpr (EARLY_O) {
+        if (A.out1) lstm_fwd_early_gate<G>(og);
+    }
     LINREC_TRACE_MARK(2);
     [[maybe_unused]] int n_windows = 0;  // (read by trace builds)
     unsigned long long next_ticket = 0xffffffffull;
@@ -1524,6 +1690,10 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
     } else if constexpr (BWD && FORM == FORM_GATED) {
         __builtin_amdgcn_sched_barrier(0);  // the epilogue's loads stay behind the rescan
         tile_store_gated_bwd<G>(A, ad, mk, col, interior, r);
+    } else if constexpr (EARLY_L) {
+        lstm_bwd_early_store<G>(A, ad, mk, col, interior, r, cst, early_l[0]);
+    } else if constexpr (EARLY_O) {
+        lstm_fwd_early_store<G>(A, ad, mk, interior, r, og);
     } else if constexpr (FORM == FORM_LSTM) {
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (BWD) tile_store_lstm_bwd<G>(A, ad, mk, col, interior, r, cst);

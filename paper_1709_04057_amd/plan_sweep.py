@@ -6,6 +6,8 @@ library is built for the tile shapes that table uses and no others.  Both are ge
     LINREC_EXTRA_FLAGS=-DLINREC_ALL_SHAPES LINREC_BUILD_OUT=$PWD/liblinrec_all.so python paper_1709_04057_amd/build.py
     LINREC_LIB_PATH=$PWD/liblinrec_all.so python -m paper_1709_04057_amd.plan_sweep measure --out sweep.jsonl
     python -m paper_1709_04057_amd.plan_sweep table sweep.jsonl         # anywhere; then build again
+(``measure --families a,b`` times some families only; ``table`` takes several files, a later file's timing of a plan
+replacing an earlier one's, so a change to one family's kernels needs that family measured again and no more.)
 
 ``measure`` (on the GPU, a few minutes, with a library that has every kernel the catalogue of shapes allows)
 times every tile shape of every entry-point family, single pass and -- for short, wide problems -- walk,
