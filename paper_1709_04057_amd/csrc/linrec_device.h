@@ -1462,6 +1462,10 @@ __device__ __forceinline__ unsigned long long lb_load(const unsigned long long *
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// Pause between polls of a predecessor's flag once the first few quick ones have failed, in units of 64 clocks.
+#ifndef LINREC_POLL_SLEEP
+#define LINREC_POLL_SLEEP 16
+#endif
 template <class G, bool BWD, bool HP_LATE, int FORM = FORM_PLAIN>
 __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
 {
@@ -1616,7 +1620,7 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
                 if (t == tag_agg || t == tag_incl) break;
                 if (++spins > A.spin_limit) { gave_up = true; break; }
                 if (spins < 4) __builtin_amdgcn_s_sleep(2);
-                else __builtin_amdgcn_s_sleep(16);
+                else __builtin_amdgcn_s_sleep(LINREC_POLL_SLEEP);
             }
             // then read this thread's own words until they are consistent
             while (!gave_up) {
