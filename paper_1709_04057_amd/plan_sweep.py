@@ -334,7 +334,7 @@ def main():
     t.add_argument("--out", default="", help="directory for the two generated files (default: csrc/)")
     t.add_argument("--mean-loss", type=float, default=0.005)
     t.add_argument("--cell-loss", type=float, default=0.03)
-    t.add_argument("--max-shapes", type=int, default=16)
+    t.add_argument("--max-shapes", type=int, default=20)
     args = ap.parse_args()
     (measure if args.cmd == "measure" else table)(args)
 
