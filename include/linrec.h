@@ -90,10 +90,12 @@ enum {
     LINREC_OPT_HPREV_LATE = 5, /* look-back backward: load h after the rescan (1), together
                                   with lambda and grad_h (0), or let the library decide (-1)  */
     LINREC_OPT_TAPER = 6,      /* look-back: cut this many eighths (0..8) of the last round of
-                                  tiles into half- and quarter-height tiles; 0 = none (default:
-                                  neutral on most shapes); linrec_tune tries 2 on the plan it
-                                  found and remembers it where that is faster; a non-zero
-                                  value set here overrides what tuning remembered            */
+                                  tiles into half- and quarter-height tiles, so that a launch
+                                  of few rounds does not end on a few workgroups finishing
+                                  big tiles; 0 = none; -1 (default) = what linrec_tune
+                                  remembered for the shape, else what the static plan has
+                                  (2 where that measured ahead, mostly long sequences on few
+                                  columns; it loses on wide problems)                        */
     LINREC_OPT_PERSISTENT = 7, /* look-back: launch as many workgroups as LINREC_OPT_GRID_CAP
                                   allows and let each loop over tiles (1; also what -1, the
                                   default, means), or one workgroup per tile (0)               */
@@ -310,6 +312,11 @@ enum {
 };
 int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward,
                     int alignment_bytes, int *variant, int *tile_id);
+
+/* The tapered tail of that plan: eighths (0..8) of the single pass's last round of tiles that are cut
+ * into shorter tiles (see LINREC_OPT_TAPER); 0 for the other variants.  Negative: LINREC_ERR_*. */
+int linrec_plan_taper(int entry_point, int64_t T, int64_t B, int64_t n, int backward,
+                      int alignment_bytes);
 
 /* 1 if the library has kernels of tile shape `tile_id` for entry-point family `entry_point`
  * (LINREC_ENTRY_*), else 0: each family is built for the shapes its static plans use.  A

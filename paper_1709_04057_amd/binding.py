@@ -94,6 +94,8 @@ def lib():
         L.linrec_get_option.restype = i64
         L.linrec_tile_info.argtypes = [ci, pi, pi, pi, pi]
         L.linrec_tile_info.restype = ci
+        L.linrec_plan_taper.argtypes = [ci, i64, i64, i64, ci, ci]
+        L.linrec_plan_taper.restype = ci
         L.linrec_tile_has.argtypes = [ci, ci]
         L.linrec_tile_has.restype = ci
         L.linrec_plan.argtypes = [i64, i64, i64, ci, ci, pi, pi]
@@ -349,6 +351,14 @@ def linrec_tile_info(tile_id: int):
         return None
     return dict(threads_cols=a.value, threads_time=b.value, rows_per_thread=c.value, cols_per_thread=d.value,
                 rows=b.value * c.value, cols=a.value * d.value)
+
+
+def linrec_plan_taper(entry_point, T, B, n, backward=False, alignment=16) -> int:
+    """Eighths of the last round of tiles the plan of this problem cuts into shorter tiles (0: none)."""
+    rc = lib().linrec_plan_taper(int(entry_point), int(T), int(B), int(n), int(bool(backward)), int(alignment))
+    if rc < 0:
+        _check(rc)
+    return rc
 
 
 def linrec_tile_has(tile_id: int, entry_point: int) -> bool:

@@ -67,7 +67,7 @@ struct Options {
     int64_t chunk_tiles = 0;
     int64_t spin_limit = 1 << 22;
     int64_t hp_late = -1;  // -1 automatic
-    int64_t taper = 0;
+    int64_t taper = -1;  // -1 automatic
     int64_t grid_cap = 0;
     int64_t stagger = 3;
     int64_t persistent = -1;  // -1 automatic (persistent)
@@ -248,6 +248,7 @@ static_assert(LINREC_ENTRY_PLAIN == 0 && LINREC_ENTRY_GILR == 1 && LINREC_ENTRY_
 struct StaticPlan {
     int lookback;  // the single pass's tile shape (0: the family has no kernel at this access width)
     int walk;      // the walk's, where the walk is the better variant; else 0
+    int taper;     // eighths of the single pass's last round cut into shorter tiles, where that measured ahead
 };
 StaticPlan static_plan(int family, bool bwd, int64_t T, int64_t C, int vec)
 {
@@ -265,13 +266,14 @@ StaticPlan static_plan(int family, bool bwd, int64_t T, int64_t C, int vec)
             // (the walk keeps one workgroup per column group busy for the whole sequence: a plan measured on a
             // much shorter or longer sequence says nothing about it)
             if (c.lookback[w] && tile_has(c.lookback[w], family))
-                return StaticPlan{c.lookback[w], (d <= 1 && tile_has(c.walk[w], family)) ? c.walk[w] : 0};
+                return StaticPlan{c.lookback[w], (d <= 1 && tile_has(c.walk[w], family)) ? c.walk[w] : 0,
+                                  d <= 1 ? c.taper[w] : 0};
         }
     }
     // nothing measured at this width: any shape the family has
     for (int id = 1; id <= MAX_TILE_ID; ++id)
-        if (tile_has(id, family) && kTable.t[id].vec <= vec) return StaticPlan{id, 0};
-    return StaticPlan{0, 0};
+        if (tile_has(id, family) && kTable.t[id].vec <= vec) return StaticPlan{id, 0, 0};
+    return StaticPlan{0, 0, 0};
 }
 
 int entry_family(int form, bool bf16)
@@ -343,7 +345,7 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
                 p.tile = it->second.tile;
                 p.variant = it->second.variant;
                 if (p.persistent < 0) p.persistent = it->second.persistent;
-                if (p.taper == 0) p.taper = it->second.taper;
+                if (p.taper < 0) p.taper = it->second.taper;
             }
         }
     }
@@ -359,8 +361,10 @@ Plan make_plan(int64_t T, int64_t C, int vec, bool bwd, int form = FORM_PLAIN, b
         } else {
             // (the walk asked for by option without a shape: the shape the table has for it, else the single pass's)
             p.tile = (p.variant == LINREC_VARIANT_WALK && sp.walk) ? sp.walk : sp.lookback;
+            if (p.taper < 0 && p.tile == sp.lookback) p.taper = sp.taper;
         }
     }
+    if (p.taper < 0) p.taper = 0;
     // bf16 tensors that are not even 4-byte aligned, or an odd number of columns: the serial kernel
     // (the gated forms have one-column shapes with 2-byte accesses for those)
     if ((bf16 && !gated && vec < 2) || !p.tile) {
@@ -867,7 +871,7 @@ extern "C" int linrec_set_option(int option, int64_t value)
         opts().hp_late = value;
         return LINREC_OK;
     case LINREC_OPT_TAPER:
-        if (value < 0 || value > 8) return LINREC_ERR_OPTION;
+        if (value < -1 || value > 8) return LINREC_ERR_OPTION;
         opts().taper = value;
         return LINREC_OK;
     case LINREC_OPT_PERSISTENT:
@@ -956,6 +960,18 @@ extern "C" int linrec_plan_for(int entry_point, int64_t T, int64_t B, int64_t n,
     if (variant) *variant = p.variant;
     if (tile_id) *tile_id = p.tile;
     return LINREC_OK;
+}
+
+extern "C" int linrec_plan_taper(int entry_point, int64_t T, int64_t B, int64_t n, int backward, int alignment_bytes)
+{
+    int64_t C = B * n;
+    if (T <= 0 || B <= 0 || n <= 0) return LINREC_ERR_SHAPE;
+    if (entry_point < LINREC_ENTRY_PLAIN || entry_point > LINREC_ENTRY_LSTM_CELL_BF16) return LINREC_ERR_OPTION;
+    const void *al = (const void *)(uintptr_t)(alignment_bytes > 0 ? alignment_bytes : 2);
+    const bool bf16 = entry_bf16(entry_point);
+    const int vec = bf16 ? max_vec_bf16(C, {al}) : max_vec(C, {al});
+    const Plan p = make_plan(T, C, vec, backward != 0, entry_form(entry_point), bf16);
+    return p.variant == LINREC_VARIANT_LOOKBACK ? p.taper : 0;
 }
 
 extern "C" int linrec_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
@@ -1056,7 +1072,8 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
     if (rc == LINREC_OK) {
         const int vec = bf16 ? max_vec_bf16(C, {}) : max_vec(C, {});
         // (candidates are forced on this thread's calls only; the options stay as they are)
-        const int64_t saved_taper = opts().taper;
+        const int base_taper = opts().taper > 0 ? (int)opts().taper : 0;  // an explicit option holds for every candidate
+        const bool try_taper = opts().taper < 0;
         ForcedPlan &fp = forced();
         // Median of five launches of the forced plan, after two warm-up launches; < 0 on failure (rc is set).
         auto time_plan = [&](int variant, int tile, int persistent, int taper) -> float {
@@ -1095,7 +1112,7 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
             if (!usable(tile)) continue;
             if (kTable.t[tile].rows() > 2 * T && tile != sp.lookback) continue;  // far taller than the problem
             for (int persistent = 0; persistent <= 1 && rc == LINREC_OK; ++persistent) {
-                const float ms = time_plan(LINREC_VARIANT_LOOKBACK, tile, persistent, (int)saved_taper);
+                const float ms = time_plan(LINREC_VARIANT_LOOKBACK, tile, persistent, base_taper);
                 if (ms < 0.f) break;
                 if (best.tile == 0 || ms < best_ms) {
                     if (best.tile != tile) {  // (the runner-up is a different shape)
@@ -1113,10 +1130,10 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
         }
         // The two best single-pass plans once more with a quarter of their last round cut into shorter
         // tiles: a launch of few rounds ends sooner that way on some shapes (kept only if it is at least
-        // half a percent faster than the best so far; an explicit LINREC_OPT_TAPER overrides what is
-        // remembered).
+        // half a percent faster than the best so far; an explicit LINREC_OPT_TAPER, 0 included, overrides what is
+        // remembered and is not second-guessed here).
         const TunedPlan untapered[2] = {best, second};
-        for (int c = 0; c < 2 && rc == LINREC_OK && saved_taper == 0; ++c) {
+        for (int c = 0; c < 2 && rc == LINREC_OK && try_taper; ++c) {
             const TunedPlan &u = untapered[c];
             if (u.tile == 0 || kTable.t[u.tile].r % 4 != 0 || kTable.t[u.tile].r < 8) continue;
             const float ms = time_plan(LINREC_VARIANT_LOOKBACK, u.tile, u.persistent, 2);

@@ -7,7 +7,9 @@ library is built for the tile shapes that table uses and no others.  Both are ge
     LINREC_LIB_PATH=$PWD/liblinrec_all.so python -m paper_1709_04057_amd.plan_sweep measure --out sweep.jsonl
     python -m paper_1709_04057_amd.plan_sweep table sweep.jsonl         # anywhere; then build again
 (``measure --families a,b`` times some families only; ``table`` takes several files, a later file's timing of a plan
-replacing an earlier one's, so a change to one family's kernels needs that family measured again and no more.)
+replacing an earlier one's, so a change to one family's kernels needs that family measured again and no more.
+``measure`` also times the tapered tail, LINREC_OPT_TAPER = 2, on the three fastest single-pass shapes of every
+cell; ``measure --taper-only sweep.jsonl ...`` does just that on the shapes an earlier sweep found.)
 
 ``measure`` (on the GPU, a few minutes, with a library that has every kernel the catalogue of shapes allows)
 times every tile shape of every entry-point family, single pass and -- for short, wide problems -- walk,
@@ -86,6 +88,8 @@ def measure(args):
     tiles = [i for i in range(1, 129) if lr.linrec_tile_info(i) is not None]
     fams = args.families.split(",") if args.families else list(FAMILIES)
     out = open(args.out, "a")
+    prior = load(args.taper_only)[0] if args.taper_only else None   # (only the tapered tail is measured)
+    lr.linrec_set_option(lr.OPT_TAPER, 0)
     for fam in fams:
         ep = FAMILIES[fam]
         bf16 = fam.endswith("bf16")
@@ -127,7 +131,12 @@ def measure(args):
                 lr.linrec_set_option(lr.OPT_TILE, 0)
                 short = timeit(call, 3) < 60.0      # the whole cell is timed one way
                 best = None
+                single = {}                         # single pass: {(tile, columns per thread): microseconds}
                 variants = [VARIANT_LOOKBACK] + ([VARIANT_WALK] if T <= 4096 and C >= 2048 else [])
+                if prior is not None:
+                    variants = []
+                    single = {(t, vec): us for (var, t, vec), us in prior.get((ep, backward, T, C), {}).items()
+                              if var == VARIANT_LOOKBACK}
                 for variant in variants:
                     for tile in tiles:
                         info = lr.linrec_tile_info(tile)
@@ -147,12 +156,53 @@ def measure(args):
                                                   vec=info["cols_per_thread"], us=us, graph=int(short))) + "\n")
                         if best is None or us < best[0]:
                             best = (us, variant, tile)
+                        if variant == VARIANT_LOOKBACK:
+                            single[(tile, info["cols_per_thread"])] = us
+                # The tapered tail (LINREC_OPT_TAPER = 2: a quarter of the last round of tiles cut into shorter ones)
+                # on the three fastest single-pass shapes of each access width (the table may settle on any of them),
+                # each against the same shape timed again without.
+                cand = set()
+                for w in (1, 2, 4):
+                    cand.update(sorted((k for k in single if k[1] <= w), key=single.get)[:3])
+                for key in sorted(cand):
+                    tile, info = key[0], lr.linrec_tile_info(key[0])
+                    if info["rows_per_thread"] % 4 or info["rows_per_thread"] < 8 or T < 4 * info["rows"]:
+                        continue
+                    lr.linrec_set_option(lr.OPT_VARIANT, VARIANT_LOOKBACK)
+                    lr.linrec_set_option(lr.OPT_TILE, tile)
+                    if lr.linrec_plan_for(ep, T, B, n, backward=backward) != (VARIANT_LOOKBACK, tile):
+                        continue
+                    pair = []
+                    for taper in (2, 0):
+                        lr.linrec_set_option(lr.OPT_TAPER, taper)
+                        if short:
+                            pair.append(timeit_graph(call, lambda st: lr.linrec_reserve_workspace(ep, T, B, n, backward=backward,
+                                                                                                 stream=st)))
+                        else:
+                            pair.append(timeit(call, 9 if T * C <= 2 ** 26 else 5))
+                    out.write(json.dumps(dict(fam=fam, T=T, C=C, p=which, var=VARIANT_LOOKBACK, tile=tile, taper=2,
+                                              vec=info["cols_per_thread"], us=pair[0], us0=pair[1], graph=int(short))) + "\n")
                 out.flush()
-                print(f"{fam} T={T} C={C} {which}: variant {best[1]} tile {best[2]} {best[0]:.1f} us", flush=True)
+                if best is not None:
+                    print(f"{fam} T={T} C={C} {which}: variant {best[1]} tile {best[2]} {best[0]:.1f} us", flush=True)
+                else:
+                    print(f"{fam} T={T} C={C} {which}: tapered tails timed", flush=True)
             lr.linrec_check()
             del inp
     lr.linrec_set_option(lr.OPT_VARIANT, lr.VARIANT_AUTO)
     lr.linrec_set_option(lr.OPT_TILE, 0)
+    lr.linrec_set_option(lr.OPT_TAPER, -1)
+
+
+def load_tapers(sweeps):
+    """{(family id, backward, T, C): {tile: (microseconds with the tapered tail, without it in the same run)}}"""
+    tapers = collections.defaultdict(dict)
+    for f in sweeps:
+        for line in open(f):
+            r = json.loads(line)
+            if r.get("taper"):
+                tapers[(FAMILIES[r["fam"]], r["p"] == "bwd", r["T"], r["C"])][r["tile"]] = (r["us"], r["us0"])
+    return tapers
 
 
 def load(sweeps):
@@ -162,6 +212,8 @@ def load(sweeps):
     for f in sweeps:
         for line in open(f):
             r = json.loads(line)
+            if r.get("taper"):
+                continue
             cells[(FAMILIES[r["fam"]], r["p"] == "bwd", r["T"], r["C"])][(r["var"], r["tile"], r["vec"])] = r["us"]
             n += 1
     return cells, n
@@ -246,18 +298,23 @@ def choose_cell(cells, key, width, allowed, variant):
 WALK_MARGIN = 0.97      # the walk is taken where it measured at least 3 % ahead of the single pass
 
 
-def make_table(cells, shapes):
-    """{(ep, bwd, lt, ci): ([single-pass tile per width], [walk tile per width or 0])}"""
+TAPER_MARGIN = 0.98     # the tapered tail is taken where it measured at least 2 % ahead of the same shape without
+
+
+def make_table(cells, shapes, tapers={}):
+    """{(ep, bwd, lt, ci): ([single-pass tile per width], [walk tile per width or 0], [tapered eighths per width])}"""
     out = {}
     for key in cells:
         ep, bwd, T, C = key
-        lb, walk = [], []
+        lb, walk, taper = [], [], []
         for width in (1, 2, 4):
             t, us = choose_cell(cells, key, width, shapes[ep], VARIANT_LOOKBACK)
             wt, wus = choose_cell(cells, key, width, shapes[ep], VARIANT_WALK)
             lb.append(t)
             walk.append(wt if wt and t and wus < WALK_MARGIN * us else 0)
-        out[(ep, bwd, int(math.log2(T)), C_GRID.index(C))] = (lb, walk)
+            tapered, plain = tapers.get(key, {}).get(t, (1.0, 1.0))
+            taper.append(2 if tapered < TAPER_MARGIN * plain and not walk[-1] else 0)
+        out[(ep, bwd, int(math.log2(T)), C_GRID.index(C))] = (lb, walk, taper)
     return out
 
 
@@ -265,7 +322,7 @@ def table_loss(cells, tab):
     """Mean and worst loss of the table's choices against the best measured choice, per family."""
     res = collections.defaultdict(list)
     for (ep, bwd, T, C), v in cells.items():
-        lb, walk = tab[(ep, bwd, int(math.log2(T)), C_GRID.index(C))]
+        lb, walk, _ = tab[(ep, bwd, int(math.log2(T)), C_GRID.index(C))]
         for w, width in enumerate((1, 2, 4)):
             ok = {k: us for k, us in v.items() if k[2] <= width}
             if not ok:
@@ -284,7 +341,8 @@ def table(args):
         shapes[ep], (missing, mean, behind) = choose_shapes(cells, ep, args.mean_loss, args.cell_loss, args.max_shapes)
         print(f"{names[ep]}: {len(shapes[ep])} shapes {shapes[ep]} (mean loss {100 * mean:.2f} %, {behind} cells more than "
               f"{100 * args.cell_loss:.0f} % behind, {missing} without a kernel)")
-    tab = make_table(cells, shapes)
+    tab = make_table(cells, shapes, load_tapers(args.sweeps))
+    print("tapered tail taken in %d of %d cell-widths" % (sum(sum(1 for x in v[2] if x) for v in tab.values()), 3 * len(tab)))
     for ep, (mean, worst) in sorted(table_loss(cells, tab).items()):
         print(f"{names[ep]}: table within {100 * mean:.2f} % of the best measured choice on average, {100 * worst:.0f} % at worst")
     csrc = args.out or os.path.join(HERE, "csrc")
@@ -300,11 +358,13 @@ def table(args):
     with open(os.path.join(csrc, "linrec_plan_table.inc"), "w") as f:
         f.write("// Static plans: per entry-point family, pass and problem [2^lt rows, kPlanC[ci] columns] the fastest\n"
                 "// single-pass tile shape among those whose accesses are 1, 2 or 4 columns wide, and the walk's where the\n"
-                "// walk measured ahead of it (else 0).  {0, ...}: not measured (too small or too large a problem).\n"
+                "// walk measured ahead of it (else 0), and the eighths of the single pass's last round that are cut into\n"
+                "// shorter tiles (the tapered tail) where that measured ahead.  {0, ...}: not measured (too small or too\n"
+                "// large a problem).\n"
                 + stamp)
         f.write(f"constexpr int kPlanLtMin = {LT_MIN}, kPlanLtMax = {LT_MAX}, kPlanNc = {len(C_GRID)};\n")
         f.write("constexpr int kPlanC[kPlanNc] = {" + ", ".join(map(str, C_GRID)) + "};\n")
-        f.write("struct PlanCell {\n    unsigned char lookback[3], walk[3];\n};\n")
+        f.write("struct PlanCell {\n    unsigned char lookback[3], walk[3], taper[3];\n};\n")
         f.write("// [family][backward][lt - kPlanLtMin][ci]\n")
         f.write(f"const PlanCell kPlanCells[{len(FAMILIES)}][2][kPlanLtMax - kPlanLtMin + 1][kPlanNc] = {{\n")
         for ep in sorted(names):
@@ -314,8 +374,8 @@ def table(args):
                 for lt in range(LT_MIN, LT_MAX + 1):
                     row = []
                     for ci in range(len(C_GRID)):
-                        lb, walk = tab.get((ep, bool(bwd), lt, ci), ([0, 0, 0], [0, 0, 0]))
-                        row.append("{{%d,%d,%d},{%d,%d,%d}}" % (*lb, *walk))
+                        lb, walk, taper = tab.get((ep, bool(bwd), lt, ci), ([0, 0, 0], [0, 0, 0], [0, 0, 0]))
+                        row.append("{{%d,%d,%d},{%d,%d,%d},{%d,%d,%d}}" % (*lb, *walk, *taper))
                     f.write("            {" + ",".join(row) + "},\n")
                 f.write("        },\n")
             f.write("    },\n")
@@ -329,6 +389,8 @@ def main():
     m = sub.add_parser("measure")
     m.add_argument("--out", required=True)
     m.add_argument("--families", default="")
+    m.add_argument("--taper-only", nargs="+", default=[], metavar="SWEEP",
+                   help="time only the tapered tails, on the fastest shapes of these earlier sweeps")
     t = sub.add_parser("table")
     t.add_argument("sweeps", nargs="+")
     t.add_argument("--out", default="", help="directory for the two generated files (default: csrc/)")

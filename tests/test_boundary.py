@@ -234,6 +234,34 @@ def test_plan_is_host_only_and_consistent(L):
     assert variant == lr.VARIANT_SERIAL
 
 
+def test_plan_taper_follows_the_option_then_the_plan(L):
+    """LINREC_OPT_TAPER: -1 (default) takes what the static plan has for the problem, 0 switches the tapered tail
+    off, 1..8 force it; only single-pass plans have one."""
+    assert lr.linrec_get_option(lr.OPT_TAPER) == -1
+    shapes = [(2 ** lt, 1, C) for lt in range(10, 19) for C in (96, 256, 768, 1024, 2048, 4096)]
+    for fam in range(6):
+        auto = {s: lr.linrec_plan_taper(fam, *s, backward=True) for s in shapes}
+        assert all(0 <= t <= 8 for t in auto.values())
+        old = lr.linrec_get_option(lr.OPT_TAPER)
+        try:
+            lr.linrec_set_option(lr.OPT_TAPER, 0)
+            assert all(lr.linrec_plan_taper(fam, *s, backward=True) == 0 for s in shapes)
+            lr.linrec_set_option(lr.OPT_TAPER, 3)
+            for s in shapes:
+                single = lr.linrec_plan_for(fam, *s, backward=True)[0] == lr.VARIANT_LOOKBACK
+                assert lr.linrec_plan_taper(fam, *s, backward=True) == (3 if single else 0)
+        finally:
+            lr.linrec_set_option(lr.OPT_TAPER, old)
+        assert {s: lr.linrec_plan_taper(fam, *s, backward=True) for s in shapes} == auto
+    # the table has tapered tails for the backward passes of the gated layer and the cell on bf16 storage
+    assert any(lr.linrec_plan_taper(lr.ENTRY_GILR_BF16, *s, backward=True) for s in shapes)
+    assert any(lr.linrec_plan_taper(lr.ENTRY_LSTM_CELL_BF16, *s, backward=True) for s in shapes)
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_plan_taper(9, 10, 1, 1)
+    with pytest.raises(lr.LinrecError):
+        lr.linrec_set_option(lr.OPT_TAPER, -2)
+
+
 def test_every_plan_names_a_shape_its_family_has_kernels_for(L):
     """Each entry-point family is built for the tile shapes its static plans use.  Whatever the problem and the
     alignment -- on the measured grid, between its points, far outside it -- the automatic plan must land on a

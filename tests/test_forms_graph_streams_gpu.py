@@ -266,6 +266,40 @@ def test_short_wide_problems_walk_in_every_family():
         assert lr.linrec_plan_for(fam, 65536, 4, 4096, alignment=8)[0] == lr.VARIANT_LOOKBACK
 
 
+def test_automatic_tapered_tail_in_every_family():
+    """Where the static plan cuts the end of a launch into shorter tiles by itself (no option set), the results are
+    right: per family, the first few problems of a list whose plan has a tapered tail."""
+    from parity import fwd_bwd_check
+    from test_bf16_parity_gpu import bf16_check, to_bf16
+    from test_gilr_parity_gpu import gated_check
+    from test_lstm_parity_gpu import cell_check
+    from test_forms_bf16_parity_gpu import cell16_check, gated16_check
+    from test_forms_bf16_parity_gpu import to_bf16 as forms_to_bf16
+
+    assert lr.linrec_get_option(lr.OPT_TAPER) == -1
+    shapes = [(2 ** lt, 1, C) for lt in range(10, 16) for C in (96, 256, 768, 1024, 2048, 4096)]
+    total = 0
+    for fam in range(6):
+        hits = [s for s in shapes if lr.linrec_plan_taper(fam, *s, backward=False) or lr.linrec_plan_taper(fam, *s, backward=True)]
+        for i, (T, B, n) in enumerate(hits[:3]):
+            label = f"automatic taper, family {fam} [{T}, {n}]"
+            say(label)
+            total += 1
+            if fam == lr.ENTRY_PLAIN:
+                fwd_bwd_check(wl.make_inputs(2, T=T, B=B, n=n, device=DEV), label)
+            elif fam == lr.ENTRY_GILR:
+                gated_check(wl.make_gated(T, B, n, seed=61 + i, device=DEV, gate_mean=1.0), lr.TAU_TANH, label)
+            elif fam == lr.ENTRY_LSTM_CELL:
+                cell_check(wl.make_lstm(T, B, n, seed=62 + i, device=DEV), label)
+            elif fam == lr.ENTRY_BF16:
+                bf16_check(to_bf16(wl.make_generic(T, B, n, seed=63 + i, device=DEV)), label)
+            elif fam == lr.ENTRY_GILR_BF16:
+                gated16_check(forms_to_bf16(wl.make_gated(T, B, n, seed=64 + i, device=DEV, gate_mean=1.0)), lr.TAU_TANH, label)
+            else:
+                cell16_check(forms_to_bf16(wl.make_lstm(T, B, n, seed=65 + i, device=DEV)), label)
+    assert total >= 6
+
+
 def test_staggered_start_changes_timing_only():
     """LINREC_OPT_STAGGER delays every other workgroup of the first round: bit-identical results for every
     entry point, whatever the delay, on a problem several rounds of workgroups long."""
