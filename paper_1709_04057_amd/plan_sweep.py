@@ -342,6 +342,11 @@ def table(args):
         print(f"{names[ep]}: {len(shapes[ep])} shapes {shapes[ep]} (mean loss {100 * mean:.2f} %, {behind} cells more than "
               f"{100 * args.cell_loss:.0f} % behind, {missing} without a kernel)")
     tab = make_table(cells, shapes, load_tapers(args.sweeps))
+    for ep in shapes:   # (a shape that, with the neighbours' weight, no cell takes in the end is not built)
+        used = {t for (e, _, _, _), (lb, walk, _) in tab.items() if e == ep for t in lb + walk} - {0}
+        if set(shapes[ep]) - used:
+            print(f"{names[ep]}: not used by any cell after all, dropped: {sorted(set(shapes[ep]) - used)}")
+        shapes[ep] = sorted(used)
     print("tapered tail taken in %d of %d cell-widths" % (sum(sum(1 for x in v[2] if x) for v in tab.values()), 3 * len(tab)))
     for ep, (mean, worst) in sorted(table_loss(cells, tab).items()):
         print(f"{names[ep]}: table within {100 * mean:.2f} % of the best measured choice on average, {100 * worst:.0f} % at worst")

@@ -234,6 +234,35 @@ def test_plan_is_host_only_and_consistent(L):
     assert variant == lr.VARIANT_SERIAL
 
 
+def test_generated_plan_table_names_only_shapes_its_family_is_built_for():
+    """The two generated files agree: every shape a family's block of the plan table names (single pass or walk)
+    carries that family's bit in the set of built shapes, and only single-pass entries have a tapered tail."""
+    import os
+    import re
+    csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_1709_04057_amd", "csrc")
+    with open(os.path.join(csrc, "linrec_tile_set.inc")) as f:
+        built = {int(t): int(m, 16) for t, m in re.findall(r"X\((\d+), 0x([0-9a-f]+)\)", f.read())}
+    with open(os.path.join(csrc, "linrec_plan_table.inc")) as f:
+        blocks = f.read().split("    {  // ")[1:]
+    assert len(blocks) == 6 and built
+    cell = re.compile(r"\{\{(\d+),(\d+),(\d+)\},\{(\d+),(\d+),(\d+)\},\{(\d+),(\d+),(\d+)\}\}")
+    for fam, block in enumerate(blocks):
+        cells = [tuple(map(int, c)) for c in cell.findall(block)]
+        assert len(cells) == 2 * 15 * 25
+        measured = 0
+        for c in cells:
+            for w in range(3):
+                lb, walk, taper = c[w], c[3 + w], c[6 + w]
+                for t in (lb, walk):
+                    assert t == 0 or built.get(t, 0) >> fam & 1, (fam, c)
+                assert 0 <= taper <= 8 and (taper == 0 or (lb and not walk)), (fam, c)
+                measured += lb != 0
+        assert measured > 500
+        # every shape the family is built for is used somewhere
+        used = {c[i] for c in cells for i in range(6)} - {0}
+        assert used == {t for t, m in built.items() if m >> fam & 1}, fam
+
+
 def test_plan_taper_follows_the_option_then_the_plan(L):
     """LINREC_OPT_TAPER: -1 (default) takes what the static plan has for the problem, 0 switches the tapered tail
     off, 1..8 force it; only single-pass plans have one."""

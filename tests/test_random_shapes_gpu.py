@@ -30,7 +30,7 @@ def _cases(seed, n):
         opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_LOOKBACK, lr.VARIANT_THREEPHASE,
                                             lr.VARIANT_SERIAL, lr.VARIANT_WALK])),
                     tile=int(rng.choice(TILE_CHOICES)), persistent=int(rng.integers(-1, 2)),
-                    taper=int(rng.choice([0, 0, 2, 8])), hprev_late=int(rng.integers(-1, 2)))
+                    taper=int(rng.choice([-1, 0, 2, 8])), hprev_late=int(rng.integers(-1, 2)))
         yield i, T, B, n_, opts, int(rng.integers(1 << 30))
 
 
@@ -41,7 +41,7 @@ def _wide_cases(seed, n):
         T, C, B = int(rng.integers(50, 2000)), int(rng.integers(1000, 12000)), int(rng.choice([1, 2, 4]))
         opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_WALK])),
                     tile=int(rng.choice(TILE_CHOICES)), persistent=int(rng.integers(-1, 2)),
-                    taper=int(rng.choice([0, 0, 2])), hprev_late=int(rng.integers(-1, 2)))
+                    taper=int(rng.choice([-1, 0, 2])), hprev_late=int(rng.integers(-1, 2)))
         yield i, T, B, max(1, C // B), opts, int(rng.integers(1 << 30))
 
 
@@ -55,7 +55,7 @@ def _long_cases(seed, n):
         B = int(rng.choice([1, 1, 2]))
         opts = dict(variant=int(rng.choice([lr.VARIANT_AUTO, lr.VARIANT_LOOKBACK, lr.VARIANT_LOOKBACK, lr.VARIANT_THREEPHASE])),
                     tile=int(rng.choice(TILE_CHOICES)), persistent=int(rng.integers(-1, 2)),
-                    taper=int(rng.choice([0, 0, 2, 8])), hprev_late=int(rng.integers(-1, 2)))
+                    taper=int(rng.choice([-1, 0, 2, 8])), hprev_late=int(rng.integers(-1, 2)))
         yield i, T, B, max(1, C // B), opts, int(rng.integers(1 << 30))
 
 
