@@ -11,7 +11,9 @@ the same run and reported beside it.  Prints ONE JSON line:
                 (K steps, wall clock between two device synchronisations, nothing else on the stream)
   roofline      the dominant kernel (the backward pass, 20 B/element) against the 8 TB/s HBM peak, its
                 duration measured with HIP events on the launch stream over a second run of the K steps;
-                frac_of_stream_probe relates it to what the library's pure streaming kernel reaches on this machine
+                frac_of_stream_probe relates it to what the library's pure streaming kernel reaches on this machine,
+                frac_of_read_write_ceiling to what the box allows this mix of reads and writes (bytes read at the
+                rate of a read-only kernel plus bytes written at the rate of a write-only one)
   per_workload  forward / backward time and fraction of the HBM peak for workloads 2, 3 and 5
   cpu_baseline  the fp64 oracle timed on the host cores on a bounded sample of the headline workload, streamed
                 in slabs of rows with a carried fp64 state, once on one thread and once on all the cores this
@@ -167,7 +169,8 @@ def stream_probe(lr, torch, E, stream, iters=10):
     a, b, c, o0, o1 = bufs
     res = {}
     for name, argv, nbytes in (("copy_1in_1out", (a, None, None, o0, None), 8), ("fwd_like_2in_1out", (a, b, None, o0, None), 12),
-                               ("bwd_like_3in_2out", (a, b, c, o0, o1), 20)):
+                               ("bwd_like_3in_2out", (a, b, c, o0, o1), 20), ("read_only", (a, None, None, None, None), 4),
+                               ("write_only", (None, None, None, o0, None), 4)):
         for _ in range(2):
             lr.linrec_stream_probe(*argv, stream=stream)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
@@ -633,6 +636,15 @@ def main():
         like = probe["bwd_like_3in_2out" if do_bwd else "fwd_like_2in_1out"]["GB/s"]
         roof["stream_probe_GB/s"] = like
         roof["frac_of_stream_probe"] = head[dom]["GB/s"] / like
+        # What this box's memory allows a kernel with this mix of reads and writes: its bytes read at the rate
+        # of a kernel that only reads plus its bytes written at the rate of one that only writes (on an MI355X
+        # writes stream at about 80 % of the rate of reads, so no mix reaches what reads alone do).
+        rd, wr = (12.0, 8.0) if do_bwd else (8.0, 4.0)
+        if bf16:
+            rd, wr = rd / 2, wr / 2
+        ceiling = (rd + wr) / (rd / probe["read_only"]["GB/s"] + wr / probe["write_only"]["GB/s"])
+        roof["read_write_ceiling_GB/s"] = ceiling
+        roof["frac_of_read_write_ceiling"] = head[dom]["GB/s"] / ceiling
 
     short = lambda r: {"T": r["T"], "B": r["B"], "n": r["n"], "elements": r["elements"],
                        "forward_ms": r["forward"]["avg_ms"], "forward_frac_of_peak": r["forward"]["frac_of_peak"],

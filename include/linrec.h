@@ -409,8 +409,10 @@ int linrec_validate_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_
  * as 1, 1, 0) and out1 (= out0 squared) that are non-NULL.  With (in0, NULL, NULL, out0, NULL)
  * it is a plain copy of 4n bytes in and 4n bytes out, used to calibrate hardware byte
  * counters; with two inputs and one output it moves the forward pass' 12 bytes per element,
- * with three inputs and two outputs the backward pass' 20.  n must be a multiple of 4 and all
- * pointers 16-byte aligned (LINREC_ERR_SHAPE otherwise); at least one output is required.
+ * with three inputs and two outputs the backward pass' 20.  Without an input it only writes,
+ * without an output it only reads (what it read decides a store that never happens): the two
+ * rates a mix of reads and writes is bounded by.  n must be a multiple of 4 and all pointers
+ * 16-byte aligned (LINREC_ERR_SHAPE otherwise); at least one array is required (LINREC_ERR_NULL).
  */
 int linrec_stream_probe(const float *in0, const float *in1, const float *in2, float *out0,
                         float *out1, int64_t n, void *stream);

@@ -398,7 +398,7 @@ def linrec_reserve_workspace(entry_point, T, B, n, backward=False, stream=None) 
 
 def linrec_stream_probe(in0, in1, in2, out0, out1, stream=None) -> None:
     """Pure streaming kernel over flat float32 CUDA tensors (None = absent); see include/linrec.h."""
-    n = (out0 if out0 is not None else out1).numel()
+    n = next(t for t in (out0, out1, in0, in1, in2) if t is not None).numel()
     _check(lib().linrec_stream_probe(_ptr(in0), _ptr(in1), _ptr(in2), _ptr(out0), _ptr(out1), n, _stream_ptr(stream)))
 
 

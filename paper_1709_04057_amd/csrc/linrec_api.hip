@@ -978,7 +978,7 @@ extern "C" int linrec_stream_probe(const float *in0, const float *in1, const flo
                                    int64_t n, void *stream)
 {
     if (n < 0 || (n & 3)) return LINREC_ERR_SHAPE;
-    if (!out0 && !out1) return LINREC_ERR_NULL;
+    if (!out0 && !out1 && !in0 && !in1 && !in2) return LINREC_ERR_NULL;
     const void *ptrs[5] = {in0, in1, in2, out0, out1};
     for (const void *p : ptrs)
         if (!aligned16(p)) return LINREC_ERR_SHAPE;

@@ -294,8 +294,11 @@ __global__ void k_set_epoch(LookbackHeader *hdr, uint32_t stored_epoch)
 
 // Streaming probe: the bandwidth a kernel with this library's access instructions reaches when it
 // does nothing but move data.  Reads the non-null inputs, writes the non-null outputs, 16 bytes per
-// lane per access, PROBE_R independent accesses per tensor in flight per thread.
-constexpr int PROBE_R = 8;
+// lane per access, PROBE_R independent accesses per tensor in flight per thread (4 measured 3-6 % ahead
+// of 8 and 10 % ahead of 16 on an MI355X).  Without an output it only reads: the sum of what it read
+// decides a store that never happens, so the loads cannot be dropped.
+constexpr int PROBE_R = 4;
+__device__ float g_probe_sink[4];
 __global__ __launch_bounds__(256) void k_stream_probe(const float *in0, const float *in1, const float *in2, float *out0,
                                                       float *out1, int64_t n4)
 {
@@ -311,6 +314,16 @@ __global__ __launch_bounds__(256) void k_stream_probe(const float *in0, const fl
             if (in2) v += ld<4>(in2 + 4 * i);
         }
         acc[j] = v;
+    }
+    if (!out0 && !out1) {  // read-only
+        vec<4> sum = acc[0];
+#pragma unroll
+        for (int j = 1; j < PROBE_R; ++j) sum += acc[j];
+        if (sum[0] == -1.0f && sum[1] == -2.0f && sum[2] == -3.0f && sum[3] == -4.0f) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) g_probe_sink[v] = sum[v];
+        }
+        return;
     }
 #pragma unroll
     for (int j = 0; j < PROBE_R; ++j) {
