@@ -184,6 +184,13 @@ def stream_probe(lr, torch, E, stream, iters=10):
     return res
 
 
+def read_write_ceiling(probe, read_bytes, write_bytes):
+    """What this box's memory allows a kernel that moves `read_bytes` in and `write_bytes` out per element: its bytes
+    read at the rate of a kernel that only reads plus its bytes written at the rate of one that only writes (on an
+    MI355X writes stream at about 80 % of the rate of reads, so no mix reaches what reads alone do)."""
+    return (read_bytes + write_bytes) / (read_bytes / probe["read_only"]["GB/s"] + write_bytes / probe["write_only"]["GB/s"])
+
+
 def table1(lr, torch):
     """Parallel / serial kernel throughput ratio on the paper's Table-1 grid (forward pass, b = 1)."""
     dev = "cuda:0"
@@ -339,7 +346,10 @@ def gated_bench(args, lr, torch, wl):
         out["roofline"]["traffic"] = measured_traffic(args.gated, "backward", "gated:",
                                                       tile_geometry(lr, out["config"]["tile_bwd"]))
     if not args.no_probe:
-        out["stream_probe"] = stream_probe(lr, torch, E, stream)
+        out["stream_probe"] = stream_probe(lr, torch, min(E, 1 << 28), stream)
+        ceiling = read_write_ceiling(out["stream_probe"], 4.0, 2.0)      # backward: four tensors in, two out
+        out["roofline"]["read_write_ceiling_GB/s"] = ceiling
+        out["roofline"]["frac_of_read_write_ceiling"] = out["roofline"]["achieved"] / ceiling
     if not args.no_cpu_baseline:
         import oracle
         threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
@@ -442,7 +452,10 @@ def lstm_bench(args, lr, torch, wl):
         out["roofline"]["traffic"] = measured_traffic(args.lstm, "backward", "lstm:",
                                                       tile_geometry(lr, out["config"]["tile_bwd"]))
     if not args.no_probe:
-        out["stream_probe"] = stream_probe(lr, torch, E, stream)
+        out["stream_probe"] = stream_probe(lr, torch, min(E, 1 << 28), stream)
+        ceiling = read_write_ceiling(out["stream_probe"], 6.0, 4.0)      # backward: six tensors in, four out
+        out["roofline"]["read_write_ceiling_GB/s"] = ceiling
+        out["roofline"]["frac_of_read_write_ceiling"] = out["roofline"]["achieved"] / ceiling
     if not args.no_cpu_baseline:
         import oracle
         threads = args.cpu_threads or min(16, len(os.sched_getaffinity(0)))
@@ -636,13 +649,8 @@ def main():
         like = probe["bwd_like_3in_2out" if do_bwd else "fwd_like_2in_1out"]["GB/s"]
         roof["stream_probe_GB/s"] = like
         roof["frac_of_stream_probe"] = head[dom]["GB/s"] / like
-        # What this box's memory allows a kernel with this mix of reads and writes: its bytes read at the rate
-        # of a kernel that only reads plus its bytes written at the rate of one that only writes (on an MI355X
-        # writes stream at about 80 % of the rate of reads, so no mix reaches what reads alone do).
         rd, wr = (12.0, 8.0) if do_bwd else (8.0, 4.0)
-        if bf16:
-            rd, wr = rd / 2, wr / 2
-        ceiling = (rd + wr) / (rd / probe["read_only"]["GB/s"] + wr / probe["write_only"]["GB/s"])
+        ceiling = read_write_ceiling(probe, rd, wr)          # (the ratio of reads to writes is what matters)
         roof["read_write_ceiling_GB/s"] = ceiling
         roof["frac_of_read_write_ceiling"] = head[dom]["GB/s"] / ceiling
 
