@@ -15,7 +15,7 @@ the same run and reported beside it.  Prints ONE JSON line:
                 frac_of_read_write_ceiling to what the box allows this mix of reads and writes (bytes read at the
                 rate of a read-only kernel plus bytes written at the rate of a write-only one)
   per_workload  forward / backward time and fraction of the HBM peak for workloads 2, 3 and 5
-  cpu_baseline  the fp64 oracle timed on the host cores on a bounded sample of the headline workload, streamed
+  cpu_baseline  the fp64 oracle timed on the host cores on the headline workload (at most 2^30 elements of it), streamed
                 in slabs of rows with a carried fp64 state, once on one thread and once on all the cores this
                 process may use (a baseline, not a target)
 
@@ -55,8 +55,9 @@ def parse():
     ap.add_argument("--no-tune", action="store_true", help="accepted for older command lines; the default now")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0)
-    ap.add_argument("--cpu-sample-elements", type=int, default=1 << 28,
-                    help="elements of the headline workload (whole rows from row 0) the oracle is timed on")
+    ap.add_argument("--cpu-sample-elements", type=int, default=1 << 30,
+                    help="elements of the headline workload (whole rows from row 0) the oracle is timed on; the default "
+                         "covers all of workload 5 (a few seconds of host time per leg)")
     ap.add_argument("--walk-grid", action="store_true",
                     help="short, wide problems: the walk variant against the single pass, and what the plan takes")
     ap.add_argument("--table1", action="store_true",
