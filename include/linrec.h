@@ -427,7 +427,10 @@ int linrec_check(void *stream);
  * graph holding a recorded linrec launch is replayed afterwards. */
 int linrec_release_workspace(void);
 
-/* Static strings; never NULL. */
+/* Never NULL.  linrec_status_string returns a static string.  linrec_last_hip_error describes the last
+ * LINREC_ERR_HIP that a call made by the CALLING host thread returned (which HIP call failed, and
+ * HIP's text for the error; empty if none has); the buffer belongs to that thread and is overwritten
+ * by its next failure. */
 const char *linrec_status_string(int status);
 const char *linrec_last_hip_error(void);
 

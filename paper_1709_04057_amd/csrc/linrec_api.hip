@@ -107,7 +107,7 @@ ForcedPlan &forced()
     return f;
 }
 
-char g_hip_error[256] = "";
+thread_local char g_hip_error[256] = "";  // per host thread, like the options: the thread that got LINREC_ERR_HIP reads its own
 unsigned long long *g_trace = nullptr;  // set by linrec_debug_trace (trace builds)
 int hip_fail(hipError_t e, const char *what)
 {
