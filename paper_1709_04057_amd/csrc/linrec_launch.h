@@ -76,8 +76,13 @@ struct TileDesc {
 // Ids are stable across versions of the library.
 //   one column per thread, 512 threads (one workgroup per compute unit): 44, 43, 42, 38, 41 (64 wide, 64 ..
 //   24 rows per thread), 22, 35, 34, 33 (32 wide); 256 threads: 20, 21, 45 (64 wide), 17, 19, 18 (32 wide),
-//   1, 2 (8 rows per thread), 23 (16 wide, for a handful of columns)
+//   1, 2 (8 rows per thread), 23 (16 wide, for a handful of columns); 52, 53 (64 wide, 36 and 28 rows per
+//   thread) for wide problems whose row length is a large power of two: the threads of a workgroup that share a
+//   column start rows-per-thread rows apart, and from 16384 columns on a distance that is a multiple of 2 MiB
+//   (32 or 64 rows of 16384 floats, 48 rows of 32768 ...) measured 10-15 % less bandwidth than the same shape
+//   on 12288 or 24576 columns; 36 and 28 rows keep it an odd multiple of at most 1 MiB up to 65536 columns
 //   two and four columns per thread (8- and 16-byte accesses; 4- and 8-byte with bf16 storage): the rest
+//   (54, 55: 40 and 56 rows per thread, 64 wide, 256 threads: the same for bf16 storage)
 #define LINREC_TILES(X) \
     X(1, 1, 8, 64, 4)   \
     X(2, 1, 8, 16, 16)  \
@@ -118,8 +123,12 @@ struct TileDesc {
     X(45, 1, 24, 64, 4)  \
     X(47, 2, 64, 64, 8)  \
     X(48, 2, 48, 64, 8)  \
-    X(51, 2, 48, 32, 16)
-constexpr int MAX_TILE_ID = 51;
+    X(51, 2, 48, 32, 16) \
+    X(52, 1, 36, 64, 4)  \
+    X(53, 1, 28, 64, 4)  \
+    X(54, 2, 40, 64, 4)  \
+    X(55, 2, 56, 64, 4)
+constexpr int MAX_TILE_ID = 55;
 
 // Families (bit LINREC_ENTRY_*) whose kernels can exist for a shape at all:
 //   plain fp32         at most 64 elements per thread and operand (one register each)

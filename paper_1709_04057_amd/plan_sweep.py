@@ -6,8 +6,9 @@ library is built for the tile shapes that table uses and no others.  Both are ge
     LINREC_EXTRA_FLAGS=-DLINREC_ALL_SHAPES LINREC_BUILD_OUT=$PWD/liblinrec_all.so python paper_1709_04057_amd/build.py
     LINREC_LIB_PATH=$PWD/liblinrec_all.so python -m paper_1709_04057_amd.plan_sweep measure --out sweep.jsonl
     python -m paper_1709_04057_amd.plan_sweep table sweep.jsonl         # anywhere; then build again
-(``measure --families a,b`` times some families only; ``table`` takes several files, a later file's timing of a plan
-replacing an earlier one's, so a change to one family's kernels needs that family measured again and no more.
+(``measure --families a,b`` times some families only, ``--min-columns n`` the wide cells only; ``table`` takes several
+files, a later file's timing of a plan replacing an earlier one's, so a change to one family's kernels, or shapes
+added for one region of the grid, need that family or region measured again and no more.
 ``measure`` also times the tapered tail, LINREC_OPT_TAPER = 2, on the three fastest single-pass shapes of every
 cell; ``measure --taper-only sweep.jsonl ...`` does just that on the shapes an earlier sweep found.)
 
@@ -95,6 +96,8 @@ def measure(args):
         bf16 = fam.endswith("bf16")
         cv = (lambda t: t.to(torch.bfloat16).contiguous() if torch.is_tensor(t) else t) if bf16 else (lambda t: t)
         for T, C in grid(fam):
+            if C < args.min_columns:
+                continue
             B, n = 1, C
             if fam.startswith("gilr"):
                 inp = {k: cv(v) for k, v in wl.make_gated(T, B, n, seed=1, device="cuda:0", gate_mean=2.0).items()}
@@ -394,6 +397,8 @@ def main():
     m = sub.add_parser("measure")
     m.add_argument("--out", required=True)
     m.add_argument("--families", default="")
+    m.add_argument("--min-columns", type=int, default=0,
+                   help="only the grid cells of at least this many columns (every shape is timed on them again)")
     m.add_argument("--taper-only", nargs="+", default=[], metavar="SWEEP",
                    help="time only the tapered tails, on the fastest shapes of these earlier sweeps")
     t = sub.add_parser("table")
