@@ -32,6 +32,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+VARIANT_NAMES = {1: "threephase", 2: "lookback", 3: "serial", 4: "walk"}    # LINREC_VARIANT_*
 FWD_BYTES_PER_EL = 12.0   # read lambda, x; write h
 BWD_BYTES_PER_EL = 20.0   # read lambda, h, grad_h; write grad_x, grad_lambda
 
@@ -140,8 +141,8 @@ def cpu_baseline(inp, h_gpu, threads, sample_elements):
                       f"1 thread: forward {f1:.3f} s, backward {b1:.3f} s"}
 
 
-def measured_traffic(cfg, direction, form="", expect=None):
-    """HBM bytes per launch of the look-back kernel from the committed rocprofv3 counter summary
+def measured_traffic(cfg, direction, form="", expect=None, kernel="lookback"):
+    """HBM bytes per launch of the look-back kernel (or the walk) from the committed rocprofv3 counter summary
     (profiles/hbm_traffic_cfg<N>.json or hbm_traffic_<gated/lstm workload>.json, written by
     profile_summary.py traffic), or None.  `expect` is the tile geometry "vec, rows, wc, wt" of the plan
     that was just timed: a summary taken on another kernel instance says nothing about this run and is not
@@ -150,7 +151,7 @@ def measured_traffic(cfg, direction, form="", expect=None):
     try:
         with open(path) as f:
             d = json.load(f)
-        k = d["kernels"][form + "k_lookback/" + direction]
+        k = d["kernels"][form + "k_" + kernel + "/" + direction]
         if expect is not None and f"Geo<{expect}," not in k["name"]:
             return None
         return k["hbm_bytes"]
@@ -332,20 +333,25 @@ def gated_bench(args, lr, torch, wl):
         "data": "synthetic",
         "config": {"workload": f"{args.gated}: gated forward+backward, {'bf16 storage' if bf16 else 'fp32'}, time-major "
                                f"[T={T}, B={B}, n={n}], tau=tanh; " + spec["note"],
+                   "variant_fwd": VARIANT_NAMES.get(lr.linrec_plan_for(family, T, B, n, backward=False)[0], "?"),
                    "tile_fwd": lr.linrec_plan_for(family, T, B, n, backward=False)[1],
+                   "variant_bwd": VARIANT_NAMES.get(lr.linrec_plan_for(family, T, B, n, backward=True)[0], "?"),
                    "tile_bwd": lr.linrec_plan_for(family, T, B, n, backward=True)[1]},
         "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(bpe_f, f_avg), "frac_of_peak": gbs(bpe_f, f_avg) / HBM_PEAK_GBS},
         "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(bpe_b, b_avg), "frac_of_peak": gbs(bpe_b, b_avg) / HBM_PEAK_GBS},
         "unfused_forward": {"avg_ms": u_avg, "min_ms": u_min, "speedup_of_fused": u_avg / f_avg,
                             "what": "torch.sigmoid, torch.tanh, torch.addcmul, then linrec_forward"},
-        "roofline": {"bound": "hbm", "kernel": "gated backward pass (look-back kernel)", "achieved": gbs(bpe_b, b_avg),
+        "roofline": {"bound": "hbm",
+                     "kernel": "gated backward pass (%s kernel)" % VARIANT_NAMES.get(lr.linrec_plan_for(family, T, B, n, backward=True)[0], "?"),
+                     "achieved": gbs(bpe_b, b_avg),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(bpe_b, b_avg) / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_element": bpe_b, "algorithmic_bytes": bpe_b * E, "avg_ms": b_avg},
         "cpu_baseline": None,
     }
     if not bf16:
         out["roofline"]["traffic"] = measured_traffic(args.gated, "backward", "gated:",
-                                                      tile_geometry(lr, out["config"]["tile_bwd"]))
+                                                      tile_geometry(lr, out["config"]["tile_bwd"]),
+                                                      kernel=out["config"]["variant_bwd"])
     if not args.no_probe:
         out["stream_probe"] = stream_probe(lr, torch, min(E, 1 << 28), stream)
         ceiling = read_write_ceiling(out["stream_probe"], 4.0, 2.0)      # backward: four tensors in, two out
@@ -438,20 +444,25 @@ def lstm_bench(args, lr, torch, wl):
         "data": "synthetic",
         "config": {"workload": f"{args.lstm}: LSTM cell forward+backward, {'bf16 storage' if bf16 else 'fp32'}, time-major "
                                f"[T={T}, B={B}, n={n}]; " + spec["note"],
+                   "variant_fwd": VARIANT_NAMES.get(lr.linrec_plan_for(family, T, B, n, backward=False)[0], "?"),
                    "tile_fwd": lr.linrec_plan_for(family, T, B, n, backward=False)[1],
+                   "variant_bwd": VARIANT_NAMES.get(lr.linrec_plan_for(family, T, B, n, backward=True)[0], "?"),
                    "tile_bwd": lr.linrec_plan_for(family, T, B, n, backward=True)[1]},
         "forward": {"avg_ms": f_avg, "min_ms": f_min, "GB/s": gbs(bpe_f, f_avg), "frac_of_peak": gbs(bpe_f, f_avg) / HBM_PEAK_GBS},
         "backward": {"avg_ms": b_avg, "min_ms": b_min, "GB/s": gbs(bpe_b, b_avg), "frac_of_peak": gbs(bpe_b, b_avg) / HBM_PEAK_GBS},
         "unfused_forward": {"avg_ms": u_avg, "min_ms": u_min, "speedup_of_fused": u_avg / f_avg,
                             "what": "torch sigmoid x3, tanh, mul x2 around linrec_forward"},
-        "roofline": {"bound": "hbm", "kernel": "LSTM-cell backward pass (look-back kernel)", "achieved": gbs(bpe_b, b_avg),
+        "roofline": {"bound": "hbm",
+                     "kernel": "LSTM-cell backward pass (%s kernel)" % VARIANT_NAMES.get(lr.linrec_plan_for(family, T, B, n, backward=True)[0], "?"),
+                     "achieved": gbs(bpe_b, b_avg),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs(bpe_b, b_avg) / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_element": bpe_b, "algorithmic_bytes": bpe_b * E, "avg_ms": b_avg},
         "cpu_baseline": None,
     }
     if not bf16:
         out["roofline"]["traffic"] = measured_traffic(args.lstm, "backward", "lstm:",
-                                                      tile_geometry(lr, out["config"]["tile_bwd"]))
+                                                      tile_geometry(lr, out["config"]["tile_bwd"]),
+                                                      kernel=out["config"]["variant_bwd"])
     if not args.no_probe:
         out["stream_probe"] = stream_probe(lr, torch, min(E, 1 << 28), stream)
         ceiling = read_write_ceiling(out["stream_probe"], 6.0, 4.0)      # backward: six tensors in, four out
@@ -641,8 +652,8 @@ def main():
     tile = head["tile_bwd"] if do_bwd else head["tile_fwd"]
     kernel = head["kernel_bwd"] if do_bwd else head["kernel_fwd"]
     traffic = None
-    if not bf16 and kernel == "lookback":
-        traffic = measured_traffic(args.config, dom, expect=tile_geometry(lr, tile))
+    if not bf16 and kernel in ("lookback", "walk"):
+        traffic = measured_traffic(args.config, dom, expect=tile_geometry(lr, tile), kernel=kernel)
     roof = {"bound": "hbm", "kernel": f"{dom} pass ({kernel} kernel, tile shape {tile})", "achieved": head[dom]["GB/s"],
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": head[dom]["GB/s"] / HBM_PEAK_GBS, "traffic": traffic,
             "bytes_per_element": bpe, "algorithmic_bytes": bpe * E, "avg_ms": head[dom]["avg_ms"]}

@@ -1143,9 +1143,10 @@ extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n,
                 best.taper = 2;
             }
         }
-        // The walk, where there are enough columns for it to stand a chance and the sequence is short enough:
+        // The walk, where there are enough columns for it to stand a chance and the sequence is short enough (from
+        // 16384 columns on, where the column groups alone fill the GPU, at any length):
         // every shape of the family that makes between one and eight workgroups per compute unit.
-        if (C >= 4096 && T <= 8192) {
+        if ((C >= 4096 && T <= 8192) || C >= 16384) {
             const int64_t units = compute_units(dev);
             for (int tile = 1; tile <= MAX_TILE_ID && rc == LINREC_OK; ++tile) {
                 if (!usable(tile)) continue;

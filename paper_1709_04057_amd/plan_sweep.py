@@ -135,7 +135,7 @@ def measure(args):
                 short = timeit(call, 3) < 60.0      # the whole cell is timed one way
                 best = None
                 single = {}                         # single pass: {(tile, columns per thread): microseconds}
-                variants = [VARIANT_LOOKBACK] + ([VARIANT_WALK] if T <= 4096 and C >= 2048 else [])
+                variants = [VARIANT_LOOKBACK] + ([VARIANT_WALK] if (T <= 4096 and C >= 2048) or C >= 16384 else [])
                 if prior is not None:
                     variants = []
                     single = {(t, vec): us for (var, t, vec), us in prior.get((ep, backward, T, C), {}).items()
@@ -277,7 +277,8 @@ def choose_shapes(cells, ep, mean_target, cell_target, max_shapes):
 
 def choose_cell(cells, key, width, allowed, variant):
     """The fastest shape of `allowed` for one cell, access width and variant, judged on the cell's own timing
-    and, at a quarter of the weight each, on its four neighbours' (a median of nine launches is good to 2-3 %)."""
+    and, at a quarter of the weight each, on its four neighbours' (a median of nine launches is good to 2-3 %);
+    never a shape that measured more than OWN_LIMIT behind the cell's own best."""
     ep, bwd, T, C = key
     ci = C_GRID.index(C)
     mine = {t: us for (var, t, vec), us in cells[key].items() if var == variant and vec <= width and t in allowed}
@@ -295,7 +296,14 @@ def choose_cell(cells, key, width, allowed, variant):
             sc += 0.25 * (theirs[t] / min(theirs.values()) if t in theirs else us / best_here)
         score[t] = sc
     t = min(score, key=score.get)
+    # The neighbours smooth noise, they do not overrule the cell: a shape that measured more than OWN_LIMIT behind
+    # the cell's own best (launch-latency differences aside) is a real loss there, whatever it does next door.
+    if loss(mine[t], best_here) > OWN_LIMIT:
+        t = min(mine, key=mine.get)
     return t, mine[t]
+
+
+OWN_LIMIT = 0.05        # what a cell's plan may lose against the cell's own best measurement for its neighbours' sake
 
 
 WALK_MARGIN = 0.97      # the walk is taken where it measured at least 3 % ahead of the single pass

@@ -51,12 +51,12 @@ def _per_kernel(db_path, counter):
 def _kind(name):
     if "k_stream_probe" in name:
         return "stream_probe"
-    if "k_lookback" in name or "k_fixup" in name or "k_reduce" in name or "k_scan_summaries" in name or "k_serial" in name:
+    if any(k in name for k in ("k_lookback", "k_walk", "k_fixup", "k_reduce", "k_scan_summaries", "k_serial")):
         bwd = ", true" in name.split("k_", 1)[1] or "_bwd" in name
         base = name.split("linrec::", 1)[1].split("<", 1)[0].split("(", 1)[0]
-        # the look-back kernel's last template argument is the form: 1 gated layer, 2 LSTM cell
+        # the last template argument of the look-back kernel and of the walk is the form: 1 gated layer, 2 LSTM cell
         form = {"1": "gated:", "2": "lstm:"}.get(name.rsplit(">(", 1)[0].rsplit(",", 1)[-1].strip(), "") \
-            if "k_lookback" in name else ""
+            if "k_lookback" in name or "k_walk" in name else ""
         return form + base + ("/backward" if bwd else "/forward")
     return None
 

@@ -107,7 +107,8 @@ def test_config4_full_size_walk():
         fwd_bwd_check(inp, "cfg4 full walk")
 
 
-@pytest.mark.parametrize("shape", [(1024, 16, 1024), (512, 8, 1024), (200, 3, 5000), (2048, 8, 4096), (64, 16, 4096)])
+@pytest.mark.parametrize("shape", [(1024, 16, 1024), (512, 8, 1024), (200, 3, 5000), (2048, 2, 4096), (1024, 16, 4096),
+                                   (64, 16, 4096)])
 def test_short_wide_shapes_take_the_walk(shape):
     """Automatic plan on short, wide problems: one workgroup per column group walks the sequence (no
     look-back) -- in the forward pass of every one of these shapes, and in the backward pass wherever it

@@ -65,6 +65,21 @@ def test_a_cell_takes_the_walk_and_the_tapered_tail_only_with_a_margin(tmp_path)
     assert ps.make_table(cells, {ep: [1, 2]})[(ep, False, 10, ci(8192))][1] == [1, 1, 1]
 
 
+def test_neighbours_smooth_a_cell_but_do_not_overrule_it(tmp_path):
+    fam, ep = "plain", ps.FAMILIES["plain"]
+    ci = ps.C_GRID.index
+
+    def table(middle):
+        rows = _rows(fam, 4096, 1024, "fwd", middle)
+        for T, C in ((2048, 1024), (8192, 1024), (4096, 768), (4096, 1536)):      # the four neighbours prefer shape 1
+            rows += _rows(fam, T, C, "fwd", {(LB, 1, 1): 100.0, (LB, 2, 1): 120.0})
+        cells, _ = ps.load([_write(tmp_path, rows)])
+        return ps.make_table(cells, {ep: [1, 2]})[(ep, False, 12, ci(1024))][0]
+
+    assert table({(LB, 1, 1): 102.0, (LB, 2, 1): 100.0}) == [1, 1, 1]      # 2 % behind here: the neighbours decide
+    assert table({(LB, 1, 1): 110.0, (LB, 2, 1): 100.0}) == [2, 2, 2]      # 10 % behind here: they do not
+
+
 def test_the_written_files(tmp_path):
     rows = []
     for fam in ps.FAMILIES:
