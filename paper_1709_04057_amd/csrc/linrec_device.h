@@ -1154,9 +1154,10 @@ __device__ __forceinline__ void std_(double *p, dvec<N> v)
 // ---------------------------------------------------------------------------------------------
 // Phase 2 inside a tile, in two levels.
 //   1. The TPW = 64/WC time-threads that share a wavefront (lanes tc + WC*ttl) run a Kogge-Stone
-//      scan over ttl with cross-lane moves (log2(TPW) steps, no LDS storage, no barrier).
-//   2. The NW wavefront totals go through LDS; every thread composes the totals of the wavefronts
-//      before its own (at most NW-1 of them) with its in-wavefront prefix.
+//      scan over ttl with cross-lane moves (log2(TPW) steps, no LDS storage, no barrier).  (A tile wider
+//      than 64 threads has one time-thread per wavefront and several wavefronts side by side: no level 1.)
+//   2. The NW wavefront totals along time go through LDS; every thread composes the totals of the
+//      wavefronts before its own (at most NW-1 of them) with its in-wavefront prefix.
 // Every thread returns its exclusive prefix (Pe, Se) -- the composition of all threads with smaller
 // tt in its columns -- and the tile total (Pt, St).  P travels in fp64; S is stored in fp32 between
 // steps but every combination is evaluated in fp64.  One __syncthreads inside.
@@ -1190,7 +1191,10 @@ __device__ __forceinline__ dvec<N> lane_move(dvec<N> v, int src_lane)
 
 template <class G>
 struct ScanLds {
-    static constexpr int NW = G::THREADS / 64;
+    // Wavefronts side by side along the columns (tiles wider than 64 threads), and along time: a wavefront holds
+    // 64/WC time-threads of a narrow tile, or a 64-column piece of one time-thread's row of a wide one.
+    static constexpr int WPR = G::WC > 64 ? G::WC / 64 : 1;
+    static constexpr int NW = G::THREADS / 64 / WPR;  // wavefronts along time
     dvec<G::VEC> wP[NW][G::WC];
     vec<G::VEC> wS[NW][G::WC];
     int wClosed[NW][G::WC];
@@ -1207,9 +1211,11 @@ __device__ __forceinline__ void tile_scan(ScanLds<G> &lds, int tid, dvec<G::VEC>
                                           vec<G::VEC> &Se, dvec<G::VEC> &Pt, vec<G::VEC> &St, bool *closed = nullptr)
 {
     constexpr int VEC = G::VEC, WC = G::WC;
-    constexpr int TPW = (64 / WC) < G::WT ? (64 / WC) : G::WT;  // time-threads per wavefront
+    static_assert(WC <= 64 ? 64 % WC == 0 : WC % 64 == 0, "a wavefront holds whole rows of a tile, or a row whole wavefronts");
+    constexpr int TPW = WC >= 64 ? 1 : ((64 / WC) < G::WT ? (64 / WC) : G::WT);  // time-threads per wavefront
     constexpr int NW = ScanLds<G>::NW;
-    const int lane = tid & 63, wave = tid >> 6, tc = tid % WC, ttl = lane / WC;
+    // (`wave` counts along time: the wavefronts that share a row of a tile wider than 64 threads have the same one)
+    const int lane = tid & 63, wave = (tid >> 6) / ScanLds<G>::WPR, tc = tid % WC, ttl = lane / WC;
     int cl = 0;
     if constexpr (CLOSED) cl = *closed ? 1 : 0;
 
@@ -1664,9 +1670,13 @@ __global__ __launch_bounds__(G::THREADS, G::OCC) void k_lookback(const Args A)
             have_state = closed;
         }
         ++n_windows;
-        // every wavefront holds every tc, so this vote is the same in all of them; a window that
-        // reached back to the initial state always closes (nothing precedes it)
-        if (!__any(!have_state) || base - (WT - 1) <= -1) break;
+        // every wavefront of a tile at most 64 threads wide holds every tc, so this vote is the same in all of
+        // them; the wavefronts of a wider tile hold different columns and vote through the workgroup.  A window
+        // that reached back to the initial state always closes (nothing precedes it).
+        bool open_left;
+        if constexpr (WC > 64) open_left = __syncthreads_or(!have_state) != 0;
+        else open_left = __any(!have_state);
+        if (!open_left || base - (WT - 1) <= -1) break;
     }
     LINREC_TRACE_MARK(3);
     LINREC_TRACE_VAL(5, n_windows);

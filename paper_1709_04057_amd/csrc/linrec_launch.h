@@ -81,6 +81,10 @@ struct TileDesc {
 //   column start rows-per-thread rows apart, and from 16384 columns on a distance that is a multiple of 2 MiB
 //   (32 or 64 rows of 16384 floats, 48 rows of 32768 ...) measured 10-15 % less bandwidth than the same shape
 //   on 12288 or 24576 columns; 36 and 28 rows keep it an odd multiple of at most 1 MiB up to 65536 columns
+//   one column per thread, more than 64 threads side by side (two or four wavefronts share a row of the tile,
+//   so a workgroup reads and writes 512-byte or 1-KiB pieces of a row at about the same time, which the memory
+//   system serves faster than the same bytes from different compute units): 56, 57, 58, 60 (128 wide, 64 .. 24
+//   rows per thread), 59 (256 wide); 61, 62 the same with two columns per thread, for bf16 storage
 //   two and four columns per thread (8- and 16-byte accesses; 4- and 8-byte with bf16 storage): the rest
 //   (54, 55: 40 and 56 rows per thread, 64 wide, 256 threads: the same for bf16 storage)
 #define LINREC_TILES(X) \
@@ -127,8 +131,15 @@ struct TileDesc {
     X(52, 1, 36, 64, 4)  \
     X(53, 1, 28, 64, 4)  \
     X(54, 2, 40, 64, 4)  \
-    X(55, 2, 56, 64, 4)
-constexpr int MAX_TILE_ID = 55;
+    X(55, 2, 56, 64, 4)  \
+    X(56, 1, 64, 128, 4) \
+    X(57, 1, 48, 128, 4) \
+    X(58, 1, 32, 128, 4) \
+    X(59, 1, 64, 256, 2) \
+    X(60, 1, 24, 128, 4) \
+    X(61, 2, 64, 128, 4) \
+    X(62, 2, 48, 128, 4)
+constexpr int MAX_TILE_ID = 62;
 
 // Families (bit LINREC_ENTRY_*) whose kernels can exist for a shape at all:
 //   plain fp32         at most 64 elements per thread and operand (one register each)
