@@ -71,7 +71,10 @@ def test_every_gated_tile_ragged_shapes(tile, tau):
         gated_check(inp, tau, f"tile {tile}")
 
 
-WIDE_GATED_TILES = [i for i in GATED_TILES if lr.linrec_tile_info(i)["cols_per_thread"] == 4]
+WIDE_GATED_TILES = [i for i in GATED_TILES if lr.linrec_tile_info(i)["cols_per_thread"] == 4] or [
+    pytest.param(0, marks=pytest.mark.skip(reason="the measured selection builds no four-column shape for the gated layer "
+                                                  "on fp32 storage (its bf16-storage instances are tested in "
+                                                  "test_forms_bf16_parity_gpu.py)"))]
 
 
 @pytest.mark.parametrize("variant", ["lookback", "walk"])
