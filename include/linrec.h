@@ -156,15 +156,16 @@ int linrec_backward(const float *lambda, const float *h, const float *h0, const 
  * instead of the cached workspace: the call makes no hipMalloc / hipFree and touches no allocator.
  * Every GPU the library runs on holds its own copy of the array until the process ends.
  *   - A problem whose look-back words do not fit -- 512 + 24 * K * B*n bytes, K = tiles along T of
- *     the plan in force (linrec_plan; ceil(T / 1024) for long sequences) -- returns
- *     LINREC_ERR_SCRATCH and enqueues nothing.  All five benchmark workloads fit.
+ *     the plan in force (linrec_plan and linrec_tile_info: ceil(T / rows of the tile), a few more
+ *     with a tapered tail) -- returns LINREC_ERR_SCRATCH and enqueues nothing.  All five benchmark
+ *     workloads fit (the largest, [262144, 8, 512] on 512-row tiles, takes 48 MiB of the 64).
  *   - The three-phase variant is not available here (an explicit request runs the single pass).
  *   - All calls on one GPU share that GPU's array, on whatever stream: calls that may overlap in time
  *     on one GPU race on it and give wrong results.  Serialise them (one stream, or events).
  *   - The array keeps the previous call's words; they are told from the running call's by their epoch,
  *     as in the cached workspace, so nothing is cleared between calls.
  */
-#define LINREC_NOALLOC_SCRATCH_BYTES (32u << 20)
+#define LINREC_NOALLOC_SCRATCH_BYTES (64u << 20)
 int linrec_forward_noalloc(const float *lambda, const float *x, const float *h0, float *h_out,
                            int64_t T, int64_t B, int64_t n, void *stream);
 /* LINREC_NOALLOC_SCRATCH_BYTES as the library was built with. */

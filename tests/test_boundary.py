@@ -391,3 +391,17 @@ def test_product_and_oracle_do_not_know_each_other():
     gen = open(os.path.join(root, "linrec_workloads.py")).read()
     assert "import oracle" not in gen and "paper_1709_04057_amd" not in gen
     assert not re.search(r"cumsum|cumprod|linrec_forward|linrec_backward", gen)
+
+
+def test_the_five_workloads_fit_the_no_allocation_scratch():
+    """linrec_forward_noalloc keeps 24 bytes per tile and column (plus a 512-byte header) in a fixed array: with
+    the automatic forward plans every benchmark workload has to fit it, as the header promises."""
+    import linrec_workloads as wl
+    cap = lr.linrec_noalloc_scratch_bytes()
+    for cfg, spec in wl.CONFIGS.items():
+        T, B, n = spec["T"], spec["B"], spec["n"]
+        variant, tile = lr.linrec_plan(T, B, n, backward=False)
+        if variant != lr.VARIANT_LOOKBACK:
+            continue                                    # the walk and the serial kernel keep no words
+        K = -(-T // lr.linrec_tile_info(tile)["rows"]) + 8   # (a tapered tail adds a few short tiles)
+        assert 512 + 24 * K * B * n <= cap, (cfg, tile, K)

@@ -42,6 +42,11 @@ def test_automatic_plan_side_stream_and_no_initial_state():
     s.synchronize()
 
 
+def test_the_largest_workload_fits():
+    # workload 5 at full size on the automatic plan: 48 MiB of look-back words
+    _both(wl.make_inputs(5, device=DEV), "no-alloc, workload 5")
+
+
 def test_too_large_is_refused_and_nothing_is_enqueued():
     # on the shortest tiles the library has for this entry point the look-back words -- 24 bytes per tile and
     # column -- do not fit the array
