@@ -418,6 +418,19 @@ int linrec_validate_lstm_cell_backward_bf16(const uint16_t *f_pre, const uint16_
 int linrec_stream_probe(const float *in0, const float *in1, const float *in2, float *out0,
                         float *out1, int64_t n, void *stream);
 
+/*
+ * The same measurement aid in the geometry of a tile: the arrays are [T, C] row-major like the
+ * tensors of the recurrence, a workgroup streams 32 rows of 256 adjacent columns, one column per
+ * lane, every thread 16 consecutive rows at the row stride -- the arrangement that streams
+ * fastest on an MI355X (a compute unit touches 1 KiB of a row at about the same time), and so
+ * the rate the scan kernels are measured against.  Arrays are given from the front (in1 needs
+ * in0, in2 needs in1, out1 needs out0; LINREC_ERR_NULL otherwise, and when there is none);
+ * out0 = in0*in1+in2 over the inputs present, out1 = out0 squared.  T must be a multiple of 32,
+ * C of 256, pointers 4-byte aligned (LINREC_ERR_SHAPE otherwise).
+ */
+int linrec_stream_probe_rows(const float *in0, const float *in1, const float *in2, float *out0,
+                             float *out1, int64_t T, int64_t C, void *stream);
+
 /* Synchronises `stream` and reports whether any look-back kernel enqueued on it since the
  * last check gave up waiting (LINREC_ERR_DEVICE), LINREC_ERR_HIP if the synchronisation
  * itself failed, else LINREC_OK.  Optional: a healthy run never needs it. */

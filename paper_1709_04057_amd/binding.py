@@ -104,6 +104,8 @@ def lib():
         L.linrec_plan_for.restype = ci
         L.linrec_stream_probe.argtypes = [p, p, p, p, p, i64, p]
         L.linrec_stream_probe.restype = ci
+        L.linrec_stream_probe_rows.argtypes = [p, p, p, p, p, i64, i64, p]
+        L.linrec_stream_probe_rows.restype = ci
         L.linrec_tune.argtypes = [i64, i64, i64, ci, p]
         L.linrec_tune.restype = ci
         L.linrec_tune_for.argtypes = [ci, i64, i64, i64, ci, p]
@@ -400,6 +402,17 @@ def linrec_stream_probe(in0, in1, in2, out0, out1, stream=None) -> None:
     """Pure streaming kernel over flat float32 CUDA tensors (None = absent); see include/linrec.h."""
     n = next(t for t in (out0, out1, in0, in1, in2) if t is not None).numel()
     _check(lib().linrec_stream_probe(_ptr(in0), _ptr(in1), _ptr(in2), _ptr(out0), _ptr(out1), n, _stream_ptr(stream)))
+
+
+def linrec_stream_probe_rows(in0, in1, in2, out0, out1, T, C, stream=None) -> None:
+    """The streaming kernel in the geometry of a tile, over [T, C] float32 CUDA tensors (None = absent, given from
+    the front); see include/linrec.h."""
+    import torch
+    for t in (in0, in1, in2, out0, out1):
+        if t is not None and (not t.is_cuda or t.dtype != torch.float32 or not t.is_contiguous() or t.numel() != T * C):
+            raise ValueError("linrec_stream_probe_rows: contiguous float32 CUDA tensors of T*C elements")
+    _check(lib().linrec_stream_probe_rows(_ptr(in0), _ptr(in1), _ptr(in2), _ptr(out0), _ptr(out1), int(T), int(C),
+                                          _stream_ptr(stream)))
 
 
 def linrec_tune_for(entry_point, T, B, n, backward=False, stream=None) -> None:

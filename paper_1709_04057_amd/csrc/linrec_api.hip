@@ -987,6 +987,21 @@ extern "C" int linrec_stream_probe(const float *in0, const float *in1, const flo
     return e == hipSuccess ? LINREC_OK : hip_fail(e, "launch(stream_probe)");
 }
 
+extern "C" int linrec_stream_probe_rows(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
+                                        int64_t T, int64_t C, void *stream)
+{
+    if (T < 0 || C < 0 || T % 32 || C % 256 || (C > 0 && T > ((int64_t)1 << 40) / C)) return LINREC_ERR_SHAPE;
+    // inputs and outputs are given from the front: in1 needs in0, in2 needs in1, out1 needs out0
+    if ((in1 && !in0) || (in2 && !in1) || (out1 && !out0) || (!in0 && !out0)) return LINREC_ERR_NULL;
+    const void *ptrs[5] = {in0, in1, in2, out0, out1};
+    for (const void *p : ptrs)
+        if ((uintptr_t)p & 3u) return LINREC_ERR_SHAPE;
+    if (T == 0 || C == 0) return LINREC_OK;
+    const int nin = in2 ? 3 : in1 ? 2 : in0 ? 1 : 0, nout = out1 ? 2 : out0 ? 1 : 0;
+    const hipError_t e = launch_rows_probe(nin, nout, in0, in1, in2, out0, out1, T, C, (hipStream_t)stream);
+    return e == hipSuccess ? LINREC_OK : hip_fail(e, "launch(rows_probe)");
+}
+
 // Times the look-back kernel under every candidate plan on scratch tensors of the given shape and
 // remembers the fastest for later calls with that shape on this device.
 extern "C" int linrec_tune_for(int entry_point, int64_t T, int64_t B, int64_t n, int backward, void *stream)

@@ -204,5 +204,9 @@ hipError_t launch_set_epoch(LookbackHeader *hdr, uint32_t stored_epoch, hipStrea
 hipError_t launch_fill16(void *p, int64_t n, hipStream_t s);  // n 16-bit zeros
 hipError_t launch_stream_probe(const float *in0, const float *in1, const float *in2, float *out0, float *out1,
                                int64_t n, hipStream_t s);
+// The probe in the geometry of a tile: the first `nin` inputs and `nout` outputs, [T, C] arrays, T a multiple of 32
+// and C of 256 (hipErrorInvalidValue otherwise).
+hipError_t launch_rows_probe(int nin, int nout, const float *in0, const float *in1, const float *in2, float *out0,
+                             float *out1, int64_t T, int64_t C, hipStream_t s);
 
 }  // namespace linrec

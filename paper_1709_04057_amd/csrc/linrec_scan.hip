@@ -345,6 +345,58 @@ hipError_t launch_stream_probe(const float *in0, const float *in1, const float *
     return hipGetLastError();
 }
 
+// The same streams in the geometry of a tile: [T, C] arrays, a workgroup of 512 threads on PROBE_ROWS rows of
+// PROBE_WC adjacent columns, one column per lane, every thread PROBE_RR consecutive rows at the row stride -- 256
+// lanes side by side, the widest arrangement, which streams fastest (a compute unit then touches 1 KiB of a row
+// at about the same time).  NIN inputs and NOUT outputs, compile-time so that the loads are straight-line code.
+constexpr int PROBE_WC = 256, PROBE_RR = 16, PROBE_ROWS = (512 / PROBE_WC) * PROBE_RR;
+template <int NIN, int NOUT>
+__global__ __launch_bounds__(512) void k_rows_probe(const float *in0, const float *in1, const float *in2, float *out0,
+                                                    float *out1, int64_t C)
+{
+    const int tc = threadIdx.x % PROBE_WC, tt = threadIdx.x / PROBE_WC;
+    const int64_t G = C / PROBE_WC, g = blockIdx.x % G, k = blockIdx.x / G;
+    const int64_t off = (k * PROBE_ROWS + (int64_t)tt * PROBE_RR) * C + g * PROBE_WC + tc;
+    float v[PROBE_RR];
+#pragma unroll
+    for (int j = 0; j < PROBE_RR; ++j) {
+        v[j] = 1.0f + j;
+        if constexpr (NIN >= 1) v[j] = __builtin_nontemporal_load(in0 + off + j * C);
+        if constexpr (NIN >= 2) v[j] *= __builtin_nontemporal_load(in1 + off + j * C);
+        if constexpr (NIN >= 3) v[j] += __builtin_nontemporal_load(in2 + off + j * C);
+    }
+    if constexpr (NOUT == 0) {  // read-only: what was read decides a store that never happens
+        float sum = v[0];
+#pragma unroll
+        for (int j = 1; j < PROBE_RR; ++j) sum += v[j];
+        if (sum == -123.25f) g_probe_sink[0] = sum;
+    } else {
+#pragma unroll
+        for (int j = 0; j < PROBE_RR; ++j) {
+            __builtin_nontemporal_store(v[j], out0 + off + j * C);
+            if constexpr (NOUT >= 2) __builtin_nontemporal_store(v[j] * v[j], out1 + off + j * C);
+        }
+    }
+}
+
+hipError_t launch_rows_probe(int nin, int nout, const float *in0, const float *in1, const float *in2, float *out0,
+                             float *out1, int64_t T, int64_t C, hipStream_t s)
+{
+    if (T % PROBE_ROWS || C % PROBE_WC || nin < 0 || nin > 3 || nout < 0 || nout > 2 || nin + nout == 0)
+        return hipErrorInvalidValue;
+    const int64_t blocks = (T / PROBE_ROWS) * (C / PROBE_WC);
+    if (blocks <= 0) return hipSuccess;
+    if (blocks > 0x7fffffff) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(512);
+#define LINREC_ROWS_PROBE(NI, NO) \
+    if (nin == NI && nout == NO) hipLaunchKernelGGL((k_rows_probe<NI, NO>), grid, block, 0, s, in0, in1, in2, out0, out1, C);
+    LINREC_ROWS_PROBE(1, 0) LINREC_ROWS_PROBE(2, 0) LINREC_ROWS_PROBE(3, 0)
+    LINREC_ROWS_PROBE(0, 1) LINREC_ROWS_PROBE(1, 1) LINREC_ROWS_PROBE(2, 1) LINREC_ROWS_PROBE(3, 1)
+    LINREC_ROWS_PROBE(0, 2) LINREC_ROWS_PROBE(1, 2) LINREC_ROWS_PROBE(2, 2) LINREC_ROWS_PROBE(3, 2)
+#undef LINREC_ROWS_PROBE
+    return hipGetLastError();
+}
+
 hipError_t launch_scan_summaries(const double *aggP, const double *aggS, const float *h0, double *carry, int64_t K,
                                  int64_t C, hipStream_t s)
 {

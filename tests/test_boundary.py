@@ -405,3 +405,15 @@ def test_the_five_workloads_fit_the_no_allocation_scratch():
             continue                                    # the walk and the serial kernel keep no words
         K = -(-T // lr.linrec_tile_info(tile)["rows"]) + 8   # (a tapered tail adds a few short tiles)
         assert 512 + 24 * K * B * n <= cap, (cfg, tile, K)
+
+
+def test_rows_probe_checks_its_arguments_before_any_gpu_call():
+    L = lr.lib()
+    one = ctypes.c_void_p(256)                                   # any aligned non-NULL address: nothing is dereferenced
+    assert L.linrec_stream_probe_rows(one, None, None, one, None, 33, 256, None) == -2       # T not a multiple of 32
+    assert L.linrec_stream_probe_rows(one, None, None, one, None, 32, 100, None) == -2       # C not a multiple of 256
+    assert L.linrec_stream_probe_rows(None, None, None, None, None, 32, 256, None) == -1     # no array at all
+    assert L.linrec_stream_probe_rows(None, one, None, one, None, 32, 256, None) == -1       # inputs come from the front
+    assert L.linrec_stream_probe_rows(one, None, None, None, one, 32, 256, None) == -1       # and so do outputs
+    assert L.linrec_stream_probe_rows(ctypes.c_void_p(258), None, None, one, None, 32, 256, None) == -2
+    assert L.linrec_stream_probe_rows(one, None, None, one, None, 0, 256, None) == 0         # an empty problem is a no-op

@@ -390,3 +390,28 @@ def test_tuned_plans_of_every_family_are_used_and_correct():
     cell16_check(forms_to_bf16(wl.make_lstm(T, B, n, seed=54, device=DEV)), "tuned lstm bf16")
     with pytest.raises(lr.LinrecError):
         lr.linrec_tune_for(7, T, B, n)
+
+
+def test_stream_probes_compute_what_the_header_says():
+    """The measurement kernels are not part of the recurrence, but a probe that skipped or doubled part of its
+    arrays would time the wrong number of bytes: every element is checked, in both geometries."""
+    T, C = 96, 1024
+    g = torch.Generator(device=DEV)
+    g.manual_seed(7)
+    a, b, c = (torch.rand((T, C), device=DEV, generator=g) + 0.5 for _ in range(3))
+    for rows in (False, True):
+        call = (lambda *t: lr.linrec_stream_probe_rows(*t, T, C)) if rows else lr.linrec_stream_probe
+        for ins, n_out in (((a, None, None), 1), ((a, b, None), 1), ((a, b, c), 2)):
+            o0, o1 = torch.full_like(a, float("nan")), torch.full_like(a, float("nan"))
+            call(*ins, o0, o1 if n_out == 2 else None)
+            torch.cuda.synchronize()
+            want = ins[0] * (ins[1] if ins[1] is not None else 1.0) + (ins[2] if ins[2] is not None else 0.0)
+            # (the kernels may fuse the multiply and the add: one rounding less than torch's two)
+            torch.testing.assert_close(o0, want, rtol=1e-6, atol=0)
+            if n_out == 2:
+                torch.testing.assert_close(o1, want * want, rtol=1e-6, atol=0)
+        o0 = torch.full_like(a, float("nan"))
+        call(None, None, None, o0, None)                          # write-only: every element is written
+        call(a, None, None, None, None)                           # read-only: runs, writes nothing
+        torch.cuda.synchronize()
+        assert bool(torch.isfinite(o0).all())
