@@ -4,8 +4,8 @@
 A step is one forward pass plus one backward pass of h_t = lambda_t*h_{t-1} + x_t over one batch of
 synthetic, HBM-resident inputs.  The headline workload is the largest of the five that fits one GPU,
 workload 5 ([T=262144, B=8, n=512] fp32, 1.07e9 elements); workloads 2 and 3 (the other two with
-T >= 65536: 65536 steps at 256 hidden units, and the one-million-step regime of Section 4.2) are timed in
-the same run and reported beside it.  Prints ONE JSON line:
+T >= 65536: 65536 steps at 256 hidden units, and the one-million-step regime of Section 4.2) and workload 4
+(4096 steps of a wide layer) are timed in the same run and reported beside it.  Prints ONE JSON line:
 
   value         elements/s of forward+backward together on the headline workload, E / ms_per_step, E = T*B*n
                 (K steps, wall clock between two device synchronisations, nothing else on the stream)
@@ -15,7 +15,7 @@ the same run and reported beside it.  Prints ONE JSON line:
                 same streams in and out (flat arrays, or rows of 256 lanes like a wide tile: whichever is faster),
                 frac_of_read_write_ceiling to what the box allows this mix of reads and writes (bytes read at the
                 rate of a read-only kernel plus bytes written at the rate of a write-only one)
-  per_workload  forward / backward time and fraction of the HBM peak for workloads 2, 3 and 5
+  per_workload  forward / backward time and fraction of the HBM peak for workloads 2, 3, 4 and 5
   cpu_baseline  the fp64 oracle timed on the host cores on the headline workload (at most 2^30 elements of it), streamed
                 in slabs of rows with a carried fp64 state, once on one thread and once on all the cores this
                 process may use (a baseline, not a target)
@@ -46,7 +46,7 @@ def parse():
     ap.add_argument("--config", type=int, default=5, help="headline workload 1..5 (default 5, the largest)")
     ap.add_argument("--also", default="auto",
                     help="comma-separated workloads timed beside the headline one and reported in per_workload "
-                         "(default: 2,3 when the headline is workload 5 in fp32, else none; '' for none)")
+                         "(default: 2,3,4 when the headline is workload 5 in fp32, else none; '' for none)")
     ap.add_argument("--variant", default="auto", choices=["auto", "threephase", "lookback", "serial", "walk"])
     ap.add_argument("--tile-fwd", type=int, default=0, help="pin this tile shape for the headline workload's forward pass")
     ap.add_argument("--tile-bwd", type=int, default=0, help="pin this tile shape for the headline workload's backward pass")
@@ -661,7 +661,7 @@ def main():
     inp, h_gpu = kept
     E = head["elements"]
     do_bwd = head["backward"] is not None
-    also = ("2,3" if args.config == 5 and not bf16 else "") if args.also == "auto" else args.also
+    also = ("2,3,4" if args.config == 5 and not bf16 else "") if args.also == "auto" else args.also
     per = {f"cfg{args.config}": head}
     cpu = None
     if not args.no_cpu_baseline:
