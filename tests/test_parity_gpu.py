@@ -420,3 +420,20 @@ def test_growing_recurrence_within_the_documented_domain(variant):
     inp["lam"] = (1.0 + 0.02 * inp["lam"]).contiguous()          # in [0.98, 1.02]: products up to ~1e6
     with options(variant=VARIANTS[variant]):
         fwd_bwd_check(inp, f"growing {variant}")
+
+
+WIDE_TILES = [i for i, info in all_tiles(lr.ENTRY_PLAIN) if info["threads_cols"] > 64]
+
+
+@pytest.mark.parametrize("variant", ["threephase", "lookback", "walk"])
+def test_tiles_wider_than_a_wavefront_on_problems_narrower_than_the_tile(variant):
+    """Shapes with 128 or 256 threads side by side: two or four wavefronts share a row of the tile, and on a narrow or
+    ragged problem whole wavefronts hold no column at all (they still take part in the scan's barriers and in the
+    look-back's vote)."""
+    assert WIDE_TILES, "the build has no tile wider than a wavefront"
+    for tile in WIDE_TILES:
+        for C in (1, 37, 65, 129, 257):
+            for T in (1, 700, 2100):
+                inp = wl.make_generic(T, 1, C, seed=tile * 1000 + C + T, device=DEV, lam_kind="mixed", with_h0=bool((C + T) & 1))
+                with options(variant=getattr(lr, "VARIANT_" + variant.upper()), tile=tile):
+                    fwd_bwd_check(inp, f"tile {tile} T={T} C={C} {variant}")
